@@ -1,0 +1,153 @@
+"""Layer tables for the synthetic workloads.
+
+A net is an ordered list of `Op`s over numbered activation buffers.  Buffer 0 is
+the net input; the last op's `dst` is the net output.  The tables only carry
+shapes, strides, sparsities and buffer wiring -- no arithmetic.
+
+ResNet-50 layout (the paper's Table 2 names the model but not its layer
+details; the standard 3/4/6/3 bottleneck ladder is used): conv1 7x7/2, maxpool
+3x3/2, 16 bottlenecks (1x1 reduce, 3x3, 1x1 expand; x4 expansion; mid channels
+64/128/256/512), projection 1x1 shortcuts on the first block of each stage,
+stride 2 placed on the 3x3 (and on the projection) of the first block of stages
+3-5, global average pool, FC 2048->1000.  That is 1 + 16*3 + 4 = 53 convs.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Dict, List, Sequence, Tuple
+
+import numpy as np
+
+from .gen import activation, bias_vector, conv_out_size, pruned_weights
+
+
+@dataclass(frozen=True)
+class Op:
+    kind: str              # "conv" | "fc" | "maxpool" | "avgpool"
+    name: str
+    src: int
+    dst: int
+    cin: int = 0
+    cout: int = 0
+    k: int = 1             # square kernel / pool window
+    stride: int = 1
+    pad: int = 0
+    sparsity: float = 0.0
+    relu: bool = False
+    res: int = -1          # buffer added before the activation, -1 = none
+
+
+def single_conv_ops(cin=64, cout=64, k=3, stride=1, pad=1, sparsity=0.9, relu=True) -> List[Op]:
+    return [Op("conv", "conv", 0, 1, cin, cout, k, stride, pad, sparsity, relu)]
+
+
+def bottleneck_conv2x_ops(sparsity: float = 0.85) -> List[Op]:
+    """conv2_x identity bottleneck: 1x1 256->64, 3x3 64->64 pad 1, 1x1 64->256 + input, ReLU."""
+    return [
+        Op("conv", "a_1x1", 0, 1, 256, 64, 1, 1, 0, sparsity, True),
+        Op("conv", "b_3x3", 1, 2, 64, 64, 3, 1, 1, sparsity, True),
+        Op("conv", "c_1x1", 2, 3, 64, 256, 1, 1, 0, sparsity, True, res=0),
+    ]
+
+
+def resnet50_ops(s_conv1: float = 0.0, s_3x3: float = 0.8, s_1x1: float = 0.9,
+                 s_fc: float = 0.9, stride_on_1x1: bool = False,
+                 uniform: float | None = None) -> List[Op]:
+    if uniform is not None:
+        s_conv1 = s_3x3 = s_1x1 = s_fc = uniform
+    ops: List[Op] = []
+    ops.append(Op("conv", "conv1", 0, 1, 3, 64, 7, 2, 3, s_conv1, True))
+    ops.append(Op("maxpool", "pool1", 1, 2, k=3, stride=2, pad=1))
+    cur, other = 2, 3
+    t1, t2, tp = 4, 5, 6
+    cin = 64
+    for stage, (nblocks, mid) in enumerate([(3, 64), (4, 128), (6, 256), (3, 512)], start=2):
+        for b in range(nblocks):
+            first = b == 0
+            stride = 2 if (first and stage > 2) else 1
+            cout = mid * 4
+            sa, sb = (stride, 1) if stride_on_1x1 else (1, stride)
+            tag = f"conv{stage}_{b + 1}"
+            ops.append(Op("conv", tag + "a", cur, t1, cin, mid, 1, sa, 0, s_1x1, True))
+            ops.append(Op("conv", tag + "b", t1, t2, mid, mid, 3, sb, 1, s_3x3, True))
+            if first:
+                ops.append(Op("conv", tag + "p", cur, tp, cin, cout, 1, stride, 0, s_1x1, False))
+                res = tp
+            else:
+                res = cur
+            ops.append(Op("conv", tag + "c", t2, other, mid, cout, 1, 1, 0, s_1x1, True, res=res))
+            cur, other = other, cur
+            cin = cout
+    ops.append(Op("avgpool", "gap", cur, 7))
+    ops.append(Op("fc", "fc", 7, 8, 2048, 1000, sparsity=s_fc, relu=False))
+    return ops
+
+
+def vgg16_ops(s_conv: float = 0.9, s_fc: float = 0.96) -> List[Op]:
+    cfg = [64, 64, "M", 128, 128, "M", 256, 256, 256, "M", 512, 512, 512, "M", 512, 512, 512, "M"]
+    ops: List[Op] = []
+    cur, cin, i = 0, 3, 0
+    nxt = 1
+    for v in cfg:
+        if v == "M":
+            ops.append(Op("maxpool", f"pool{len(ops)}", cur, nxt, k=2, stride=2, pad=0))
+        else:
+            i += 1
+            ops.append(Op("conv", f"conv{i}", cur, nxt, cin, int(v), 3, 1, 1, s_conv, True))
+            cin = int(v)
+        cur, nxt = nxt, (1 if nxt == 2 else 2)
+    ops.append(Op("fc", "fc1", cur, 3, 512 * 7 * 7, 4096, sparsity=s_fc, relu=True))
+    ops.append(Op("fc", "fc2", 3, 4, 4096, 4096, sparsity=s_fc, relu=True))
+    ops.append(Op("fc", "fc3", 4, 5, 4096, 1000, sparsity=s_fc, relu=False))
+    return ops
+
+
+def buffer_shapes(ops: Sequence[Op], input_shape: Tuple[int, int, int, int]) -> Dict[int, Tuple[int, ...]]:
+    """Largest shape each buffer id takes, by walking the op list (shape inference only)."""
+    cur: Dict[int, Tuple[int, ...]] = {0: tuple(input_shape)}
+    biggest: Dict[int, Tuple[int, ...]] = {0: tuple(input_shape)}
+    for op in ops:
+        s = cur[op.src]
+        if op.kind == "conv":
+            n, c, h, w = s
+            assert c == op.cin, (op, s)
+            o = (n, op.cout, conv_out_size(h, op.k, op.stride, op.pad),
+                 conv_out_size(w, op.k, op.stride, op.pad))
+        elif op.kind == "maxpool":
+            n, c, h, w = s
+            o = (n, c, conv_out_size(h, op.k, op.stride, op.pad),
+                 conv_out_size(w, op.k, op.stride, op.pad))
+        elif op.kind == "avgpool":
+            n, c, h, w = s
+            o = (n, c, 1, 1)
+        elif op.kind == "fc":
+            n = s[0]
+            assert int(np.prod(s[1:])) == op.cin, (op, s)
+            o = (n, op.cout, 1, 1)
+        else:
+            raise ValueError(op.kind)
+        cur[op.dst] = o
+        if op.dst not in biggest or np.prod(o) > np.prod(biggest[op.dst]):
+            biggest[op.dst] = o
+    return biggest
+
+
+def net_tensors(ops: Sequence[Op], config: str, input_shape, input_relu: bool = False,
+                mask: str = "magnitude"):
+    """Seeded input, pruned weights and biases for every conv/fc op of a net.
+
+    Returns (x, weights, biases): weights[i] / biases[i] are None for pool ops.
+    """
+    x = activation(input_shape, config, 0, relu=input_relu)
+    weights, biases = [], []
+    for i, op in enumerate(ops):
+        if op.kind == "conv":
+            weights.append(pruned_weights(op.cout, op.cin, op.k, op.k, op.sparsity, config, i + 1, mask))
+            biases.append(bias_vector(op.cout, config, i + 1))
+        elif op.kind == "fc":
+            weights.append(pruned_weights(op.cout, op.cin, 1, 1, op.sparsity, config, i + 1, mask))
+            biases.append(bias_vector(op.cout, config, i + 1))
+        else:
+            weights.append(None)
+            biases.append(None)
+    return x, weights, biases
