@@ -1,0 +1,182 @@
+/*
+ * libcadnn -- sparse-weight x dense-activation CNN inference layers for AMD gfx950.
+ *
+ * The operations follow the CADNN paper's statement of the problem: weights are
+ * pruned offline to unstructured sparsity (Section 3), stored compactly with
+ * their indices, and each layer runs as convolution + folded batch-norm (bias)
+ * + activation in ONE fused kernel (Section 4, "Model computation fusion and
+ * transformation"); 1x1 convolutions are matrix multiplies (same paragraph) and
+ * the filter layout is transformed for the device (Section 4, "Memory layout
+ * transformation and load optimization").
+ *
+ * General conventions
+ *   - Every call returns a cadnn_status; nothing throws or aborts.  The text of
+ *     the last failure on the calling thread is available from cadnn_last_error().
+ *   - Activations are NCHW, contiguous, in DEVICE memory owned by the caller.
+ *     Element type is float for CADNN_F32 handles and IEEE binary16 for
+ *     CADNN_F16 handles (products and sums are always taken in fp32).
+ *     Bias vectors are always fp32 device arrays of `cout` elements.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Compute calls are asynchronous on that stream and do not synchronise.
+ *   - Handles are opaque, owned by the library until the matching free call,
+ *     and bound to the device that was current when they were created.
+ *   - Host pointers are only read/written during the call that receives them.
+ */
+#ifndef CADNN_H
+#define CADNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    CADNN_OK = 0,
+    CADNN_EINVAL = 1,        /* NULL pointer, non-positive size, empty output, mismatched handle */
+    CADNN_EUNSUPPORTED = 2,  /* valid request this build has no kernel for */
+    CADNN_ENOMEM = 3,        /* host or device allocation failed */
+    CADNN_EHIP = 4           /* a HIP runtime call failed (text in cadnn_last_error) */
+} cadnn_status;
+
+typedef enum {
+    CADNN_F32 = 0,           /* fp32 storage, fp32 accumulate */
+    CADNN_F16 = 1            /* fp16 storage (weights, activations, residual, output), fp32 accumulate */
+} cadnn_dtype;
+
+typedef struct cadnn_weights cadnn_weights;
+typedef struct cadnn_net cadnn_net;
+
+/* Text of the most recent error on this thread ("" if none).  Never NULL. */
+const char* cadnn_last_error(void);
+
+/* ------------------------------------------------------------------------- *
+ * Weight packing (Section 3: pruned weights are exact zeros stored with their
+ * indices; Section 4: filter layout transformed for the device).
+ *
+ * w_host: HOST pointer to the dense pruned tensor [cout][cin][kh][kw], fp32.
+ * A fully connected layer is kh = kw = 1.  An entry is a nonzero iff its fp32
+ * value != 0.  The canonical compact form is: row co = filter of output channel
+ * co flattened over k = (ci*kh_ + r)*kw_ + c; entries of a row in ascending k;
+ * rows ordered by nonzero count, descending, ties by ascending channel (so that
+ * neighbouring rows -- which share a wavefront or workgroup -- carry balanced
+ * work).  For CADNN_F16 values are rounded to nearest-even binary16 after the
+ * fp32 nonzero test.  An all-zero tensor is valid.  Packing is pure host work
+ * (no GPU needed); device-side layouts derived from the canonical form are
+ * built on the first use of a layer geometry, on the device current at that
+ * time (see cadnn_conv2d_prepare / cadnn_fc_prepare).
+ * Errors: EINVAL for NULL / non-positive sizes; EUNSUPPORTED if cin*kh*kw or
+ * cout exceed 2^24; ENOMEM.  *out is set to NULL on failure.
+ * ------------------------------------------------------------------------- */
+cadnn_status cadnn_pack_weights(const float* w_host, int cout, int cin, int kh, int kw,
+                                cadnn_dtype dtype, cadnn_weights** out);
+cadnn_status cadnn_free_weights(cadnn_weights* w);   /* NULL is accepted */
+
+/* Number of stored nonzeros. */
+cadnn_status cadnn_packed_nnz(const cadnn_weights* w, int64_t* nnz);
+/* Copies the canonical form to HOST arrays: perm[cout], row_ptr[cout+1],
+ * col_idx[nnz] (int32 k), vals[nnz] (float for F32 handles, uint16 binary16 bit
+ * patterns for F16 handles).  Any output pointer may be NULL to skip it. */
+cadnn_status cadnn_packed_export(const cadnn_weights* w, int32_t* perm, int32_t* row_ptr,
+                                 int32_t* col_idx, void* vals);
+/* Inverse of packing: writes the dense HOST tensor [cout][cin][kh][kw] (fp32;
+ * for F16 handles the binary16 values widened exactly), zeros elsewhere. */
+cadnn_status cadnn_unpack_weights(const cadnn_weights* w, float* w_host_out);
+
+/* ------------------------------------------------------------------------- *
+ * Fused sparse convolution layer (Section 4: conv + batch-norm + activation in
+ * one kernel; batch-norm arrives pre-folded as `bias`):
+ *
+ *   y[n][co][oh][ow] = act( sum_{ci,r,c} W[co][ci][r][c] * X~[n][ci][oh*stride+r-pad][ow*stride+c-pad]
+ *                           + bias[co] + residual[n][co][oh][ow] )
+ *
+ * X~ is x inside the image and 0 outside; hout = (h + 2*pad - kh)/stride + 1
+ * (floor), wout likewise; act = ReLU if relu != 0 else identity.
+ * x: device [n][cin][h][wdt]; y: device [n][cout][hout][wout]; bias: device
+ * fp32 [cout] or NULL; residual: device, same shape/type as y, or NULL.
+ * y must not overlap x.  residual may be y itself (in-place add: each element
+ * is read before the same thread writes it) but must not partially overlap it.
+ * The first call with a new (h, wdt, stride, pad, n) geometry may build and
+ * upload a device layout (allocates, synchronous); call cadnn_conv2d_prepare
+ * beforehand to keep the timed call allocation-free.
+ * Errors: EINVAL (NULL x/y/w, sizes <= 0, stride <= 0, pad < 0, empty output);
+ * EUNSUPPORTED (no kernel variant for the geometry); EHIP.
+ * ------------------------------------------------------------------------- */
+cadnn_status cadnn_sparse_conv2d(const cadnn_weights* w, const void* x, void* y, int n, int h,
+                                 int wdt, int stride, int pad, const void* bias,
+                                 const void* residual, int relu, void* stream);
+/* Builds whatever device layout cadnn_sparse_conv2d would need for this geometry. */
+cadnn_status cadnn_conv2d_prepare(const cadnn_weights* w, int n, int h, int wdt, int stride,
+                                  int pad);
+
+/* Sparse fully connected layer: y[n][o] = act( sum_i W[o][i]*x[n][i] + bias[o] ).
+ * w must have kh = kw = 1; x: device [n][cin]; y: device [n][cout]. */
+cadnn_status cadnn_sparse_fc(const cadnn_weights* w, const void* x, void* y, int n,
+                             const void* bias, int relu, void* stream);
+/* Uploads the device arrays cadnn_sparse_fc needs (otherwise done on its first call). */
+cadnn_status cadnn_fc_prepare(const cadnn_weights* w);
+
+/* Pooling layers used between the convolutions of the benchmark networks.
+ * Max pooling takes the maximum over the in-image part of each k x k window
+ * (padding never wins); global average pooling writes y[n][c] = mean over h*w. */
+cadnn_status cadnn_maxpool2d(const void* x, void* y, int n, int c, int h, int wdt, int k,
+                             int stride, int pad, cadnn_dtype dtype, void* stream);
+cadnn_status cadnn_global_avgpool(const void* x, void* y, int n, int c, int h, int wdt,
+                                  cadnn_dtype dtype, void* stream);
+
+/* Dense comparator on the same ABI (implicit-GEMM convolution over the dense
+ * [cout][cin][kh][kw] DEVICE weight tensor, same fused epilogue), used for the
+ * dense-vs-compressed comparison the paper reports (Section 5) and as the
+ * fallback for layers that are not pruned. */
+cadnn_status cadnn_dense_conv2d(const void* w_dev, const void* x, void* y, int n, int cin, int h,
+                                int wdt, int cout, int kh, int kw, int stride, int pad,
+                                const void* bias, const void* residual, int relu,
+                                cadnn_dtype dtype, void* stream);
+
+/* ------------------------------------------------------------------------- *
+ * Whole-network runner (Section 5 measures single-image latency of a whole
+ * network): an ordered list of ops over numbered activation buffers.  Buffer 0
+ * is the network input (shape given at creation); the last op's dst buffer is
+ * the network output.  All other buffers live in one caller-provided device
+ * workspace.  Weight handles and bias arrays must outlive the net.
+ *   create -> add_* (shapes are inferred and checked op by op) ->
+ *   workspace_bytes -> finalize(workspace) -> run (any number of times) -> free
+ * cadnn_run_net launches every op on `stream` in order (as one HIP graph launch
+ * when graph capture was requested in finalize); x / y are the device input and
+ * output tensors.  No host synchronisation inside.
+ * ------------------------------------------------------------------------- */
+cadnn_status cadnn_net_create(cadnn_dtype dtype, int n, int c, int h, int w, cadnn_net** out);
+cadnn_status cadnn_net_add_conv(cadnn_net* net, const cadnn_weights* w, const void* bias_dev,
+                                int stride, int pad, int relu, int src_buf, int dst_buf,
+                                int residual_buf /* -1 = none */);
+cadnn_status cadnn_net_add_maxpool(cadnn_net* net, int k, int stride, int pad, int src_buf,
+                                   int dst_buf);
+cadnn_status cadnn_net_add_global_avgpool(cadnn_net* net, int src_buf, int dst_buf);
+cadnn_status cadnn_net_add_fc(cadnn_net* net, const cadnn_weights* w, const void* bias_dev,
+                              int relu, int src_buf, int dst_buf);
+cadnn_status cadnn_net_workspace_bytes(const cadnn_net* net, size_t* bytes);
+/* use_graph != 0: cadnn_run_net replays a captured HIP graph (re-captured when
+ * x / y change between calls). */
+cadnn_status cadnn_net_finalize(cadnn_net* net, void* workspace_dev, size_t bytes, int use_graph);
+cadnn_status cadnn_run_net(cadnn_net* net, const void* x, void* y, void* stream);
+/* Number of ops, and per-op device time of one eager pass measured with HIP
+ * events on `stream` (synchronises; ms_per_op has cadnn_net_num_ops entries). */
+cadnn_status cadnn_net_num_ops(const cadnn_net* net, int* num_ops);
+cadnn_status cadnn_net_profile(cadnn_net* net, const void* x, void* y, void* stream, int repeats,
+                               float* ms_per_op);
+/* Copies the current contents of activation buffer `buf` (as left by the last
+ * run) to a HOST array of `bytes` bytes; synchronises `stream`. */
+cadnn_status cadnn_net_read_buffer(cadnn_net* net, int buf, void* host_out, size_t bytes,
+                                   void* stream);
+cadnn_status cadnn_net_free(cadnn_net* net);          /* NULL is accepted */
+
+/* Name of the kernel variant cadnn_sparse_conv2d / cadnn_sparse_fc would launch
+ * for this geometry, written to buf (NUL-terminated, truncated to len). */
+cadnn_status cadnn_conv2d_variant_name(const cadnn_weights* w, int n, int h, int wdt, int stride,
+                                       int pad, char* buf, size_t len);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CADNN_H */

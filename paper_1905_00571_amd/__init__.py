@@ -1,0 +1,31 @@
+"""Thin Python binding over libcadnn.so (argument marshalling only).
+
+Every function here has the name of the C entry point it forwards to (see
+include/cadnn.h); all arithmetic runs in the HIP kernels behind the C ABI.
+PyTorch is used only to own device memory and streams.  If the shared library
+has not been built the import fails loudly: there is no CPU fallback.
+"""
+from .binding import (  # noqa: F401
+    CadnnError,
+    F32,
+    F16,
+    lib,
+    lib_path,
+    Weights,
+    Net,
+    cadnn_pack_weights,
+    cadnn_free_weights,
+    cadnn_packed_nnz,
+    cadnn_packed_export,
+    cadnn_unpack_weights,
+    cadnn_sparse_conv2d,
+    cadnn_conv2d_prepare,
+    cadnn_conv2d_variant_name,
+    cadnn_sparse_fc,
+    cadnn_fc_prepare,
+    cadnn_maxpool2d,
+    cadnn_global_avgpool,
+    cadnn_dense_conv2d,
+    cadnn_run_net,
+    build_net,
+)

@@ -1,0 +1,141 @@
+// Internal declarations shared by the translation units of libcadnn.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <map>
+#include <memory>
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "cadnn.h"
+
+namespace cadnn {
+
+// ---- error reporting -------------------------------------------------------
+cadnn_status fail(cadnn_status code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+void clear_error();
+
+#define CADNN_HIP(expr)                                                                     \
+    do {                                                                                    \
+        hipError_t e_ = (expr);                                                             \
+        if (e_ != hipSuccess)                                                               \
+            return ::cadnn::fail(CADNN_EHIP, "%s failed: %s (%s:%d)", #expr,                \
+                                 hipGetErrorString(e_), __FILE__, __LINE__);                \
+    } while (0)
+
+inline int conv_out(int size, int k, int stride, int pad) {
+    const int t = size + 2 * pad - k;
+    return t < 0 ? 0 : t / stride + 1;
+}
+
+// ---- device buffer with RAII -------------------------------------------------
+struct DevBuf {
+    void* p = nullptr;
+    size_t bytes = 0;
+    DevBuf() = default;
+    DevBuf(const DevBuf&) = delete;
+    DevBuf& operator=(const DevBuf&) = delete;
+    ~DevBuf() { release(); }
+    void release() {
+        if (p) (void)hipFree(p);
+        p = nullptr;
+        bytes = 0;
+    }
+    // Allocates (at least 16 bytes so that p is never NULL) and uploads `n` bytes from host.
+    cadnn_status upload(const void* host, size_t n);
+};
+
+// ---- tile-kernel variants ----------------------------------------------------
+// A variant is one instantiation of the LDS-tiled sparse convolution kernel.  Its
+// compile-time geometry decides how a canonical column index k = (ci*KH + r)*KW + c is
+// translated into a byte offset inside the staged activation tile, so every variant
+// needs its own device copy of the nonzero stream (a "plan").
+struct TileVariant {
+    const char* name;
+    int kh, kw, stride;   // filter geometry served
+    int tw, rw, p;        // lanes along ow, lane rows per wave, pixels per lane (stacked in oh)
+    int nw, rpw;          // waves per workgroup, packed rows per wave
+    int cch;              // input channels staged per chunk
+    int th;               // = rw * p   output rows per tile
+    int rh, nrph;         // LDS rows per row phase, number of row phases
+    int cw, nph;          // LDS columns per column phase, number of column phases
+    int pitch, plane;     // LDS floats per tile row / per channel
+    int unroll;           // nonzeros per scalar fetch; segments are padded to a multiple of it
+    size_t lds_bytes;
+    int elem_bytes;       // size of one staged tile element in LDS
+    bool is_f16;          // activation storage type served (false = fp32, true = fp16)
+    // launcher
+    hipError_t (*launch)(const struct ConvLaunch&, hipStream_t);
+};
+
+struct ConvLaunch {
+    const void* x;
+    void* y;
+    const float* bias;
+    const void* residual;
+    const uint2* nz;          // (value bits, byte offset) pairs, segment-padded
+    const int32_t* seg_ptr;   // [rows_padded][nchunks + 1] indices into nz
+    const int32_t* perm;      // [rows_padded] original channel, -1 for padding rows
+    int n, cin, h, w, cout, hout, wout, pad, relu, nchunks;
+    int tiles_x, tiles_y, row_groups;
+};
+
+struct ConvPlan {
+    const TileVariant* variant = nullptr;
+    DevBuf nz, seg_ptr, perm;
+    int nchunks = 0;
+    int rows_padded = 0;
+    int64_t nz_padded = 0;
+};
+
+const TileVariant* select_tile_variant(int kh, int kw, int stride, int hout, int wout, int cout,
+                                       cadnn_dtype dtype);
+const std::vector<TileVariant>& all_tile_variants();
+
+}  // namespace cadnn
+
+// ---- opaque handles ----------------------------------------------------------
+struct cadnn_weights {
+    int cout = 0, cin = 0, kh = 0, kw = 0;
+    cadnn_dtype dtype = CADNN_F32;
+    int64_t nnz = 0;
+    // canonical form (host)
+    std::vector<int32_t> perm, row_ptr, col_idx;
+    std::vector<float> vals;       // fp32 values (for F16 handles: the binary16 value widened)
+    std::vector<uint16_t> vals16;  // F16 handles only: binary16 bit patterns
+    // device copies used by the FC kernel (canonical order)
+    mutable cadnn::DevBuf d_row_ptr, d_perm, d_col, d_val;
+    mutable bool fc_ready = false;
+    // per-variant conv plans, built lazily
+    mutable std::mutex mu;
+    mutable std::map<const cadnn::TileVariant*, std::unique_ptr<cadnn::ConvPlan>> plans;
+};
+
+namespace cadnn {
+cadnn_status get_conv_plan(const cadnn_weights* w, const TileVariant* v, const ConvPlan** out);
+cadnn_status ensure_fc_device(const cadnn_weights* w);
+uint16_t f32_to_f16_rne(float f);
+float f16_to_f32(uint16_t h);
+
+cadnn_status launch_fc(const cadnn_weights* w, const void* x, void* y, int n, const float* bias,
+                       int relu, hipStream_t s);
+cadnn_status launch_maxpool(const void* x, void* y, int n, int c, int h, int wdt, int k, int stride,
+                            int pad, cadnn_dtype dt, hipStream_t s);
+cadnn_status launch_avgpool(const void* x, void* y, int n, int c, int h, int wdt, cadnn_dtype dt,
+                            hipStream_t s);
+}  // namespace cadnn
+
+namespace cadnn {
+cadnn_status conv2d_impl(const cadnn_weights* w, const void* x, void* y, int n, int h, int wdt,
+                         int stride, int pad, const void* bias, const void* residual, int relu,
+                         hipStream_t s);
+cadnn_status dense_conv2d_impl(const void* w_dev, const void* x, void* y, int n, int cin, int h,
+                               int wdt, int cout, int kh, int kw, int stride, int pad,
+                               const void* bias, const void* residual, int relu, cadnn_dtype dtype,
+                               hipStream_t s);
+}  // namespace cadnn

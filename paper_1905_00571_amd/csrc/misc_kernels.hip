@@ -1,0 +1,152 @@
+// Sparse fully connected layer (row-per-wave SpMV / skinny SpMM) and the pooling layers
+// that sit between the convolutions of the benchmark networks.
+#include "internal.h"
+
+namespace cadnn {
+
+// One wave per packed row: lanes stride over the row's nonzeros with coalesced loads of
+// (value, column), gather the activations, and finish with a wavefront shuffle reduction.
+// NB batch entries are carried per pass so the weights are streamed once per NB images.
+template <typename T, int NB>
+__global__ __launch_bounds__(256) void sfc_kernel(const int32_t* __restrict__ row_ptr,
+                                                  const int32_t* __restrict__ perm,
+                                                  const int32_t* __restrict__ col,
+                                                  const float* __restrict__ val,
+                                                  const T* __restrict__ x, T* __restrict__ y,
+                                                  const float* __restrict__ bias, int n, int cin,
+                                                  int cout, int relu) {
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= cout) return;
+    const int n0 = blockIdx.y * NB;
+    const int s = row_ptr[row], e = row_ptr[row + 1];
+    float acc[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) acc[b] = 0.0f;
+    for (int i = s + lane; i < e; i += 64) {
+        const int c = col[i];
+        const float v = val[i];
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+            if (n0 + b < n) acc[b] = fmaf(v, (float)x[(size_t)(n0 + b) * cin + c], acc[b]);
+    }
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        float v = acc[b];
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+        acc[b] = v;
+    }
+    if (lane == 0) {
+        const int co = perm[row];
+        const float bv = bias ? bias[co] : 0.0f;
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            if (n0 + b < n) {
+                float v = acc[b] + bv;
+                if (relu) v = v > 0.0f ? v : 0.0f;
+                y[(size_t)(n0 + b) * cout + co] = (T)v;
+            }
+        }
+    }
+}
+
+template <typename T>
+static cadnn_status launch_fc_t(const cadnn_weights* w, const void* x, void* y, int n,
+                                const float* bias, int relu, hipStream_t s) {
+    const int rows_per_block = 4;
+    const unsigned gx = (unsigned)((w->cout + rows_per_block - 1) / rows_per_block);
+    const int32_t* rp = (const int32_t*)w->d_row_ptr.p;
+    const int32_t* pm = (const int32_t*)w->d_perm.p;
+    const int32_t* cl = (const int32_t*)w->d_col.p;
+    const float* vl = (const float*)w->d_val.p;
+    if (n == 1) {
+        hipLaunchKernelGGL((sfc_kernel<T, 1>), dim3(gx, 1), dim3(256), 0, s, rp, pm, cl, vl,
+                           (const T*)x, (T*)y, bias, n, w->cin, w->cout, relu);
+    } else {
+        constexpr int NB = 8;
+        hipLaunchKernelGGL((sfc_kernel<T, NB>), dim3(gx, (unsigned)((n + NB - 1) / NB)), dim3(256),
+                           0, s, rp, pm, cl, vl, (const T*)x, (T*)y, bias, n, w->cin, w->cout, relu);
+    }
+    CADNN_HIP(hipGetLastError());
+    return CADNN_OK;
+}
+
+cadnn_status launch_fc(const cadnn_weights* w, const void* x, void* y, int n, const float* bias,
+                       int relu, hipStream_t s) {
+    return w->dtype == CADNN_F16 ? launch_fc_t<_Float16>(w, x, y, n, bias, relu, s)
+                                 : launch_fc_t<float>(w, x, y, n, bias, relu, s);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void maxpool_kernel(const T* __restrict__ x, T* __restrict__ y,
+                                                      int nc, int h, int w, int hout, int wout,
+                                                      int k, int stride, int pad) {
+    const size_t total = (size_t)nc * hout * wout;
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    const int ow = (int)(i % wout);
+    const int oh = (int)((i / wout) % hout);
+    const size_t c = i / ((size_t)wout * hout);
+    const T* xp = x + c * (size_t)h * w;
+    bool seen = false;
+    float m = 0.0f;
+    for (int r = 0; r < k; ++r) {
+        const int ih = oh * stride + r - pad;
+        if (ih < 0 || ih >= h) continue;
+        for (int q = 0; q < k; ++q) {
+            const int iw = ow * stride + q - pad;
+            if (iw < 0 || iw >= w) continue;
+            const float v = (float)xp[(size_t)ih * w + iw];
+            if (!seen || v > m) m = v;
+            seen = true;
+        }
+    }
+    y[i] = (T)m;
+}
+
+// One wave per (n, c) plane; lanes stride over the plane, shuffle reduction at the end.
+template <typename T>
+__global__ __launch_bounds__(256) void avgpool_kernel(const T* __restrict__ x, T* __restrict__ y,
+                                                      int nc, int hw) {
+    const int lane = threadIdx.x & 63;
+    const int plane = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (plane >= nc) return;
+    const T* xp = x + (size_t)plane * hw;
+    float s = 0.0f;
+    for (int i = lane; i < hw; i += 64) s += (float)xp[i];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+    if (lane == 0) y[plane] = (T)(s / (float)hw);
+}
+
+cadnn_status launch_maxpool(const void* x, void* y, int n, int c, int h, int wdt, int k, int stride,
+                            int pad, cadnn_dtype dt, hipStream_t s) {
+    const int hout = conv_out(h, k, stride, pad), wout = conv_out(wdt, k, stride, pad);
+    const size_t total = (size_t)n * c * hout * wout;
+    const unsigned blocks = (unsigned)((total + 255) / 256);
+    if (dt == CADNN_F16)
+        hipLaunchKernelGGL(maxpool_kernel<_Float16>, dim3(blocks), dim3(256), 0, s,
+                           (const _Float16*)x, (_Float16*)y, n * c, h, wdt, hout, wout, k, stride, pad);
+    else
+        hipLaunchKernelGGL(maxpool_kernel<float>, dim3(blocks), dim3(256), 0, s, (const float*)x,
+                           (float*)y, n * c, h, wdt, hout, wout, k, stride, pad);
+    CADNN_HIP(hipGetLastError());
+    return CADNN_OK;
+}
+
+cadnn_status launch_avgpool(const void* x, void* y, int n, int c, int h, int wdt, cadnn_dtype dt,
+                            hipStream_t s) {
+    const int nc = n * c;
+    const unsigned blocks = (unsigned)((nc + 3) / 4);
+    if (dt == CADNN_F16)
+        hipLaunchKernelGGL(avgpool_kernel<_Float16>, dim3(blocks), dim3(256), 0, s,
+                           (const _Float16*)x, (_Float16*)y, nc, h * wdt);
+    else
+        hipLaunchKernelGGL(avgpool_kernel<float>, dim3(blocks), dim3(256), 0, s, (const float*)x,
+                           (float*)y, nc, h * wdt);
+    CADNN_HIP(hipGetLastError());
+    return CADNN_OK;
+}
+
+}  // namespace cadnn

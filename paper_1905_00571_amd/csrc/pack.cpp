@@ -1,0 +1,287 @@
+// Host-side weight packing: dense pruned tensor -> canonical permuted row-compressed form
+// (paper Section 3: pruned weights are exact zeros kept with their indices; Section 4:
+// filter memory layout is transformed for the device) and the per-variant device plans.
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <numeric>
+
+#include "internal.h"
+
+namespace cadnn {
+
+static thread_local std::string g_last_error;
+
+cadnn_status fail(cadnn_status code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof(buf), fmt, ap);
+    va_end(ap);
+    g_last_error = buf;
+    return code;
+}
+void clear_error() { g_last_error.clear(); }
+
+cadnn_status DevBuf::upload(const void* host, size_t n) {
+    release();
+    const size_t alloc = n < 16 ? 16 : n;
+    hipError_t e = hipMalloc(&p, alloc);
+    if (e != hipSuccess) {
+        p = nullptr;
+        return fail(CADNN_ENOMEM, "hipMalloc(%zu) failed: %s", alloc, hipGetErrorString(e));
+    }
+    bytes = alloc;
+    if (n) CADNN_HIP(hipMemcpy(p, host, n, hipMemcpyHostToDevice));
+    return CADNN_OK;
+}
+
+// IEEE binary32 -> binary16, round to nearest even (overflow -> inf, NaN kept quiet).
+uint16_t f32_to_f16_rne(float f) {
+    uint32_t x;
+    std::memcpy(&x, &f, 4);
+    const uint32_t sign = (x >> 16) & 0x8000u;
+    const uint32_t absx = x & 0x7fffffffu;
+    if (absx >= 0x7f800000u) {  // inf / NaN
+        return (uint16_t)(sign | 0x7c00u | (absx > 0x7f800000u ? (0x200u | ((absx >> 13) & 0x3ffu)) : 0));
+    }
+    const int32_t exp = (int32_t)(absx >> 23) - 127;
+    if (exp > 15) return (uint16_t)(sign | 0x7c00u);  // too large even before rounding
+    uint32_t mant = absx & 0x7fffffu;
+    if (exp >= -14) {
+        // normal half candidate: keep 10 mantissa bits, round on the 13 dropped
+        uint32_t half = ((uint32_t)(exp + 15) << 10) | (mant >> 13);
+        const uint32_t rem = mant & 0x1fffu;
+        if (rem > 0x1000u || (rem == 0x1000u && (half & 1u))) ++half;  // carry may reach inf: correct
+        return (uint16_t)(sign | half);
+    }
+    if (exp < -25) return (uint16_t)sign;  // below half of the smallest subnormal
+    // subnormal half: value = mant24 * 2^(exp-23); unit = 2^-24
+    mant |= 0x800000u;
+    const int shift = -exp - 1;  // 14..24 -> bits dropped from the 24-bit significand: shift
+    const uint32_t q = mant >> shift;
+    const uint32_t rem = mant & ((1u << shift) - 1u);
+    const uint32_t halfway = 1u << (shift - 1);
+    uint32_t half = q;
+    if (rem > halfway || (rem == halfway && (half & 1u))) ++half;
+    return (uint16_t)(sign | half);
+}
+
+float f16_to_f32(uint16_t h) {
+    const uint32_t sign = ((uint32_t)h & 0x8000u) << 16;
+    const uint32_t exp = (h >> 10) & 0x1fu;
+    uint32_t mant = h & 0x3ffu;
+    uint32_t out;
+    if (exp == 0) {
+        if (mant == 0) {
+            out = sign;
+        } else {  // subnormal: normalise
+            int e = -1;
+            do {
+                ++e;
+                mant <<= 1;
+            } while (!(mant & 0x400u));
+            out = sign | ((uint32_t)(127 - 15 - e) << 23) | ((mant & 0x3ffu) << 13);
+        }
+    } else if (exp == 31) {
+        out = sign | 0x7f800000u | (mant << 13);
+    } else {
+        out = sign | ((exp + 112u) << 23) | (mant << 13);
+    }
+    float f;
+    std::memcpy(&f, &out, 4);
+    return f;
+}
+
+// Builds the device copy of the nonzero stream for one tile-kernel variant.
+//
+// Layout: packed rows are padded up to a multiple of the variant's rows-per-workgroup.
+// For packed row i and channel chunk c, seg_ptr[i*(nchunks+1) + c .. + c+1] delimits that
+// row's nonzeros whose input channel lies in [c*cch, (c+1)*cch); every segment is padded
+// with (0.0f, offset 0) pairs to a multiple of `unroll` entries so the kernel can fetch
+// fixed-size groups.  Each entry is (fp32 value bits, byte offset of the tap inside the
+// staged tile for output pixel (0,0) of the tile).
+static cadnn_status build_plan(const cadnn_weights* w, const TileVariant* v, ConvPlan* plan) {
+    const int g = v->nw * v->rpw;
+    const int rows_padded = (w->cout + g - 1) / g * g;
+    const int nchunks = (w->cin + v->cch - 1) / v->cch;
+    const int taps = w->kh * w->kw;
+    std::vector<int32_t> seg((size_t)rows_padded * (nchunks + 1), 0);
+    std::vector<int32_t> perm(rows_padded, -1);
+    std::vector<uint2> nz;
+    nz.reserve((size_t)w->nnz + (size_t)rows_padded * nchunks * (v->unroll - 1) / 2 + 16);
+    for (int i = 0; i < rows_padded; ++i) {
+        if (i < w->cout) perm[i] = w->perm[i];
+        int32_t cur = i < w->cout ? w->row_ptr[i] : 0;
+        const int32_t end = i < w->cout ? w->row_ptr[i + 1] : 0;
+        for (int c = 0; c < nchunks; ++c) {
+            seg[(size_t)i * (nchunks + 1) + c] = (int32_t)nz.size();
+            const int32_t k_end = (int32_t)std::min<int64_t>((int64_t)(c + 1) * v->cch, w->cin) * taps;
+            while (cur < end && w->col_idx[cur] < k_end) {
+                const int32_t k = w->col_idx[cur];
+                const int ci = k / taps - c * v->cch;
+                const int r = (k % taps) / w->kw;
+                const int q = k % w->kw;
+                const int lrow = (r % v->stride) * v->rh + r / v->stride;
+                const int lcol = (q % v->stride) * v->cw + q / v->stride;
+                const uint32_t off = (uint32_t)((ci * v->plane + lrow * v->pitch + lcol) * v->elem_bytes);
+                uint32_t bits;
+                std::memcpy(&bits, &w->vals[cur], 4);
+                nz.push_back(make_uint2(bits, off));
+                ++cur;
+            }
+            while (nz.size() % (size_t)v->unroll) nz.push_back(make_uint2(0u, 0u));
+        }
+        seg[(size_t)i * (nchunks + 1) + nchunks] = (int32_t)nz.size();
+    }
+    if (nz.size() > (size_t)INT32_MAX) return fail(CADNN_EUNSUPPORTED, "plan too large");
+    plan->variant = v;
+    plan->nchunks = nchunks;
+    plan->rows_padded = rows_padded;
+    plan->nz_padded = (int64_t)nz.size();
+    cadnn_status st;
+    if ((st = plan->nz.upload(nz.data(), nz.size() * sizeof(uint2))) != CADNN_OK) return st;
+    if ((st = plan->seg_ptr.upload(seg.data(), seg.size() * 4)) != CADNN_OK) return st;
+    if ((st = plan->perm.upload(perm.data(), perm.size() * 4)) != CADNN_OK) return st;
+    return CADNN_OK;
+}
+
+cadnn_status get_conv_plan(const cadnn_weights* w, const TileVariant* v, const ConvPlan** out) {
+    std::lock_guard<std::mutex> lock(w->mu);
+    auto it = w->plans.find(v);
+    if (it == w->plans.end()) {
+        std::unique_ptr<ConvPlan> plan(new (std::nothrow) ConvPlan());
+        if (!plan) return fail(CADNN_ENOMEM, "out of host memory");
+        cadnn_status st;
+        try {
+            st = build_plan(w, v, plan.get());
+        } catch (const std::bad_alloc&) {
+            return fail(CADNN_ENOMEM, "out of host memory building a conv plan");
+        }
+        if (st != CADNN_OK) return st;
+        it = w->plans.emplace(v, std::move(plan)).first;
+    }
+    *out = it->second.get();
+    return CADNN_OK;
+}
+
+// Device copies of the canonical arrays, used by the fully connected kernel.
+cadnn_status ensure_fc_device(const cadnn_weights* w) {
+    std::lock_guard<std::mutex> lock(w->mu);
+    if (w->fc_ready) return CADNN_OK;
+    cadnn_status st;
+    if ((st = w->d_row_ptr.upload(w->row_ptr.data(), w->row_ptr.size() * 4)) != CADNN_OK) return st;
+    if ((st = w->d_perm.upload(w->perm.data(), w->perm.size() * 4)) != CADNN_OK) return st;
+    if ((st = w->d_col.upload(w->col_idx.data(), w->col_idx.size() * 4)) != CADNN_OK) return st;
+    if ((st = w->d_val.upload(w->vals.data(), w->vals.size() * 4)) != CADNN_OK) return st;
+    w->fc_ready = true;
+    return CADNN_OK;
+}
+
+}  // namespace cadnn
+
+using namespace cadnn;
+
+extern "C" const char* cadnn_last_error(void) { return g_last_error.c_str(); }
+
+extern "C" cadnn_status cadnn_pack_weights(const float* w_host, int cout, int cin, int kh, int kw,
+                                           cadnn_dtype dtype, cadnn_weights** out) {
+    if (out) *out = nullptr;
+    if (!w_host || !out) return fail(CADNN_EINVAL, "cadnn_pack_weights: NULL pointer");
+    if (cout <= 0 || cin <= 0 || kh <= 0 || kw <= 0)
+        return fail(CADNN_EINVAL, "cadnn_pack_weights: non-positive size");
+    if (dtype != CADNN_F32 && dtype != CADNN_F16)
+        return fail(CADNN_EINVAL, "cadnn_pack_weights: unknown dtype %d", (int)dtype);
+    const int64_t K = (int64_t)cin * kh * kw;
+    if (K > (1 << 24) || cout > (1 << 24))
+        return fail(CADNN_EUNSUPPORTED, "cadnn_pack_weights: cin*kh*kw or cout above 2^24");
+    std::unique_ptr<cadnn_weights> w;
+    try {
+        w.reset(new cadnn_weights());
+        w->cout = cout;
+        w->cin = cin;
+        w->kh = kh;
+        w->kw = kw;
+        w->dtype = dtype;
+        // pass 1: nonzero count per row
+        std::vector<int32_t> counts(cout);
+        int64_t nnz = 0;
+        for (int r = 0; r < cout; ++r) {
+            const float* row = w_host + (int64_t)r * K;
+            int32_t c = 0;
+            for (int64_t k = 0; k < K; ++k) c += (row[k] != 0.0f);
+            counts[r] = c;
+            nnz += c;
+        }
+        if (nnz > (int64_t)INT32_MAX) return fail(CADNN_EUNSUPPORTED, "more than 2^31-1 nonzeros");
+        w->nnz = nnz;
+        // rows by nonzero count, descending; ties by ascending channel
+        w->perm.resize(cout);
+        std::iota(w->perm.begin(), w->perm.end(), 0);
+        std::stable_sort(w->perm.begin(), w->perm.end(),
+                         [&](int32_t a, int32_t b) { return counts[a] > counts[b]; });
+        w->row_ptr.assign(cout + 1, 0);
+        for (int i = 0; i < cout; ++i) w->row_ptr[i + 1] = w->row_ptr[i] + counts[w->perm[i]];
+        w->col_idx.resize((size_t)nnz);
+        w->vals.resize((size_t)nnz);
+        if (dtype == CADNN_F16) w->vals16.resize((size_t)nnz);
+        for (int i = 0; i < cout; ++i) {
+            const float* row = w_host + (int64_t)w->perm[i] * K;
+            int64_t o = w->row_ptr[i];
+            for (int64_t k = 0; k < K; ++k) {
+                if (row[k] != 0.0f) {
+                    w->col_idx[o] = (int32_t)k;
+                    if (dtype == CADNN_F16) {
+                        const uint16_t hbits = f32_to_f16_rne(row[k]);
+                        w->vals16[o] = hbits;
+                        w->vals[o] = f16_to_f32(hbits);
+                    } else {
+                        w->vals[o] = row[k];
+                    }
+                    ++o;
+                }
+            }
+        }
+    } catch (const std::bad_alloc&) {
+        return fail(CADNN_ENOMEM, "cadnn_pack_weights: out of host memory");
+    }
+    *out = w.release();
+    return CADNN_OK;
+}
+
+extern "C" cadnn_status cadnn_free_weights(cadnn_weights* w) {
+    delete w;
+    return CADNN_OK;
+}
+
+extern "C" cadnn_status cadnn_packed_nnz(const cadnn_weights* w, int64_t* nnz) {
+    if (!w || !nnz) return fail(CADNN_EINVAL, "cadnn_packed_nnz: NULL pointer");
+    *nnz = w->nnz;
+    return CADNN_OK;
+}
+
+extern "C" cadnn_status cadnn_packed_export(const cadnn_weights* w, int32_t* perm, int32_t* row_ptr,
+                                            int32_t* col_idx, void* vals) {
+    if (!w) return fail(CADNN_EINVAL, "cadnn_packed_export: NULL handle");
+    if (perm) std::memcpy(perm, w->perm.data(), w->perm.size() * 4);
+    if (row_ptr) std::memcpy(row_ptr, w->row_ptr.data(), w->row_ptr.size() * 4);
+    if (col_idx && w->nnz) std::memcpy(col_idx, w->col_idx.data(), w->col_idx.size() * 4);
+    if (vals && w->nnz) {
+        if (w->dtype == CADNN_F16)
+            std::memcpy(vals, w->vals16.data(), w->vals16.size() * 2);
+        else
+            std::memcpy(vals, w->vals.data(), w->vals.size() * 4);
+    }
+    return CADNN_OK;
+}
+
+extern "C" cadnn_status cadnn_unpack_weights(const cadnn_weights* w, float* out) {
+    if (!w || !out) return fail(CADNN_EINVAL, "cadnn_unpack_weights: NULL pointer");
+    const int64_t K = (int64_t)w->cin * w->kh * w->kw;
+    std::memset(out, 0, (size_t)w->cout * K * sizeof(float));
+    for (int i = 0; i < w->cout; ++i) {
+        float* row = out + (int64_t)w->perm[i] * K;
+        for (int32_t j = w->row_ptr[i]; j < w->row_ptr[i + 1]; ++j) row[w->col_idx[j]] = w->vals[j];
+    }
+    return CADNN_OK;
+}

@@ -1,0 +1,198 @@
+"""GPU parity: every layer kind through the C ABI against the CPU oracle."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+from util import TOL_F32, TOL_F16, assert_close
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def cad():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_1905_00571_amd as cad
+    cad.lib()
+    return cad
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def run_conv(cad, x, w, b, r, stride, pad, relu, dtype=None):
+    dtype = dtype if dtype is not None else cad.F32
+    npdt = np.float16 if dtype == cad.F16 else np.float32
+    xs = x.astype(npdt)
+    rs = None if r is None else r.astype(npdt)
+    h = cad.cadnn_pack_weights(w, dtype)
+    y = cad.cadnn_sparse_conv2d(h, dev(xs), stride, pad, None if b is None else dev(b),
+                                None if rs is None else dev(rs), relu)
+    torch.cuda.synchronize()
+    got = y.cpu().numpy()
+    ref = oracle.conv2d(xs, w.astype(npdt), b, rs, stride, pad, relu, npdt)
+    h.free()
+    return got, ref
+
+
+def test_config0_single_conv(cad):
+    """64->64 3x3 @56x56, 90 % sparse, stride 1, pad 1, bias, fused ReLU."""
+    x = wl.activation((1, 64, 56, 56), "c0", 0, relu=True)
+    w = wl.pruned_weights(64, 64, 3, 3, 0.9, "c0", 1)
+    b = wl.bias_vector(64, "c0", 1)
+    got, ref = run_conv(cad, x, w, b, None, 1, 1, True)
+    assert got.shape == (1, 64, 56, 56)
+    print("C0", assert_close(got, ref, TOL_F32, "config 0"))
+
+
+def test_config1_bottleneck_layers_and_chain(cad):
+    ops = wl.bottleneck_conv2x_ops(0.85)
+    shape = (1, 256, 56, 56)
+    x, ws, bs = wl.net_tensors(ops, "c1", shape, input_relu=True)
+    ref, ins, outs = oracle.run_net(ops, x, ws, bs)
+    # each layer in isolation on the oracle's own input
+    for i, op in enumerate(ops):
+        h = cad.cadnn_pack_weights(ws[i])
+        res = dev(ins[0]) if op.res == 0 else None
+        y = cad.cadnn_sparse_conv2d(h, dev(ins[i]), op.stride, op.pad, dev(bs[i]), res, op.relu)
+        torch.cuda.synchronize()
+        assert_close(y.cpu().numpy(), outs[i], TOL_F32, f"bottleneck layer {op.name}")
+        h.free()
+    # and chained through the net runner, eager and graph
+    for graph in (False, True):
+        net = cad.build_net(ops, ws, bs, shape, cad.F32, use_graph=graph)
+        xd = dev(x)
+        for _ in range(3):
+            y = net.run(xd)
+            torch.cuda.synchronize()
+            assert_close(y.cpu().numpy(), ref, TOL_F32, f"bottleneck chain graph={graph}")
+        net.free()
+
+
+GEOMS = [
+    # cin, cout, k, stride, pad, h, w, sparsity
+    (5, 7, 1, 1, 0, 9, 11, 0.5),
+    (16, 24, 1, 2, 0, 14, 14, 0.9),
+    (8, 8, 3, 1, 1, 7, 7, 0.5),
+    (8, 8, 3, 1, 0, 9, 8, 0.0),
+    (37, 19, 3, 1, 1, 30, 33, 0.9),       # ragged channels and tiles, several channel chunks
+    (40, 20, 3, 2, 1, 29, 31, 0.8),
+    (16, 16, 3, 2, 1, 14, 14, 0.99),
+    (3, 8, 7, 2, 3, 37, 41, 0.0),
+    (4, 6, 7, 1, 3, 12, 12, 0.5),
+    (3, 5, 3, 1, 3, 6, 6, 0.3),           # pad larger than the kernel radius
+    (300, 10, 1, 1, 0, 5, 5, 0.9),        # more channels than one 1x1 chunk
+    (70, 33, 1, 1, 0, 40, 40, 0.7),
+]
+
+
+@pytest.mark.parametrize("geom", GEOMS)
+def test_property_sweep(cad, geom):
+    cin, cout, k, stride, pad, h, w_, s = geom
+    tag = "sweep-%d-%d-%d-%d-%d" % (cin, cout, k, stride, pad)
+    for n in (1, 3):
+        x = wl.activation((n, cin, h, w_), tag, n, relu=False)
+        w = wl.pruned_weights(cout, cin, k, k, s, tag, 1, mask="random")
+        b = wl.bias_vector(cout, tag, 1, sigma=0.5)
+        hout, wout = oracle.out_size(h, k, stride, pad), oracle.out_size(w_, k, stride, pad)
+        r = wl.activation((n, cout, hout, wout), tag, 2, relu=False, role="r")
+        for bias, res, relu in [(None, None, False), (b, r, True), (b, None, True), (None, r, False)]:
+            got, ref = run_conv(cad, x, w, bias, res, stride, pad, relu)
+            assert_close(got, ref, TOL_F32, f"{geom} n={n} bias={bias is not None} res={res is not None}")
+
+
+def test_degenerate_rows_and_all_zero(cad):
+    x = wl.activation((2, 16, 12, 12), "degen", 0, relu=False)
+    w = wl.pruned_weights(20, 16, 3, 3, 0.9, "degen", 1, row_skew=2.0)
+    w[4] = 0
+    w[11] = np.float32(0.125)
+    b = wl.bias_vector(20, "degen", 1, sigma=1.0)
+    r = wl.activation((2, 20, 12, 12), "degen", 2, relu=False, role="r")
+    got, ref = run_conv(cad, x, w, b, r, 1, 1, True)
+    assert_close(got, ref, TOL_F32, "skewed rows")
+    # all-zero weights: exactly act(bias + residual)
+    got, ref = run_conv(cad, x, np.zeros_like(w), b, r, 1, 1, True)
+    assert np.array_equal(got, ref)
+    # identity kernel: exactly ReLU(x)
+    wi = np.zeros((16, 16, 3, 3), np.float32)
+    for c in range(16):
+        wi[c, c, 1, 1] = 1
+    got, _ = run_conv(cad, x, wi, None, None, 1, 1, True)
+    assert np.array_equal(got, np.maximum(x, 0))
+
+
+def test_nan_poison_catches_unwritten_outputs(cad):
+    x = wl.activation((1, 8, 19, 23), "poison", 0, relu=False)
+    w = wl.pruned_weights(5, 8, 3, 3, 0.5, "poison", 1)
+    h = cad.cadnn_pack_weights(w)
+    out = torch.full((1, 5, 19, 23), float("nan"), device="cuda")
+    cad.cadnn_sparse_conv2d(h, dev(x), 1, 1, None, None, False, out=out)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out).all()
+    h.free()
+
+
+@pytest.mark.parametrize("n,cin,cout,s,relu", [(1, 2048, 1000, 0.9, False), (1, 300, 70, 0.5, True),
+                                               (8, 512, 100, 0.96, True), (11, 64, 9, 0.0, False),
+                                               (1, 25088, 256, 0.96, True)])
+def test_sparse_fc(cad, n, cin, cout, s, relu):
+    tag = f"fc-{n}-{cin}-{cout}"
+    x = wl.activation((n, cin), tag, 0, relu=True)
+    w = wl.pruned_weights(cout, cin, 1, 1, s, tag, 1)
+    if cout > 5:
+        w[2] = 0
+    b = wl.bias_vector(cout, tag, 1, sigma=0.1)
+    h = cad.cadnn_pack_weights(w)
+    y = cad.cadnn_sparse_fc(h, dev(x), dev(b), relu)
+    torch.cuda.synchronize()
+    assert_close(y.cpu().numpy(), oracle.fc(x, w, b, relu), TOL_F32, tag)
+    h.free()
+
+
+def test_pools(cad):
+    x = wl.activation((2, 5, 23, 17), "pool", 0, relu=False)
+    for k, s, p in [(3, 2, 1), (2, 2, 0)]:
+        y = cad.cadnn_maxpool2d(dev(x), k, s, p)
+        assert np.array_equal(y.cpu().numpy(), oracle.maxpool(x, k, s, p))
+    y = cad.cadnn_global_avgpool(dev(x))
+    assert_close(y.cpu().numpy(), oracle.global_avgpool(x), 1e-6, "avgpool")
+    x16 = x.astype(np.float16)
+    y = cad.cadnn_maxpool2d(dev(x16), 3, 2, 1)
+    assert np.array_equal(y.cpu().numpy(), oracle.maxpool(x16, 3, 2, 1))
+
+
+def test_fp16_storage_variant(cad):
+    x = wl.activation((2, 32, 28, 28), "h", 0, relu=True)
+    w = wl.pruned_weights(48, 32, 3, 3, 0.8, "h", 1)
+    b = wl.bias_vector(48, "h", 1)
+    r = wl.activation((2, 48, 28, 28), "h", 2, relu=False, role="r")
+    got, ref = run_conv(cad, x, w, b, r, 1, 1, True, dtype=cad.F16)
+    assert got.dtype == np.float16
+    assert_close(got, ref, TOL_F16, "fp16 3x3")
+    w1 = wl.pruned_weights(40, 32, 1, 1, 0.5, "h", 3)
+    got, ref = run_conv(cad, x, w1, None, None, 2, 0, False, dtype=cad.F16)
+    assert_close(got, ref, TOL_F16, "fp16 1x1 s2")
+    # fc
+    xf = wl.activation((3, 200), "h", 4, relu=True).astype(np.float16)
+    wf = wl.pruned_weights(30, 200, 1, 1, 0.7, "h", 5)
+    h = cad.cadnn_pack_weights(wf, cad.F16)
+    y = cad.cadnn_sparse_fc(h, dev(xf), None, False)
+    torch.cuda.synchronize()
+    assert_close(y.cpu().numpy(), oracle.fc(xf, wf.astype(np.float16), None, False, np.float16), TOL_F16, "fp16 fc")
+    h.free()
+
+
+def test_runtime_error_paths(cad):
+    h = cad.cadnn_pack_weights(wl.pruned_weights(8, 4, 3, 3, 0.5, "err", 1))
+    x = dev(wl.activation((1, 4, 8, 8), "err", 0, relu=False))
+    L = cad.lib()
+    y = torch.empty((1, 8, 8, 8), device="cuda")
+    assert L.cadnn_sparse_conv2d(h.handle, x.data_ptr(), x.data_ptr(), 1, 8, 8, 1, 1, None, None, 0, None) == 1
+    assert L.cadnn_sparse_conv2d(h.handle, x.data_ptr(), None, 1, 8, 8, 1, 1, None, None, 0, None) == 1
+    assert L.cadnn_sparse_conv2d(h.handle, x.data_ptr(), y.data_ptr(), 1, 8, 8, 1, 1, None, None, 0, None) == 0
+    torch.cuda.synchronize()
+    h.free()

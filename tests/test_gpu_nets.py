@@ -1,0 +1,106 @@
+"""GPU parity for whole networks through cadnn_run_net (full-size configurations)."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+from util import TOL_F32, TOL_F16, assert_close
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def cad():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_1905_00571_amd as cad
+    cad.lib()
+    return cad
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def check_layers_in_isolation(cad, ops, ws, bs, ins, outs, tol, dtype, which=None):
+    """Each conv/fc of the net on the ORACLE's input for that layer (sensitive to a bug in
+    one branch, which an end-to-end check dominated by identity shortcuts can hide)."""
+    worst = 0.0
+    for i, op in enumerate(ops):
+        if which is not None and i not in which:
+            continue
+        if op.kind == "conv":
+            h = cad.cadnn_pack_weights(ws[i], dtype)
+            res = None
+            if op.res >= 0:
+                j = max(k for k in range(i) if ops[k].dst == op.res) if op.res != 0 else -1
+                res = dev(outs[j]) if j >= 0 else dev(ins[0])
+            y = cad.cadnn_sparse_conv2d(h, dev(ins[i]), op.stride, op.pad, dev(bs[i]), res, op.relu)
+        elif op.kind == "fc":
+            h = cad.cadnn_pack_weights(ws[i], dtype)
+            y = cad.cadnn_sparse_fc(h, dev(ins[i].reshape(ins[i].shape[0], -1)), dev(bs[i]), op.relu)
+            y = y.reshape(outs[i].shape)
+        elif op.kind == "maxpool":
+            y = cad.cadnn_maxpool2d(dev(ins[i]), op.k, op.stride, op.pad)
+            h = None
+        else:
+            y = cad.cadnn_global_avgpool(dev(ins[i]))
+            h = None
+        torch.cuda.synchronize()
+        e = assert_close(y.cpu().numpy(), outs[i], tol, f"layer {i} {op.name}")
+        worst = max(worst, e[0])
+        if h is not None:
+            h.free()
+    return worst
+
+
+def test_config2_resnet50_fp32(cad):
+    ops = wl.resnet50_ops()
+    shape = (1, 3, 224, 224)
+    x, ws, bs = wl.net_tensors(ops, "c2", shape)
+    ref, ins, outs = oracle.run_net(ops, x, ws, bs)
+    worst = check_layers_in_isolation(cad, ops, ws, bs, ins, outs, TOL_F32, cad.F32)
+    print("resnet50 per-layer worst E_inf", worst)
+    net = cad.build_net(ops, ws, bs, shape, cad.F32, use_graph=True)
+    xd = dev(x)
+    for rep in range(3):
+        y = net.run(xd)
+        torch.cuda.synchronize()
+        e = assert_close(y.cpu().numpy(), ref, TOL_F32, f"resnet50 end to end (replay {rep})")
+    print("resnet50 end-to-end", e)
+    ms = net.profile(xd, y, repeats=2)
+    assert ms.shape == (len(ops),) and (ms > 0).all()
+    net.free()
+
+
+def test_config4_vgg16_fp32(cad):
+    ops = wl.vgg16_ops()
+    shape = (1, 3, 224, 224)
+    x, ws, bs = wl.net_tensors(ops, "c4", shape)
+    ref, ins, outs = oracle.run_net(ops, x, ws, bs)
+    worst = check_layers_in_isolation(cad, ops, ws, bs, ins, outs, TOL_F32, cad.F32)
+    print("vgg16 per-layer worst E_inf", worst)
+    net = cad.build_net(ops, ws, bs, shape, cad.F32, use_graph=True)
+    y = net.run(dev(x))
+    torch.cuda.synchronize()
+    print("vgg16 end-to-end", assert_close(y.cpu().numpy(), ref, TOL_F32, "vgg16 end to end"))
+    net.free()
+
+
+@pytest.mark.parametrize("n,s", [(1, 0.8), (8, 0.5)])
+def test_config3_resnet50_fp16(cad, n, s):
+    ops = wl.resnet50_ops(uniform=s)
+    shape = (n, 3, 224, 224)
+    x, ws, bs = wl.net_tensors(ops, f"c3-{s}", shape)
+    x16 = x.astype(np.float16)
+    ref, ins, outs = oracle.run_net(ops, x16, ws, bs, dtype=np.float16)
+    convs = [i for i, o in enumerate(ops) if o.kind in ("conv", "fc")]
+    subset = set(convs[:3] + convs[-4:] + convs[20:23])
+    check_layers_in_isolation(cad, ops, ws, bs, ins, outs, TOL_F16, cad.F16, which=subset)
+    net = cad.build_net(ops, ws, bs, shape, cad.F16, use_graph=True)
+    y = net.run(dev(x16))
+    torch.cuda.synchronize()
+    print("resnet50 fp16 end-to-end", n, s, assert_close(y.cpu().numpy(), ref, 3 * TOL_F16, "fp16 chain"))
+    net.free()
