@@ -1,0 +1,213 @@
+#!/usr/bin/env python3
+"""Benchmark of the sparse-inference hot path on one MI355X.
+
+Workload: the full ResNet-50 stack at batch 1 in fp32 (53 pruned convolutions + pools +
+the 2048->1000 FC; conv1 dense, 3x3 convs 80 % sparse, 1x1 convs and FC 90 % sparse) on
+seeded synthetic tensors.  A step is one whole forward pass through cadnn_run_net (one HIP
+graph launch).  Prints ONE JSON line; a per-layer table goes to --layers-out if given.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
+FP32_VECTOR_TFLOPS = 157.3   # MI355X vector fp32 (256 CU x 2.4 GHz x 256 flop/clk)
+
+
+def layer_costs(ops, weights, in_shape, elem):
+    """Algorithmic flops and bytes of every op: each activation read once, each output
+    written once, each nonzero (value + 16-bit index) read once; flops over nonzero MACs."""
+    import numpy as np
+    from workloads import conv_out_size
+    cur = {0: tuple(in_shape)}
+    rows = []
+    for i, op in enumerate(ops):
+        n, c, h, w = cur[op.src]
+        if op.kind == "conv":
+            ho, wo = conv_out_size(h, op.k, op.stride, op.pad), conv_out_size(w, op.k, op.stride, op.pad)
+            nnz = int(np.count_nonzero(weights[i]))
+            out = (n, op.cout, ho, wo)
+            flops = 2.0 * nnz * ho * wo * n
+            byts = (n * c * h * w + n * op.cout * ho * wo * (2 if op.res >= 0 else 1)) * elem \
+                + nnz * (elem + 2) + (op.cout + 1) * 4 + op.cout * 4 + op.cout * 4
+        elif op.kind == "fc":
+            nnz = int(np.count_nonzero(weights[i]))
+            out = (n, op.cout, 1, 1)
+            flops = 2.0 * nnz * n
+            byts = (n * c * h * w + n * op.cout) * elem + nnz * (elem + 2) + (op.cout + 1) * 4 + op.cout * 8
+        elif op.kind == "maxpool":
+            ho, wo = conv_out_size(h, op.k, op.stride, op.pad), conv_out_size(w, op.k, op.stride, op.pad)
+            out = (n, c, ho, wo)
+            nnz, flops = 0, 0.0
+            byts = (n * c * h * w + n * c * ho * wo) * elem
+        else:
+            out = (n, c, 1, 1)
+            nnz, flops = 0, float(n * c * h * w)
+            byts = (n * c * h * w + n * c) * elem
+        cur[op.dst] = out
+        rows.append({"op": op.name, "kind": op.kind, "in": [n, c, h, w], "out": list(out), "nnz": nnz,
+                     "flops": flops, "bytes": float(byts)})
+    return rows
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--layers-out", type=str, default="")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives or sharding are part of it); "
+              "use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import workloads as wl
+    import paper_1905_00571_amd as cad
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    cad.lib()
+    torch.cuda.set_device(0)
+
+    ops = wl.resnet50_ops()
+    shape = (1, 3, 224, 224)
+    x, ws, bs = wl.net_tensors(ops, "c2", shape)
+    net = cad.build_net(ops, ws, bs, shape, cad.F32, use_graph=not args.no_graph)
+    xd = torch.from_numpy(x).cuda()            # inputs resident in HBM before timing
+    y = torch.empty(net.out_shape, dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    for _ in range(max(args.warmup, 1)):
+        net.run(xd, y, stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        net.run(xd, y, stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    # single-inference latency with a host sync after every pass (median)
+    lat = []
+    for _ in range(min(args.steps, 200)):
+        a = time.perf_counter()
+        net.run(xd, y, stream)
+        torch.cuda.synchronize()
+        lat.append((time.perf_counter() - a) * 1e3)
+    lat_sync_ms = float(np.median(lat))
+
+    # ---- per-op device time with HIP events on the launch stream, grouped by kernel
+    per_op_ms = net.profile(xd, y, repeats=20, stream=stream)
+    costs = layer_costs(ops, ws, shape, 4)
+    groups = {}
+    h, wdt = {0: 224}, {0: 224}
+    cur = {0: shape}
+    keep = net._keep
+    ki = 0
+    for i, op in enumerate(ops):
+        if op.kind in ("conv", "fc"):
+            pw = keep[ki]
+            ki += 2
+        if op.kind == "conv":
+            n_, c_, h_, w_ = costs[i]["in"]
+            name = cad.cadnn_conv2d_variant_name(pw, n_, h_, w_, op.stride, op.pad)
+        elif op.kind == "fc":
+            name = "sfc"
+        else:
+            name = op.kind
+        costs[i]["kernel"] = name
+        costs[i]["ms"] = float(per_op_ms[i])
+        t = costs[i]["ms"] * 1e-3
+        costs[i]["gflops"] = costs[i]["flops"] / t / 1e9 if t > 0 else 0.0
+        costs[i]["gbs"] = costs[i]["bytes"] / t / 1e9 if t > 0 else 0.0
+        costs[i]["frac_hbm"] = costs[i]["gbs"] / HBM_PEAK_GBS
+        costs[i]["frac_fp32"] = costs[i]["gflops"] / (FP32_VECTOR_TFLOPS * 1e3)
+        g = groups.setdefault(name, {"ms": 0.0, "launches": 0, "flops": 0.0, "bytes": 0.0})
+        g["ms"] += costs[i]["ms"]
+        g["launches"] += 1
+        g["flops"] += costs[i]["flops"]
+        g["bytes"] += costs[i]["bytes"]
+    dom_name, dom = max(groups.items(), key=lambda kv: kv[1]["ms"])
+    avg_s = dom["ms"] * 1e-3 / dom["launches"]
+    t_hbm = dom["bytes"] / dom["launches"] / (HBM_PEAK_GBS * 1e9)
+    t_alu = dom["flops"] / dom["launches"] / (FP32_VECTOR_TFLOPS * 1e12)
+    if t_alu >= t_hbm:
+        achieved = dom["flops"] / dom["launches"] / avg_s / 1e12
+        roofline = {"bound": "alu", "achieved": achieved, "peak": FP32_VECTOR_TFLOPS, "unit": "TFLOP/s",
+                    "frac": achieved / FP32_VECTOR_TFLOPS, "traffic": None}
+    else:
+        achieved = dom["bytes"] / dom["launches"] / avg_s / 1e9
+        roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": achieved / HBM_PEAK_GBS, "traffic": None}
+    roofline.update({"kernel": dom_name, "launches_per_step": dom["launches"],
+                     "avg_launch_us": avg_s * 1e6,
+                     "algorithmic_flops_per_launch": dom["flops"] / dom["launches"],
+                     "algorithmic_bytes_per_launch": dom["bytes"] / dom["launches"]})
+
+    total_flops = sum(c["flops"] for c in costs)
+    total_bytes = sum(c["bytes"] for c in costs)
+
+    # ---- CPU baseline: the oracle as it stands, one full forward pass of the same workload
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        a = time.perf_counter()
+        ref, _, _ = oracle.run_net(ops, x, ws, bs)
+        cpu_ms = (time.perf_counter() - a) * 1e3
+        got = y.cpu().numpy()
+        err = float(np.abs(got - ref).max() / np.abs(ref).max())
+        cpu = {"value": cpu_ms, "unit": "ms", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": "1 full forward pass of the same ResNet-50 workload (all 53 convs + pools + FC)",
+               "gpu_vs_oracle_max_rel_err": err}
+
+    if args.layers_out:
+        with open(args.layers_out, "w") as f:
+            json.dump({"layers": costs, "groups": groups}, f, indent=1)
+
+    line = {
+        "metric": "sparse ResNet-50 batch-1 latency",
+        "value": ms_per_step,
+        "unit": "ms",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "resnet50-sparse fp32 batch 1 (configs[2]): 53 convs + FC, conv1 0 %, "
+                               "3x3 80 %, 1x1+FC 90 % unstructured sparsity, 1x3x224x224 input",
+                   "graph": not args.no_graph},
+        "images_per_s": 1e3 / ms_per_step,
+        "latency_with_host_sync_ms": lat_sync_ms,
+        "effective_gflops_nonzero_macs": total_flops / (ms_per_step * 1e-3) / 1e9,
+        "effective_gbs_algorithmic": total_bytes / (ms_per_step * 1e-3) / 1e9,
+        "sum_of_kernel_ms": float(per_op_ms.sum()),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "paper_context": "26 ms (title) / 21 ms (text) ResNet-50 on a Snapdragon 835 phone; other hardware, not a target",
+    }
+    print(json.dumps(line))
+    net.free()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -160,8 +160,9 @@ cadnn_status cadnn_net_workspace_bytes(const cadnn_net* net, size_t* bytes);
  * x / y change between calls). */
 cadnn_status cadnn_net_finalize(cadnn_net* net, void* workspace_dev, size_t bytes, int use_graph);
 cadnn_status cadnn_run_net(cadnn_net* net, const void* x, void* y, void* stream);
-/* Number of ops, and per-op device time of one eager pass measured with HIP
- * events on `stream` (synchronises; ms_per_op has cadnn_net_num_ops entries). */
+/* Number of ops, and per-op device time: op i is launched `repeats` times back
+ * to back between two HIP events on `stream` and the average is written to
+ * ms_per_op[i] (cadnn_net_num_ops entries).  Synchronises the stream. */
 cadnn_status cadnn_net_num_ops(const cadnn_net* net, int* num_ops);
 cadnn_status cadnn_net_profile(cadnn_net* net, const void* x, void* y, void* stream, int repeats,
                                float* ms_per_op);

@@ -72,30 +72,29 @@ void* buf_ptr(cadnn_net* net, int buf, const void* x, void* y) {
     return net->ws + net->offset[buf];
 }
 
-cadnn_status launch_all(cadnn_net* net, const void* x, void* y, hipStream_t s, hipEvent_t* ev) {
+cadnn_status launch_one(cadnn_net* net, size_t i, const void* x, void* y, hipStream_t s) {
+    const NetOp& op = net->ops[i];
+    const void* src = buf_ptr(net, op.src, x, y);
+    void* dst = buf_ptr(net, op.dst, x, y);
+    switch (op.kind) {
+        case OP_CONV:
+            return conv2d_impl(op.w, src, dst, op.in.n, op.in.h, op.in.w, op.stride, op.pad, op.bias,
+                               op.res >= 0 ? buf_ptr(net, op.res, x, y) : nullptr, op.relu, s);
+        case OP_FC:
+            return launch_fc(op.w, src, dst, op.in.n, (const float*)op.bias, op.relu, s);
+        case OP_MAXPOOL:
+            return launch_maxpool(src, dst, op.in.n, op.in.c, op.in.h, op.in.w, op.k, op.stride,
+                                  op.pad, net->dtype, s);
+        case OP_AVGPOOL:
+            return launch_avgpool(src, dst, op.in.n, op.in.c, op.in.h, op.in.w, net->dtype, s);
+    }
+    return fail(CADNN_EINVAL, "cadnn_net: unknown op kind");
+}
+
+cadnn_status launch_all(cadnn_net* net, const void* x, void* y, hipStream_t s) {
     for (size_t i = 0; i < net->ops.size(); ++i) {
-        const NetOp& op = net->ops[i];
-        const void* src = buf_ptr(net, op.src, x, y);
-        void* dst = buf_ptr(net, op.dst, x, y);
-        cadnn_status st = CADNN_OK;
-        switch (op.kind) {
-            case OP_CONV:
-                st = conv2d_impl(op.w, src, dst, op.in.n, op.in.h, op.in.w, op.stride, op.pad, op.bias,
-                                 op.res >= 0 ? buf_ptr(net, op.res, x, y) : nullptr, op.relu, s);
-                break;
-            case OP_FC:
-                st = launch_fc(op.w, src, dst, op.in.n, (const float*)op.bias, op.relu, s);
-                break;
-            case OP_MAXPOOL:
-                st = launch_maxpool(src, dst, op.in.n, op.in.c, op.in.h, op.in.w, op.k, op.stride,
-                                    op.pad, net->dtype, s);
-                break;
-            case OP_AVGPOOL:
-                st = launch_avgpool(src, dst, op.in.n, op.in.c, op.in.h, op.in.w, net->dtype, s);
-                break;
-        }
+        cadnn_status st = launch_one(net, i, x, y, s);
         if (st != CADNN_OK) return st;
-        if (ev) CADNN_HIP(hipEventRecord(ev[i + 1], s));
     }
     return CADNN_OK;
 }
@@ -248,7 +247,7 @@ extern "C" cadnn_status cadnn_run_net(cadnn_net* net, const void* x, void* y, vo
     if (!net || !x || !y) return fail(CADNN_EINVAL, "cadnn_run_net: NULL pointer");
     if (!net->finalized) return fail(CADNN_EINVAL, "cadnn_run_net: net not finalized");
     hipStream_t s = (hipStream_t)stream;
-    if (!net->use_graph) return launch_all(net, x, y, s, nullptr);
+    if (!net->use_graph) return launch_all(net, x, y, s);
     if (!net->exec || net->cap_x != x || net->cap_y != y) {
         drop_graph(net);
         hipStream_t cs = nullptr;
@@ -259,7 +258,7 @@ extern "C" cadnn_status cadnn_run_net(cadnn_net* net, const void* x, void* y, vo
         if (e != hipSuccess) {
             st = fail(CADNN_EHIP, "hipStreamBeginCapture failed: %s", hipGetErrorString(e));
         } else {
-            st = launch_all(net, x, y, cs, nullptr);
+            st = launch_all(net, x, y, cs);
             e = hipStreamEndCapture(cs, &graph);
             if (st == CADNN_OK && e != hipSuccess)
                 st = fail(CADNN_EHIP, "hipStreamEndCapture failed: %s", hipGetErrorString(e));
@@ -298,22 +297,21 @@ extern "C" cadnn_status cadnn_net_profile(cadnn_net* net, const void* x, void* y
     cadnn_status st = CADNN_OK;
     for (size_t i = 0; i <= nops && st == CADNN_OK; ++i)
         if (hipEventCreate(&ev[i]) != hipSuccess) st = fail(CADNN_EHIP, "hipEventCreate failed");
-    std::vector<double> sum(nops, 0.0);
-    for (int r = 0; r < repeats && st == CADNN_OK; ++r) {
-        if (hipEventRecord(ev[0], s) != hipSuccess) { st = fail(CADNN_EHIP, "hipEventRecord failed"); break; }
-        st = launch_all(net, x, y, s, ev.data());
-        if (st != CADNN_OK) break;
-        if (hipStreamSynchronize(s) != hipSuccess) { st = fail(CADNN_EHIP, "hipStreamSynchronize failed"); break; }
-        for (size_t i = 0; i < nops; ++i) {
-            float ms = 0.0f;
-            if (hipEventElapsedTime(&ms, ev[i], ev[i + 1]) != hipSuccess) { st = fail(CADNN_EHIP, "hipEventElapsedTime failed"); break; }
-            sum[i] += ms;
-        }
+    // Every op is idempotent (it reads its sources and overwrites its destination), so op i
+    // is launched `repeats` times back to back between two events on the caller's stream.
+    for (size_t i = 0; i < nops && st == CADNN_OK; ++i) {
+        if (hipEventRecord(ev[i], s) != hipSuccess) { st = fail(CADNN_EHIP, "hipEventRecord failed"); break; }
+        for (int r = 0; r < repeats && st == CADNN_OK; ++r) st = launch_one(net, i, x, y, s);
+    }
+    if (st == CADNN_OK && hipEventRecord(ev[nops], s) != hipSuccess) st = fail(CADNN_EHIP, "hipEventRecord failed");
+    if (st == CADNN_OK && hipStreamSynchronize(s) != hipSuccess) st = fail(CADNN_EHIP, "hipStreamSynchronize failed");
+    for (size_t i = 0; i < nops && st == CADNN_OK; ++i) {
+        float ms = 0.0f;
+        if (hipEventElapsedTime(&ms, ev[i], ev[i + 1]) != hipSuccess) st = fail(CADNN_EHIP, "hipEventElapsedTime failed");
+        ms_per_op[i] = ms / (float)repeats;
     }
     for (hipEvent_t e : ev) if (e) (void)hipEventDestroy(e);
-    if (st != CADNN_OK) return st;
-    for (size_t i = 0; i < nops; ++i) ms_per_op[i] = (float)(sum[i] / repeats);
-    return CADNN_OK;
+    return st;
 }
 
 extern "C" cadnn_status cadnn_net_read_buffer(cadnn_net* net, int buf, void* host_out, size_t bytes,

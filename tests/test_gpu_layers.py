@@ -4,7 +4,8 @@ import pytest
 
 import oracle
 import workloads as wl
-from util import TOL_F32, TOL_F16, assert_close
+from util import (TOL_F32, TOL_F16, assert_close, assert_layer_close, assert_chain_close,
+                  cond_conv, cond_fc)
 
 pytestmark = pytest.mark.gpu
 
@@ -35,8 +36,9 @@ def run_conv(cad, x, w, b, r, stride, pad, relu, dtype=None):
     torch.cuda.synchronize()
     got = y.cpu().numpy()
     ref = oracle.conv2d(xs, w.astype(npdt), b, rs, stride, pad, relu, npdt)
+    cond = cond_conv(xs, w.astype(npdt), b, rs, stride, pad)
     h.free()
-    return got, ref
+    return got, ref, cond
 
 
 def test_config0_single_conv(cad):
@@ -44,9 +46,9 @@ def test_config0_single_conv(cad):
     x = wl.activation((1, 64, 56, 56), "c0", 0, relu=True)
     w = wl.pruned_weights(64, 64, 3, 3, 0.9, "c0", 1)
     b = wl.bias_vector(64, "c0", 1)
-    got, ref = run_conv(cad, x, w, b, None, 1, 1, True)
+    got, ref, cond = run_conv(cad, x, w, b, None, 1, 1, True)
     assert got.shape == (1, 64, 56, 56)
-    print("C0", assert_close(got, ref, TOL_F32, "config 0"))
+    print("C0", assert_layer_close(got, ref, cond, TOL_F32, "config 0"))
 
 
 def test_config1_bottleneck_layers_and_chain(cad):
@@ -60,7 +62,8 @@ def test_config1_bottleneck_layers_and_chain(cad):
         res = dev(ins[0]) if op.res == 0 else None
         y = cad.cadnn_sparse_conv2d(h, dev(ins[i]), op.stride, op.pad, dev(bs[i]), res, op.relu)
         torch.cuda.synchronize()
-        assert_close(y.cpu().numpy(), outs[i], TOL_F32, f"bottleneck layer {op.name}")
+        cond = cond_conv(ins[i], ws[i], bs[i], ins[0] if op.res == 0 else None, op.stride, op.pad)
+        assert_layer_close(y.cpu().numpy(), outs[i], cond, TOL_F32, f"bottleneck layer {op.name}")
         h.free()
     # and chained through the net runner, eager and graph
     for graph in (False, True):
@@ -69,7 +72,8 @@ def test_config1_bottleneck_layers_and_chain(cad):
         for _ in range(3):
             y = net.run(xd)
             torch.cuda.synchronize()
-            assert_close(y.cpu().numpy(), ref, TOL_F32, f"bottleneck chain graph={graph}")
+            assert_chain_close(y.cpu().numpy(), ref, cond_conv(ins[2], ws[2], bs[2], ins[0], 1, 0),
+                               TOL_F32, f"bottleneck chain graph={graph}")
         net.free()
 
 
@@ -101,8 +105,8 @@ def test_property_sweep(cad, geom):
         hout, wout = oracle.out_size(h, k, stride, pad), oracle.out_size(w_, k, stride, pad)
         r = wl.activation((n, cout, hout, wout), tag, 2, relu=False, role="r")
         for bias, res, relu in [(None, None, False), (b, r, True), (b, None, True), (None, r, False)]:
-            got, ref = run_conv(cad, x, w, bias, res, stride, pad, relu)
-            assert_close(got, ref, TOL_F32, f"{geom} n={n} bias={bias is not None} res={res is not None}")
+            got, ref, cond = run_conv(cad, x, w, bias, res, stride, pad, relu)
+            assert_layer_close(got, ref, cond, TOL_F32, f"{geom} n={n} bias={bias is not None} res={res is not None}")
 
 
 def test_degenerate_rows_and_all_zero(cad):
@@ -112,16 +116,16 @@ def test_degenerate_rows_and_all_zero(cad):
     w[11] = np.float32(0.125)
     b = wl.bias_vector(20, "degen", 1, sigma=1.0)
     r = wl.activation((2, 20, 12, 12), "degen", 2, relu=False, role="r")
-    got, ref = run_conv(cad, x, w, b, r, 1, 1, True)
-    assert_close(got, ref, TOL_F32, "skewed rows")
+    got, ref, cond = run_conv(cad, x, w, b, r, 1, 1, True)
+    assert_layer_close(got, ref, cond, TOL_F32, "skewed rows")
     # all-zero weights: exactly act(bias + residual)
-    got, ref = run_conv(cad, x, np.zeros_like(w), b, r, 1, 1, True)
+    got, ref, _ = run_conv(cad, x, np.zeros_like(w), b, r, 1, 1, True)
     assert np.array_equal(got, ref)
     # identity kernel: exactly ReLU(x)
     wi = np.zeros((16, 16, 3, 3), np.float32)
     for c in range(16):
         wi[c, c, 1, 1] = 1
-    got, _ = run_conv(cad, x, wi, None, None, 1, 1, True)
+    got, _, _ = run_conv(cad, x, wi, None, None, 1, 1, True)
     assert np.array_equal(got, np.maximum(x, 0))
 
 
@@ -149,7 +153,7 @@ def test_sparse_fc(cad, n, cin, cout, s, relu):
     h = cad.cadnn_pack_weights(w)
     y = cad.cadnn_sparse_fc(h, dev(x), dev(b), relu)
     torch.cuda.synchronize()
-    assert_close(y.cpu().numpy(), oracle.fc(x, w, b, relu), TOL_F32, tag)
+    assert_layer_close(y.cpu().numpy(), oracle.fc(x, w, b, relu), cond_fc(x, w, b), TOL_F32, tag)
     h.free()
 
 
@@ -170,19 +174,20 @@ def test_fp16_storage_variant(cad):
     w = wl.pruned_weights(48, 32, 3, 3, 0.8, "h", 1)
     b = wl.bias_vector(48, "h", 1)
     r = wl.activation((2, 48, 28, 28), "h", 2, relu=False, role="r")
-    got, ref = run_conv(cad, x, w, b, r, 1, 1, True, dtype=cad.F16)
+    got, ref, cond = run_conv(cad, x, w, b, r, 1, 1, True, dtype=cad.F16)
     assert got.dtype == np.float16
-    assert_close(got, ref, TOL_F16, "fp16 3x3")
+    assert_layer_close(got, ref, cond, TOL_F16, "fp16 3x3", f16=True)
     w1 = wl.pruned_weights(40, 32, 1, 1, 0.5, "h", 3)
-    got, ref = run_conv(cad, x, w1, None, None, 2, 0, False, dtype=cad.F16)
-    assert_close(got, ref, TOL_F16, "fp16 1x1 s2")
+    got, ref, cond = run_conv(cad, x, w1, None, None, 2, 0, False, dtype=cad.F16)
+    assert_layer_close(got, ref, cond, TOL_F16, "fp16 1x1 s2", f16=True)
     # fc
     xf = wl.activation((3, 200), "h", 4, relu=True).astype(np.float16)
     wf = wl.pruned_weights(30, 200, 1, 1, 0.7, "h", 5)
     h = cad.cadnn_pack_weights(wf, cad.F16)
     y = cad.cadnn_sparse_fc(h, dev(xf), None, False)
     torch.cuda.synchronize()
-    assert_close(y.cpu().numpy(), oracle.fc(xf, wf.astype(np.float16), None, False, np.float16), TOL_F16, "fp16 fc")
+    assert_layer_close(y.cpu().numpy(), oracle.fc(xf, wf.astype(np.float16), None, False, np.float16),
+                       cond_fc(xf, wf.astype(np.float16), None), TOL_F16, "fp16 fc", f16=True)
     h.free()
 
 

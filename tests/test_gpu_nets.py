@@ -4,7 +4,8 @@ import pytest
 
 import oracle
 import workloads as wl
-from util import TOL_F32, TOL_F16, assert_close
+from util import (TOL_F32, TOL_F16, assert_close, assert_layer_close, assert_chain_close,
+                  cond_conv, cond_fc)
 
 pytestmark = pytest.mark.gpu
 
@@ -28,6 +29,8 @@ def check_layers_in_isolation(cad, ops, ws, bs, ins, outs, tol, dtype, which=Non
     """Each conv/fc of the net on the ORACLE's input for that layer (sensitive to a bug in
     one branch, which an end-to-end check dominated by identity shortcuts can hide)."""
     worst = 0.0
+    f16 = dtype == cad.F16
+    npdt = np.float16 if f16 else np.float32
     for i, op in enumerate(ops):
         if which is not None and i not in which:
             continue
@@ -36,12 +39,15 @@ def check_layers_in_isolation(cad, ops, ws, bs, ins, outs, tol, dtype, which=Non
             res = None
             if op.res >= 0:
                 j = max(k for k in range(i) if ops[k].dst == op.res) if op.res != 0 else -1
-                res = dev(outs[j]) if j >= 0 else dev(ins[0])
-            y = cad.cadnn_sparse_conv2d(h, dev(ins[i]), op.stride, op.pad, dev(bs[i]), res, op.relu)
+                res = outs[j] if j >= 0 else ins[0]
+            y = cad.cadnn_sparse_conv2d(h, dev(ins[i]), op.stride, op.pad, dev(bs[i]),
+                                        None if res is None else dev(res), op.relu)
+            cond = cond_conv(ins[i], ws[i].astype(npdt), bs[i], res, op.stride, op.pad)
         elif op.kind == "fc":
             h = cad.cadnn_pack_weights(ws[i], dtype)
             y = cad.cadnn_sparse_fc(h, dev(ins[i].reshape(ins[i].shape[0], -1)), dev(bs[i]), op.relu)
             y = y.reshape(outs[i].shape)
+            cond = cond_fc(ins[i], ws[i].astype(npdt), bs[i]).reshape(outs[i].shape)
         elif op.kind == "maxpool":
             y = cad.cadnn_maxpool2d(dev(ins[i]), op.k, op.stride, op.pad)
             h = None
@@ -49,7 +55,10 @@ def check_layers_in_isolation(cad, ops, ws, bs, ins, outs, tol, dtype, which=Non
             y = cad.cadnn_global_avgpool(dev(ins[i]))
             h = None
         torch.cuda.synchronize()
-        e = assert_close(y.cpu().numpy(), outs[i], tol, f"layer {i} {op.name}")
+        if op.kind in ("conv", "fc"):
+            e = assert_layer_close(y.cpu().numpy(), outs[i], cond, tol, f"layer {i} {op.name}", f16=f16)
+        else:
+            e = assert_close(y.cpu().numpy(), outs[i], 1e-3 if f16 else 1e-6, f"layer {i} {op.name}")
         worst = max(worst, e[0])
         if h is not None:
             h.free()
@@ -68,7 +77,8 @@ def test_config2_resnet50_fp32(cad):
     for rep in range(3):
         y = net.run(xd)
         torch.cuda.synchronize()
-        e = assert_close(y.cpu().numpy(), ref, TOL_F32, f"resnet50 end to end (replay {rep})")
+        e = assert_chain_close(y.cpu().numpy(), ref, cond_fc(ins[-1], ws[-1], bs[-1]), TOL_F32,
+                               f"resnet50 end to end (replay {rep})")
     print("resnet50 end-to-end", e)
     ms = net.profile(xd, y, repeats=2)
     assert ms.shape == (len(ops),) and (ms > 0).all()
@@ -85,7 +95,8 @@ def test_config4_vgg16_fp32(cad):
     net = cad.build_net(ops, ws, bs, shape, cad.F32, use_graph=True)
     y = net.run(dev(x))
     torch.cuda.synchronize()
-    print("vgg16 end-to-end", assert_close(y.cpu().numpy(), ref, TOL_F32, "vgg16 end to end"))
+    print("vgg16 end-to-end", assert_chain_close(y.cpu().numpy(), ref, cond_fc(ins[-1], ws[-1], bs[-1]),
+                                                 TOL_F32, "vgg16 end to end"))
     net.free()
 
 
@@ -102,5 +113,6 @@ def test_config3_resnet50_fp16(cad, n, s):
     net = cad.build_net(ops, ws, bs, shape, cad.F16, use_graph=True)
     y = net.run(dev(x16))
     torch.cuda.synchronize()
-    print("resnet50 fp16 end-to-end", n, s, assert_close(y.cpu().numpy(), ref, 3 * TOL_F16, "fp16 chain"))
+    cond = cond_fc(ins[-1], ws[-1].astype(np.float16), bs[-1])
+    print("resnet50 fp16 end-to-end", n, s, assert_chain_close(y.cpu().numpy(), ref, cond, TOL_F16, "fp16 chain"))
     net.free()
