@@ -110,6 +110,23 @@ cadnn_status cadnn_sparse_conv2d(const cadnn_weights* w, const void* x, void* y,
 cadnn_status cadnn_conv2d_prepare(const cadnn_weights* w, int n, int h, int wdt, int stride,
                                   int pad);
 
+/* Kernel-variant selection (Section 4, "Optimization parameters selection": tile sizes
+ * and work splits are chosen per layer).  cadnn_conv2d_tune times every kernel variant
+ * that can serve this layer on the given tensors (`reps` launches each, events on
+ * `stream`, synchronises, overwrites y) and pins the fastest for this (n, h, wdt,
+ * stride, pad); best_us (may be NULL) receives its time per launch in microseconds.
+ * cadnn_conv2d_list_variants writes the newline-separated names of the variants that
+ * can serve the layer; cadnn_conv2d_set_variant pins one by name (NULL or "" removes
+ * the pin, returning to the built-in heuristic). */
+cadnn_status cadnn_conv2d_tune(const cadnn_weights* w, const void* x, void* y, int n, int h,
+                               int wdt, int stride, int pad, const void* bias,
+                               const void* residual, int relu, void* stream, int reps,
+                               float* best_us);
+cadnn_status cadnn_conv2d_list_variants(const cadnn_weights* w, int n, int h, int wdt, int stride,
+                                        int pad, char* buf, size_t len);
+cadnn_status cadnn_conv2d_set_variant(const cadnn_weights* w, int n, int h, int wdt, int stride,
+                                      int pad, const char* name);
+
 /* Sparse fully connected layer: y[n][o] = act( sum_i W[o][i]*x[n][i] + bias[o] ).
  * w must have kh = kw = 1; x: device [n][cin]; y: device [n][cout]. */
 cadnn_status cadnn_sparse_fc(const cadnn_weights* w, const void* x, void* y, int n,
@@ -156,9 +173,13 @@ cadnn_status cadnn_net_add_global_avgpool(cadnn_net* net, int src_buf, int dst_b
 cadnn_status cadnn_net_add_fc(cadnn_net* net, const cadnn_weights* w, const void* bias_dev,
                               int relu, int src_buf, int dst_buf);
 cadnn_status cadnn_net_workspace_bytes(const cadnn_net* net, size_t* bytes);
-/* use_graph != 0: cadnn_run_net replays a captured HIP graph (re-captured when
- * x / y change between calls). */
-cadnn_status cadnn_net_finalize(cadnn_net* net, void* workspace_dev, size_t bytes, int use_graph);
+/* flags: CADNN_NET_GRAPH -- cadnn_run_net replays a captured HIP graph (re-captured
+ * when x / y change between calls); CADNN_NET_TUNE -- the first cadnn_run_net call
+ * first runs cadnn_conv2d_tune on every convolution with the net's own buffers
+ * (that first call synchronises and takes a fraction of a second). */
+#define CADNN_NET_GRAPH 1
+#define CADNN_NET_TUNE 2
+cadnn_status cadnn_net_finalize(cadnn_net* net, void* workspace_dev, size_t bytes, int flags);
 cadnn_status cadnn_run_net(cadnn_net* net, const void* x, void* y, void* stream);
 /* Number of ops, and per-op device time: op i is launched `repeats` times back
  * to back between two HIP events on `stream` and the average is written to

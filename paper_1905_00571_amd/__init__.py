@@ -21,6 +21,9 @@ from .binding import (  # noqa: F401
     cadnn_sparse_conv2d,
     cadnn_conv2d_prepare,
     cadnn_conv2d_variant_name,
+    cadnn_conv2d_list_variants,
+    cadnn_conv2d_set_variant,
+    cadnn_conv2d_tune,
     cadnn_sparse_fc,
     cadnn_fc_prepare,
     cadnn_maxpool2d,

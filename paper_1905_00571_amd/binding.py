@@ -57,6 +57,9 @@ def lib() -> ctypes.CDLL:
         "cadnn_sparse_conv2d": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _vp, _vp, _i, _vp]),
         "cadnn_conv2d_prepare": (_i, [_vp, _i, _i, _i, _i, _i]),
         "cadnn_conv2d_variant_name": (_i, [_vp, _i, _i, _i, _i, _i, ctypes.c_char_p, ctypes.c_size_t]),
+        "cadnn_conv2d_tune": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _vp, _vp, _i, _vp, _i, _f32p]),
+        "cadnn_conv2d_list_variants": (_i, [_vp, _i, _i, _i, _i, _i, ctypes.c_char_p, ctypes.c_size_t]),
+        "cadnn_conv2d_set_variant": (_i, [_vp, _i, _i, _i, _i, _i, ctypes.c_char_p]),
         "cadnn_sparse_fc": (_i, [_vp, _vp, _vp, _i, _vp, _i, _vp]),
         "cadnn_fc_prepare": (_i, [_vp]),
         "cadnn_maxpool2d": (_i, [_vp, _vp, _i, _i, _i, _i, _i, _i, _i, _i, _vp]),
@@ -170,6 +173,30 @@ def cadnn_conv2d_variant_name(w: Weights, n: int, h: int, wdt: int, stride: int,
     buf = ctypes.create_string_buffer(256)
     _check(lib().cadnn_conv2d_variant_name(w.handle, n, h, wdt, stride, pad, buf, 256))
     return buf.value.decode()
+
+
+def cadnn_conv2d_list_variants(w: Weights, n: int, h: int, wdt: int, stride: int, pad: int) -> List[str]:
+    buf = ctypes.create_string_buffer(1 << 16)
+    _check(lib().cadnn_conv2d_list_variants(w.handle, n, h, wdt, stride, pad, buf, 1 << 16))
+    text = buf.value.decode()
+    return text.split("\n") if text else []
+
+
+def cadnn_conv2d_set_variant(w: Weights, n: int, h: int, wdt: int, stride: int, pad: int,
+                             name: Optional[str]) -> None:
+    _check(lib().cadnn_conv2d_set_variant(w.handle, n, h, wdt, stride, pad,
+                                          None if not name else name.encode()))
+
+
+def cadnn_conv2d_tune(w: Weights, x, y, stride: int = 1, pad: int = 0, bias=None, residual=None,
+                      relu: bool = False, reps: int = 20, stream=None) -> float:
+    """Times every variant on (x, y) and pins the fastest; returns its microseconds per launch."""
+    n, _, h, wdt = x.shape
+    us = ctypes.c_float()
+    _check(lib().cadnn_conv2d_tune(w.handle, _dptr(x), _dptr(y), n, h, wdt, stride, pad, _dptr(bias),
+                                   _dptr(residual), int(bool(relu)), _stream_ptr(stream), reps,
+                                   ctypes.byref(us)))
+    return float(us.value)
 
 
 def _out_size(size: int, k: int, stride: int, pad: int) -> int:
@@ -309,7 +336,7 @@ def cadnn_run_net(net: Net, x, y=None, stream=None):
 
 
 def build_net(ops: Sequence, weights: Sequence, biases: Sequence, input_shape, dtype: int = F32,
-              use_graph: bool = True, device: str = "cuda:0") -> Net:
+              use_graph: bool = True, tune: bool = False, device: str = "cuda:0") -> Net:
     """Packs every layer's weights and wires the op list into a cadnn_net.
 
     `ops` are records with .kind in {"conv", "fc", "maxpool", "avgpool"} and
@@ -354,7 +381,8 @@ def build_net(ops: Sequence, weights: Sequence, biases: Sequence, input_shape, d
         _check(L.cadnn_net_workspace_bytes(handle, ctypes.byref(nbytes)))
         ws = torch.empty(max(int(nbytes.value), 256), dtype=torch.uint8, device=device)
         keep.append(ws)
-        _check(L.cadnn_net_finalize(handle, _dptr(ws), int(nbytes.value), int(bool(use_graph))))
+        _check(L.cadnn_net_finalize(handle, _dptr(ws), int(nbytes.value),
+                                    (1 if use_graph else 0) | (2 if tune else 0)))
     except Exception:
         L.cadnn_net_free(handle)
         raise

@@ -168,6 +168,8 @@ template <class Cfg>
 static TileVariant make_variant(const char* name) {
     TileVariant v{};
     v.name = name;
+    v.family = FAM_TILE;
+    v.ks = 1;
     v.kh = Cfg::KH; v.kw = Cfg::KW; v.stride = Cfg::S;
     v.tw = Cfg::TW; v.rw = Cfg::RW; v.p = Cfg::P;
     v.nw = Cfg::NW; v.rpw = Cfg::RPW; v.cch = Cfg::CCH;
@@ -209,23 +211,6 @@ static TileVariant make_variant(const char* name) {
 const std::vector<TileVariant>& all_tile_variants() {
     static const std::vector<TileVariant> v = {CADNN_SHAPES(float), CADNN_SHAPES(_Float16)};
     return v;
-}
-
-const TileVariant* select_tile_variant(int kh, int kw, int stride, int hout, int wout, int cout,
-                                       cadnn_dtype dtype) {
-    (void)hout; (void)cout;
-    const int want = wout >= 24 ? 32 : (wout >= 12 ? 16 : 8);
-    const TileVariant* best = nullptr;
-    for (const TileVariant& v : all_tile_variants()) {
-        if (v.kh != kh || v.kw != kw || v.stride != stride) continue;
-        if (v.is_f16 != (dtype == CADNN_F16)) continue;
-        if (!best) best = &v;
-        // closest tile width to the wanted one, preferring the first listed on ties
-        const int d = v.tw > want ? v.tw - want : want - v.tw;
-        const int bd = best->tw > want ? best->tw - want : want - best->tw;
-        if (d < bd) best = &v;
-    }
-    return best;
 }
 
 }  // namespace cadnn

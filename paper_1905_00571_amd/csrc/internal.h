@@ -3,6 +3,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <array>
 #include <cstdarg>
 #include <cstdint>
 #include <cstdio>
@@ -50,52 +51,71 @@ struct DevBuf {
     cadnn_status upload(const void* host, size_t n);
 };
 
-// ---- tile-kernel variants ----------------------------------------------------
-// A variant is one instantiation of the LDS-tiled sparse convolution kernel.  Its
-// compile-time geometry decides how a canonical column index k = (ci*KH + r)*KW + c is
-// translated into a byte offset inside the staged activation tile, so every variant
-// needs its own device copy of the nonzero stream (a "plan").
-struct TileVariant {
+// ---- convolution kernel variants ------------------------------------------------
+// A variant is one instantiation of a sparse convolution kernel.  Its compile-time
+// geometry decides how a canonical column index k = (ci*KH + r)*KW + c is laid out in the
+// device copy of the nonzero stream (a "plan"), so every variant owns its plan.
+//
+//  FAM_TILE   : activations staged per channel chunk in an LDS tile with halo; lanes are
+//               the pixels of a TW x TH tile; entries are (value, byte offset in the tile).
+//  FAM_DIRECT : no staging; lanes are flattened output pixels and read activations from
+//               global memory through a buffer resource (out-of-image taps are turned
+//               into out-of-range buffer offsets, which read as zero); a row's entries
+//               are regrouped tap-major so the per-lane tap offset is a fixed register;
+//               entries are (value, input channel).
+enum ConvFamily { FAM_TILE = 0, FAM_DIRECT = 1 };
+
+struct ConvLaunch;
+
+struct ConvVariant {
     const char* name;
-    int kh, kw, stride;   // filter geometry served
-    int tw, rw, p;        // lanes along ow, lane rows per wave, pixels per lane (stacked in oh)
+    int family;
+    bool is_f16;          // activation storage type served (false = fp32, true = fp16)
+    int kh, kw;           // filter geometry served
+    int stride;           // stride served (0 = any)
+    int p;                // output pixels per lane
     int nw, rpw;          // waves per workgroup, packed rows per wave
+    int ks;               // waves that split one row's input channels (partial sums reduced in LDS)
+    // FAM_TILE only
+    int tw, rw;           // lanes along ow, lane rows per wave
     int cch;              // input channels staged per chunk
     int th;               // = rw * p   output rows per tile
     int rh, nrph;         // LDS rows per row phase, number of row phases
     int cw, nph;          // LDS columns per column phase, number of column phases
     int pitch, plane;     // LDS floats per tile row / per channel
+    int elem_bytes;       // size of one staged tile element in LDS
     int unroll;           // nonzeros per scalar fetch; segments are padded to a multiple of it
     size_t lds_bytes;
-    int elem_bytes;       // size of one staged tile element in LDS
-    bool is_f16;          // activation storage type served (false = fp32, true = fp16)
-    // launcher
-    hipError_t (*launch)(const struct ConvLaunch&, hipStream_t);
+    hipError_t (*launch)(const ConvLaunch&, hipStream_t);
+    int rows_per_block() const { return family == FAM_TILE ? nw * rpw : (nw / ks) * rpw; }
 };
+typedef ConvVariant TileVariant;
 
 struct ConvLaunch {
     const void* x;
     void* y;
     const float* bias;
     const void* residual;
-    const uint2* nz;          // (value bits, byte offset) pairs, segment-padded
-    const int32_t* seg_ptr;   // [rows_padded][nchunks + 1] indices into nz
+    const uint2* nz;          // plan entries, segment-padded
+    const int32_t* seg_ptr;   // plan segment table
     const int32_t* perm;      // [rows_padded] original channel, -1 for padding rows
-    int n, cin, h, w, cout, hout, wout, pad, relu, nchunks;
+    int n, cin, h, w, cout, hout, wout, stride, pad, relu, nchunks;
     int tiles_x, tiles_y, row_groups;
+    int hwout;                // hout * wout
+    uint32_t chan_stride_bytes;   // h * w * sizeof(element)
+    uint32_t image_bytes;         // cin * h * w * sizeof(element)
 };
 
 struct ConvPlan {
-    const TileVariant* variant = nullptr;
+    const ConvVariant* variant = nullptr;
     DevBuf nz, seg_ptr, perm;
     int nchunks = 0;
     int rows_padded = 0;
     int64_t nz_padded = 0;
 };
 
-const TileVariant* select_tile_variant(int kh, int kw, int stride, int hout, int wout, int cout,
-                                       cadnn_dtype dtype);
-const std::vector<TileVariant>& all_tile_variants();
+const std::vector<ConvVariant>& all_tile_variants();
+const std::vector<ConvVariant>& all_direct_variants();
 
 }  // namespace cadnn
 
@@ -113,11 +133,14 @@ struct cadnn_weights {
     mutable bool fc_ready = false;
     // per-variant conv plans, built lazily
     mutable std::mutex mu;
-    mutable std::map<const cadnn::TileVariant*, std::unique_ptr<cadnn::ConvPlan>> plans;
+    mutable std::map<const cadnn::ConvVariant*, std::unique_ptr<cadnn::ConvPlan>> plans;
+    // variant pinned for a geometry (n, h, w, stride, pad) by tuning or by the caller
+    mutable std::map<std::array<int, 5>, const cadnn::ConvVariant*> chosen;
 };
 
 namespace cadnn {
-cadnn_status get_conv_plan(const cadnn_weights* w, const TileVariant* v, const ConvPlan** out);
+cadnn_status get_conv_plan(const cadnn_weights* w, const ConvVariant* v, const ConvPlan** out);
+void drop_plans_except(const cadnn_weights* w, const ConvVariant* keep);
 cadnn_status ensure_fc_device(const cadnn_weights* w);
 uint16_t f32_to_f16_rne(float f);
 float f16_to_f32(uint16_t h);
@@ -134,6 +157,9 @@ namespace cadnn {
 cadnn_status conv2d_impl(const cadnn_weights* w, const void* x, void* y, int n, int h, int wdt,
                          int stride, int pad, const void* bias, const void* residual, int relu,
                          hipStream_t s);
+cadnn_status conv2d_tune_impl(const cadnn_weights* w, const void* x, void* y, int n, int h, int wdt,
+                              int stride, int pad, const void* bias, const void* residual, int relu,
+                              hipStream_t s, int reps, float* best_us);
 cadnn_status dense_conv2d_impl(const void* w_dev, const void* x, void* y, int n, int cin, int h,
                                int wdt, int cout, int kh, int kw, int stride, int pad,
                                const void* bias, const void* residual, int relu, cadnn_dtype dtype,

@@ -40,6 +40,7 @@ struct cadnn_net {
     size_t ws_bytes = 0;
     bool finalized = false;
     bool use_graph = false;
+    bool want_tune = false;
     char* ws = nullptr;
     // captured graph
     hipGraphExec_t exec = nullptr;
@@ -225,7 +226,7 @@ extern "C" cadnn_status cadnn_net_workspace_bytes(const cadnn_net* net, size_t* 
     return CADNN_OK;
 }
 
-extern "C" cadnn_status cadnn_net_finalize(cadnn_net* net, void* ws, size_t bytes, int use_graph) {
+extern "C" cadnn_status cadnn_net_finalize(cadnn_net* net, void* ws, size_t bytes, int flags) {
     if (!net) return fail(CADNN_EINVAL, "cadnn_net_finalize: NULL net");
     if (net->ops.empty()) return fail(CADNN_EINVAL, "cadnn_net_finalize: empty net");
     // the output buffer is the caller's y: it must not also be read after a later write
@@ -238,7 +239,8 @@ extern "C" cadnn_status cadnn_net_finalize(cadnn_net* net, void* ws, size_t byte
     if (bytes < net->ws_bytes) return fail(CADNN_EINVAL, "cadnn_net_finalize: workspace of %zu bytes, %zu needed", bytes, net->ws_bytes);
     drop_graph(net);
     net->ws = (char*)ws;
-    net->use_graph = use_graph != 0;
+    net->use_graph = (flags & CADNN_NET_GRAPH) != 0;
+    net->want_tune = (flags & CADNN_NET_TUNE) != 0;
     net->finalized = true;
     return CADNN_OK;
 }
@@ -247,6 +249,20 @@ extern "C" cadnn_status cadnn_run_net(cadnn_net* net, const void* x, void* y, vo
     if (!net || !x || !y) return fail(CADNN_EINVAL, "cadnn_run_net: NULL pointer");
     if (!net->finalized) return fail(CADNN_EINVAL, "cadnn_run_net: net not finalized");
     hipStream_t s = (hipStream_t)stream;
+    if (net->want_tune) {
+        // the inputs of every layer must hold finite, representative data while it is timed
+        cadnn_status st = launch_all(net, x, y, s);
+        for (size_t i = 0; i < net->ops.size() && st == CADNN_OK; ++i) {
+            const NetOp& op = net->ops[i];
+            if (op.kind != OP_CONV) continue;
+            st = conv2d_tune_impl(op.w, buf_ptr(net, op.src, x, y), buf_ptr(net, op.dst, x, y), op.in.n,
+                                  op.in.h, op.in.w, op.stride, op.pad, op.bias,
+                                  op.res >= 0 ? buf_ptr(net, op.res, x, y) : nullptr, op.relu, s, 20, nullptr);
+        }
+        if (st != CADNN_OK) return st;
+        net->want_tune = false;
+        drop_graph(net);
+    }
     if (!net->use_graph) return launch_all(net, x, y, s);
     if (!net->exec || net->cap_x != x || net->cap_y != y) {
         drop_graph(net);

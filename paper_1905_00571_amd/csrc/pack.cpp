@@ -101,7 +101,7 @@ float f16_to_f32(uint16_t h) {
 // with (0.0f, offset 0) pairs to a multiple of `unroll` entries so the kernel can fetch
 // fixed-size groups.  Each entry is (fp32 value bits, byte offset of the tap inside the
 // staged tile for output pixel (0,0) of the tile).
-static cadnn_status build_plan(const cadnn_weights* w, const TileVariant* v, ConvPlan* plan) {
+static cadnn_status build_tile_plan(const cadnn_weights* w, const ConvVariant* v, ConvPlan* plan) {
     const int g = v->nw * v->rpw;
     const int rows_padded = (w->cout + g - 1) / g * g;
     const int nchunks = (w->cin + v->cch - 1) / v->cch;
@@ -146,7 +146,74 @@ static cadnn_status build_plan(const cadnn_weights* w, const TileVariant* v, Con
     return CADNN_OK;
 }
 
-cadnn_status get_conv_plan(const cadnn_weights* w, const TileVariant* v, const ConvPlan** out) {
+// Device copy of the nonzero stream for a staging-free (FAM_DIRECT) variant.
+//
+// Packed rows are padded to a multiple of the variant's rows-per-workgroup.  A row's
+// input channels are cut into KS equal slices; inside a slice the entries are regrouped
+// tap-major (tap t = r*KW + c), ascending channel inside a tap.  seg_ptr[((i*KS + s)*(T+1)
+// + t .. t+1] delimits the entries of packed row i, slice s, tap t; every such segment is
+// padded to a multiple of `unroll` with (0.0f, channel 0) entries.  An entry is (fp32
+// value bits, input channel).
+static cadnn_status build_direct_plan(const cadnn_weights* w, const ConvVariant* v, ConvPlan* plan) {
+    const int g = v->rows_per_block();
+    const int rows_padded = (w->cout + g - 1) / g * g;
+    const int taps = w->kh * w->kw;
+    const int ks = v->ks;
+    const int slice = (w->cin + ks - 1) / ks;
+    std::vector<int32_t> seg((size_t)rows_padded * ks * (taps + 1), 0);
+    std::vector<int32_t> perm(rows_padded, -1);
+    std::vector<uint2> nz;
+    nz.reserve((size_t)w->nnz + (size_t)w->cout * ks * taps * (v->unroll - 1) / 2 + 16);
+    std::vector<std::vector<uint2>> bucket((size_t)ks * taps);
+    for (int i = 0; i < rows_padded; ++i) {
+        for (auto& b : bucket) b.clear();
+        if (i < w->cout) {
+            perm[i] = w->perm[i];
+            for (int32_t j = w->row_ptr[i]; j < w->row_ptr[i + 1]; ++j) {
+                const int32_t k = w->col_idx[j];
+                const int ci = k / taps, t = k % taps;
+                uint32_t bits;
+                std::memcpy(&bits, &w->vals[j], 4);
+                bucket[(size_t)(ci / slice) * taps + t].push_back(make_uint2(bits, (uint32_t)ci));
+            }
+        }
+        for (int s = 0; s < ks; ++s) {
+            int32_t* sp = &seg[((size_t)i * ks + s) * (taps + 1)];
+            for (int t = 0; t < taps; ++t) {
+                sp[t] = (int32_t)nz.size();
+                const auto& b = bucket[(size_t)s * taps + t];
+                nz.insert(nz.end(), b.begin(), b.end());
+                while (nz.size() % (size_t)v->unroll) nz.push_back(make_uint2(0u, 0u));
+            }
+            sp[taps] = (int32_t)nz.size();
+        }
+    }
+    if (nz.size() > (size_t)INT32_MAX) return fail(CADNN_EUNSUPPORTED, "plan too large");
+    plan->variant = v;
+    plan->nchunks = 1;
+    plan->rows_padded = rows_padded;
+    plan->nz_padded = (int64_t)nz.size();
+    cadnn_status st;
+    if ((st = plan->nz.upload(nz.data(), nz.size() * sizeof(uint2))) != CADNN_OK) return st;
+    if ((st = plan->seg_ptr.upload(seg.data(), seg.size() * 4)) != CADNN_OK) return st;
+    if ((st = plan->perm.upload(perm.data(), perm.size() * 4)) != CADNN_OK) return st;
+    return CADNN_OK;
+}
+
+static cadnn_status build_plan(const cadnn_weights* w, const ConvVariant* v, ConvPlan* plan) {
+    return v->family == FAM_DIRECT ? build_direct_plan(w, v, plan) : build_tile_plan(w, v, plan);
+}
+
+void drop_plans_except(const cadnn_weights* w, const ConvVariant* keep) {
+    std::lock_guard<std::mutex> lock(w->mu);
+    for (auto it = w->plans.begin(); it != w->plans.end();) {
+        bool pinned = it->first == keep;
+        for (const auto& c : w->chosen) pinned = pinned || c.second == it->first;
+        if (pinned) ++it; else it = w->plans.erase(it);
+    }
+}
+
+cadnn_status get_conv_plan(const cadnn_weights* w, const ConvVariant* v, const ConvPlan** out) {
     std::lock_guard<std::mutex> lock(w->mu);
     auto it = w->plans.find(v);
     if (it == w->plans.end()) {

@@ -201,3 +201,51 @@ def test_runtime_error_paths(cad):
     assert L.cadnn_sparse_conv2d(h.handle, x.data_ptr(), y.data_ptr(), 1, 8, 8, 1, 1, None, None, 0, None) == 0
     torch.cuda.synchronize()
     h.free()
+
+
+VARIANT_GEOMS = [
+    # cin, cout, k, stride, pad, h, w, sparsity, n
+    (24, 20, 3, 1, 1, 19, 21, 0.8, 2),
+    (40, 12, 3, 2, 1, 30, 27, 0.7, 1),
+    (70, 37, 1, 1, 0, 23, 9, 0.85, 2),
+    (48, 16, 1, 2, 0, 14, 14, 0.5, 1),
+    (3, 9, 7, 2, 3, 40, 33, 0.0, 1),
+    (520, 6, 3, 1, 1, 7, 7, 0.9, 1),      # long rows: exercises the channel-split variants
+]
+
+
+@pytest.mark.parametrize("geom", VARIANT_GEOMS)
+def test_every_kernel_variant(cad, geom):
+    """Each instantiated kernel variant that can serve a layer is pinned in turn and must
+    meet the same bar (both activation storage types)."""
+    cin, cout, k, stride, pad, h, w_, s, n = geom
+    tag = "var-%d-%d-%d-%d" % (cin, cout, k, stride)
+    x = wl.activation((n, cin, h, w_), tag, 0, relu=False)
+    w = wl.pruned_weights(cout, cin, k, k, s, tag, 1, row_skew=0.5)
+    b = wl.bias_vector(cout, tag, 1, sigma=0.5)
+    hout, wout = oracle.out_size(h, k, stride, pad), oracle.out_size(w_, k, stride, pad)
+    r = wl.activation((n, cout, hout, wout), tag, 2, relu=False, role="r")
+    for dtype, npdt, tol in ((cad.F32, np.float32, TOL_F32), (cad.F16, np.float16, TOL_F16)):
+        xs, rs = x.astype(npdt), r.astype(npdt)
+        ref = oracle.conv2d(xs, w.astype(npdt), b, rs, stride, pad, True, npdt)
+        cond = cond_conv(xs, w.astype(npdt), b, rs, stride, pad)
+        hnd = cad.cadnn_pack_weights(w, dtype)
+        names = cad.cadnn_conv2d_list_variants(hnd, n, h, w_, stride, pad)
+        assert names, geom
+        xd, rd, bd = dev(xs), dev(rs), dev(b)
+        for name in names:
+            cad.cadnn_conv2d_set_variant(hnd, n, h, w_, stride, pad, name)
+            assert cad.cadnn_conv2d_variant_name(hnd, n, h, w_, stride, pad) == name
+            out = torch.full((n, cout, hout, wout), float("nan"), device="cuda", dtype=xd.dtype)
+            cad.cadnn_sparse_conv2d(hnd, xd, stride, pad, bd, rd, True, out=out)
+            torch.cuda.synchronize()
+            assert_layer_close(out.cpu().numpy(), ref, cond, tol, f"{geom} {name}", f16=dtype == cad.F16)
+        # tuning pins one of them and the result still matches
+        out = torch.empty((n, cout, hout, wout), device="cuda", dtype=xd.dtype)
+        us = cad.cadnn_conv2d_tune(hnd, xd, out, stride, pad, bd, rd, True, reps=3)
+        assert us > 0 and cad.cadnn_conv2d_variant_name(hnd, n, h, w_, stride, pad) in names
+        cad.cadnn_sparse_conv2d(hnd, xd, stride, pad, bd, rd, True, out=out)
+        torch.cuda.synchronize()
+        assert_layer_close(out.cpu().numpy(), ref, cond, tol, f"{geom} tuned", f16=dtype == cad.F16)
+        cad.cadnn_conv2d_set_variant(hnd, n, h, w_, stride, pad, None)
+        hnd.free()

@@ -121,8 +121,19 @@ def test_layer_argument_checks_without_a_gpu():
     assert L.cadnn_sparse_conv2d(None, None, None, 1, 8, 8, 1, 1, None, None, 0, None) == 1
     assert L.cadnn_sparse_conv2d(h.handle, None, None, 1, 8, 8, 0, 1, None, None, 0, None) == 1
     assert L.cadnn_sparse_conv2d(h.handle, None, None, 1, 2, 2, 1, 0, None, None, 0, None) == 1   # empty output
-    assert L.cadnn_sparse_conv2d(h.handle, None, None, 1, 8, 8, 3, 1, None, None, 0, None) == 2   # no stride-3 kernel
-    assert b"stride 3" in L.cadnn_last_error()
+    h5 = cad.cadnn_pack_weights(wl.pruned_weights(8, 4, 5, 5, 0.5, "packtest", 4))
+    assert L.cadnn_conv2d_prepare(h5.handle, 1, 8, 8, 1, 2) == 2                                    # no 5x5 kernel
+    assert b"5x5" in L.cadnn_last_error()
+    buf = ctypes.create_string_buffer(4096)
+    assert L.cadnn_conv2d_list_variants(h.handle, 1, 8, 8, 1, 1, buf, 4096) == 0
+    names = buf.value.decode().split("\n")
+    assert len(names) >= 4 and all("3x3" in n and "float" in n for n in names)
+    assert L.cadnn_conv2d_set_variant(h.handle, 1, 8, 8, 1, 1, b"no-such-kernel") == 1
+    assert L.cadnn_conv2d_set_variant(h.handle, 1, 8, 8, 1, 1, names[-1].encode()) == 0
+    assert L.cadnn_conv2d_variant_name(h.handle, 1, 8, 8, 1, 1, buf, 4096) == 0
+    assert buf.value.decode() == names[-1]
+    assert L.cadnn_conv2d_set_variant(h.handle, 1, 8, 8, 1, 1, None) == 0
+    h5.free()
     assert L.cadnn_sparse_fc(h.handle, 1, 1, 1, None, 0, None) == 1                                # 3x3 handle in fc
     assert L.cadnn_maxpool2d(None, None, 1, 1, 4, 4, 2, 2, 0, 0, None) == 1
     net = ctypes.c_void_p()
