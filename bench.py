@@ -115,21 +115,8 @@ def main() -> int:
     per_op_ms = net.profile(xd, y, repeats=20, stream=stream)
     costs = layer_costs(ops, ws, shape, 4)
     groups = {}
-    h, wdt = {0: 224}, {0: 224}
-    cur = {0: shape}
-    keep = net._keep
-    ki = 0
     for i, op in enumerate(ops):
-        if op.kind in ("conv", "fc"):
-            pw = keep[ki]
-            ki += 2
-        if op.kind == "conv":
-            n_, c_, h_, w_ = costs[i]["in"]
-            name = cad.cadnn_conv2d_variant_name(pw, n_, h_, w_, op.stride, op.pad)
-        elif op.kind == "fc":
-            name = "sfc"
-        else:
-            name = op.kind
+        name = net.op_variant(i)
         costs[i]["kernel"] = name
         costs[i]["ms"] = float(per_op_ms[i])
         t = costs[i]["ms"] * 1e-3

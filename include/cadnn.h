@@ -155,8 +155,12 @@ cadnn_status cadnn_dense_conv2d(const void* w_dev, const void* x, void* y, int n
  * Whole-network runner (Section 5 measures single-image latency of a whole
  * network): an ordered list of ops over numbered activation buffers.  Buffer 0
  * is the network input (shape given at creation); the last op's dst buffer is
- * the network output.  All other buffers live in one caller-provided device
- * workspace.  Weight handles and bias arrays must outlive the net.
+ * the network output.  All other tensors live in one caller-provided device
+ * workspace, one region per op output; an output that feeds a padded convolution is
+ * stored with a zero halo of that padding around every channel plane (the halo is
+ * zeroed once in cadnn_net_finalize and never written), so those convolutions read
+ * their zero padding from memory.  Buffer ids only express the wiring.  Weight
+ * handles and bias arrays must outlive the net.
  *   create -> add_* (shapes are inferred and checked op by op) ->
  *   workspace_bytes -> finalize(workspace) -> run (any number of times) -> free
  * cadnn_run_net launches every op on `stream` in order (as one HIP graph launch
@@ -187,6 +191,9 @@ cadnn_status cadnn_run_net(cadnn_net* net, const void* x, void* y, void* stream)
 cadnn_status cadnn_net_num_ops(const cadnn_net* net, int* num_ops);
 cadnn_status cadnn_net_profile(cadnn_net* net, const void* x, void* y, void* stream, int repeats,
                                float* ms_per_op);
+/* Name of the kernel serving op `op_index` (a conv variant name, "sfc", "maxpool" or
+ * "avgpool"), NUL-terminated into buf. */
+cadnn_status cadnn_net_op_variant(const cadnn_net* net, int op_index, char* buf, size_t len);
 /* Copies the current contents of activation buffer `buf` (as left by the last
  * run) to a HOST array of `bytes` bytes; synchronises `stream`. */
 cadnn_status cadnn_net_read_buffer(cadnn_net* net, int buf, void* host_out, size_t bytes,

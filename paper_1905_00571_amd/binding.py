@@ -75,6 +75,7 @@ def lib() -> ctypes.CDLL:
         "cadnn_run_net": (_i, [_vp, _vp, _vp, _vp]),
         "cadnn_net_num_ops": (_i, [_vp, ctypes.POINTER(_i)]),
         "cadnn_net_profile": (_i, [_vp, _vp, _vp, _vp, _i, _f32p]),
+        "cadnn_net_op_variant": (_i, [_vp, _i, ctypes.c_char_p, ctypes.c_size_t]),
         "cadnn_net_read_buffer": (_i, [_vp, _i, _vp, ctypes.c_size_t, _vp]),
         "cadnn_net_free": (_i, [_vp]),
     }
@@ -311,6 +312,11 @@ class Net:
         _check(lib().cadnn_net_profile(self.handle, _dptr(x), _dptr(y), _stream_ptr(stream), repeats,
                                        ms.ctypes.data_as(_f32p)))
         return ms
+
+    def op_variant(self, op_index: int) -> str:
+        buf = ctypes.create_string_buffer(256)
+        _check(lib().cadnn_net_op_variant(self.handle, op_index, buf, 256))
+        return buf.value.decode()
 
     def read_buffer(self, buf: int, shape, stream=None) -> np.ndarray:
         out = np.empty(shape, np.float16 if self.dtype == F16 else np.float32)

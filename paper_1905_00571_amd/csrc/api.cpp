@@ -11,48 +11,52 @@ using namespace cadnn;
 namespace cadnn {
 
 struct ConvGeom {
-    int n, h, w, stride, pad, hout, wout;
-    std::array<int, 5> key() const { return {n, h, w, stride, pad}; }
+    int n, stride, pad, hout, wout;
+    TensorDesc xd;
+    GeomKey key() const { return {n, xd.h, xd.w, stride, pad, xd.ph, xd.pw}; }
 };
 
-static cadnn_status check_conv(const char* who, const cadnn_weights* w, int n, int h, int wdt,
+static cadnn_status check_conv(const char* who, const cadnn_weights* w, const TensorDesc& xd, int n,
                                int stride, int pad, ConvGeom* g) {
     if (!w) return fail(CADNN_EINVAL, "%s: NULL weight handle", who);
-    if (n <= 0 || h <= 0 || wdt <= 0) return fail(CADNN_EINVAL, "%s: non-positive size", who);
+    if (n <= 0 || xd.h <= 0 || xd.w <= 0) return fail(CADNN_EINVAL, "%s: non-positive size", who);
     if (stride <= 0 || pad < 0) return fail(CADNN_EINVAL, "%s: bad stride/pad", who);
-    *g = ConvGeom{n, h, wdt, stride, pad, conv_out(h, w->kh, stride, pad), conv_out(wdt, w->kw, stride, pad)};
+    if (xd.c != w->cin) return fail(CADNN_EINVAL, "%s: %d input channels, weights take %d", who, xd.c, w->cin);
+    g->n = n; g->stride = stride; g->pad = pad; g->xd = xd;
+    g->hout = conv_out(xd.h, w->kh, stride, pad);
+    g->wout = conv_out(xd.w, w->kw, stride, pad);
     if (g->hout <= 0 || g->wout <= 0) return fail(CADNN_EINVAL, "%s: empty output", who);
     if (n > 65535) return fail(CADNN_EUNSUPPORTED, "%s: batch above 65535", who);
-    if ((int64_t)n * w->cin * h * wdt > (int64_t)INT32_MAX * 64 ||
-        (int64_t)n * w->cout * g->hout * g->wout > (int64_t)INT32_MAX * 64)
-        return fail(CADNN_EUNSUPPORTED, "%s: tensor too large", who);
+    if (xd.image * (int64_t)w->elem() >= 0x7ffffff0ll ||
+        (int64_t)w->cout * (g->hout + 64) * (g->wout + 64) * (int64_t)w->elem() >= 0x7ffffff0ll)
+        return fail(CADNN_EUNSUPPORTED, "%s: one image of the tensor is 2 GiB or more", who);
     return CADNN_OK;
 }
 
 static bool variant_fits(const ConvVariant& v, const cadnn_weights* w, const ConvGeom& g) {
-    if (v.kh != w->kh || v.kw != w->kw) return false;
     if (v.is_f16 != (w->dtype == CADNN_F16)) return false;
     if (v.stride != 0 && v.stride != g.stride) return false;
-    const int64_t esz = w->dtype == CADNN_F16 ? 2 : 4;
-    if (v.family == FAM_DIRECT) {
-        if ((int64_t)w->cin * g.h * g.w * esz >= 0x7ffffff0ll) return false;
-        if ((w->cout + v.rows_per_block() - 1) / v.rows_per_block() > 65535) return false;
-    } else {
-        if ((w->cout + v.rows_per_block() - 1) / v.rows_per_block() > 65535) return false;
+    if ((w->cout + v.rows_per_block() - 1) / v.rows_per_block() > 65535) return false;
+    if (v.family == FAM_LINEAR) {
+        // 1x1 filters read only the image proper; larger filters need the zero halo
+        if (w->kh == 1 && w->kw == 1) return g.pad == 0;
+        return g.xd.ph >= g.pad && g.xd.pw >= g.pad;
     }
-    return true;
+    return v.kh == w->kh && v.kw == w->kw;
 }
 
 static std::vector<const ConvVariant*> candidates(const cadnn_weights* w, const ConvGeom& g) {
     std::vector<const ConvVariant*> out;
+    for (const ConvVariant& v : all_linear_variants()) if (variant_fits(v, w, g)) out.push_back(&v);
     for (const ConvVariant& v : all_direct_variants()) if (variant_fits(v, w, g)) out.push_back(&v);
     for (const ConvVariant& v : all_tile_variants()) if (variant_fits(v, w, g)) out.push_back(&v);
     return out;
 }
 
-// Default choice when nothing was tuned or pinned: a rough occupancy/latency model.
-// A wave of a staging-free variant runs rpw * nnz_row / ks groups of loads one after the
-// other; the chip wants at least a couple of waves on each of its 1024 SIMDs.
+// Default choice when nothing was tuned or pinned: a rough latency/throughput model of one
+// launch on 256 CUs x 4 SIMDs (cycles).  Staging-free families: a wave runs
+// rpw * nnz_row / ks load groups back to back; the address units of a CU take about four
+// cycles per wave-wide load.
 static const ConvVariant* heuristic_variant(const cadnn_weights* w, const ConvGeom& g) {
     const std::vector<const ConvVariant*> cand = candidates(w, g);
     if (cand.empty()) return nullptr;
@@ -62,26 +66,27 @@ static const ConvVariant* heuristic_variant(const cadnn_weights* w, const ConvGe
     double best_cost = 0.0;
     for (const ConvVariant* v : cand) {
         double cost;
-        if (v->family == FAM_DIRECT) {
+        if (v->family != FAM_TILE) {
             const double tiles = std::ceil(pixels / (64.0 * v->p)) * g.n;
             const double blocks = tiles * std::ceil((double)w->cout / v->rows_per_block());
             const double waves = blocks * v->nw;
-            const double iters = v->rpw * nnz_row / v->ks;            // loop trips per wave
+            const double iters = v->rpw * nnz_row / v->ks;
             const double lane_eff = pixels * g.n / (tiles * 64.0 * v->p);
-            // latency-bound part: one wave alone; throughput part: address units of a CU
-            const double t_wave = 900.0 + iters / 4.0 * (160.0 + 40.0 * v->p) + (v->ks > 1 ? 300.0 : 0.0);
+            const double per_group = v->family == FAM_LINEAR ? 90.0 + 30.0 * v->p : 200.0 + 40.0 * v->p;
+            const double t_wave = 900.0 + iters / v->unroll * per_group + (v->ks > 1 ? 300.0 : 0.0) +
+                                  (v->family == FAM_DIRECT ? 400.0 : 0.0);
             const double rounds = std::ceil(waves / (1024.0 * 6.0));
             const double t_cu = waves * iters * v->p * 4.2 / 256.0;
-            cost = std::max(t_wave * rounds, t_cu) / std::max(lane_eff, 0.05) * (lane_eff < 1 ? 1.0 : 1.0);
+            cost = std::max(t_wave * rounds, t_cu) / std::max(lane_eff, 0.05);
         } else {
             const double tiles = std::ceil((double)g.wout / v->tw) * std::ceil((double)g.hout / v->th) * g.n;
             const double blocks = tiles * std::ceil((double)w->cout / v->rows_per_block());
             const double nchunks = std::ceil((double)w->cin / v->cch);
             const double stage = nchunks * (1500.0 + (double)std::min(w->cin, v->cch) * v->plane / (v->nw * 64.0) * 24.0);
             const double iters = v->rpw * nnz_row;
-            const double t_block = stage + iters * (10.0 + 6.0 * v->p) / 1.0;
+            const double t_block = stage + iters * (10.0 + 6.0 * v->p);
             const double rounds = std::ceil(blocks / 256.0);
-            cost = t_block * rounds * 3.0;   // until tuned, prefer the staging-free family
+            cost = t_block * rounds * 2.0;   // until tuned, prefer the staging-free families
         }
         if (!best || cost < best_cost) { best = v; best_cost = cost; }
     }
@@ -98,12 +103,11 @@ static const ConvVariant* pick_variant(const cadnn_weights* w, const ConvGeom& g
 }
 
 static cadnn_status launch_variant(const cadnn_weights* w, const ConvVariant* v, const ConvGeom& g,
-                                   const void* x, void* y, const void* bias, const void* residual,
-                                   int relu, hipStream_t s) {
+                                   const void* x, void* y, const TensorDesc& yd, const void* residual,
+                                   const TensorDesc& rd, const void* bias, int relu, hipStream_t s) {
     const ConvPlan* plan = nullptr;
-    cadnn_status st = get_conv_plan(w, v, &plan);
+    cadnn_status st = get_conv_plan(w, v, g.xd, &plan);
     if (st != CADNN_OK) return st;
-    const uint32_t esz = w->dtype == CADNN_F16 ? 2 : 4;
     ConvLaunch a{};
     a.x = x;
     a.y = y;
@@ -112,48 +116,78 @@ static cadnn_status launch_variant(const cadnn_weights* w, const ConvVariant* v,
     a.nz = (const uint2*)plan->nz.p;
     a.seg_ptr = (const int32_t*)plan->seg_ptr.p;
     a.perm = (const int32_t*)plan->perm.p;
-    a.n = g.n; a.cin = w->cin; a.h = g.h; a.w = g.w; a.cout = w->cout;
-    a.hout = g.hout; a.wout = g.wout; a.stride = g.stride; a.pad = g.pad; a.relu = relu ? 1 : 0;
+    a.xd = g.xd; a.yd = yd; a.rd = rd;
+    a.n = g.n; a.cout = w->cout; a.stride = g.stride; a.pad = g.pad; a.relu = relu ? 1 : 0;
     a.nchunks = plan->nchunks;
     a.hwout = g.hout * g.wout;
-    a.chan_stride_bytes = (uint32_t)g.h * (uint32_t)g.w * esz;
-    a.image_bytes = (uint32_t)((int64_t)w->cin * g.h * g.w * esz > 0x7fffffffll ? 0 : (int64_t)w->cin * g.h * g.w * esz);
-    if (v->family == FAM_DIRECT) {
-        a.tiles_x = (a.hwout + 64 * v->p - 1) / (64 * v->p);
-        a.tiles_y = 1;
-        if (a.tiles_x > 0x7fffffff / 64) return fail(CADNN_EUNSUPPORTED, "cadnn_sparse_conv2d: image too large");
-    } else {
+    a.image_bytes = (uint32_t)(g.xd.image * (int64_t)w->elem());
+    if (v->family == FAM_TILE) {
         a.tiles_x = (g.wout + v->tw - 1) / v->tw;
         a.tiles_y = (g.hout + v->th - 1) / v->th;
+    } else {
+        a.tiles_x = (a.hwout + 64 * v->p - 1) / (64 * v->p);
+        a.tiles_y = 1;
     }
     a.row_groups = plan->rows_padded / v->rows_per_block();
-    if (a.row_groups > 65535) return fail(CADNN_EUNSUPPORTED, "cadnn_sparse_conv2d: too many rows");
     CADNN_HIP(v->launch(a, s));
     return CADNN_OK;
 }
 
-cadnn_status conv2d_impl(const cadnn_weights* w, const void* x, void* y, int n, int h, int wdt,
-                         int stride, int pad, const void* bias, const void* residual, int relu,
-                         hipStream_t s) {
+static cadnn_status check_io(const char* who, const cadnn_weights* w, const ConvGeom& g, const void* x,
+                             void* y, const TensorDesc& yd, const void* residual, const TensorDesc& rd) {
+    if (!x || !y) return fail(CADNN_EINVAL, "%s: NULL tensor", who);
+    if (x == y) return fail(CADNN_EINVAL, "%s: y aliases x", who);
+    if (yd.c != w->cout || yd.h != g.hout || yd.w != g.wout) return fail(CADNN_EINVAL, "%s: output layout does not match the layer", who);
+    if (residual && (rd.c != w->cout || rd.h != g.hout || rd.w != g.wout))
+        return fail(CADNN_EINVAL, "%s: residual layout does not match the output", who);
+    return CADNN_OK;
+}
+
+cadnn_status conv2d_impl(const cadnn_weights* w, const void* x, const TensorDesc& xd, void* y,
+                         const TensorDesc& yd, const void* residual, const TensorDesc& rd, int n,
+                         int stride, int pad, const void* bias, int relu, hipStream_t s) {
     ConvGeom g;
-    cadnn_status st = check_conv("cadnn_sparse_conv2d", w, n, h, wdt, stride, pad, &g);
+    cadnn_status st = check_conv("cadnn_sparse_conv2d", w, xd, n, stride, pad, &g);
     if (st != CADNN_OK) return st;
-    if (!x || !y) return fail(CADNN_EINVAL, "cadnn_sparse_conv2d: NULL tensor");
-    if (x == y) return fail(CADNN_EINVAL, "cadnn_sparse_conv2d: y aliases x");
+    if ((st = check_io("cadnn_sparse_conv2d", w, g, x, y, yd, residual, rd)) != CADNN_OK) return st;
     const ConvVariant* v = pick_variant(w, g);
     if (!v)
         return fail(CADNN_EUNSUPPORTED, "cadnn_sparse_conv2d: no kernel for %dx%d filters with stride %d",
                     w->kh, w->kw, stride);
-    return launch_variant(w, v, g, x, y, bias, residual, relu, s);
+    return launch_variant(w, v, g, x, y, yd, residual, rd, bias, relu, s);
 }
 
-cadnn_status conv2d_tune_impl(const cadnn_weights* w, const void* x, void* y, int n, int h, int wdt,
-                              int stride, int pad, const void* bias, const void* residual, int relu,
-                              hipStream_t s, int reps, float* best_us) {
+cadnn_status conv2d_prepare_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad) {
     ConvGeom g;
-    cadnn_status st = check_conv("cadnn_conv2d_tune", w, n, h, wdt, stride, pad, &g);
+    cadnn_status st = check_conv("cadnn_conv2d_prepare", w, xd, n, stride, pad, &g);
     if (st != CADNN_OK) return st;
-    if (!x || !y) return fail(CADNN_EINVAL, "cadnn_conv2d_tune: NULL tensor");
+    const ConvVariant* v = pick_variant(w, g);
+    if (!v)
+        return fail(CADNN_EUNSUPPORTED, "cadnn_conv2d_prepare: no kernel for %dx%d filters with stride %d",
+                    w->kh, w->kw, stride);
+    const ConvPlan* plan = nullptr;
+    return get_conv_plan(w, v, xd, &plan);
+}
+
+const char* conv2d_variant_name_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad) {
+    ConvGeom g;
+    if (check_conv("cadnn_net_op_variant", w, xd, n, stride, pad, &g) != CADNN_OK) return nullptr;
+    const ConvVariant* v = pick_variant(w, g);
+    if (!v) {
+        (void)fail(CADNN_EUNSUPPORTED, "no kernel for %dx%d filters with stride %d", w->kh, w->kw, stride);
+        return nullptr;
+    }
+    return v->name;
+}
+
+cadnn_status conv2d_tune_impl(const cadnn_weights* w, const void* x, const TensorDesc& xd, void* y,
+                              const TensorDesc& yd, const void* residual, const TensorDesc& rd, int n,
+                              int stride, int pad, const void* bias, int relu, hipStream_t s, int reps,
+                              float* best_us) {
+    ConvGeom g;
+    cadnn_status st = check_conv("cadnn_conv2d_tune", w, xd, n, stride, pad, &g);
+    if (st != CADNN_OK) return st;
+    if ((st = check_io("cadnn_conv2d_tune", w, g, x, y, yd, residual, rd)) != CADNN_OK) return st;
     if (reps <= 0) return fail(CADNN_EINVAL, "cadnn_conv2d_tune: reps must be positive");
     const std::vector<const ConvVariant*> cand = candidates(w, g);
     if (cand.empty())
@@ -165,17 +199,17 @@ cadnn_status conv2d_tune_impl(const cadnn_weights* w, const void* x, void* y, in
     const ConvVariant* best = nullptr;
     float best_ms = 0.0f;
     for (const ConvVariant* v : cand) {
-        for (int i = 0; i < 2 && st == CADNN_OK; ++i) st = launch_variant(w, v, g, x, y, bias, residual, relu, s);
+        for (int i = 0; i < 2 && st == CADNN_OK; ++i) st = launch_variant(w, v, g, x, y, yd, residual, rd, bias, relu, s);
         if (st != CADNN_OK) break;
         if (hipEventRecord(e0, s) != hipSuccess) { st = fail(CADNN_EHIP, "hipEventRecord failed"); break; }
-        for (int i = 0; i < reps && st == CADNN_OK; ++i) st = launch_variant(w, v, g, x, y, bias, residual, relu, s);
+        for (int i = 0; i < reps && st == CADNN_OK; ++i) st = launch_variant(w, v, g, x, y, yd, residual, rd, bias, relu, s);
         if (st != CADNN_OK) break;
         if (hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess) { st = fail(CADNN_EHIP, "event wait failed"); break; }
         float ms = 0.0f;
         if (hipEventElapsedTime(&ms, e0, e1) != hipSuccess) { st = fail(CADNN_EHIP, "hipEventElapsedTime failed"); break; }
         if (std::getenv("CADNN_TUNE_LOG"))
             std::fprintf(stderr, "[cadnn tune] cin=%d cout=%d k=%d s=%d hw=%dx%d nnz=%lld %-44s %8.2f us\n", w->cin,
-                         w->cout, w->kh, stride, h, wdt, (long long)w->nnz, v->name, ms * 1e3f / reps);
+                         w->cout, w->kh, stride, xd.h, xd.w, (long long)w->nnz, v->name, ms * 1e3f / reps);
         if (!best || ms < best_ms) { best = v; best_ms = ms; }
     }
     (void)hipEventDestroy(e0);
@@ -185,45 +219,45 @@ cadnn_status conv2d_tune_impl(const cadnn_weights* w, const void* x, void* y, in
         std::lock_guard<std::mutex> lock(w->mu);
         w->chosen[g.key()] = best;
     }
-    drop_plans_except(w, best);
+    drop_unpinned_plans(w);
     if (best_us) *best_us = best_ms * 1e3f / reps;
     return CADNN_OK;
 }
 
 }  // namespace cadnn
 
+static TensorDesc out_desc(const cadnn_weights* w, int h, int wdt, int stride, int pad) {
+    if (stride <= 0 || pad < 0) return make_desc(0, 0, 0);   // rejected by the argument checks
+    return make_desc(w ? w->cout : 0, w ? conv_out(h, w->kh, stride, pad) : 0, w ? conv_out(wdt, w->kw, stride, pad) : 0);
+}
+
 extern "C" cadnn_status cadnn_sparse_conv2d(const cadnn_weights* w, const void* x, void* y, int n,
                                             int h, int wdt, int stride, int pad, const void* bias,
                                             const void* residual, int relu, void* stream) {
-    return conv2d_impl(w, x, y, n, h, wdt, stride, pad, bias, residual, relu, (hipStream_t)stream);
+    const TensorDesc yd = out_desc(w, h, wdt, stride, pad);
+    return conv2d_impl(w, x, make_desc(w ? w->cin : 0, h, wdt), y, yd, residual, yd, n, stride, pad, bias,
+                       relu, (hipStream_t)stream);
 }
 
 extern "C" cadnn_status cadnn_conv2d_tune(const cadnn_weights* w, const void* x, void* y, int n, int h,
                                           int wdt, int stride, int pad, const void* bias,
                                           const void* residual, int relu, void* stream, int reps,
                                           float* best_us) {
-    return conv2d_tune_impl(w, x, y, n, h, wdt, stride, pad, bias, residual, relu, (hipStream_t)stream,
-                            reps, best_us);
+    const TensorDesc yd = out_desc(w, h, wdt, stride, pad);
+    return conv2d_tune_impl(w, x, make_desc(w ? w->cin : 0, h, wdt), y, yd, residual, yd, n, stride, pad,
+                            bias, relu, (hipStream_t)stream, reps, best_us);
 }
 
 extern "C" cadnn_status cadnn_conv2d_prepare(const cadnn_weights* w, int n, int h, int wdt,
                                              int stride, int pad) {
-    ConvGeom g;
-    cadnn_status st = check_conv("cadnn_conv2d_prepare", w, n, h, wdt, stride, pad, &g);
-    if (st != CADNN_OK) return st;
-    const ConvVariant* v = pick_variant(w, g);
-    if (!v)
-        return fail(CADNN_EUNSUPPORTED, "cadnn_conv2d_prepare: no kernel for %dx%d filters with stride %d",
-                    w->kh, w->kw, stride);
-    const ConvPlan* plan = nullptr;
-    return get_conv_plan(w, v, &plan);
+    return conv2d_prepare_impl(w, make_desc(w ? w->cin : 0, h, wdt), n, stride, pad);
 }
 
 extern "C" cadnn_status cadnn_conv2d_variant_name(const cadnn_weights* w, int n, int h, int wdt,
                                                   int stride, int pad, char* buf, size_t len) {
     if (!buf || len == 0) return fail(CADNN_EINVAL, "cadnn_conv2d_variant_name: NULL buffer");
     ConvGeom g;
-    cadnn_status st = check_conv("cadnn_conv2d_variant_name", w, n, h, wdt, stride, pad, &g);
+    cadnn_status st = check_conv("cadnn_conv2d_variant_name", w, make_desc(w ? w->cin : 0, h, wdt), n, stride, pad, &g);
     if (st != CADNN_OK) return st;
     const ConvVariant* v = pick_variant(w, g);
     if (!v)
@@ -238,7 +272,7 @@ extern "C" cadnn_status cadnn_conv2d_list_variants(const cadnn_weights* w, int n
                                                    int stride, int pad, char* buf, size_t len) {
     if (!buf || len == 0) return fail(CADNN_EINVAL, "cadnn_conv2d_list_variants: NULL buffer");
     ConvGeom g;
-    cadnn_status st = check_conv("cadnn_conv2d_list_variants", w, n, h, wdt, stride, pad, &g);
+    cadnn_status st = check_conv("cadnn_conv2d_list_variants", w, make_desc(w ? w->cin : 0, h, wdt), n, stride, pad, &g);
     if (st != CADNN_OK) return st;
     std::string all;
     for (const ConvVariant* v : candidates(w, g)) {
@@ -253,7 +287,7 @@ extern "C" cadnn_status cadnn_conv2d_list_variants(const cadnn_weights* w, int n
 extern "C" cadnn_status cadnn_conv2d_set_variant(const cadnn_weights* w, int n, int h, int wdt,
                                                  int stride, int pad, const char* name) {
     ConvGeom g;
-    cadnn_status st = check_conv("cadnn_conv2d_set_variant", w, n, h, wdt, stride, pad, &g);
+    cadnn_status st = check_conv("cadnn_conv2d_set_variant", w, make_desc(w ? w->cin : 0, h, wdt), n, stride, pad, &g);
     if (st != CADNN_OK) return st;
     std::lock_guard<std::mutex> lock(w->mu);
     if (!name || !*name) {
@@ -295,7 +329,9 @@ extern "C" cadnn_status cadnn_maxpool2d(const void* x, void* y, int n, int c, in
     if (dtype != CADNN_F32 && dtype != CADNN_F16) return fail(CADNN_EINVAL, "cadnn_maxpool2d: dtype");
     if (conv_out(h, k, stride, pad) <= 0 || conv_out(wdt, k, stride, pad) <= 0)
         return fail(CADNN_EINVAL, "cadnn_maxpool2d: empty output");
-    return launch_maxpool(x, y, n, c, h, wdt, k, stride, pad, dtype, (hipStream_t)stream);
+    return launch_maxpool(x, make_desc(c, h, wdt), y,
+                          make_desc(c, conv_out(h, k, stride, pad), conv_out(wdt, k, stride, pad)), n, k, stride,
+                          pad, dtype, (hipStream_t)stream);
 }
 
 extern "C" cadnn_status cadnn_global_avgpool(const void* x, void* y, int n, int c, int h, int wdt,
@@ -303,5 +339,5 @@ extern "C" cadnn_status cadnn_global_avgpool(const void* x, void* y, int n, int 
     if (!x || !y) return fail(CADNN_EINVAL, "cadnn_global_avgpool: NULL tensor");
     if (n <= 0 || c <= 0 || h <= 0 || wdt <= 0) return fail(CADNN_EINVAL, "cadnn_global_avgpool: bad size");
     if (dtype != CADNN_F32 && dtype != CADNN_F16) return fail(CADNN_EINVAL, "cadnn_global_avgpool: dtype");
-    return launch_avgpool(x, y, n, c, h, wdt, dtype, (hipStream_t)stream);
+    return launch_avgpool(x, make_desc(c, h, wdt), y, n, dtype, (hipStream_t)stream);
 }

@@ -61,24 +61,26 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_direct_kernel(const ConvLa
 
     // per-lane byte offset of every tap for each of the lane's pixels
     uint32_t voff[TAPS][P];
+    int oh_[P], ow_[P];
 #pragma unroll
     for (int j = 0; j < P; ++j) {
         const int q = q0 + j * 64 + lane;
         const bool qok = q < a.hwout;
-        const int oh = q / a.wout, ow = q - oh * a.wout;
+        const int oh = q / a.yd.w, ow = q - oh * a.yd.w;
+        oh_[j] = oh; ow_[j] = ow;
 #pragma unroll
         for (int t = 0; t < TAPS; ++t) {
             const int ih = oh * a.stride + t / KW - a.pad;
             const int iw = ow * a.stride + t % KW - a.pad;
-            const bool ok = qok && ih >= 0 && ih < a.h && iw >= 0 && iw < a.w;
-            voff[t][j] = ok ? (uint32_t)(ih * a.w + iw) * (uint32_t)sizeof(T) : kOutOfRange;
+            const bool ok = qok && ih >= 0 && ih < a.xd.h && iw >= 0 && iw < a.xd.w;
+            voff[t][j] = ok ? (uint32_t)(a.xd.origin + ih * a.xd.pitch + iw) * (uint32_t)sizeof(T) : kOutOfRange;
         }
     }
 
     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
         (void*)((const char*)a.x + (size_t)n * a.image_bytes), 0, a.image_bytes, 0x00020000);
     const uint2* __restrict__ nz = a.nz;
-    const uint32_t cs = a.chan_stride_bytes;
+    const uint32_t cs = (uint32_t)a.xd.plane * (uint32_t)sizeof(T);
 
     float acc[RPW][P];
 #pragma unroll
@@ -129,8 +131,8 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_direct_kernel(const ConvLa
     }
 
     // ---- fused epilogue: + bias, + residual, ReLU, store at the original channel
-    T* __restrict__ y = (T*)a.y;
-    const T* __restrict__ res = (const T*)a.residual;
+    T* __restrict__ y = (T*)a.y + (size_t)n * a.yd.image + a.yd.origin;
+    const T* __restrict__ res = a.residual ? (const T*)a.residual + (size_t)n * a.rd.image + a.rd.origin : nullptr;
 #pragma unroll
     for (int r = 0; r < RPW; ++r) {
         const int co = a.perm[row0 + r];
@@ -140,11 +142,10 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_direct_kernel(const ConvLa
         for (int j = 0; j < P; ++j) {
             const int q = q0 + j * 64 + lane;
             if (q < a.hwout) {
-                const size_t idx = ((size_t)n * a.cout + co) * a.hwout + q;
                 float v = acc[r][j] + b;
-                if (res) v += (float)res[idx];
+                if (res) v += (float)res[(size_t)co * a.rd.plane + oh_[j] * a.rd.pitch + ow_[j]];
                 if (a.relu) v = v > 0.0f ? v : 0.0f;
-                y[idx] = (T)v;
+                y[(size_t)co * a.yd.plane + oh_[j] * a.yd.pitch + ow_[j]] = (T)v;
             }
         }
     }
@@ -190,8 +191,7 @@ static ConvVariant make_direct(const char* name) {
 
 const std::vector<ConvVariant>& all_direct_variants() {
     static const std::vector<ConvVariant> v = {
-        CADNN_DIRECT_SHAPES(float, 1, 1), CADNN_DIRECT_SHAPES(float, 3, 3),
-        CADNN_DIRECT_SHAPES(_Float16, 1, 1), CADNN_DIRECT_SHAPES(_Float16, 3, 3)};
+        CADNN_DIRECT_SHAPES(float, 3, 3), CADNN_DIRECT_SHAPES(_Float16, 3, 3)};
     return v;
 }
 

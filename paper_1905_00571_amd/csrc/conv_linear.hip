@@ -1,0 +1,270 @@
+// Linear-address sparse convolution for gfx950 (wave64): no staging, no bounds handling.
+//
+// Lanes of a wave are consecutive flattened output pixels of one image.  The input tensor
+// is read in a layout whose zero halo covers the layer's padding (1x1 filters need none),
+// so the address of the activation a nonzero weight multiplies is simply
+//     base(image) + soffset(channel, tap: uniform, precomputed in the plan)
+//                 + voffset(lane: fixed for the whole kernel)
+// and the inner loop per nonzero is one buffer load and one FMA with the weight as scalar
+// operand (a filter element is loaded once per wave and reused by all its pixels: the
+// paper's redundant filter-load elimination, Section 4).  The (value, offset) pairs are
+// streamed with coalesced vector loads, 64 pairs per wave-wide load and one such load
+// ahead, and broadcast to scalar registers lane by lane: a scalar load per group of
+// nonzeros would expose a cache-miss latency every few FMAs.  A 1x1 layer is the same loop: a sparse-matrix x dense-matrix product
+// (Section 4: 1x1 convolution as matrix multiply).  Keeping the halo of every activation
+// buffer at zero is the layout transformation ("padding", Section 4) that removes the
+// irregular border handling from the hot loop.
+//
+// The loop is software-pipelined by hand: the activations of group g+1 are in flight
+// while group g is accumulated.
+// KS waves may split a row's nonzeros evenly; partial sums meet in LDS before the fused
+// bias / residual / ReLU epilogue (Section 4: conv + batch-norm + activation fused).
+#include "internal.h"
+
+namespace cadnn {
+
+constexpr uint32_t kLinOutOfRange = 0x7ffffff0u;   // beyond any buffer this library accepts
+
+template <typename T_, int P_, int RPW_, int KS_, int NW_, int U_>
+struct LinearCfg {
+    using T = T_;
+    static constexpr int P = P_, RPW = RPW_, KS = KS_, NW = NW_, U = U_;
+    static constexpr int RG = NW / KS;
+    static constexpr int THREADS = NW * 64;
+    static_assert(NW % KS == 0, "KS must divide the waves of a workgroup");
+};
+
+// Wave-wide window over the plan's (value, offset) stream: lane l of `cur` holds entry
+// base + l, `nxt` the entry 64 further on (already in flight).
+struct NzWindow {
+    const uint2* __restrict__ nz;
+    int lane;
+    int base;
+    uint2 cur, nxt;
+    __device__ __forceinline__ void reset(int i) {
+        base = i;
+        cur = nz[base + lane];
+        nxt = nz[base + 64 + lane];
+    }
+    __device__ __forceinline__ void seek(int i) {
+        if (i < base || i >= base + 64) reset(i);
+    }
+    // Broadcasts the U entries starting at absolute index gi (a multiple of U past base).
+    template <int U>
+    __device__ __forceinline__ void group(int gi, float (&w)[U], uint32_t (&o)[U]) {
+        if (gi - base >= 64) {
+            cur = nxt;
+            base += 64;
+            nxt = nz[base + 64 + lane];
+        }
+        const int l0 = gi - base;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            w[u] = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)cur.x, l0 + u));
+            o[u] = (uint32_t)__builtin_amdgcn_readlane((int)cur.y, l0 + u);
+        }
+    }
+};
+
+template <typename T>
+__device__ __forceinline__ float lin_load(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff);
+template <>
+__device__ __forceinline__ float lin_load<float>(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 0));
+}
+template <>
+__device__ __forceinline__ float lin_load<_Float16>(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+    const unsigned short h = __builtin_amdgcn_raw_buffer_load_b16(r, voff, soff, 0);
+    return (float)__builtin_bit_cast(_Float16, h);
+}
+
+template <class Cfg>
+__global__ __launch_bounds__(Cfg::THREADS) void sconv_linear_kernel(const ConvLaunch a) {
+    using T = typename Cfg::T;
+    constexpr int P = Cfg::P, RPW = Cfg::RPW, KS = Cfg::KS, RG = Cfg::RG, U = Cfg::U;
+    __shared__ float red[KS > 1 ? Cfg::NW * RPW * P * 64 : 1];
+
+    const int lane = threadIdx.x & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int rg = wv / KS, ks = wv % KS;
+    const int n = blockIdx.z;
+    const int q0 = blockIdx.x * (64 * P);
+    const int row0 = (blockIdx.y * RG + rg) * RPW;
+
+    // byte offset of tap (0,0) of each of the lane's pixels inside the padded image
+    uint32_t voff[P];
+    int oidx[P];
+    const int base = a.xd.origin - a.pad * a.xd.pitch - a.pad;
+#pragma unroll
+    for (int j = 0; j < P; ++j) {
+        const int q = q0 + j * 64 + lane;
+        const int oh = q / a.yd.w, ow = q - oh * a.yd.w;
+        oidx[j] = q < a.hwout ? oh * a.yd.pitch + ow : -1;
+        voff[j] = q < a.hwout
+                      ? (uint32_t)(base + oh * a.stride * a.xd.pitch + ow * a.stride) * (uint32_t)sizeof(T)
+                      : kLinOutOfRange;
+    }
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)((const char*)a.x + (size_t)n * a.image_bytes), 0, a.image_bytes, 0x00020000);
+
+    NzWindow win;
+    win.nz = a.nz;
+    win.lane = lane;
+    win.base = -(1 << 30);
+
+    float acc[RPW][P];
+#pragma unroll
+    for (int r = 0; r < RPW; ++r) {
+#pragma unroll
+        for (int j = 0; j < P; ++j) acc[r][j] = 0.0f;
+        const int32_t* __restrict__ seg = a.seg_ptr + ((size_t)(row0 + r) * KS + ks);
+        int i = seg[0];
+        const int end = seg[1];
+        if (i >= end) continue;
+        win.seek(i);
+        // Two register sets (A, B) take turns: while one group is accumulated the
+        // activations of the next are in flight.
+        int groups = (end - i) / U;
+        float wa[U], xa[U][P], wb[U], xb[U][P];
+        uint32_t oa[U], ob[U];
+        win.group<U>(i, wa, oa);
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int j = 0; j < P; ++j) xa[u][j] = lin_load<T>(rsrc, voff[j], oa[u]);
+        while (true) {
+            if (groups == 1) {
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+#pragma unroll
+                    for (int j = 0; j < P; ++j) acc[r][j] = fmaf(wa[u], xa[u][j], acc[r][j]);
+                break;
+            }
+            win.group<U>(i + U, wb, ob);
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int j = 0; j < P; ++j) xb[u][j] = lin_load<T>(rsrc, voff[j], ob[u]);
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int j = 0; j < P; ++j) acc[r][j] = fmaf(wa[u], xa[u][j], acc[r][j]);
+            if (groups == 2) {
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+#pragma unroll
+                    for (int j = 0; j < P; ++j) acc[r][j] = fmaf(wb[u], xb[u][j], acc[r][j]);
+                break;
+            }
+            win.group<U>(i + 2 * U, wa, oa);
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int j = 0; j < P; ++j) xa[u][j] = lin_load<T>(rsrc, voff[j], oa[u]);
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int j = 0; j < P; ++j) acc[r][j] = fmaf(wb[u], xb[u][j], acc[r][j]);
+            groups -= 2;
+            i += 2 * U;
+        }
+    }
+
+    if (KS > 1) {
+        // partial sums of the KS slices meet in LDS; slice 0 finishes the row
+#pragma unroll
+        for (int r = 0; r < RPW; ++r)
+#pragma unroll
+            for (int j = 0; j < P; ++j) red[((wv * RPW + r) * P + j) * 64 + lane] = acc[r][j];
+        __syncthreads();
+        if (ks != 0) return;
+#pragma unroll
+        for (int r = 0; r < RPW; ++r)
+#pragma unroll
+            for (int j = 0; j < P; ++j) {
+                float s = acc[r][j];
+#pragma unroll
+                for (int k = 1; k < KS; ++k) s += red[(((wv + k) * RPW + r) * P + j) * 64 + lane];
+                acc[r][j] = s;
+            }
+    }
+
+    // ---- fused epilogue: + bias, + residual, ReLU, store at the original channel
+    T* __restrict__ y = (T*)a.y + (size_t)n * a.yd.image + a.yd.origin;
+    const T* __restrict__ res = a.residual ? (const T*)a.residual + (size_t)n * a.rd.image + a.rd.origin : nullptr;
+    int ridx[P];
+#pragma unroll
+    for (int j = 0; j < P; ++j) {
+        const int q = q0 + j * 64 + lane;
+        const int oh = q / a.yd.w, ow = q - oh * a.yd.w;
+        ridx[j] = oh * a.rd.pitch + ow;
+    }
+#pragma unroll
+    for (int r = 0; r < RPW; ++r) {
+        const int co = a.perm[row0 + r];
+        if (co < 0) continue;
+        const float b = a.bias ? a.bias[co] : 0.0f;
+#pragma unroll
+        for (int j = 0; j < P; ++j) {
+            if (oidx[j] >= 0) {
+                float v = acc[r][j] + b;
+                if (res) v += (float)res[(size_t)co * a.rd.plane + ridx[j]];
+                if (a.relu) v = v > 0.0f ? v : 0.0f;
+                y[(size_t)co * a.yd.plane + oidx[j]] = (T)v;
+            }
+        }
+    }
+}
+
+template <class Cfg>
+static hipError_t launch_linear(const ConvLaunch& a, hipStream_t s) {
+    dim3 grid((unsigned)a.tiles_x, (unsigned)a.row_groups, (unsigned)a.n);
+    dim3 block(Cfg::THREADS);
+    hipLaunchKernelGGL(sconv_linear_kernel<Cfg>, grid, block, 0, s, a);
+    return hipGetLastError();
+}
+
+template <class Cfg>
+static ConvVariant make_linear(const char* name) {
+    ConvVariant v{};
+    v.name = name;
+    v.family = FAM_LINEAR;
+    v.is_f16 = sizeof(typename Cfg::T) == 2;
+    v.kh = 0; v.kw = 0; v.stride = 0;
+    v.p = Cfg::P; v.nw = Cfg::NW; v.rpw = Cfg::RPW; v.ks = Cfg::KS;
+    v.unroll = Cfg::U;
+    v.lds_bytes = Cfg::KS > 1 ? (size_t)Cfg::NW * Cfg::RPW * Cfg::P * 64 * 4 : 0;
+    v.launch = &launch_linear<Cfg>;
+    return v;
+}
+
+#define CADNN_LINEAR(T, P, RPW, KS, NW, U) \
+    make_linear<LinearCfg<T, P, RPW, KS, NW, U>>("slinear_" #T "_p" #P "_r" #RPW "k" #KS "w" #NW "u" #U)
+
+#define CADNN_LINEAR_SHAPES(T)          \
+    CADNN_LINEAR(T, 1, 1, 1, 4, 4),     \
+    CADNN_LINEAR(T, 1, 1, 1, 4, 8),     \
+    CADNN_LINEAR(T, 1, 2, 1, 4, 4),     \
+    CADNN_LINEAR(T, 1, 2, 1, 4, 8),     \
+    CADNN_LINEAR(T, 1, 4, 1, 4, 4),     \
+    CADNN_LINEAR(T, 2, 1, 1, 4, 4),     \
+    CADNN_LINEAR(T, 2, 2, 1, 4, 4),     \
+    CADNN_LINEAR(T, 2, 4, 1, 4, 4),     \
+    CADNN_LINEAR(T, 4, 2, 1, 4, 4),     \
+    CADNN_LINEAR(T, 4, 4, 1, 4, 2),     \
+    CADNN_LINEAR(T, 1, 1, 2, 4, 4),     \
+    CADNN_LINEAR(T, 1, 1, 2, 4, 8),     \
+    CADNN_LINEAR(T, 1, 1, 4, 4, 4),     \
+    CADNN_LINEAR(T, 1, 1, 4, 4, 8),     \
+    CADNN_LINEAR(T, 1, 2, 4, 4, 4),     \
+    CADNN_LINEAR(T, 1, 1, 8, 8, 4),     \
+    CADNN_LINEAR(T, 1, 1, 8, 8, 8),     \
+    CADNN_LINEAR(T, 1, 1, 16, 16, 4),   \
+    CADNN_LINEAR(T, 2, 1, 4, 4, 4)
+
+const std::vector<ConvVariant>& all_linear_variants() {
+    static const std::vector<ConvVariant> v = {CADNN_LINEAR_SHAPES(float), CADNN_LINEAR_SHAPES(_Float16)};
+    return v;
+}
+
+}  // namespace cadnn

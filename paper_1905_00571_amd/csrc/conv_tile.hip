@@ -65,11 +65,13 @@ __device__ __forceinline__ float to_f32(T v) { return (float)v; }
 template <class Cfg>
 __global__ __launch_bounds__(Cfg::THREADS) void sconv_tile_kernel(const ConvLaunch a) {
     using T = typename Cfg::T;
-    constexpr int KH = Cfg::KH, KW = Cfg::KW, S = Cfg::S, TW = Cfg::TW, P = Cfg::P, NW = Cfg::NW,
-                  RPW = Cfg::RPW, CCH = Cfg::CCH, RW = Cfg::RW, TH = Cfg::TH, RH = Cfg::RH,
-                  NPH = Cfg::NPH, CW = Cfg::CW, PITCH = Cfg::PITCH, PLANE = Cfg::PLANE;
-    (void)KH; (void)KW;
-    __shared__ float lds[CCH * PLANE];
+    constexpr int S = Cfg::S, TW = Cfg::TW, P = Cfg::P, NW = Cfg::NW, RPW = Cfg::RPW,
+                  CCH = Cfg::CCH, RW = Cfg::RW, TH = Cfg::TH, RH = Cfg::RH, NPH = Cfg::NPH,
+                  CW = Cfg::CW, PITCH = Cfg::PITCH, PLANE = Cfg::PLANE, U = kUnroll;
+    constexpr int TOTAL = CCH * PLANE;
+    constexpr int NIT = (TOTAL + Cfg::THREADS - 1) / Cfg::THREADS;   // staging passes per chunk
+    constexpr int SB = NIT < 16 ? NIT : 16;                          // loads kept in flight
+    __shared__ float lds[TOTAL];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -80,8 +82,9 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_tile_kernel(const ConvLaun
     const int oh0 = tile_y * TH, ow0 = tile_x * TW;
     const int ih0 = oh0 * S - a.pad, iw0 = ow0 * S - a.pad;
     const int row0 = (blockIdx.y * NW + wv) * RPW;
+    const int cin = a.xd.c, h = a.xd.h, w = a.xd.w;
 
-    const T* __restrict__ xn = (const T*)a.x + (size_t)n * a.cin * a.h * a.w;
+    const T* __restrict__ xn = (const T*)a.x + (size_t)n * a.xd.image + a.xd.origin;
     const uint2* __restrict__ nz = a.nz;
     const int32_t* __restrict__ seg = a.seg_ptr + (size_t)row0 * (a.nchunks + 1);
 
@@ -95,48 +98,77 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_tile_kernel(const ConvLaun
 
     for (int c = 0; c < a.nchunks; ++c) {
         if (c) __syncthreads();
-        // ---- stage CCH channels of the input tile (+halo), zero-filled outside the image
+        // ---- stage CCH channels of the input tile (+halo), zero-filled outside the image;
+        //      SB loads are issued before the first of them is stored
         const int c0 = c * CCH;
-        for (int e = tid; e < CCH * PLANE; e += Cfg::THREADS) {
-            const int ch = e / PLANE;
-            const int rem = e - ch * PLANE;
-            const int rr = rem / PITCH;
-            const int cc = rem - rr * PITCH;
-            const int rph = rr / RH, ri = rr - rph * RH;
-            const int cph = cc / CW, cj = cc - cph * CW;
-            const int ci = c0 + ch;
-            const int ih = ih0 + ri * S + rph;
-            const int iw = iw0 + cj * S + cph;
-            float v = 0.0f;
-            if (cph < NPH && ci < a.cin && ih >= 0 && ih < a.h && iw >= 0 && iw < a.w)
-                v = to_f32(xn[((size_t)ci * a.h + ih) * a.w + iw]);
-            lds[e] = v;
+#pragma unroll
+        for (int it0 = 0; it0 < NIT; it0 += SB) {
+            float v[SB];
+#pragma unroll
+            for (int k = 0; k < SB; ++k) {
+                const int e = tid + (it0 + k) * Cfg::THREADS;
+                const int ch = e / PLANE;
+                const int rem = e - ch * PLANE;
+                const int rr = rem / PITCH;
+                const int cc = rem - rr * PITCH;
+                const int rph = rr / RH, ri = rr - rph * RH;
+                const int cph = cc / CW, cj = cc - cph * CW;
+                const int ci = c0 + ch;
+                const int ih = ih0 + ri * S + rph;
+                const int iw = iw0 + cj * S + cph;
+                v[k] = 0.0f;
+                if (it0 + k < NIT && e < TOTAL && cph < NPH && ci < cin && ih >= 0 && ih < h && iw >= 0 && iw < w)
+                    v[k] = to_f32(xn[(size_t)ci * a.xd.plane + ih * a.xd.pitch + iw]);
+            }
+#pragma unroll
+            for (int k = 0; k < SB; ++k) {
+                const int e = tid + (it0 + k) * Cfg::THREADS;
+                if (it0 + k < NIT && e < TOTAL) lds[e] = v[k];
+            }
         }
         __syncthreads();
-        // ---- stream this chunk's nonzeros of each of the wave's rows
+        // ---- stream this chunk's nonzeros of each of the wave's rows; the next group of
+        //      (value, offset) pairs is fetched while the current one is consumed
 #pragma unroll
         for (int r = 0; r < RPW; ++r) {
             int i = seg[r * (a.nchunks + 1) + c];
             const int end = seg[r * (a.nchunks + 1) + c + 1];
-            for (; i < end; i += kUnroll) {
+            if (i >= end) continue;
+            uint2 cur[U];
 #pragma unroll
-                for (int u = 0; u < kUnroll; ++u) {
-                    const uint2 pr = nz[i + u];
-                    const float wval = __uint_as_float(pr.x);
-                    const char* lp = lane_ptr + pr.y;
+            for (int u = 0; u < U; ++u) cur[u] = nz[i + u];
+            for (i += U; i < end; i += U) {
+                uint2 nxt[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) nxt[u] = nz[i + u];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const float wval = __uint_as_float(cur[u].x);
+                    const char* lp = lane_ptr + cur[u].y;
 #pragma unroll
                     for (int j = 0; j < P; ++j)
                         acc[r][j] = fmaf(wval, *(const float*)(lp + j * RW * PITCH * (int)sizeof(float)),
                                          acc[r][j]);
                 }
+#pragma unroll
+                for (int u = 0; u < U; ++u) cur[u] = nxt[u];
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const float wval = __uint_as_float(cur[u].x);
+                const char* lp = lane_ptr + cur[u].y;
+#pragma unroll
+                for (int j = 0; j < P; ++j)
+                    acc[r][j] = fmaf(wval, *(const float*)(lp + j * RW * PITCH * (int)sizeof(float)),
+                                     acc[r][j]);
             }
         }
     }
 
     // ---- fused epilogue: + bias, + residual, ReLU, store at the original channel
     const int ow = ow0 + tx;
-    T* __restrict__ y = (T*)a.y;
-    const T* __restrict__ res = (const T*)a.residual;
+    T* __restrict__ y = (T*)a.y + (size_t)n * a.yd.image + a.yd.origin;
+    const T* __restrict__ res = a.residual ? (const T*)a.residual + (size_t)n * a.rd.image + a.rd.origin : nullptr;
 #pragma unroll
     for (int r = 0; r < RPW; ++r) {
         const int co = a.perm[row0 + r];
@@ -145,12 +177,11 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_tile_kernel(const ConvLaun
 #pragma unroll
         for (int j = 0; j < P; ++j) {
             const int oh = oh0 + ty + j * RW;
-            if (oh < a.hout && ow < a.wout) {
-                const size_t idx = (((size_t)n * a.cout + co) * a.hout + oh) * a.wout + ow;
+            if (oh < a.yd.h && ow < a.yd.w) {
                 float v = acc[r][j] + b;
-                if (res) v += to_f32(res[idx]);
+                if (res) v += to_f32(res[(size_t)co * a.rd.plane + oh * a.rd.pitch + ow]);
                 if (a.relu) v = v > 0.0f ? v : 0.0f;
-                y[idx] = (T)v;
+                y[(size_t)co * a.yd.plane + oh * a.yd.pitch + ow] = (T)v;
             }
         }
     }
@@ -165,8 +196,8 @@ static hipError_t launch_tile(const ConvLaunch& a, hipStream_t s) {
 }
 
 template <class Cfg>
-static TileVariant make_variant(const char* name) {
-    TileVariant v{};
+static ConvVariant make_variant(const char* name) {
+    ConvVariant v{};
     v.name = name;
     v.family = FAM_TILE;
     v.ks = 1;
@@ -208,8 +239,8 @@ static TileVariant make_variant(const char* name) {
     CADNN_VARIANT(T, 7, 7, 1, 32, 2, 4, 4, 4),              \
     CADNN_VARIANT(T, 7, 7, 1, 8, 1, 4, 4, 8)
 
-const std::vector<TileVariant>& all_tile_variants() {
-    static const std::vector<TileVariant> v = {CADNN_SHAPES(float), CADNN_SHAPES(_Float16)};
+const std::vector<ConvVariant>& all_tile_variants() {
+    static const std::vector<ConvVariant> v = {CADNN_SHAPES(float), CADNN_SHAPES(_Float16)};
     return v;
 }
 

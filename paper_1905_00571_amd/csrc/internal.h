@@ -11,6 +11,7 @@
 #include <memory>
 #include <mutex>
 #include <string>
+#include <tuple>
 #include <vector>
 
 #include "cadnn.h"
@@ -51,19 +52,47 @@ struct DevBuf {
     cadnn_status upload(const void* host, size_t n);
 };
 
+// ---- activation tensor layout --------------------------------------------------
+// One image of an activation tensor is `c` planes of (h + 2*ph) rows of `pitch` elements;
+// element (ch, i, j) of the image proper sits at ch*plane + origin + i*pitch + j.  With
+// ph = pw = 0 this is plain contiguous NCHW.  A halo (ph, pw > 0) is kept at zero by
+// whoever owns the buffer: kernels only ever write the image proper, so a consumer
+// convolution can read its zero padding from memory instead of testing bounds.
+struct TensorDesc {
+    int c, h, w;
+    int ph, pw;
+    int pitch, plane, origin;
+    int64_t image;      // elements between consecutive images
+};
+
+inline TensorDesc make_desc(int c, int h, int w, int ph = 0, int pw = 0) {
+    TensorDesc d;
+    d.c = c; d.h = h; d.w = w; d.ph = ph; d.pw = pw;
+    d.pitch = w + 2 * pw;
+    d.plane = (h + 2 * ph) * d.pitch;
+    d.origin = ph * d.pitch + pw;
+    d.image = (int64_t)c * d.plane;
+    return d;
+}
+
 // ---- convolution kernel variants ------------------------------------------------
 // A variant is one instantiation of a sparse convolution kernel.  Its compile-time
 // geometry decides how a canonical column index k = (ci*KH + r)*KW + c is laid out in the
-// device copy of the nonzero stream (a "plan"), so every variant owns its plan.
+// device copy of the nonzero stream (a "plan"), so every variant owns its plans.
 //
 //  FAM_TILE   : activations staged per channel chunk in an LDS tile with halo; lanes are
 //               the pixels of a TW x TH tile; entries are (value, byte offset in the tile).
 //  FAM_DIRECT : no staging; lanes are flattened output pixels and read activations from
-//               global memory through a buffer resource (out-of-image taps are turned
-//               into out-of-range buffer offsets, which read as zero); a row's entries
-//               are regrouped tap-major so the per-lane tap offset is a fixed register;
+//               global memory through a buffer resource (out-of-image taps become
+//               out-of-range buffer offsets, which read as zero); a row's entries are
+//               regrouped tap-major so the per-lane tap offset is a fixed register;
 //               entries are (value, input channel).
-enum ConvFamily { FAM_TILE = 0, FAM_DIRECT = 1 };
+//  FAM_LINEAR : no staging and no bounds handling at all: the address of a tap is
+//               lane offset + (channel, tap) offset, both linear in the padded layout.
+//               Serves 1x1 filters on any input and larger filters on inputs whose zero
+//               halo covers the padding; entries are (value, byte offset of the tap),
+//               in canonical order, so a plan also depends on the input's plane/pitch.
+enum ConvFamily { FAM_TILE = 0, FAM_DIRECT = 1, FAM_LINEAR = 2 };
 
 struct ConvLaunch;
 
@@ -71,11 +100,11 @@ struct ConvVariant {
     const char* name;
     int family;
     bool is_f16;          // activation storage type served (false = fp32, true = fp16)
-    int kh, kw;           // filter geometry served
+    int kh, kw;           // filter geometry served (0 = any, FAM_LINEAR)
     int stride;           // stride served (0 = any)
     int p;                // output pixels per lane
     int nw, rpw;          // waves per workgroup, packed rows per wave
-    int ks;               // waves that split one row's input channels (partial sums reduced in LDS)
+    int ks;               // waves that split one row's nonzeros (partial sums reduced in LDS)
     // FAM_TILE only
     int tw, rw;           // lanes along ow, lane rows per wave
     int cch;              // input channels staged per chunk
@@ -89,7 +118,6 @@ struct ConvVariant {
     hipError_t (*launch)(const ConvLaunch&, hipStream_t);
     int rows_per_block() const { return family == FAM_TILE ? nw * rpw : (nw / ks) * rpw; }
 };
-typedef ConvVariant TileVariant;
 
 struct ConvLaunch {
     const void* x;
@@ -99,11 +127,11 @@ struct ConvLaunch {
     const uint2* nz;          // plan entries, segment-padded
     const int32_t* seg_ptr;   // plan segment table
     const int32_t* perm;      // [rows_padded] original channel, -1 for padding rows
-    int n, cin, h, w, cout, hout, wout, stride, pad, relu, nchunks;
+    TensorDesc xd, yd, rd;    // layouts of x, y and residual
+    int n, cout, stride, pad, relu, nchunks;
     int tiles_x, tiles_y, row_groups;
-    int hwout;                // hout * wout
-    uint32_t chan_stride_bytes;   // h * w * sizeof(element)
-    uint32_t image_bytes;         // cin * h * w * sizeof(element)
+    int hwout;                // yd.h * yd.w
+    uint32_t image_bytes;     // xd.image * sizeof(element)
 };
 
 struct ConvPlan {
@@ -114,8 +142,14 @@ struct ConvPlan {
     int64_t nz_padded = 0;
 };
 
+// (variant, input plane, input pitch): the last two are 0 for layout-independent plans
+typedef std::tuple<const ConvVariant*, int, int> PlanKey;
+// (n, h, w, stride, pad, input halo rows, input halo columns)
+typedef std::array<int, 7> GeomKey;
+
 const std::vector<ConvVariant>& all_tile_variants();
 const std::vector<ConvVariant>& all_direct_variants();
+const std::vector<ConvVariant>& all_linear_variants();
 
 }  // namespace cadnn
 
@@ -131,35 +165,40 @@ struct cadnn_weights {
     // device copies used by the FC kernel (canonical order)
     mutable cadnn::DevBuf d_row_ptr, d_perm, d_col, d_val;
     mutable bool fc_ready = false;
-    // per-variant conv plans, built lazily
+    // conv plans, built lazily
     mutable std::mutex mu;
-    mutable std::map<const cadnn::ConvVariant*, std::unique_ptr<cadnn::ConvPlan>> plans;
-    // variant pinned for a geometry (n, h, w, stride, pad) by tuning or by the caller
-    mutable std::map<std::array<int, 5>, const cadnn::ConvVariant*> chosen;
+    mutable std::map<cadnn::PlanKey, std::unique_ptr<cadnn::ConvPlan>> plans;
+    // variant pinned for a geometry by tuning or by the caller
+    mutable std::map<cadnn::GeomKey, const cadnn::ConvVariant*> chosen;
+    size_t elem() const { return dtype == CADNN_F16 ? 2 : 4; }
 };
 
 namespace cadnn {
-cadnn_status get_conv_plan(const cadnn_weights* w, const ConvVariant* v, const ConvPlan** out);
-void drop_plans_except(const cadnn_weights* w, const ConvVariant* keep);
+cadnn_status get_conv_plan(const cadnn_weights* w, const ConvVariant* v, const TensorDesc& xd,
+                           const ConvPlan** out);
+void drop_unpinned_plans(const cadnn_weights* w);
 cadnn_status ensure_fc_device(const cadnn_weights* w);
 uint16_t f32_to_f16_rne(float f);
 float f16_to_f32(uint16_t h);
 
 cadnn_status launch_fc(const cadnn_weights* w, const void* x, void* y, int n, const float* bias,
                        int relu, hipStream_t s);
-cadnn_status launch_maxpool(const void* x, void* y, int n, int c, int h, int wdt, int k, int stride,
-                            int pad, cadnn_dtype dt, hipStream_t s);
-cadnn_status launch_avgpool(const void* x, void* y, int n, int c, int h, int wdt, cadnn_dtype dt,
+cadnn_status launch_maxpool(const void* x, const TensorDesc& xd, void* y, const TensorDesc& yd, int n,
+                            int k, int stride, int pad, cadnn_dtype dt, hipStream_t s);
+cadnn_status launch_avgpool(const void* x, const TensorDesc& xd, void* y, int n, cadnn_dtype dt,
                             hipStream_t s);
-}  // namespace cadnn
 
-namespace cadnn {
-cadnn_status conv2d_impl(const cadnn_weights* w, const void* x, void* y, int n, int h, int wdt,
-                         int stride, int pad, const void* bias, const void* residual, int relu,
-                         hipStream_t s);
-cadnn_status conv2d_tune_impl(const cadnn_weights* w, const void* x, void* y, int n, int h, int wdt,
-                              int stride, int pad, const void* bias, const void* residual, int relu,
-                              hipStream_t s, int reps, float* best_us);
+// Layer entry points on explicit layouts (the C ABI wraps them with contiguous layouts).
+cadnn_status conv2d_impl(const cadnn_weights* w, const void* x, const TensorDesc& xd, void* y,
+                         const TensorDesc& yd, const void* residual, const TensorDesc& rd, int n,
+                         int stride, int pad, const void* bias, int relu, hipStream_t s);
+cadnn_status conv2d_tune_impl(const cadnn_weights* w, const void* x, const TensorDesc& xd, void* y,
+                              const TensorDesc& yd, const void* residual, const TensorDesc& rd, int n,
+                              int stride, int pad, const void* bias, int relu, hipStream_t s, int reps,
+                              float* best_us);
+// Name of the variant that would serve the layer (NULL if none).
+const char* conv2d_variant_name_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad);
+cadnn_status conv2d_prepare_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad);
 cadnn_status dense_conv2d_impl(const void* w_dev, const void* x, void* y, int n, int cin, int h,
                                int wdt, int cout, int kh, int kw, int stride, int pad,
                                const void* bias, const void* residual, int relu, cadnn_dtype dtype,

@@ -80,71 +80,77 @@ cadnn_status launch_fc(const cadnn_weights* w, const void* x, void* y, int n, co
 
 template <typename T>
 __global__ __launch_bounds__(256) void maxpool_kernel(const T* __restrict__ x, T* __restrict__ y,
-                                                      int nc, int h, int w, int hout, int wout,
-                                                      int k, int stride, int pad) {
-    const size_t total = (size_t)nc * hout * wout;
+                                                      TensorDesc xd, TensorDesc yd, int n, int k,
+                                                      int stride, int pad) {
+    const size_t per_image = (size_t)yd.c * yd.h * yd.w;
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= total) return;
-    const int ow = (int)(i % wout);
-    const int oh = (int)((i / wout) % hout);
-    const size_t c = i / ((size_t)wout * hout);
-    const T* xp = x + c * (size_t)h * w;
+    if (i >= per_image * n) return;
+    const int img = (int)(i / per_image);
+    const size_t r = i - (size_t)img * per_image;
+    const int ow = (int)(r % yd.w);
+    const int oh = (int)((r / yd.w) % yd.h);
+    const int c = (int)(r / ((size_t)yd.w * yd.h));
+    const T* xp = x + (size_t)img * xd.image + (size_t)c * xd.plane + xd.origin;
     bool seen = false;
     float m = 0.0f;
-    for (int r = 0; r < k; ++r) {
-        const int ih = oh * stride + r - pad;
-        if (ih < 0 || ih >= h) continue;
+    for (int a = 0; a < k; ++a) {
+        const int ih = oh * stride + a - pad;
+        if (ih < 0 || ih >= xd.h) continue;
         for (int q = 0; q < k; ++q) {
             const int iw = ow * stride + q - pad;
-            if (iw < 0 || iw >= w) continue;
-            const float v = (float)xp[(size_t)ih * w + iw];
+            if (iw < 0 || iw >= xd.w) continue;
+            const float v = (float)xp[(size_t)ih * xd.pitch + iw];
             if (!seen || v > m) m = v;
             seen = true;
         }
     }
-    y[i] = (T)m;
+    y[(size_t)img * yd.image + (size_t)c * yd.plane + yd.origin + (size_t)oh * yd.pitch + ow] = (T)m;
 }
 
 // One wave per (n, c) plane; lanes stride over the plane, shuffle reduction at the end.
 template <typename T>
 __global__ __launch_bounds__(256) void avgpool_kernel(const T* __restrict__ x, T* __restrict__ y,
-                                                      int nc, int hw) {
+                                                      TensorDesc xd, int n) {
     const int lane = threadIdx.x & 63;
     const int plane = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (plane >= nc) return;
-    const T* xp = x + (size_t)plane * hw;
+    if (plane >= n * xd.c) return;
+    const int img = plane / xd.c, c = plane - img * xd.c;
+    const T* xp = x + (size_t)img * xd.image + (size_t)c * xd.plane + xd.origin;
+    const int hw = xd.h * xd.w;
     float s = 0.0f;
-    for (int i = lane; i < hw; i += 64) s += (float)xp[i];
+    for (int i = lane; i < hw; i += 64) {
+        const int r = i / xd.w, q = i - r * xd.w;
+        s += (float)xp[(size_t)r * xd.pitch + q];
+    }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
     if (lane == 0) y[plane] = (T)(s / (float)hw);
 }
 
-cadnn_status launch_maxpool(const void* x, void* y, int n, int c, int h, int wdt, int k, int stride,
-                            int pad, cadnn_dtype dt, hipStream_t s) {
-    const int hout = conv_out(h, k, stride, pad), wout = conv_out(wdt, k, stride, pad);
-    const size_t total = (size_t)n * c * hout * wout;
+cadnn_status launch_maxpool(const void* x, const TensorDesc& xd, void* y, const TensorDesc& yd, int n,
+                            int k, int stride, int pad, cadnn_dtype dt, hipStream_t s) {
+    const size_t total = (size_t)n * yd.c * yd.h * yd.w;
     const unsigned blocks = (unsigned)((total + 255) / 256);
     if (dt == CADNN_F16)
-        hipLaunchKernelGGL(maxpool_kernel<_Float16>, dim3(blocks), dim3(256), 0, s,
-                           (const _Float16*)x, (_Float16*)y, n * c, h, wdt, hout, wout, k, stride, pad);
+        hipLaunchKernelGGL(maxpool_kernel<_Float16>, dim3(blocks), dim3(256), 0, s, (const _Float16*)x,
+                           (_Float16*)y, xd, yd, n, k, stride, pad);
     else
         hipLaunchKernelGGL(maxpool_kernel<float>, dim3(blocks), dim3(256), 0, s, (const float*)x,
-                           (float*)y, n * c, h, wdt, hout, wout, k, stride, pad);
+                           (float*)y, xd, yd, n, k, stride, pad);
     CADNN_HIP(hipGetLastError());
     return CADNN_OK;
 }
 
-cadnn_status launch_avgpool(const void* x, void* y, int n, int c, int h, int wdt, cadnn_dtype dt,
+cadnn_status launch_avgpool(const void* x, const TensorDesc& xd, void* y, int n, cadnn_dtype dt,
                             hipStream_t s) {
-    const int nc = n * c;
+    const int nc = n * xd.c;
     const unsigned blocks = (unsigned)((nc + 3) / 4);
     if (dt == CADNN_F16)
-        hipLaunchKernelGGL(avgpool_kernel<_Float16>, dim3(blocks), dim3(256), 0, s,
-                           (const _Float16*)x, (_Float16*)y, nc, h * wdt);
+        hipLaunchKernelGGL(avgpool_kernel<_Float16>, dim3(blocks), dim3(256), 0, s, (const _Float16*)x,
+                           (_Float16*)y, xd, n);
     else
         hipLaunchKernelGGL(avgpool_kernel<float>, dim3(blocks), dim3(256), 0, s, (const float*)x,
-                           (float*)y, nc, h * wdt);
+                           (float*)y, xd, n);
     CADNN_HIP(hipGetLastError());
     return CADNN_OK;
 }

@@ -18,13 +18,19 @@ struct Shape {
     bool operator==(const Shape& o) const { return n == o.n && c == o.c && h == o.h && w == o.w; }
 };
 
+// Where a tensor lives: -1 = the caller's x, -2 = the caller's y, otherwise the output of
+// op `inst` inside the workspace.  Every op output has a region of its own, so a halo
+// that is zeroed once stays zero (kernels only write the image proper).
 struct NetOp {
     OpKind kind;
     const cadnn_weights* w = nullptr;
     const void* bias = nullptr;
     int stride = 1, pad = 0, relu = 0, k = 0;
-    int src = 0, dst = 0, res = -1;
+    int src = 0, dst = 0, res = -1;          // buffer ids as given by the caller
     Shape in, out;
+    int src_inst = -1, res_inst = -1;        // producing op of each input (-1 = net input)
+    TensorDesc xd, yd, rd;
+    size_t y_off = 0;                        // byte offset of this op's output region
 };
 
 }  // namespace
@@ -33,16 +39,14 @@ struct cadnn_net {
     cadnn_dtype dtype = CADNN_F32;
     Shape input;
     std::vector<NetOp> ops;
-    std::map<int, Shape> cur;        // current shape held by each buffer while building
-    std::map<int, size_t> max_elems; // largest element count each buffer ever holds
-    std::map<int, size_t> offset;    // byte offset of each workspace buffer
-    int out_buf = -1;
+    std::map<int, Shape> cur;        // shape currently held by each buffer id while building
+    std::map<int, int> producer;     // op that last wrote each buffer id (-1 = net input)
     size_t ws_bytes = 0;
+    bool laid_out = false;
     bool finalized = false;
     bool use_graph = false;
     bool want_tune = false;
     char* ws = nullptr;
-    // captured graph
     hipGraphExec_t exec = nullptr;
     const void* cap_x = nullptr;
     void* cap_y = nullptr;
@@ -54,40 +58,74 @@ namespace {
 cadnn_status note_output(cadnn_net* net, int dst, const Shape& s) {
     if (dst <= 0) return fail(CADNN_EINVAL, "cadnn_net: dst buffer must be >= 1 (0 is the input)");
     net->cur[dst] = s;
-    size_t& m = net->max_elems[dst];
-    m = std::max(m, s.elems());
-    net->out_buf = dst;
+    net->producer[dst] = (int)net->ops.size();
+    net->laid_out = false;
     return CADNN_OK;
 }
 
-cadnn_status src_shape(cadnn_net* net, int src, Shape* s) {
+cadnn_status src_shape(cadnn_net* net, int src, Shape* s, int* inst) {
     auto it = net->cur.find(src);
     if (it == net->cur.end()) return fail(CADNN_EINVAL, "cadnn_net: buffer %d read before it is written", src);
     *s = it->second;
+    *inst = net->producer[src];
     return CADNN_OK;
 }
 
-void* buf_ptr(cadnn_net* net, int buf, const void* x, void* y) {
-    if (buf == 0) return const_cast<void*>(x);
-    if (buf == net->out_buf) return y;
-    return net->ws + net->offset[buf];
+// Chooses the halo of every op output (the largest padding among the convolutions with
+// filters larger than 1x1 that read it; none if a fully connected layer reads it or if it
+// is the net's output) and lays the regions out back to back.
+void layout(cadnn_net* net) {
+    const int nops = (int)net->ops.size();
+    std::vector<int> halo(nops, 0);
+    std::vector<bool> flat(nops, false);
+    for (const NetOp& op : net->ops) {
+        if (op.src_inst < 0) continue;
+        if (op.kind == OP_FC) flat[op.src_inst] = true;
+        if (op.kind == OP_CONV && (op.w->kh > 1 || op.w->kw > 1))
+            halo[op.src_inst] = std::max(halo[op.src_inst], op.pad);
+    }
+    if (nops) flat[nops - 1] = true;
+    size_t off = 0;
+    for (int i = 0; i < nops; ++i) {
+        NetOp& op = net->ops[i];
+        const int hp = flat[i] ? 0 : halo[i];
+        op.yd = make_desc(op.out.c, op.out.h, op.out.w, hp, hp);
+        op.y_off = off;
+        if (i != nops - 1) off += ((size_t)op.out.n * op.yd.image * net->elem() + 255) / 256 * 256;
+    }
+    for (NetOp& op : net->ops) {
+        op.xd = op.src_inst < 0 ? make_desc(op.in.c, op.in.h, op.in.w) : net->ops[op.src_inst].yd;
+        if (op.res >= 0)
+            op.rd = op.res_inst < 0 ? make_desc(net->input.c, net->input.h, net->input.w) : net->ops[op.res_inst].yd;
+        else
+            op.rd = op.yd;
+    }
+    net->ws_bytes = off;
+    net->laid_out = true;
+}
+
+const void* in_ptr(const cadnn_net* net, int inst, const void* x) {
+    return inst < 0 ? x : (const void*)(net->ws + net->ops[inst].y_off);
+}
+
+void* out_ptr(const cadnn_net* net, size_t i, void* y) {
+    return i + 1 == net->ops.size() ? y : (void*)(net->ws + net->ops[i].y_off);
 }
 
 cadnn_status launch_one(cadnn_net* net, size_t i, const void* x, void* y, hipStream_t s) {
     const NetOp& op = net->ops[i];
-    const void* src = buf_ptr(net, op.src, x, y);
-    void* dst = buf_ptr(net, op.dst, x, y);
+    const void* src = in_ptr(net, op.src_inst, x);
+    void* dst = out_ptr(net, i, y);
     switch (op.kind) {
         case OP_CONV:
-            return conv2d_impl(op.w, src, dst, op.in.n, op.in.h, op.in.w, op.stride, op.pad, op.bias,
-                               op.res >= 0 ? buf_ptr(net, op.res, x, y) : nullptr, op.relu, s);
+            return conv2d_impl(op.w, src, op.xd, dst, op.yd, op.res >= 0 ? in_ptr(net, op.res_inst, x) : nullptr,
+                               op.rd, op.in.n, op.stride, op.pad, op.bias, op.relu, s);
         case OP_FC:
             return launch_fc(op.w, src, dst, op.in.n, (const float*)op.bias, op.relu, s);
         case OP_MAXPOOL:
-            return launch_maxpool(src, dst, op.in.n, op.in.c, op.in.h, op.in.w, op.k, op.stride,
-                                  op.pad, net->dtype, s);
+            return launch_maxpool(src, op.xd, dst, op.yd, op.in.n, op.k, op.stride, op.pad, net->dtype, s);
         case OP_AVGPOOL:
-            return launch_avgpool(src, dst, op.in.n, op.in.c, op.in.h, op.in.w, net->dtype, s);
+            return launch_avgpool(src, op.xd, dst, op.in.n, net->dtype, s);
     }
     return fail(CADNN_EINVAL, "cadnn_net: unknown op kind");
 }
@@ -120,6 +158,7 @@ extern "C" cadnn_status cadnn_net_create(cadnn_dtype dtype, int n, int c, int h,
     net->dtype = dtype;
     net->input = Shape{n, c, h, w};
     net->cur[0] = net->input;
+    net->producer[0] = -1;
     *out = net;
     return CADNN_OK;
 }
@@ -130,23 +169,21 @@ extern "C" cadnn_status cadnn_net_add_conv(cadnn_net* net, const cadnn_weights* 
     if (net->finalized) return fail(CADNN_EINVAL, "cadnn_net_add_conv: net already finalized");
     if (w->dtype != net->dtype) return fail(CADNN_EINVAL, "cadnn_net_add_conv: dtype of weights and net differ");
     if (src == dst || res == dst) return fail(CADNN_EINVAL, "cadnn_net_add_conv: dst aliases an input");
-    Shape in;
-    cadnn_status st = src_shape(net, src, &in);
+    NetOp op;
+    cadnn_status st = src_shape(net, src, &op.in, &op.src_inst);
     if (st != CADNN_OK) return st;
-    if (in.c != w->cin) return fail(CADNN_EINVAL, "cadnn_net_add_conv: %d input channels, weights take %d", in.c, w->cin);
+    if (op.in.c != w->cin) return fail(CADNN_EINVAL, "cadnn_net_add_conv: %d input channels, weights take %d", op.in.c, w->cin);
     if (stride <= 0 || pad < 0) return fail(CADNN_EINVAL, "cadnn_net_add_conv: bad stride/pad");
-    Shape o{in.n, w->cout, conv_out(in.h, w->kh, stride, pad), conv_out(in.w, w->kw, stride, pad)};
-    if (o.h <= 0 || o.w <= 0) return fail(CADNN_EINVAL, "cadnn_net_add_conv: empty output");
+    op.out = Shape{op.in.n, w->cout, conv_out(op.in.h, w->kh, stride, pad), conv_out(op.in.w, w->kw, stride, pad)};
+    if (op.out.h <= 0 || op.out.w <= 0) return fail(CADNN_EINVAL, "cadnn_net_add_conv: empty output");
     if (res >= 0) {
         Shape r;
-        if ((st = src_shape(net, res, &r)) != CADNN_OK) return st;
-        if (!(r == o)) return fail(CADNN_EINVAL, "cadnn_net_add_conv: residual shape differs from output");
+        if ((st = src_shape(net, res, &r, &op.res_inst)) != CADNN_OK) return st;
+        if (!(r == op.out)) return fail(CADNN_EINVAL, "cadnn_net_add_conv: residual shape differs from output");
     }
-    if ((st = cadnn_conv2d_prepare(w, in.n, in.h, in.w, stride, pad)) != CADNN_OK) return st;
-    NetOp op;
     op.kind = OP_CONV; op.w = w; op.bias = bias; op.stride = stride; op.pad = pad; op.relu = relu;
-    op.src = src; op.dst = dst; op.res = res < 0 ? -1 : res; op.in = in; op.out = o;
-    if ((st = note_output(net, dst, o)) != CADNN_OK) return st;
+    op.src = src; op.dst = dst; op.res = res < 0 ? -1 : res;
+    if ((st = note_output(net, dst, op.out)) != CADNN_OK) return st;
     net->ops.push_back(op);
     return CADNN_OK;
 }
@@ -156,15 +193,13 @@ extern "C" cadnn_status cadnn_net_add_maxpool(cadnn_net* net, int k, int stride,
     if (!net) return fail(CADNN_EINVAL, "cadnn_net_add_maxpool: NULL net");
     if (net->finalized) return fail(CADNN_EINVAL, "cadnn_net_add_maxpool: net already finalized");
     if (k <= 0 || stride <= 0 || pad < 0 || src == dst) return fail(CADNN_EINVAL, "cadnn_net_add_maxpool: bad argument");
-    Shape in;
-    cadnn_status st = src_shape(net, src, &in);
-    if (st != CADNN_OK) return st;
-    Shape o{in.n, in.c, conv_out(in.h, k, stride, pad), conv_out(in.w, k, stride, pad)};
-    if (o.h <= 0 || o.w <= 0) return fail(CADNN_EINVAL, "cadnn_net_add_maxpool: empty output");
     NetOp op;
+    cadnn_status st = src_shape(net, src, &op.in, &op.src_inst);
+    if (st != CADNN_OK) return st;
+    op.out = Shape{op.in.n, op.in.c, conv_out(op.in.h, k, stride, pad), conv_out(op.in.w, k, stride, pad)};
+    if (op.out.h <= 0 || op.out.w <= 0) return fail(CADNN_EINVAL, "cadnn_net_add_maxpool: empty output");
     op.kind = OP_MAXPOOL; op.k = k; op.stride = stride; op.pad = pad; op.src = src; op.dst = dst;
-    op.in = in; op.out = o;
-    if ((st = note_output(net, dst, o)) != CADNN_OK) return st;
+    if ((st = note_output(net, dst, op.out)) != CADNN_OK) return st;
     net->ops.push_back(op);
     return CADNN_OK;
 }
@@ -173,13 +208,12 @@ extern "C" cadnn_status cadnn_net_add_global_avgpool(cadnn_net* net, int src, in
     if (!net) return fail(CADNN_EINVAL, "cadnn_net_add_global_avgpool: NULL net");
     if (net->finalized) return fail(CADNN_EINVAL, "cadnn_net_add_global_avgpool: net already finalized");
     if (src == dst) return fail(CADNN_EINVAL, "cadnn_net_add_global_avgpool: dst aliases src");
-    Shape in;
-    cadnn_status st = src_shape(net, src, &in);
-    if (st != CADNN_OK) return st;
-    Shape o{in.n, in.c, 1, 1};
     NetOp op;
-    op.kind = OP_AVGPOOL; op.src = src; op.dst = dst; op.in = in; op.out = o;
-    if ((st = note_output(net, dst, o)) != CADNN_OK) return st;
+    cadnn_status st = src_shape(net, src, &op.in, &op.src_inst);
+    if (st != CADNN_OK) return st;
+    op.out = Shape{op.in.n, op.in.c, 1, 1};
+    op.kind = OP_AVGPOOL; op.src = src; op.dst = dst;
+    if ((st = note_output(net, dst, op.out)) != CADNN_OK) return st;
     net->ops.push_back(op);
     return CADNN_OK;
 }
@@ -191,37 +225,23 @@ extern "C" cadnn_status cadnn_net_add_fc(cadnn_net* net, const cadnn_weights* w,
     if (w->dtype != net->dtype) return fail(CADNN_EINVAL, "cadnn_net_add_fc: dtype of weights and net differ");
     if (w->kh != 1 || w->kw != 1) return fail(CADNN_EINVAL, "cadnn_net_add_fc: weights are not a matrix");
     if (src == dst) return fail(CADNN_EINVAL, "cadnn_net_add_fc: dst aliases src");
-    Shape in;
-    cadnn_status st = src_shape(net, src, &in);
-    if (st != CADNN_OK) return st;
-    if ((size_t)in.c * in.h * in.w != (size_t)w->cin)
-        return fail(CADNN_EINVAL, "cadnn_net_add_fc: %zu input features, weights take %d",
-                    (size_t)in.c * in.h * in.w, w->cin);
-    if ((st = cadnn_fc_prepare(w)) != CADNN_OK) return st;
-    Shape o{in.n, w->cout, 1, 1};
     NetOp op;
+    cadnn_status st = src_shape(net, src, &op.in, &op.src_inst);
+    if (st != CADNN_OK) return st;
+    if ((size_t)op.in.c * op.in.h * op.in.w != (size_t)w->cin)
+        return fail(CADNN_EINVAL, "cadnn_net_add_fc: %zu input features, weights take %d",
+                    (size_t)op.in.c * op.in.h * op.in.w, w->cin);
+    op.out = Shape{op.in.n, w->cout, 1, 1};
     op.kind = OP_FC; op.w = w; op.bias = bias; op.relu = relu; op.src = src; op.dst = dst;
-    op.in = in; op.out = o;
-    if ((st = note_output(net, dst, o)) != CADNN_OK) return st;
+    if ((st = note_output(net, dst, op.out)) != CADNN_OK) return st;
     net->ops.push_back(op);
     return CADNN_OK;
-}
-
-static void layout_workspace(cadnn_net* net) {
-    size_t off = 0;
-    net->offset.clear();
-    for (const auto& kv : net->max_elems) {
-        if (kv.first == net->out_buf) continue;
-        net->offset[kv.first] = off;
-        off += (kv.second * net->elem() + 255) / 256 * 256;
-    }
-    net->ws_bytes = off;
 }
 
 extern "C" cadnn_status cadnn_net_workspace_bytes(const cadnn_net* net, size_t* bytes) {
     if (!net || !bytes) return fail(CADNN_EINVAL, "cadnn_net_workspace_bytes: NULL pointer");
     if (net->ops.empty()) return fail(CADNN_EINVAL, "cadnn_net_workspace_bytes: empty net");
-    layout_workspace(const_cast<cadnn_net*>(net));
+    if (!net->laid_out) layout(const_cast<cadnn_net*>(net));
     *bytes = net->ws_bytes;
     return CADNN_OK;
 }
@@ -229,16 +249,22 @@ extern "C" cadnn_status cadnn_net_workspace_bytes(const cadnn_net* net, size_t* 
 extern "C" cadnn_status cadnn_net_finalize(cadnn_net* net, void* ws, size_t bytes, int flags) {
     if (!net) return fail(CADNN_EINVAL, "cadnn_net_finalize: NULL net");
     if (net->ops.empty()) return fail(CADNN_EINVAL, "cadnn_net_finalize: empty net");
-    // the output buffer is the caller's y: it must not also be read after a later write
-    // to another buffer with the same id -- it is simply the last op's dst.
-    for (const NetOp& op : net->ops)
-        if (op.dst == net->out_buf && &op != &net->ops.back() && net->max_elems[op.dst] > net->ops.back().out.elems())
-            return fail(CADNN_EINVAL, "cadnn_net_finalize: output buffer %d is also used for a larger intermediate", op.dst);
-    layout_workspace(net);
+    if (!net->laid_out) layout(net);
     if (net->ws_bytes > 0 && !ws) return fail(CADNN_EINVAL, "cadnn_net_finalize: NULL workspace");
     if (bytes < net->ws_bytes) return fail(CADNN_EINVAL, "cadnn_net_finalize: workspace of %zu bytes, %zu needed", bytes, net->ws_bytes);
     drop_graph(net);
     net->ws = (char*)ws;
+    // halos are read as the zero padding of the consumer layers and are never written again
+    if (net->ws_bytes) {
+        CADNN_HIP(hipMemset(ws, 0, net->ws_bytes));
+        CADNN_HIP(hipDeviceSynchronize());
+    }
+    for (const NetOp& op : net->ops) {
+        cadnn_status st = CADNN_OK;
+        if (op.kind == OP_CONV) st = conv2d_prepare_impl(op.w, op.xd, op.in.n, op.stride, op.pad);
+        if (op.kind == OP_FC) st = cadnn_fc_prepare(op.w);
+        if (st != CADNN_OK) return st;
+    }
     net->use_graph = (flags & CADNN_NET_GRAPH) != 0;
     net->want_tune = (flags & CADNN_NET_TUNE) != 0;
     net->finalized = true;
@@ -250,14 +276,14 @@ extern "C" cadnn_status cadnn_run_net(cadnn_net* net, const void* x, void* y, vo
     if (!net->finalized) return fail(CADNN_EINVAL, "cadnn_run_net: net not finalized");
     hipStream_t s = (hipStream_t)stream;
     if (net->want_tune) {
-        // the inputs of every layer must hold finite, representative data while it is timed
+        // every layer is timed on the data an ordinary pass leaves in its input region
         cadnn_status st = launch_all(net, x, y, s);
         for (size_t i = 0; i < net->ops.size() && st == CADNN_OK; ++i) {
             const NetOp& op = net->ops[i];
             if (op.kind != OP_CONV) continue;
-            st = conv2d_tune_impl(op.w, buf_ptr(net, op.src, x, y), buf_ptr(net, op.dst, x, y), op.in.n,
-                                  op.in.h, op.in.w, op.stride, op.pad, op.bias,
-                                  op.res >= 0 ? buf_ptr(net, op.res, x, y) : nullptr, op.relu, s, 20, nullptr);
+            st = conv2d_tune_impl(op.w, in_ptr(net, op.src_inst, x), op.xd, out_ptr(net, i, y), op.yd,
+                                  op.res >= 0 ? in_ptr(net, op.res_inst, x) : nullptr, op.rd, op.in.n,
+                                  op.stride, op.pad, op.bias, op.relu, s, 20, nullptr);
         }
         if (st != CADNN_OK) return st;
         net->want_tune = false;
@@ -330,15 +356,44 @@ extern "C" cadnn_status cadnn_net_profile(cadnn_net* net, const void* x, void* y
     return st;
 }
 
+extern "C" cadnn_status cadnn_net_op_variant(const cadnn_net* net, int op_index, char* buf, size_t len) {
+    if (!net || !buf || len == 0) return fail(CADNN_EINVAL, "cadnn_net_op_variant: NULL pointer");
+    if (!net->finalized) return fail(CADNN_EINVAL, "cadnn_net_op_variant: net not finalized");
+    if (op_index < 0 || op_index >= (int)net->ops.size()) return fail(CADNN_EINVAL, "cadnn_net_op_variant: no op %d", op_index);
+    const NetOp& op = net->ops[op_index];
+    const char* name = "";
+    switch (op.kind) {
+        case OP_CONV: name = conv2d_variant_name_impl(op.w, op.xd, op.in.n, op.stride, op.pad); break;
+        case OP_FC: name = "sfc"; break;
+        case OP_MAXPOOL: name = "maxpool"; break;
+        case OP_AVGPOOL: name = "avgpool"; break;
+    }
+    if (!name) return CADNN_EUNSUPPORTED;
+    std::strncpy(buf, name, len - 1);
+    buf[len - 1] = '\0';
+    return CADNN_OK;
+}
+
 extern "C" cadnn_status cadnn_net_read_buffer(cadnn_net* net, int buf, void* host_out, size_t bytes,
                                               void* stream) {
     if (!net || !host_out) return fail(CADNN_EINVAL, "cadnn_net_read_buffer: NULL pointer");
     if (!net->finalized) return fail(CADNN_EINVAL, "cadnn_net_read_buffer: net not finalized");
-    auto it = net->offset.find(buf);
-    if (it == net->offset.end()) return fail(CADNN_EINVAL, "cadnn_net_read_buffer: buffer %d is not in the workspace", buf);
-    if (bytes > net->max_elems[buf] * net->elem()) return fail(CADNN_EINVAL, "cadnn_net_read_buffer: buffer %d is smaller than %zu bytes", buf, bytes);
+    auto it = net->producer.find(buf);
+    if (it == net->producer.end() || it->second < 0 || it->second + 1 == (int)net->ops.size())
+        return fail(CADNN_EINVAL, "cadnn_net_read_buffer: buffer %d is not in the workspace", buf);
+    const NetOp& op = net->ops[it->second];
+    const size_t e = net->elem();
+    if (bytes != op.out.elems() * e)
+        return fail(CADNN_EINVAL, "cadnn_net_read_buffer: buffer %d holds %zu bytes, %zu asked", buf, op.out.elems() * e, bytes);
     CADNN_HIP(hipStreamSynchronize((hipStream_t)stream));
-    CADNN_HIP(hipMemcpy(host_out, net->ws + it->second, bytes, hipMemcpyDeviceToHost));
+    // strip the halo: one 2-D copy per (image, channel) plane
+    for (int n = 0; n < op.out.n; ++n)
+        for (int c = 0; c < op.out.c; ++c) {
+            const char* src = net->ws + op.y_off + ((size_t)n * op.yd.image + (size_t)c * op.yd.plane + op.yd.origin) * e;
+            char* dst = (char*)host_out + ((size_t)n * op.out.c + c) * op.out.h * op.out.w * e;
+            CADNN_HIP(hipMemcpy2D(dst, (size_t)op.out.w * e, src, (size_t)op.yd.pitch * e, (size_t)op.out.w * e,
+                                  (size_t)op.out.h, hipMemcpyDeviceToHost));
+        }
     return CADNN_OK;
 }
 

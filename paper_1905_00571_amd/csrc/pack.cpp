@@ -200,33 +200,99 @@ static cadnn_status build_direct_plan(const cadnn_weights* w, const ConvVariant*
     return CADNN_OK;
 }
 
-static cadnn_status build_plan(const cadnn_weights* w, const ConvVariant* v, ConvPlan* plan) {
-    return v->family == FAM_DIRECT ? build_direct_plan(w, v, plan) : build_tile_plan(w, v, plan);
+// Device copy of the nonzero stream for a linear-address (FAM_LINEAR) variant.
+//
+// Entries stay in canonical order.  A packed row's entries are cut into KS contiguous
+// parts of (nearly) equal length, each padded to a multiple of `unroll` with (0.0f, 0)
+// entries; seg_ptr[i*KS + s .. + 1] delimits part s of packed row i (parts are laid out
+// back to back, so one table of rows_padded*KS + 1 entries suffices).  An entry is (fp32
+// value bits, byte offset of the tap relative to tap (0,0) of channel 0 in the input's
+// padded layout) -- hence the dependence on the input's plane and pitch.  128 spare zero
+// entries end the stream: a wave reads it 64 entries at a time and one such read ahead.
+static cadnn_status build_linear_plan(const cadnn_weights* w, const ConvVariant* v, const TensorDesc& xd,
+                                      ConvPlan* plan) {
+    const int g = v->rows_per_block();
+    const int rows_padded = (w->cout + g - 1) / g * g;
+    const int taps = w->kh * w->kw;
+    const int ks = v->ks;
+    const int64_t esz = (int64_t)w->elem();
+    std::vector<int32_t> seg((size_t)rows_padded * ks + 1, 0);
+    std::vector<int32_t> perm(rows_padded, -1);
+    std::vector<uint2> nz;
+    nz.reserve((size_t)w->nnz + (size_t)w->cout * ks * (v->unroll - 1) / 2 + 16);
+    for (int i = 0; i < rows_padded; ++i) {
+        const int32_t b = i < w->cout ? w->row_ptr[i] : 0;
+        const int32_t e = i < w->cout ? w->row_ptr[i + 1] : 0;
+        if (i < w->cout) perm[i] = w->perm[i];
+        const int32_t per = (e - b + ks - 1) / ks;
+        for (int s = 0; s < ks; ++s) {
+            seg[(size_t)i * ks + s] = (int32_t)nz.size();
+            const int32_t pb = std::min<int64_t>((int64_t)b + (int64_t)s * per, e);
+            const int32_t pe = std::min<int64_t>((int64_t)pb + per, e);
+            for (int32_t j = pb; j < pe; ++j) {
+                const int32_t k = w->col_idx[j];
+                const int ci = k / taps, r = (k % taps) / w->kw, c = k % w->kw;
+                const int64_t off = ((int64_t)ci * xd.plane + (int64_t)r * xd.pitch + c) * esz;
+                uint32_t bits;
+                std::memcpy(&bits, &w->vals[j], 4);
+                nz.push_back(make_uint2(bits, (uint32_t)off));
+            }
+            while (nz.size() % (size_t)v->unroll) nz.push_back(make_uint2(0u, 0u));
+        }
+    }
+    seg[(size_t)rows_padded * ks] = (int32_t)nz.size();
+    for (int u = 0; u < 128; ++u) nz.push_back(make_uint2(0u, 0u));   // read-ahead room
+    if (nz.size() > (size_t)INT32_MAX) return fail(CADNN_EUNSUPPORTED, "plan too large");
+    plan->variant = v;
+    plan->nchunks = 1;
+    plan->rows_padded = rows_padded;
+    plan->nz_padded = (int64_t)nz.size();
+    cadnn_status st;
+    if ((st = plan->nz.upload(nz.data(), nz.size() * sizeof(uint2))) != CADNN_OK) return st;
+    if ((st = plan->seg_ptr.upload(seg.data(), seg.size() * 4)) != CADNN_OK) return st;
+    if ((st = plan->perm.upload(perm.data(), perm.size() * 4)) != CADNN_OK) return st;
+    return CADNN_OK;
 }
 
-void drop_plans_except(const cadnn_weights* w, const ConvVariant* keep) {
+static cadnn_status build_plan(const cadnn_weights* w, const ConvVariant* v, const TensorDesc& xd,
+                               ConvPlan* plan) {
+    switch (v->family) {
+        case FAM_DIRECT: return build_direct_plan(w, v, plan);
+        case FAM_LINEAR: return build_linear_plan(w, v, xd, plan);
+        default: return build_tile_plan(w, v, plan);
+    }
+}
+
+static PlanKey plan_key(const ConvVariant* v, const TensorDesc& xd) {
+    return v->family == FAM_LINEAR ? PlanKey(v, xd.plane, xd.pitch) : PlanKey(v, 0, 0);
+}
+
+// Frees every plan whose variant is not pinned for some geometry of this handle.
+void drop_unpinned_plans(const cadnn_weights* w) {
     std::lock_guard<std::mutex> lock(w->mu);
     for (auto it = w->plans.begin(); it != w->plans.end();) {
-        bool pinned = it->first == keep;
-        for (const auto& c : w->chosen) pinned = pinned || c.second == it->first;
+        bool pinned = false;
+        for (const auto& c : w->chosen) pinned = pinned || c.second == std::get<0>(it->first);
         if (pinned) ++it; else it = w->plans.erase(it);
     }
 }
 
-cadnn_status get_conv_plan(const cadnn_weights* w, const ConvVariant* v, const ConvPlan** out) {
+cadnn_status get_conv_plan(const cadnn_weights* w, const ConvVariant* v, const TensorDesc& xd,
+                           const ConvPlan** out) {
     std::lock_guard<std::mutex> lock(w->mu);
-    auto it = w->plans.find(v);
+    const PlanKey key = plan_key(v, xd);
+    auto it = w->plans.find(key);
     if (it == w->plans.end()) {
         std::unique_ptr<ConvPlan> plan(new (std::nothrow) ConvPlan());
         if (!plan) return fail(CADNN_ENOMEM, "out of host memory");
         cadnn_status st;
         try {
-            st = build_plan(w, v, plan.get());
+            st = build_plan(w, v, xd, plan.get());
         } catch (const std::bad_alloc&) {
             return fail(CADNN_ENOMEM, "out of host memory building a conv plan");
         }
         if (st != CADNN_OK) return st;
-        it = w->plans.emplace(v, std::move(plan)).first;
+        it = w->plans.emplace(key, std::move(plan)).first;
     }
     *out = it->second.get();
     return CADNN_OK;
