@@ -66,6 +66,7 @@ def main() -> int:
     ap.add_argument("--layers-out", type=str, default="")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--no-tune", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives or sharding are part of it); "
@@ -87,7 +88,7 @@ def main() -> int:
     ops = wl.resnet50_ops()
     shape = (1, 3, 224, 224)
     x, ws, bs = wl.net_tensors(ops, "c2", shape)
-    net = cad.build_net(ops, ws, bs, shape, cad.F32, use_graph=not args.no_graph)
+    net = cad.build_net(ops, ws, bs, shape, cad.F32, use_graph=not args.no_graph, tune=not args.no_tune)
     xd = torch.from_numpy(x).cuda()            # inputs resident in HBM before timing
     y = torch.empty(net.out_shape, dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream()
@@ -181,7 +182,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": "resnet50-sparse fp32 batch 1 (configs[2]): 53 convs + FC, conv1 0 %, "
                                "3x3 80 %, 1x1+FC 90 % unstructured sparsity, 1x3x224x224 input",
-                   "graph": not args.no_graph},
+                   "graph": not args.no_graph, "per_layer_kernel_tuning": not args.no_tune},
         "images_per_s": 1e3 / ms_per_step,
         "latency_with_host_sync_ms": lat_sync_ms,
         "effective_gflops_nonzero_macs": total_flops / (ms_per_step * 1e-3) / 1e9,
