@@ -67,6 +67,10 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--no-tune", action="store_true")
+    ap.add_argument("--save-tune", type=str, default="", help="write the tuned variant names (JSON)")
+    ap.add_argument("--load-tune", type=str, default="", help="pin saved variant names instead of tuning")
+    ap.add_argument("--no-layer-profile", action="store_true",
+                    help="skip the per-op event pass (for clean rocprofv3 kernel statistics)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives or sharding are part of it); "
@@ -88,7 +92,11 @@ def main() -> int:
     ops = wl.resnet50_ops()
     shape = (1, 3, 224, 224)
     x, ws, bs = wl.net_tensors(ops, "c2", shape)
-    net = cad.build_net(ops, ws, bs, shape, cad.F32, use_graph=not args.no_graph, tune=not args.no_tune)
+    net = cad.build_net(ops, ws, bs, shape, cad.F32, use_graph=not args.no_graph,
+                        tune=not (args.no_tune or args.load_tune))
+    if args.load_tune:
+        with open(args.load_tune) as f:
+            net.set_variants(json.load(f)["variants"])
     xd = torch.from_numpy(x).cuda()            # inputs resident in HBM before timing
     y = torch.empty(net.out_shape, dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream()
@@ -113,6 +121,14 @@ def main() -> int:
     lat_sync_ms = float(np.median(lat))
 
     # ---- per-op device time with HIP events on the launch stream, grouped by kernel
+    if args.save_tune:
+        with open(args.save_tune, "w") as f:
+            json.dump({"workload": "resnet50-c2-f32-n1", "variants": net.variants()}, f, indent=1)
+    if args.no_layer_profile:
+        print(json.dumps({"metric": "sparse ResNet-50 batch-1 latency", "value": ms_per_step, "unit": "ms",
+                          "note": "per-op pass skipped"}))
+        net.free()
+        return 0
     per_op_ms = net.profile(xd, y, repeats=20, stream=stream)
     costs = layer_costs(ops, ws, shape, 4)
     groups = {}

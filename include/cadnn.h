@@ -194,6 +194,10 @@ cadnn_status cadnn_net_profile(cadnn_net* net, const void* x, void* y, void* str
 /* Name of the kernel serving op `op_index` (a conv variant name, "sfc", "maxpool" or
  * "avgpool"), NUL-terminated into buf. */
 cadnn_status cadnn_net_op_variant(const cadnn_net* net, int op_index, char* buf, size_t len);
+/* Pins the kernel variant of convolution op `op_index` by name (as reported by
+ * cadnn_net_op_variant after tuning), e.g. to replay a saved tuning result.  NULL or ""
+ * returns the op to the built-in heuristic.  The net must be finalized. */
+cadnn_status cadnn_net_set_op_variant(cadnn_net* net, int op_index, const char* name);
 /* Copies the current contents of activation buffer `buf` (as left by the last
  * run) to a HOST array of `bytes` bytes; synchronises `stream`. */
 cadnn_status cadnn_net_read_buffer(cadnn_net* net, int buf, void* host_out, size_t bytes,

@@ -76,6 +76,7 @@ def lib() -> ctypes.CDLL:
         "cadnn_net_num_ops": (_i, [_vp, ctypes.POINTER(_i)]),
         "cadnn_net_profile": (_i, [_vp, _vp, _vp, _vp, _i, _f32p]),
         "cadnn_net_op_variant": (_i, [_vp, _i, ctypes.c_char_p, ctypes.c_size_t]),
+        "cadnn_net_set_op_variant": (_i, [_vp, _i, ctypes.c_char_p]),
         "cadnn_net_read_buffer": (_i, [_vp, _i, _vp, ctypes.c_size_t, _vp]),
         "cadnn_net_free": (_i, [_vp]),
     }
@@ -317,6 +318,18 @@ class Net:
         buf = ctypes.create_string_buffer(256)
         _check(lib().cadnn_net_op_variant(self.handle, op_index, buf, 256))
         return buf.value.decode()
+
+    def set_op_variant(self, op_index: int, name: Optional[str]) -> None:
+        _check(lib().cadnn_net_set_op_variant(self.handle, op_index, None if not name else name.encode()))
+
+    def variants(self) -> List[str]:
+        return [self.op_variant(i) for i in range(self.num_ops())]
+
+    def set_variants(self, names: Sequence[str]) -> None:
+        """Pins every convolution op to the named variant (a saved tuning result)."""
+        for i, (op, name) in enumerate(zip(self.ops, names)):
+            if op.kind == "conv":
+                self.set_op_variant(i, name)
 
     def read_buffer(self, buf: int, shape, stream=None) -> np.ndarray:
         out = np.empty(shape, np.float16 if self.dtype == F16 else np.float32)

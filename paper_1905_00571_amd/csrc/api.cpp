@@ -37,6 +37,8 @@ static bool variant_fits(const ConvVariant& v, const cadnn_weights* w, const Con
     if (v.is_f16 != (w->dtype == CADNN_F16)) return false;
     if (v.stride != 0 && v.stride != g.stride) return false;
     if ((w->cout + v.rows_per_block() - 1) / v.rows_per_block() > 65535) return false;
+    if (v.family == FAM_DENSE)
+        return (double)w->nnz >= 0.25 * (double)w->cout * w->cin * w->kh * w->kw;
     if (v.family == FAM_LINEAR) {
         // 1x1 filters read only the image proper; larger filters need the zero halo
         if (w->kh == 1 && w->kw == 1) return g.pad == 0;
@@ -50,6 +52,7 @@ static std::vector<const ConvVariant*> candidates(const cadnn_weights* w, const 
     for (const ConvVariant& v : all_linear_variants()) if (variant_fits(v, w, g)) out.push_back(&v);
     for (const ConvVariant& v : all_direct_variants()) if (variant_fits(v, w, g)) out.push_back(&v);
     for (const ConvVariant& v : all_tile_variants()) if (variant_fits(v, w, g)) out.push_back(&v);
+    for (const ConvVariant& v : all_dense_variants()) if (variant_fits(v, w, g)) out.push_back(&v);
     return out;
 }
 
@@ -66,7 +69,12 @@ static const ConvVariant* heuristic_variant(const cadnn_weights* w, const ConvGe
     double best_cost = 0.0;
     for (const ConvVariant* v : cand) {
         double cost;
-        if (v->family != FAM_TILE) {
+        if (v->family == FAM_DENSE) {
+            // matrix cores: 64 x 64 tiles, ~1024 cycles per 32-deep chunk of K per tile
+            const double blocks = std::ceil(pixels / 64.0) * g.n * std::ceil(w->cout / 64.0);
+            const double K = (double)w->cin * w->kh * w->kw;
+            cost = 2500.0 + std::ceil(blocks / 256.0) * std::ceil(K / 32.0) * 1100.0;
+        } else if (v->family != FAM_TILE) {
             const double tiles = std::ceil(pixels / (64.0 * v->p)) * g.n;
             const double blocks = tiles * std::ceil((double)w->cout / v->rows_per_block());
             const double waves = blocks * v->nw;
@@ -119,6 +127,7 @@ static cadnn_status launch_variant(const cadnn_weights* w, const ConvVariant* v,
     a.xd = g.xd; a.yd = yd; a.rd = rd;
     a.n = g.n; a.cout = w->cout; a.stride = g.stride; a.pad = g.pad; a.relu = relu ? 1 : 0;
     a.nchunks = plan->nchunks;
+    a.kh = w->kh; a.kw = w->kw; a.is_f16 = w->dtype == CADNN_F16;
     a.hwout = g.hout * g.wout;
     a.image_bytes = (uint32_t)(g.xd.image * (int64_t)w->elem());
     if (v->family == FAM_TILE) {
@@ -178,6 +187,25 @@ const char* conv2d_variant_name_impl(const cadnn_weights* w, const TensorDesc& x
         return nullptr;
     }
     return v->name;
+}
+
+cadnn_status conv2d_set_variant_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad,
+                                     const char* name) {
+    ConvGeom g;
+    cadnn_status st = check_conv("cadnn_conv2d_set_variant", w, xd, n, stride, pad, &g);
+    if (st != CADNN_OK) return st;
+    std::lock_guard<std::mutex> lock(w->mu);
+    if (!name || !*name) {
+        w->chosen.erase(g.key());
+        return CADNN_OK;
+    }
+    for (const ConvVariant* v : candidates(w, g)) {
+        if (std::strcmp(v->name, name) == 0) {
+            w->chosen[g.key()] = v;
+            return CADNN_OK;
+        }
+    }
+    return fail(CADNN_EINVAL, "cadnn_conv2d_set_variant: '%s' does not serve this layer", name);
 }
 
 cadnn_status conv2d_tune_impl(const cadnn_weights* w, const void* x, const TensorDesc& xd, void* y,
@@ -286,21 +314,7 @@ extern "C" cadnn_status cadnn_conv2d_list_variants(const cadnn_weights* w, int n
 
 extern "C" cadnn_status cadnn_conv2d_set_variant(const cadnn_weights* w, int n, int h, int wdt,
                                                  int stride, int pad, const char* name) {
-    ConvGeom g;
-    cadnn_status st = check_conv("cadnn_conv2d_set_variant", w, make_desc(w ? w->cin : 0, h, wdt), n, stride, pad, &g);
-    if (st != CADNN_OK) return st;
-    std::lock_guard<std::mutex> lock(w->mu);
-    if (!name || !*name) {
-        w->chosen.erase(g.key());
-        return CADNN_OK;
-    }
-    for (const ConvVariant* v : candidates(w, g)) {
-        if (std::strcmp(v->name, name) == 0) {
-            w->chosen[g.key()] = v;
-            return CADNN_OK;
-        }
-    }
-    return fail(CADNN_EINVAL, "cadnn_conv2d_set_variant: '%s' does not serve this layer", name);
+    return conv2d_set_variant_impl(w, make_desc(w ? w->cin : 0, h, wdt), n, stride, pad, name);
 }
 
 extern "C" cadnn_status cadnn_sparse_fc(const cadnn_weights* w, const void* x, void* y, int n,

@@ -92,7 +92,10 @@ inline TensorDesc make_desc(int c, int h, int w, int ph = 0, int pw = 0) {
 //               Serves 1x1 filters on any input and larger filters on inputs whose zero
 //               halo covers the padding; entries are (value, byte offset of the tap),
 //               in canonical order, so a plan also depends on the input's plane/pitch.
-enum ConvFamily { FAM_TILE = 0, FAM_DIRECT = 1, FAM_LINEAR = 2 };
+//  FAM_DENSE  : the layer as a dense implicit GEMM on the matrix cores; the plan is the
+//               unpacked [cout][K] weight matrix.  Offered only when at least a quarter
+//               of the weights are nonzero (the unpruned first layer of a network).
+enum ConvFamily { FAM_TILE = 0, FAM_DIRECT = 1, FAM_LINEAR = 2, FAM_DENSE = 3 };
 
 struct ConvLaunch;
 
@@ -116,7 +119,7 @@ struct ConvVariant {
     int unroll;           // nonzeros per scalar fetch; segments are padded to a multiple of it
     size_t lds_bytes;
     hipError_t (*launch)(const ConvLaunch&, hipStream_t);
-    int rows_per_block() const { return family == FAM_TILE ? nw * rpw : (nw / ks) * rpw; }
+    int rows_per_block() const { return family == FAM_TILE || family == FAM_DENSE ? nw * rpw : (nw / ks) * rpw; }
 };
 
 struct ConvLaunch {
@@ -129,6 +132,7 @@ struct ConvLaunch {
     const int32_t* perm;      // [rows_padded] original channel, -1 for padding rows
     TensorDesc xd, yd, rd;    // layouts of x, y and residual
     int n, cout, stride, pad, relu, nchunks;
+    int kh, kw, is_f16;
     int tiles_x, tiles_y, row_groups;
     int hwout;                // yd.h * yd.w
     uint32_t image_bytes;     // xd.image * sizeof(element)
@@ -150,6 +154,7 @@ typedef std::array<int, 7> GeomKey;
 const std::vector<ConvVariant>& all_tile_variants();
 const std::vector<ConvVariant>& all_direct_variants();
 const std::vector<ConvVariant>& all_linear_variants();
+const std::vector<ConvVariant>& all_dense_variants();
 
 }  // namespace cadnn
 
@@ -198,7 +203,13 @@ cadnn_status conv2d_tune_impl(const cadnn_weights* w, const void* x, const Tenso
                               float* best_us);
 // Name of the variant that would serve the layer (NULL if none).
 const char* conv2d_variant_name_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad);
+cadnn_status conv2d_set_variant_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad,
+                                     const char* name);
 cadnn_status conv2d_prepare_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad);
+cadnn_status dense_conv2d_desc(const void* w_dev, const void* x, const TensorDesc& xd, void* y,
+                               const TensorDesc& yd, const void* residual, const TensorDesc& rd, int n,
+                               int cout, int kh, int kw, int stride, int pad, const void* bias, int relu,
+                               cadnn_dtype dtype, hipStream_t s);
 cadnn_status dense_conv2d_impl(const void* w_dev, const void* x, void* y, int n, int cin, int h,
                                int wdt, int cout, int kh, int kw, int stride, int pad,
                                const void* bias, const void* residual, int relu, cadnn_dtype dtype,

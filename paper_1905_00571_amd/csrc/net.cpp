@@ -374,6 +374,18 @@ extern "C" cadnn_status cadnn_net_op_variant(const cadnn_net* net, int op_index,
     return CADNN_OK;
 }
 
+extern "C" cadnn_status cadnn_net_set_op_variant(cadnn_net* net, int op_index, const char* name) {
+    if (!net) return fail(CADNN_EINVAL, "cadnn_net_set_op_variant: NULL net");
+    if (!net->finalized) return fail(CADNN_EINVAL, "cadnn_net_set_op_variant: net not finalized");
+    if (op_index < 0 || op_index >= (int)net->ops.size()) return fail(CADNN_EINVAL, "cadnn_net_set_op_variant: no op %d", op_index);
+    const NetOp& op = net->ops[op_index];
+    if (op.kind != OP_CONV) return fail(CADNN_EINVAL, "cadnn_net_set_op_variant: op %d is not a convolution", op_index);
+    cadnn_status st = conv2d_set_variant_impl(op.w, op.xd, op.in.n, op.stride, op.pad, name);
+    if (st != CADNN_OK) return st;
+    drop_graph(net);
+    return conv2d_prepare_impl(op.w, op.xd, op.in.n, op.stride, op.pad);
+}
+
 extern "C" cadnn_status cadnn_net_read_buffer(cadnn_net* net, int buf, void* host_out, size_t bytes,
                                               void* stream) {
     if (!net || !host_out) return fail(CADNN_EINVAL, "cadnn_net_read_buffer: NULL pointer");

@@ -254,9 +254,34 @@ static cadnn_status build_linear_plan(const cadnn_weights* w, const ConvVariant*
     return CADNN_OK;
 }
 
+// Plan of the dense fallback: the unpacked [cout][K] matrix in the storage type.
+static cadnn_status build_dense_plan(const cadnn_weights* w, const ConvVariant* v, ConvPlan* plan) {
+    const size_t K = (size_t)w->cin * w->kh * w->kw;
+    plan->variant = v;
+    plan->nchunks = 1;
+    plan->rows_padded = (w->cout + 63) / 64 * 64;
+    plan->nz_padded = (int64_t)((size_t)w->cout * K);
+    cadnn_status st;
+    if (w->dtype == CADNN_F16) {
+        std::vector<uint16_t> dense((size_t)w->cout * K, 0);
+        for (int i = 0; i < w->cout; ++i)
+            for (int32_t j = w->row_ptr[i]; j < w->row_ptr[i + 1]; ++j)
+                dense[(size_t)w->perm[i] * K + w->col_idx[j]] = w->vals16[j];
+        st = plan->nz.upload(dense.data(), dense.size() * 2);
+    } else {
+        std::vector<float> dense((size_t)w->cout * K, 0.0f);
+        for (int i = 0; i < w->cout; ++i)
+            for (int32_t j = w->row_ptr[i]; j < w->row_ptr[i + 1]; ++j)
+                dense[(size_t)w->perm[i] * K + w->col_idx[j]] = w->vals[j];
+        st = plan->nz.upload(dense.data(), dense.size() * 4);
+    }
+    return st;
+}
+
 static cadnn_status build_plan(const cadnn_weights* w, const ConvVariant* v, const TensorDesc& xd,
                                ConvPlan* plan) {
     switch (v->family) {
+        case FAM_DENSE: return build_dense_plan(w, v, plan);
         case FAM_DIRECT: return build_direct_plan(w, v, plan);
         case FAM_LINEAR: return build_linear_plan(w, v, xd, plan);
         default: return build_tile_plan(w, v, plan);

@@ -211,6 +211,8 @@ VARIANT_GEOMS = [
     (48, 16, 1, 2, 0, 14, 14, 0.5, 1),
     (3, 9, 7, 2, 3, 40, 33, 0.0, 1),
     (520, 6, 3, 1, 1, 7, 7, 0.9, 1),      # long rows: exercises the channel-split variants
+    (37, 70, 3, 2, 1, 21, 17, 0.5, 2),    # dense enough for the matrix-core fallback too
+    (19, 33, 1, 1, 0, 9, 9, 0.0, 1),
 ]
 
 
@@ -249,3 +251,29 @@ def test_every_kernel_variant(cad, geom):
         assert_layer_close(out.cpu().numpy(), ref, cond, tol, f"{geom} tuned", f16=dtype == cad.F16)
         cad.cadnn_conv2d_set_variant(hnd, n, h, w_, stride, pad, None)
         hnd.free()
+
+
+@pytest.mark.parametrize("geom", [(3, 64, 7, 2, 3, 56, 56, 1), (64, 64, 3, 1, 1, 28, 28, 2),
+                                  (100, 70, 1, 1, 0, 13, 13, 1), (33, 40, 3, 2, 1, 19, 23, 1),
+                                  (16, 8, 5, 1, 2, 11, 11, 1)])
+def test_dense_comparator(cad, geom):
+    """cadnn_dense_conv2d (matrix-core implicit GEMM over the dense tensor) meets the same bar."""
+    cin, cout, k, stride, pad, h, w_, n = geom
+    tag = "dense-%d-%d-%d-%d" % (cin, cout, k, stride)
+    x = wl.activation((n, cin, h, w_), tag, 0, relu=False)
+    w = wl.pruned_weights(cout, cin, k, k, 0.3, tag, 1)
+    b = wl.bias_vector(cout, tag, 1, sigma=0.5)
+    hout, wout = oracle.out_size(h, k, stride, pad), oracle.out_size(w_, k, stride, pad)
+    r = wl.activation((n, cout, hout, wout), tag, 2, relu=False, role="r")
+    for npdt, tol, f16 in ((np.float32, TOL_F32, False), (np.float16, TOL_F16, True)):
+        xs, rs, wsd = x.astype(npdt), r.astype(npdt), w.astype(npdt)
+        ref = oracle.conv2d(xs, wsd, b, rs, stride, pad, True, npdt)
+        cond = cond_conv(xs, wsd, b, rs, stride, pad)
+        y = cad.cadnn_dense_conv2d(dev(wsd), dev(xs), stride, pad, dev(b), dev(rs), True)
+        torch.cuda.synchronize()
+        assert_layer_close(y.cpu().numpy(), ref, cond, tol, f"dense {geom} f16={f16}", f16=f16)
+        y = cad.cadnn_dense_conv2d(dev(wsd), dev(xs), stride, pad, None, None, False)
+        torch.cuda.synchronize()
+        ref = oracle.conv2d(xs, wsd, None, None, stride, pad, False, npdt)
+        assert_layer_close(y.cpu().numpy(), ref, cond_conv(xs, wsd, None, None, stride, pad), tol,
+                           f"dense {geom} plain f16={f16}", f16=f16)

@@ -121,8 +121,8 @@ def test_layer_argument_checks_without_a_gpu():
     assert L.cadnn_sparse_conv2d(None, None, None, 1, 8, 8, 1, 1, None, None, 0, None) == 1
     assert L.cadnn_sparse_conv2d(h.handle, None, None, 1, 8, 8, 0, 1, None, None, 0, None) == 1
     assert L.cadnn_sparse_conv2d(h.handle, None, None, 1, 2, 2, 1, 0, None, None, 0, None) == 1   # empty output
-    h5 = cad.cadnn_pack_weights(wl.pruned_weights(8, 4, 5, 5, 0.5, "packtest", 4))
-    assert L.cadnn_conv2d_prepare(h5.handle, 1, 8, 8, 1, 2) == 2                                    # no 5x5 kernel
+    h5 = cad.cadnn_pack_weights(wl.pruned_weights(8, 4, 5, 5, 0.9, "packtest", 4))
+    assert L.cadnn_conv2d_prepare(h5.handle, 1, 8, 8, 1, 2) == 2                                    # no sparse 5x5 kernel
     assert b"5x5" in L.cadnn_last_error()
     buf = ctypes.create_string_buffer(4096)
     assert L.cadnn_conv2d_list_variants(h.handle, 1, 8, 8, 1, 1, buf, 4096) == 0
