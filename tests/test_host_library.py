@@ -127,7 +127,7 @@ def test_layer_argument_checks_without_a_gpu():
     buf = ctypes.create_string_buffer(4096)
     assert L.cadnn_conv2d_list_variants(h.handle, 1, 8, 8, 1, 1, buf, 4096) == 0
     names = buf.value.decode().split("\n")
-    assert len(names) >= 4 and all("3x3" in n and "float" in n for n in names)
+    assert len(names) >= 4 and all("float" in n for n in names) and any("3x3" in n for n in names)
     assert L.cadnn_conv2d_set_variant(h.handle, 1, 8, 8, 1, 1, b"no-such-kernel") == 1
     assert L.cadnn_conv2d_set_variant(h.handle, 1, 8, 8, 1, 1, names[-1].encode()) == 0
     assert L.cadnn_conv2d_variant_name(h.handle, 1, 8, 8, 1, 1, buf, 4096) == 0
