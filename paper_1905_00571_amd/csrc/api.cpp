@@ -53,6 +53,7 @@ static std::vector<const ConvVariant*> candidates(const cadnn_weights* w, const 
     for (const ConvVariant& v : all_direct_variants()) if (variant_fits(v, w, g)) out.push_back(&v);
     for (const ConvVariant& v : all_tile_variants()) if (variant_fits(v, w, g)) out.push_back(&v);
     for (const ConvVariant& v : all_dense_variants()) if (variant_fits(v, w, g)) out.push_back(&v);
+    for (const ConvVariant& v : all_stile_variants()) if (variant_fits(v, w, g)) out.push_back(&v);
     return out;
 }
 
@@ -74,6 +75,8 @@ static const ConvVariant* heuristic_variant(const cadnn_weights* w, const ConvGe
             const double blocks = std::ceil(pixels / 64.0) * g.n * std::ceil(w->cout / 64.0);
             const double K = (double)w->cin * w->kh * w->kw;
             cost = 2500.0 + std::ceil(blocks / 256.0) * std::ceil(K / 32.0) * 1100.0;
+        } else if (v->family == FAM_STILE) {
+            continue;   // chosen by tuning only: whether its plan fits depends on the weights
         } else if (v->family != FAM_TILE) {
             const double tiles = std::ceil(pixels / (64.0 * v->p)) * g.n;
             const double blocks = tiles * std::ceil((double)w->cout / v->rows_per_block());
@@ -130,7 +133,7 @@ static cadnn_status launch_variant(const cadnn_weights* w, const ConvVariant* v,
     a.kh = w->kh; a.kw = w->kw; a.is_f16 = w->dtype == CADNN_F16;
     a.hwout = g.hout * g.wout;
     a.image_bytes = (uint32_t)(g.xd.image * (int64_t)w->elem());
-    if (v->family == FAM_TILE) {
+    if (v->family == FAM_TILE || v->family == FAM_STILE) {
         a.tiles_x = (g.wout + v->tw - 1) / v->tw;
         a.tiles_y = (g.hout + v->th - 1) / v->th;
     } else {
@@ -227,6 +230,10 @@ cadnn_status conv2d_tune_impl(const cadnn_weights* w, const void* x, const Tenso
     const ConvVariant* best = nullptr;
     float best_ms = 0.0f;
     for (const ConvVariant* v : cand) {
+        {
+            const ConvPlan* probe = nullptr;
+            if (get_conv_plan(w, v, g.xd, &probe) == CADNN_EUNSUPPORTED) continue;   // does not fit these weights
+        }
         for (int i = 0; i < 2 && st == CADNN_OK; ++i) st = launch_variant(w, v, g, x, y, yd, residual, rd, bias, relu, s);
         if (st != CADNN_OK) break;
         if (hipEventRecord(e0, s) != hipSuccess) { st = fail(CADNN_EHIP, "hipEventRecord failed"); break; }

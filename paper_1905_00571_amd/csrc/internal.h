@@ -95,7 +95,10 @@ inline TensorDesc make_desc(int c, int h, int w, int ph = 0, int pw = 0) {
 //  FAM_DENSE  : the layer as a dense implicit GEMM on the matrix cores; the plan is the
 //               unpacked [cout][K] weight matrix.  Offered only when at least a quarter
 //               of the weights are nonzero (the unpruned first layer of a network).
-enum ConvFamily { FAM_TILE = 0, FAM_DIRECT = 1, FAM_LINEAR = 2, FAM_DENSE = 3 };
+//  FAM_STILE  : LDS tiles as FAM_TILE, but every wave of the workgroup stages and consumes
+//               its own channel chunks (no barrier in the main loop) for all G rows of
+//               the workgroup; the plan is chunk-major per group of G rows.
+enum ConvFamily { FAM_TILE = 0, FAM_DIRECT = 1, FAM_LINEAR = 2, FAM_DENSE = 3, FAM_STILE = 4 };
 
 struct ConvLaunch;
 
@@ -117,6 +120,7 @@ struct ConvVariant {
     int pitch, plane;     // LDS floats per tile row / per channel
     int elem_bytes;       // size of one staged tile element in LDS
     int unroll;           // nonzeros per scalar fetch; segments are padded to a multiple of it
+    int nz_cap;           // FAM_STILE: most stream entries per (row group, chunk) the kernel buffers
     size_t lds_bytes;
     hipError_t (*launch)(const ConvLaunch&, hipStream_t);
     int rows_per_block() const { return family == FAM_TILE || family == FAM_DENSE ? nw * rpw : (nw / ks) * rpw; }
@@ -155,6 +159,7 @@ const std::vector<ConvVariant>& all_tile_variants();
 const std::vector<ConvVariant>& all_direct_variants();
 const std::vector<ConvVariant>& all_linear_variants();
 const std::vector<ConvVariant>& all_dense_variants();
+const std::vector<ConvVariant>& all_stile_variants();
 
 }  // namespace cadnn
 

@@ -254,6 +254,71 @@ static cadnn_status build_linear_plan(const cadnn_weights* w, const ConvVariant*
     return CADNN_OK;
 }
 
+// Device copy of the nonzero stream for a wave-sliced tile (FAM_STILE) variant.
+//
+// Packed rows are taken G at a time (G = rows per workgroup).  For group g and channel
+// chunk c the entries of the G rows whose channel lies in the chunk are laid out row after
+// row, each row's run padded to a multiple of `unroll` with (0.0f, offset 0);
+// seg_ptr[(g*nchunks + c)*(G+1) + r .. + 1] delimits row r's run.  An entry is (fp32 value
+// bits, byte offset of the tap inside the wave's staged slice for pixel (0,0) of the tile).
+// A (group, chunk) stream longer than the kernel's buffer makes the variant unusable for
+// these weights (CADNN_EUNSUPPORTED).
+static cadnn_status build_stile_plan(const cadnn_weights* w, const ConvVariant* v, ConvPlan* plan) {
+    const int G = v->rpw;
+    const int rows_padded = (w->cout + G - 1) / G * G;
+    const int ngroups = rows_padded / G;
+    const int nchunks = (w->cin + v->cch - 1) / v->cch;
+    const int taps = w->kh * w->kw;
+    std::vector<int32_t> seg((size_t)ngroups * nchunks * (G + 1), 0);
+    std::vector<int32_t> perm(rows_padded, -1);
+    std::vector<uint2> nz;
+    nz.reserve((size_t)w->nnz + (size_t)rows_padded * nchunks + 16);
+    std::vector<int32_t> cur(G), end(G);
+    for (int g = 0; g < ngroups; ++g) {
+        for (int r = 0; r < G; ++r) {
+            const int i = g * G + r;
+            if (i < w->cout) perm[i] = w->perm[i];
+            cur[r] = i < w->cout ? w->row_ptr[i] : 0;
+            end[r] = i < w->cout ? w->row_ptr[i + 1] : 0;
+        }
+        for (int c = 0; c < nchunks; ++c) {
+            int32_t* sp = &seg[((size_t)g * nchunks + c) * (G + 1)];
+            const size_t start = nz.size();
+            const int32_t k_end = (int32_t)std::min<int64_t>((int64_t)(c + 1) * v->cch, w->cin) * taps;
+            for (int r = 0; r < G; ++r) {
+                sp[r] = (int32_t)nz.size();
+                while (cur[r] < end[r] && w->col_idx[cur[r]] < k_end) {
+                    const int32_t k = w->col_idx[cur[r]];
+                    const int ci = k / taps - c * v->cch;
+                    const int tr = (k % taps) / w->kw, tc = k % w->kw;
+                    const int lrow = (tr % v->stride) * v->rh + tr / v->stride;
+                    const int lcol = (tc % v->stride) * v->cw + tc / v->stride;
+                    const uint32_t off = (uint32_t)((ci * v->plane + lrow * v->pitch + lcol) * 4);
+                    uint32_t bits;
+                    std::memcpy(&bits, &w->vals[cur[r]], 4);
+                    nz.push_back(make_uint2(bits, off));
+                    ++cur[r];
+                }
+                while (nz.size() % (size_t)v->unroll) nz.push_back(make_uint2(0u, 0u));
+            }
+            sp[G] = (int32_t)nz.size();
+            if (nz.size() - start > (size_t)v->nz_cap)
+                return fail(CADNN_EUNSUPPORTED, "%s: %zu nonzeros in one (row group, channel chunk), buffer holds %d",
+                            v->name, nz.size() - start, v->nz_cap);
+        }
+    }
+    if (nz.size() > (size_t)INT32_MAX) return fail(CADNN_EUNSUPPORTED, "plan too large");
+    plan->variant = v;
+    plan->nchunks = nchunks;
+    plan->rows_padded = rows_padded;
+    plan->nz_padded = (int64_t)nz.size();
+    cadnn_status st;
+    if ((st = plan->nz.upload(nz.data(), nz.size() * sizeof(uint2))) != CADNN_OK) return st;
+    if ((st = plan->seg_ptr.upload(seg.data(), seg.size() * 4)) != CADNN_OK) return st;
+    if ((st = plan->perm.upload(perm.data(), perm.size() * 4)) != CADNN_OK) return st;
+    return CADNN_OK;
+}
+
 // Plan of the dense fallback: the unpacked [cout][K] matrix in the storage type.
 static cadnn_status build_dense_plan(const cadnn_weights* w, const ConvVariant* v, ConvPlan* plan) {
     const size_t K = (size_t)w->cin * w->kh * w->kw;
@@ -282,6 +347,7 @@ static cadnn_status build_plan(const cadnn_weights* w, const ConvVariant* v, con
                                ConvPlan* plan) {
     switch (v->family) {
         case FAM_DENSE: return build_dense_plan(w, v, plan);
+        case FAM_STILE: return build_stile_plan(w, v, plan);
         case FAM_DIRECT: return build_direct_plan(w, v, plan);
         case FAM_LINEAR: return build_linear_plan(w, v, xd, plan);
         default: return build_tile_plan(w, v, plan);
