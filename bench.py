@@ -69,6 +69,8 @@ def main() -> int:
     ap.add_argument("--no-tune", action="store_true")
     ap.add_argument("--save-tune", type=str, default="", help="write the tuned variant names (JSON)")
     ap.add_argument("--load-tune", type=str, default="", help="pin saved variant names instead of tuning")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a 256 MiB device copy 10 times (known traffic, for counter calibration)")
     ap.add_argument("--no-layer-profile", action="store_true",
                     help="skip the per-op event pass (for clean rocprofv3 kernel statistics)")
     args = ap.parse_args()
@@ -121,6 +123,13 @@ def main() -> int:
     lat_sync_ms = float(np.median(lat))
 
     # ---- per-op device time with HIP events on the launch stream, grouped by kernel
+    if args.calibrate_copy:
+        a_ = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+        b_ = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+        a_.zero_()
+        for _ in range(10):
+            cad.cadnn_device_copy(a_, b_, stream)
+        torch.cuda.synchronize()
     if args.save_tune:
         with open(args.save_tune, "w") as f:
             json.dump({"workload": "resnet50-c2-f32-n1", "variants": net.variants()}, f, indent=1)

@@ -142,6 +142,11 @@ cadnn_status cadnn_maxpool2d(const void* x, void* y, int n, int c, int h, int wd
 cadnn_status cadnn_global_avgpool(const void* x, void* y, int n, int c, int h, int wdt,
                                   cadnn_dtype dtype, void* stream);
 
+/* Measurement aid, not part of the paper's method: a plain device-to-device streaming copy
+ * of `bytes` bytes (a multiple of 16; 16-byte aligned pointers), whose memory traffic is
+ * known exactly and against which hardware traffic counters are calibrated. */
+cadnn_status cadnn_device_copy(const void* src, void* dst, size_t bytes, void* stream);
+
 /* Dense comparator on the same ABI (implicit-GEMM convolution over the dense
  * [cout][cin][kh][kw] DEVICE weight tensor, same fused epilogue), used for the
  * dense-vs-compressed comparison the paper reports (Section 5) and as the
@@ -194,6 +199,9 @@ cadnn_status cadnn_net_profile(cadnn_net* net, const void* x, void* y, void* str
 /* Name of the kernel serving op `op_index` (a conv variant name, "sfc", "maxpool" or
  * "avgpool"), NUL-terminated into buf. */
 cadnn_status cadnn_net_op_variant(const cadnn_net* net, int op_index, char* buf, size_t len);
+/* Newline-separated names of the variants that can serve convolution op `op_index` in
+ * the layout the net gave its input (a halo opens the linear-address kernels to 3x3). */
+cadnn_status cadnn_net_op_candidates(const cadnn_net* net, int op_index, char* buf, size_t len);
 /* Pins the kernel variant of convolution op `op_index` by name (as reported by
  * cadnn_net_op_variant after tuning), e.g. to replay a saved tuning result.  NULL or ""
  * returns the op to the built-in heuristic.  The net must be finalized. */

@@ -62,6 +62,7 @@ def lib() -> ctypes.CDLL:
         "cadnn_conv2d_set_variant": (_i, [_vp, _i, _i, _i, _i, _i, ctypes.c_char_p]),
         "cadnn_sparse_fc": (_i, [_vp, _vp, _vp, _i, _vp, _i, _vp]),
         "cadnn_fc_prepare": (_i, [_vp]),
+        "cadnn_device_copy": (_i, [_vp, _vp, ctypes.c_size_t, _vp]),
         "cadnn_maxpool2d": (_i, [_vp, _vp, _i, _i, _i, _i, _i, _i, _i, _i, _vp]),
         "cadnn_global_avgpool": (_i, [_vp, _vp, _i, _i, _i, _i, _i, _vp]),
         "cadnn_dense_conv2d": (_i, [_vp, _vp, _vp] + [_i] * 9 + [_vp, _vp, _i, _i, _vp]),
@@ -76,6 +77,7 @@ def lib() -> ctypes.CDLL:
         "cadnn_net_num_ops": (_i, [_vp, ctypes.POINTER(_i)]),
         "cadnn_net_profile": (_i, [_vp, _vp, _vp, _vp, _i, _f32p]),
         "cadnn_net_op_variant": (_i, [_vp, _i, ctypes.c_char_p, ctypes.c_size_t]),
+        "cadnn_net_op_candidates": (_i, [_vp, _i, ctypes.c_char_p, ctypes.c_size_t]),
         "cadnn_net_set_op_variant": (_i, [_vp, _i, ctypes.c_char_p]),
         "cadnn_net_read_buffer": (_i, [_vp, _i, _vp, ctypes.c_size_t, _vp]),
         "cadnn_net_free": (_i, [_vp]),
@@ -244,6 +246,13 @@ def cadnn_fc_prepare(w: Weights) -> None:
     _check(lib().cadnn_fc_prepare(w.handle))
 
 
+def cadnn_device_copy(src, dst, stream=None) -> None:
+    assert src.is_cuda and dst.is_cuda and src.is_contiguous() and dst.is_contiguous()
+    nbytes = src.numel() * src.element_size()
+    assert nbytes == dst.numel() * dst.element_size()
+    _check(lib().cadnn_device_copy(_dptr(src), _dptr(dst), nbytes, _stream_ptr(stream)))
+
+
 def cadnn_maxpool2d(x, k: int, stride: int, pad: int, stream=None):
     import torch
     assert x.is_cuda and x.is_contiguous()
@@ -318,6 +327,12 @@ class Net:
         buf = ctypes.create_string_buffer(256)
         _check(lib().cadnn_net_op_variant(self.handle, op_index, buf, 256))
         return buf.value.decode()
+
+    def op_candidates(self, op_index: int) -> List[str]:
+        buf = ctypes.create_string_buffer(1 << 16)
+        _check(lib().cadnn_net_op_candidates(self.handle, op_index, buf, 1 << 16))
+        text = buf.value.decode()
+        return text.split("\n") if text else []
 
     def set_op_variant(self, op_index: int, name: Optional[str]) -> None:
         _check(lib().cadnn_net_set_op_variant(self.handle, op_index, None if not name else name.encode()))

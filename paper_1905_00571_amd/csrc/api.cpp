@@ -40,6 +40,7 @@ static bool variant_fits(const ConvVariant& v, const cadnn_weights* w, const Con
     if (v.family == FAM_DENSE)
         return (double)w->nnz >= 0.25 * (double)w->cout * w->cin * w->kh * w->kw;
     if (v.family == FAM_LINEAR) {
+        if (v.adjacent && (g.stride != 1 || g.wout % v.p != 0)) return false;
         // 1x1 filters read only the image proper; larger filters need the zero halo
         if (w->kh == 1 && w->kw == 1) return g.pad == 0;
         return g.xd.ph >= g.pad && g.xd.pw >= g.pad;
@@ -192,6 +193,22 @@ const char* conv2d_variant_name_impl(const cadnn_weights* w, const TensorDesc& x
     return v->name;
 }
 
+cadnn_status conv2d_list_variants_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad,
+                                       char* buf, size_t len) {
+    if (!buf || len == 0) return fail(CADNN_EINVAL, "cadnn_conv2d_list_variants: NULL buffer");
+    ConvGeom g;
+    cadnn_status st = check_conv("cadnn_conv2d_list_variants", w, xd, n, stride, pad, &g);
+    if (st != CADNN_OK) return st;
+    std::string all;
+    for (const ConvVariant* v : candidates(w, g)) {
+        if (!all.empty()) all += "\n";
+        all += v->name;
+    }
+    if (all.size() + 1 > len) return fail(CADNN_EINVAL, "cadnn_conv2d_list_variants: buffer of %zu bytes, %zu needed", len, all.size() + 1);
+    std::memcpy(buf, all.c_str(), all.size() + 1);
+    return CADNN_OK;
+}
+
 cadnn_status conv2d_set_variant_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad,
                                      const char* name) {
     ConvGeom g;
@@ -305,18 +322,7 @@ extern "C" cadnn_status cadnn_conv2d_variant_name(const cadnn_weights* w, int n,
 
 extern "C" cadnn_status cadnn_conv2d_list_variants(const cadnn_weights* w, int n, int h, int wdt,
                                                    int stride, int pad, char* buf, size_t len) {
-    if (!buf || len == 0) return fail(CADNN_EINVAL, "cadnn_conv2d_list_variants: NULL buffer");
-    ConvGeom g;
-    cadnn_status st = check_conv("cadnn_conv2d_list_variants", w, make_desc(w ? w->cin : 0, h, wdt), n, stride, pad, &g);
-    if (st != CADNN_OK) return st;
-    std::string all;
-    for (const ConvVariant* v : candidates(w, g)) {
-        if (!all.empty()) all += "\n";
-        all += v->name;
-    }
-    if (all.size() + 1 > len) return fail(CADNN_EINVAL, "cadnn_conv2d_list_variants: buffer of %zu bytes, %zu needed", len, all.size() + 1);
-    std::memcpy(buf, all.c_str(), all.size() + 1);
-    return CADNN_OK;
+    return conv2d_list_variants_impl(w, make_desc(w ? w->cin : 0, h, wdt), n, stride, pad, buf, len);
 }
 
 extern "C" cadnn_status cadnn_conv2d_set_variant(const cadnn_weights* w, int n, int h, int wdt,
@@ -340,6 +346,12 @@ extern "C" cadnn_status cadnn_fc_prepare(const cadnn_weights* w) {
     if (!w) return fail(CADNN_EINVAL, "cadnn_fc_prepare: NULL handle");
     if (w->kh != 1 || w->kw != 1) return fail(CADNN_EINVAL, "cadnn_fc_prepare: weights are not a matrix");
     return ensure_fc_device(w);
+}
+
+extern "C" cadnn_status cadnn_device_copy(const void* src, void* dst, size_t bytes, void* stream) {
+    if (!src || !dst) return fail(CADNN_EINVAL, "cadnn_device_copy: NULL pointer");
+    if (bytes % 16) return fail(CADNN_EINVAL, "cadnn_device_copy: size must be a multiple of 16 bytes");
+    return launch_copy(src, dst, bytes, (hipStream_t)stream);
 }
 
 extern "C" cadnn_status cadnn_maxpool2d(const void* x, void* y, int n, int c, int h, int wdt, int k,

@@ -25,10 +25,14 @@ namespace cadnn {
 
 constexpr uint32_t kLinOutOfRange = 0x7ffffff0u;   // beyond any buffer this library accepts
 
-template <typename T_, int P_, int RPW_, int KS_, int NW_, int U_>
+// ADJ = 0: the P pixels of a lane are 64 apart (P wave-wide loads of one element each);
+// ADJ = 1: they are P adjacent pixels of one output row fetched with ONE P-element load
+//          (stride-1 layers whose output width is a multiple of P): fewer, wider loads and
+//          fewer cache lines touched per useful byte.
+template <typename T_, int P_, int RPW_, int KS_, int NW_, int U_, int ADJ_ = 0>
 struct LinearCfg {
     using T = T_;
-    static constexpr int P = P_, RPW = RPW_, KS = KS_, NW = NW_, U = U_;
+    static constexpr int P = P_, RPW = RPW_, KS = KS_, NW = NW_, U = U_, ADJ = ADJ_;
     static constexpr int RG = NW / KS;
     static constexpr int THREADS = NW * 64;
     static_assert(NW % KS == 0, "KS must divide the waves of a workgroup");
@@ -78,10 +82,41 @@ __device__ __forceinline__ float lin_load<_Float16>(__amdgpu_buffer_rsrc_t r, ui
     return (float)__builtin_bit_cast(_Float16, h);
 }
 
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+
+// Activations of one nonzero for the P pixels of a lane.
+template <typename T, int P, int ADJ>
+__device__ __forceinline__ void lin_fetch(__amdgpu_buffer_rsrc_t r, const uint32_t (&voff)[P], uint32_t soff,
+                                          float (&x)[P]) {
+    if constexpr (ADJ == 0 || P == 1) {
+#pragma unroll
+        for (int j = 0; j < P; ++j) x[j] = lin_load<T>(r, voff[j], soff);
+    } else if constexpr (sizeof(T) == 4 && P == 2) {
+        const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(r, voff[0], soff, 0);
+        x[0] = __uint_as_float(v[0]); x[1] = __uint_as_float(v[1]);
+    } else if constexpr (sizeof(T) == 4 && P == 4) {
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, voff[0], soff, 0);
+        x[0] = __uint_as_float(v[0]); x[1] = __uint_as_float(v[1]);
+        x[2] = __uint_as_float(v[2]); x[3] = __uint_as_float(v[3]);
+    } else if constexpr (sizeof(T) == 2 && P == 2) {
+        const uint32_t v = __builtin_amdgcn_raw_buffer_load_b32(r, voff[0], soff, 0);
+        const f16x2 h = __builtin_bit_cast(f16x2, v);
+        x[0] = (float)h[0]; x[1] = (float)h[1];
+    } else {
+        static_assert(sizeof(T) == 2 && P == 4, "unsupported adjacent-pixel width");
+        const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(r, voff[0], soff, 0);
+        const f16x4 h = __builtin_bit_cast(f16x4, v);
+        x[0] = (float)h[0]; x[1] = (float)h[1]; x[2] = (float)h[2]; x[3] = (float)h[3];
+    }
+}
+
 template <class Cfg>
 __global__ __launch_bounds__(Cfg::THREADS) void sconv_linear_kernel(const ConvLaunch a) {
     using T = typename Cfg::T;
-    constexpr int P = Cfg::P, RPW = Cfg::RPW, KS = Cfg::KS, RG = Cfg::RG, U = Cfg::U;
+    constexpr int P = Cfg::P, RPW = Cfg::RPW, KS = Cfg::KS, RG = Cfg::RG, U = Cfg::U, ADJ = Cfg::ADJ;
     __shared__ float red[KS > 1 ? Cfg::NW * RPW * P * 64 : 1];
 
     const int lane = threadIdx.x & 63;
@@ -97,7 +132,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_linear_kernel(const ConvLa
     const int base = a.xd.origin - a.pad * a.xd.pitch - a.pad;
 #pragma unroll
     for (int j = 0; j < P; ++j) {
-        const int q = q0 + j * 64 + lane;
+        const int q = ADJ ? q0 + lane * P + j : q0 + j * 64 + lane;
         const int oh = q / a.yd.w, ow = q - oh * a.yd.w;
         oidx[j] = q < a.hwout ? oh * a.yd.pitch + ow : -1;
         voff[j] = q < a.hwout
@@ -130,8 +165,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_linear_kernel(const ConvLa
         win.group<U>(i, wa, oa);
 #pragma unroll
         for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int j = 0; j < P; ++j) xa[u][j] = lin_load<T>(rsrc, voff[j], oa[u]);
+            lin_fetch<T, P, ADJ>(rsrc, voff, oa[u], xa[u]);
         while (true) {
             if (groups == 1) {
 #pragma unroll
@@ -143,8 +177,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_linear_kernel(const ConvLa
             win.group<U>(i + U, wb, ob);
 #pragma unroll
             for (int u = 0; u < U; ++u)
-#pragma unroll
-                for (int j = 0; j < P; ++j) xb[u][j] = lin_load<T>(rsrc, voff[j], ob[u]);
+                lin_fetch<T, P, ADJ>(rsrc, voff, ob[u], xb[u]);
 #pragma unroll
             for (int u = 0; u < U; ++u)
 #pragma unroll
@@ -159,8 +192,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_linear_kernel(const ConvLa
             win.group<U>(i + 2 * U, wa, oa);
 #pragma unroll
             for (int u = 0; u < U; ++u)
-#pragma unroll
-                for (int j = 0; j < P; ++j) xa[u][j] = lin_load<T>(rsrc, voff[j], oa[u]);
+                lin_fetch<T, P, ADJ>(rsrc, voff, oa[u], xa[u]);
 #pragma unroll
             for (int u = 0; u < U; ++u)
 #pragma unroll
@@ -195,7 +227,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_linear_kernel(const ConvLa
     int ridx[P];
 #pragma unroll
     for (int j = 0; j < P; ++j) {
-        const int q = q0 + j * 64 + lane;
+        const int q = ADJ ? q0 + lane * P + j : q0 + j * 64 + lane;
         const int oh = q / a.yd.w, ow = q - oh * a.yd.w;
         ridx[j] = oh * a.rd.pitch + ow;
     }
@@ -233,6 +265,7 @@ static ConvVariant make_linear(const char* name) {
     v.kh = 0; v.kw = 0; v.stride = 0;
     v.p = Cfg::P; v.nw = Cfg::NW; v.rpw = Cfg::RPW; v.ks = Cfg::KS;
     v.unroll = Cfg::U;
+    v.adjacent = Cfg::ADJ;
     v.lds_bytes = Cfg::KS > 1 ? (size_t)Cfg::NW * Cfg::RPW * Cfg::P * 64 * 4 : 0;
     v.launch = &launch_linear<Cfg>;
     return v;
@@ -241,9 +274,30 @@ static ConvVariant make_linear(const char* name) {
 #define CADNN_LINEAR(T, P, RPW, KS, NW, U) \
     make_linear<LinearCfg<T, P, RPW, KS, NW, U>>("slinear_" #T "_p" #P "_r" #RPW "k" #KS "w" #NW "u" #U)
 
+#define CADNN_LINEAR_ADJ(T, P, RPW, KS, NW, U) \
+    make_linear<LinearCfg<T, P, RPW, KS, NW, U, 1>>("slinear_" #T "_a" #P "_r" #RPW "k" #KS "w" #NW "u" #U)
+
 #define CADNN_LINEAR_SHAPES(T)          \
+    CADNN_LINEAR_ADJ(T, 2, 1, 1, 4, 4), \
+    CADNN_LINEAR_ADJ(T, 2, 1, 2, 4, 4), \
+    CADNN_LINEAR_ADJ(T, 2, 1, 4, 4, 4), \
+    CADNN_LINEAR_ADJ(T, 2, 1, 4, 4, 8), \
+    CADNN_LINEAR_ADJ(T, 2, 1, 8, 8, 4), \
+    CADNN_LINEAR_ADJ(T, 2, 2, 1, 4, 4), \
+    CADNN_LINEAR_ADJ(T, 4, 1, 1, 4, 4), \
+    CADNN_LINEAR_ADJ(T, 4, 1, 2, 4, 4), \
+    CADNN_LINEAR_ADJ(T, 4, 1, 4, 4, 4), \
+    CADNN_LINEAR_ADJ(T, 4, 1, 8, 8, 4), \
+    CADNN_LINEAR_ADJ(T, 4, 2, 1, 4, 4), \
+    CADNN_LINEAR_ADJ(T, 4, 1, 16, 16, 4), \
     CADNN_LINEAR(T, 1, 1, 1, 4, 4),     \
     CADNN_LINEAR(T, 1, 1, 1, 4, 8),     \
+    CADNN_LINEAR(T, 1, 1, 1, 4, 16),    \
+    CADNN_LINEAR(T, 1, 1, 2, 4, 16),    \
+    CADNN_LINEAR(T, 1, 1, 4, 4, 16),    \
+    CADNN_LINEAR(T, 1, 1, 8, 8, 16),    \
+    CADNN_LINEAR(T, 2, 1, 4, 4, 8),     \
+    CADNN_LINEAR(T, 2, 1, 2, 4, 8),     \
     CADNN_LINEAR(T, 1, 2, 1, 4, 4),     \
     CADNN_LINEAR(T, 1, 2, 1, 4, 8),     \
     CADNN_LINEAR(T, 1, 4, 1, 4, 4),     \

@@ -49,7 +49,7 @@ constexpr int spitch(int need, int tw) {
     return need;
 }
 
-template <typename T_, int KH_, int KW_, int S_, int TW_, int P_, int NW_, int G_, int CCH_>
+template <typename T_, int KH_, int KW_, int S_, int TW_, int P_, int NW_, int G_, int CCH_, int CF_>
 struct StileCfg {
     using T = T_;
     static constexpr int KH = KH_, KW = KW_, S = S_, TW = TW_, P = P_, NW = NW_, G = G_, CCH = CCH_;
@@ -59,27 +59,52 @@ struct StileCfg {
     static constexpr int RH = TH + (KH - 1) / S;
     static constexpr int NPH = smin(S, KW);
     static constexpr int CW = TW + (KW - 1) / S;
-    static constexpr int PITCH = spitch(NPH * CW, TW);
+    // CF = 1 pads the pitch until lane rows fall into disjoint banks; CF = 0 keeps the tile
+    // compact (small images: more channels per slice at the price of 2-way conflicts)
+    static constexpr int PITCH = CF_ ? spitch(NPH * CW, TW) : NPH * CW;
     static constexpr int PLANE = NRPH * RH * PITCH;
     static constexpr int NSTP = (PLANE + 63) / 64;          // staging instructions per channel
     static constexpr int PLANE_PAD = NSTP * 64;
     static constexpr int SLICE_BYTES = CCH * PLANE_PAD * 4;
     // nonzero-stream entries a wave buffers per (G rows, chunk): never more than the dense
     // count (+ segment padding); layers whose streams exceed the cap are not served
-    static constexpr int CAP = smin(1024, (G * (CCH * KH * KW + 2) + 1) / 2 * 2);
-    static constexpr int NZ_BYTES = CAP * 8;
+    static constexpr int CAP = smin(1024, (G * (CCH * KH * KW + 4) + 3) / 4 * 4);
+    static constexpr int NZ_BYTES = ((CAP + 63) / 64 * 64 + 8) * 8;   // whole lanes + read-ahead slack
     static constexpr int RED_BYTES = G * P * 64 * 4;
     static constexpr int WAVE_BYTES = smax(SLICE_BYTES + NZ_BYTES, RED_BYTES);
     static constexpr int LDS_BYTES = NW * WAVE_BYTES;
     static constexpr int THREADS = NW * 64;
     static_assert(64 % TW == 0, "TW must divide the wavefront");
-    static_assert(G % NW == 0, "rows are finished NW waves at a time");
     static_assert(LDS_BYTES <= 160 * 1024, "beyond the LDS of a compute unit");
 };
 
 constexpr uint32_t kStileOob = 0x7ffffff0u;
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
+// Four nonzeros (two broadcast 128-bit pairs) against the P pixels of a lane.
+template <int P, int STEP>
+__device__ __forceinline__ void stile_fma4(float (&acc)[P], const char* lane_ptr, const uint4& q0, const uint4& q1) {
+    const char* l0 = lane_ptr + q0.y;
+    const char* l1 = lane_ptr + q0.w;
+    const char* l2 = lane_ptr + q1.y;
+    const char* l3 = lane_ptr + q1.w;
+    float x0[P], x1[P], x2[P], x3[P];
+#pragma unroll
+    for (int j = 0; j < P; ++j) {
+        x0[j] = *(const float*)(l0 + j * STEP);
+        x1[j] = *(const float*)(l1 + j * STEP);
+        x2[j] = *(const float*)(l2 + j * STEP);
+        x3[j] = *(const float*)(l3 + j * STEP);
+    }
+#pragma unroll
+    for (int j = 0; j < P; ++j) {
+        acc[j] = fmaf(__uint_as_float(q0.x), x0[j], acc[j]);
+        acc[j] = fmaf(__uint_as_float(q0.z), x1[j], acc[j]);
+        acc[j] = fmaf(__uint_as_float(q1.x), x2[j], acc[j]);
+        acc[j] = fmaf(__uint_as_float(q1.z), x3[j], acc[j]);
+    }
+}
 
 template <class Cfg>
 __global__ __launch_bounds__(Cfg::THREADS) void sconv_stile_kernel(const ConvLaunch a) {
@@ -130,12 +155,46 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_stile_kernel(const ConvLau
 #pragma unroll
         for (int j = 0; j < P; ++j) acc[r][j] = 0.0f;
 
+    constexpr int NZR = (Cfg::CAP + 63) / 64;        // stream entries a lane carries per chunk
+    // The nonzero stream of the wave's NEXT chunk is fetched into registers while the
+    // current chunk is staged and consumed, so a chunk exposes one memory latency (its
+    // staging), not three (segment table, stream, staging).
+    uint2 nzr[NZR];
+    int myseg = 0;
+    if (wv < a.nchunks) {
+        myseg = seg_grp[(size_t)wv * (G + 1) + (lane < G ? lane : G)];
+        const int sb0 = __builtin_amdgcn_readlane(myseg, 0), se0 = __builtin_amdgcn_readlane(myseg, G);
+#pragma unroll
+        for (int k = 0; k < NZR; ++k) {
+            const int i = sb0 + k * 64 + lane;
+            nzr[k] = i < se0 ? nz[i] : make_uint2(0u, 0u);
+        }
+    }
+
     for (int c = wv; c < a.nchunks; c += NW) {
-        const int32_t* __restrict__ seg = seg_grp + (size_t)c * (G + 1);
-        const int sb = seg[0], se = seg[G];
-        if (sb == se) continue;                       // none of the G rows touches this chunk
+        // segment table of this (group, chunk), broadcast lane by lane
+        int sg[G + 1];
+#pragma unroll
+        for (int r = 0; r <= G; ++r) sg[r] = __builtin_amdgcn_readlane(myseg, r);
+        const int sb = sg[0], se = sg[G];
         // everything this wave read from its slice for the previous chunk has been consumed
         __builtin_amdgcn_wave_barrier();
+        // ---- the chunk's nonzero stream goes next to the tile
+#pragma unroll
+        for (int k = 0; k < NZR; ++k)
+            if (k * 64 < se - sb) nzbuf[k * 64 + lane] = nzr[k];
+        // ---- fetch the next chunk's table and stream
+        const int cn = c + NW;
+        if (cn < a.nchunks) {
+            myseg = seg_grp[(size_t)cn * (G + 1) + (lane < G ? lane : G)];
+            const int sbn = __builtin_amdgcn_readlane(myseg, 0), sen = __builtin_amdgcn_readlane(myseg, G);
+#pragma unroll
+            for (int k = 0; k < NZR; ++k) {
+                const int i = sbn + k * 64 + lane;
+                nzr[k] = i < sen ? nz[i] : make_uint2(0u, 0u);
+            }
+        }
+        if (sb == se) continue;                       // none of the G rows touches this chunk
         const int c0 = c * CCH;
         const int nch = smin(CCH, cin - c0);
         const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
@@ -155,25 +214,25 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_stile_kernel(const ConvLau
                 }
             }
         }
-        // ---- copy the nonzero stream of the G rows for this chunk next to the tile
-        for (int i = sb + lane; i < se; i += 64) nzbuf[i - sb] = nz[i];
         asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_wave_barrier();
-        // ---- accumulate: two (value, offset) pairs per broadcast read
+        // ---- accumulate.  Runs are padded to four entries; two register sets take turns so
+        //      the (value, offset) pairs of the next four are in flight while these are used.
 #pragma unroll
         for (int r = 0; r < G; ++r) {
-            const uint4* p4 = (const uint4*)(nzbuf + (seg[r] - sb));
-            const uint4* e4 = (const uint4*)(nzbuf + (seg[r + 1] - sb));
-            for (; p4 < e4; ++p4) {
-                const uint4 pr = *p4;
-                const float w0 = __uint_as_float(pr.x), w1 = __uint_as_float(pr.z);
-                const char* l0 = lane_ptr + pr.y;
-                const char* l1 = lane_ptr + pr.w;
-#pragma unroll
-                for (int j = 0; j < P; ++j) {
-                    acc[r][j] = fmaf(w0, *(const float*)(l0 + j * RW * PITCH * 4), acc[r][j]);
-                    acc[r][j] = fmaf(w1, *(const float*)(l1 + j * RW * PITCH * 4), acc[r][j]);
-                }
+            const uint4* p4 = (const uint4*)(nzbuf + (sg[r] - sb));
+            int groups = (sg[r + 1] - sg[r]) >> 2;
+            if (groups == 0) continue;
+            uint4 a0 = p4[0], a1 = p4[1], b0, b1;
+            while (true) {
+                b0 = p4[2]; b1 = p4[3];               // next four (stays inside the buffer's slack)
+                stile_fma4<P, RW * PITCH * 4>(acc[r], lane_ptr, a0, a1);
+                if (groups == 1) break;
+                a0 = p4[4]; a1 = p4[5];
+                stile_fma4<P, RW * PITCH * 4>(acc[r], lane_ptr, b0, b1);
+                if (groups == 2) break;
+                groups -= 2;
+                p4 += 4;
             }
         }
     }
@@ -190,10 +249,11 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_stile_kernel(const ConvLau
     const int ow = ow0 + tx;
     T* __restrict__ y = (T*)a.y + (size_t)n * a.yd.image + a.yd.origin;
     const T* __restrict__ res = a.residual ? (const T*)a.residual + (size_t)n * a.rd.image + a.rd.origin : nullptr;
-    constexpr int RPF = G / NW;
+    constexpr int RPF = (G + NW - 1) / NW;          // rows finished per wave
 #pragma unroll
     for (int rr = 0; rr < RPF; ++rr) {
         const int r = wv * RPF + rr;
+        if (r >= G) break;
         const int co = a.perm[grp * G + r];
         if (co < 0) continue;
         const float b = a.bias ? a.bias[co] : 0.0f;
@@ -240,7 +300,7 @@ ConvVariant make_stile(const char* name) {
     v.th = Cfg::TH; v.rh = Cfg::RH; v.nrph = Cfg::NRPH; v.cw = Cfg::CW; v.nph = Cfg::NPH;
     v.pitch = Cfg::PITCH; v.plane = Cfg::PLANE_PAD;
     v.elem_bytes = 4;
-    v.unroll = 2;
+    v.unroll = 4;
     v.nz_cap = Cfg::CAP;
     v.lds_bytes = Cfg::LDS_BYTES;
     v.launch = &launch_stile<Cfg>;
@@ -249,43 +309,46 @@ ConvVariant make_stile(const char* name) {
 
 }  // namespace
 
-#define CADNN_STILE(T, KH, KW, S, TW, P, NW, G, CCH) \
-    make_stile<StileCfg<T, KH, KW, S, TW, P, NW, G, CCH>>( \
-        "stile_" #T "_k" #KH "x" #KW "s" #S "_t" #TW "p" #P "_w" #NW "g" #G "c" #CCH)
+#define CADNN_STILE(T, KH, KW, S, TW, P, NW, G, CCH, CF) \
+    make_stile<StileCfg<T, KH, KW, S, TW, P, NW, G, CCH, CF>>( \
+        "stile_" #T "_k" #KH "x" #KW "s" #S "_t" #TW "p" #P "_w" #NW "g" #G "c" #CCH "f" #CF)
 
-#define CADNN_STILE_SHAPES(T)                       \
-    /* 3x3 stride 1 */                              \
-    CADNN_STILE(T, 3, 3, 1, 32, 4, 4, 4, 8),        \
-    CADNN_STILE(T, 3, 3, 1, 32, 2, 4, 8, 8),        \
-    CADNN_STILE(T, 3, 3, 1, 32, 2, 4, 4, 8),        \
-    CADNN_STILE(T, 3, 3, 1, 16, 4, 4, 4, 8),        \
-    CADNN_STILE(T, 3, 3, 1, 16, 4, 8, 8, 2),        \
-    CADNN_STILE(T, 3, 3, 1, 16, 2, 4, 8, 8),        \
-    CADNN_STILE(T, 3, 3, 1, 8, 1, 4, 16, 16),       \
-    CADNN_STILE(T, 3, 3, 1, 8, 1, 4, 8, 16),        \
-    CADNN_STILE(T, 3, 3, 1, 8, 1, 8, 8, 8),         \
-    CADNN_STILE(T, 3, 3, 1, 8, 1, 8, 16, 8),        \
-    /* 3x3 stride 2 */                              \
-    CADNN_STILE(T, 3, 3, 2, 32, 2, 4, 8, 4),        \
-    CADNN_STILE(T, 3, 3, 2, 32, 2, 4, 4, 4),        \
-    CADNN_STILE(T, 3, 3, 2, 16, 2, 4, 8, 4),        \
-    CADNN_STILE(T, 3, 3, 2, 16, 4, 4, 4, 4),        \
-    CADNN_STILE(T, 3, 3, 2, 8, 1, 4, 16, 8),        \
-    CADNN_STILE(T, 3, 3, 2, 8, 1, 8, 8, 8),         \
-    /* 1x1 stride 2 (projection shortcuts) */       \
-    CADNN_STILE(T, 1, 1, 2, 32, 2, 4, 8, 32),       \
-    CADNN_STILE(T, 1, 1, 2, 16, 4, 4, 8, 16),       \
-    CADNN_STILE(T, 1, 1, 2, 16, 4, 8, 8, 16),       \
-    CADNN_STILE(T, 1, 1, 2, 8, 1, 8, 16, 32),       \
-    CADNN_STILE(T, 1, 1, 2, 8, 1, 4, 8, 32),        \
-    /* 1x1 stride 1 */                              \
-    CADNN_STILE(T, 1, 1, 1, 32, 2, 4, 8, 32),       \
-    CADNN_STILE(T, 1, 1, 1, 16, 4, 4, 8, 16),       \
-    CADNN_STILE(T, 1, 1, 1, 16, 4, 8, 8, 16),       \
-    CADNN_STILE(T, 1, 1, 1, 8, 1, 8, 16, 32),       \
-    /* 7x7 stride 2 */                              \
-    CADNN_STILE(T, 7, 7, 2, 32, 4, 4, 4, 1),        \
-    CADNN_STILE(T, 7, 7, 2, 32, 2, 4, 8, 1)
+#define CADNN_STILE_SHAPES(T)                          \
+    /* 3x3 stride 1: 56x56 / 28x28 images */           \
+    CADNN_STILE(T, 3, 3, 1, 32, 4, 8, 8, 8, 1),        \
+    CADNN_STILE(T, 3, 3, 1, 32, 2, 8, 8, 8, 1),        \
+    CADNN_STILE(T, 3, 3, 1, 8, 1, 8, 16, 8, 1),        \
+    CADNN_STILE(T, 3, 3, 1, 8, 1, 8, 8, 8, 1),         \
+    CADNN_STILE(T, 3, 3, 1, 8, 1, 16, 16, 4, 1),       \
+    /* 3x3 stride 1: whole 14x14 / 7x7 image per tile */ \
+    CADNN_STILE(T, 3, 3, 1, 16, 4, 8, 8, 8, 0),        \
+    CADNN_STILE(T, 3, 3, 1, 16, 4, 8, 8, 4, 1),        \
+    CADNN_STILE(T, 3, 3, 1, 8, 1, 8, 8, 16, 0),        \
+    CADNN_STILE(T, 3, 3, 1, 8, 1, 16, 16, 4, 0),       \
+    CADNN_STILE(T, 3, 3, 1, 8, 1, 8, 2, 24, 0),        \
+    CADNN_STILE(T, 3, 3, 1, 8, 1, 4, 2, 32, 0),        \
+    CADNN_STILE(T, 3, 3, 1, 8, 1, 8, 4, 16, 0),        \
+    CADNN_STILE(T, 3, 3, 1, 16, 4, 8, 1, 8, 0),        \
+    CADNN_STILE(T, 3, 3, 1, 16, 4, 8, 2, 8, 0),        \
+    CADNN_STILE(T, 3, 3, 1, 16, 4, 4, 2, 8, 0),        \
+    /* 3x3 stride 2 */                                 \
+    CADNN_STILE(T, 3, 3, 2, 8, 1, 8, 2, 8, 0),         \
+    CADNN_STILE(T, 3, 3, 2, 16, 4, 8, 2, 2, 0),        \
+    CADNN_STILE(T, 3, 3, 2, 32, 2, 8, 8, 4, 1),        \
+    CADNN_STILE(T, 3, 3, 2, 8, 1, 8, 8, 8, 1),         \
+    CADNN_STILE(T, 3, 3, 2, 16, 4, 8, 8, 2, 0),        \
+    CADNN_STILE(T, 3, 3, 2, 8, 1, 8, 8, 8, 0),         \
+    /* 1x1 stride 2 (projection shortcuts) */          \
+    CADNN_STILE(T, 1, 1, 2, 32, 2, 8, 8, 16, 1),       \
+    CADNN_STILE(T, 1, 1, 2, 16, 4, 8, 8, 16, 1),       \
+    CADNN_STILE(T, 1, 1, 2, 8, 1, 8, 8, 32, 1),        \
+    CADNN_STILE(T, 1, 1, 2, 8, 1, 16, 16, 16, 1),      \
+    /* 1x1 stride 1 */                                 \
+    CADNN_STILE(T, 1, 1, 1, 32, 2, 8, 8, 16, 1),       \
+    CADNN_STILE(T, 1, 1, 1, 16, 4, 8, 8, 16, 1),       \
+    CADNN_STILE(T, 1, 1, 1, 8, 1, 16, 16, 16, 1),      \
+    /* 7x7 stride 2 */                                 \
+    CADNN_STILE(T, 7, 7, 2, 32, 4, 4, 4, 1, 1)
 
 const std::vector<ConvVariant>& all_stile_variants() {
     static const std::vector<ConvVariant> v = {CADNN_STILE_SHAPES(float), CADNN_STILE_SHAPES(_Float16)};

@@ -120,6 +120,7 @@ struct ConvVariant {
     int pitch, plane;     // LDS floats per tile row / per channel
     int elem_bytes;       // size of one staged tile element in LDS
     int unroll;           // nonzeros per scalar fetch; segments are padded to a multiple of it
+    int adjacent;         // FAM_LINEAR: a lane's P pixels are adjacent in one output row (stride 1 only)
     int nz_cap;           // FAM_STILE: most stream entries per (row group, chunk) the kernel buffers
     size_t lds_bytes;
     hipError_t (*launch)(const ConvLaunch&, hipStream_t);
@@ -193,6 +194,7 @@ float f16_to_f32(uint16_t h);
 
 cadnn_status launch_fc(const cadnn_weights* w, const void* x, void* y, int n, const float* bias,
                        int relu, hipStream_t s);
+cadnn_status launch_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
 cadnn_status launch_maxpool(const void* x, const TensorDesc& xd, void* y, const TensorDesc& yd, int n,
                             int k, int stride, int pad, cadnn_dtype dt, hipStream_t s);
 cadnn_status launch_avgpool(const void* x, const TensorDesc& xd, void* y, int n, cadnn_dtype dt,
@@ -208,6 +210,8 @@ cadnn_status conv2d_tune_impl(const cadnn_weights* w, const void* x, const Tenso
                               float* best_us);
 // Name of the variant that would serve the layer (NULL if none).
 const char* conv2d_variant_name_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad);
+cadnn_status conv2d_list_variants_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad,
+                                       char* buf, size_t len);
 cadnn_status conv2d_set_variant_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad,
                                      const char* name);
 cadnn_status conv2d_prepare_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad);

@@ -1,5 +1,7 @@
 // Sparse fully connected layer (row-per-wave SpMV / skinny SpMM) and the pooling layers
 // that sit between the convolutions of the benchmark networks.
+#include <algorithm>
+
 #include "internal.h"
 
 namespace cadnn {
@@ -125,6 +127,22 @@ __global__ __launch_bounds__(256) void avgpool_kernel(const T* __restrict__ x, T
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
     if (lane == 0) y[plane] = (T)(s / (float)hw);
+}
+
+// Plain streaming copy (16 bytes per thread per step); a known-traffic reference used to
+// calibrate memory-traffic counters against.
+__global__ __launch_bounds__(256) void copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+cadnn_status launch_copy(const void* src, void* dst, size_t bytes, hipStream_t s) {
+    const size_t n16 = bytes / 16;
+    if (n16 == 0) return CADNN_OK;
+    const unsigned blocks = (unsigned)std::min<size_t>((n16 + 255) / 256, 256 * 16);
+    hipLaunchKernelGGL(copy_kernel, dim3(blocks), dim3(256), 0, s, (const uint4*)src, (uint4*)dst, n16);
+    CADNN_HIP(hipGetLastError());
+    return CADNN_OK;
 }
 
 cadnn_status launch_maxpool(const void* x, const TensorDesc& xd, void* y, const TensorDesc& yd, int n,

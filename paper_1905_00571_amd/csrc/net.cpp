@@ -374,6 +374,15 @@ extern "C" cadnn_status cadnn_net_op_variant(const cadnn_net* net, int op_index,
     return CADNN_OK;
 }
 
+extern "C" cadnn_status cadnn_net_op_candidates(const cadnn_net* net, int op_index, char* buf, size_t len) {
+    if (!net || !buf || len == 0) return fail(CADNN_EINVAL, "cadnn_net_op_candidates: NULL pointer");
+    if (!net->finalized) return fail(CADNN_EINVAL, "cadnn_net_op_candidates: net not finalized");
+    if (op_index < 0 || op_index >= (int)net->ops.size()) return fail(CADNN_EINVAL, "cadnn_net_op_candidates: no op %d", op_index);
+    const NetOp& op = net->ops[op_index];
+    if (op.kind != OP_CONV) return fail(CADNN_EINVAL, "cadnn_net_op_candidates: op %d is not a convolution", op_index);
+    return conv2d_list_variants_impl(op.w, op.xd, op.in.n, op.stride, op.pad, buf, len);
+}
+
 extern "C" cadnn_status cadnn_net_set_op_variant(cadnn_net* net, int op_index, const char* name) {
     if (!net) return fail(CADNN_EINVAL, "cadnn_net_set_op_variant: NULL net");
     if (!net->finalized) return fail(CADNN_EINVAL, "cadnn_net_set_op_variant: net not finalized");

@@ -213,6 +213,7 @@ VARIANT_GEOMS = [
     (520, 6, 3, 1, 1, 7, 7, 0.9, 1),      # long rows: exercises the channel-split variants
     (37, 70, 3, 2, 1, 21, 17, 0.5, 2),    # dense enough for the matrix-core fallback too
     (19, 33, 1, 1, 0, 9, 9, 0.0, 1),
+    (40, 24, 1, 1, 0, 12, 20, 0.8, 2),    # even width: adjacent-pixel wide loads
 ]
 
 
@@ -277,3 +278,34 @@ def test_dense_comparator(cad, geom):
         ref = oracle.conv2d(xs, wsd, None, None, stride, pad, False, npdt)
         assert_layer_close(y.cpu().numpy(), ref, cond_conv(xs, wsd, None, None, stride, pad), tol,
                            f"dense {geom} plain f16={f16}", f16=f16)
+
+
+@pytest.mark.parametrize("geom", [(24, 20, 3, 1, 1, 18, 20, 0.8, 2), (16, 12, 3, 2, 1, 15, 17, 0.7, 1),
+                                  (130, 9, 3, 1, 1, 7, 7, 0.9, 1), (12, 10, 3, 1, 1, 14, 14, 0.5, 1)])
+def test_every_variant_on_a_haloed_input(cad, geom):
+    """Inside a net the input of a 3x3 layer carries a zero halo, which opens the
+    linear-address kernels to it: a 1x1 producer feeds the 3x3 layer and every variant that
+    can serve the 3x3 layer there is pinned in turn (both storage types)."""
+    cin, cout, k, stride, pad, h, w_, s, n = geom
+    tag = "halo-%d-%d-%d-%d" % (cin, cout, k, stride)
+    ops = [wl.Op("conv", "pre", 0, 1, 8, cin, 1, 1, 0, 0.3, True),
+           wl.Op("conv", "main", 1, 2, cin, cout, k, stride, pad, s, True),
+           wl.Op("conv", "post", 2, 3, cout, 6, 1, 1, 0, 0.2, False)]
+    shape = (n, 8, h, w_)
+    x, ws, bs = wl.net_tensors(ops, tag, shape, input_relu=True)
+    for dtype, npdt, tol in ((cad.F32, np.float32, TOL_F32), (cad.F16, np.float16, TOL_F16)):
+        xs = x.astype(npdt)
+        ref, ins, outs = oracle.run_net(ops, xs, ws, bs, dtype=npdt)
+        cond = cond_conv(ins[1], ws[1].astype(npdt), bs[1], None, stride, pad)
+        net = cad.build_net(ops, ws, bs, shape, dtype, use_graph=False)
+        names = net.op_candidates(1)
+        assert any(nm.startswith("slinear") for nm in names), names
+        xd = dev(xs)
+        for name in names:
+            net.set_op_variant(1, name)
+            assert net.op_variant(1) == name
+            y = net.run(xd)
+            torch.cuda.synchronize()
+            mid = net.read_buffer(2, outs[1].shape)
+            assert_layer_close(mid, outs[1], cond, tol, f"{geom} {name}", f16=dtype == cad.F16)
+        net.free()
