@@ -115,6 +115,8 @@ cadnn_status cadnn_conv2d_prepare(const cadnn_weights* w, int n, int h, int wdt,
  * that can serve this layer on the given tensors (`reps` launches each, events on
  * `stream`, synchronises, overwrites y) and pins the fastest for this (n, h, wdt,
  * stride, pad); best_us (may be NULL) receives its time per launch in microseconds.
+ * Every timed launch follows a 64 MiB device copy that sweeps the L2 caches, because
+ * inside a network a layer always starts cold (allocates 128 MiB for the duration).
  * cadnn_conv2d_list_variants writes the newline-separated names of the variants that
  * can serve the layer; cadnn_conv2d_set_variant pins one by name (NULL or "" removes
  * the pin, returning to the built-in heuristic). */

@@ -82,6 +82,14 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_direct_kernel(const ConvLa
     const uint2* __restrict__ nz = a.nz;
     const uint32_t cs = (uint32_t)a.xd.plane * (uint32_t)sizeof(T);
 
+    int co_[RPW];
+    float bias_[RPW];
+#pragma unroll
+    for (int r = 0; r < RPW; ++r) {
+        co_[r] = a.perm[row0 + r];
+        bias_[r] = (a.bias && co_[r] >= 0) ? a.bias[co_[r]] : 0.0f;
+    }
+
     float acc[RPW][P];
 #pragma unroll
     for (int r = 0; r < RPW; ++r) {
@@ -135,9 +143,9 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_direct_kernel(const ConvLa
     const T* __restrict__ res = a.residual ? (const T*)a.residual + (size_t)n * a.rd.image + a.rd.origin : nullptr;
 #pragma unroll
     for (int r = 0; r < RPW; ++r) {
-        const int co = a.perm[row0 + r];
+        const int co = co_[r];
         if (co < 0) continue;
-        const float b = a.bias ? a.bias[co] : 0.0f;
+        const float b = bias_[r];
 #pragma unroll
         for (int j = 0; j < P; ++j) {
             const int q = q0 + j * 64 + lane;

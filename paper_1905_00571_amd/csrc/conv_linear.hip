@@ -123,8 +123,13 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_linear_kernel(const ConvLa
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int rg = wv / KS, ks = wv % KS;
     const int n = blockIdx.z;
-    const int q0 = blockIdx.x * (64 * P);
-    const int row0 = (blockIdx.y * RG + rg) * RPW;
+    // Workgroups in plain launch order.  (Die-aware placements were measured: giving each
+    // of the 8 dies its own pixel tiles made the whole net 2.5x slower -- every CU of a die
+    // then hammers the same few L2 channels -- and giving each die its own rows changed
+    // nothing.)
+    const int tile = blockIdx.x, grp = blockIdx.y;
+    const int q0 = tile * (64 * P);
+    const int row0 = (grp * RG + rg) * RPW;
 
     // byte offset of tap (0,0) of each of the lane's pixels inside the padded image
     uint32_t voff[P];
@@ -142,19 +147,47 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_linear_kernel(const ConvLa
     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
         (void*)((const char*)a.x + (size_t)n * a.image_bytes), 0, a.image_bytes, 0x00020000);
 
+    // Header {padded length, original channel} of each of the wave's parts.  A part starts
+    // at (row*KS + ks) * stride, so the first window of the first row is requested in the
+    // same breath as the headers and the bias follows one round trip later, in parallel
+    // with the first activations.
+    const int stride = a.nchunks;
+    const int2* __restrict__ hdr = (const int2*)a.seg_ptr;
     NzWindow win;
     win.nz = a.nz;
     win.lane = lane;
-    win.base = -(1 << 30);
+    win.reset(((row0 + 0) * KS + ks) * stride);
+    int co_[RPW], len_[RPW];
+    float bias_[RPW];
+#pragma unroll
+    for (int r = 0; r < RPW; ++r) {
+        const int2 h = hdr[(row0 + r) * KS + ks];
+        len_[r] = h.x;
+        co_[r] = h.y;
+    }
+#pragma unroll
+    for (int r = 0; r < RPW; ++r) bias_[r] = (a.bias && co_[r] >= 0) ? a.bias[co_[r]] : 0.0f;
+
+    // the residual is also fetched up front: one more round trip off the tail
+    const T* __restrict__ res = a.residual ? (const T*)a.residual + (size_t)n * a.rd.image + a.rd.origin : nullptr;
+    float resv[RPW][P];
+#pragma unroll
+    for (int j = 0; j < P; ++j) {
+        const int q = ADJ ? q0 + lane * P + j : q0 + j * 64 + lane;
+        const int oh = q / a.yd.w, ow = q - oh * a.yd.w;
+        const int ridx = oh * a.rd.pitch + ow;
+#pragma unroll
+        for (int r = 0; r < RPW; ++r)
+            resv[r][j] = (res && ks == 0 && co_[r] >= 0 && oidx[j] >= 0) ? (float)res[(size_t)co_[r] * a.rd.plane + ridx] : 0.0f;
+    }
 
     float acc[RPW][P];
 #pragma unroll
     for (int r = 0; r < RPW; ++r) {
 #pragma unroll
         for (int j = 0; j < P; ++j) acc[r][j] = 0.0f;
-        const int32_t* __restrict__ seg = a.seg_ptr + ((size_t)(row0 + r) * KS + ks);
-        int i = seg[0];
-        const int end = seg[1];
+        int i = ((row0 + r) * KS + ks) * stride;
+        const int end = i + len_[r];
         if (i >= end) continue;
         win.seek(i);
         // Two register sets (A, B) take turns: while one group is accumulated the
@@ -223,24 +256,16 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_linear_kernel(const ConvLa
 
     // ---- fused epilogue: + bias, + residual, ReLU, store at the original channel
     T* __restrict__ y = (T*)a.y + (size_t)n * a.yd.image + a.yd.origin;
-    const T* __restrict__ res = a.residual ? (const T*)a.residual + (size_t)n * a.rd.image + a.rd.origin : nullptr;
-    int ridx[P];
-#pragma unroll
-    for (int j = 0; j < P; ++j) {
-        const int q = ADJ ? q0 + lane * P + j : q0 + j * 64 + lane;
-        const int oh = q / a.yd.w, ow = q - oh * a.yd.w;
-        ridx[j] = oh * a.rd.pitch + ow;
-    }
 #pragma unroll
     for (int r = 0; r < RPW; ++r) {
-        const int co = a.perm[row0 + r];
+        const int co = co_[r];
         if (co < 0) continue;
-        const float b = a.bias ? a.bias[co] : 0.0f;
+        const float b = bias_[r];
 #pragma unroll
         for (int j = 0; j < P; ++j) {
             if (oidx[j] >= 0) {
                 float v = acc[r][j] + b;
-                if (res) v += (float)res[(size_t)co * a.rd.plane + ridx[j]];
+                v += resv[r][j];
                 if (a.relu) v = v > 0.0f ? v : 0.0f;
                 y[(size_t)co * a.yd.plane + oidx[j]] = (T)v;
             }
@@ -290,12 +315,25 @@ static ConvVariant make_linear(const char* name) {
     CADNN_LINEAR_ADJ(T, 4, 1, 8, 8, 4), \
     CADNN_LINEAR_ADJ(T, 4, 2, 1, 4, 4), \
     CADNN_LINEAR_ADJ(T, 4, 1, 16, 16, 4), \
+    CADNN_LINEAR_ADJ(T, 2, 1, 1, 4, 16), \
+    CADNN_LINEAR_ADJ(T, 2, 1, 2, 4, 16), \
+    CADNN_LINEAR_ADJ(T, 2, 1, 4, 4, 16), \
+    CADNN_LINEAR_ADJ(T, 4, 1, 1, 4, 16), \
+    CADNN_LINEAR_ADJ(T, 4, 1, 2, 4, 16), \
+    CADNN_LINEAR_ADJ(T, 4, 1, 4, 4, 16), \
+    CADNN_LINEAR_ADJ(T, 4, 1, 1, 4, 8),  \
+    CADNN_LINEAR_ADJ(T, 4, 1, 2, 4, 8),  \
+    CADNN_LINEAR_ADJ(T, 4, 1, 4, 4, 8),  \
+    CADNN_LINEAR_ADJ(T, 2, 1, 1, 4, 8),  \
+    CADNN_LINEAR_ADJ(T, 2, 1, 2, 4, 8),  \
     CADNN_LINEAR(T, 1, 1, 1, 4, 4),     \
     CADNN_LINEAR(T, 1, 1, 1, 4, 8),     \
     CADNN_LINEAR(T, 1, 1, 1, 4, 16),    \
     CADNN_LINEAR(T, 1, 1, 2, 4, 16),    \
     CADNN_LINEAR(T, 1, 1, 4, 4, 16),    \
     CADNN_LINEAR(T, 1, 1, 8, 8, 16),    \
+    CADNN_LINEAR(T, 1, 1, 16, 16, 16),  \
+    CADNN_LINEAR(T, 1, 1, 16, 16, 8),   \
     CADNN_LINEAR(T, 2, 1, 4, 4, 8),     \
     CADNN_LINEAR(T, 2, 1, 2, 4, 8),     \
     CADNN_LINEAR(T, 1, 2, 1, 4, 4),     \

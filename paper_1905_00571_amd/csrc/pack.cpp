@@ -204,52 +204,63 @@ static cadnn_status build_direct_plan(const cadnn_weights* w, const ConvVariant*
 //
 // Entries stay in canonical order.  A packed row's entries are cut into KS contiguous
 // parts of (nearly) equal length, each padded to a multiple of `unroll` with (0.0f, 0)
-// entries; seg_ptr[i*KS + s .. + 1] delimits part s of packed row i (parts are laid out
-// back to back, so one table of rows_padded*KS + 1 entries suffices).  An entry is (fp32
-// value bits, byte offset of the tap relative to tap (0,0) of channel 0 in the input's
-// padded layout) -- hence the dependence on the input's plane and pitch.  128 spare zero
-// entries end the stream: a wave reads it 64 entries at a time and one such read ahead.
+// entries.  Part s of packed row i starts at entry (i*KS + s)*stride, where `stride` is the
+// longest padded part of the layer: the start of a part is therefore computable from the
+// row number alone, and its first entries can be fetched together with its header instead
+// of one memory round trip after it.  The header table (stored in the plan's segment
+// buffer) holds, per part, {padded length, original channel of the row (-1: padding row)}.
+// An entry is (fp32 value bits, byte offset of the tap relative to tap (0,0) of channel 0
+// in the input's padded layout) -- hence the dependence on the input's plane and pitch.
+// 128 spare zero entries end the stream: a wave reads it 64 entries at a time, one read
+// ahead.
 static cadnn_status build_linear_plan(const cadnn_weights* w, const ConvVariant* v, const TensorDesc& xd,
                                       ConvPlan* plan) {
     const int g = v->rows_per_block();
     const int rows_padded = (w->cout + g - 1) / g * g;
     const int taps = w->kh * w->kw;
     const int ks = v->ks;
+    const int U = v->unroll;
     const int64_t esz = (int64_t)w->elem();
-    std::vector<int32_t> seg((size_t)rows_padded * ks + 1, 0);
+    // longest padded part
+    int64_t stride = U;
+    for (int i = 0; i < w->cout; ++i) {
+        const int32_t cnt = w->row_ptr[i + 1] - w->row_ptr[i];
+        const int32_t per = (cnt + ks - 1) / ks;
+        stride = std::max<int64_t>(stride, (int64_t)(per + U - 1) / U * U);
+    }
+    const int64_t total = (int64_t)rows_padded * ks * stride + 128;
+    if (total > (int64_t)INT32_MAX / 2) return fail(CADNN_EUNSUPPORTED, "plan too large");
+    std::vector<int32_t> hdr((size_t)rows_padded * ks * 2, 0);
     std::vector<int32_t> perm(rows_padded, -1);
-    std::vector<uint2> nz;
-    nz.reserve((size_t)w->nnz + (size_t)w->cout * ks * (v->unroll - 1) / 2 + 16);
+    std::vector<uint2> nz((size_t)total, make_uint2(0u, 0u));
     for (int i = 0; i < rows_padded; ++i) {
         const int32_t b = i < w->cout ? w->row_ptr[i] : 0;
         const int32_t e = i < w->cout ? w->row_ptr[i + 1] : 0;
         if (i < w->cout) perm[i] = w->perm[i];
         const int32_t per = (e - b + ks - 1) / ks;
         for (int s = 0; s < ks; ++s) {
-            seg[(size_t)i * ks + s] = (int32_t)nz.size();
-            const int32_t pb = std::min<int64_t>((int64_t)b + (int64_t)s * per, e);
-            const int32_t pe = std::min<int64_t>((int64_t)pb + per, e);
+            const int32_t pb = (int32_t)std::min<int64_t>((int64_t)b + (int64_t)s * per, e);
+            const int32_t pe = (int32_t)std::min<int64_t>((int64_t)pb + per, e);
+            uint2* out = &nz[((size_t)i * ks + s) * (size_t)stride];
             for (int32_t j = pb; j < pe; ++j) {
                 const int32_t k = w->col_idx[j];
                 const int ci = k / taps, r = (k % taps) / w->kw, c = k % w->kw;
                 const int64_t off = ((int64_t)ci * xd.plane + (int64_t)r * xd.pitch + c) * esz;
                 uint32_t bits;
                 std::memcpy(&bits, &w->vals[j], 4);
-                nz.push_back(make_uint2(bits, (uint32_t)off));
+                out[j - pb] = make_uint2(bits, (uint32_t)off);
             }
-            while (nz.size() % (size_t)v->unroll) nz.push_back(make_uint2(0u, 0u));
+            hdr[((size_t)i * ks + s) * 2 + 0] = (pe - pb + U - 1) / U * U;
+            hdr[((size_t)i * ks + s) * 2 + 1] = perm[i];
         }
     }
-    seg[(size_t)rows_padded * ks] = (int32_t)nz.size();
-    for (int u = 0; u < 128; ++u) nz.push_back(make_uint2(0u, 0u));   // read-ahead room
-    if (nz.size() > (size_t)INT32_MAX) return fail(CADNN_EUNSUPPORTED, "plan too large");
     plan->variant = v;
-    plan->nchunks = 1;
+    plan->nchunks = (int)stride;
     plan->rows_padded = rows_padded;
     plan->nz_padded = (int64_t)nz.size();
     cadnn_status st;
     if ((st = plan->nz.upload(nz.data(), nz.size() * sizeof(uint2))) != CADNN_OK) return st;
-    if ((st = plan->seg_ptr.upload(seg.data(), seg.size() * 4)) != CADNN_OK) return st;
+    if ((st = plan->seg_ptr.upload(hdr.data(), hdr.size() * 4)) != CADNN_OK) return st;
     if ((st = plan->perm.upload(perm.data(), perm.size() * 4)) != CADNN_OK) return st;
     return CADNN_OK;
 }
