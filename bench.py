@@ -19,6 +19,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
+TUNED_DIR = os.path.join(ROOT, "paper_1905_00571_amd", "tuned")
+DEFAULT_TUNE = os.path.join(TUNED_DIR, "resnet50_c2_f32_n1.json")      # saved per-layer kernel choice
+DEFAULT_TRAFFIC = os.path.join(TUNED_DIR, "traffic_resnet50_c2_f32_n1.json")  # measured HBM bytes per launch
 FP32_VECTOR_TFLOPS = 157.3   # MI355X vector fp32 (256 CU x 2.4 GHz x 256 flop/clk)
 
 
@@ -58,6 +61,17 @@ def layer_costs(ops, weights, in_shape, elem):
     return rows
 
 
+KERNEL_OF_PREFIX = {"slinear": "sconv_linear_kernel", "stile": "sconv_stile_kernel",
+                    "sdirect": "sconv_direct_kernel", "sconv": "sconv_tile_kernel",
+                    "dense": "dense_conv_kernel", "sfc": "sfc_kernel", "maxpool": "maxpool_kernel",
+                    "avgpool": "avgpool_kernel"}
+
+
+def kernel_of(variant: str) -> str:
+    """The __global__ function a variant name is an instantiation of."""
+    return KERNEL_OF_PREFIX.get(variant.split("_")[0], variant)
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -68,7 +82,13 @@ def main() -> int:
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--no-tune", action="store_true")
     ap.add_argument("--save-tune", type=str, default="", help="write the tuned variant names (JSON)")
-    ap.add_argument("--load-tune", type=str, default="", help="pin saved variant names instead of tuning")
+    ap.add_argument("--load-tune", type=str, default=DEFAULT_TUNE if os.path.exists(DEFAULT_TUNE) else "",
+                    help="pin saved variant names instead of tuning (default: the saved choice for this "
+                         "workload that ships with the package)")
+    ap.add_argument("--retune", action="store_true", help="ignore --load-tune and time every variant per layer now")
+    ap.add_argument("--traffic", type=str, default=DEFAULT_TRAFFIC,
+                    help="JSON of HBM bytes per launch per kernel measured with rocprofv3 --pmc "
+                         "(written by paper_1905_00571_amd/profile_summary.py)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a 256 MiB device copy 10 times (known traffic, for counter calibration)")
     ap.add_argument("--no-layer-profile", action="store_true",
@@ -94,11 +114,15 @@ def main() -> int:
     ops = wl.resnet50_ops()
     shape = (1, 3, 224, 224)
     x, ws, bs = wl.net_tensors(ops, "c2", shape)
+    if args.retune or args.no_tune:
+        args.load_tune = ""
     net = cad.build_net(ops, ws, bs, shape, cad.F32, use_graph=not args.no_graph,
                         tune=not (args.no_tune or args.load_tune))
+    tuning = "none" if args.no_tune else "live"
     if args.load_tune:
         with open(args.load_tune) as f:
             net.set_variants(json.load(f)["variants"])
+        tuning = "saved:" + os.path.relpath(args.load_tune, ROOT)
     xd = torch.from_numpy(x).cuda()            # inputs resident in HBM before timing
     y = torch.empty(net.out_shape, dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream()
@@ -122,7 +146,8 @@ def main() -> int:
         lat.append((time.perf_counter() - a) * 1e3)
     lat_sync_ms = float(np.median(lat))
 
-    # ---- per-op device time with HIP events on the launch stream, grouped by kernel
+    # ---- per-op device time with HIP events on the launch stream, grouped by kernel function
+    # (all tile-shape instantiations of one __global__ template count as one kernel)
     if args.calibrate_copy:
         a_ = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
         b_ = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
@@ -150,7 +175,7 @@ def main() -> int:
         costs[i]["gbs"] = costs[i]["bytes"] / t / 1e9 if t > 0 else 0.0
         costs[i]["frac_hbm"] = costs[i]["gbs"] / HBM_PEAK_GBS
         costs[i]["frac_fp32"] = costs[i]["gflops"] / (FP32_VECTOR_TFLOPS * 1e3)
-        g = groups.setdefault(name, {"ms": 0.0, "launches": 0, "flops": 0.0, "bytes": 0.0})
+        g = groups.setdefault(kernel_of(name), {"ms": 0.0, "launches": 0, "flops": 0.0, "bytes": 0.0})
         g["ms"] += costs[i]["ms"]
         g["launches"] += 1
         g["flops"] += costs[i]["flops"]
@@ -167,6 +192,11 @@ def main() -> int:
         achieved = dom["bytes"] / dom["launches"] / avg_s / 1e9
         roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": achieved / HBM_PEAK_GBS, "traffic": None}
+    if args.traffic and os.path.exists(args.traffic):
+        with open(args.traffic) as f:
+            measured = json.load(f).get("kernels", {})
+        if dom_name in measured:
+            roofline["traffic"] = measured[dom_name]["hbm_bytes_per_launch"]
     roofline.update({"kernel": dom_name, "launches_per_step": dom["launches"],
                      "avg_launch_us": avg_s * 1e6,
                      "algorithmic_flops_per_launch": dom["flops"] / dom["launches"],
@@ -207,7 +237,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": "resnet50-sparse fp32 batch 1 (configs[2]): 53 convs + FC, conv1 0 %, "
                                "3x3 80 %, 1x1+FC 90 % unstructured sparsity, 1x3x224x224 input",
-                   "graph": not args.no_graph, "per_layer_kernel_tuning": not args.no_tune},
+                   "graph": not args.no_graph, "per_layer_kernel_tuning": tuning},
         "images_per_s": 1e3 / ms_per_step,
         "latency_with_host_sync_ms": lat_sync_ms,
         "effective_gflops_nonzero_macs": total_flops / (ms_per_step * 1e-3) / 1e9,

@@ -1,0 +1,107 @@
+#!/usr/bin/env python3
+"""Condenses rocprofv3 CSV output of a bench.py run into a short text summary and a JSON
+of measured HBM traffic per kernel launch.
+
+Inputs (any subset):
+  --stats  <..._kernel_stats.csv>        from  rocprofv3 --kernel-trace --stats --output-format csv
+  --fetch  <..._counter_collection.csv>  from  rocprofv3 --pmc FETCH_SIZE --output-format csv
+  --write  <..._counter_collection.csv>  from  rocprofv3 --pmc WRITE_SIZE --output-format csv
+The two counter runs must come from `bench.py --calibrate-copy`, which also launches the
+library's plain copy kernel on a 256 MiB buffer: what the counters read for that known
+traffic gives the scale factor applied to every other kernel.
+
+All tile-shape instantiations of one __global__ template are summed under the template's
+name, as bench.py does for its roofline object.
+"""
+from __future__ import annotations
+
+import argparse
+import csv
+import json
+import re
+import sys
+from collections import defaultdict
+
+COPY_BYTES = 256 << 20
+
+
+def kernel_of(symbol: str) -> str:
+    m = re.search(r"(\w+_kernel)\b", symbol)
+    return m.group(1) if m else symbol.split("(")[0].split("<")[0]
+
+
+def read_stats(path):
+    agg = defaultdict(lambda: [0, 0.0])
+    with open(path) as f:
+        for r in csv.DictReader(f):
+            k = kernel_of(r["Name"])
+            agg[k][0] += int(r["Calls"])
+            agg[k][1] += float(r["TotalDurationNs"])
+    return {k: {"calls": c, "total_ns": t, "avg_ns": t / c} for k, (c, t) in agg.items()}
+
+
+def read_counter(path, counter):
+    """Average counter value (KiB) per dispatch, per kernel."""
+    per = defaultdict(lambda: defaultdict(float))      # kernel -> dispatch -> sum over rows
+    with open(path) as f:
+        for r in csv.DictReader(f):
+            if r["Counter_Name"] != counter:
+                continue
+            per[kernel_of(r["Kernel_Name"])][r["Dispatch_Id"]] += float(r["Counter_Value"])
+    return {k: {"dispatches": len(d), "avg_kib": sum(d.values()) / len(d)} for k, d in per.items()}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--stats")
+    ap.add_argument("--fetch")
+    ap.add_argument("--write")
+    ap.add_argument("--command", action="append", default=[], help="command line(s) to record in the summary")
+    ap.add_argument("--title", default="rocprofv3 summary")
+    ap.add_argument("--out-txt", required=True)
+    ap.add_argument("--out-json", default="")
+    args = ap.parse_args()
+
+    lines = [args.title, "=" * len(args.title), ""]
+    for c in args.command:
+        lines.append("command: " + c)
+    lines.append("")
+    stats = read_stats(args.stats) if args.stats else {}
+    if stats:
+        tot = sum(v["total_ns"] for v in stats.values())
+        lines.append("kernel time (rocprofv3 --kernel-trace --stats; instantiations of one template summed)")
+        lines.append("%-28s %8s %14s %12s %7s" % ("kernel", "calls", "total_us", "avg_us", "share"))
+        for k, v in sorted(stats.items(), key=lambda kv: -kv[1]["total_ns"]):
+            lines.append("%-28s %8d %14.1f %12.3f %6.1f%%" % (k, v["calls"], v["total_ns"] / 1e3, v["avg_ns"] / 1e3,
+                                                              100.0 * v["total_ns"] / tot))
+        lines.append("")
+    traffic = {}
+    factors = {}
+    for label, path, counter in (("fetch", args.fetch, "FETCH_SIZE"), ("write", args.write, "WRITE_SIZE")):
+        if not path:
+            continue
+        c = read_counter(path, counter)
+        if "copy_kernel" not in c:
+            print("no copy_kernel dispatches in %s: run bench.py with --calibrate-copy" % path, file=sys.stderr)
+            return 1
+        factor = (COPY_BYTES / 1024.0) / c["copy_kernel"]["avg_kib"]
+        factors[label] = factor
+        lines.append("%s per dispatch (rocprofv3 --pmc %s, KiB); plain copy of %d KiB reads %.0f KiB "
+                     "=> scale factor %.3f" % (counter, counter, COPY_BYTES // 1024, c["copy_kernel"]["avg_kib"], factor))
+        lines.append("%-28s %10s %14s %14s" % ("kernel", "dispatches", "raw_avg_KiB", "scaled_KiB"))
+        for k, v in sorted(c.items(), key=lambda kv: -kv[1]["avg_kib"] * kv[1]["dispatches"]):
+            lines.append("%-28s %10d %14.1f %14.1f" % (k, v["dispatches"], v["avg_kib"], v["avg_kib"] * factor))
+            traffic.setdefault(k, {})[label + "_bytes_per_launch"] = v["avg_kib"] * factor * 1024.0
+        lines.append("")
+    for k, v in traffic.items():
+        v["hbm_bytes_per_launch"] = v.get("fetch_bytes_per_launch", 0.0) + v.get("write_bytes_per_launch", 0.0)
+    with open(args.out_txt, "w") as f:
+        f.write("\n".join(lines) + "\n")
+    if args.out_json:
+        with open(args.out_json, "w") as f:
+            json.dump({"scale_factors": factors, "kernels": traffic}, f, indent=1, sort_keys=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
