@@ -45,6 +45,12 @@ static bool variant_fits(const ConvVariant& v, const cadnn_weights* w, const Con
         if (w->kh == 1 && w->kw == 1) return g.pad == 0;
         return g.xd.ph >= g.pad && g.xd.pw >= g.pad;
     }
+    if (v.family == FAM_PTILE) {
+        // staging pays only when a staged element is reused by several taps
+        if (w->kh * w->kw == 1) return false;
+        const PtileGeom pg = ptile_geom(v, w->cin, w->kh, w->kw, g.stride, g.pad, g.wout);
+        return pg.nstp <= kPtileMaxSteps && (size_t)pg.plane * 4 <= kLdsBytesPerCU;
+    }
     return v.kh == w->kh && v.kw == w->kw;
 }
 
@@ -55,6 +61,7 @@ static std::vector<const ConvVariant*> candidates(const cadnn_weights* w, const 
     for (const ConvVariant& v : all_tile_variants()) if (variant_fits(v, w, g)) out.push_back(&v);
     for (const ConvVariant& v : all_dense_variants()) if (variant_fits(v, w, g)) out.push_back(&v);
     for (const ConvVariant& v : all_stile_variants()) if (variant_fits(v, w, g)) out.push_back(&v);
+    for (const ConvVariant& v : all_ptile_variants()) if (variant_fits(v, w, g)) out.push_back(&v);
     return out;
 }
 
@@ -76,8 +83,8 @@ static const ConvVariant* heuristic_variant(const cadnn_weights* w, const ConvGe
             const double blocks = std::ceil(pixels / 64.0) * g.n * std::ceil(w->cout / 64.0);
             const double K = (double)w->cin * w->kh * w->kw;
             cost = 2500.0 + std::ceil(blocks / 256.0) * std::ceil(K / 32.0) * 1100.0;
-        } else if (v->family == FAM_STILE) {
-            continue;   // chosen by tuning only: whether its plan fits depends on the weights
+        } else if (v->family == FAM_STILE || v->family == FAM_PTILE) {
+            continue;   // chosen by tuning only
         } else if (v->family != FAM_TILE) {
             const double tiles = std::ceil(pixels / (64.0 * v->p)) * g.n;
             const double blocks = tiles * std::ceil((double)w->cout / v->rows_per_block());
@@ -118,7 +125,7 @@ static cadnn_status launch_variant(const cadnn_weights* w, const ConvVariant* v,
                                    const void* x, void* y, const TensorDesc& yd, const void* residual,
                                    const TensorDesc& rd, const void* bias, int relu, hipStream_t s) {
     const ConvPlan* plan = nullptr;
-    cadnn_status st = get_conv_plan(w, v, g.xd, &plan);
+    cadnn_status st = get_conv_plan(w, v, g.xd, g.stride, g.pad, g.wout, &plan);
     if (st != CADNN_OK) return st;
     ConvLaunch a{};
     a.x = x;
@@ -134,7 +141,15 @@ static cadnn_status launch_variant(const cadnn_weights* w, const ConvVariant* v,
     a.kh = w->kh; a.kw = w->kw; a.is_f16 = w->dtype == CADNN_F16;
     a.hwout = g.hout * g.wout;
     a.image_bytes = (uint32_t)(g.xd.image * (int64_t)w->elem());
-    if (v->family == FAM_TILE || v->family == FAM_STILE) {
+    if (v->family == FAM_PTILE) {
+        const PtileGeom pg = ptile_geom(*v, w->cin, w->kh, w->kw, g.stride, g.pad, g.wout);
+        a.tiles_x = (g.wout + 7 * v->p - 1) / (7 * v->p);
+        a.tiles_y = (g.hout + 6) / 7;
+        a.pt_pitch = pg.pitch; a.pt_sub = pg.sub; a.pt_plane = pg.plane; a.pt_nphc = pg.nphc;
+        a.pt_nph = pg.nphr * pg.nphc; a.pt_in_rows = pg.in_rows; a.pt_in_cols = pg.alias ? pg.in_cols - 1 : pg.in_cols;
+        a.pt_cch = pg.cch; a.pt_nstp = pg.nstp; a.pt_nchunks = pg.nchunks;
+        a.pt_lds_bytes = (uint32_t)pg.lds_bytes;
+    } else if (v->family == FAM_TILE || v->family == FAM_STILE) {
         a.tiles_x = (g.wout + v->tw - 1) / v->tw;
         a.tiles_y = (g.hout + v->th - 1) / v->th;
     } else {
@@ -179,7 +194,7 @@ cadnn_status conv2d_prepare_impl(const cadnn_weights* w, const TensorDesc& xd, i
         return fail(CADNN_EUNSUPPORTED, "cadnn_conv2d_prepare: no kernel for %dx%d filters with stride %d",
                     w->kh, w->kw, stride);
     const ConvPlan* plan = nullptr;
-    return get_conv_plan(w, v, xd, &plan);
+    return get_conv_plan(w, v, xd, g.stride, g.pad, g.wout, &plan);
 }
 
 const char* conv2d_variant_name_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad) {
@@ -261,7 +276,7 @@ cadnn_status conv2d_tune_impl(const cadnn_weights* w, const void* x, const Tenso
     for (const ConvVariant* v : cand) {
         {
             const ConvPlan* probe = nullptr;
-            if (get_conv_plan(w, v, g.xd, &probe) == CADNN_EUNSUPPORTED) continue;   // does not fit these weights
+            if (get_conv_plan(w, v, g.xd, g.stride, g.pad, g.wout, &probe) == CADNN_EUNSUPPORTED) continue;   // does not fit these weights
         }
         st = launch_variant(w, v, g, x, y, yd, residual, rd, bias, relu, s);
         float total_ms = 0.0f;

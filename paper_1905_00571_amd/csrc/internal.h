@@ -98,7 +98,12 @@ inline TensorDesc make_desc(int c, int h, int w, int ph = 0, int pw = 0) {
 //  FAM_STILE  : LDS tiles as FAM_TILE, but every wave of the workgroup stages and consumes
 //               its own channel chunks (no barrier in the main loop) for all G rows of
 //               the workgroup; the plan is chunk-major per group of G rows.
-enum ConvFamily { FAM_TILE = 0, FAM_DIRECT = 1, FAM_LINEAR = 2, FAM_DENSE = 3, FAM_STILE = 4 };
+//  FAM_PTILE  : the workgroup stages ONE input tile (all channels, or channel chunks in
+//               turn) in LDS for a 7-row block of output pixels and all its waves read it:
+//               the waves split G rows and each row's nonzeros between them, so a staged
+//               element is reused by every row of the group; entries are (value, byte
+//               offset of the tap in the staged tile).
+enum ConvFamily { FAM_TILE = 0, FAM_DIRECT = 1, FAM_LINEAR = 2, FAM_DENSE = 3, FAM_STILE = 4, FAM_PTILE = 5 };
 
 struct ConvLaunch;
 
@@ -140,6 +145,9 @@ struct ConvLaunch {
     int kh, kw, is_f16;
     int tiles_x, tiles_y, row_groups;
     int hwout;                // yd.h * yd.w
+    // FAM_PTILE: geometry of the staged tile (see PtileGeom)
+    int pt_pitch, pt_sub, pt_plane, pt_nphc, pt_nph, pt_in_rows, pt_in_cols, pt_cch, pt_nstp, pt_nchunks;
+    uint32_t pt_lds_bytes;
     uint32_t image_bytes;     // xd.image * sizeof(element)
 };
 
@@ -151,7 +159,29 @@ struct ConvPlan {
     int64_t nz_padded = 0;
 };
 
-// (variant, input plane, input pitch): the last two are 0 for layout-independent plans
+// Staged tile of the FAM_PTILE kernels for one layer geometry.  A tile serves 7 output rows
+// x 7*P output columns.  The input region it needs is de-interleaved by the stride into
+// nphr x nphc phases (sub-planes) so that lanes always read consecutive LDS words:
+// input element (u, v) of the region sits at phase (u % S, v % S), position (u / S, v / S).
+// `alias`: 3x3 / stride-1 tiles that span the whole image width drop the right halo column
+// (its reads fall on the left halo of the next row, which is zero as well), which makes the
+// pitch 8 words: bank-conflict free and small enough for 512 channels of a 7x7 image.
+struct PtileGeom {
+    int S, P;
+    int in_rows, in_cols;     // input region of a tile
+    int nphr, nphc;           // phases used
+    int pitch, sub, plane;    // words per tile row / per phase / per channel
+    int nstp;                 // 64-word staging steps per channel
+    int cch, nchunks;         // channels staged at a time, number of such chunks
+    int alias;
+    size_t lds_bytes;
+};
+PtileGeom ptile_geom(const ConvVariant& v, int cin, int kh, int kw, int stride, int pad, int wout);
+constexpr int kPtileMaxSteps = 6;
+constexpr size_t kLdsBytesPerCU = 160 * 1024;
+
+// (variant, a, b): FAM_LINEAR a = input plane, b = input pitch; FAM_PTILE a = stride,
+// b = alias flag; 0, 0 for layout-independent plans
 typedef std::tuple<const ConvVariant*, int, int> PlanKey;
 // (n, h, w, stride, pad, input halo rows, input halo columns)
 typedef std::array<int, 7> GeomKey;
@@ -161,6 +191,7 @@ const std::vector<ConvVariant>& all_direct_variants();
 const std::vector<ConvVariant>& all_linear_variants();
 const std::vector<ConvVariant>& all_dense_variants();
 const std::vector<ConvVariant>& all_stile_variants();
+const std::vector<ConvVariant>& all_ptile_variants();
 
 }  // namespace cadnn
 
@@ -185,8 +216,9 @@ struct cadnn_weights {
 };
 
 namespace cadnn {
-cadnn_status get_conv_plan(const cadnn_weights* w, const ConvVariant* v, const TensorDesc& xd,
-                           const ConvPlan** out);
+// stride / pad / wout matter to FAM_PTILE plans only.
+cadnn_status get_conv_plan(const cadnn_weights* w, const ConvVariant* v, const TensorDesc& xd, int stride,
+                           int pad, int wout, const ConvPlan** out);
 void drop_unpinned_plans(const cadnn_weights* w);
 cadnn_status ensure_fc_device(const cadnn_weights* w);
 uint16_t f32_to_f16_rne(float f);

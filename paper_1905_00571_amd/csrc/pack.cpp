@@ -265,6 +265,104 @@ static cadnn_status build_linear_plan(const cadnn_weights* w, const ConvVariant*
     return CADNN_OK;
 }
 
+// Geometry of the staged tile of a FAM_PTILE variant for one layer (see PtileGeom).
+PtileGeom ptile_geom(const ConvVariant& v, int cin, int kh, int kw, int stride, int pad, int wout) {
+    PtileGeom g{};
+    g.S = stride;
+    g.P = v.p;
+    g.in_rows = 6 * stride + kh;
+    g.in_cols = (7 * v.p - 1) * stride + kw;
+    g.nphr = std::min(stride, kh);
+    g.nphc = std::min(stride, kw);
+    const int ph_r = (g.in_rows + stride - 1) / stride;
+    const int ph_c = (g.in_cols + stride - 1) / stride;
+    g.alias = (stride == 1 && kh == 3 && kw == 3 && pad == 1 && wout == 7 * v.p) ? 1 : 0;
+    g.pitch = g.alias ? ph_c - 1 : ph_c;
+    g.sub = ph_r * g.pitch;
+    g.plane = g.nphr * g.nphc * g.sub + g.alias;
+    g.nstp = (g.plane + 63) / 64;
+    const size_t red_bytes = (size_t)v.nw * v.rpw * v.p * 64 * 4;
+    const int cch_max = (int)std::max<size_t>(1, kLdsBytesPerCU / ((size_t)g.plane * 4));
+    g.nchunks = (cin + cch_max - 1) / cch_max;
+    g.cch = (cin + g.nchunks - 1) / g.nchunks;
+    g.lds_bytes = std::max((size_t)g.cch * g.plane * 4, red_bytes);
+    return g;
+}
+
+// Device copy of the nonzero stream for a shared-tile (FAM_PTILE) variant.
+//
+// The input channels are cut into `nchunks` chunks of `cch`.  Packed row i is served by KS
+// waves; within chunk c its entries (ascending canonical column) are split evenly between
+// them.  Part (i, s, c) starts at ((i*KS + s)*nchunks + c) * stride entries, `stride` being
+// the longest part rounded up to the unroll, and the header table holds {padded length,
+// original channel} at the same index.  An entry is (fp32 value bits, byte offset of the tap
+// in the staged tile relative to the lane's pixel).
+static cadnn_status build_ptile_plan(const cadnn_weights* w, const ConvVariant* v, int conv_stride, int pad,
+                                     int wout, ConvPlan* plan) {
+    const PtileGeom g = ptile_geom(*v, w->cin, w->kh, w->kw, conv_stride, pad, wout);
+    const int rb = v->rows_per_block();
+    const int rows_padded = (w->cout + rb - 1) / rb * rb;
+    const int taps = w->kh * w->kw;
+    const int ks = v->ks;
+    const int U = v->unroll;
+    // chunk boundaries of every row in the canonical stream
+    std::vector<int32_t> cut((size_t)w->cout * (g.nchunks + 1));
+    int64_t stride = U;
+    for (int i = 0; i < w->cout; ++i) {
+        int32_t j = w->row_ptr[i];
+        const int32_t e = w->row_ptr[i + 1];
+        for (int c = 0; c < g.nchunks; ++c) {
+            cut[(size_t)i * (g.nchunks + 1) + c] = j;
+            const int32_t k_end = (int32_t)std::min<int64_t>((int64_t)(c + 1) * g.cch, w->cin) * taps;
+            while (j < e && w->col_idx[j] < k_end) ++j;
+            const int32_t cnt = j - cut[(size_t)i * (g.nchunks + 1) + c];
+            const int32_t per = (cnt + ks - 1) / ks;
+            stride = std::max<int64_t>(stride, (int64_t)(per + U - 1) / U * U);
+        }
+        cut[(size_t)i * (g.nchunks + 1) + g.nchunks] = e;
+    }
+    const int64_t parts = (int64_t)rows_padded * ks * g.nchunks;
+    const int64_t total = parts * stride + 128;
+    if (total > (int64_t)INT32_MAX / 2) return fail(CADNN_EUNSUPPORTED, "plan too large");
+    std::vector<int32_t> hdr((size_t)parts * 2, 0);
+    std::vector<int32_t> perm(rows_padded, -1);
+    std::vector<uint2> nz((size_t)total, make_uint2(0u, 0u));
+    for (int i = 0; i < rows_padded; ++i) {
+        if (i < w->cout) perm[i] = w->perm[i];
+        for (int c = 0; c < g.nchunks; ++c) {
+            const int32_t b = i < w->cout ? cut[(size_t)i * (g.nchunks + 1) + c] : 0;
+            const int32_t e = i < w->cout ? cut[(size_t)i * (g.nchunks + 1) + c + 1] : 0;
+            const int32_t per = (e - b + ks - 1) / ks;
+            for (int s = 0; s < ks; ++s) {
+                const int32_t pb = (int32_t)std::min<int64_t>((int64_t)b + (int64_t)s * per, e);
+                const int32_t pe = (int32_t)std::min<int64_t>((int64_t)pb + per, e);
+                const size_t part = ((size_t)i * ks + s) * g.nchunks + c;
+                uint2* out = &nz[part * (size_t)stride];
+                for (int32_t j = pb; j < pe; ++j) {
+                    const int32_t k = w->col_idx[j];
+                    const int ci = k / taps - c * g.cch, r = (k % taps) / w->kw, cc = k % w->kw;
+                    const int phase = (r % g.S) * g.nphc + (cc % g.S);
+                    const int64_t off = ((int64_t)ci * g.plane + (int64_t)phase * g.sub + (r / g.S) * g.pitch + cc / g.S) * 4;
+                    uint32_t bits;
+                    std::memcpy(&bits, &w->vals[j], 4);
+                    out[j - pb] = make_uint2(bits, (uint32_t)off);
+                }
+                hdr[part * 2 + 0] = (pe - pb + U - 1) / U * U;
+                hdr[part * 2 + 1] = perm[i];
+            }
+        }
+    }
+    plan->variant = v;
+    plan->nchunks = (int)stride;
+    plan->rows_padded = rows_padded;
+    plan->nz_padded = (int64_t)nz.size();
+    cadnn_status st;
+    if ((st = plan->nz.upload(nz.data(), nz.size() * sizeof(uint2))) != CADNN_OK) return st;
+    if ((st = plan->seg_ptr.upload(hdr.data(), hdr.size() * 4)) != CADNN_OK) return st;
+    if ((st = plan->perm.upload(perm.data(), perm.size() * 4)) != CADNN_OK) return st;
+    return CADNN_OK;
+}
+
 // Device copy of the nonzero stream for a wave-sliced tile (FAM_STILE) variant.
 //
 // Packed rows are taken G at a time (G = rows per workgroup).  For group g and channel
@@ -354,9 +452,10 @@ static cadnn_status build_dense_plan(const cadnn_weights* w, const ConvVariant* 
     return st;
 }
 
-static cadnn_status build_plan(const cadnn_weights* w, const ConvVariant* v, const TensorDesc& xd,
-                               ConvPlan* plan) {
+static cadnn_status build_plan(const cadnn_weights* w, const ConvVariant* v, const TensorDesc& xd, int stride,
+                               int pad, int wout, ConvPlan* plan) {
     switch (v->family) {
+        case FAM_PTILE: return build_ptile_plan(w, v, stride, pad, wout, plan);
         case FAM_DENSE: return build_dense_plan(w, v, plan);
         case FAM_STILE: return build_stile_plan(w, v, plan);
         case FAM_DIRECT: return build_direct_plan(w, v, plan);
@@ -365,8 +464,12 @@ static cadnn_status build_plan(const cadnn_weights* w, const ConvVariant* v, con
     }
 }
 
-static PlanKey plan_key(const ConvVariant* v, const TensorDesc& xd) {
-    return v->family == FAM_LINEAR ? PlanKey(v, xd.plane, xd.pitch) : PlanKey(v, 0, 0);
+static PlanKey plan_key(const cadnn_weights* w, const ConvVariant* v, const TensorDesc& xd, int stride, int pad,
+                        int wout) {
+    if (v->family == FAM_LINEAR) return PlanKey(v, xd.plane, xd.pitch);
+    if (v->family == FAM_PTILE)
+        return PlanKey(v, stride, ptile_geom(*v, w->cin, w->kh, w->kw, stride, pad, wout).alias);
+    return PlanKey(v, 0, 0);
 }
 
 // Frees every plan whose variant is not pinned for some geometry of this handle.
@@ -379,17 +482,17 @@ void drop_unpinned_plans(const cadnn_weights* w) {
     }
 }
 
-cadnn_status get_conv_plan(const cadnn_weights* w, const ConvVariant* v, const TensorDesc& xd,
-                           const ConvPlan** out) {
+cadnn_status get_conv_plan(const cadnn_weights* w, const ConvVariant* v, const TensorDesc& xd, int stride,
+                           int pad, int wout, const ConvPlan** out) {
     std::lock_guard<std::mutex> lock(w->mu);
-    const PlanKey key = plan_key(v, xd);
+    const PlanKey key = plan_key(w, v, xd, stride, pad, wout);
     auto it = w->plans.find(key);
     if (it == w->plans.end()) {
         std::unique_ptr<ConvPlan> plan(new (std::nothrow) ConvPlan());
         if (!plan) return fail(CADNN_ENOMEM, "out of host memory");
         cadnn_status st;
         try {
-            st = build_plan(w, v, xd, plan.get());
+            st = build_plan(w, v, xd, stride, pad, wout, plan.get());
         } catch (const std::bad_alloc&) {
             return fail(CADNN_ENOMEM, "out of host memory building a conv plan");
         }

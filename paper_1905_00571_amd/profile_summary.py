@@ -6,6 +6,8 @@ Inputs (any subset):
   --stats  <..._kernel_stats.csv>        from  rocprofv3 --kernel-trace --stats --output-format csv
   --fetch  <..._counter_collection.csv>  from  rocprofv3 --pmc FETCH_SIZE --output-format csv
   --write  <..._counter_collection.csv>  from  rocprofv3 --pmc WRITE_SIZE --output-format csv
+  --pmc    <..._counter_collection.csv>  (repeatable) any other counter run: every counter in
+                                         it is averaged per dispatch and per kernel
 The two counter runs must come from `bench.py --calibrate-copy`, which also launches the
 library's plain copy kernel on a 256 MiB buffer: what the counters read for that known
 traffic gives the scale factor applied to every other kernel.
@@ -51,11 +53,34 @@ def read_counter(path, counter):
     return {k: {"dispatches": len(d), "avg_kib": sum(d.values()) / len(d)} for k, d in per.items()}
 
 
+def read_all_counters(path):
+    """{kernel: {counter: average value per dispatch}} for every counter in the file."""
+    per = defaultdict(lambda: defaultdict(lambda: defaultdict(float)))
+    with open(path) as f:
+        for r in csv.DictReader(f):
+            per[kernel_of(r["Kernel_Name"])][r["Counter_Name"]][r["Dispatch_Id"]] += float(r["Counter_Value"])
+    return {k: {c: sum(d.values()) / len(d) for c, d in cs.items()} for k, cs in per.items()}
+
+
+# (label, numerator, denominator): plain ratios of the raw per-dispatch averages above.  The
+# SQ "cycles" counters are sums over all SIMDs / CUs / dies in the tool's own units, so the
+# ratios are for comparing kernels with each other, not absolute utilisations.
+RATIOS = [
+    ("FMA share of VALU instructions", "SQ_INSTS_VALU_FMA_F32", "SQ_INSTS_VALU"),
+    ("VALU instructions per vector memory read", "SQ_INSTS_VALU", "SQ_INSTS_VMEM_RD"),
+    ("VALU active / busy-CU cycles", "SQ_ACTIVE_INST_VALU", "SQ_BUSY_CU_CYCLES"),
+    ("LDS bank-conflict / LDS active cycles", "SQ_LDS_BANK_CONFLICT", "SQ_ACTIVE_INST_LDS"),
+    ("MFMA busy / busy-CU cycles", "SQ_VALU_MFMA_BUSY_CYCLES", "SQ_BUSY_CU_CYCLES"),
+    ("L2 hit rate", "TCC_HIT_sum", None),
+]
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--stats")
     ap.add_argument("--fetch")
     ap.add_argument("--write")
+    ap.add_argument("--pmc", action="append", default=[])
     ap.add_argument("--command", action="append", default=[], help="command line(s) to record in the summary")
     ap.add_argument("--title", default="rocprofv3 summary")
     ap.add_argument("--out-txt", required=True)
@@ -92,6 +117,29 @@ def main() -> int:
         for k, v in sorted(c.items(), key=lambda kv: -kv[1]["avg_kib"] * kv[1]["dispatches"]):
             lines.append("%-28s %10d %14.1f %14.1f" % (k, v["dispatches"], v["avg_kib"], v["avg_kib"] * factor))
             traffic.setdefault(k, {})[label + "_bytes_per_launch"] = v["avg_kib"] * factor * 1024.0
+        lines.append("")
+    merged = defaultdict(dict)
+    for path in args.pmc:
+        for k, cs in read_all_counters(path).items():
+            merged[k].update(cs)
+    if merged:
+        names = sorted({c for cs in merged.values() for c in cs})
+        lines.append("other counters, average per dispatch (rocprofv3 --pmc, one run per counter group)")
+        for k in sorted(merged, key=lambda k: -merged[k].get("SQ_BUSY_CYCLES", merged[k].get("SQ_WAVES", 0.0))):
+            if not k.endswith("_kernel"):
+                continue
+            lines.append("  " + k)
+            for c in names:
+                if c in merged[k]:
+                    lines.append("    %-34s %16.1f" % (c, merged[k][c]))
+            for label, num, den in RATIOS:
+                if num in merged[k]:
+                    if den is None:
+                        tot = merged[k][num] + merged[k].get("TCC_MISS_sum", 0.0)
+                        if tot > 0:
+                            lines.append("    %-50s %8.3f" % (label, merged[k][num] / tot))
+                    elif merged[k].get(den, 0.0) > 0:
+                        lines.append("    %-50s %8.3f" % (label, merged[k][num] / merged[k][den]))
         lines.append("")
     for k, v in traffic.items():
         v["hbm_bytes_per_launch"] = v.get("fetch_bytes_per_launch", 0.0) + v.get("write_bytes_per_launch", 0.0)
