@@ -187,9 +187,13 @@ cadnn_status cadnn_net_workspace_bytes(const cadnn_net* net, size_t* bytes);
 /* flags: CADNN_NET_GRAPH -- cadnn_run_net replays a captured HIP graph (re-captured
  * when x / y change between calls); CADNN_NET_TUNE -- the first cadnn_run_net call
  * first runs cadnn_conv2d_tune on every convolution with the net's own buffers
- * (that first call synchronises and takes a fraction of a second). */
+ * (that first call synchronises and takes a fraction of a second);
+ * CADNN_NET_PLAIN_LAYOUT -- keep every intermediate tensor in plain (haloed) NCHW; by
+ * default the output of a convolution that is read by stride-2 convolutions is kept
+ * de-interleaved by row/column parity, so those layers read it with unit stride. */
 #define CADNN_NET_GRAPH 1
 #define CADNN_NET_TUNE 2
+#define CADNN_NET_PLAIN_LAYOUT 4
 cadnn_status cadnn_net_finalize(cadnn_net* net, void* workspace_dev, size_t bytes, int flags);
 cadnn_status cadnn_run_net(cadnn_net* net, const void* x, void* y, void* stream);
 /* Number of ops, and per-op device time: op i is launched `repeats` times back

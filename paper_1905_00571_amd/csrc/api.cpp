@@ -13,16 +13,17 @@ namespace cadnn {
 struct ConvGeom {
     int n, stride, pad, hout, wout;
     TensorDesc xd;
-    GeomKey key() const { return {n, xd.h, xd.w, stride, pad, xd.ph, xd.pw}; }
+    int out_s2d = 0;          // output or residual de-interleaved
+    GeomKey key() const { return {n, xd.h, xd.w, stride, pad, xd.ph, xd.pw, (xd.s2d ? 1 : 0) | (out_s2d ? 2 : 0)}; }
 };
 
 static cadnn_status check_conv(const char* who, const cadnn_weights* w, const TensorDesc& xd, int n,
-                               int stride, int pad, ConvGeom* g) {
+                               int stride, int pad, ConvGeom* g, int out_s2d = 0) {
     if (!w) return fail(CADNN_EINVAL, "%s: NULL weight handle", who);
     if (n <= 0 || xd.h <= 0 || xd.w <= 0) return fail(CADNN_EINVAL, "%s: non-positive size", who);
     if (stride <= 0 || pad < 0) return fail(CADNN_EINVAL, "%s: bad stride/pad", who);
     if (xd.c != w->cin) return fail(CADNN_EINVAL, "%s: %d input channels, weights take %d", who, xd.c, w->cin);
-    g->n = n; g->stride = stride; g->pad = pad; g->xd = xd;
+    g->n = n; g->stride = stride; g->pad = pad; g->xd = xd; g->out_s2d = out_s2d;
     g->hout = conv_out(xd.h, w->kh, stride, pad);
     g->wout = conv_out(xd.w, w->kw, stride, pad);
     if (g->hout <= 0 || g->wout <= 0) return fail(CADNN_EINVAL, "%s: empty output", who);
@@ -37,12 +38,32 @@ static bool variant_fits(const ConvVariant& v, const cadnn_weights* w, const Con
     if (v.is_f16 != (w->dtype == CADNN_F16)) return false;
     if (v.stride != 0 && v.stride != g.stride) return false;
     if ((w->cout + v.rows_per_block() - 1) / v.rows_per_block() > 65535) return false;
+    // de-interleaved tensors are understood by the linear-address kernels only
+    if ((g.xd.s2d || g.out_s2d) && v.family != FAM_LINEAR) return false;
     if (v.family == FAM_DENSE)
         return (double)w->nnz >= 0.25 * (double)w->cout * w->cin * w->kh * w->kw;
     if (v.family == FAM_LINEAR) {
-        if (v.adjacent && (g.stride != 1 || g.wout % v.p != 0)) return false;
+        const bool one = w->kh == 1 && w->kw == 1;
+        if (g.xd.s2d) {
+            // a stride-2 layer walks one phase per tap with unit stride (for filters larger
+            // than 1x1 the taps must start on an even padded position); a stride-1 layer can
+            // only be pixel-wise
+            if (g.stride == 2) {
+                if (!one && (((g.xd.ph - g.pad) & 1) || ((g.xd.pw - g.pad) & 1))) return false;
+            } else if (g.stride != 1 || !one) {
+                return false;
+            }
+        }
+        // Writing a de-interleaved tensor, or reading one pixel by pixel, takes the
+        // instantiations with the general address arithmetic; a stride-2 layer on a
+        // de-interleaved input is handed a plain view of the phase it starts in.
+        const bool general = g.out_s2d || (g.xd.s2d && g.stride == 1);
+        if (general != (v.s2d != 0)) return false;
+        // a lane's adjacent pixels must be adjacent in memory, on both sides
+        const int unit = g.xd.s2d ? 2 : 1;
+        if (v.adjacent && (g.stride != unit || g.wout % v.p != 0)) return false;
         // 1x1 filters read only the image proper; larger filters need the zero halo
-        if (w->kh == 1 && w->kw == 1) return g.pad == 0;
+        if (one) return g.pad == 0;
         return g.xd.ph >= g.pad && g.xd.pw >= g.pad;
     }
     if (v.family == FAM_PTILE) {
@@ -137,6 +158,14 @@ static cadnn_status launch_variant(const cadnn_weights* w, const ConvVariant* v,
     a.perm = (const int32_t*)plan->perm.p;
     a.xd = g.xd; a.yd = yd; a.rd = rd;
     a.n = g.n; a.cout = w->cout; a.stride = g.stride; a.pad = g.pad; a.relu = relu ? 1 : 0;
+    if (g.xd.s2d && g.stride == 2) {
+        // plain view for the kernel: unit stride over the rows of one phase, starting at the
+        // position of tap (0, 0) of output pixel (0, 0); the plan's tap offsets pick the phase
+        a.xd.origin = tensor_off(g.xd, -g.pad, -g.pad);
+        a.xd.s2d = 0;
+        a.stride = 1;
+        a.pad = 0;
+    }
     a.nchunks = plan->nchunks;
     a.kh = w->kh; a.kw = w->kw; a.is_f16 = w->dtype == CADNN_F16;
     a.hwout = g.hout * g.wout;
@@ -175,7 +204,7 @@ cadnn_status conv2d_impl(const cadnn_weights* w, const void* x, const TensorDesc
                          const TensorDesc& yd, const void* residual, const TensorDesc& rd, int n,
                          int stride, int pad, const void* bias, int relu, hipStream_t s) {
     ConvGeom g;
-    cadnn_status st = check_conv("cadnn_sparse_conv2d", w, xd, n, stride, pad, &g);
+    cadnn_status st = check_conv("cadnn_sparse_conv2d", w, xd, n, stride, pad, &g, yd.s2d || (residual && rd.s2d));
     if (st != CADNN_OK) return st;
     if ((st = check_io("cadnn_sparse_conv2d", w, g, x, y, yd, residual, rd)) != CADNN_OK) return st;
     const ConvVariant* v = pick_variant(w, g);
@@ -185,9 +214,10 @@ cadnn_status conv2d_impl(const cadnn_weights* w, const void* x, const TensorDesc
     return launch_variant(w, v, g, x, y, yd, residual, rd, bias, relu, s);
 }
 
-cadnn_status conv2d_prepare_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad) {
+cadnn_status conv2d_prepare_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad,
+                                 int out_s2d) {
     ConvGeom g;
-    cadnn_status st = check_conv("cadnn_conv2d_prepare", w, xd, n, stride, pad, &g);
+    cadnn_status st = check_conv("cadnn_conv2d_prepare", w, xd, n, stride, pad, &g, out_s2d);
     if (st != CADNN_OK) return st;
     const ConvVariant* v = pick_variant(w, g);
     if (!v)
@@ -197,9 +227,10 @@ cadnn_status conv2d_prepare_impl(const cadnn_weights* w, const TensorDesc& xd, i
     return get_conv_plan(w, v, xd, g.stride, g.pad, g.wout, &plan);
 }
 
-const char* conv2d_variant_name_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad) {
+const char* conv2d_variant_name_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad,
+                                     int out_s2d) {
     ConvGeom g;
-    if (check_conv("cadnn_net_op_variant", w, xd, n, stride, pad, &g) != CADNN_OK) return nullptr;
+    if (check_conv("cadnn_net_op_variant", w, xd, n, stride, pad, &g, out_s2d) != CADNN_OK) return nullptr;
     const ConvVariant* v = pick_variant(w, g);
     if (!v) {
         (void)fail(CADNN_EUNSUPPORTED, "no kernel for %dx%d filters with stride %d", w->kh, w->kw, stride);
@@ -209,10 +240,10 @@ const char* conv2d_variant_name_impl(const cadnn_weights* w, const TensorDesc& x
 }
 
 cadnn_status conv2d_list_variants_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad,
-                                       char* buf, size_t len) {
+                                       char* buf, size_t len, int out_s2d) {
     if (!buf || len == 0) return fail(CADNN_EINVAL, "cadnn_conv2d_list_variants: NULL buffer");
     ConvGeom g;
-    cadnn_status st = check_conv("cadnn_conv2d_list_variants", w, xd, n, stride, pad, &g);
+    cadnn_status st = check_conv("cadnn_conv2d_list_variants", w, xd, n, stride, pad, &g, out_s2d);
     if (st != CADNN_OK) return st;
     std::string all;
     for (const ConvVariant* v : candidates(w, g)) {
@@ -225,9 +256,9 @@ cadnn_status conv2d_list_variants_impl(const cadnn_weights* w, const TensorDesc&
 }
 
 cadnn_status conv2d_set_variant_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad,
-                                     const char* name) {
+                                     const char* name, int out_s2d) {
     ConvGeom g;
-    cadnn_status st = check_conv("cadnn_conv2d_set_variant", w, xd, n, stride, pad, &g);
+    cadnn_status st = check_conv("cadnn_conv2d_set_variant", w, xd, n, stride, pad, &g, out_s2d);
     if (st != CADNN_OK) return st;
     std::lock_guard<std::mutex> lock(w->mu);
     if (!name || !*name) {
@@ -248,7 +279,7 @@ cadnn_status conv2d_tune_impl(const cadnn_weights* w, const void* x, const Tenso
                               int stride, int pad, const void* bias, int relu, hipStream_t s, int reps,
                               float* best_us) {
     ConvGeom g;
-    cadnn_status st = check_conv("cadnn_conv2d_tune", w, xd, n, stride, pad, &g);
+    cadnn_status st = check_conv("cadnn_conv2d_tune", w, xd, n, stride, pad, &g, yd.s2d || (residual && rd.s2d));
     if (st != CADNN_OK) return st;
     if ((st = check_io("cadnn_conv2d_tune", w, g, x, y, yd, residual, rd)) != CADNN_OK) return st;
     if (reps <= 0) return fail(CADNN_EINVAL, "cadnn_conv2d_tune: reps must be positive");

@@ -29,10 +29,14 @@ constexpr uint32_t kLinOutOfRange = 0x7ffffff0u;   // beyond any buffer this lib
 // ADJ = 1: they are P adjacent pixels of one output row fetched with ONE P-element load
 //          (stride-1 layers whose output width is a multiple of P): fewer, wider loads and
 //          fewer cache lines touched per useful byte.
-template <typename T_, int P_, int RPW_, int KS_, int NW_, int U_, int ADJ_ = 0>
+// S2D = 1: the instantiation understands de-interleaved tensors (TensorDesc::s2d) on its
+//          output, residual and -- for pixel-wise layers -- input.  Kept apart because the
+//          general address arithmetic costs every launch a fraction of a microsecond.
+template <typename T_, int P_, int RPW_, int KS_, int NW_, int U_, int ADJ_ = 0, int S2D_ = 0>
 struct LinearCfg {
     using T = T_;
-    static constexpr int P = P_, RPW = RPW_, KS = KS_, NW = NW_, U = U_, ADJ = ADJ_;
+    static constexpr int P = P_, RPW = RPW_, KS = KS_, NW = NW_, U = U_, ADJ = ADJ_, S2D = S2D_;
+    static_assert(!(ADJ && S2D), "adjacent pixels are not adjacent in a de-interleaved tensor");
     static constexpr int RG = NW / KS;
     static constexpr int THREADS = NW * 64;
     static_assert(NW % KS == 0, "KS must divide the waves of a workgroup");
@@ -113,6 +117,23 @@ __device__ __forceinline__ void lin_fetch(__amdgpu_buffer_rsrc_t r, const uint32
     }
 }
 
+// Output pixel served by flattened index q.  Normally row-major.  A pixel-wise layer on a
+// de-interleaved input walks the pixels parity class by parity class instead (all pixels of
+// one row/column parity, row-major, then the next class), which is the order they lie in
+// memory: consecutive lanes then read consecutive elements again.
+__device__ __forceinline__ void lin_pixel(const ConvLaunch& a, int q, int& oh, int& ow) {
+    if (a.xd.s2d && a.stride == 1) {
+        const int w2 = a.yd.w >> 1, hw2 = (a.yd.h >> 1) * w2;
+        const int cls = q / hw2, rem = q - cls * hw2;
+        const int i2 = rem / w2, j2 = rem - i2 * w2;
+        oh = 2 * i2 + (cls >> 1);
+        ow = 2 * j2 + (cls & 1);
+    } else {
+        oh = q / a.yd.w;
+        ow = q - oh * a.yd.w;
+    }
+}
+
 template <class Cfg>
 __global__ __launch_bounds__(Cfg::THREADS) void sconv_linear_kernel(const ConvLaunch a) {
     using T = typename Cfg::T;
@@ -131,18 +152,29 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_linear_kernel(const ConvLa
     const int q0 = tile * (64 * P);
     const int row0 = (grp * RG + rg) * RPW;
 
-    // byte offset of tap (0,0) of each of the lane's pixels inside the padded image
+    // byte offset of tap (0,0) of each of the lane's pixels inside the padded image (in a
+    // de-interleaved input the taps of a stride-2 layer follow at the plan's offsets too)
     uint32_t voff[P];
     int oidx[P];
     const int base = a.xd.origin - a.pad * a.xd.pitch - a.pad;
 #pragma unroll
     for (int j = 0; j < P; ++j) {
         const int q = ADJ ? q0 + lane * P + j : q0 + j * 64 + lane;
-        const int oh = q / a.yd.w, ow = q - oh * a.yd.w;
-        oidx[j] = q < a.hwout ? oh * a.yd.pitch + ow : -1;
-        voff[j] = q < a.hwout
-                      ? (uint32_t)(base + oh * a.stride * a.xd.pitch + ow * a.stride) * (uint32_t)sizeof(T)
-                      : kLinOutOfRange;
+        int oh, ow;
+        if constexpr (Cfg::S2D) {
+            lin_pixel(a, q, oh, ow);
+            oidx[j] = q < a.hwout ? tensor_off(a.yd, oh, ow) : -1;
+            voff[j] = q < a.hwout
+                          ? (uint32_t)tensor_off(a.xd, oh * a.stride - a.pad, ow * a.stride - a.pad) * (uint32_t)sizeof(T)
+                          : kLinOutOfRange;
+        } else {
+            oh = q / a.yd.w;
+            ow = q - oh * a.yd.w;
+            oidx[j] = q < a.hwout ? a.yd.origin + oh * a.yd.pitch + ow : -1;
+            voff[j] = q < a.hwout
+                          ? (uint32_t)(base + oh * a.stride * a.xd.pitch + ow * a.stride) * (uint32_t)sizeof(T)
+                          : kLinOutOfRange;
+        }
     }
     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
         (void*)((const char*)a.x + (size_t)n * a.image_bytes), 0, a.image_bytes, 0x00020000);
@@ -169,13 +201,20 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_linear_kernel(const ConvLa
     for (int r = 0; r < RPW; ++r) bias_[r] = (a.bias && co_[r] >= 0) ? a.bias[co_[r]] : 0.0f;
 
     // the residual is also fetched up front: one more round trip off the tail
-    const T* __restrict__ res = a.residual ? (const T*)a.residual + (size_t)n * a.rd.image + a.rd.origin : nullptr;
+    const T* __restrict__ res = a.residual ? (const T*)a.residual + (size_t)n * a.rd.image : nullptr;
     float resv[RPW][P];
 #pragma unroll
     for (int j = 0; j < P; ++j) {
         const int q = ADJ ? q0 + lane * P + j : q0 + j * 64 + lane;
-        const int oh = q / a.yd.w, ow = q - oh * a.yd.w;
-        const int ridx = oh * a.rd.pitch + ow;
+        int oh, ow, ridx;
+        if constexpr (Cfg::S2D) {
+            lin_pixel(a, q, oh, ow);
+            ridx = tensor_off(a.rd, oh, ow);
+        } else {
+            oh = q / a.yd.w;
+            ow = q - oh * a.yd.w;
+            ridx = a.rd.origin + oh * a.rd.pitch + ow;
+        }
 #pragma unroll
         for (int r = 0; r < RPW; ++r)
             resv[r][j] = (res && ks == 0 && co_[r] >= 0 && oidx[j] >= 0) ? (float)res[(size_t)co_[r] * a.rd.plane + ridx] : 0.0f;
@@ -255,7 +294,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_linear_kernel(const ConvLa
     }
 
     // ---- fused epilogue: + bias, + residual, ReLU, store at the original channel
-    T* __restrict__ y = (T*)a.y + (size_t)n * a.yd.image + a.yd.origin;
+    T* __restrict__ y = (T*)a.y + (size_t)n * a.yd.image;
 #pragma unroll
     for (int r = 0; r < RPW; ++r) {
         const int co = co_[r];
@@ -291,6 +330,7 @@ static ConvVariant make_linear(const char* name) {
     v.p = Cfg::P; v.nw = Cfg::NW; v.rpw = Cfg::RPW; v.ks = Cfg::KS;
     v.unroll = Cfg::U;
     v.adjacent = Cfg::ADJ;
+    v.s2d = Cfg::S2D;
     v.lds_bytes = Cfg::KS > 1 ? (size_t)Cfg::NW * Cfg::RPW * Cfg::P * 64 * 4 : 0;
     v.launch = &launch_linear<Cfg>;
     return v;
@@ -302,7 +342,25 @@ static ConvVariant make_linear(const char* name) {
 #define CADNN_LINEAR_ADJ(T, P, RPW, KS, NW, U) \
     make_linear<LinearCfg<T, P, RPW, KS, NW, U, 1>>("slinear_" #T "_a" #P "_r" #RPW "k" #KS "w" #NW "u" #U)
 
+#define CADNN_LINEAR_S2D(T, P, RPW, KS, NW, U) \
+    make_linear<LinearCfg<T, P, RPW, KS, NW, U, 0, 1>>("slinear_" #T "_d" #P "_r" #RPW "k" #KS "w" #NW "u" #U)
+
 #define CADNN_LINEAR_SHAPES(T)          \
+    CADNN_LINEAR_S2D(T, 1, 1, 1, 4, 4), \
+    CADNN_LINEAR_S2D(T, 1, 1, 1, 4, 8), \
+    CADNN_LINEAR_S2D(T, 1, 1, 1, 4, 16), \
+    CADNN_LINEAR_S2D(T, 1, 1, 2, 4, 4), \
+    CADNN_LINEAR_S2D(T, 1, 1, 2, 4, 8), \
+    CADNN_LINEAR_S2D(T, 1, 1, 4, 4, 4), \
+    CADNN_LINEAR_S2D(T, 1, 1, 4, 4, 8), \
+    CADNN_LINEAR_S2D(T, 1, 1, 8, 8, 4), \
+    CADNN_LINEAR_S2D(T, 1, 2, 1, 4, 4), \
+    CADNN_LINEAR_S2D(T, 1, 2, 1, 4, 8), \
+    CADNN_LINEAR_S2D(T, 2, 1, 1, 4, 4), \
+    CADNN_LINEAR_S2D(T, 2, 1, 2, 4, 4), \
+    CADNN_LINEAR_S2D(T, 2, 1, 2, 4, 8), \
+    CADNN_LINEAR_S2D(T, 2, 1, 4, 4, 4), \
+    CADNN_LINEAR_S2D(T, 2, 2, 1, 4, 4), \
     CADNN_LINEAR_ADJ(T, 2, 1, 1, 4, 4), \
     CADNN_LINEAR_ADJ(T, 2, 1, 2, 4, 4), \
     CADNN_LINEAR_ADJ(T, 2, 1, 4, 4, 4), \

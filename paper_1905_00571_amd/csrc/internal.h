@@ -58,12 +58,27 @@ struct DevBuf {
 // ph = pw = 0 this is plain contiguous NCHW.  A halo (ph, pw > 0) is kept at zero by
 // whoever owns the buffer: kernels only ever write the image proper, so a consumer
 // convolution can read its zero padding from memory instead of testing bounds.
+//
+// De-interleaved layout (s2d = 1), for tensors read by stride-2 convolutions: the padded
+// plane is split by row and column parity into four sub-planes ("phases") of `sub`
+// elements and `pitch` elements per row each; padded position (R, C) sits at
+// ((R & 1) * 2 + (C & 1)) * sub + (R >> 1) * pitch + (C >> 1).  A stride-2 filter tap then
+// walks one phase with unit stride, so such a layer reads memory as densely as a stride-1
+// layer does (the paper's memory layout transformation, Section 4, applied to strides).
 struct TensorDesc {
     int c, h, w;
     int ph, pw;
     int pitch, plane, origin;
     int64_t image;      // elements between consecutive images
+    int s2d, sub;
 };
+
+// Element offset of image position (row, col) -- halo positions are row/col < 0 or
+// >= h/w -- from the start of its channel plane.
+__host__ __device__ inline int tensor_off(const TensorDesc& d, int row, int col) {
+    const int R = row + d.ph, C = col + d.pw;
+    return d.s2d ? ((R & 1) * 2 + (C & 1)) * d.sub + (R >> 1) * d.pitch + (C >> 1) : R * d.pitch + C;
+}
 
 inline TensorDesc make_desc(int c, int h, int w, int ph = 0, int pw = 0) {
     TensorDesc d;
@@ -72,6 +87,19 @@ inline TensorDesc make_desc(int c, int h, int w, int ph = 0, int pw = 0) {
     d.plane = (h + 2 * ph) * d.pitch;
     d.origin = ph * d.pitch + pw;
     d.image = (int64_t)c * d.plane;
+    d.s2d = 0; d.sub = 0;
+    return d;
+}
+
+inline TensorDesc make_desc_s2d(int c, int h, int w, int ph, int pw) {
+    TensorDesc d;
+    d.c = c; d.h = h; d.w = w; d.ph = ph; d.pw = pw;
+    d.pitch = (w + 2 * pw + 1) / 2;
+    d.sub = ((h + 2 * ph + 1) / 2) * d.pitch;
+    d.plane = 4 * d.sub;
+    d.origin = 0;
+    d.image = (int64_t)c * d.plane;
+    d.s2d = 1;
     return d;
 }
 
@@ -125,7 +153,8 @@ struct ConvVariant {
     int pitch, plane;     // LDS floats per tile row / per channel
     int elem_bytes;       // size of one staged tile element in LDS
     int unroll;           // nonzeros per scalar fetch; segments are padded to a multiple of it
-    int adjacent;         // FAM_LINEAR: a lane's P pixels are adjacent in one output row (stride 1 only)
+    int adjacent;         // FAM_LINEAR: a lane's P pixels are adjacent in one output row (unit stride only)
+    int s2d;              // FAM_LINEAR: understands de-interleaved output / residual / pixel-wise input
     int nz_cap;           // FAM_STILE: most stream entries per (row group, chunk) the kernel buffers
     size_t lds_bytes;
     hipError_t (*launch)(const ConvLaunch&, hipStream_t);
@@ -183,8 +212,9 @@ constexpr size_t kLdsBytesPerCU = 160 * 1024;
 // (variant, a, b): FAM_LINEAR a = input plane, b = input pitch; FAM_PTILE a = stride,
 // b = alias flag; 0, 0 for layout-independent plans
 typedef std::tuple<const ConvVariant*, int, int> PlanKey;
-// (n, h, w, stride, pad, input halo rows, input halo columns)
-typedef std::array<int, 7> GeomKey;
+// (n, h, w, stride, pad, input halo rows, input halo columns, layout flags: 1 = input
+// de-interleaved, 2 = output or residual de-interleaved)
+typedef std::array<int, 8> GeomKey;
 
 const std::vector<ConvVariant>& all_tile_variants();
 const std::vector<ConvVariant>& all_direct_variants();
@@ -241,12 +271,15 @@ cadnn_status conv2d_tune_impl(const cadnn_weights* w, const void* x, const Tenso
                               int stride, int pad, const void* bias, int relu, hipStream_t s, int reps,
                               float* best_us);
 // Name of the variant that would serve the layer (NULL if none).
-const char* conv2d_variant_name_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad);
+// `out_s2d`: the layer's output or residual is in the de-interleaved layout.
+const char* conv2d_variant_name_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad,
+                                     int out_s2d = 0);
 cadnn_status conv2d_list_variants_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad,
-                                       char* buf, size_t len);
+                                       char* buf, size_t len, int out_s2d = 0);
 cadnn_status conv2d_set_variant_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad,
-                                     const char* name);
-cadnn_status conv2d_prepare_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad);
+                                     const char* name, int out_s2d = 0);
+cadnn_status conv2d_prepare_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad,
+                                 int out_s2d = 0);
 cadnn_status dense_conv2d_desc(const void* w_dev, const void* x, const TensorDesc& xd, void* y,
                                const TensorDesc& yd, const void* residual, const TensorDesc& rd, int n,
                                int cout, int kh, int kw, int stride, int pad, const void* bias, int relu,

@@ -46,6 +46,7 @@ struct cadnn_net {
     bool finalized = false;
     bool use_graph = false;
     bool want_tune = false;
+    bool allow_s2d = true;
     char* ws = nullptr;
     hipGraphExec_t exec = nullptr;
     const void* cap_x = nullptr;
@@ -85,11 +86,37 @@ void layout(cadnn_net* net) {
             halo[op.src_inst] = std::max(halo[op.src_inst], op.pad);
     }
     if (nops) flat[nops - 1] = true;
+    // De-interleaved layout for the output of a convolution whose readers are all
+    // convolutions, at least one of them with stride 2: every reader must be either a
+    // stride-2 layer whose taps start on an even padded position (any 1x1; larger filters
+    // when halo - pad is even) or a pixel-wise stride-1 layer, and both the producer and
+    // the readers must be servable by the linear-address kernels.
+    std::vector<int> s2d(nops, 0), strided(nops, 0);
+    for (int i = 0; i < nops; ++i) {
+        const NetOp& p = net->ops[i];
+        bool ok = p.kind == OP_CONV && !flat[i] && (p.out.h % 2 == 0) && (p.out.w % 2 == 0);
+        if (ok) {
+            const bool one = p.w->kh == 1 && p.w->kw == 1;
+            const int src_halo = p.src_inst < 0 ? 0 : (flat[p.src_inst] ? 0 : halo[p.src_inst]);
+            ok = one ? p.pad == 0 : src_halo >= p.pad;
+        }
+        s2d[i] = ok ? 1 : 0;
+    }
+    for (const NetOp& op : net->ops) {
+        if (op.res_inst >= 0) s2d[op.res_inst] = 0;
+        if (op.src_inst < 0) continue;
+        const int i = op.src_inst;
+        if (op.kind != OP_CONV) { s2d[i] = 0; continue; }
+        const bool one = op.w->kh == 1 && op.w->kw == 1;
+        if (op.stride == 2 && (one ? op.pad == 0 : ((halo[i] - op.pad) & 1) == 0)) strided[i] = 1;
+        else if (!(op.stride == 1 && one && op.pad == 0)) s2d[i] = 0;
+    }
     size_t off = 0;
     for (int i = 0; i < nops; ++i) {
         NetOp& op = net->ops[i];
         const int hp = flat[i] ? 0 : halo[i];
-        op.yd = make_desc(op.out.c, op.out.h, op.out.w, hp, hp);
+        op.yd = (s2d[i] && strided[i] && net->allow_s2d) ? make_desc_s2d(op.out.c, op.out.h, op.out.w, hp, hp)
+                                                        : make_desc(op.out.c, op.out.h, op.out.w, hp, hp);
         op.y_off = off;
         if (i != nops - 1) off += ((size_t)op.out.n * op.yd.image * net->elem() + 255) / 256 * 256;
     }
@@ -103,6 +130,8 @@ void layout(cadnn_net* net) {
     net->ws_bytes = off;
     net->laid_out = true;
 }
+
+int out_s2d(const NetOp& op) { return (op.yd.s2d || (op.res >= 0 && op.rd.s2d)) ? 1 : 0; }
 
 const void* in_ptr(const cadnn_net* net, int inst, const void* x) {
     return inst < 0 ? x : (const void*)(net->ws + net->ops[inst].y_off);
@@ -249,7 +278,13 @@ extern "C" cadnn_status cadnn_net_workspace_bytes(const cadnn_net* net, size_t* 
 extern "C" cadnn_status cadnn_net_finalize(cadnn_net* net, void* ws, size_t bytes, int flags) {
     if (!net) return fail(CADNN_EINVAL, "cadnn_net_finalize: NULL net");
     if (net->ops.empty()) return fail(CADNN_EINVAL, "cadnn_net_finalize: empty net");
-    if (!net->laid_out) layout(net);
+    // (a plain layout never needs more room than the de-interleaved one that
+    // cadnn_net_workspace_bytes reports)
+    const bool allow = (flags & CADNN_NET_PLAIN_LAYOUT) == 0;
+    if (!net->laid_out || allow != net->allow_s2d) {
+        net->allow_s2d = allow;
+        layout(net);
+    }
     if (net->ws_bytes > 0 && !ws) return fail(CADNN_EINVAL, "cadnn_net_finalize: NULL workspace");
     if (bytes < net->ws_bytes) return fail(CADNN_EINVAL, "cadnn_net_finalize: workspace of %zu bytes, %zu needed", bytes, net->ws_bytes);
     drop_graph(net);
@@ -261,7 +296,7 @@ extern "C" cadnn_status cadnn_net_finalize(cadnn_net* net, void* ws, size_t byte
     }
     for (const NetOp& op : net->ops) {
         cadnn_status st = CADNN_OK;
-        if (op.kind == OP_CONV) st = conv2d_prepare_impl(op.w, op.xd, op.in.n, op.stride, op.pad);
+        if (op.kind == OP_CONV) st = conv2d_prepare_impl(op.w, op.xd, op.in.n, op.stride, op.pad, out_s2d(op));
         if (op.kind == OP_FC) st = cadnn_fc_prepare(op.w);
         if (st != CADNN_OK) return st;
     }
@@ -363,7 +398,7 @@ extern "C" cadnn_status cadnn_net_op_variant(const cadnn_net* net, int op_index,
     const NetOp& op = net->ops[op_index];
     const char* name = "";
     switch (op.kind) {
-        case OP_CONV: name = conv2d_variant_name_impl(op.w, op.xd, op.in.n, op.stride, op.pad); break;
+        case OP_CONV: name = conv2d_variant_name_impl(op.w, op.xd, op.in.n, op.stride, op.pad, out_s2d(op)); break;
         case OP_FC: name = "sfc"; break;
         case OP_MAXPOOL: name = "maxpool"; break;
         case OP_AVGPOOL: name = "avgpool"; break;
@@ -380,7 +415,7 @@ extern "C" cadnn_status cadnn_net_op_candidates(const cadnn_net* net, int op_ind
     if (op_index < 0 || op_index >= (int)net->ops.size()) return fail(CADNN_EINVAL, "cadnn_net_op_candidates: no op %d", op_index);
     const NetOp& op = net->ops[op_index];
     if (op.kind != OP_CONV) return fail(CADNN_EINVAL, "cadnn_net_op_candidates: op %d is not a convolution", op_index);
-    return conv2d_list_variants_impl(op.w, op.xd, op.in.n, op.stride, op.pad, buf, len);
+    return conv2d_list_variants_impl(op.w, op.xd, op.in.n, op.stride, op.pad, buf, len, out_s2d(op));
 }
 
 extern "C" cadnn_status cadnn_net_set_op_variant(cadnn_net* net, int op_index, const char* name) {
@@ -389,10 +424,10 @@ extern "C" cadnn_status cadnn_net_set_op_variant(cadnn_net* net, int op_index, c
     if (op_index < 0 || op_index >= (int)net->ops.size()) return fail(CADNN_EINVAL, "cadnn_net_set_op_variant: no op %d", op_index);
     const NetOp& op = net->ops[op_index];
     if (op.kind != OP_CONV) return fail(CADNN_EINVAL, "cadnn_net_set_op_variant: op %d is not a convolution", op_index);
-    cadnn_status st = conv2d_set_variant_impl(op.w, op.xd, op.in.n, op.stride, op.pad, name);
+    cadnn_status st = conv2d_set_variant_impl(op.w, op.xd, op.in.n, op.stride, op.pad, name, out_s2d(op));
     if (st != CADNN_OK) return st;
     drop_graph(net);
-    return conv2d_prepare_impl(op.w, op.xd, op.in.n, op.stride, op.pad);
+    return conv2d_prepare_impl(op.w, op.xd, op.in.n, op.stride, op.pad, out_s2d(op));
 }
 
 extern "C" cadnn_status cadnn_net_read_buffer(cadnn_net* net, int buf, void* host_out, size_t bytes,
@@ -407,6 +442,21 @@ extern "C" cadnn_status cadnn_net_read_buffer(cadnn_net* net, int buf, void* hos
     if (bytes != op.out.elems() * e)
         return fail(CADNN_EINVAL, "cadnn_net_read_buffer: buffer %d holds %zu bytes, %zu asked", buf, op.out.elems() * e, bytes);
     CADNN_HIP(hipStreamSynchronize((hipStream_t)stream));
+    if (op.yd.s2d) {
+        // de-interleaved region: fetch it whole and pick the image positions on the host
+        const size_t total = (size_t)op.out.n * op.yd.image * e;
+        std::vector<char> raw(total);
+        CADNN_HIP(hipMemcpy(raw.data(), net->ws + op.y_off, total, hipMemcpyDeviceToHost));
+        for (int n = 0; n < op.out.n; ++n)
+            for (int c = 0; c < op.out.c; ++c)
+                for (int i = 0; i < op.out.h; ++i)
+                    for (int j = 0; j < op.out.w; ++j) {
+                        const size_t src = ((size_t)n * op.yd.image + (size_t)c * op.yd.plane + tensor_off(op.yd, i, j)) * e;
+                        const size_t dst = ((((size_t)n * op.out.c + c) * op.out.h + i) * op.out.w + j) * e;
+                        std::memcpy((char*)host_out + dst, raw.data() + src, e);
+                    }
+        return CADNN_OK;
+    }
     // strip the halo: one 2-D copy per (image, channel) plane
     for (int n = 0; n < op.out.n; ++n)
         for (int c = 0; c < op.out.c; ++c) {

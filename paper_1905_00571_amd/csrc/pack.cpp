@@ -245,7 +245,10 @@ static cadnn_status build_linear_plan(const cadnn_weights* w, const ConvVariant*
             for (int32_t j = pb; j < pe; ++j) {
                 const int32_t k = w->col_idx[j];
                 const int ci = k / taps, r = (k % taps) / w->kw, c = k % w->kw;
-                const int64_t off = ((int64_t)ci * xd.plane + (int64_t)r * xd.pitch + c) * esz;
+                // de-interleaved input (stride-2 layers): the tap picks the phase
+                const int64_t tap = xd.s2d ? (int64_t)((r & 1) * 2 + (c & 1)) * xd.sub + (int64_t)(r >> 1) * xd.pitch + (c >> 1)
+                                           : (int64_t)r * xd.pitch + c;
+                const int64_t off = ((int64_t)ci * xd.plane + tap) * esz;
                 uint32_t bits;
                 std::memcpy(&bits, &w->vals[j], 4);
                 out[j - pb] = make_uint2(bits, (uint32_t)off);
@@ -466,7 +469,7 @@ static cadnn_status build_plan(const cadnn_weights* w, const ConvVariant* v, con
 
 static PlanKey plan_key(const cadnn_weights* w, const ConvVariant* v, const TensorDesc& xd, int stride, int pad,
                         int wout) {
-    if (v->family == FAM_LINEAR) return PlanKey(v, xd.plane, xd.pitch);
+    if (v->family == FAM_LINEAR) return PlanKey(v, xd.plane, xd.pitch | (xd.s2d ? 1 << 30 : 0));
     if (v->family == FAM_PTILE)
         return PlanKey(v, stride, ptile_geom(*v, w->cin, w->kh, w->kw, stride, pad, wout).alias);
     return PlanKey(v, 0, 0);

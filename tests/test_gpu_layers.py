@@ -309,3 +309,47 @@ def test_every_variant_on_a_haloed_input(cad, geom):
             mid = net.read_buffer(2, outs[1].shape)
             assert_layer_close(mid, outs[1], cond, tol, f"{geom} {name}", f16=dtype == cad.F16)
         net.free()
+
+
+@pytest.mark.parametrize("geom", [(12, 12, 1), (20, 28, 2), (14, 14, 3)])
+def test_every_variant_on_deinterleaved_tensors(cad, geom):
+    """The output of a convolution read by stride-2 convolutions is kept de-interleaved by
+    row/column parity inside a net.  A downsampling bottleneck (1x1 -> 3x3/2 -> 1x1 plus a
+    1x1/2 projection shortcut) behind a 1x1 producer exercises every role: writing such a
+    tensor, reading it pixel-wise, reading it with a strided 3x3 and with a strided 1x1.
+    Every variant that can serve each layer is pinned in turn and every intermediate tensor
+    is compared with the oracle; the same net in plain layout must agree."""
+    h, w_, n = geom
+    ops = [wl.Op("conv", "t", 0, 1, 8, 16, 1, 1, 0, 0.3, True),
+           wl.Op("conv", "a", 1, 2, 16, 8, 1, 1, 0, 0.4, True),
+           wl.Op("conv", "b", 2, 3, 8, 8, 3, 2, 1, 0.6, True),
+           wl.Op("conv", "p", 1, 4, 16, 16, 1, 2, 0, 0.5, False),
+           wl.Op("conv", "c", 3, 5, 8, 16, 1, 1, 0, 0.3, True, 4),
+           wl.Op("conv", "post", 5, 6, 16, 6, 1, 1, 0, 0.2, False)]
+    shape = (n, 8, h, w_)
+    x, ws, bs = wl.net_tensors(ops, "s2d-%d-%d" % (h, w_), shape, input_relu=True)
+    for dtype, npdt, tol in ((cad.F32, np.float32, TOL_F32), (cad.F16, np.float16, TOL_F16)):
+        xs = x.astype(npdt)
+        ref, ins, outs = oracle.run_net(ops, xs, ws, bs, dtype=npdt)
+        net = cad.build_net(ops, ws, bs, shape, dtype, use_graph=False)
+        plain = cad.build_net(ops, ws, bs, shape, dtype, use_graph=False, plain_layout=True)
+        xd = dev(xs)
+        for i in range(5):
+            names = net.op_candidates(i)
+            assert names and (i == 4 or all(nm.startswith("slinear") for nm in names)), (i, names)
+            r = outs[3] if ops[i].res >= 0 else None
+            cond = cond_conv(ins[i], ws[i].astype(npdt), bs[i], r, ops[i].stride, ops[i].pad)
+            for name in names:
+                net.set_op_variant(i, name)
+                assert net.op_variant(i) == name
+                net.run(xd)
+                torch.cuda.synchronize()
+                got = net.read_buffer(ops[i].dst, outs[i].shape)
+                assert_layer_close(got, outs[i], cond, tol, f"{geom} op {ops[i].name} {name}", f16=dtype == cad.F16)
+        y = net.run(xd)
+        yp = plain.run(xd)
+        torch.cuda.synchronize()
+        assert np.array_equal(y.cpu().numpy(), yp.cpu().numpy()) or np.allclose(
+            y.cpu().numpy().astype(np.float64), yp.cpu().numpy().astype(np.float64), rtol=0, atol=tol * np.abs(ref).max())
+        net.free()
+        plain.free()
