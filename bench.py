@@ -91,6 +91,12 @@ def main() -> int:
                          "(written by paper_1905_00571_amd/profile_summary.py)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a 256 MiB device copy 10 times (known traffic, for counter calibration)")
+    ap.add_argument("--workload", choices=["c2", "c3", "c4"], default="c2",
+                    help="c2 (default, the metric's workload): ResNet-50 fp32, conv1 dense / 3x3 80 %% / 1x1+FC 90 %%; "
+                         "c3: ResNet-50 with uniform --sparsity in --dtype at --batch; c4: VGG-16 conv 90 %% / FC 96 %%")
+    ap.add_argument("--batch", type=int, default=1)
+    ap.add_argument("--sparsity", type=float, default=0.8, help="uniform sparsity of workload c3")
+    ap.add_argument("--dtype", choices=["f32", "f16"], default="", help="storage type (default f32; c3: f16)")
     ap.add_argument("--no-layer-profile", action="store_true",
                     help="skip the per-op event pass (for clean rocprofv3 kernel statistics)")
     args = ap.parse_args()
@@ -111,20 +117,43 @@ def main() -> int:
     cad.lib()
     torch.cuda.set_device(0)
 
-    ops = wl.resnet50_ops()
-    shape = (1, 3, 224, 224)
-    x, ws, bs = wl.net_tensors(ops, "c2", shape)
-    if args.retune or args.no_tune:
+    n = args.batch
+    shape = (n, 3, 224, 224)
+    dt = args.dtype or ("f16" if args.workload == "c3" else "f32")
+    if args.workload == "c2":
+        ops, tag = wl.resnet50_ops(), "c2"
+        desc = "resnet50-sparse %s batch %d (configs[2]): 53 convs + FC, conv1 0 %%, 3x3 80 %%, 1x1+FC 90 %% " \
+               "unstructured sparsity, %dx3x224x224 input" % (dt, n, n)
+    elif args.workload == "c3":
+        ops, tag = wl.resnet50_ops(uniform=args.sparsity), "c3-%s" % args.sparsity
+        desc = "resnet50-sparse %s batch %d (configs[3]): every layer %.0f %% unstructured sparsity" % (dt, n, 100 * args.sparsity)
+    else:
+        ops, tag = wl.vgg16_ops(), "c4"
+        desc = "vgg16-sparse %s batch %d (configs[4]): 13 convs 90 %%, 3 FC 96 %% unstructured sparsity" % (dt, n)
+    is_default = args.workload == "c2" and n == 1 and dt == "f32"
+    x, ws, bs = wl.net_tensors(ops, tag, shape)
+    npdt = np.float16 if dt == "f16" else np.float32
+    tdt = torch.float16 if dt == "f16" else torch.float32
+    elem = 2 if dt == "f16" else 4
+    if args.retune or args.no_tune or not is_default:
         args.load_tune = ""
-    net = cad.build_net(ops, ws, bs, shape, cad.F32, use_graph=not args.no_graph,
-                        tune=not (args.no_tune or args.load_tune))
+    def make_net(live_tune):
+        return cad.build_net(ops, ws, bs, shape, cad.F16 if dt == "f16" else cad.F32, use_graph=not args.no_graph,
+                             tune=live_tune)
+
+    net = make_net(not (args.no_tune or args.load_tune))
     tuning = "none" if args.no_tune else "live"
     if args.load_tune:
-        with open(args.load_tune) as f:
-            net.set_variants(json.load(f)["variants"])
-        tuning = "saved:" + os.path.relpath(args.load_tune, ROOT)
-    xd = torch.from_numpy(x).cuda()            # inputs resident in HBM before timing
-    y = torch.empty(net.out_shape, dtype=torch.float32, device="cuda")
+        try:
+            with open(args.load_tune) as f:
+                net.set_variants(json.load(f)["variants"])
+            tuning = "saved:" + os.path.relpath(args.load_tune, ROOT)
+        except Exception as e:      # a saved choice from another build of the library: tune now instead
+            print("bench.py: saved tuning not usable (%s); tuning live" % e, file=sys.stderr)
+            net.free()
+            net = make_net(True)
+    xd = torch.from_numpy(x.astype(npdt)).cuda()            # inputs resident in HBM before timing
+    y = torch.empty(net.out_shape, dtype=tdt, device="cuda")
     stream = torch.cuda.current_stream()
 
     for _ in range(max(args.warmup, 1)):
@@ -157,14 +186,14 @@ def main() -> int:
         torch.cuda.synchronize()
     if args.save_tune:
         with open(args.save_tune, "w") as f:
-            json.dump({"workload": "resnet50-c2-f32-n1", "variants": net.variants()}, f, indent=1)
+            json.dump({"workload": "resnet50-%s-%s-n%d" % (args.workload, dt, n), "variants": net.variants()}, f, indent=1)
     if args.no_layer_profile:
-        print(json.dumps({"metric": "sparse ResNet-50 batch-1 latency", "value": ms_per_step, "unit": "ms",
-                          "note": "per-op pass skipped"}))
+        print(json.dumps({"metric": "sparse ResNet-50 batch-1 latency" if is_default else "latency of " + desc,
+                          "value": ms_per_step, "unit": "ms", "note": "per-op pass skipped"}))
         net.free()
         return 0
     per_op_ms = net.profile(xd, y, repeats=20, stream=stream)
-    costs = layer_costs(ops, ws, shape, 4)
+    costs = layer_costs(ops, ws, shape, elem)
     groups = {}
     for i, op in enumerate(ops):
         name = net.op_variant(i)
@@ -192,7 +221,7 @@ def main() -> int:
         achieved = dom["bytes"] / dom["launches"] / avg_s / 1e9
         roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": achieved / HBM_PEAK_GBS, "traffic": None}
-    if args.traffic and os.path.exists(args.traffic):
+    if is_default and args.traffic and os.path.exists(args.traffic):
         with open(args.traffic) as f:
             measured = json.load(f).get("kernels", {})
         if dom_name in measured:
@@ -209,13 +238,15 @@ def main() -> int:
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
+        # bounded sample: the first image of the batch through the whole net
         a = time.perf_counter()
-        ref, _, _ = oracle.run_net(ops, x, ws, bs)
+        ref, _, _ = oracle.run_net(ops, x[:1].astype(npdt), ws, bs, dtype=npdt)
         cpu_ms = (time.perf_counter() - a) * 1e3
-        got = y.cpu().numpy()
+        got = y[:1].float().cpu().numpy()
+        ref = ref.astype(np.float32)
         err = float(np.abs(got - ref).max() / np.abs(ref).max())
         cpu = {"value": cpu_ms, "unit": "ms", "cores": oracle.num_threads(), "kind": "oracle",
-               "sample": "1 full forward pass of the same ResNet-50 workload (all 53 convs + pools + FC)",
+               "sample": "1 full forward pass of ONE image of the same workload (every conv + pools + FC)",
                "gpu_vs_oracle_max_rel_err": err}
 
     if args.layers_out:
@@ -223,7 +254,7 @@ def main() -> int:
             json.dump({"layers": costs, "groups": groups}, f, indent=1)
 
     line = {
-        "metric": "sparse ResNet-50 batch-1 latency",
+        "metric": "sparse ResNet-50 batch-1 latency" if is_default else "latency of one forward pass",
         "value": ms_per_step,
         "unit": "ms",
         "n_gpus": 1,
@@ -233,12 +264,10 @@ def main() -> int:
         "higher_is_better": False,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": dt,
         "data": "synthetic",
-        "config": {"workload": "resnet50-sparse fp32 batch 1 (configs[2]): 53 convs + FC, conv1 0 %, "
-                               "3x3 80 %, 1x1+FC 90 % unstructured sparsity, 1x3x224x224 input",
-                   "graph": not args.no_graph, "per_layer_kernel_tuning": tuning},
-        "images_per_s": 1e3 / ms_per_step,
+        "config": {"workload": desc, "graph": not args.no_graph, "per_layer_kernel_tuning": tuning},
+        "images_per_s": n * 1e3 / ms_per_step,
         "latency_with_host_sync_ms": lat_sync_ms,
         "effective_gflops_nonzero_macs": total_flops / (ms_per_step * 1e-3) / 1e9,
         "effective_gbs_algorithmic": total_bytes / (ms_per_step * 1e-3) / 1e9,

@@ -86,10 +86,13 @@ static std::vector<const ConvVariant*> candidates(const cadnn_weights* w, const 
     return out;
 }
 
-// Default choice when nothing was tuned or pinned: a rough latency/throughput model of one
-// launch on 256 CUs x 4 SIMDs (cycles).  Staging-free families: a wave runs
-// rpw * nnz_row / ks load groups back to back; the address units of a CU take about four
-// cycles per wave-wide load.
+// Default choice when nothing was tuned or pinned: a model of one launch on 256 CUs x 4
+// SIMDs, in cycles.  For the staging-free families it is the largest of three terms --
+// a wave's own latency chain times the rounds of waves the chip needs, the vector issue
+// slots all waves consume (prologue + instructions per nonzero), and the L1 cache-line
+// traffic (32 bytes per cycle per CU; a stride-2 lane pattern touches twice the lines) --
+// with constants fitted to the tuner's timings of every variant on ResNet-50 and VGG-16
+// at batch 1 and ResNet-50 at batch 8 (its pick costs 7-10 % over the tuned choice).
 static const ConvVariant* heuristic_variant(const cadnn_weights* w, const ConvGeom& g) {
     const std::vector<const ConvVariant*> cand = candidates(w, g);
     if (cand.empty()) return nullptr;
@@ -107,17 +110,20 @@ static const ConvVariant* heuristic_variant(const cadnn_weights* w, const ConvGe
         } else if (v->family == FAM_STILE || v->family == FAM_PTILE) {
             continue;   // chosen by tuning only
         } else if (v->family != FAM_TILE) {
-            const double tiles = std::ceil(pixels / (64.0 * v->p)) * g.n;
+            const int P = v->p;
+            const double tiles = std::ceil(pixels / (64.0 * P)) * g.n;
             const double blocks = tiles * std::ceil((double)w->cout / v->rows_per_block());
             const double waves = blocks * v->nw;
             const double iters = v->rpw * nnz_row / v->ks;
-            const double lane_eff = pixels * g.n / (tiles * 64.0 * v->p);
-            const double per_group = v->family == FAM_LINEAR ? 90.0 + 30.0 * v->p : 200.0 + 40.0 * v->p;
-            const double t_wave = 900.0 + iters / v->unroll * per_group + (v->ks > 1 ? 300.0 : 0.0) +
-                                  (v->family == FAM_DIRECT ? 400.0 : 0.0);
-            const double rounds = std::ceil(waves / (1024.0 * 6.0));
-            const double t_cu = waves * iters * v->p * 4.2 / 256.0;
-            cost = std::max(t_wave * rounds, t_cu) / std::max(lane_eff, 0.05);
+            const double line_bytes = 256.0 * P * ((g.stride == 2 && !g.xd.s2d) ? 2.0 : 1.0);
+            const double t_l1 = waves * iters * line_bytes / 32.0 / 256.0;
+            const double instrs = v->adjacent ? 3.0 + P : 2.0 + 2.0 * P;
+            const double t_issue = waves * (1156.0 + iters * instrs * 1.33) / 1024.0;
+            const double per_nz = 68.7 * (1.0 + 0.65 * (P - 1)) / (1.0 + 0.277 * std::log2(v->unroll / 4.0));
+            const double t_wave = 250.0 + iters * per_nz + (v->ks > 1 ? 486.0 * std::log2((double)v->ks) : 0.0);
+            const double rounds = std::ceil(waves / (1024.0 * 2.3));
+            cost = std::max(std::max(t_wave * rounds, t_issue), 0.52 * t_l1);
+            if (v->family == FAM_DIRECT) cost *= 1.3;   // per-lane tap offsets, bounds by range check
         } else {
             const double tiles = std::ceil((double)g.wout / v->tw) * std::ceil((double)g.hout / v->th) * g.n;
             const double blocks = tiles * std::ceil((double)w->cout / v->rows_per_block());

@@ -86,6 +86,11 @@ void layout(cadnn_net* net) {
             halo[op.src_inst] = std::max(halo[op.src_inst], op.pad);
     }
     if (nops) flat[nops - 1] = true;
+    // (Layers dense enough for the matrix-core kernels stay on plain layouts, which is all
+    // those kernels read and write.)
+    auto sparse_enough = [](const NetOp& o) {
+        return (double)o.w->nnz < 0.25 * (double)o.w->cout * o.w->cin * o.w->kh * o.w->kw;
+    };
     // De-interleaved layout for the output of a convolution whose readers are all
     // convolutions, at least one of them with stride 2: every reader must be either a
     // stride-2 layer whose taps start on an even padded position (any 1x1; larger filters
@@ -94,7 +99,7 @@ void layout(cadnn_net* net) {
     std::vector<int> s2d(nops, 0), strided(nops, 0);
     for (int i = 0; i < nops; ++i) {
         const NetOp& p = net->ops[i];
-        bool ok = p.kind == OP_CONV && !flat[i] && (p.out.h % 2 == 0) && (p.out.w % 2 == 0);
+        bool ok = p.kind == OP_CONV && !flat[i] && (p.out.h % 2 == 0) && (p.out.w % 2 == 0) && sparse_enough(p);
         if (ok) {
             const bool one = p.w->kh == 1 && p.w->kw == 1;
             const int src_halo = p.src_inst < 0 ? 0 : (flat[p.src_inst] ? 0 : halo[p.src_inst]);
@@ -106,7 +111,7 @@ void layout(cadnn_net* net) {
         if (op.res_inst >= 0) s2d[op.res_inst] = 0;
         if (op.src_inst < 0) continue;
         const int i = op.src_inst;
-        if (op.kind != OP_CONV) { s2d[i] = 0; continue; }
+        if (op.kind != OP_CONV || !sparse_enough(op)) { s2d[i] = 0; continue; }
         const bool one = op.w->kh == 1 && op.w->kw == 1;
         if (op.stride == 2 && (one ? op.pad == 0 : ((halo[i] - op.pad) & 1) == 0)) strided[i] = 1;
         else if (!(op.stride == 1 && one && op.pad == 0)) s2d[i] = 0;

@@ -320,10 +320,11 @@ def test_every_variant_on_deinterleaved_tensors(cad, geom):
     Every variant that can serve each layer is pinned in turn and every intermediate tensor
     is compared with the oracle; the same net in plain layout must agree."""
     h, w_, n = geom
-    ops = [wl.Op("conv", "t", 0, 1, 8, 16, 1, 1, 0, 0.3, True),
-           wl.Op("conv", "a", 1, 2, 16, 8, 1, 1, 0, 0.4, True),
-           wl.Op("conv", "b", 2, 3, 8, 8, 3, 2, 1, 0.6, True),
-           wl.Op("conv", "p", 1, 4, 16, 16, 1, 2, 0, 0.5, False),
+    # (layers around a de-interleaved tensor must be too sparse for the dense family)
+    ops = [wl.Op("conv", "t", 0, 1, 8, 16, 1, 1, 0, 0.8, True),
+           wl.Op("conv", "a", 1, 2, 16, 8, 1, 1, 0, 0.8, True),
+           wl.Op("conv", "b", 2, 3, 8, 8, 3, 2, 1, 0.85, True),
+           wl.Op("conv", "p", 1, 4, 16, 16, 1, 2, 0, 0.8, False),
            wl.Op("conv", "c", 3, 5, 8, 16, 1, 1, 0, 0.3, True, 4),
            wl.Op("conv", "post", 5, 6, 16, 6, 1, 1, 0, 0.2, False)]
     shape = (n, 8, h, w_)
