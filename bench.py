@@ -97,6 +97,10 @@ def main() -> int:
     ap.add_argument("--batch", type=int, default=1)
     ap.add_argument("--sparsity", type=float, default=0.8, help="uniform sparsity of workload c3")
     ap.add_argument("--dtype", choices=["f32", "f16"], default="", help="storage type (default f32; c3: f16)")
+    ap.add_argument("--dense-compare", action="store_true",
+                    help="also time every distinct convolution of the workload as a DENSE layer on the same GPU: "
+                         "the library's own MFMA implicit GEMM and MIOpen through torch.nn.functional.conv2d "
+                         "(the only use of torch compute anywhere: a comparator)")
     ap.add_argument("--no-layer-profile", action="store_true",
                     help="skip the per-op event pass (for clean rocprofv3 kernel statistics)")
     args = ap.parse_args()
@@ -192,6 +196,28 @@ def main() -> int:
                           "value": ms_per_step, "unit": "ms", "note": "per-op pass skipped"}))
         net.free()
         return 0
+    # cold caches: a 512 MiB copy (twice the Infinity Cache) before every pass, the pass
+    # itself timed with events on the launch stream; the copy also gives an achieved HBM rate
+    big_a = torch.empty(512 << 20, dtype=torch.uint8, device="cuda")
+    big_b = torch.empty(512 << 20, dtype=torch.uint8, device="cuda")
+    big_a.zero_()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    e2 = torch.cuda.Event(enable_timing=True)
+    cold, copy_ms = [], []
+    for _ in range(20):
+        e0.record(stream)
+        cad.cadnn_device_copy(big_a, big_b, stream)
+        e1.record(stream)
+        net.run(xd, y, stream)
+        e2.record(stream)
+        torch.cuda.synchronize()
+        copy_ms.append(e0.elapsed_time(e1))
+        cold.append(e1.elapsed_time(e2))
+    lat_cold_ms = float(np.median(cold))
+    copy_gbs = 2.0 * (512 << 20) / (float(np.median(copy_ms)) * 1e-3) / 1e9
+    del big_a, big_b
+
     per_op_ms = net.profile(xd, y, repeats=20, stream=stream)
     costs = layer_costs(ops, ws, shape, elem)
     groups = {}
@@ -231,6 +257,57 @@ def main() -> int:
                      "algorithmic_flops_per_launch": dom["flops"] / dom["launches"],
                      "algorithmic_bytes_per_launch": dom["bytes"] / dom["launches"]})
 
+    roofline["frac_of_measured_copy_rate"] = (roofline["achieved"] / copy_gbs) if roofline["bound"] == "hbm" else None
+
+    # ---- the same layers as dense convolutions on this GPU (comparators)
+    dense_cmp = None
+    if args.dense_compare:
+        torch.backends.cudnn.benchmark = True
+
+        def time_us(fn, reps=30):
+            for _ in range(5):
+                fn()
+            a_ = torch.cuda.Event(enable_timing=True)
+            b_ = torch.cuda.Event(enable_timing=True)
+            a_.record(stream)
+            for _ in range(reps):
+                fn()
+            b_.record(stream)
+            torch.cuda.synchronize()
+            return a_.elapsed_time(b_) * 1e3 / reps
+
+        memo = {}
+        tot = {"sparse": 0.0, "mfma": 0.0, "miopen": 0.0}
+        wins = cnt = 0
+        for i, op in enumerate(ops):
+            if op.kind != "conv":
+                continue
+            nn_, c_, h_, w_ = costs[i]["in"]
+            key = (c_, op.cout, op.k, op.stride, op.pad, h_, w_)
+            if key not in memo:
+                xin = torch.randn(nn_, c_, h_, w_, device="cuda").relu_().to(tdt)
+                wd = torch.from_numpy(ws[i]).cuda().to(tdt)
+                bd = torch.from_numpy(bs[i]).cuda()
+                yo = torch.empty(costs[i]["out"], dtype=tdt, device="cuda")
+                t_mfma = time_us(lambda: cad.cadnn_dense_conv2d(wd, xin, op.stride, op.pad, bd, None, True, out=yo,
+                                                                stream=stream))
+                bt = bd.to(tdt)
+                t_mio = time_us(lambda: torch.relu_(torch.nn.functional.conv2d(xin, wd, bt, stride=op.stride,
+                                                                                padding=op.pad)))
+                memo[key] = (t_mfma, t_mio)
+            costs[i]["dense_mfma_us"], costs[i]["miopen_us"] = memo[key]
+            density = costs[i]["nnz"] / float(ws[i].size)
+            if density <= 0.2001:              # layers pruned to >= 80 % sparsity (up to nnz rounding)
+                cnt += 1
+                tot["sparse"] += costs[i]["ms"] * 1e3
+                tot["mfma"] += memo[key][0]
+                tot["miopen"] += memo[key][1]
+                wins += int(costs[i]["ms"] * 1e3 < min(memo[key]))
+        dense_cmp = {"layers_at_80pct_or_more": cnt, "sparse_faster_than_both_on": wins,
+                     "sum_sparse_us": tot["sparse"], "sum_own_mfma_dense_us": tot["mfma"],
+                     "sum_miopen_dense_us": tot["miopen"],
+                     "note": "per-layer times, back-to-back launches; dense layers get the unpruned-shape weights"}
+
     total_flops = sum(c["flops"] for c in costs)
     total_bytes = sum(c["bytes"] for c in costs)
 
@@ -269,6 +346,9 @@ def main() -> int:
         "config": {"workload": desc, "graph": not args.no_graph, "per_layer_kernel_tuning": tuning},
         "images_per_s": n * 1e3 / ms_per_step,
         "latency_with_host_sync_ms": lat_sync_ms,
+        "latency_cold_caches_ms": lat_cold_ms,
+        "measured_copy_rate_gbs": copy_gbs,
+        "dense_comparison": dense_cmp,
         "effective_gflops_nonzero_macs": total_flops / (ms_per_step * 1e-3) / 1e9,
         "effective_gbs_algorithmic": total_bytes / (ms_per_step * 1e-3) / 1e9,
         "sum_of_kernel_ms": float(per_op_ms.sum()),
