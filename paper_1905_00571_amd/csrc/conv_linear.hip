@@ -10,8 +10,9 @@
 // paper's redundant filter-load elimination, Section 4).  The (value, offset) pairs are
 // streamed with coalesced vector loads, 64 pairs per wave-wide load and one such load
 // ahead, and broadcast to scalar registers lane by lane: a scalar load per group of
-// nonzeros would expose a cache-miss latency every few FMAs.  A 1x1 layer is the same loop: a sparse-matrix x dense-matrix product
-// (Section 4: 1x1 convolution as matrix multiply).  Keeping the halo of every activation
+// nonzeros would expose a cache-miss latency every few FMAs.  A 1x1 layer is the same
+// loop: a sparse-matrix x dense-matrix product (Section 4: 1x1 convolution as matrix
+// multiply).  Keeping the halo of every activation
 // buffer at zero is the layout transformation ("padding", Section 4) that removes the
 // irregular border handling from the hot loop.
 //
@@ -144,10 +145,10 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_linear_kernel(const ConvLa
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int rg = wv / KS, ks = wv % KS;
     const int n = blockIdx.z;
-    // Workgroups in plain launch order.  (Die-aware placements were measured: giving each
-    // of the 8 dies its own pixel tiles made the whole net 2.5x slower -- every CU of a die
-    // then hammers the same few L2 channels -- and giving each die its own rows changed
-    // nothing.)
+    // Workgroups in plain launch order.  (Die-aware placements were measured -- workgroup
+    // L runs on die L % 8: giving each die its own pixel tiles leaves most of the chip idle
+    // on layers with few tiles and gains nothing on the others, and giving each die its
+    // own rows changes nothing.)
     const int tile = blockIdx.x, grp = blockIdx.y;
     const int q0 = tile * (64 * P);
     const int row0 = (grp * RG + rg) * RPW;

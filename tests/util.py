@@ -1,6 +1,6 @@
 """Helpers shared by the parity tests.
 
-Tolerance (written here, derived in DESIGN.md "Parity bar").  The stated bar is a maximum
+Tolerance.  The stated bar is a maximum
 relative error of 1e-4 for fp32 outputs and 1e-2 for the fp16-storage variant.  It is
 enforced in two ways:
 
