@@ -70,7 +70,7 @@ static bool variant_fits(const ConvVariant& v, const cadnn_weights* w, const Con
         // staging pays only when a staged element is reused by several taps
         if (w->kh * w->kw == 1) return false;
         const PtileGeom pg = ptile_geom(v, w->cin, w->kh, w->kw, g.stride, g.pad, g.wout);
-        return pg.nstp <= kPtileMaxSteps && (size_t)pg.plane * 4 <= kLdsBytesPerCU;
+        return pg.nstp <= kPtileMaxSteps && (int64_t)pg.plane * 4 <= (int64_t)kLdsBytesPerCU;
     }
     return v.kh == w->kh && v.kw == w->kw;
 }
@@ -178,12 +178,13 @@ static cadnn_status launch_variant(const cadnn_weights* w, const ConvVariant* v,
     a.image_bytes = (uint32_t)(g.xd.image * (int64_t)w->elem());
     if (v->family == FAM_PTILE) {
         const PtileGeom pg = ptile_geom(*v, w->cin, w->kh, w->kw, g.stride, g.pad, g.wout);
-        a.tiles_x = (g.wout + 7 * v->p - 1) / (7 * v->p);
-        a.tiles_y = (g.hout + 6) / 7;
+        a.tiles_x = (g.wout + pg.tile_w - 1) / pg.tile_w;
+        a.tiles_y = (g.hout + pg.tile_h - 1) / pg.tile_h;
         a.pt_pitch = pg.pitch; a.pt_sub = pg.sub; a.pt_plane = pg.plane; a.pt_nphc = pg.nphc;
         a.pt_nph = pg.nphr * pg.nphc; a.pt_in_rows = pg.in_rows; a.pt_in_cols = pg.alias ? pg.in_cols - 1 : pg.in_cols;
         a.pt_cch = pg.cch; a.pt_nstp = pg.nstp; a.pt_nchunks = pg.nchunks;
         a.pt_lds_bytes = (uint32_t)pg.lds_bytes;
+        a.pt_nbuf = pg.nbuf;
     } else if (v->family == FAM_TILE || v->family == FAM_STILE) {
         a.tiles_x = (g.wout + v->tw - 1) / v->tw;
         a.tiles_y = (g.hout + v->th - 1) / v->th;

@@ -28,20 +28,24 @@ constexpr uint32_t kPtOutOfRange = 0x7ffffff0u;
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
-template <typename T_, int P_, int RPW_, int KS_, int NW_, int U_>
+template <typename T_, int P_, int RPW_, int KS_, int NW_, int U_, int LW_ = 8>
 struct PtileCfg {
     using T = T_;
-    static constexpr int P = P_, RPW = RPW_, KS = KS_, NW = NW_, U = U_;
+    static constexpr int P = P_, RPW = RPW_, KS = KS_, NW = NW_, U = U_, LW = LW_;
+    // LDS bytes between the pixels of a lane: 7 words to the right (LW = 8) or 4 rows of
+    // 16 words further down (LW = 16)
+    static constexpr int STEP = LW == 16 ? 4 * 16 * 4 : 7 * 4;
+    static_assert(LW == 8 || LW == 16, "lane grid width");
     static constexpr int RG = NW / KS;
     static constexpr int THREADS = NW * 64;
     static_assert(NW % KS == 0, "KS must divide the waves of a workgroup");
 };
 
-template <int P>
+template <int P, int STEP>
 __device__ __forceinline__ void pt_fetch(const char* lane_ptr, uint32_t off, float (&x)[P]) {
     const char* p = lane_ptr + off;
 #pragma unroll
-    for (int j = 0; j < P; ++j) x[j] = *(const float*)(p + j * 28);
+    for (int j = 0; j < P; ++j) x[j] = *(const float*)(p + j * STEP);
 }
 
 // Broadcasts entries l0 .. l0+U-1 of a 64-entry window held one entry per lane.
@@ -54,18 +58,18 @@ __device__ __forceinline__ void pt_group(const uint2& win, int l0, float (&w)[U]
     }
 }
 
-// Up to 64 entries of one window against the P pixels of a lane, U at a time: U LDS reads
+// Entries l0 .. l1-1 of one window against the P pixels of a lane, U at a time: U LDS reads
 // in flight, then U FMAs per pixel.  The LDS latency of a group is covered by the other
 // waves of the SIMD (a hand-pipelined loop made the compiler serialise the reads on false
 // register hazards).
-template <int U, int P>
-__device__ __forceinline__ void pt_window(const uint2& win, int count, const char* lane_ptr, float (&acc)[P]) {
-    for (int l0 = 0; l0 < count; l0 += U) {
+template <int U, int P, int STEP>
+__device__ __forceinline__ void pt_window(const uint2& win, int l0, int l1, const char* lane_ptr, float (&acc)[P]) {
+    for (; l0 < l1; l0 += U) {
         float w[U], x[U][P];
         uint32_t o[U];
         pt_group<U>(win, l0, w, o);
 #pragma unroll
-        for (int u = 0; u < U; ++u) pt_fetch<P>(lane_ptr, o[u], x[u]);
+        for (int u = 0; u < U; ++u) pt_fetch<P, STEP>(lane_ptr, o[u], x[u]);
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
@@ -95,43 +99,45 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_ptile_kernel(const ConvLau
     const int row0 = (blockIdx.y * RG + rg) * RPW;
     const int nchunks = a.pt_nchunks;
 
-    // ---- the plan's stream and headers are requested first: they do not depend on the tile
-    const int stride = a.nchunks;
-    const int2* __restrict__ hdr = (const int2*)a.seg_ptr;
-    const uint2* __restrict__ nzl = a.nz + lane;
-    // the two windows of the wave's first part; later parts fetch theirs when they start
-    const int first = ((row0 + 0) * KS + ks) * nchunks * stride;
-    uint2 winA = nzl[first], winB = nzl[first + 64];
-    int co_[RPW], len0_[RPW];
+    // ---- the wave's stream and part lengths are requested first: they do not depend on
+    //      the tile.  A wave's parts (chunk by chunk, row by row within a chunk) lie back to
+    //      back in one stream of fixed stride per wave, so two 64-entry windows can run
+    //      ahead of the consumption across part boundaries without ever stalling on them.
+    const int wsi = (blockIdx.y * RG + rg) * KS + ks;        // wave stream index
+    const uint2* __restrict__ nzl = a.nz + (size_t)wsi * a.nchunks + lane;
+    uint2 winA = nzl[0], winB = nzl[64];
+    const int32_t* __restrict__ lens = a.seg_ptr + (size_t)wsi * nchunks * RPW;
+    int co_[RPW], len_[RPW];
     float bias_[RPW];
 #pragma unroll
     for (int r = 0; r < RPW; ++r) {
-        const int2 h = hdr[((row0 + r) * KS + ks) * nchunks];
-        len0_[r] = h.x;
-        co_[r] = h.y;
+        co_[r] = a.perm[row0 + r];
+        len_[r] = lens[r];
     }
 #pragma unroll
     for (int r = 0; r < RPW; ++r) bias_[r] = (a.bias && co_[r] >= 0) ? a.bias[co_[r]] : 0.0f;
 
     // ---- lane -> pixels
-    const int li = lane >> 3, lj = lane & 7;
-    const int oh = ty * 7 + li;
-    int oidx[P];
+    constexpr int LW = Cfg::LW;
+    constexpr int TILE_H = LW == 16 ? 4 * P : 7, TILE_W = LW == 16 ? 14 : 7 * P, USED = LW == 16 ? 14 : 7;
+    const int li = lane / LW, lj = lane % LW;
+    const bool lane_used = lj < USED && (LW == 16 || li < 7);
+    int oidx[P], orow[P], ocol[P];
 #pragma unroll
     for (int j = 0; j < P; ++j) {
-        const int ow = tx * (7 * P) + j * 7 + lj;
-        oidx[j] = (li < 7 && lj < 7 && oh < a.yd.h && ow < a.yd.w) ? oh * a.yd.pitch + ow : -1;
+        orow[j] = ty * TILE_H + li + (LW == 16 ? 4 * j : 0);
+        ocol[j] = tx * TILE_W + lj + (LW == 16 ? 0 : 7 * j);
+        oidx[j] = (lane_used && orow[j] < a.yd.h && ocol[j] < a.yd.w) ? orow[j] * a.yd.pitch + ocol[j] : -1;
     }
-    // (the unused lanes of the 8 x 8 grid read the tile origin: harmless and in range)
-    const char* lane_ptr = (const char*)tile + ((li < 7 && lj < 7) ? (li * a.pt_pitch + lj) * 4 : 0);
+    // (the unused lanes of the grid read the tile origin: harmless and in range)
+    const char* lane_ptr = (const char*)tile + (lane_used ? (li * a.pt_pitch + lj) * 4 : 0);
 
     // ---- residual up front: one more round trip off the tail
     const T* __restrict__ res = a.residual ? (const T*)a.residual + (size_t)n * a.rd.image + a.rd.origin : nullptr;
     float resv[RPW][P];
 #pragma unroll
     for (int j = 0; j < P; ++j) {
-        const int ow = tx * (7 * P) + j * 7 + lj;
-        const int ridx = oh * a.rd.pitch + ow;
+        const int ridx = orow[j] * a.rd.pitch + ocol[j];
 #pragma unroll
         for (int r = 0; r < RPW; ++r)
             resv[r][j] = (res && ks == 0 && co_[r] >= 0 && oidx[j] >= 0) ? (float)res[(size_t)co_[r] * a.rd.plane + ridx] : 0.0f;
@@ -140,8 +146,8 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_ptile_kernel(const ConvLau
     // ---- staging offsets: tile word p = lane + 64*t of a channel plane comes from here
     uint32_t goff[kPtileMaxSteps];
     {
-        const int r_base = ty * 7 * a.stride - a.pad;          // image row of region row 0
-        const int c_base = tx * (7 * P) * a.stride - a.pad;
+        const int r_base = ty * TILE_H * a.stride - a.pad;     // image row of region row 0
+        const int c_base = tx * TILE_W * a.stride - a.pad;
 #pragma unroll
         for (int t = 0; t < kPtileMaxSteps; ++t) {
             const int p = lane + 64 * t;
@@ -170,27 +176,26 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_ptile_kernel(const ConvLau
 #pragma unroll
         for (int j = 0; j < P; ++j) acc[r][j] = 0.0f;
 
-    for (int c = 0; c < nchunks; ++c) {
-        // ---- stage chunk c: wave w takes channels w, w + NW, ... of the chunk
-        if (c > 0) __syncthreads();      // everyone is done reading the previous chunk
+    // Staging of one chunk.  fp32: `buffer_load ... lds` moves 64 words per instruction
+    // from per-lane global offsets straight to consecutive LDS words, with no register in
+    // between, so a wave keeps all the loads of its channels in flight at once (lanes past
+    // the end of a plane are masked off: they would land on the next channel) -- and the
+    // kernel goes on computing on the other buffer meanwhile.  fp16: through registers,
+    // widened to fp32 on the way, four channels at a time.
+    const int chunk_words = a.pt_cch * a.pt_plane;
+    auto stage = [&](int c, float* buf) {
         const int ch0 = c * a.pt_cch;
         const int cch = min(a.pt_cch, cin - ch0);
         if constexpr (sizeof(T) == 4) {
-            // fp32: `buffer_load ... lds` moves 64 words per instruction from per-lane global
-            // offsets straight to consecutive LDS words, with no register in between, so a
-            // wave keeps all the loads of its channels in flight at once.  Lanes past the
-            // end of the plane are masked off (they would land on the next channel).
             for (int ch = wv; ch < cch; ch += NW) {
                 const uint32_t soff = (uint32_t)(ch0 + ch) * plane_bytes;
 #pragma unroll
                 for (int t = 0; t < kPtileMaxSteps; ++t)
                     if (t < a.pt_nstp && lane + 64 * t < a.pt_plane)
-                        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)(tile + ch * a.pt_plane + 64 * t), 4,
+                        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)(buf + ch * a.pt_plane + 64 * t), 4,
                                                                  goff[t], soff, 0, 0);
             }
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         } else {
-            // fp16: through registers (converted to fp32 on the way), four channels at a time
             for (int ch = wv; ch < cch; ch += 4 * NW) {
                 float v[4][kPtileMaxSteps];
 #pragma unroll
@@ -207,35 +212,60 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_ptile_kernel(const ConvLau
 #pragma unroll
                     for (int t = 0; t < kPtileMaxSteps; ++t) {
                         const int p = lane + 64 * t;
-                        if (t < a.pt_nstp && p < a.pt_plane) tile[(ch + k * NW) * a.pt_plane + p] = v[k][t];
+                        if (t < a.pt_nstp && p < a.pt_plane) buf[(ch + k * NW) * a.pt_plane + p] = v[k][t];
                     }
                 }
             }
         }
-        __syncthreads();
+    };
+
+    // fp32 with several chunks: two LDS buffers, chunk c+1 lands while chunk c is consumed
+    // (one barrier per chunk); otherwise one buffer, staged and consumed in turn.
+    const bool twobuf = sizeof(T) == 4 && a.pt_nbuf == 2;
+    int pos = 0;                 // entries of the wave's stream consumed so far
+    int wbase = 0;               // stream index of entry 0 of the older window
+    bool a_older = true;         // which of the two windows is the older one
+    if (twobuf) stage(0, tile);
+    for (int c = 0; c < nchunks; ++c) {
+        float* buf = tile + ((twobuf && (c & 1)) ? chunk_words : 0);
+        if (twobuf) {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // this wave's share of chunk c landed
+            __syncthreads();                                    // ... everyone's; and chunk c-1 is consumed
+            if (c + 1 < nchunks) stage(c + 1, tile + ((c & 1) ? 0 : chunk_words));
+        } else {
+            if (c > 0) __syncthreads();                         // everyone is done reading the previous chunk
+            stage(c, buf);
+            if constexpr (sizeof(T) == 4) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+        }
+        const char* lp = lane_ptr + (buf - tile) * 4;
+        // part lengths of the next chunk: needed only after the next barrier
+        int nlen_[RPW];
+#pragma unroll
+        for (int r = 0; r < RPW; ++r) nlen_[r] = c + 1 < nchunks ? lens[(c + 1) * RPW + r] : 0;
 
         // ---- accumulate the wave's parts of this chunk
 #pragma unroll
         for (int r = 0; r < RPW; ++r) {
-            const int part = ((row0 + r) * KS + ks) * nchunks + c;
-            int i = part * stride;
-            const int end = i + (c == 0 ? len0_[r] : hdr[part].x);
-            if (i >= end) continue;
-            if (i != first) { winA = nzl[i]; winB = nzl[i + 64]; }
-            // Two 64-entry windows take turns; a window is refilled (for 128 entries further
-            // on) as soon as it has been consumed, i.e. a whole window ahead of its use.
-            // The plan ends with 128 spare entries, so the read-ahead stays inside it.
-            while (true) {
-                pt_window<U, P>(winA, min(64, end - i), lane_ptr, acc[r]);
-                i += 64;
-                if (i >= end) break;
-                winA = nzl[i + 64];
-                pt_window<U, P>(winB, min(64, end - i), lane_ptr, acc[r]);
-                i += 64;
-                if (i >= end) break;
-                winB = nzl[i + 64];
+            int left = len_[r];
+            while (left > 0) {
+                const int l0 = pos - wbase;                      // 0 .. 63, a multiple of U
+                const int take = min(left, 64 - l0);
+                if (a_older) pt_window<U, P, Cfg::STEP>(winA, l0, l0 + take, lp, acc[r]);
+                else pt_window<U, P, Cfg::STEP>(winB, l0, l0 + take, lp, acc[r]);
+                pos += take;
+                left -= take;
+                if (l0 + take == 64) {
+                    // the older window is used up: refill it for 128 entries further on (the
+                    // plan ends with spare entries, so the read-ahead stays inside it)
+                    if (a_older) winA = nzl[wbase + 128]; else winB = nzl[wbase + 128];
+                    wbase += 64;
+                    a_older = !a_older;
+                }
             }
         }
+#pragma unroll
+        for (int r = 0; r < RPW; ++r) len_[r] = nlen_[r];
     }
 
     if (KS > 1) {
@@ -298,6 +328,7 @@ static ConvVariant make_ptile(const char* name) {
     v.kh = 0; v.kw = 0; v.stride = 0;
     v.p = Cfg::P; v.nw = Cfg::NW; v.rpw = Cfg::RPW; v.ks = Cfg::KS;
     v.unroll = Cfg::U;
+    v.tw = Cfg::LW;
     v.lds_bytes = 0;
     v.launch = &launch_ptile<Cfg>;
     return v;
@@ -306,7 +337,29 @@ static ConvVariant make_ptile(const char* name) {
 #define CADNN_PTILE(T, P, RPW, KS, NW, U) \
     make_ptile<PtileCfg<T, P, RPW, KS, NW, U>>("sptile_" #T "_p" #P "_r" #RPW "k" #KS "w" #NW "u" #U)
 
+#define CADNN_PTILE_WIDE(T, P, RPW, KS, NW, U) \
+    make_ptile<PtileCfg<T, P, RPW, KS, NW, U, 16>>("sptile_" #T "_v" #P "_r" #RPW "k" #KS "w" #NW "u" #U)
+
 #define CADNN_PTILE_SHAPES(T)         \
+    CADNN_PTILE_WIDE(T, 1, 1, 1, 16, 4),  \
+    CADNN_PTILE_WIDE(T, 1, 1, 2, 16, 4),  \
+    CADNN_PTILE_WIDE(T, 1, 1, 4, 16, 4),  \
+    CADNN_PTILE_WIDE(T, 1, 2, 1, 16, 4),  \
+    CADNN_PTILE_WIDE(T, 2, 1, 1, 16, 4),  \
+    CADNN_PTILE_WIDE(T, 2, 1, 2, 16, 4),  \
+    CADNN_PTILE_WIDE(T, 2, 1, 4, 16, 4),  \
+    CADNN_PTILE_WIDE(T, 2, 1, 8, 16, 4),  \
+    CADNN_PTILE_WIDE(T, 2, 2, 1, 16, 4),  \
+    CADNN_PTILE_WIDE(T, 2, 4, 1, 16, 4),  \
+    CADNN_PTILE_WIDE(T, 4, 1, 1, 16, 4),  \
+    CADNN_PTILE_WIDE(T, 4, 1, 2, 16, 4),  \
+    CADNN_PTILE_WIDE(T, 4, 1, 4, 16, 4),  \
+    CADNN_PTILE_WIDE(T, 4, 1, 8, 16, 4),  \
+    CADNN_PTILE_WIDE(T, 4, 2, 1, 16, 4),  \
+    CADNN_PTILE_WIDE(T, 4, 4, 1, 16, 4),  \
+    CADNN_PTILE_WIDE(T, 4, 4, 1, 8, 4),   \
+    CADNN_PTILE_WIDE(T, 4, 2, 2, 8, 4),   \
+    CADNN_PTILE_WIDE(T, 4, 1, 2, 8, 4),   \
     CADNN_PTILE(T, 1, 1, 1, 16, 4),   \
     CADNN_PTILE(T, 1, 1, 2, 16, 4),   \
     CADNN_PTILE(T, 1, 1, 4, 16, 4),   \

@@ -177,6 +177,7 @@ struct ConvLaunch {
     // FAM_PTILE: geometry of the staged tile (see PtileGeom)
     int pt_pitch, pt_sub, pt_plane, pt_nphc, pt_nph, pt_in_rows, pt_in_cols, pt_cch, pt_nstp, pt_nchunks;
     uint32_t pt_lds_bytes;
+    int pt_nbuf;
     uint32_t image_bytes;     // xd.image * sizeof(element)
 };
 
@@ -188,8 +189,15 @@ struct ConvPlan {
     int64_t nz_padded = 0;
 };
 
-// Staged tile of the FAM_PTILE kernels for one layer geometry.  A tile serves 7 output rows
-// x 7*P output columns.  The input region it needs is de-interleaved by the stride into
+// Staged tile of the FAM_PTILE kernels for one layer geometry.  Two lane arrangements:
+//   tw = 8 : an 8 x 8 lane grid of which 7 x 7 is used; pixel j of a lane lies 7*j columns
+//            to the right: a tile serves 7 output rows x 7*P columns (image sizes that are
+//            multiples of 7 but not of 14, and 7 x 7 images);
+//   tw = 16: a 4 x 16 lane grid of which 4 x 14 is used; pixel j of a lane lies 4*j rows
+//            further down: a tile serves 4*P output rows x 14 columns and the staged rows
+//            are exactly 16 words apart, so the four lane rows of a 32-lane LDS access fall
+//            into disjoint banks (filters up to 3 wide).
+// The input region a tile needs is de-interleaved by the stride into
 // nphr x nphc phases (sub-planes) so that lanes always read consecutive LDS words:
 // input element (u, v) of the region sits at phase (u % S, v % S), position (u / S, v / S).
 // `alias`: 3x3 / stride-1 tiles that span the whole image width drop the right halo column
@@ -197,16 +205,18 @@ struct ConvPlan {
 // pitch 8 words: bank-conflict free and small enough for 512 channels of a 7x7 image.
 struct PtileGeom {
     int S, P;
+    int tile_h, tile_w;       // output pixels of a tile
     int in_rows, in_cols;     // input region of a tile
     int nphr, nphc;           // phases used
     int pitch, sub, plane;    // words per tile row / per phase / per channel
     int nstp;                 // 64-word staging steps per channel
     int cch, nchunks;         // channels staged at a time, number of such chunks
+    int nbuf;                 // LDS buffers: 2 = the next chunk is staged while one is consumed (fp32)
     int alias;
     size_t lds_bytes;
 };
-PtileGeom ptile_geom(const ConvVariant& v, int cin, int kh, int kw, int stride, int pad, int wout);
-constexpr int kPtileMaxSteps = 6;
+PtileGeom ptile_geom(const ConvVariant& v, int cin, int kh, int kw, int stride, int pad, int wout);   // v.is_f16 matters
+constexpr int kPtileMaxSteps = 9;
 constexpr size_t kLdsBytesPerCU = 160 * 1024;
 
 // (variant, a, b): FAM_LINEAR a = input plane, b = input pitch; FAM_PTILE a = stride,

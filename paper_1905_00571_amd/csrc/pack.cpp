@@ -273,44 +273,58 @@ PtileGeom ptile_geom(const ConvVariant& v, int cin, int kh, int kw, int stride, 
     PtileGeom g{};
     g.S = stride;
     g.P = v.p;
-    g.in_rows = 6 * stride + kh;
-    g.in_cols = (7 * v.p - 1) * stride + kw;
+    const bool wide = v.tw == 16;
+    g.tile_h = wide ? 4 * v.p : 7;
+    g.tile_w = wide ? 14 : 7 * v.p;
+    g.in_rows = (g.tile_h - 1) * stride + kh;
+    g.in_cols = (g.tile_w - 1) * stride + kw;
     g.nphr = std::min(stride, kh);
     g.nphc = std::min(stride, kw);
     const int ph_r = (g.in_rows + stride - 1) / stride;
     const int ph_c = (g.in_cols + stride - 1) / stride;
-    g.alias = (stride == 1 && kh == 3 && kw == 3 && pad == 1 && wout == 7 * v.p) ? 1 : 0;
-    g.pitch = g.alias ? ph_c - 1 : ph_c;
+    g.alias = (!wide && stride == 1 && kh == 3 && kw == 3 && pad == 1 && wout == 7 * v.p) ? 1 : 0;
+    // the wide arrangement has its pitch compiled in (16); a region that does not fit makes
+    // the plane larger than LDS below, which excludes the variant
+    g.pitch = wide ? (ph_c <= 16 ? 16 : (1 << 20)) : (g.alias ? ph_c - 1 : ph_c);
     g.sub = ph_r * g.pitch;
     g.plane = g.nphr * g.nphc * g.sub + g.alias;
     g.nstp = (g.plane + 63) / 64;
     const size_t red_bytes = (size_t)v.nw * v.rpw * v.p * 64 * 4;
-    const int cch_max = (int)std::max<size_t>(1, kLdsBytesPerCU / ((size_t)g.plane * 4));
-    g.nchunks = (cin + cch_max - 1) / cch_max;
-    g.cch = (cin + g.nchunks - 1) / g.nchunks;
-    g.lds_bytes = std::max((size_t)g.cch * g.plane * 4, red_bytes);
+    const size_t plane_bytes = (size_t)g.plane * 4;
+    if ((size_t)cin * plane_bytes <= kLdsBytesPerCU) {
+        g.nbuf = 1; g.nchunks = 1; g.cch = cin;
+    } else {
+        // several chunks: fp32 stages chunk c+1 into a second buffer while chunk c is consumed
+        g.nbuf = v.is_f16 ? 1 : 2;
+        const int cch_max = (int)std::max<size_t>(1, kLdsBytesPerCU / g.nbuf / plane_bytes);
+        g.nchunks = (cin + cch_max - 1) / cch_max;
+        g.cch = (cin + g.nchunks - 1) / g.nchunks;
+    }
+    g.lds_bytes = std::max((size_t)g.nbuf * g.cch * plane_bytes, red_bytes);
     return g;
 }
 
 // Device copy of the nonzero stream for a shared-tile (FAM_PTILE) variant.
 //
-// The input channels are cut into `nchunks` chunks of `cch`.  Packed row i is served by KS
-// waves; within chunk c its entries (ascending canonical column) are split evenly between
-// them.  Part (i, s, c) starts at ((i*KS + s)*nchunks + c) * stride entries, `stride` being
-// the longest part rounded up to the unroll, and the header table holds {padded length,
-// original channel} at the same index.  An entry is (fp32 value bits, byte offset of the tap
-// in the staged tile relative to the lane's pixel).
+// The input channels are cut into `nchunks` chunks of `cch`.  A wave serves RPW packed rows
+// and the `s`-th of KS even slices of each row's entries per chunk.  All its parts -- chunk
+// by chunk, row by row within a chunk, each padded to the unroll -- lie back to back in one
+// stream; stream w starts at w * stride entries (`stride` = the longest stream), w =
+// (row / RPW) * KS + s, and the table holds the padded part lengths [w][chunk][row].  An
+// entry is (fp32 value bits, byte offset of the tap in the staged chunk relative to the
+// lane's pixel).  192 spare entries follow the last stream (the kernel reads two 64-entry
+// windows ahead).
 static cadnn_status build_ptile_plan(const cadnn_weights* w, const ConvVariant* v, int conv_stride, int pad,
                                      int wout, ConvPlan* plan) {
     const PtileGeom g = ptile_geom(*v, w->cin, w->kh, w->kw, conv_stride, pad, wout);
     const int rb = v->rows_per_block();
     const int rows_padded = (w->cout + rb - 1) / rb * rb;
     const int taps = w->kh * w->kw;
-    const int ks = v->ks;
+    const int ks = v->ks, rpw = v->rpw;
     const int U = v->unroll;
+    const int nstreams = rows_padded / rpw * ks;
     // chunk boundaries of every row in the canonical stream
-    std::vector<int32_t> cut((size_t)w->cout * (g.nchunks + 1));
-    int64_t stride = U;
+    std::vector<int32_t> cut((size_t)rows_padded * (g.nchunks + 1), 0);
     for (int i = 0; i < w->cout; ++i) {
         int32_t j = w->row_ptr[i];
         const int32_t e = w->row_ptr[i + 1];
@@ -318,42 +332,53 @@ static cadnn_status build_ptile_plan(const cadnn_weights* w, const ConvVariant* 
             cut[(size_t)i * (g.nchunks + 1) + c] = j;
             const int32_t k_end = (int32_t)std::min<int64_t>((int64_t)(c + 1) * g.cch, w->cin) * taps;
             while (j < e && w->col_idx[j] < k_end) ++j;
-            const int32_t cnt = j - cut[(size_t)i * (g.nchunks + 1) + c];
-            const int32_t per = (cnt + ks - 1) / ks;
-            stride = std::max<int64_t>(stride, (int64_t)(per + U - 1) / U * U);
         }
         cut[(size_t)i * (g.nchunks + 1) + g.nchunks] = e;
     }
-    const int64_t parts = (int64_t)rows_padded * ks * g.nchunks;
-    const int64_t total = parts * stride + 128;
+    auto part_range = [&](int row, int c, int s, int32_t* pb, int32_t* pe) {
+        const int32_t b = cut[(size_t)row * (g.nchunks + 1) + c], e = cut[(size_t)row * (g.nchunks + 1) + c + 1];
+        const int32_t per = (e - b + ks - 1) / ks;
+        *pb = (int32_t)std::min<int64_t>((int64_t)b + (int64_t)s * per, e);
+        *pe = (int32_t)std::min<int64_t>((int64_t)*pb + per, e);
+    };
+    std::vector<int32_t> lens((size_t)nstreams * g.nchunks * rpw, 0);
+    int64_t stride = U;
+    for (int ws = 0; ws < nstreams; ++ws) {
+        const int row0 = (ws / ks) * rpw, s = ws % ks;
+        int64_t total = 0;
+        for (int c = 0; c < g.nchunks; ++c)
+            for (int r = 0; r < rpw; ++r) {
+                int32_t pb, pe;
+                part_range(row0 + r, c, s, &pb, &pe);
+                const int32_t padded = (pe - pb + U - 1) / U * U;
+                lens[((size_t)ws * g.nchunks + c) * rpw + r] = padded;
+                total += padded;
+            }
+        stride = std::max(stride, total);
+    }
+    const int64_t total = (int64_t)nstreams * stride + 192;
     if (total > (int64_t)INT32_MAX / 2) return fail(CADNN_EUNSUPPORTED, "plan too large");
-    std::vector<int32_t> hdr((size_t)parts * 2, 0);
     std::vector<int32_t> perm(rows_padded, -1);
+    for (int i = 0; i < w->cout; ++i) perm[i] = w->perm[i];
     std::vector<uint2> nz((size_t)total, make_uint2(0u, 0u));
-    for (int i = 0; i < rows_padded; ++i) {
-        if (i < w->cout) perm[i] = w->perm[i];
-        for (int c = 0; c < g.nchunks; ++c) {
-            const int32_t b = i < w->cout ? cut[(size_t)i * (g.nchunks + 1) + c] : 0;
-            const int32_t e = i < w->cout ? cut[(size_t)i * (g.nchunks + 1) + c + 1] : 0;
-            const int32_t per = (e - b + ks - 1) / ks;
-            for (int s = 0; s < ks; ++s) {
-                const int32_t pb = (int32_t)std::min<int64_t>((int64_t)b + (int64_t)s * per, e);
-                const int32_t pe = (int32_t)std::min<int64_t>((int64_t)pb + per, e);
-                const size_t part = ((size_t)i * ks + s) * g.nchunks + c;
-                uint2* out = &nz[part * (size_t)stride];
+    for (int ws = 0; ws < nstreams; ++ws) {
+        const int row0 = (ws / ks) * rpw, s = ws % ks;
+        uint2* out = &nz[(size_t)ws * (size_t)stride];
+        for (int c = 0; c < g.nchunks; ++c)
+            for (int r = 0; r < rpw; ++r) {
+                int32_t pb, pe;
+                part_range(row0 + r, c, s, &pb, &pe);
                 for (int32_t j = pb; j < pe; ++j) {
                     const int32_t k = w->col_idx[j];
-                    const int ci = k / taps - c * g.cch, r = (k % taps) / w->kw, cc = k % w->kw;
-                    const int phase = (r % g.S) * g.nphc + (cc % g.S);
-                    const int64_t off = ((int64_t)ci * g.plane + (int64_t)phase * g.sub + (r / g.S) * g.pitch + cc / g.S) * 4;
+                    const int ci = k / taps - c * g.cch, tr = (k % taps) / w->kw, tc = k % w->kw;
+                    const int phase = (tr % g.S) * g.nphc + (tc % g.S);
+                    const int64_t off = ((int64_t)ci * g.plane + (int64_t)phase * g.sub + (tr / g.S) * g.pitch + tc / g.S) * 4;
                     uint32_t bits;
                     std::memcpy(&bits, &w->vals[j], 4);
                     out[j - pb] = make_uint2(bits, (uint32_t)off);
                 }
-                hdr[part * 2 + 0] = (pe - pb + U - 1) / U * U;
-                hdr[part * 2 + 1] = perm[i];
+                out += lens[((size_t)ws * g.nchunks + c) * rpw + r];
             }
-        }
     }
     plan->variant = v;
     plan->nchunks = (int)stride;
@@ -361,7 +386,7 @@ static cadnn_status build_ptile_plan(const cadnn_weights* w, const ConvVariant* 
     plan->nz_padded = (int64_t)nz.size();
     cadnn_status st;
     if ((st = plan->nz.upload(nz.data(), nz.size() * sizeof(uint2))) != CADNN_OK) return st;
-    if ((st = plan->seg_ptr.upload(hdr.data(), hdr.size() * 4)) != CADNN_OK) return st;
+    if ((st = plan->seg_ptr.upload(lens.data(), lens.size() * 4)) != CADNN_OK) return st;
     if ((st = plan->perm.upload(perm.data(), perm.size() * 4)) != CADNN_OK) return st;
     return CADNN_OK;
 }
