@@ -281,7 +281,9 @@ def test_dense_comparator(cad, geom):
 
 
 @pytest.mark.parametrize("geom", [(24, 20, 3, 1, 1, 18, 20, 0.8, 2), (16, 12, 3, 2, 1, 15, 17, 0.7, 1),
-                                  (130, 9, 3, 1, 1, 7, 7, 0.9, 1), (12, 10, 3, 1, 1, 14, 14, 0.5, 1)])
+                                  (130, 9, 3, 1, 1, 7, 7, 0.9, 1), (12, 10, 3, 1, 1, 14, 14, 0.5, 1),
+                                  # enough channels that the LDS families stage them chunk by chunk
+                                  (600, 12, 3, 1, 1, 14, 14, 0.9, 1), (520, 8, 3, 2, 1, 14, 14, 0.9, 2)])
 def test_every_variant_on_a_haloed_input(cad, geom):
     """Inside a net the input of a 3x3 layer carries a zero halo, which opens the
     linear-address kernels to it: a 1x1 producer feeds the 3x3 layer and every variant that
