@@ -186,8 +186,9 @@ cadnn_status cadnn_net_add_fc(cadnn_net* net, const cadnn_weights* w, const void
 cadnn_status cadnn_net_workspace_bytes(const cadnn_net* net, size_t* bytes);
 /* flags: CADNN_NET_GRAPH -- cadnn_run_net replays a captured HIP graph (re-captured
  * when x / y change between calls); CADNN_NET_TUNE -- the first cadnn_run_net call
- * first runs cadnn_conv2d_tune on every convolution with the net's own buffers
- * (that first call synchronises and takes a fraction of a second);
+ * first runs cadnn_conv2d_tune on every convolution with the net's own buffers, the
+ * op that produces its input launched before every timed launch so that the caches are
+ * as they will be (that first call synchronises and takes a fraction of a second);
  * CADNN_NET_PLAIN_LAYOUT -- keep every intermediate tensor in plain (haloed) NCHW; by
  * default the output of a convolution that is read by stride-2 convolutions is kept
  * de-interleaved by row/column parity, so those layers read it with unit stride. */

@@ -284,7 +284,7 @@ cadnn_status conv2d_set_variant_impl(const cadnn_weights* w, const TensorDesc& x
 cadnn_status conv2d_tune_impl(const cadnn_weights* w, const void* x, const TensorDesc& xd, void* y,
                               const TensorDesc& yd, const void* residual, const TensorDesc& rd, int n,
                               int stride, int pad, const void* bias, int relu, hipStream_t s, int reps,
-                              float* best_us) {
+                              float* best_us, const std::function<cadnn_status()>* before) {
     ConvGeom g;
     cadnn_status st = check_conv("cadnn_conv2d_tune", w, xd, n, stride, pad, &g, yd.s2d || (residual && rd.s2d));
     if (st != CADNN_OK) return st;
@@ -321,6 +321,8 @@ cadnn_status conv2d_tune_impl(const cadnn_weights* w, const void* x, const Tenso
         for (int i = 0; i < reps && st == CADNN_OK; ++i) {
             st = launch_copy(sweep.p, (char*)sweep.p + sweep_bytes, sweep_bytes, s);
             if (st != CADNN_OK) break;
+            // inside a net: the producer of the input runs right before, as it will
+            if (before && (st = (*before)()) != CADNN_OK) break;
             if (hipEventRecord(e0, s) != hipSuccess) { st = fail(CADNN_EHIP, "hipEventRecord failed"); break; }
             st = launch_variant(w, v, g, x, y, yd, residual, rd, bias, relu, s);
             if (st != CADNN_OK) break;

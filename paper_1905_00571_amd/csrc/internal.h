@@ -7,6 +7,7 @@
 #include <cstdarg>
 #include <cstdint>
 #include <cstdio>
+#include <functional>
 #include <map>
 #include <memory>
 #include <mutex>
@@ -279,7 +280,7 @@ cadnn_status conv2d_impl(const cadnn_weights* w, const void* x, const TensorDesc
 cadnn_status conv2d_tune_impl(const cadnn_weights* w, const void* x, const TensorDesc& xd, void* y,
                               const TensorDesc& yd, const void* residual, const TensorDesc& rd, int n,
                               int stride, int pad, const void* bias, int relu, hipStream_t s, int reps,
-                              float* best_us);
+                              float* best_us, const std::function<cadnn_status()>* before = nullptr);
 // Name of the variant that would serve the layer (NULL if none).
 // `out_s2d`: the layer's output or residual is in the de-interleaved layout.
 const char* conv2d_variant_name_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad,

@@ -2,6 +2,7 @@
 // back to back on one stream (optionally as one captured HIP graph) so that a single-image
 // inference (the quantity the paper's evaluation reports, Section 5) costs one submission.
 #include <algorithm>
+#include <cstdlib>
 #include <cstring>
 
 #include "internal.h"
@@ -321,9 +322,13 @@ extern "C" cadnn_status cadnn_run_net(cadnn_net* net, const void* x, void* y, vo
         for (size_t i = 0; i < net->ops.size() && st == CADNN_OK; ++i) {
             const NetOp& op = net->ops[i];
             if (op.kind != OP_CONV) continue;
+            const std::function<cadnn_status()> producer = [&]() {
+                return op.src_inst >= 0 ? launch_one(net, (size_t)op.src_inst, x, y, s) : CADNN_OK;
+            };
             st = conv2d_tune_impl(op.w, in_ptr(net, op.src_inst, x), op.xd, out_ptr(net, i, y), op.yd,
                                   op.res >= 0 ? in_ptr(net, op.res_inst, x) : nullptr, op.rd, op.in.n,
-                                  op.stride, op.pad, op.bias, op.relu, s, 20, nullptr);
+                                  op.stride, op.pad, op.bias, op.relu, s, 20, nullptr,
+                                  &producer);
         }
         if (st != CADNN_OK) return st;
         net->want_tune = false;
