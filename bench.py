@@ -64,7 +64,7 @@ def layer_costs(ops, weights, in_shape, elem):
 KERNEL_OF_PREFIX = {"slinear": "sconv_linear_kernel", "stile": "sconv_stile_kernel",
                     "sdirect": "sconv_direct_kernel", "sconv": "sconv_tile_kernel",
                     "dense": "dense_conv_kernel", "sfc": "sfc_kernel", "maxpool": "maxpool_kernel",
-                    "avgpool": "avgpool_kernel"}
+                    "avgpool": "avgpool_kernel", "fused": "(computed inside another op)"}
 
 
 def kernel_of(variant: str) -> str:

@@ -191,10 +191,15 @@ cadnn_status cadnn_net_workspace_bytes(const cadnn_net* net, size_t* bytes);
  * as they will be (that first call synchronises and takes a fraction of a second);
  * CADNN_NET_PLAIN_LAYOUT -- keep every intermediate tensor in plain (haloed) NCHW; by
  * default the output of a convolution that is read by stride-2 convolutions is kept
- * de-interleaved by row/column parity, so those layers read it with unit stride. */
+ * de-interleaved by row/column parity, so those layers read it with unit stride;
+ * CADNN_NET_NO_FUSION -- launch every op on its own; by default a 1x1 projection shortcut
+ * whose only reader adds it as residual is computed inside that reader (its buffer is
+ * then never written and cadnn_net_read_buffer refuses it, its profile time is zero and
+ * its variant name is "fused"). */
 #define CADNN_NET_GRAPH 1
 #define CADNN_NET_TUNE 2
 #define CADNN_NET_PLAIN_LAYOUT 4
+#define CADNN_NET_NO_FUSION 8
 cadnn_status cadnn_net_finalize(cadnn_net* net, void* workspace_dev, size_t bytes, int flags);
 cadnn_status cadnn_run_net(cadnn_net* net, const void* x, void* y, void* stream);
 /* Number of ops, and per-op device time: op i is launched `repeats` times back

@@ -371,7 +371,7 @@ def cadnn_run_net(net: Net, x, y=None, stream=None):
 
 def build_net(ops: Sequence, weights: Sequence, biases: Sequence, input_shape, dtype: int = F32,
               use_graph: bool = True, tune: bool = False, device: str = "cuda:0",
-              plain_layout: bool = False) -> Net:
+              plain_layout: bool = False, fuse: bool = True) -> Net:
     """Packs every layer's weights and wires the op list into a cadnn_net.
 
     `ops` are records with .kind in {"conv", "fc", "maxpool", "avgpool"} and
@@ -417,7 +417,8 @@ def build_net(ops: Sequence, weights: Sequence, biases: Sequence, input_shape, d
         ws = torch.empty(max(int(nbytes.value), 256), dtype=torch.uint8, device=device)
         keep.append(ws)
         _check(L.cadnn_net_finalize(handle, _dptr(ws), int(nbytes.value),
-                                    (1 if use_graph else 0) | (2 if tune else 0) | (4 if plain_layout else 0)))
+                                    (1 if use_graph else 0) | (2 if tune else 0) | (4 if plain_layout else 0) |
+                                    (0 if fuse else 8)))
     except Exception:
         L.cadnn_net_free(handle)
         raise

@@ -14,16 +14,27 @@ struct ConvGeom {
     int n, stride, pad, hout, wout;
     TensorDesc xd;
     int out_s2d = 0;          // output or residual de-interleaved
-    GeomKey key() const { return {n, xd.h, xd.w, stride, pad, xd.ph, xd.pw, (xd.s2d ? 1 : 0) | (out_s2d ? 2 : 0)}; }
+    const ConvExtra* ex = nullptr;   // fused 1x1 shortcut
+    GeomKey key() const {
+        return {n, xd.h, xd.w, stride, pad, xd.ph, xd.pw, (xd.s2d ? 1 : 0) | (out_s2d ? 2 : 0) | (ex ? 4 : 0)};
+    }
 };
 
 static cadnn_status check_conv(const char* who, const cadnn_weights* w, const TensorDesc& xd, int n,
-                               int stride, int pad, ConvGeom* g, int out_s2d = 0) {
+                               int stride, int pad, ConvGeom* g, int out_s2d = 0, const ConvExtra* ex = nullptr) {
     if (!w) return fail(CADNN_EINVAL, "%s: NULL weight handle", who);
     if (n <= 0 || xd.h <= 0 || xd.w <= 0) return fail(CADNN_EINVAL, "%s: non-positive size", who);
     if (stride <= 0 || pad < 0) return fail(CADNN_EINVAL, "%s: bad stride/pad", who);
     if (xd.c != w->cin) return fail(CADNN_EINVAL, "%s: %d input channels, weights take %d", who, xd.c, w->cin);
-    g->n = n; g->stride = stride; g->pad = pad; g->xd = xd; g->out_s2d = out_s2d;
+    g->n = n; g->stride = stride; g->pad = pad; g->xd = xd; g->out_s2d = out_s2d; g->ex = ex;
+    if (ex) {
+        if (!ex->w || !ex->x) return fail(CADNN_EINVAL, "%s: NULL fused shortcut", who);
+        if (ex->w->kh != 1 || ex->w->kw != 1 || ex->w->cout != w->cout || ex->w->dtype != w->dtype ||
+            ex->w->cin != ex->xd.c || ex->stride <= 0)
+            return fail(CADNN_EINVAL, "%s: the fused shortcut must be a 1x1 layer of the same type and output channels", who);
+        if (ex->xd.image * (int64_t)w->elem() >= 0x7ffffff0ll)
+            return fail(CADNN_EUNSUPPORTED, "%s: one image of the shortcut's input is 2 GiB or more", who);
+    }
     g->hout = conv_out(xd.h, w->kh, stride, pad);
     g->wout = conv_out(xd.w, w->kw, stride, pad);
     if (g->hout <= 0 || g->wout <= 0) return fail(CADNN_EINVAL, "%s: empty output", who);
@@ -38,8 +49,8 @@ static bool variant_fits(const ConvVariant& v, const cadnn_weights* w, const Con
     if (v.is_f16 != (w->dtype == CADNN_F16)) return false;
     if (v.stride != 0 && v.stride != g.stride) return false;
     if ((w->cout + v.rows_per_block() - 1) / v.rows_per_block() > 65535) return false;
-    // de-interleaved tensors are understood by the linear-address kernels only
-    if ((g.xd.s2d || g.out_s2d) && v.family != FAM_LINEAR) return false;
+    // de-interleaved tensors and fused shortcuts are understood by the linear-address kernels only
+    if ((g.xd.s2d || g.out_s2d || g.ex) && v.family != FAM_LINEAR) return false;
     if (v.family == FAM_DENSE)
         return (double)w->nnz >= 0.25 * (double)w->cout * w->cin * w->kh * w->kw;
     if (v.family == FAM_LINEAR) {
@@ -59,6 +70,15 @@ static bool variant_fits(const ConvVariant& v, const cadnn_weights* w, const Con
         // de-interleaved input is handed a plain view of the phase it starts in.
         const bool general = g.out_s2d || (g.xd.s2d && g.stride == 1);
         if (general != (v.s2d != 0)) return false;
+        // a fused shortcut takes the dual-input instantiations; its input must be walkable
+        // with one stride (plain layout, or de-interleaved and read with stride 2)
+        if ((g.ex != nullptr) != (v.dual != 0)) return false;
+        if (g.ex) {
+            if (general) return false;
+            if (g.ex->xd.s2d && g.ex->stride != 2) return false;
+            const int unit2 = g.ex->xd.s2d ? 2 : 1;
+            if (v.adjacent && g.ex->stride != unit2) return false;
+        }
         // a lane's adjacent pixels must be adjacent in memory, on both sides
         const int unit = g.xd.s2d ? 2 : 1;
         if (v.adjacent && (g.stride != unit || g.wout % v.p != 0)) return false;
@@ -152,7 +172,7 @@ static cadnn_status launch_variant(const cadnn_weights* w, const ConvVariant* v,
                                    const void* x, void* y, const TensorDesc& yd, const void* residual,
                                    const TensorDesc& rd, const void* bias, int relu, hipStream_t s) {
     const ConvPlan* plan = nullptr;
-    cadnn_status st = get_conv_plan(w, v, g.xd, g.stride, g.pad, g.wout, &plan);
+    cadnn_status st = get_conv_plan(w, v, g.xd, g.stride, g.pad, g.wout, &plan, g.ex);
     if (st != CADNN_OK) return st;
     ConvLaunch a{};
     a.x = x;
@@ -164,6 +184,19 @@ static cadnn_status launch_variant(const cadnn_weights* w, const ConvVariant* v,
     a.perm = (const int32_t*)plan->perm.p;
     a.xd = g.xd; a.yd = yd; a.rd = rd;
     a.n = g.n; a.cout = w->cout; a.stride = g.stride; a.pad = g.pad; a.relu = relu ? 1 : 0;
+    if (g.ex) {
+        // the shortcut's input as a plain view walked with one stride from pixel (0, 0)
+        a.x2 = g.ex->x;
+        a.bias2 = (const float*)g.ex->bias;
+        a.x2d = g.ex->xd;
+        a.stride2 = g.ex->stride;
+        if (g.ex->xd.s2d) {
+            a.x2d.origin = tensor_off(g.ex->xd, 0, 0);
+            a.x2d.s2d = 0;
+            a.stride2 = 1;
+        }
+        a.image2_bytes = (uint32_t)(g.ex->xd.image * (int64_t)w->elem());
+    }
     if (g.xd.s2d && g.stride == 2) {
         // plain view for the kernel: unit stride over the rows of one phase, starting at the
         // position of tap (0, 0) of output pixel (0, 0); the plan's tap offsets pick the phase
@@ -209,9 +242,9 @@ static cadnn_status check_io(const char* who, const cadnn_weights* w, const Conv
 
 cadnn_status conv2d_impl(const cadnn_weights* w, const void* x, const TensorDesc& xd, void* y,
                          const TensorDesc& yd, const void* residual, const TensorDesc& rd, int n,
-                         int stride, int pad, const void* bias, int relu, hipStream_t s) {
+                         int stride, int pad, const void* bias, int relu, hipStream_t s, const ConvExtra* ex) {
     ConvGeom g;
-    cadnn_status st = check_conv("cadnn_sparse_conv2d", w, xd, n, stride, pad, &g, yd.s2d || (residual && rd.s2d));
+    cadnn_status st = check_conv("cadnn_sparse_conv2d", w, xd, n, stride, pad, &g, yd.s2d || (residual && rd.s2d), ex);
     if (st != CADNN_OK) return st;
     if ((st = check_io("cadnn_sparse_conv2d", w, g, x, y, yd, residual, rd)) != CADNN_OK) return st;
     const ConvVariant* v = pick_variant(w, g);
@@ -222,22 +255,22 @@ cadnn_status conv2d_impl(const cadnn_weights* w, const void* x, const TensorDesc
 }
 
 cadnn_status conv2d_prepare_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad,
-                                 int out_s2d) {
+                                 int out_s2d, const ConvExtra* ex) {
     ConvGeom g;
-    cadnn_status st = check_conv("cadnn_conv2d_prepare", w, xd, n, stride, pad, &g, out_s2d);
+    cadnn_status st = check_conv("cadnn_conv2d_prepare", w, xd, n, stride, pad, &g, out_s2d, ex);
     if (st != CADNN_OK) return st;
     const ConvVariant* v = pick_variant(w, g);
     if (!v)
         return fail(CADNN_EUNSUPPORTED, "cadnn_conv2d_prepare: no kernel for %dx%d filters with stride %d",
                     w->kh, w->kw, stride);
     const ConvPlan* plan = nullptr;
-    return get_conv_plan(w, v, xd, g.stride, g.pad, g.wout, &plan);
+    return get_conv_plan(w, v, xd, g.stride, g.pad, g.wout, &plan, g.ex);
 }
 
 const char* conv2d_variant_name_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad,
-                                     int out_s2d) {
+                                     int out_s2d, const ConvExtra* ex) {
     ConvGeom g;
-    if (check_conv("cadnn_net_op_variant", w, xd, n, stride, pad, &g, out_s2d) != CADNN_OK) return nullptr;
+    if (check_conv("cadnn_net_op_variant", w, xd, n, stride, pad, &g, out_s2d, ex) != CADNN_OK) return nullptr;
     const ConvVariant* v = pick_variant(w, g);
     if (!v) {
         (void)fail(CADNN_EUNSUPPORTED, "no kernel for %dx%d filters with stride %d", w->kh, w->kw, stride);
@@ -247,10 +280,10 @@ const char* conv2d_variant_name_impl(const cadnn_weights* w, const TensorDesc& x
 }
 
 cadnn_status conv2d_list_variants_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad,
-                                       char* buf, size_t len, int out_s2d) {
+                                       char* buf, size_t len, int out_s2d, const ConvExtra* ex) {
     if (!buf || len == 0) return fail(CADNN_EINVAL, "cadnn_conv2d_list_variants: NULL buffer");
     ConvGeom g;
-    cadnn_status st = check_conv("cadnn_conv2d_list_variants", w, xd, n, stride, pad, &g, out_s2d);
+    cadnn_status st = check_conv("cadnn_conv2d_list_variants", w, xd, n, stride, pad, &g, out_s2d, ex);
     if (st != CADNN_OK) return st;
     std::string all;
     for (const ConvVariant* v : candidates(w, g)) {
@@ -263,9 +296,9 @@ cadnn_status conv2d_list_variants_impl(const cadnn_weights* w, const TensorDesc&
 }
 
 cadnn_status conv2d_set_variant_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad,
-                                     const char* name, int out_s2d) {
+                                     const char* name, int out_s2d, const ConvExtra* ex) {
     ConvGeom g;
-    cadnn_status st = check_conv("cadnn_conv2d_set_variant", w, xd, n, stride, pad, &g, out_s2d);
+    cadnn_status st = check_conv("cadnn_conv2d_set_variant", w, xd, n, stride, pad, &g, out_s2d, ex);
     if (st != CADNN_OK) return st;
     std::lock_guard<std::mutex> lock(w->mu);
     if (!name || !*name) {
@@ -284,9 +317,9 @@ cadnn_status conv2d_set_variant_impl(const cadnn_weights* w, const TensorDesc& x
 cadnn_status conv2d_tune_impl(const cadnn_weights* w, const void* x, const TensorDesc& xd, void* y,
                               const TensorDesc& yd, const void* residual, const TensorDesc& rd, int n,
                               int stride, int pad, const void* bias, int relu, hipStream_t s, int reps,
-                              float* best_us, const std::function<cadnn_status()>* before) {
+                              float* best_us, const std::function<cadnn_status()>* before, const ConvExtra* ex) {
     ConvGeom g;
-    cadnn_status st = check_conv("cadnn_conv2d_tune", w, xd, n, stride, pad, &g, yd.s2d || (residual && rd.s2d));
+    cadnn_status st = check_conv("cadnn_conv2d_tune", w, xd, n, stride, pad, &g, yd.s2d || (residual && rd.s2d), ex);
     if (st != CADNN_OK) return st;
     if ((st = check_io("cadnn_conv2d_tune", w, g, x, y, yd, residual, rd)) != CADNN_OK) return st;
     if (reps <= 0) return fail(CADNN_EINVAL, "cadnn_conv2d_tune: reps must be positive");
@@ -314,7 +347,7 @@ cadnn_status conv2d_tune_impl(const cadnn_weights* w, const void* x, const Tenso
     for (const ConvVariant* v : cand) {
         {
             const ConvPlan* probe = nullptr;
-            if (get_conv_plan(w, v, g.xd, g.stride, g.pad, g.wout, &probe) == CADNN_EUNSUPPORTED) continue;   // does not fit these weights
+            if (get_conv_plan(w, v, g.xd, g.stride, g.pad, g.wout, &probe, g.ex) == CADNN_EUNSUPPORTED) continue;   // does not fit these weights
         }
         st = launch_variant(w, v, g, x, y, yd, residual, rd, bias, relu, s);
         float total_ms = 0.0f;

@@ -33,10 +33,16 @@ constexpr uint32_t kLinOutOfRange = 0x7ffffff0u;   // beyond any buffer this lib
 // S2D = 1: the instantiation understands de-interleaved tensors (TensorDesc::s2d) on its
 //          output, residual and -- for pixel-wise layers -- input.  Kept apart because the
 //          general address arithmetic costs every launch a fraction of a microsecond.
-template <typename T_, int P_, int RPW_, int KS_, int NW_, int U_, int ADJ_ = 0, int S2D_ = 0>
+// DUAL = 1: a second sparse matrix on a second input tensor is accumulated into the same
+//          outputs: a 1x1 projection shortcut fused into the layer it would have been the
+//          residual of (the shortcut's kernel launch, its output write and the residual
+//          read disappear).  A part of the stream is then the layer's entries followed by
+//          the shortcut's, and the header is {length, channel, shortcut length, -}.
+template <typename T_, int P_, int RPW_, int KS_, int NW_, int U_, int ADJ_ = 0, int S2D_ = 0, int DUAL_ = 0>
 struct LinearCfg {
     using T = T_;
-    static constexpr int P = P_, RPW = RPW_, KS = KS_, NW = NW_, U = U_, ADJ = ADJ_, S2D = S2D_;
+    static constexpr int P = P_, RPW = RPW_, KS = KS_, NW = NW_, U = U_, ADJ = ADJ_, S2D = S2D_, DUAL = DUAL_;
+    static_assert(!(S2D && DUAL), "not combined");
     static_assert(!(ADJ && S2D), "adjacent pixels are not adjacent in a de-interleaved tensor");
     static constexpr int RG = NW / KS;
     static constexpr int THREADS = NW * 64;
@@ -118,6 +124,55 @@ __device__ __forceinline__ void lin_fetch(__amdgpu_buffer_rsrc_t r, const uint32
     }
 }
 
+// Entries [i, end) of the stream (end - i a positive multiple of U) against the P pixels of
+// a lane.  Two register sets (A, B) take turns: while one group is accumulated the
+// activations of the next are in flight.
+template <class Cfg>
+__device__ __forceinline__ void lin_accumulate(__amdgpu_buffer_rsrc_t rsrc, const uint32_t (&voff)[Cfg::P], NzWindow& win,
+                                               int i, int end, float (&acc)[Cfg::P]) {
+    using T = typename Cfg::T;
+    constexpr int P = Cfg::P, U = Cfg::U, ADJ = Cfg::ADJ;
+    win.seek(i);
+    int groups = (end - i) / U;
+    float wa[U], xa[U][P], wb[U], xb[U][P];
+    uint32_t oa[U], ob[U];
+    win.group<U>(i, wa, oa);
+#pragma unroll
+    for (int u = 0; u < U; ++u) lin_fetch<T, P, ADJ>(rsrc, voff, oa[u], xa[u]);
+    while (true) {
+        if (groups == 1) {
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int j = 0; j < P; ++j) acc[j] = fmaf(wa[u], xa[u][j], acc[j]);
+            break;
+        }
+        win.group<U>(i + U, wb, ob);
+#pragma unroll
+        for (int u = 0; u < U; ++u) lin_fetch<T, P, ADJ>(rsrc, voff, ob[u], xb[u]);
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int j = 0; j < P; ++j) acc[j] = fmaf(wa[u], xa[u][j], acc[j]);
+        if (groups == 2) {
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int j = 0; j < P; ++j) acc[j] = fmaf(wb[u], xb[u][j], acc[j]);
+            break;
+        }
+        win.group<U>(i + 2 * U, wa, oa);
+#pragma unroll
+        for (int u = 0; u < U; ++u) lin_fetch<T, P, ADJ>(rsrc, voff, oa[u], xa[u]);
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int j = 0; j < P; ++j) acc[j] = fmaf(wb[u], xb[u][j], acc[j]);
+        groups -= 2;
+        i += 2 * U;
+    }
+}
+
 // Output pixel served by flattened index q.  Normally row-major.  A pixel-wise layer on a
 // de-interleaved input walks the pixels parity class by parity class instead (all pixels of
 // one row/column parity, row-major, then the next class), which is the order they lie in
@@ -138,7 +193,7 @@ __device__ __forceinline__ void lin_pixel(const ConvLaunch& a, int q, int& oh, i
 template <class Cfg>
 __global__ __launch_bounds__(Cfg::THREADS) void sconv_linear_kernel(const ConvLaunch a) {
     using T = typename Cfg::T;
-    constexpr int P = Cfg::P, RPW = Cfg::RPW, KS = Cfg::KS, RG = Cfg::RG, U = Cfg::U, ADJ = Cfg::ADJ;
+    constexpr int P = Cfg::P, RPW = Cfg::RPW, KS = Cfg::KS, RG = Cfg::RG, ADJ = Cfg::ADJ;
     __shared__ float red[KS > 1 ? Cfg::NW * RPW * P * 64 : 1];
 
     const int lane = threadIdx.x & 63;
@@ -179,6 +234,21 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_linear_kernel(const ConvLa
     }
     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
         (void*)((const char*)a.x + (size_t)n * a.image_bytes), 0, a.image_bytes, 0x00020000);
+    // fused shortcut: the same pixels in the second input (a 1x1 filter: one tap, no padding)
+    uint32_t voff2[Cfg::DUAL ? P : 1];
+    __amdgpu_buffer_rsrc_t rsrc2 = rsrc;
+    if constexpr (Cfg::DUAL) {
+#pragma unroll
+        for (int j = 0; j < P; ++j) {
+            const int q = ADJ ? q0 + lane * P + j : q0 + j * 64 + lane;
+            const int oh = q / a.yd.w, ow = q - oh * a.yd.w;
+            voff2[j] = q < a.hwout
+                           ? (uint32_t)(a.x2d.origin + oh * a.stride2 * a.x2d.pitch + ow * a.stride2) * (uint32_t)sizeof(T)
+                           : kLinOutOfRange;
+        }
+        rsrc2 = __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)a.x2 + (size_t)n * a.image2_bytes), 0,
+                                                  a.image2_bytes, 0x00020000);
+    }
 
     // Header {padded length, original channel} of each of the wave's parts.  A part starts
     // at (row*KS + ks) * stride, so the first window of the first row is requested in the
@@ -190,16 +260,27 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_linear_kernel(const ConvLa
     win.nz = a.nz;
     win.lane = lane;
     win.reset(((row0 + 0) * KS + ks) * stride);
-    int co_[RPW], len_[RPW];
+    int co_[RPW], len_[RPW], len2_[RPW];
     float bias_[RPW];
 #pragma unroll
     for (int r = 0; r < RPW; ++r) {
-        const int2 h = hdr[(row0 + r) * KS + ks];
-        len_[r] = h.x;
-        co_[r] = h.y;
+        if constexpr (Cfg::DUAL) {
+            const int4 h = ((const int4*)a.seg_ptr)[(row0 + r) * KS + ks];
+            len_[r] = h.x;
+            co_[r] = h.y;
+            len2_[r] = h.z;
+        } else {
+            const int2 h = hdr[(row0 + r) * KS + ks];
+            len_[r] = h.x;
+            co_[r] = h.y;
+            len2_[r] = 0;
+        }
     }
 #pragma unroll
-    for (int r = 0; r < RPW; ++r) bias_[r] = (a.bias && co_[r] >= 0) ? a.bias[co_[r]] : 0.0f;
+    for (int r = 0; r < RPW; ++r) {
+        bias_[r] = (a.bias && co_[r] >= 0) ? a.bias[co_[r]] : 0.0f;
+        if constexpr (Cfg::DUAL) bias_[r] += (a.bias2 && co_[r] >= 0) ? a.bias2[co_[r]] : 0.0f;
+    }
 
     // the residual is also fetched up front: one more round trip off the tail
     const T* __restrict__ res = a.residual ? (const T*)a.residual + (size_t)n * a.rd.image : nullptr;
@@ -226,52 +307,10 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_linear_kernel(const ConvLa
     for (int r = 0; r < RPW; ++r) {
 #pragma unroll
         for (int j = 0; j < P; ++j) acc[r][j] = 0.0f;
-        int i = ((row0 + r) * KS + ks) * stride;
-        const int end = i + len_[r];
-        if (i >= end) continue;
-        win.seek(i);
-        // Two register sets (A, B) take turns: while one group is accumulated the
-        // activations of the next are in flight.
-        int groups = (end - i) / U;
-        float wa[U], xa[U][P], wb[U], xb[U][P];
-        uint32_t oa[U], ob[U];
-        win.group<U>(i, wa, oa);
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-            lin_fetch<T, P, ADJ>(rsrc, voff, oa[u], xa[u]);
-        while (true) {
-            if (groups == 1) {
-#pragma unroll
-                for (int u = 0; u < U; ++u)
-#pragma unroll
-                    for (int j = 0; j < P; ++j) acc[r][j] = fmaf(wa[u], xa[u][j], acc[r][j]);
-                break;
-            }
-            win.group<U>(i + U, wb, ob);
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-                lin_fetch<T, P, ADJ>(rsrc, voff, ob[u], xb[u]);
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-#pragma unroll
-                for (int j = 0; j < P; ++j) acc[r][j] = fmaf(wa[u], xa[u][j], acc[r][j]);
-            if (groups == 2) {
-#pragma unroll
-                for (int u = 0; u < U; ++u)
-#pragma unroll
-                    for (int j = 0; j < P; ++j) acc[r][j] = fmaf(wb[u], xb[u][j], acc[r][j]);
-                break;
-            }
-            win.group<U>(i + 2 * U, wa, oa);
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-                lin_fetch<T, P, ADJ>(rsrc, voff, oa[u], xa[u]);
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-#pragma unroll
-                for (int j = 0; j < P; ++j) acc[r][j] = fmaf(wb[u], xb[u][j], acc[r][j]);
-            groups -= 2;
-            i += 2 * U;
+        const int i = ((row0 + r) * KS + ks) * stride;
+        if (len_[r] > 0) lin_accumulate<Cfg>(rsrc, voff, win, i, i + len_[r], acc[r]);
+        if constexpr (Cfg::DUAL) {
+            if (len2_[r] > 0) lin_accumulate<Cfg>(rsrc2, voff2, win, i + len_[r], i + len_[r] + len2_[r], acc[r]);
         }
     }
 
@@ -332,6 +371,7 @@ static ConvVariant make_linear(const char* name) {
     v.unroll = Cfg::U;
     v.adjacent = Cfg::ADJ;
     v.s2d = Cfg::S2D;
+    v.dual = Cfg::DUAL;
     v.lds_bytes = Cfg::KS > 1 ? (size_t)Cfg::NW * Cfg::RPW * Cfg::P * 64 * 4 : 0;
     v.launch = &launch_linear<Cfg>;
     return v;
@@ -346,7 +386,29 @@ static ConvVariant make_linear(const char* name) {
 #define CADNN_LINEAR_S2D(T, P, RPW, KS, NW, U) \
     make_linear<LinearCfg<T, P, RPW, KS, NW, U, 0, 1>>("slinear_" #T "_d" #P "_r" #RPW "k" #KS "w" #NW "u" #U)
 
+#define CADNN_LINEAR_DUAL(T, P, RPW, KS, NW, U) \
+    make_linear<LinearCfg<T, P, RPW, KS, NW, U, 0, 0, 1>>("slinear_" #T "_fp" #P "_r" #RPW "k" #KS "w" #NW "u" #U)
+
+#define CADNN_LINEAR_DUAL_ADJ(T, P, RPW, KS, NW, U) \
+    make_linear<LinearCfg<T, P, RPW, KS, NW, U, 1, 0, 1>>("slinear_" #T "_fa" #P "_r" #RPW "k" #KS "w" #NW "u" #U)
+
 #define CADNN_LINEAR_SHAPES(T)          \
+    CADNN_LINEAR_DUAL(T, 1, 1, 1, 4, 4), \
+    CADNN_LINEAR_DUAL(T, 1, 1, 1, 4, 8), \
+    CADNN_LINEAR_DUAL(T, 1, 1, 2, 4, 4), \
+    CADNN_LINEAR_DUAL(T, 1, 1, 2, 4, 8), \
+    CADNN_LINEAR_DUAL(T, 1, 1, 4, 4, 4), \
+    CADNN_LINEAR_DUAL(T, 1, 1, 4, 4, 8), \
+    CADNN_LINEAR_DUAL(T, 1, 1, 8, 8, 4), \
+    CADNN_LINEAR_DUAL(T, 1, 2, 1, 4, 4), \
+    CADNN_LINEAR_DUAL(T, 2, 1, 1, 4, 4), \
+    CADNN_LINEAR_DUAL(T, 2, 1, 2, 4, 4), \
+    CADNN_LINEAR_DUAL_ADJ(T, 2, 1, 1, 4, 4), \
+    CADNN_LINEAR_DUAL_ADJ(T, 2, 1, 2, 4, 4), \
+    CADNN_LINEAR_DUAL_ADJ(T, 2, 1, 4, 4, 4), \
+    CADNN_LINEAR_DUAL_ADJ(T, 4, 1, 1, 4, 4), \
+    CADNN_LINEAR_DUAL_ADJ(T, 4, 1, 2, 4, 4), \
+    CADNN_LINEAR_DUAL_ADJ(T, 4, 1, 4, 4, 4), \
     CADNN_LINEAR_S2D(T, 1, 1, 1, 4, 4), \
     CADNN_LINEAR_S2D(T, 1, 1, 1, 4, 8), \
     CADNN_LINEAR_S2D(T, 1, 1, 1, 4, 16), \

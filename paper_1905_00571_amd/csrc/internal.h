@@ -156,6 +156,7 @@ struct ConvVariant {
     int unroll;           // nonzeros per scalar fetch; segments are padded to a multiple of it
     int adjacent;         // FAM_LINEAR: a lane's P pixels are adjacent in one output row (unit stride only)
     int s2d;              // FAM_LINEAR: understands de-interleaved output / residual / pixel-wise input
+    int dual;             // FAM_LINEAR: accumulates a fused 1x1 shortcut on a second input
     int nz_cap;           // FAM_STILE: most stream entries per (row group, chunk) the kernel buffers
     size_t lds_bytes;
     hipError_t (*launch)(const ConvLaunch&, hipStream_t);
@@ -175,6 +176,12 @@ struct ConvLaunch {
     int kh, kw, is_f16;
     int tiles_x, tiles_y, row_groups;
     int hwout;                // yd.h * yd.w
+    // fused 1x1 shortcut (FAM_LINEAR dual instantiations): second input, plain view
+    const void* x2;
+    const float* bias2;
+    TensorDesc x2d;
+    int stride2;
+    uint32_t image2_bytes;
     // FAM_PTILE: geometry of the staged tile (see PtileGeom)
     int pt_pitch, pt_sub, pt_plane, pt_nphc, pt_nph, pt_in_rows, pt_in_cols, pt_cch, pt_nstp, pt_nchunks;
     uint32_t pt_lds_bytes;
@@ -220,11 +227,12 @@ PtileGeom ptile_geom(const ConvVariant& v, int cin, int kh, int kw, int stride, 
 constexpr int kPtileMaxSteps = 9;
 constexpr size_t kLdsBytesPerCU = 160 * 1024;
 
-// (variant, a, b): FAM_LINEAR a = input plane, b = input pitch; FAM_PTILE a = stride,
-// b = alias flag; 0, 0 for layout-independent plans
-typedef std::tuple<const ConvVariant*, int, int> PlanKey;
-// (n, h, w, stride, pad, input halo rows, input halo columns, layout flags: 1 = input
-// de-interleaved, 2 = output or residual de-interleaved)
+// (variant, a, b, shortcut weights, shortcut input plane): FAM_LINEAR a = input plane,
+// b = input pitch; FAM_PTILE a = stride, b = alias flag; 0, 0 for layout-independent plans;
+// the last two are NULL, 0 unless a 1x1 shortcut is fused into the layer
+typedef std::tuple<const ConvVariant*, int, int, const void*, int> PlanKey;
+// (n, h, w, stride, pad, input halo rows, input halo columns, flags: 1 = input
+// de-interleaved, 2 = output or residual de-interleaved, 4 = a shortcut is fused in)
 typedef std::array<int, 8> GeomKey;
 
 const std::vector<ConvVariant>& all_tile_variants();
@@ -257,9 +265,19 @@ struct cadnn_weights {
 };
 
 namespace cadnn {
+// A 1x1 projection shortcut fused into the layer whose residual it would have been
+// (paper Section 4, layer fusion): its weights, the tensor it reads and that tensor's layout.
+struct ConvExtra {
+    const cadnn_weights* w;
+    const void* x;
+    TensorDesc xd;
+    int stride;
+    const void* bias;     // device, fp32, may be NULL
+};
+
 // stride / pad / wout matter to FAM_PTILE plans only.
 cadnn_status get_conv_plan(const cadnn_weights* w, const ConvVariant* v, const TensorDesc& xd, int stride,
-                           int pad, int wout, const ConvPlan** out);
+                           int pad, int wout, const ConvPlan** out, const ConvExtra* ex = nullptr);
 void drop_unpinned_plans(const cadnn_weights* w);
 cadnn_status ensure_fc_device(const cadnn_weights* w);
 uint16_t f32_to_f16_rne(float f);
@@ -276,21 +294,23 @@ cadnn_status launch_avgpool(const void* x, const TensorDesc& xd, void* y, int n,
 // Layer entry points on explicit layouts (the C ABI wraps them with contiguous layouts).
 cadnn_status conv2d_impl(const cadnn_weights* w, const void* x, const TensorDesc& xd, void* y,
                          const TensorDesc& yd, const void* residual, const TensorDesc& rd, int n,
-                         int stride, int pad, const void* bias, int relu, hipStream_t s);
+                         int stride, int pad, const void* bias, int relu, hipStream_t s,
+                         const ConvExtra* ex = nullptr);
 cadnn_status conv2d_tune_impl(const cadnn_weights* w, const void* x, const TensorDesc& xd, void* y,
                               const TensorDesc& yd, const void* residual, const TensorDesc& rd, int n,
                               int stride, int pad, const void* bias, int relu, hipStream_t s, int reps,
-                              float* best_us, const std::function<cadnn_status()>* before = nullptr);
+                              float* best_us, const std::function<cadnn_status()>* before = nullptr,
+                              const ConvExtra* ex = nullptr);
 // Name of the variant that would serve the layer (NULL if none).
 // `out_s2d`: the layer's output or residual is in the de-interleaved layout.
 const char* conv2d_variant_name_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad,
-                                     int out_s2d = 0);
+                                     int out_s2d = 0, const ConvExtra* ex = nullptr);
 cadnn_status conv2d_list_variants_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad,
-                                       char* buf, size_t len, int out_s2d = 0);
+                                       char* buf, size_t len, int out_s2d = 0, const ConvExtra* ex = nullptr);
 cadnn_status conv2d_set_variant_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad,
-                                     const char* name, int out_s2d = 0);
+                                     const char* name, int out_s2d = 0, const ConvExtra* ex = nullptr);
 cadnn_status conv2d_prepare_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad,
-                                 int out_s2d = 0);
+                                 int out_s2d = 0, const ConvExtra* ex = nullptr);
 cadnn_status dense_conv2d_desc(const void* w_dev, const void* x, const TensorDesc& xd, void* y,
                                const TensorDesc& yd, const void* residual, const TensorDesc& rd, int n,
                                int cout, int kh, int kw, int stride, int pad, const void* bias, int relu,

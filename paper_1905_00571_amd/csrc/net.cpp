@@ -32,6 +32,8 @@ struct NetOp {
     int src_inst = -1, res_inst = -1;        // producing op of each input (-1 = net input)
     TensorDesc xd, yd, rd;
     size_t y_off = 0;                        // byte offset of this op's output region
+    int shortcut = -1;                       // conv: the 1x1 projection op fused into this one
+    int fused_into = -1;                     // projection: the op that now computes it (it is skipped)
 };
 
 }  // namespace
@@ -48,6 +50,7 @@ struct cadnn_net {
     bool use_graph = false;
     bool want_tune = false;
     bool allow_s2d = true;
+    bool allow_fusion = true;
     char* ws = nullptr;
     hipGraphExec_t exec = nullptr;
     const void* cap_x = nullptr;
@@ -133,11 +136,40 @@ void layout(cadnn_net* net) {
         else
             op.rd = op.yd;
     }
+    // A 1x1 projection shortcut whose only reader takes it as residual is computed inside
+    // that reader (a second sparse matrix on a second input, same accumulators): one launch,
+    // one output write and one residual read less (paper Section 4, layer fusion).
+    for (NetOp& op : net->ops) { op.shortcut = -1; op.fused_into = -1; }
+    if (net->allow_fusion) {
+        std::vector<int> readers(nops, 0);
+        for (const NetOp& op : net->ops) {
+            if (op.src_inst >= 0) ++readers[op.src_inst];
+            if (op.res_inst >= 0) ++readers[op.res_inst];
+        }
+        for (int i = 0; i < nops; ++i) {
+            NetOp& c = net->ops[i];
+            if (c.kind != OP_CONV || c.res_inst < 0) continue;
+            NetOp& p = net->ops[c.res_inst];
+            const bool c_one = c.w->kh == 1 && c.w->kw == 1;
+            const bool ok = p.kind == OP_CONV && p.w->kh == 1 && p.w->kw == 1 && p.pad == 0 && !p.relu && p.res < 0 &&
+                            readers[c.res_inst] == 1 && c.res_inst != nops - 1 && p.w->cout == c.w->cout &&
+                            sparse_enough(c) && sparse_enough(p) && !c.yd.s2d && !(c.xd.s2d && c.stride == 1) &&
+                            (c_one ? c.pad == 0 : (c.xd.ph >= c.pad && c.xd.pw >= c.pad)) &&
+                            (!c.xd.s2d || c_one || (((c.xd.ph - c.pad) & 1) == 0 && ((c.xd.pw - c.pad) & 1) == 0)) &&
+                            (!p.xd.s2d || p.stride == 2);
+            if (ok) {
+                c.shortcut = c.res_inst;
+                p.fused_into = i;
+            }
+        }
+    }
     net->ws_bytes = off;
     net->laid_out = true;
 }
 
-int out_s2d(const NetOp& op) { return (op.yd.s2d || (op.res >= 0 && op.rd.s2d)) ? 1 : 0; }
+int out_s2d(const NetOp& op) {
+    return (op.yd.s2d || (op.res >= 0 && op.shortcut < 0 && op.rd.s2d)) ? 1 : 0;
+}
 
 const void* in_ptr(const cadnn_net* net, int inst, const void* x) {
     return inst < 0 ? x : (const void*)(net->ws + net->ops[inst].y_off);
@@ -147,14 +179,35 @@ void* out_ptr(const cadnn_net* net, size_t i, void* y) {
     return i + 1 == net->ops.size() ? y : (void*)(net->ws + net->ops[i].y_off);
 }
 
+// The fused shortcut of op (if any), reading from the caller's x or the workspace.
+bool shortcut_of(const cadnn_net* net, const NetOp& op, const void* x, ConvExtra* ex) {
+    if (op.shortcut < 0) return false;
+    const NetOp& p = net->ops[op.shortcut];
+    ex->w = p.w;
+    ex->x = in_ptr(net, p.src_inst, x);
+    ex->xd = p.xd;
+    ex->stride = p.stride;
+    ex->bias = p.bias;
+    return true;
+}
+
+// Same for calls that only look at the geometry (the tensor pointer is a placeholder).
+const ConvExtra* shortcut_geom(const cadnn_net* net, const NetOp& op, ConvExtra* ex) {
+    return shortcut_of(net, op, (const void*)net, ex) ? ex : nullptr;
+}
+
 cadnn_status launch_one(cadnn_net* net, size_t i, const void* x, void* y, hipStream_t s) {
     const NetOp& op = net->ops[i];
+    if (op.fused_into >= 0) return CADNN_OK;     // computed inside the op that reads it
     const void* src = in_ptr(net, op.src_inst, x);
     void* dst = out_ptr(net, i, y);
+    ConvExtra ex;
+    const bool fused = shortcut_of(net, op, x, &ex);
     switch (op.kind) {
         case OP_CONV:
-            return conv2d_impl(op.w, src, op.xd, dst, op.yd, op.res >= 0 ? in_ptr(net, op.res_inst, x) : nullptr,
-                               op.rd, op.in.n, op.stride, op.pad, op.bias, op.relu, s);
+            return conv2d_impl(op.w, src, op.xd, dst, op.yd,
+                               (op.res >= 0 && !fused) ? in_ptr(net, op.res_inst, x) : nullptr, op.rd, op.in.n,
+                               op.stride, op.pad, op.bias, op.relu, s, fused ? &ex : nullptr);
         case OP_FC:
             return launch_fc(op.w, src, dst, op.in.n, (const float*)op.bias, op.relu, s);
         case OP_MAXPOOL:
@@ -287,8 +340,10 @@ extern "C" cadnn_status cadnn_net_finalize(cadnn_net* net, void* ws, size_t byte
     // (a plain layout never needs more room than the de-interleaved one that
     // cadnn_net_workspace_bytes reports)
     const bool allow = (flags & CADNN_NET_PLAIN_LAYOUT) == 0;
-    if (!net->laid_out || allow != net->allow_s2d) {
+    const bool fuse = (flags & CADNN_NET_NO_FUSION) == 0;
+    if (!net->laid_out || allow != net->allow_s2d || fuse != net->allow_fusion) {
         net->allow_s2d = allow;
+        net->allow_fusion = fuse;
         layout(net);
     }
     if (net->ws_bytes > 0 && !ws) return fail(CADNN_EINVAL, "cadnn_net_finalize: NULL workspace");
@@ -302,7 +357,9 @@ extern "C" cadnn_status cadnn_net_finalize(cadnn_net* net, void* ws, size_t byte
     }
     for (const NetOp& op : net->ops) {
         cadnn_status st = CADNN_OK;
-        if (op.kind == OP_CONV) st = conv2d_prepare_impl(op.w, op.xd, op.in.n, op.stride, op.pad, out_s2d(op));
+        ConvExtra ex;
+        if (op.kind == OP_CONV && op.fused_into < 0)
+            st = conv2d_prepare_impl(op.w, op.xd, op.in.n, op.stride, op.pad, out_s2d(op), shortcut_geom(net, op, &ex));
         if (op.kind == OP_FC) st = cadnn_fc_prepare(op.w);
         if (st != CADNN_OK) return st;
     }
@@ -321,14 +378,16 @@ extern "C" cadnn_status cadnn_run_net(cadnn_net* net, const void* x, void* y, vo
         cadnn_status st = launch_all(net, x, y, s);
         for (size_t i = 0; i < net->ops.size() && st == CADNN_OK; ++i) {
             const NetOp& op = net->ops[i];
-            if (op.kind != OP_CONV) continue;
+            if (op.kind != OP_CONV || op.fused_into >= 0) continue;
             const std::function<cadnn_status()> producer = [&]() {
                 return op.src_inst >= 0 ? launch_one(net, (size_t)op.src_inst, x, y, s) : CADNN_OK;
             };
+            ConvExtra ex;
+            const bool fused = shortcut_of(net, op, x, &ex);
             st = conv2d_tune_impl(op.w, in_ptr(net, op.src_inst, x), op.xd, out_ptr(net, i, y), op.yd,
-                                  op.res >= 0 ? in_ptr(net, op.res_inst, x) : nullptr, op.rd, op.in.n,
-                                  op.stride, op.pad, op.bias, op.relu, s, 20, nullptr,
-                                  &producer);
+                                  (op.res >= 0 && !fused) ? in_ptr(net, op.res_inst, x) : nullptr, op.rd, op.in.n,
+                                  op.stride, op.pad, op.bias, op.relu, s, 20, nullptr, &producer,
+                                  fused ? &ex : nullptr);
         }
         if (st != CADNN_OK) return st;
         net->want_tune = false;
@@ -408,7 +467,13 @@ extern "C" cadnn_status cadnn_net_op_variant(const cadnn_net* net, int op_index,
     const NetOp& op = net->ops[op_index];
     const char* name = "";
     switch (op.kind) {
-        case OP_CONV: name = conv2d_variant_name_impl(op.w, op.xd, op.in.n, op.stride, op.pad, out_s2d(op)); break;
+        case OP_CONV: {
+            ConvExtra ex;
+            name = op.fused_into >= 0 ? "fused"
+                                      : conv2d_variant_name_impl(op.w, op.xd, op.in.n, op.stride, op.pad, out_s2d(op),
+                                                                 shortcut_geom(net, op, &ex));
+            break;
+        }
         case OP_FC: name = "sfc"; break;
         case OP_MAXPOOL: name = "maxpool"; break;
         case OP_AVGPOOL: name = "avgpool"; break;
@@ -425,7 +490,9 @@ extern "C" cadnn_status cadnn_net_op_candidates(const cadnn_net* net, int op_ind
     if (op_index < 0 || op_index >= (int)net->ops.size()) return fail(CADNN_EINVAL, "cadnn_net_op_candidates: no op %d", op_index);
     const NetOp& op = net->ops[op_index];
     if (op.kind != OP_CONV) return fail(CADNN_EINVAL, "cadnn_net_op_candidates: op %d is not a convolution", op_index);
-    return conv2d_list_variants_impl(op.w, op.xd, op.in.n, op.stride, op.pad, buf, len, out_s2d(op));
+    if (op.fused_into >= 0) return fail(CADNN_EINVAL, "cadnn_net_op_candidates: op %d is computed inside op %d", op_index, op.fused_into);
+    ConvExtra ex;
+    return conv2d_list_variants_impl(op.w, op.xd, op.in.n, op.stride, op.pad, buf, len, out_s2d(op), shortcut_geom(net, op, &ex));
 }
 
 extern "C" cadnn_status cadnn_net_set_op_variant(cadnn_net* net, int op_index, const char* name) {
@@ -434,10 +501,12 @@ extern "C" cadnn_status cadnn_net_set_op_variant(cadnn_net* net, int op_index, c
     if (op_index < 0 || op_index >= (int)net->ops.size()) return fail(CADNN_EINVAL, "cadnn_net_set_op_variant: no op %d", op_index);
     const NetOp& op = net->ops[op_index];
     if (op.kind != OP_CONV) return fail(CADNN_EINVAL, "cadnn_net_set_op_variant: op %d is not a convolution", op_index);
-    cadnn_status st = conv2d_set_variant_impl(op.w, op.xd, op.in.n, op.stride, op.pad, name, out_s2d(op));
+    if (op.fused_into >= 0) return CADNN_OK;     // nothing to pin: computed inside another op
+    ConvExtra ex;
+    cadnn_status st = conv2d_set_variant_impl(op.w, op.xd, op.in.n, op.stride, op.pad, name, out_s2d(op), shortcut_geom(net, op, &ex));
     if (st != CADNN_OK) return st;
     drop_graph(net);
-    return conv2d_prepare_impl(op.w, op.xd, op.in.n, op.stride, op.pad, out_s2d(op));
+    return conv2d_prepare_impl(op.w, op.xd, op.in.n, op.stride, op.pad, out_s2d(op), shortcut_geom(net, op, &ex));
 }
 
 extern "C" cadnn_status cadnn_net_read_buffer(cadnn_net* net, int buf, void* host_out, size_t bytes,
@@ -448,6 +517,8 @@ extern "C" cadnn_status cadnn_net_read_buffer(cadnn_net* net, int buf, void* hos
     if (it == net->producer.end() || it->second < 0 || it->second + 1 == (int)net->ops.size())
         return fail(CADNN_EINVAL, "cadnn_net_read_buffer: buffer %d is not in the workspace", buf);
     const NetOp& op = net->ops[it->second];
+    if (op.fused_into >= 0)
+        return fail(CADNN_EINVAL, "cadnn_net_read_buffer: buffer %d is never materialised (its op is computed inside op %d)", buf, op.fused_into);
     const size_t e = net->elem();
     if (bytes != op.out.elems() * e)
         return fail(CADNN_EINVAL, "cadnn_net_read_buffer: buffer %d holds %zu bytes, %zu asked", buf, op.out.elems() * e, bytes);

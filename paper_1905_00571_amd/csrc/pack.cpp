@@ -214,7 +214,17 @@ static cadnn_status build_direct_plan(const cadnn_weights* w, const ConvVariant*
 // 128 spare zero entries end the stream: a wave reads it 64 entries at a time, one read
 // ahead.
 static cadnn_status build_linear_plan(const cadnn_weights* w, const ConvVariant* v, const TensorDesc& xd,
-                                      ConvPlan* plan) {
+                                      ConvPlan* plan, const ConvExtra* ex) {
+    if ((v->dual != 0) != (ex != nullptr)) return fail(CADNN_EINVAL, "fused shortcut and kernel variant do not match");
+    // fused 1x1 shortcut: its row for original channel co, wherever its own ordering put it
+    std::vector<int32_t> row2;
+    if (ex) {
+        if (ex->w->cout != w->cout || ex->w->kh != 1 || ex->w->kw != 1)
+            return fail(CADNN_EINVAL, "fused shortcut must be a 1x1 layer with the same output channels");
+        row2.assign(w->cout, 0);
+        for (int i = 0; i < ex->w->cout; ++i) row2[ex->w->perm[i]] = i;
+    }
+    const int hw = ex ? 4 : 2;      // header words per part
     const int g = v->rows_per_block();
     const int rows_padded = (w->cout + g - 1) / g * g;
     const int taps = w->kh * w->kw;
@@ -226,11 +236,17 @@ static cadnn_status build_linear_plan(const cadnn_weights* w, const ConvVariant*
     for (int i = 0; i < w->cout; ++i) {
         const int32_t cnt = w->row_ptr[i + 1] - w->row_ptr[i];
         const int32_t per = (cnt + ks - 1) / ks;
-        stride = std::max<int64_t>(stride, (int64_t)(per + U - 1) / U * U);
+        int64_t len = (int64_t)(per + U - 1) / U * U;
+        if (ex) {
+            const int i2 = row2[w->perm[i]];
+            const int32_t per2 = (ex->w->row_ptr[i2 + 1] - ex->w->row_ptr[i2] + ks - 1) / ks;
+            len += (int64_t)(per2 + U - 1) / U * U;
+        }
+        stride = std::max<int64_t>(stride, len);
     }
     const int64_t total = (int64_t)rows_padded * ks * stride + 128;
     if (total > (int64_t)INT32_MAX / 2) return fail(CADNN_EUNSUPPORTED, "plan too large");
-    std::vector<int32_t> hdr((size_t)rows_padded * ks * 2, 0);
+    std::vector<int32_t> hdr((size_t)rows_padded * ks * hw, 0);
     std::vector<int32_t> perm(rows_padded, -1);
     std::vector<uint2> nz((size_t)total, make_uint2(0u, 0u));
     for (int i = 0; i < rows_padded; ++i) {
@@ -253,8 +269,24 @@ static cadnn_status build_linear_plan(const cadnn_weights* w, const ConvVariant*
                 std::memcpy(&bits, &w->vals[j], 4);
                 out[j - pb] = make_uint2(bits, (uint32_t)off);
             }
-            hdr[((size_t)i * ks + s) * 2 + 0] = (pe - pb + U - 1) / U * U;
-            hdr[((size_t)i * ks + s) * 2 + 1] = perm[i];
+            const int32_t len1 = (pe - pb + U - 1) / U * U;
+            hdr[((size_t)i * ks + s) * hw + 0] = len1;
+            hdr[((size_t)i * ks + s) * hw + 1] = perm[i];
+            if (ex && i < w->cout) {
+                // the shortcut's slice follows the layer's own (padded) slice
+                const int i2 = row2[w->perm[i]];
+                const int32_t b2 = ex->w->row_ptr[i2], e2 = ex->w->row_ptr[i2 + 1];
+                const int32_t per2 = (e2 - b2 + ks - 1) / ks;
+                const int32_t qb = (int32_t)std::min<int64_t>((int64_t)b2 + (int64_t)s * per2, e2);
+                const int32_t qe = (int32_t)std::min<int64_t>((int64_t)qb + per2, e2);
+                for (int32_t j = qb; j < qe; ++j) {
+                    const int64_t off = (int64_t)ex->w->col_idx[j] * ex->xd.plane * esz;   // 1x1: column = channel
+                    uint32_t bits;
+                    std::memcpy(&bits, &ex->w->vals[j], 4);
+                    out[len1 + (j - qb)] = make_uint2(bits, (uint32_t)off);
+                }
+                hdr[((size_t)i * ks + s) * hw + 2] = (qe - qb + U - 1) / U * U;
+            }
         }
     }
     plan->variant = v;
@@ -481,23 +513,26 @@ static cadnn_status build_dense_plan(const cadnn_weights* w, const ConvVariant* 
 }
 
 static cadnn_status build_plan(const cadnn_weights* w, const ConvVariant* v, const TensorDesc& xd, int stride,
-                               int pad, int wout, ConvPlan* plan) {
+                               int pad, int wout, ConvPlan* plan, const ConvExtra* ex) {
+    if (ex && v->family != FAM_LINEAR) return fail(CADNN_EINVAL, "a fused shortcut needs a linear-address kernel");
     switch (v->family) {
         case FAM_PTILE: return build_ptile_plan(w, v, stride, pad, wout, plan);
         case FAM_DENSE: return build_dense_plan(w, v, plan);
         case FAM_STILE: return build_stile_plan(w, v, plan);
         case FAM_DIRECT: return build_direct_plan(w, v, plan);
-        case FAM_LINEAR: return build_linear_plan(w, v, xd, plan);
+        case FAM_LINEAR: return build_linear_plan(w, v, xd, plan, ex);
         default: return build_tile_plan(w, v, plan);
     }
 }
 
 static PlanKey plan_key(const cadnn_weights* w, const ConvVariant* v, const TensorDesc& xd, int stride, int pad,
-                        int wout) {
-    if (v->family == FAM_LINEAR) return PlanKey(v, xd.plane, xd.pitch | (xd.s2d ? 1 << 30 : 0));
+                        int wout, const ConvExtra* ex) {
+    if (v->family == FAM_LINEAR)
+        return PlanKey(v, xd.plane, xd.pitch | (xd.s2d ? 1 << 30 : 0), ex ? (const void*)ex->w : nullptr,
+                       ex ? ex->xd.plane : 0);
     if (v->family == FAM_PTILE)
-        return PlanKey(v, stride, ptile_geom(*v, w->cin, w->kh, w->kw, stride, pad, wout).alias);
-    return PlanKey(v, 0, 0);
+        return PlanKey(v, stride, ptile_geom(*v, w->cin, w->kh, w->kw, stride, pad, wout).alias, nullptr, 0);
+    return PlanKey(v, 0, 0, nullptr, 0);
 }
 
 // Frees every plan whose variant is not pinned for some geometry of this handle.
@@ -511,16 +546,16 @@ void drop_unpinned_plans(const cadnn_weights* w) {
 }
 
 cadnn_status get_conv_plan(const cadnn_weights* w, const ConvVariant* v, const TensorDesc& xd, int stride,
-                           int pad, int wout, const ConvPlan** out) {
+                           int pad, int wout, const ConvPlan** out, const ConvExtra* ex) {
     std::lock_guard<std::mutex> lock(w->mu);
-    const PlanKey key = plan_key(w, v, xd, stride, pad, wout);
+    const PlanKey key = plan_key(w, v, xd, stride, pad, wout, ex);
     auto it = w->plans.find(key);
     if (it == w->plans.end()) {
         std::unique_ptr<ConvPlan> plan(new (std::nothrow) ConvPlan());
         if (!plan) return fail(CADNN_ENOMEM, "out of host memory");
         cadnn_status st;
         try {
-            st = build_plan(w, v, xd, stride, pad, wout, plan.get());
+            st = build_plan(w, v, xd, stride, pad, wout, plan.get(), ex);
         } catch (const std::bad_alloc&) {
             return fail(CADNN_ENOMEM, "out of host memory building a conv plan");
         }

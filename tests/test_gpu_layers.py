@@ -334,8 +334,8 @@ def test_every_variant_on_deinterleaved_tensors(cad, geom):
     for dtype, npdt, tol in ((cad.F32, np.float32, TOL_F32), (cad.F16, np.float16, TOL_F16)):
         xs = x.astype(npdt)
         ref, ins, outs = oracle.run_net(ops, xs, ws, bs, dtype=npdt)
-        net = cad.build_net(ops, ws, bs, shape, dtype, use_graph=False)
-        plain = cad.build_net(ops, ws, bs, shape, dtype, use_graph=False, plain_layout=True)
+        net = cad.build_net(ops, ws, bs, shape, dtype, use_graph=False, fuse=False)
+        plain = cad.build_net(ops, ws, bs, shape, dtype, use_graph=False, plain_layout=True, fuse=False)
         xd = dev(xs)
         for i in range(5):
             names = net.op_candidates(i)
@@ -356,3 +356,53 @@ def test_every_variant_on_deinterleaved_tensors(cad, geom):
             y.cpu().numpy().astype(np.float64), yp.cpu().numpy().astype(np.float64), rtol=0, atol=tol * np.abs(ref).max())
         net.free()
         plain.free()
+
+
+@pytest.mark.parametrize("geom", [(12, 12, 1, 2), (20, 28, 2, 2), (14, 14, 3, 1), (9, 11, 2, 1)])
+def test_fused_projection_shortcut(cad, geom):
+    """A 1x1 projection shortcut whose only reader adds it as residual is computed inside
+    that reader: the projection op reports "fused", its buffer is never materialised, and
+    every dual-input variant of the reader must reproduce the oracle's block output -- with
+    the block input de-interleaved (stride-2 block) or plain (stride-1 block), both storage
+    types, and the same as the net without fusion."""
+    h, w_, n, stride = geom
+    ops = [wl.Op("conv", "t", 0, 1, 8, 16, 1, 1, 0, 0.8, True),
+           wl.Op("conv", "a", 1, 2, 16, 8, 1, 1, 0, 0.8, True),
+           wl.Op("conv", "b", 2, 3, 8, 8, 3, stride, 1, 0.85, True),
+           wl.Op("conv", "p", 1, 4, 16, 24, 1, stride, 0, 0.8, False),
+           wl.Op("conv", "c", 3, 5, 8, 24, 1, 1, 0, 0.8, True, 4),
+           wl.Op("conv", "post", 5, 6, 24, 6, 1, 1, 0, 0.2, False)]
+    shape = (n, 8, h, w_)
+    x, ws, bs = wl.net_tensors(ops, "fuse-%d-%d-%d" % (h, w_, stride), shape, input_relu=True)
+    for dtype, npdt, tol in ((cad.F32, np.float32, TOL_F32), (cad.F16, np.float16, TOL_F16)):
+        xs = x.astype(npdt)
+        ref, ins, outs = oracle.run_net(ops, xs, ws, bs, dtype=npdt)
+        net = cad.build_net(ops, ws, bs, shape, dtype, use_graph=False)
+        unfused = cad.build_net(ops, ws, bs, shape, dtype, use_graph=False, fuse=False)
+        xd = dev(xs)
+        assert net.op_variant(3) == "fused" and unfused.op_variant(3) != "fused"
+        with pytest.raises(cad.CadnnError):
+            net.read_buffer(4, outs[3].shape)
+        names = net.op_candidates(4)
+        assert names and all("_f" in nm for nm in names), names
+        # what is summed now: the layer's own terms and the shortcut's
+        cond = cond_conv(ins[4], ws[4].astype(npdt), bs[4], None, 1, 0) + \
+            cond_conv(ins[3], ws[3].astype(npdt), bs[3], None, stride, 0)
+        for name in names:
+            net.set_op_variant(4, name)
+            assert net.op_variant(4) == name
+            y = net.run(xd)
+            torch.cuda.synchronize()
+            got = net.read_buffer(5, outs[4].shape)
+            # fp16: the unfused definition rounds the shortcut to fp16 before adding it
+            extra_tol = 2.0 ** -10 * np.abs(outs[3].astype(np.float64)) if dtype == cad.F16 else 0.0
+            d = np.abs(got.astype(np.float64) - outs[4].astype(np.float64))
+            bound = 1e-4 * cond + (2.0 ** -10 if dtype == cad.F16 else 0.0) * np.abs(outs[4].astype(np.float64)) + extra_tol + 1e-30
+            assert (d <= bound).all(), f"{geom} {name}: worst ratio {(d / bound).max():.3f}"
+            assert d.max() / np.abs(outs[4]).max() <= tol
+        yf = net.run(xd).cpu().numpy().astype(np.float64)
+        yu = unfused.run(xd).cpu().numpy().astype(np.float64)
+        torch.cuda.synchronize()
+        assert np.abs(yf - yu).max() <= tol * np.abs(ref).max()
+        net.free()
+        unfused.free()
