@@ -221,8 +221,20 @@ def main() -> int:
     per_op_ms = net.profile(xd, y, repeats=20, stream=stream)
     costs = layer_costs(ops, ws, shape, elem)
     groups = {}
+    names = [net.op_variant(i) for i in range(len(ops))]
+    # a projection shortcut computed inside its reader: its multiply-adds, input and weights
+    # move to the reader; its output write and the reader's residual read no longer exist
     for i, op in enumerate(ops):
-        name = net.op_variant(i)
+        if names[i] != "fused":
+            continue
+        j = next(k for k, o in enumerate(ops) if o.kind == "conv" and o.res == op.dst)
+        out_bytes = float(np.prod(costs[i]["out"])) * elem
+        costs[j]["flops"] += costs[i]["flops"]
+        costs[j]["bytes"] += costs[i]["bytes"] - out_bytes - out_bytes
+        costs[j]["nnz"] += costs[i]["nnz"]
+        costs[i]["flops"] = costs[i]["bytes"] = 0.0
+    for i, op in enumerate(ops):
+        name = names[i]
         costs[i]["kernel"] = name
         costs[i]["ms"] = float(per_op_ms[i])
         t = costs[i]["ms"] * 1e-3
