@@ -227,6 +227,15 @@ def main() -> int:
     for i, op in enumerate(ops):
         if names[i] != "fused":
             continue
+        if op.kind == "avgpool":
+            # pooled in the epilogue of the convolution that feeds it: that layer's feature map
+            # is neither written nor read back; only the pooled vector is written
+            j = max(k for k, o in enumerate(ops[:i]) if o.dst == op.src)
+            map_bytes = float(np.prod(costs[i]["in"])) * elem
+            costs[j]["flops"] += costs[i]["flops"]
+            costs[j]["bytes"] += costs[i]["bytes"] - 2.0 * map_bytes
+            costs[i]["flops"] = costs[i]["bytes"] = 0.0
+            continue
         j = next(k for k, o in enumerate(ops) if o.kind == "conv" and o.res == op.dst)
         out_bytes = float(np.prod(costs[i]["out"])) * elem
         costs[j]["flops"] += costs[i]["flops"]

@@ -193,9 +193,10 @@ cadnn_status cadnn_net_workspace_bytes(const cadnn_net* net, size_t* bytes);
  * default the output of a convolution that is read by stride-2 convolutions is kept
  * de-interleaved by row/column parity, so those layers read it with unit stride;
  * CADNN_NET_NO_FUSION -- launch every op on its own; by default a 1x1 projection shortcut
- * whose only reader adds it as residual is computed inside that reader (its buffer is
- * then never written and cadnn_net_read_buffer refuses it, its profile time is zero and
- * its variant name is "fused"). */
+ * whose only reader adds it as residual is computed inside that reader, and a global
+ * average pool that is the only reader of a small-image convolution is computed in that
+ * convolution's epilogue (the skipped op's profile time is zero and its variant name is
+ * "fused"; the buffer that is no longer written is refused by cadnn_net_read_buffer). */
 #define CADNN_NET_GRAPH 1
 #define CADNN_NET_TUNE 2
 #define CADNN_NET_PLAIN_LAYOUT 4

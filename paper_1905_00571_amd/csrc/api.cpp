@@ -16,7 +16,8 @@ struct ConvGeom {
     int out_s2d = 0;          // output or residual de-interleaved
     const ConvExtra* ex = nullptr;   // fused 1x1 shortcut
     GeomKey key() const {
-        return {n, xd.h, xd.w, stride, pad, xd.ph, xd.pw, (xd.s2d ? 1 : 0) | (out_s2d ? 2 : 0) | (ex ? 4 : 0)};
+        return {n, xd.h, xd.w, stride, pad, xd.ph, xd.pw,
+                (xd.s2d ? 1 : 0) | (out_s2d ? 2 : 0) | ((ex && ex->w) ? 4 : 0) | ((ex && ex->pool_y) ? 8 : 0)};
     }
 };
 
@@ -27,8 +28,9 @@ static cadnn_status check_conv(const char* who, const cadnn_weights* w, const Te
     if (stride <= 0 || pad < 0) return fail(CADNN_EINVAL, "%s: bad stride/pad", who);
     if (xd.c != w->cin) return fail(CADNN_EINVAL, "%s: %d input channels, weights take %d", who, xd.c, w->cin);
     g->n = n; g->stride = stride; g->pad = pad; g->xd = xd; g->out_s2d = out_s2d; g->ex = ex;
-    if (ex) {
-        if (!ex->w || !ex->x) return fail(CADNN_EINVAL, "%s: NULL fused shortcut", who);
+    if (ex && !ex->w && !ex->pool_y) return fail(CADNN_EINVAL, "%s: empty fusion request", who);
+    if (ex && ex->w) {
+        if (!ex->x) return fail(CADNN_EINVAL, "%s: NULL fused shortcut", who);
         if (ex->w->kh != 1 || ex->w->kw != 1 || ex->w->cout != w->cout || ex->w->dtype != w->dtype ||
             ex->w->cin != ex->xd.c || ex->stride <= 0)
             return fail(CADNN_EINVAL, "%s: the fused shortcut must be a 1x1 layer of the same type and output channels", who);
@@ -72,8 +74,11 @@ static bool variant_fits(const ConvVariant& v, const cadnn_weights* w, const Con
         if (general != (v.s2d != 0)) return false;
         // a fused shortcut takes the dual-input instantiations; its input must be walkable
         // with one stride (plain layout, or de-interleaved and read with stride 2)
-        if ((g.ex != nullptr) != (v.dual != 0)) return false;
-        if (g.ex) {
+        const bool shortcut = g.ex && g.ex->w, pooled = g.ex && g.ex->pool_y;
+        if (shortcut != (v.dual != 0) || pooled != (v.pool != 0)) return false;
+        // a fused pool needs the whole image in one pixel tile of the variant
+        if (pooled && (general || shortcut || g.hout * g.wout > 64 * v.p)) return false;
+        if (shortcut) {
             if (general) return false;
             if (g.ex->xd.s2d && g.ex->stride != 2) return false;
             const int unit2 = g.ex->xd.s2d ? 2 : 1;
@@ -184,7 +189,11 @@ static cadnn_status launch_variant(const cadnn_weights* w, const ConvVariant* v,
     a.perm = (const int32_t*)plan->perm.p;
     a.xd = g.xd; a.yd = yd; a.rd = rd;
     a.n = g.n; a.cout = w->cout; a.stride = g.stride; a.pad = g.pad; a.relu = relu ? 1 : 0;
-    if (g.ex) {
+    if (g.ex && g.ex->pool_y) {
+        a.pool_y = g.ex->pool_y;
+        a.pool_scale = 1.0f / (float)(g.hout * g.wout);
+    }
+    if (g.ex && g.ex->w) {
         // the shortcut's input as a plain view walked with one stride from pixel (0, 0)
         a.x2 = g.ex->x;
         a.bias2 = (const float*)g.ex->bias;

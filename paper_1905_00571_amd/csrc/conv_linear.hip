@@ -38,11 +38,16 @@ constexpr uint32_t kLinOutOfRange = 0x7ffffff0u;   // beyond any buffer this lib
 //          residual of (the shortcut's kernel launch, its output write and the residual
 //          read disappear).  A part of the stream is then the layer's entries followed by
 //          the shortcut's, and the header is {length, channel, shortcut length, -}.
-template <typename T_, int P_, int RPW_, int KS_, int NW_, int U_, int ADJ_ = 0, int S2D_ = 0, int DUAL_ = 0>
+// POOL = 1: the layer's only reader is a global average pool and one pixel tile covers the
+//          image: the epilogue averages the wave's pixels and writes the pooled vector;
+//          the feature map itself is never written.
+template <typename T_, int P_, int RPW_, int KS_, int NW_, int U_, int ADJ_ = 0, int S2D_ = 0, int DUAL_ = 0,
+          int POOL_ = 0>
 struct LinearCfg {
     using T = T_;
-    static constexpr int P = P_, RPW = RPW_, KS = KS_, NW = NW_, U = U_, ADJ = ADJ_, S2D = S2D_, DUAL = DUAL_;
-    static_assert(!(S2D && DUAL), "not combined");
+    static constexpr int P = P_, RPW = RPW_, KS = KS_, NW = NW_, U = U_, ADJ = ADJ_, S2D = S2D_, DUAL = DUAL_,
+                         POOL = POOL_;
+    static_assert(!(S2D && DUAL) && !(POOL && (S2D || DUAL || ADJ)), "not combined");
     static_assert(!(ADJ && S2D), "adjacent pixels are not adjacent in a de-interleaved tensor");
     static constexpr int RG = NW / KS;
     static constexpr int THREADS = NW * 64;
@@ -333,6 +338,28 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_linear_kernel(const ConvLa
             }
     }
 
+    if constexpr (Cfg::POOL) {
+        // ---- fused epilogue + global average pool: every pixel of the channel is in this
+        //      wave (each value rounded to the storage type first, as the separate pool
+        //      would have read it), summed across the wavefront
+        T* __restrict__ py = (T*)a.pool_y + (size_t)n * a.cout;
+#pragma unroll
+        for (int r = 0; r < RPW; ++r) {
+            const int co = co_[r];
+            float sum = 0.0f;
+#pragma unroll
+            for (int j = 0; j < P; ++j) {
+                float v = acc[r][j] + bias_[r] + resv[r][j];
+                if (a.relu) v = v > 0.0f ? v : 0.0f;
+                sum += oidx[j] >= 0 ? (float)(T)v : 0.0f;
+            }
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off, 64);
+            if (lane == 0 && co >= 0) py[co] = (T)(sum * a.pool_scale);
+        }
+        return;
+    }
+
     // ---- fused epilogue: + bias, + residual, ReLU, store at the original channel
     T* __restrict__ y = (T*)a.y + (size_t)n * a.yd.image;
 #pragma unroll
@@ -372,6 +399,7 @@ static ConvVariant make_linear(const char* name) {
     v.adjacent = Cfg::ADJ;
     v.s2d = Cfg::S2D;
     v.dual = Cfg::DUAL;
+    v.pool = Cfg::POOL;
     v.lds_bytes = Cfg::KS > 1 ? (size_t)Cfg::NW * Cfg::RPW * Cfg::P * 64 * 4 : 0;
     v.launch = &launch_linear<Cfg>;
     return v;
@@ -392,7 +420,19 @@ static ConvVariant make_linear(const char* name) {
 #define CADNN_LINEAR_DUAL_ADJ(T, P, RPW, KS, NW, U) \
     make_linear<LinearCfg<T, P, RPW, KS, NW, U, 1, 0, 1>>("slinear_" #T "_fa" #P "_r" #RPW "k" #KS "w" #NW "u" #U)
 
+#define CADNN_LINEAR_POOL(T, P, RPW, KS, NW, U) \
+    make_linear<LinearCfg<T, P, RPW, KS, NW, U, 0, 0, 0, 1>>("slinear_" #T "_gp" #P "_r" #RPW "k" #KS "w" #NW "u" #U)
+
 #define CADNN_LINEAR_SHAPES(T)          \
+    CADNN_LINEAR_POOL(T, 1, 1, 1, 4, 4), \
+    CADNN_LINEAR_POOL(T, 1, 1, 1, 4, 8), \
+    CADNN_LINEAR_POOL(T, 1, 1, 2, 4, 4), \
+    CADNN_LINEAR_POOL(T, 1, 1, 2, 4, 8), \
+    CADNN_LINEAR_POOL(T, 1, 1, 4, 4, 4), \
+    CADNN_LINEAR_POOL(T, 1, 1, 4, 4, 8), \
+    CADNN_LINEAR_POOL(T, 1, 1, 8, 8, 4), \
+    CADNN_LINEAR_POOL(T, 2, 1, 2, 4, 4), \
+    CADNN_LINEAR_POOL(T, 4, 1, 2, 4, 4), \
     CADNN_LINEAR_DUAL(T, 1, 1, 1, 4, 4), \
     CADNN_LINEAR_DUAL(T, 1, 1, 1, 4, 8), \
     CADNN_LINEAR_DUAL(T, 1, 1, 2, 4, 4), \

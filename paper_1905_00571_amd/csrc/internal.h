@@ -157,6 +157,7 @@ struct ConvVariant {
     int adjacent;         // FAM_LINEAR: a lane's P pixels are adjacent in one output row (unit stride only)
     int s2d;              // FAM_LINEAR: understands de-interleaved output / residual / pixel-wise input
     int dual;             // FAM_LINEAR: accumulates a fused 1x1 shortcut on a second input
+    int pool;             // FAM_LINEAR: global average pool fused into the epilogue
     int nz_cap;           // FAM_STILE: most stream entries per (row group, chunk) the kernel buffers
     size_t lds_bytes;
     hipError_t (*launch)(const ConvLaunch&, hipStream_t);
@@ -182,6 +183,9 @@ struct ConvLaunch {
     TensorDesc x2d;
     int stride2;
     uint32_t image2_bytes;
+    // fused global average pool (FAM_LINEAR pool instantiations): [n][cout] means
+    void* pool_y;
+    float pool_scale;
     // FAM_PTILE: geometry of the staged tile (see PtileGeom)
     int pt_pitch, pt_sub, pt_plane, pt_nphc, pt_nph, pt_in_rows, pt_in_cols, pt_cch, pt_nstp, pt_nchunks;
     uint32_t pt_lds_bytes;
@@ -232,7 +236,8 @@ constexpr size_t kLdsBytesPerCU = 160 * 1024;
 // the last two are NULL, 0 unless a 1x1 shortcut is fused into the layer
 typedef std::tuple<const ConvVariant*, int, int, const void*, int> PlanKey;
 // (n, h, w, stride, pad, input halo rows, input halo columns, flags: 1 = input
-// de-interleaved, 2 = output or residual de-interleaved, 4 = a shortcut is fused in)
+// de-interleaved, 2 = output or residual de-interleaved, 4 = a shortcut is fused in,
+// 8 = a global average pool is fused in)
 typedef std::array<int, 8> GeomKey;
 
 const std::vector<ConvVariant>& all_tile_variants();
@@ -267,12 +272,15 @@ struct cadnn_weights {
 namespace cadnn {
 // A 1x1 projection shortcut fused into the layer whose residual it would have been
 // (paper Section 4, layer fusion): its weights, the tensor it reads and that tensor's layout.
+// Or (w == NULL, pool_y != NULL) a global average pool fused into the layer it reads: the
+// layer writes the pooled [n][cout] vector to pool_y instead of its feature map.
 struct ConvExtra {
     const cadnn_weights* w;
     const void* x;
     TensorDesc xd;
     int stride;
     const void* bias;     // device, fp32, may be NULL
+    void* pool_y;
 };
 
 // stride / pad / wout matter to FAM_PTILE plans only.

@@ -33,7 +33,8 @@ struct NetOp {
     TensorDesc xd, yd, rd;
     size_t y_off = 0;                        // byte offset of this op's output region
     int shortcut = -1;                       // conv: the 1x1 projection op fused into this one
-    int fused_into = -1;                     // projection: the op that now computes it (it is skipped)
+    int pool_op = -1;                        // conv: the global average pool op fused into this one
+    int fused_into = -1;                     // projection / pool: the op that now computes it (it is skipped)
 };
 
 }  // namespace
@@ -139,7 +140,7 @@ void layout(cadnn_net* net) {
     // A 1x1 projection shortcut whose only reader takes it as residual is computed inside
     // that reader (a second sparse matrix on a second input, same accumulators): one launch,
     // one output write and one residual read less (paper Section 4, layer fusion).
-    for (NetOp& op : net->ops) { op.shortcut = -1; op.fused_into = -1; }
+    for (NetOp& op : net->ops) { op.shortcut = -1; op.pool_op = -1; op.fused_into = -1; }
     if (net->allow_fusion) {
         std::vector<int> readers(nops, 0);
         for (const NetOp& op : net->ops) {
@@ -162,6 +163,22 @@ void layout(cadnn_net* net) {
                 p.fused_into = i;
             }
         }
+        // A global average pool that is the only reader of a convolution whose image fits one
+        // pixel tile is computed in that convolution's epilogue; the feature map is not written.
+        for (int i = 0; i < nops; ++i) {
+            NetOp& a = net->ops[i];
+            if (a.kind != OP_AVGPOOL || a.src_inst < 0) continue;
+            NetOp& c = net->ops[a.src_inst];
+            const bool c_one = c.kind == OP_CONV && c.w->kh == 1 && c.w->kw == 1;
+            const bool ok = c.kind == OP_CONV && readers[a.src_inst] == 1 && c.shortcut < 0 && c.fused_into < 0 &&
+                            sparse_enough(c) && !c.yd.s2d && !c.xd.s2d && !(c.res >= 0 && c.rd.s2d) &&
+                            c.out.h * c.out.w <= 256 &&
+                            (c_one ? c.pad == 0 : (c.xd.ph >= c.pad && c.xd.pw >= c.pad));
+            if (ok) {
+                c.pool_op = i;
+                a.fused_into = a.src_inst;
+            }
+        }
     }
     net->ws_bytes = off;
     net->laid_out = true;
@@ -179,16 +196,26 @@ void* out_ptr(const cadnn_net* net, size_t i, void* y) {
     return i + 1 == net->ops.size() ? y : (void*)(net->ws + net->ops[i].y_off);
 }
 
-// The fused shortcut of op (if any), reading from the caller's x or the workspace.
-bool shortcut_of(const cadnn_net* net, const NetOp& op, const void* x, ConvExtra* ex) {
-    if (op.shortcut < 0) return false;
-    const NetOp& p = net->ops[op.shortcut];
-    ex->w = p.w;
-    ex->x = in_ptr(net, p.src_inst, x);
-    ex->xd = p.xd;
-    ex->stride = p.stride;
-    ex->bias = p.bias;
-    return true;
+void* out_ptr(const cadnn_net* net, size_t i, void* y);
+
+// What is fused into op (if anything): a projection shortcut, reading from the caller's x or
+// the workspace, or a global average pool, writing to the pool op's own output.
+bool shortcut_of(const cadnn_net* net, const NetOp& op, const void* x, ConvExtra* ex, void* y = nullptr) {
+    *ex = ConvExtra{};
+    if (op.shortcut >= 0) {
+        const NetOp& p = net->ops[op.shortcut];
+        ex->w = p.w;
+        ex->x = in_ptr(net, p.src_inst, x);
+        ex->xd = p.xd;
+        ex->stride = p.stride;
+        ex->bias = p.bias;
+        return true;
+    }
+    if (op.pool_op >= 0) {
+        ex->pool_y = y ? out_ptr(net, (size_t)op.pool_op, y) : (void*)net;   // placeholder for geometry-only calls
+        return true;
+    }
+    return false;
 }
 
 // Same for calls that only look at the geometry (the tensor pointer is a placeholder).
@@ -202,11 +229,11 @@ cadnn_status launch_one(cadnn_net* net, size_t i, const void* x, void* y, hipStr
     const void* src = in_ptr(net, op.src_inst, x);
     void* dst = out_ptr(net, i, y);
     ConvExtra ex;
-    const bool fused = shortcut_of(net, op, x, &ex);
+    const bool fused = shortcut_of(net, op, x, &ex, y);
     switch (op.kind) {
         case OP_CONV:
             return conv2d_impl(op.w, src, op.xd, dst, op.yd,
-                               (op.res >= 0 && !fused) ? in_ptr(net, op.res_inst, x) : nullptr, op.rd, op.in.n,
+                               (op.res >= 0 && op.shortcut < 0) ? in_ptr(net, op.res_inst, x) : nullptr, op.rd, op.in.n,
                                op.stride, op.pad, op.bias, op.relu, s, fused ? &ex : nullptr);
         case OP_FC:
             return launch_fc(op.w, src, dst, op.in.n, (const float*)op.bias, op.relu, s);
@@ -383,9 +410,9 @@ extern "C" cadnn_status cadnn_run_net(cadnn_net* net, const void* x, void* y, vo
                 return op.src_inst >= 0 ? launch_one(net, (size_t)op.src_inst, x, y, s) : CADNN_OK;
             };
             ConvExtra ex;
-            const bool fused = shortcut_of(net, op, x, &ex);
+            const bool fused = shortcut_of(net, op, x, &ex, y);
             st = conv2d_tune_impl(op.w, in_ptr(net, op.src_inst, x), op.xd, out_ptr(net, i, y), op.yd,
-                                  (op.res >= 0 && !fused) ? in_ptr(net, op.res_inst, x) : nullptr, op.rd, op.in.n,
+                                  (op.res >= 0 && op.shortcut < 0) ? in_ptr(net, op.res_inst, x) : nullptr, op.rd, op.in.n,
                                   op.stride, op.pad, op.bias, op.relu, s, 20, nullptr, &producer,
                                   fused ? &ex : nullptr);
         }
@@ -476,7 +503,7 @@ extern "C" cadnn_status cadnn_net_op_variant(const cadnn_net* net, int op_index,
         }
         case OP_FC: name = "sfc"; break;
         case OP_MAXPOOL: name = "maxpool"; break;
-        case OP_AVGPOOL: name = "avgpool"; break;
+        case OP_AVGPOOL: name = op.fused_into >= 0 ? "fused" : "avgpool"; break;
     }
     if (!name) return CADNN_EUNSUPPORTED;
     std::strncpy(buf, name, len - 1);
@@ -517,8 +544,11 @@ extern "C" cadnn_status cadnn_net_read_buffer(cadnn_net* net, int buf, void* hos
     if (it == net->producer.end() || it->second < 0 || it->second + 1 == (int)net->ops.size())
         return fail(CADNN_EINVAL, "cadnn_net_read_buffer: buffer %d is not in the workspace", buf);
     const NetOp& op = net->ops[it->second];
-    if (op.fused_into >= 0)
+    // (a fused pool's vector is written, by the convolution; a fused projection's map is not)
+    if (op.fused_into >= 0 && op.kind == OP_CONV)
         return fail(CADNN_EINVAL, "cadnn_net_read_buffer: buffer %d is never materialised (its op is computed inside op %d)", buf, op.fused_into);
+    if (op.pool_op >= 0)
+        return fail(CADNN_EINVAL, "cadnn_net_read_buffer: buffer %d is never materialised (op %d pools it on the fly)", buf, it->second);
     const size_t e = net->elem();
     if (bytes != op.out.elems() * e)
         return fail(CADNN_EINVAL, "cadnn_net_read_buffer: buffer %d holds %zu bytes, %zu asked", buf, op.out.elems() * e, bytes);

@@ -215,6 +215,7 @@ static cadnn_status build_direct_plan(const cadnn_weights* w, const ConvVariant*
 // ahead.
 static cadnn_status build_linear_plan(const cadnn_weights* w, const ConvVariant* v, const TensorDesc& xd,
                                       ConvPlan* plan, const ConvExtra* ex) {
+    if (ex && !ex->w) ex = nullptr;      // a fused pool does not touch the plan
     if ((v->dual != 0) != (ex != nullptr)) return fail(CADNN_EINVAL, "fused shortcut and kernel variant do not match");
     // fused 1x1 shortcut: its row for original channel co, wherever its own ordering put it
     std::vector<int32_t> row2;
@@ -514,7 +515,7 @@ static cadnn_status build_dense_plan(const cadnn_weights* w, const ConvVariant* 
 
 static cadnn_status build_plan(const cadnn_weights* w, const ConvVariant* v, const TensorDesc& xd, int stride,
                                int pad, int wout, ConvPlan* plan, const ConvExtra* ex) {
-    if (ex && v->family != FAM_LINEAR) return fail(CADNN_EINVAL, "a fused shortcut needs a linear-address kernel");
+    if (ex && v->family != FAM_LINEAR) return fail(CADNN_EINVAL, "a fused shortcut or pool needs a linear-address kernel");
     switch (v->family) {
         case FAM_PTILE: return build_ptile_plan(w, v, stride, pad, wout, plan);
         case FAM_DENSE: return build_dense_plan(w, v, plan);
@@ -529,7 +530,7 @@ static PlanKey plan_key(const cadnn_weights* w, const ConvVariant* v, const Tens
                         int wout, const ConvExtra* ex) {
     if (v->family == FAM_LINEAR)
         return PlanKey(v, xd.plane, xd.pitch | (xd.s2d ? 1 << 30 : 0), ex ? (const void*)ex->w : nullptr,
-                       ex ? ex->xd.plane : 0);
+                       (ex && ex->w) ? ex->xd.plane : 0);
     if (v->family == FAM_PTILE)
         return PlanKey(v, stride, ptile_geom(*v, w->cin, w->kh, w->kw, stride, pad, wout).alias, nullptr, 0);
     return PlanKey(v, 0, 0, nullptr, 0);

@@ -406,3 +406,46 @@ def test_fused_projection_shortcut(cad, geom):
         assert np.abs(yf - yu).max() <= tol * np.abs(ref).max()
         net.free()
         unfused.free()
+
+
+@pytest.mark.parametrize("geom", [(7, 7, 1, 1), (7, 7, 3, 3), (14, 14, 2, 1), (9, 5, 2, 3)])
+def test_fused_global_average_pool(cad, geom):
+    """A global average pool that is the only reader of a small-image convolution is computed
+    in that convolution's epilogue: the pool op reports "fused", the feature map is never
+    materialised, and every pooling variant of the convolution must reproduce the oracle's
+    pooled vector (and the logits of the FC behind it), with and without an identity
+    residual, both storage types."""
+    h, w_, n, k = geom
+    ops = [wl.Op("conv", "pre", 0, 1, 8, 24, 1, 1, 0, 0.8, True),
+           wl.Op("conv", "mid", 1, 2, 24, 24, k, 1, k // 2, 0.85, True),
+           wl.Op("conv", "last", 2, 3, 24, 24, 1, 1, 0, 0.8, True, 1),
+           wl.Op("avgpool", "gap", 3, 4, 0, 0, 0, 1, 0, 0.0, False),
+           wl.Op("fc", "fc", 4, 5, 24, 10, 1, 1, 0, 0.5, False)]
+    shape = (n, 8, h, w_)
+    x, ws, bs = wl.net_tensors(ops, "gap-%d-%d-%d" % (h, w_, k), shape, input_relu=True)
+    for dtype, npdt, tol in ((cad.F32, np.float32, TOL_F32), (cad.F16, np.float16, TOL_F16)):
+        xs = x.astype(npdt)
+        ref, ins, outs = oracle.run_net(ops, xs, ws, bs, dtype=npdt)
+        net = cad.build_net(ops, ws, bs, shape, dtype, use_graph=False)
+        unfused = cad.build_net(ops, ws, bs, shape, dtype, use_graph=False, fuse=False)
+        xd = dev(xs)
+        assert net.op_variant(3) == "fused" and unfused.op_variant(3) == "avgpool"
+        with pytest.raises(cad.CadnnError):
+            net.read_buffer(3, outs[2].shape)
+        names = net.op_candidates(2)
+        assert names and all("_gp" in nm for nm in names), names
+        pooled = outs[3].reshape(n, 24).astype(np.float64)
+        scale = np.abs(pooled).max()
+        for name in names:
+            net.set_op_variant(2, name)
+            y = net.run(xd)
+            torch.cuda.synchronize()
+            got = net.read_buffer(4, outs[3].shape).reshape(n, 24).astype(np.float64)
+            # the mean of values that each obey the layer bound; one more rounding in fp16
+            assert np.abs(got - pooled).max() <= (1e-4 if dtype == cad.F32 else 2e-3) * scale, name
+            assert np.abs(y.cpu().numpy().astype(np.float64) - ref.astype(np.float64)).max() <= tol * np.abs(ref).max()
+        yu = unfused.run(xd).cpu().numpy().astype(np.float64)
+        torch.cuda.synchronize()
+        assert np.abs(yu - ref.astype(np.float64)).max() <= tol * np.abs(ref).max()
+        net.free()
+        unfused.free()
