@@ -230,6 +230,7 @@ struct PtileGeom {
 PtileGeom ptile_geom(const ConvVariant& v, int cin, int kh, int kw, int stride, int pad, int wout);   // v.is_f16 matters
 constexpr int kPtileMaxSteps = 9;
 constexpr size_t kLdsBytesPerCU = 160 * 1024;
+constexpr int kFcTailEntries = 1024;   // 4 loads x 64 lanes x 4 entries
 
 // (variant, a, b, shortcut weights, shortcut input plane): FAM_LINEAR a = input plane,
 // b = input pitch; FAM_PTILE a = stride, b = alias flag; 0, 0 for layout-independent plans;
@@ -261,6 +262,12 @@ struct cadnn_weights {
     // device copies used by the FC kernel (canonical order)
     mutable cadnn::DevBuf d_row_ptr, d_perm, d_col, d_val;
     mutable bool fc_ready = false;
+    // compact FC form (cin <= 65536): every row padded with zero entries to a multiple of
+    // four, 16-bit columns, values in the handle's own precision; d_frow[r] is the row's
+    // start in units of four entries.  kFcTailEntries zero entries follow the last row so
+    // that a wave may read a whole chunk past a row's end.
+    mutable cadnn::DevBuf d_frow, d_fcol, d_fval;
+    mutable bool fc_compact = false;
     // conv plans, built lazily
     mutable std::mutex mu;
     mutable std::map<cadnn::PlanKey, std::unique_ptr<cadnn::ConvPlan>> plans;

@@ -53,9 +53,152 @@ __global__ __launch_bounds__(256) void sfc_kernel(const int32_t* __restrict__ ro
     }
 }
 
+// The same product for matrices whose columns fit 16 bits, with the input vectors of NB
+// images staged in LDS first.  The activation gather, which touches up to 64 different cache
+// lines per wave instruction when it goes to the vector L1, becomes an LDS read, and the
+// weights stream as aligned 16-byte (values) + 8-byte (columns) loads per lane, four
+// nonzeros at a time, up to four such loads in flight per lane.  Row r goes to workgroup
+// r % gridDim.x, so the rows, which are ordered by length, spread evenly over the workgroups.
+// Rows are padded to a multiple of four entries and the arrays end in kFcTailEntries
+// zero entries: a chunk may be read whole past the end of its row and masked afterwards.
+typedef float fc_f4 __attribute__((ext_vector_type(4)));
+typedef _Float16 fc_h4 __attribute__((ext_vector_type(4)));
+typedef unsigned short fc_u4 __attribute__((ext_vector_type(4)));
+template <typename T> struct FcVec { typedef fc_f4 type; };
+template <> struct FcVec<_Float16> { typedef fc_h4 type; };
+
+template <typename T, int NB, int U>
+__device__ __forceinline__ void fc_use(const typename FcVec<T>::type (&v)[U], const fc_u4 (&c)[U],
+                                       const T* xs, int cin, int nb, float (&acc)[NB]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const float wv = (float)v[u][k];
+            const int ci = c[u][k];
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+                if (b < nb) acc[b] = fmaf(wv, (float)xs[b * cin + ci], acc[b]);
+        }
+    }
+}
+
+// Loads U x 64 groups of four entries starting at group `first` (this lane's), whole, and
+// zeroes the values of the groups at or past e4, the end of the row.
+template <typename T, int NB, int U>
+__device__ __forceinline__ void fc_chunk(const typename FcVec<T>::type* __restrict__ val4,
+                                         const fc_u4* __restrict__ col4, const T* xs, int cin, int nb,
+                                         int first, int e4, float (&acc)[NB]) {
+    typename FcVec<T>::type v[U];
+    fc_u4 c[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        v[u] = val4[first + u * 64];
+        c[u] = col4[first + u * 64];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+        if (first + u * 64 >= e4) v[u] = 0;
+    fc_use<T, NB, U>(v, c, xs, cin, nb, acc);
+}
+
+template <typename T, int NB, int THREADS>
+__global__ __launch_bounds__(THREADS) void sfc_lds_kernel(const int32_t* __restrict__ row4,
+                                                          const int32_t* __restrict__ perm,
+                                                          const void* __restrict__ col,
+                                                          const void* __restrict__ val,
+                                                          const T* __restrict__ x, T* __restrict__ y,
+                                                          const float* __restrict__ bias, int n, int cin,
+                                                          int cout, int relu) {
+    extern __shared__ __align__(16) unsigned char fc_smem[];
+    T* xs = (T*)fc_smem;
+    typedef typename FcVec<T>::type VT;
+    constexpr int WPB = THREADS / 64;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n0 = blockIdx.y * NB;
+    const int nb = min(NB, n - n0);
+    const VT* val4 = (const VT*)val;
+    const fc_u4* col4 = (const fc_u4*)col;
+    const int G = gridDim.x;
+    const T* xg = x + (size_t)n0 * cin;
+    for (int i = threadIdx.x; i < nb * cin; i += THREADS) xs[i] = xg[i];
+    __syncthreads();
+    for (int row = blockIdx.x + G * wave; row < cout; row += G * WPB) {
+        const int s4 = row4[row], e4 = row4[row + 1];
+        float acc[NB];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) acc[b] = 0.0f;
+        int base = s4;
+        for (; e4 - base > 128; base += 256)
+            fc_chunk<T, NB, 4>(val4, col4, xs, cin, nb, base + lane, e4, acc);
+        if (e4 - base > 64)
+            fc_chunk<T, NB, 2>(val4, col4, xs, cin, nb, base + lane, e4, acc);
+        else if (e4 - base > 0)
+            fc_chunk<T, NB, 1>(val4, col4, xs, cin, nb, base + lane, e4, acc);
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            float v = acc[b];
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+            acc[b] = v;
+        }
+        if (lane == 0) {
+            const int co = perm[row];
+            const float bv = bias ? bias[co] : 0.0f;
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                if (b < nb) {
+                    float v = acc[b] + bv;
+                    if (relu) v = v > 0.0f ? v : 0.0f;
+                    y[(size_t)(n0 + b) * cout + co] = (T)v;
+                }
+            }
+        }
+    }
+}
+
+template <typename T, int NB, int THREADS>
+static hipError_t launch_fc_lds(const cadnn_weights* w, const void* x, void* y, int n, const float* bias,
+                                int relu, hipStream_t s) {
+    // more than 64 KB of dynamic LDS has to be asked for once per kernel
+    static const hipError_t attr =
+        hipFuncSetAttribute((const void*)sfc_lds_kernel<T, NB, THREADS>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytesPerCU);
+    if (attr != hipSuccess) return attr;
+    const size_t lds = (size_t)NB * w->cin * sizeof(T);
+    constexpr int WPB = THREADS / 64;
+    const int per_cu = (int)std::min<size_t>(2048 / THREADS, std::max<size_t>(1, kLdsBytesPerCU / std::max<size_t>(lds, 1)));
+    const int gx = std::min((w->cout + WPB - 1) / WPB, 256 * per_cu);
+    hipLaunchKernelGGL((sfc_lds_kernel<T, NB, THREADS>), dim3((unsigned)gx, (unsigned)((n + NB - 1) / NB)),
+                       dim3(THREADS), lds, s, (const int32_t*)w->d_frow.p, (const int32_t*)w->d_perm.p,
+                       w->d_fcol.p, w->d_fval.p, (const T*)x, (T*)y, bias, n, w->cin, w->cout, relu);
+    return hipGetLastError();
+}
+
 template <typename T>
 static cadnn_status launch_fc_t(const cadnn_weights* w, const void* x, void* y, int n,
                                 const float* bias, int relu, hipStream_t s) {
+    // The staged kernel pays for itself once the gather is long (many nonzeros) or the weights
+    // serve several images; small single-image products are latency-bound and skip the staging.
+    if (w->fc_compact && (n > 1 || w->nnz >= (1 << 20))) {
+        // images per pass: eight when their input vectors fit LDS together, else one
+        const size_t vec = (size_t)w->cin * sizeof(T);
+        const int nb = n > 1 && 8 * vec <= kLdsBytesPerCU ? 8 : (vec <= kLdsBytesPerCU && n <= 65535 ? 1 : 0);
+        // 16 waves per workgroup once there are enough rows to give every wave one
+        const bool big = w->cout > 256 * 4;
+        if (nb == 8) {
+            const hipError_t e = big ? launch_fc_lds<T, 8, 1024>(w, x, y, n, bias, relu, s)
+                                     : launch_fc_lds<T, 8, 256>(w, x, y, n, bias, relu, s);
+            CADNN_HIP(e);
+            return CADNN_OK;
+        }
+        if (nb == 1) {
+            const hipError_t e = big ? launch_fc_lds<T, 1, 1024>(w, x, y, n, bias, relu, s)
+                                     : launch_fc_lds<T, 1, 256>(w, x, y, n, bias, relu, s);
+            CADNN_HIP(e);
+            return CADNN_OK;
+        }
+    }
     const int rows_per_block = 4;
     const unsigned gx = (unsigned)((w->cout + rows_per_block - 1) / rows_per_block);
     const int32_t* rp = (const int32_t*)w->d_row_ptr.p;

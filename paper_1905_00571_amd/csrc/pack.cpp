@@ -576,6 +576,38 @@ cadnn_status ensure_fc_device(const cadnn_weights* w) {
     if ((st = w->d_perm.upload(w->perm.data(), w->perm.size() * 4)) != CADNN_OK) return st;
     if ((st = w->d_col.upload(w->col_idx.data(), w->col_idx.size() * 4)) != CADNN_OK) return st;
     if ((st = w->d_val.upload(w->vals.data(), w->vals.size() * 4)) != CADNN_OK) return st;
+    if (w->kh == 1 && w->kw == 1 && w->cin <= 65536) {
+        try {
+            std::vector<int32_t> frow((size_t)w->cout + 1);
+            int64_t groups = 0;
+            for (int r = 0; r < w->cout; ++r) {
+                frow[r] = (int32_t)groups;
+                groups += (w->row_ptr[r + 1] - w->row_ptr[r] + 3) / 4;
+            }
+            frow[w->cout] = (int32_t)groups;
+            const size_t entries = (size_t)groups * 4 + kFcTailEntries;
+            std::vector<uint16_t> fcol(entries, 0);
+            const bool half = w->dtype == CADNN_F16;
+            std::vector<float> fval(half ? 0 : entries, 0.0f);
+            std::vector<uint16_t> fval16(half ? entries : 0, 0);
+            for (int r = 0; r < w->cout; ++r) {
+                size_t o = (size_t)frow[r] * 4;
+                for (int32_t i = w->row_ptr[r]; i < w->row_ptr[r + 1]; ++i, ++o) {
+                    fcol[o] = (uint16_t)w->col_idx[i];
+                    if (half) fval16[o] = w->vals16[i];
+                    else fval[o] = w->vals[i];
+                }
+            }
+            if ((st = w->d_frow.upload(frow.data(), frow.size() * 4)) != CADNN_OK) return st;
+            if ((st = w->d_fcol.upload(fcol.data(), fcol.size() * 2)) != CADNN_OK) return st;
+            st = half ? w->d_fval.upload(fval16.data(), fval16.size() * 2)
+                      : w->d_fval.upload(fval.data(), fval.size() * 4);
+            if (st != CADNN_OK) return st;
+            w->fc_compact = true;
+        } catch (const std::bad_alloc&) {
+            return fail(CADNN_ENOMEM, "out of host memory building the fully connected layout");
+        }
+    }
     w->fc_ready = true;
     return CADNN_OK;
 }

@@ -142,7 +142,10 @@ def test_nan_poison_catches_unwritten_outputs(cad):
 
 @pytest.mark.parametrize("n,cin,cout,s,relu", [(1, 2048, 1000, 0.9, False), (1, 300, 70, 0.5, True),
                                                (8, 512, 100, 0.96, True), (11, 64, 9, 0.0, False),
-                                               (1, 25088, 256, 0.96, True)])
+                                               (1, 25088, 256, 0.96, True), (3, 25088, 64, 0.96, True), (1, 25088, 1100, 0.96, True),
+                                               (9, 2048, 1000, 0.9, False), (1, 48, 20000, 0.5, True),
+                                               (2, 300, 1500, 0.3, True), (1, 70000, 12, 0.9, False),
+                                               (10, 70000, 5, 0.99, True)])
 def test_sparse_fc(cad, n, cin, cout, s, relu):
     tag = f"fc-{n}-{cin}-{cout}"
     x = wl.activation((n, cin), tag, 0, relu=True)
