@@ -52,6 +52,8 @@ def _load():
         i = ctypes.c_int
         lib.oracle_conv2d.argtypes = [fp, fp, fp, fp, dp] + [i] * 10
         lib.oracle_conv2d.restype = i
+        lib.oracle_depthwise_conv2d.argtypes = [fp, fp, fp, dp] + [i] * 9
+        lib.oracle_depthwise_conv2d.restype = i
         lib.oracle_fc.argtypes = [fp, fp, fp, dp, i, i, i, i]
         lib.oracle_fc.restype = i
         lib.oracle_maxpool.argtypes = [fp, dp] + [i] * 7
@@ -115,6 +117,33 @@ def conv2d_f64(x, w, bias=None, residual=None, stride=1, pad=0, relu=False) -> n
 def conv2d(x, w, bias=None, residual=None, stride=1, pad=0, relu=False, dtype=np.float32):
     """Fused conv layer rounded once to `dtype` (float32 or float16)."""
     return conv2d_f64(x, w, bias, residual, stride, pad, relu).astype(dtype)
+
+
+def depthwise_conv2d_f64(x, w, bias=None, stride=1, pad=0, relu=False) -> np.ndarray:
+    """Fused depthwise layer (paper Section 4), w of shape [c][1][kh][kw]; result in float64."""
+    xf, wf = _f32(x), _f32(w)
+    n, ch, h, wd = xf.shape
+    if wf.ndim != 4 or wf.shape[0] != ch or wf.shape[1] != 1:
+        raise ValueError("depthwise weights must be [channels][1][kh][kw]")
+    kh, kw = wf.shape[2], wf.shape[3]
+    hout, wout = out_size(h, kh, stride, pad), out_size(wd, kw, stride, pad)
+    if hout <= 0 or wout <= 0:
+        raise ValueError("empty output")
+    bf = None if bias is None else _f32(bias)
+    if bf is not None and bf.shape != (ch,):
+        raise ValueError("bias shape")
+    y = np.empty((n, ch, hout, wout), dtype=np.float64)
+    rc = _load().oracle_depthwise_conv2d(_ptr(xf, ctypes.c_float), _ptr(wf, ctypes.c_float),
+                                         _ptr(bf, ctypes.c_float), _ptr(y, ctypes.c_double), n, ch, h, wd,
+                                         kh, kw, stride, pad, int(bool(relu)))
+    if rc != 0:
+        raise RuntimeError("oracle_depthwise_conv2d failed")
+    return y
+
+
+def depthwise_conv2d(x, w, bias=None, stride=1, pad=0, relu=False, dtype=np.float32):
+    """Fused depthwise layer rounded once to `dtype` (float32 or float16)."""
+    return depthwise_conv2d_f64(x, w, bias, stride, pad, relu).astype(dtype)
 
 
 def fc_f64(x, w, bias=None, relu=False) -> np.ndarray:
@@ -223,6 +252,9 @@ def run_net(ops: Sequence, x, weights: Sequence, biases: Sequence, dtype=np.floa
             res = bufs[op.res] if op.res >= 0 else None
             w = np.asarray(weights[i]).astype(dtype)
             y = conv2d(src, w, biases[i], res, op.stride, op.pad, op.relu, dtype)
+        elif op.kind == "dwconv":
+            w = np.asarray(weights[i]).astype(dtype)
+            y = depthwise_conv2d(src, w, biases[i], op.stride, op.pad, op.relu, dtype)
         elif op.kind == "fc":
             w = np.asarray(weights[i]).astype(dtype)
             y = fc(src, w, biases[i], op.relu, dtype)

@@ -25,7 +25,9 @@
  * example, numpy.matmul (1x1 conv and FC, Section 4: 1x1 convolution is a
  * matrix multiply), explicit im2col + matmul, torch's float64 conv2d, and the
  * invariants (zero-weight invariance, identity kernel, linearity, fused ==
- * unfused).  Whole-network outputs have no pin from the paper (it prints no
+ * unfused); the depthwise layer against the full convolution over the
+ * block-diagonal expansion of its filters, a box-filter closed form and torch's
+ * grouped float64 conv2d.  Whole-network outputs have no pin from the paper (it prints no
  * logits): parity unpinned beyond the per-layer pins.
  */
 #include <stdlib.h>
@@ -92,6 +94,50 @@ int oracle_conv2d(const float* x, const float* w, const float* bias, const float
                 if (rp) t += (double)rp[i];
                 if (relu && !(t > 0.0)) t = 0.0;
                 acc[i] = t;
+            }
+        }
+    }
+    return 0;
+}
+
+/* Fused depthwise convolution layer (Section 4 names depthwise convolution + batch-norm +
+ * activation as one fused kernel of MobileNet-V1): every channel is filtered by its own
+ * kh x kw filter and nothing is summed across channels,
+ *
+ *   y[n,c,oh,ow] = act( sum_{r,s} W[c,r,s] * X~[n,c,oh*stride+r-pad,ow*stride+s-pad] + bias[c] )
+ *
+ * x[n][ch][h][w], w[ch][kh][kw], bias[ch] or NULL, y[n][ch][hout][wout] (double).  Sums in
+ * double, taps in r -> s order, zero taps skipped. */
+int oracle_depthwise_conv2d(const float* x, const float* w, const float* bias, double* y, int n,
+                            int ch, int h, int wd, int kh, int kw, int stride, int pad, int relu) {
+    if (!x || !w || !y || n <= 0 || ch <= 0 || h <= 0 || wd <= 0 || kh <= 0 || kw <= 0 ||
+        stride <= 0 || pad < 0)
+        return -1;
+    const int hout = out_size(h, kh, stride, pad), wout = out_size(wd, kw, stride, pad);
+    if (hout <= 0 || wout <= 0) return -1;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int in = 0; in < n; ++in) {
+        for (int c = 0; c < ch; ++c) {
+            const float* xp = x + ((long)in * ch + c) * h * wd;
+            double* yp = y + ((long)in * ch + c) * hout * wout;
+            for (int oh = 0; oh < hout; ++oh) {
+                for (int ow = 0; ow < wout; ++ow) {
+                    double t = 0.0;
+                    for (int r = 0; r < kh; ++r) {
+                        const int ih = oh * stride + r - pad;
+                        if (ih < 0 || ih >= h) continue;       /* outside the image: X~ = 0 */
+                        for (int q = 0; q < kw; ++q) {
+                            const int iw = ow * stride + q - pad;
+                            if (iw < 0 || iw >= wd) continue;
+                            const float wv = w[((long)c * kh + r) * kw + q];
+                            if (wv == 0.0f) continue;
+                            t += (double)wv * (double)xp[(long)ih * wd + iw];
+                        }
+                    }
+                    if (bias) t += (double)bias[c];
+                    if (relu && !(t > 0.0)) t = 0.0;
+                    yp[(long)oh * wout + ow] = t;
+                }
             }
         }
     }

@@ -281,3 +281,97 @@ def test_fp16_variant_single_rounding():
     y16 = oracle.conv2d(x, w, None, None, 1, 1, False, dtype=np.float16)
     assert y16.dtype == np.float16
     assert np.array_equal(y16, ref.astype(np.float16))
+
+
+# ---------------------------------------------------------------------------
+# Depthwise layer (paper Section 4: depthwise convolution + batch-norm + activation fused)
+# ---------------------------------------------------------------------------
+
+def brute_depthwise(x, w, bias, stride, pad, relu):
+    """Each channel against its own filter, as scalar loops in Python floats."""
+    n, ch, h, wd = x.shape
+    kh, kw = w.shape[2], w.shape[3]
+    hout = (h + 2 * pad - kh) // stride + 1
+    wout = (wd + 2 * pad - kw) // stride + 1
+    y = np.zeros((n, ch, hout, wout))
+    for b in range(n):
+        for c in range(ch):
+            for oh in range(hout):
+                for ow in range(wout):
+                    s = 0.0
+                    for r in range(kh):
+                        for q in range(kw):
+                            ih, iw = oh * stride + r - pad, ow * stride + q - pad
+                            if 0 <= ih < h and 0 <= iw < wd:
+                                s += float(w[c, 0, r, q]) * float(x[b, c, ih, iw])
+                    if bias is not None:
+                        s += float(bias[c])
+                    y[b, c, oh, ow] = max(s, 0.0) if relu else s
+    return y
+
+
+@pytest.mark.parametrize("kh,kw,stride,pad", [(3, 3, 1, 1), (3, 3, 2, 1), (5, 3, 1, 2), (1, 1, 1, 0), (3, 3, 2, 0)])
+def test_depthwise_brute_force(kh, kw, stride, pad):
+    x = rnd((2, 5, 9, 8), 70 + kh)
+    w = rnd((5, 1, kh, kw), 71 + kw, sparsity=0.3)
+    b = rnd((5,), 72)
+    got = oracle.depthwise_conv2d_f64(x, w, b, stride, pad, True)
+    np.testing.assert_allclose(got, brute_depthwise(x, w, b, stride, pad, True), rtol=1e-13, atol=1e-13)
+    got = oracle.depthwise_conv2d_f64(x, w, None, stride, pad, False)
+    np.testing.assert_allclose(got, brute_depthwise(x, w, None, stride, pad, False), rtol=1e-13, atol=1e-13)
+
+
+@pytest.mark.parametrize("stride", [1, 2])
+def test_depthwise_is_full_conv_with_block_diagonal_filters(stride):
+    """Placing filter c at [c, c] of an otherwise zero [C][C][kh][kw] tensor turns the
+    depthwise layer into an ordinary convolution (which has its own pins above)."""
+    x = rnd((2, 6, 11, 10), 80)
+    w = rnd((6, 1, 3, 3), 81)
+    b = rnd((6,), 82)
+    full = np.zeros((6, 6, 3, 3), np.float32)
+    for c in range(6):
+        full[c, c] = w[c, 0]
+    want = oracle.conv2d_f64(x, full, b, None, stride, 1, True)
+    got = oracle.depthwise_conv2d_f64(x, w, b, stride, 1, True)
+    np.testing.assert_allclose(got, want, rtol=1e-14, atol=1e-14)
+
+
+def test_depthwise_box_filter_closed_form():
+    """All-ones 3x3 filters on an all-ones image count the in-image taps: 9 inside,
+    6 on edges, 4 in corners; a channel scaled by a gives a times that."""
+    x = np.ones((1, 3, 6, 7), np.float32)
+    x[0, 1] *= 2.0
+    x[0, 2] *= -0.5
+    w = np.ones((3, 1, 3, 3), np.float32)
+    got = oracle.depthwise_conv2d_f64(x, w, None, 1, 1, False)
+    rows = np.array([2, 3, 3, 3, 3, 2], float)[:, None]
+    cols = np.array([2, 3, 3, 3, 3, 3, 2], float)[None, :]
+    for c, a in enumerate([1.0, 2.0, -0.5]):
+        assert np.array_equal(got[0, c], a * rows * cols)
+
+
+def test_depthwise_against_torch_grouped_float64():
+    torch = pytest.importorskip("torch")
+    x = rnd((2, 7, 13, 12), 90)
+    w = rnd((7, 1, 3, 3), 91, sparsity=0.2)
+    b = rnd((7,), 92)
+    for stride in (1, 2):
+        want = torch.nn.functional.conv2d(torch.from_numpy(x).double(), torch.from_numpy(w).double(),
+                                          torch.from_numpy(b).double(), stride=stride, padding=1, groups=7)
+        got = oracle.depthwise_conv2d_f64(x, w, b, stride, 1, False)
+        np.testing.assert_allclose(got, want.numpy(), rtol=1e-12, atol=1e-12)
+
+
+def test_depthwise_channels_do_not_mix_and_fp16_rounds_once():
+    x = rnd((1, 4, 8, 8), 95)
+    w = rnd((4, 1, 3, 3), 96)
+    base = oracle.depthwise_conv2d_f64(x, w, None, 1, 1, False)
+    x2 = x.copy()
+    x2[0, 2] += 1.0                      # only channel 2 of the output may move
+    moved = oracle.depthwise_conv2d_f64(x2, w, None, 1, 1, False)
+    assert np.array_equal(moved[0, [0, 1, 3]], base[0, [0, 1, 3]])
+    assert not np.array_equal(moved[0, 2], base[0, 2])
+    x16, w16 = x.astype(np.float16), w.astype(np.float16)
+    y16 = oracle.depthwise_conv2d(x16, w16, None, 1, 1, True, dtype=np.float16)
+    assert y16.dtype == np.float16
+    assert np.array_equal(y16, oracle.depthwise_conv2d_f64(x16, w16, None, 1, 1, True).astype(np.float16))
