@@ -136,6 +136,26 @@ cadnn_status cadnn_sparse_fc(const cadnn_weights* w, const void* x, void* y, int
 /* Uploads the device arrays cadnn_sparse_fc needs (otherwise done on its first call). */
 cadnn_status cadnn_fc_prepare(const cadnn_weights* w);
 
+/* ------------------------------------------------------------------------- *
+ * Fused depthwise convolution layer (Section 4 names depthwise convolution +
+ * batch-norm + activation, as in MobileNet-V1, among the fused kernels): each
+ * channel is filtered by its own kh x kw filter and channels are not summed,
+ *
+ *   y[n][c][oh][ow] = act( sum_{r,s} W[c][0][r][s] * X~[n][c][oh*stride+r-pad][ow*stride+s-pad] + bias[c] )
+ *
+ * w: a handle packed from the HOST tensor [channels][1][kh][kw] (cin = 1, cout =
+ * channels); taps that are exactly zero are skipped.  x: device [n][channels][h][wdt];
+ * y: device [n][channels][hout][wout], sizes as for cadnn_sparse_conv2d; bias: device fp32
+ * [channels] or NULL.  y must not overlap x.  The first call uploads the filter
+ * table (allocates, synchronous) unless cadnn_depthwise_prepare was called.
+ * Errors: EINVAL (NULL pointer, sizes <= 0, pad < 0, empty output, a handle with
+ * cin != 1); EUNSUPPORTED (more than 2^31 wavefronts of work); EHIP.
+ * ------------------------------------------------------------------------- */
+cadnn_status cadnn_depthwise_conv2d(const cadnn_weights* w, const void* x, void* y, int n, int h,
+                                    int wdt, int stride, int pad, const void* bias, int relu,
+                                    void* stream);
+cadnn_status cadnn_depthwise_prepare(const cadnn_weights* w);
+
 /* Pooling layers used between the convolutions of the benchmark networks.
  * Max pooling takes the maximum over the in-image part of each k x k window
  * (padding never wins); global average pooling writes y[n][c] = mean over h*w. */
@@ -178,6 +198,10 @@ cadnn_status cadnn_net_create(cadnn_dtype dtype, int n, int c, int h, int w, cad
 cadnn_status cadnn_net_add_conv(cadnn_net* net, const cadnn_weights* w, const void* bias_dev,
                                 int stride, int pad, int relu, int src_buf, int dst_buf,
                                 int residual_buf /* -1 = none */);
+/* Depthwise layer (see cadnn_depthwise_conv2d); w must have cin = 1 and as many filters as
+ * src_buf has channels. */
+cadnn_status cadnn_net_add_depthwise(cadnn_net* net, const cadnn_weights* w, const void* bias_dev,
+                                     int stride, int pad, int relu, int src_buf, int dst_buf);
 cadnn_status cadnn_net_add_maxpool(cadnn_net* net, int k, int stride, int pad, int src_buf,
                                    int dst_buf);
 cadnn_status cadnn_net_add_global_avgpool(cadnn_net* net, int src_buf, int dst_buf);
@@ -209,8 +233,8 @@ cadnn_status cadnn_run_net(cadnn_net* net, const void* x, void* y, void* stream)
 cadnn_status cadnn_net_num_ops(const cadnn_net* net, int* num_ops);
 cadnn_status cadnn_net_profile(cadnn_net* net, const void* x, void* y, void* stream, int repeats,
                                float* ms_per_op);
-/* Name of the kernel serving op `op_index` (a conv variant name, "sfc", "maxpool" or
- * "avgpool"), NUL-terminated into buf. */
+/* Name of the kernel serving op `op_index` (a conv variant name, "dwconv", "sfc", "maxpool"
+ * or "avgpool"), NUL-terminated into buf. */
 cadnn_status cadnn_net_op_variant(const cadnn_net* net, int op_index, char* buf, size_t len);
 /* Newline-separated names of the variants that can serve convolution op `op_index` in
  * the layout the net gave its input (a halo opens the linear-address kernels to 3x3). */

@@ -26,6 +26,8 @@ from .binding import (  # noqa: F401
     cadnn_conv2d_tune,
     cadnn_sparse_fc,
     cadnn_fc_prepare,
+    cadnn_depthwise_conv2d,
+    cadnn_depthwise_prepare,
     cadnn_device_copy,
     cadnn_maxpool2d,
     cadnn_global_avgpool,

@@ -62,12 +62,15 @@ def lib() -> ctypes.CDLL:
         "cadnn_conv2d_set_variant": (_i, [_vp, _i, _i, _i, _i, _i, ctypes.c_char_p]),
         "cadnn_sparse_fc": (_i, [_vp, _vp, _vp, _i, _vp, _i, _vp]),
         "cadnn_fc_prepare": (_i, [_vp]),
+        "cadnn_depthwise_conv2d": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _vp, _i, _vp]),
+        "cadnn_depthwise_prepare": (_i, [_vp]),
         "cadnn_device_copy": (_i, [_vp, _vp, ctypes.c_size_t, _vp]),
         "cadnn_maxpool2d": (_i, [_vp, _vp, _i, _i, _i, _i, _i, _i, _i, _i, _vp]),
         "cadnn_global_avgpool": (_i, [_vp, _vp, _i, _i, _i, _i, _i, _vp]),
         "cadnn_dense_conv2d": (_i, [_vp, _vp, _vp] + [_i] * 9 + [_vp, _vp, _i, _i, _vp]),
         "cadnn_net_create": (_i, [_i, _i, _i, _i, _i, ctypes.POINTER(_vp)]),
         "cadnn_net_add_conv": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i]),
+        "cadnn_net_add_depthwise": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i]),
         "cadnn_net_add_maxpool": (_i, [_vp, _i, _i, _i, _i, _i]),
         "cadnn_net_add_global_avgpool": (_i, [_vp, _i, _i]),
         "cadnn_net_add_fc": (_i, [_vp, _vp, _vp, _i, _i, _i]),
@@ -229,6 +232,30 @@ def cadnn_sparse_conv2d(w: Weights, x, stride: int = 1, pad: int = 0, bias=None,
     return out
 
 
+def cadnn_depthwise_conv2d(w: Weights, x, stride: int = 1, pad: int = 0, bias=None, relu: bool = False,
+                           out=None, stream=None):
+    """w packed from [channels][1][kh][kw]; x: contiguous CUDA tensor [n][channels][h][w]."""
+    import torch
+    assert x.is_cuda and x.is_contiguous() and x.dtype == _torch_dtype(w.dtype)
+    n, ch, h, wdt = x.shape
+    if ch != w.cout:
+        raise ValueError("channel mismatch")
+    hout, wout = _out_size(h, w.kh, stride, pad), _out_size(wdt, w.kw, stride, pad)
+    if out is None:
+        if hout <= 0 or wout <= 0:
+            raise CadnnError(1, "empty output")
+        out = torch.empty((n, ch, hout, wout), dtype=x.dtype, device=x.device)
+    if bias is not None:
+        assert bias.is_cuda and bias.dtype == torch.float32 and bias.numel() == ch
+    _check(lib().cadnn_depthwise_conv2d(w.handle, _dptr(x), _dptr(out), n, h, wdt, stride, pad, _dptr(bias),
+                                        int(bool(relu)), _stream_ptr(stream)))
+    return out
+
+
+def cadnn_depthwise_prepare(w: Weights) -> None:
+    _check(lib().cadnn_depthwise_prepare(w.handle))
+
+
 def cadnn_sparse_fc(w: Weights, x, bias=None, relu: bool = False, out=None, stream=None):
     import torch
     assert x.is_cuda and x.is_contiguous() and x.dtype == _torch_dtype(w.dtype)
@@ -374,7 +401,7 @@ def build_net(ops: Sequence, weights: Sequence, biases: Sequence, input_shape, d
               plain_layout: bool = False, fuse: bool = True) -> Net:
     """Packs every layer's weights and wires the op list into a cadnn_net.
 
-    `ops` are records with .kind in {"conv", "fc", "maxpool", "avgpool"} and
+    `ops` are records with .kind in {"conv", "dwconv", "fc", "maxpool", "avgpool"} and
     .src/.dst/.res/.k/.stride/.pad/.relu fields (see workloads.nets.Op).
     """
     import torch
@@ -386,7 +413,7 @@ def build_net(ops: Sequence, weights: Sequence, biases: Sequence, input_shape, d
     try:
         shapes = {0: tuple(input_shape)}
         for i, op in enumerate(ops):
-            if op.kind in ("conv", "fc"):
+            if op.kind in ("conv", "fc", "dwconv"):
                 pw = cadnn_pack_weights(np.asarray(weights[i], dtype=np.float32), dtype)
                 b = None
                 if biases[i] is not None:
@@ -397,6 +424,12 @@ def build_net(ops: Sequence, weights: Sequence, biases: Sequence, input_shape, d
                                                 int(bool(op.relu)), op.src, op.dst, op.res))
                     s = shapes[op.src]
                     shapes[op.dst] = (s[0], pw.cout, _out_size(s[2], pw.kh, op.stride, op.pad),
+                                      _out_size(s[3], pw.kw, op.stride, op.pad))
+                elif op.kind == "dwconv":
+                    _check(L.cadnn_net_add_depthwise(handle, pw.handle, _dptr(b), op.stride, op.pad,
+                                                     int(bool(op.relu)), op.src, op.dst))
+                    s = shapes[op.src]
+                    shapes[op.dst] = (s[0], s[1], _out_size(s[2], pw.kh, op.stride, op.pad),
                                       _out_size(s[3], pw.kw, op.stride, op.pad))
                 else:
                     _check(L.cadnn_net_add_fc(handle, pw.handle, _dptr(b), int(bool(op.relu)), op.src, op.dst))

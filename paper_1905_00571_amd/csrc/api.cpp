@@ -464,6 +464,34 @@ extern "C" cadnn_status cadnn_fc_prepare(const cadnn_weights* w) {
     return ensure_fc_device(w);
 }
 
+static cadnn_status check_depthwise(const char* who, const cadnn_weights* w, int n, int h, int wdt, int stride,
+                                    int pad) {
+    if (!w) return fail(CADNN_EINVAL, "%s: NULL handle", who);
+    if (w->cin != 1) return fail(CADNN_EINVAL, "%s: weights have %d input channels per filter, a depthwise filter bank has 1", who, w->cin);
+    if (n <= 0 || h <= 0 || wdt <= 0 || stride <= 0 || pad < 0) return fail(CADNN_EINVAL, "%s: bad size", who);
+    if (conv_out(h, w->kh, stride, pad) <= 0 || conv_out(wdt, w->kw, stride, pad) <= 0)
+        return fail(CADNN_EINVAL, "%s: empty output", who);
+    return CADNN_OK;
+}
+
+extern "C" cadnn_status cadnn_depthwise_conv2d(const cadnn_weights* w, const void* x, void* y, int n, int h,
+                                               int wdt, int stride, int pad, const void* bias, int relu,
+                                               void* stream) {
+    if (!x || !y) return fail(CADNN_EINVAL, "cadnn_depthwise_conv2d: NULL tensor");
+    cadnn_status st = check_depthwise("cadnn_depthwise_conv2d", w, n, h, wdt, stride, pad);
+    if (st != CADNN_OK) return st;
+    if ((st = ensure_dw_device(w)) != CADNN_OK) return st;
+    const TensorDesc xd = make_desc(w->cout, h, wdt);
+    const TensorDesc yd = make_desc(w->cout, conv_out(h, w->kh, stride, pad), conv_out(wdt, w->kw, stride, pad));
+    return launch_depthwise(w, x, xd, y, yd, n, stride, pad, (const float*)bias, relu ? 1 : 0, (hipStream_t)stream);
+}
+
+extern "C" cadnn_status cadnn_depthwise_prepare(const cadnn_weights* w) {
+    if (!w) return fail(CADNN_EINVAL, "cadnn_depthwise_prepare: NULL handle");
+    if (w->cin != 1) return fail(CADNN_EINVAL, "cadnn_depthwise_prepare: not a depthwise filter bank");
+    return ensure_dw_device(w);
+}
+
 extern "C" cadnn_status cadnn_device_copy(const void* src, void* dst, size_t bytes, void* stream) {
     if (!src || !dst) return fail(CADNN_EINVAL, "cadnn_device_copy: NULL pointer");
     if (bytes % 16) return fail(CADNN_EINVAL, "cadnn_device_copy: size must be a multiple of 16 bytes");

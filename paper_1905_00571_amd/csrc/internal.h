@@ -268,6 +268,9 @@ struct cadnn_weights {
     // that a wave may read a whole chunk past a row's end.
     mutable cadnn::DevBuf d_frow, d_fcol, d_fval;
     mutable bool fc_compact = false;
+    // depthwise filters (cin == 1): fp32 table [cout][kh*kw], zeros where pruned
+    mutable cadnn::DevBuf d_dw;
+    mutable bool dw_ready = false;
     // conv plans, built lazily
     mutable std::mutex mu;
     mutable std::map<cadnn::PlanKey, std::unique_ptr<cadnn::ConvPlan>> plans;
@@ -295,12 +298,17 @@ cadnn_status get_conv_plan(const cadnn_weights* w, const ConvVariant* v, const T
                            int pad, int wout, const ConvPlan** out, const ConvExtra* ex = nullptr);
 void drop_unpinned_plans(const cadnn_weights* w);
 cadnn_status ensure_fc_device(const cadnn_weights* w);
+cadnn_status ensure_dw_device(const cadnn_weights* w);
 uint16_t f32_to_f16_rne(float f);
 float f16_to_f32(uint16_t h);
 
 cadnn_status launch_fc(const cadnn_weights* w, const void* x, void* y, int n, const float* bias,
                        int relu, hipStream_t s);
 cadnn_status launch_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
+// Depthwise layer on plain (possibly haloed) tensors; yd carries the output size.
+cadnn_status launch_depthwise(const cadnn_weights* w, const void* x, const TensorDesc& xd, void* y,
+                              const TensorDesc& yd, int n, int stride, int pad, const float* bias, int relu,
+                              hipStream_t s);
 cadnn_status launch_maxpool(const void* x, const TensorDesc& xd, void* y, const TensorDesc& yd, int n,
                             int k, int stride, int pad, cadnn_dtype dt, hipStream_t s);
 cadnn_status launch_avgpool(const void* x, const TensorDesc& xd, void* y, int n, cadnn_dtype dt,

@@ -11,7 +11,7 @@ using namespace cadnn;
 
 namespace {
 
-enum OpKind { OP_CONV, OP_FC, OP_MAXPOOL, OP_AVGPOOL };
+enum OpKind { OP_CONV, OP_FC, OP_MAXPOOL, OP_AVGPOOL, OP_DEPTHWISE };
 
 struct Shape {
     int n = 0, c = 0, h = 0, w = 0;
@@ -87,7 +87,7 @@ void layout(cadnn_net* net) {
     for (const NetOp& op : net->ops) {
         if (op.src_inst < 0) continue;
         if (op.kind == OP_FC) flat[op.src_inst] = true;
-        if (op.kind == OP_CONV && (op.w->kh > 1 || op.w->kw > 1))
+        if ((op.kind == OP_CONV || op.kind == OP_DEPTHWISE) && (op.w->kh > 1 || op.w->kw > 1))
             halo[op.src_inst] = std::max(halo[op.src_inst], op.pad);
     }
     if (nops) flat[nops - 1] = true;
@@ -235,6 +235,9 @@ cadnn_status launch_one(cadnn_net* net, size_t i, const void* x, void* y, hipStr
             return conv2d_impl(op.w, src, op.xd, dst, op.yd,
                                (op.res >= 0 && op.shortcut < 0) ? in_ptr(net, op.res_inst, x) : nullptr, op.rd, op.in.n,
                                op.stride, op.pad, op.bias, op.relu, s, fused ? &ex : nullptr);
+        case OP_DEPTHWISE:
+            return launch_depthwise(op.w, src, op.xd, dst, op.yd, op.in.n, op.stride, op.pad, (const float*)op.bias,
+                                    op.relu, s);
         case OP_FC:
             return launch_fc(op.w, src, dst, op.in.n, (const float*)op.bias, op.relu, s);
         case OP_MAXPOOL:
@@ -298,6 +301,27 @@ extern "C" cadnn_status cadnn_net_add_conv(cadnn_net* net, const cadnn_weights* 
     }
     op.kind = OP_CONV; op.w = w; op.bias = bias; op.stride = stride; op.pad = pad; op.relu = relu;
     op.src = src; op.dst = dst; op.res = res < 0 ? -1 : res;
+    if ((st = note_output(net, dst, op.out)) != CADNN_OK) return st;
+    net->ops.push_back(op);
+    return CADNN_OK;
+}
+
+extern "C" cadnn_status cadnn_net_add_depthwise(cadnn_net* net, const cadnn_weights* w, const void* bias,
+                                                int stride, int pad, int relu, int src, int dst) {
+    if (!net || !w) return fail(CADNN_EINVAL, "cadnn_net_add_depthwise: NULL pointer");
+    if (net->finalized) return fail(CADNN_EINVAL, "cadnn_net_add_depthwise: net already finalized");
+    if (w->dtype != net->dtype) return fail(CADNN_EINVAL, "cadnn_net_add_depthwise: dtype of weights and net differ");
+    if (w->cin != 1) return fail(CADNN_EINVAL, "cadnn_net_add_depthwise: weights are not a depthwise filter bank");
+    if (src == dst) return fail(CADNN_EINVAL, "cadnn_net_add_depthwise: dst aliases src");
+    NetOp op;
+    cadnn_status st = src_shape(net, src, &op.in, &op.src_inst);
+    if (st != CADNN_OK) return st;
+    if (op.in.c != w->cout) return fail(CADNN_EINVAL, "cadnn_net_add_depthwise: %d channels, %d filters", op.in.c, w->cout);
+    if (stride <= 0 || pad < 0) return fail(CADNN_EINVAL, "cadnn_net_add_depthwise: bad stride/pad");
+    op.out = Shape{op.in.n, op.in.c, conv_out(op.in.h, w->kh, stride, pad), conv_out(op.in.w, w->kw, stride, pad)};
+    if (op.out.h <= 0 || op.out.w <= 0) return fail(CADNN_EINVAL, "cadnn_net_add_depthwise: empty output");
+    op.kind = OP_DEPTHWISE; op.w = w; op.bias = bias; op.stride = stride; op.pad = pad; op.relu = relu;
+    op.src = src; op.dst = dst;
     if ((st = note_output(net, dst, op.out)) != CADNN_OK) return st;
     net->ops.push_back(op);
     return CADNN_OK;
@@ -388,6 +412,7 @@ extern "C" cadnn_status cadnn_net_finalize(cadnn_net* net, void* ws, size_t byte
         if (op.kind == OP_CONV && op.fused_into < 0)
             st = conv2d_prepare_impl(op.w, op.xd, op.in.n, op.stride, op.pad, out_s2d(op), shortcut_geom(net, op, &ex));
         if (op.kind == OP_FC) st = cadnn_fc_prepare(op.w);
+        if (op.kind == OP_DEPTHWISE) st = ensure_dw_device(op.w);
         if (st != CADNN_OK) return st;
     }
     net->use_graph = (flags & CADNN_NET_GRAPH) != 0;
@@ -502,6 +527,7 @@ extern "C" cadnn_status cadnn_net_op_variant(const cadnn_net* net, int op_index,
             break;
         }
         case OP_FC: name = "sfc"; break;
+        case OP_DEPTHWISE: name = "dwconv"; break;
         case OP_MAXPOOL: name = "maxpool"; break;
         case OP_AVGPOOL: name = op.fused_into >= 0 ? "fused" : "avgpool"; break;
     }

@@ -612,6 +612,27 @@ cadnn_status ensure_fc_device(const cadnn_weights* w) {
     return CADNN_OK;
 }
 
+// Depthwise filters as a dense fp32 table [cout][kh*kw] (pruned taps are zeros, which the
+// kernel skips); a depthwise handle is packed from [channels][1][kh][kw], so a row's column
+// index is the tap index itself.
+cadnn_status ensure_dw_device(const cadnn_weights* w) {
+    std::lock_guard<std::mutex> lock(w->mu);
+    if (w->dw_ready) return CADNN_OK;
+    try {
+        const size_t kk = (size_t)w->kh * w->kw;
+        std::vector<float> table((size_t)w->cout * kk, 0.0f);
+        for (int r = 0; r < w->cout; ++r)
+            for (int32_t i = w->row_ptr[r]; i < w->row_ptr[r + 1]; ++i)
+                table[(size_t)w->perm[r] * kk + w->col_idx[i]] = w->vals[i];
+        cadnn_status st = w->d_dw.upload(table.data(), table.size() * 4);
+        if (st != CADNN_OK) return st;
+    } catch (const std::bad_alloc&) {
+        return fail(CADNN_ENOMEM, "out of host memory building the depthwise filter table");
+    }
+    w->dw_ready = true;
+    return CADNN_OK;
+}
+
 }  // namespace cadnn
 
 using namespace cadnn;

@@ -5,7 +5,7 @@ import pytest
 import oracle
 import workloads as wl
 from util import (TOL_F32, TOL_F16, assert_close, assert_layer_close, assert_chain_close,
-                  cond_conv, cond_fc)
+                  cond_conv, cond_fc, cond_depthwise)
 
 pytestmark = pytest.mark.gpu
 
@@ -158,6 +158,55 @@ def test_sparse_fc(cad, n, cin, cout, s, relu):
     torch.cuda.synchronize()
     assert_layer_close(y.cpu().numpy(), oracle.fc(x, w, b, relu), cond_fc(x, w, b), TOL_F32, tag)
     h.free()
+
+
+@pytest.mark.parametrize("n,ch,h,w,kh,kw,stride,pad,s", [
+    (1, 32, 112, 112, 3, 3, 1, 1, 0.0),     # MobileNet dw1: four pixels per lane
+    (1, 64, 112, 112, 3, 3, 2, 1, 0.0),     # dw2: stride 2, four pixels per lane
+    (2, 19, 23, 17, 3, 3, 1, 1, 0.3),       # ragged sizes, pruned taps, one pixel per lane
+    (1, 1024, 7, 7, 3, 3, 1, 1, 0.0),       # dw13: 49 of 64 lanes
+    (3, 7, 20, 24, 3, 3, 2, 0, 0.2),        # no padding
+    (1, 6, 15, 13, 5, 3, 1, 2, 0.0),        # rectangular filter: run-time size path
+    (2, 5, 16, 16, 3, 3, 3, 1, 0.0),        # stride 3: run-time path
+    (1, 3, 9, 9, 1, 1, 1, 0, 0.0),          # 1x1 depthwise = per-channel scale
+])
+def test_depthwise(cad, n, ch, h, w, kh, kw, stride, pad, s):
+    tag = f"dw-{n}-{ch}-{h}-{w}-{kh}{kw}-{stride}-{pad}"
+    x = wl.activation((n, ch, h, w), tag, 0, relu=False)
+    wt = wl.pruned_weights(ch, 1, kh, kw, s, tag, 1)
+    if ch > 4:
+        wt[3] = 0                                      # an all-zero filter: output = act(bias)
+    b = wl.bias_vector(ch, tag, 1, sigma=0.1)
+    hd = cad.cadnn_pack_weights(wt)
+    for relu in (True, False):
+        y = cad.cadnn_depthwise_conv2d(hd, dev(x), stride, pad, dev(b), relu)
+        torch.cuda.synchronize()
+        ref = oracle.depthwise_conv2d(x, wt, b, stride, pad, relu)
+        assert_layer_close(y.cpu().numpy(), ref, cond_depthwise(x, wt, b, stride, pad), TOL_F32, tag)
+    y = cad.cadnn_depthwise_conv2d(hd, dev(x), stride, pad, None, False)
+    torch.cuda.synchronize()
+    assert_layer_close(y.cpu().numpy(), oracle.depthwise_conv2d(x, wt, None, stride, pad, False),
+                       cond_depthwise(x, wt, None, stride, pad), TOL_F32, tag + " no bias")
+    hd.free()
+
+
+def test_depthwise_fp16_and_errors(cad):
+    x = wl.activation((2, 24, 28, 28), "dwh", 0, relu=True).astype(np.float16)
+    wt = wl.pruned_weights(24, 1, 3, 3, 0.0, "dwh", 1)
+    b = wl.bias_vector(24, "dwh", 1)
+    hd = cad.cadnn_pack_weights(wt, cad.F16)
+    w16 = wt.astype(np.float16)
+    for stride in (1, 2):
+        y = cad.cadnn_depthwise_conv2d(hd, dev(x), stride, 1, dev(b), True)
+        torch.cuda.synchronize()
+        assert y.dtype == torch.float16
+        ref = oracle.depthwise_conv2d(x, w16, b, stride, 1, True, dtype=np.float16)
+        assert_layer_close(y.cpu().numpy(), ref, cond_depthwise(x, w16, b, stride, 1), TOL_F16, "dw fp16", f16=True)
+    hd.free()
+    full = cad.cadnn_pack_weights(wl.pruned_weights(8, 8, 3, 3, 0.5, "dwh", 2))
+    with pytest.raises(cad.CadnnError):
+        cad.cadnn_depthwise_conv2d(full, dev(wl.activation((1, 8, 9, 9), "dwh", 3, relu=False)), 1, 1)
+    full.free()
 
 
 def test_pools(cad):

@@ -5,7 +5,7 @@ import pytest
 import oracle
 import workloads as wl
 from util import (TOL_F32, TOL_F16, assert_close, assert_layer_close, assert_chain_close,
-                  cond_conv, cond_fc)
+                  cond_conv, cond_fc, cond_depthwise)
 
 pytestmark = pytest.mark.gpu
 
@@ -43,6 +43,10 @@ def check_layers_in_isolation(cad, ops, ws, bs, ins, outs, tol, dtype, which=Non
             y = cad.cadnn_sparse_conv2d(h, dev(ins[i]), op.stride, op.pad, dev(bs[i]),
                                         None if res is None else dev(res), op.relu)
             cond = cond_conv(ins[i], ws[i].astype(npdt), bs[i], res, op.stride, op.pad)
+        elif op.kind == "dwconv":
+            h = cad.cadnn_pack_weights(ws[i], dtype)
+            y = cad.cadnn_depthwise_conv2d(h, dev(ins[i]), op.stride, op.pad, dev(bs[i]), op.relu)
+            cond = cond_depthwise(ins[i], ws[i].astype(npdt), bs[i], op.stride, op.pad)
         elif op.kind == "fc":
             h = cad.cadnn_pack_weights(ws[i], dtype)
             y = cad.cadnn_sparse_fc(h, dev(ins[i].reshape(ins[i].shape[0], -1)), dev(bs[i]), op.relu)
@@ -55,7 +59,7 @@ def check_layers_in_isolation(cad, ops, ws, bs, ins, outs, tol, dtype, which=Non
             y = cad.cadnn_global_avgpool(dev(ins[i]))
             h = None
         torch.cuda.synchronize()
-        if op.kind in ("conv", "fc"):
+        if op.kind in ("conv", "fc", "dwconv"):
             e = assert_layer_close(y.cpu().numpy(), outs[i], cond, tol, f"layer {i} {op.name}", f16=f16)
         else:
             e = assert_close(y.cpu().numpy(), outs[i], 1e-3 if f16 else 1e-6, f"layer {i} {op.name}")
@@ -98,6 +102,38 @@ def test_config4_vgg16_fp32(cad):
     print("vgg16 end-to-end", assert_chain_close(y.cpu().numpy(), ref, cond_fc(ins[-1], ws[-1], bs[-1]),
                                                  TOL_F32, "vgg16 end to end"))
     net.free()
+
+
+@pytest.mark.parametrize("dtype_name,n", [("f32", 1), ("f16", 4)])
+def test_mobilenet_v1(cad, dtype_name, n):
+    """Second workload family (the paper's Table 2 lists MobileNet-V1): depthwise layers chained
+    with pruned pointwise layers, every layer in isolation and the whole net, with and without
+    the net-level fusions and tuned layouts."""
+    f16 = dtype_name == "f16"
+    dtype, npdt, tol = (cad.F16, np.float16, TOL_F16) if f16 else (cad.F32, np.float32, TOL_F32)
+    ops = wl.mobilenet_v1_ops()
+    shape = (n, 3, 224, 224)
+    x, ws, bs = wl.net_tensors(ops, "mbv1", shape)
+    xs = x.astype(npdt)
+    ref, ins, outs = oracle.run_net(ops, xs, ws, bs, dtype=npdt)
+    which = None if not f16 else set(range(0, len(ops), 3))
+    worst = check_layers_in_isolation(cad, ops, ws, bs, ins, outs, tol, dtype, which=which)
+    print("mobilenet per-layer worst E_inf", worst)
+    cond = cond_fc(ins[-1], ws[-1].astype(npdt), bs[-1])
+    for kw in ({}, {"plain_layout": True, "fuse": False}):
+        net = cad.build_net(ops, ws, bs, shape, dtype, use_graph=True, **kw)
+        assert [net.op_variant(i) for i, o in enumerate(ops) if o.kind == "dwconv"] == ["dwconv"] * 13
+        xd = dev(xs)
+        for rep in range(2):
+            y = net.run(xd)
+            torch.cuda.synchronize()
+            e = assert_chain_close(y.cpu().numpy(), ref, cond, tol, f"mobilenet end to end {kw} (replay {rep})")
+        # the last depthwise output (no later op reuses its buffer id), read back from the workspace
+        i = next(k for k, o in enumerate(ops) if o.name == "dw13")
+        got = net.read_buffer(ops[i].dst, outs[i].shape)
+        assert_close(got, outs[i], tol * 10, "dw13 inside the net")
+        net.free()
+    print("mobilenet end-to-end", e)
 
 
 @pytest.mark.parametrize("n,s", [(1, 0.8), (8, 0.5)])

@@ -56,6 +56,11 @@ def cond_conv(x, w, bias, residual, stride, pad):
     return oracle.conv2d_f64(ab(x), ab(w), ab(bias), ab(residual), stride, pad, False)
 
 
+def cond_depthwise(x, w, bias, stride, pad):
+    ab = lambda a: None if a is None else np.abs(np.asarray(a, dtype=np.float32))
+    return oracle.depthwise_conv2d_f64(ab(x), ab(w), ab(bias), stride, pad, False)
+
+
 def cond_fc(x, w, bias):
     ab = lambda a: None if a is None else np.abs(np.asarray(a, dtype=np.float32))
     return oracle.fc_f64(ab(x), ab(w), ab(bias), False)

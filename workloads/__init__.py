@@ -18,6 +18,7 @@ from .nets import (  # noqa: F401
     Op,
     resnet50_ops,
     vgg16_ops,
+    mobilenet_v1_ops,
     bottleneck_conv2x_ops,
     single_conv_ops,
     net_tensors,

@@ -23,7 +23,7 @@ from .gen import activation, bias_vector, conv_out_size, pruned_weights
 
 @dataclass(frozen=True)
 class Op:
-    kind: str              # "conv" | "fc" | "maxpool" | "avgpool"
+    kind: str              # "conv" | "dwconv" (depthwise; cin == cout) | "fc" | "maxpool" | "avgpool"
     name: str
     src: int
     dst: int
@@ -102,6 +102,29 @@ def vgg16_ops(s_conv: float = 0.9, s_fc: float = 0.96) -> List[Op]:
     return ops
 
 
+def mobilenet_v1_ops(s_conv1: float = 0.0, s_dw: float = 0.0, s_pw: float = 0.8,
+                     s_fc: float = 0.9) -> List[Op]:
+    """MobileNet-V1 at width 1.0 and 224x224 input (the paper's Table 2 names the model):
+    a 3x3/2 convolution to 32 channels, 13 depthwise-separable blocks (3x3 depthwise +
+    1x1 pointwise, each followed by batch-norm + ReLU, folded here into bias + ReLU; the
+    blocks' output channels and depthwise strides below are the published ladder), global
+    average pool, FC 1024->1000.  The pointwise layers carry nearly all the weights and are
+    the pruned ones; depthwise filters (9 weights per channel) stay dense by default."""
+    ladder = [(64, 1), (128, 2), (128, 1), (256, 2), (256, 1), (512, 2), (512, 1), (512, 1),
+              (512, 1), (512, 1), (512, 1), (1024, 2), (1024, 1)]
+    ops: List[Op] = [Op("conv", "conv1", 0, 1, 3, 32, 3, 2, 1, s_conv1, True)]
+    cur, cin = 1, 32
+    for i, (cout, stride) in enumerate(ladder, start=1):
+        mid = 2 if cur == 1 else (1 if cur == 3 else 3)
+        nxt = ({1, 2, 3} - {cur, mid}).pop()
+        ops.append(Op("dwconv", f"dw{i}", cur, mid, cin, cin, 3, stride, 1, s_dw, True))
+        ops.append(Op("conv", f"pw{i}", mid, nxt, cin, cout, 1, 1, 0, s_pw, True))
+        cur, cin = nxt, cout
+    ops.append(Op("avgpool", "gap", cur, 4))
+    ops.append(Op("fc", "fc", 4, 5, 1024, 1000, sparsity=s_fc, relu=False))
+    return ops
+
+
 def buffer_shapes(ops: Sequence[Op], input_shape: Tuple[int, int, int, int]) -> Dict[int, Tuple[int, ...]]:
     """Largest shape each buffer id takes, by walking the op list (shape inference only)."""
     cur: Dict[int, Tuple[int, ...]] = {0: tuple(input_shape)}
@@ -112,6 +135,11 @@ def buffer_shapes(ops: Sequence[Op], input_shape: Tuple[int, int, int, int]) -> 
             n, c, h, w = s
             assert c == op.cin, (op, s)
             o = (n, op.cout, conv_out_size(h, op.k, op.stride, op.pad),
+                 conv_out_size(w, op.k, op.stride, op.pad))
+        elif op.kind == "dwconv":
+            n, c, h, w = s
+            assert c == op.cin == op.cout, (op, s)
+            o = (n, c, conv_out_size(h, op.k, op.stride, op.pad),
                  conv_out_size(w, op.k, op.stride, op.pad))
         elif op.kind == "maxpool":
             n, c, h, w = s
@@ -143,6 +171,9 @@ def net_tensors(ops: Sequence[Op], config: str, input_shape, input_relu: bool = 
     for i, op in enumerate(ops):
         if op.kind == "conv":
             weights.append(pruned_weights(op.cout, op.cin, op.k, op.k, op.sparsity, config, i + 1, mask))
+            biases.append(bias_vector(op.cout, config, i + 1))
+        elif op.kind == "dwconv":
+            weights.append(pruned_weights(op.cout, 1, op.k, op.k, op.sparsity, config, i + 1, mask))
             biases.append(bias_vector(op.cout, config, i + 1))
         elif op.kind == "fc":
             weights.append(pruned_weights(op.cout, op.cin, 1, 1, op.sparsity, config, i + 1, mask))
