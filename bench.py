@@ -41,6 +41,12 @@ def layer_costs(ops, weights, in_shape, elem):
             flops = 2.0 * nnz * ho * wo * n
             byts = (n * c * h * w + n * op.cout * ho * wo * (2 if op.res >= 0 else 1)) * elem \
                 + nnz * (elem + 2) + (op.cout + 1) * 4 + op.cout * 4 + op.cout * 4
+        elif op.kind == "dwconv":
+            ho, wo = conv_out_size(h, op.k, op.stride, op.pad), conv_out_size(w, op.k, op.stride, op.pad)
+            nnz = int(np.count_nonzero(weights[i]))
+            out = (n, c, ho, wo)
+            flops = 2.0 * nnz * ho * wo * n
+            byts = (n * c * h * w + n * c * ho * wo) * elem + c * op.k * op.k * 4 + c * 4
         elif op.kind == "fc":
             nnz = int(np.count_nonzero(weights[i]))
             out = (n, op.cout, 1, 1)
@@ -63,7 +69,7 @@ def layer_costs(ops, weights, in_shape, elem):
 
 KERNEL_OF_PREFIX = {"slinear": "sconv_linear_kernel", "stile": "sconv_stile_kernel",
                     "sdirect": "sconv_direct_kernel", "sconv": "sconv_tile_kernel",
-                    "dense": "dense_conv_kernel", "sfc": "sfc_kernel", "maxpool": "maxpool_kernel",
+                    "dense": "dense_conv_kernel", "sfc": "sfc_kernel", "dwconv": "dwconv_kernel", "maxpool": "maxpool_kernel",
                     "avgpool": "avgpool_kernel", "fused": "(computed inside another op)"}
 
 
@@ -91,9 +97,10 @@ def main() -> int:
                          "(written by paper_1905_00571_amd/profile_summary.py)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a 256 MiB device copy 10 times (known traffic, for counter calibration)")
-    ap.add_argument("--workload", choices=["c2", "c3", "c4"], default="c2",
+    ap.add_argument("--workload", choices=["c2", "c3", "c4", "mobilenet"], default="c2",
                     help="c2 (default, the metric's workload): ResNet-50 fp32, conv1 dense / 3x3 80 %% / 1x1+FC 90 %%; "
-                         "c3: ResNet-50 with uniform --sparsity in --dtype at --batch; c4: VGG-16 conv 90 %% / FC 96 %%")
+                         "c3: ResNet-50 with uniform --sparsity in --dtype at --batch; c4: VGG-16 conv 90 %% / FC 96 %%; "
+                         "mobilenet: MobileNet-V1, dense first layer and depthwise filters, pointwise 80 %% / FC 90 %%")
     ap.add_argument("--batch", type=int, default=1)
     ap.add_argument("--sparsity", type=float, default=0.8, help="uniform sparsity of workload c3")
     ap.add_argument("--dtype", choices=["f32", "f16"], default="", help="storage type (default f32; c3: f16)")
@@ -131,6 +138,10 @@ def main() -> int:
     elif args.workload == "c3":
         ops, tag = wl.resnet50_ops(uniform=args.sparsity), "c3-%s" % args.sparsity
         desc = "resnet50-sparse %s batch %d (configs[3]): every layer %.0f %% unstructured sparsity" % (dt, n, 100 * args.sparsity)
+    elif args.workload == "mobilenet":
+        ops, tag = wl.mobilenet_v1_ops(), "mbv1"
+        desc = "mobilenet-v1-sparse %s batch %d: conv1 and 13 depthwise 3x3 dense, 13 pointwise 80 %%, FC 90 %% " \
+               "unstructured sparsity" % (dt, n)
     else:
         ops, tag = wl.vgg16_ops(), "c4"
         desc = "vgg16-sparse %s batch %d (configs[4]): 13 convs 90 %%, 3 FC 96 %% unstructured sparsity" % (dt, n)

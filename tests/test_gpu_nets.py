@@ -89,6 +89,40 @@ def test_config2_resnet50_fp32(cad):
     net.free()
 
 
+def test_config2_resnet50_fp32_in_the_benchmark_configuration(cad):
+    """The launch configuration bench.py times: the saved per-layer kernel choice that ships
+    with the package, default layouts and fusions, one HIP graph replayed."""
+    import json
+    import os
+    path = os.path.join(os.path.dirname(cad.__file__), "tuned", "resnet50_c2_f32_n1.json")
+    names = json.load(open(path))["variants"]
+    ops = wl.resnet50_ops()
+    assert len(names) == len(ops)
+    shape = (1, 3, 224, 224)
+    x, ws, bs = wl.net_tensors(ops, "c2", shape)
+    ref, ins, outs = oracle.run_net(ops, x, ws, bs)
+    net = cad.build_net(ops, ws, bs, shape, cad.F32, use_graph=True)
+    net.set_variants(names)                      # raises if a saved name does not fit this build
+    assert net.variants() == names
+    kinds = {n.split("_")[0] for n in names}
+    assert {"slinear", "dense", "fused", "sfc"} <= kinds, kinds
+    xd = dev(x)
+    cond = cond_fc(ins[-1], ws[-1], bs[-1])
+    for rep in range(3):
+        y = net.run(xd)
+        torch.cuda.synchronize()
+        e = assert_chain_close(y.cpu().numpy(), ref, cond, TOL_F32, f"resnet50 saved tuning (replay {rep})")
+    # sampled intermediate tensors of the same run against the oracle's
+    for name in ("conv4_6c", "conv5_3a", "conv5_3b"):
+        i = next(k for k, o in enumerate(ops) if o.name == name)
+        if any(o.dst == ops[i].dst for o in ops[i + 1:]):
+            continue                              # buffer id reused by a later op
+        got = net.read_buffer(ops[i].dst, outs[i].shape)
+        assert_close(got, outs[i], 1e-3, name + " inside the tuned net")
+    print("resnet50 saved tuning end-to-end", e)
+    net.free()
+
+
 def test_config4_vgg16_fp32(cad):
     ops = wl.vgg16_ops()
     shape = (1, 3, 224, 224)

@@ -148,6 +148,33 @@ def test_layer_argument_checks_without_a_gpu():
     h.free()
 
 
+def test_depthwise_argument_checks_without_a_gpu():
+    L = cad.lib()
+    dw = cad.cadnn_pack_weights(wl.pruned_weights(4, 1, 3, 3, 0.0, "packtest", 5))
+    full = cad.cadnn_pack_weights(wl.pruned_weights(4, 4, 3, 3, 0.5, "packtest", 6))
+    assert L.cadnn_depthwise_conv2d(None, 1, 1, 1, 8, 8, 1, 1, None, 0, None) == 1
+    assert L.cadnn_depthwise_conv2d(dw.handle, None, None, 1, 8, 8, 1, 1, None, 0, None) == 1      # NULL tensors
+    assert L.cadnn_depthwise_conv2d(full.handle, 1, 1, 1, 8, 8, 1, 1, None, 0, None) == 1          # cin != 1
+    assert b"depthwise" in L.cadnn_last_error()
+    assert L.cadnn_depthwise_conv2d(dw.handle, 1, 1, 1, 2, 2, 1, 0, None, 0, None) == 1            # empty output
+    assert L.cadnn_depthwise_conv2d(dw.handle, 1, 1, 1, 8, 8, 0, 1, None, 0, None) == 1            # stride 0
+    assert L.cadnn_depthwise_prepare(full.handle) == 1
+    net = ctypes.c_void_p()
+    assert L.cadnn_net_create(0, 1, 4, 8, 8, ctypes.byref(net)) == 0
+    assert L.cadnn_net_add_depthwise(net, full.handle, None, 1, 1, 1, 0, 1) == 1     # not a depthwise bank
+    assert L.cadnn_net_add_depthwise(net, dw.handle, None, 1, 1, 1, 0, 0) == 1       # dst aliases src
+    assert L.cadnn_net_add_depthwise(net, dw.handle, None, 1, 1, 1, 0, 1) == 0
+    dw8 = cad.cadnn_pack_weights(wl.pruned_weights(8, 1, 3, 3, 0.0, "packtest", 7))
+    assert L.cadnn_net_add_depthwise(net, dw8.handle, None, 1, 1, 1, 1, 2) == 1      # 8 filters on 4 channels
+    assert L.cadnn_net_add_depthwise(net, dw.handle, None, 2, 1, 1, 1, 2) == 0
+    nbytes = ctypes.c_size_t()
+    assert L.cadnn_net_workspace_bytes(net, ctypes.byref(nbytes)) == 0
+    assert nbytes.value >= 4 * 10 * 10 * 4           # first output: 4 planes of 8x8 inside a 1-pixel zero halo
+    assert L.cadnn_net_free(net) == 0
+    for h in (dw, full, dw8):
+        h.free()
+
+
 def test_binding_exposes_the_c_names():
     for n in declared_symbols():
         if n.startswith("cadnn_net_") or n in ("cadnn_last_error",):

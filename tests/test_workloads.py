@@ -103,3 +103,23 @@ def test_vgg16_table():
     assert [o.relu for o in fcs] == [True, True, False]
     shapes = wl.buffer_shapes(ops, (1, 3, 224, 224))
     assert shapes[5] == (1, 1000, 1, 1)
+
+
+def test_mobilenet_v1_table():
+    ops = wl.mobilenet_v1_ops()
+    kinds = [o.kind for o in ops]
+    assert kinds.count("dwconv") == 13 and kinds.count("conv") == 14 and kinds.count("fc") == 1
+    assert kinds.count("avgpool") == 1 and len(ops) == 29
+    # 28 weight layers (the count the architecture is known by) and 4.2 M weights
+    x, ws, bs = wl.net_tensors(ops, "mbtest", (1, 3, 224, 224))
+    total = sum(w.size for w in ws if w is not None)
+    assert 4.1e6 < total < 4.3e6, total
+    shapes = wl.buffer_shapes(ops, (1, 3, 224, 224))
+    assert shapes[ops[-1].dst] == (1, 1000, 1, 1)
+    for o, w in zip(ops, ws):
+        if o.kind == "dwconv":
+            assert w.shape == (o.cin, 1, 3, 3) and np.count_nonzero(w) == w.size
+        if o.kind == "conv" and o.k == 1:
+            assert abs(1 - np.count_nonzero(w) / w.size - 0.8) < 1e-3
+    # strides: four stride-2 depthwise layers and the stride-2 first layer take 224 down to 7
+    assert [o.stride for o in ops if o.kind == "dwconv"].count(2) == 4 and ops[0].stride == 2
