@@ -97,10 +97,11 @@ def main() -> int:
                          "(written by paper_1905_00571_amd/profile_summary.py)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a 256 MiB device copy 10 times (known traffic, for counter calibration)")
-    ap.add_argument("--workload", choices=["c2", "c3", "c4", "mobilenet"], default="c2",
+    ap.add_argument("--workload", choices=["c2", "c3", "c4", "mobilenet", "mobilenet2"], default="c2",
                     help="c2 (default, the metric's workload): ResNet-50 fp32, conv1 dense / 3x3 80 %% / 1x1+FC 90 %%; "
                          "c3: ResNet-50 with uniform --sparsity in --dtype at --batch; c4: VGG-16 conv 90 %% / FC 96 %%; "
-                         "mobilenet: MobileNet-V1, dense first layer and depthwise filters, pointwise 80 %% / FC 90 %%")
+                         "mobilenet / mobilenet2: MobileNet-V1 / -V2, dense first layer and depthwise filters, "
+                         "pointwise 80 %% / FC 90 %%")
     ap.add_argument("--batch", type=int, default=1)
     ap.add_argument("--sparsity", type=float, default=0.8, help="uniform sparsity of workload c3")
     ap.add_argument("--dtype", choices=["f32", "f16"], default="", help="storage type (default f32; c3: f16)")
@@ -141,6 +142,10 @@ def main() -> int:
     elif args.workload == "mobilenet":
         ops, tag = wl.mobilenet_v1_ops(), "mbv1"
         desc = "mobilenet-v1-sparse %s batch %d: conv1 and 13 depthwise 3x3 dense, 13 pointwise 80 %%, FC 90 %% " \
+               "unstructured sparsity" % (dt, n)
+    elif args.workload == "mobilenet2":
+        ops, tag = wl.mobilenet_v2_ops(), "mbv2"
+        desc = "mobilenet-v2-sparse %s batch %d: conv1 and 17 depthwise 3x3 dense, 34 pointwise 80 %%, FC 90 %% " \
                "unstructured sparsity" % (dt, n)
     else:
         ops, tag = wl.vgg16_ops(), "c4"

@@ -123,3 +123,21 @@ def test_mobilenet_v1_table():
             assert abs(1 - np.count_nonzero(w) / w.size - 0.8) < 1e-3
     # strides: four stride-2 depthwise layers and the stride-2 first layer take 224 down to 7
     assert [o.stride for o in ops if o.kind == "dwconv"].count(2) == 4 and ops[0].stride == 2
+
+
+def test_mobilenet_v2_table():
+    ops = wl.mobilenet_v2_ops()
+    kinds = [o.kind for o in ops]
+    assert kinds.count("dwconv") == 17 and kinds.count("conv") == 35 and kinds.count("fc") == 1
+    assert sum(o.res >= 0 for o in ops) == 10           # blocks with stride 1 and equal widths
+    assert all(not o.relu for o in ops if o.name.endswith("_project"))
+    x, ws, bs = wl.net_tensors(ops, "mbtest2", (1, 3, 224, 224))
+    total = sum(w.size for w in ws if w is not None)
+    assert 3.4e6 < total < 3.55e6, total
+    shapes = wl.buffer_shapes(ops, (1, 3, 224, 224))
+    assert shapes[ops[-1].dst] == (1, 1000, 1, 1)
+    # a residual is read from a buffer no op of its block overwrites
+    for i, o in enumerate(ops):
+        if o.res >= 0:
+            blk = o.name.split("_")[0]
+            assert all(p.dst != o.res for p in ops[:i + 1] if p.name.startswith(blk + "_"))

@@ -19,6 +19,7 @@ from .nets import (  # noqa: F401
     resnet50_ops,
     vgg16_ops,
     mobilenet_v1_ops,
+    mobilenet_v2_ops,
     bottleneck_conv2x_ops,
     single_conv_ops,
     net_tensors,

@@ -125,6 +125,40 @@ def mobilenet_v1_ops(s_conv1: float = 0.0, s_dw: float = 0.0, s_pw: float = 0.8,
     return ops
 
 
+def mobilenet_v2_ops(s_conv1: float = 0.0, s_dw: float = 0.0, s_pw: float = 0.8,
+                     s_fc: float = 0.9) -> List[Op]:
+    """MobileNet-V2 at width 1.0 and 224x224 input (named in the paper's Table 2): a 3x3/2
+    convolution to 32 channels, 17 inverted-residual blocks -- 1x1 expansion by t (absent
+    when t = 1) + ReLU, 3x3 depthwise + ReLU, linear 1x1 projection, plus the block input when
+    the stride is 1 and the channel counts agree -- in the published (t, c, n, s) ladder, a
+    1x1 convolution to 1280 channels, global average pool, FC 1280->1000.  The published
+    network clips activations at 6; the layers here use plain ReLU (the fused epilogue the
+    paper describes)."""
+    ladder = [(1, 16, 1, 1), (6, 24, 2, 2), (6, 32, 3, 2), (6, 64, 4, 2), (6, 96, 3, 1), (6, 160, 3, 2),
+              (6, 320, 1, 1)]
+    ops: List[Op] = [Op("conv", "conv1", 0, 1, 3, 32, 3, 2, 1, s_conv1, True)]
+    cur, cin, blk = 1, 32, 0
+    for t, cout, reps, stride in ladder:
+        for r in range(reps):
+            blk += 1
+            st = stride if r == 0 else 1
+            free = [b for b in (1, 2, 3, 4) if b != cur]
+            mid = cin * t
+            src = cur
+            if t != 1:
+                ops.append(Op("conv", f"b{blk}_expand", src, free[0], cin, mid, 1, 1, 0, s_pw, True))
+                src = free[0]
+            ops.append(Op("dwconv", f"b{blk}_dw", src, free[1], mid, mid, 3, st, 1, s_dw, True))
+            res = cur if (st == 1 and cin == cout) else -1
+            ops.append(Op("conv", f"b{blk}_project", free[1], free[2], mid, cout, 1, 1, 0, s_pw, False, res=res))
+            cur, cin = free[2], cout
+    last = 1 if cur != 1 else 2
+    ops.append(Op("conv", "conv_last", cur, last, cin, 1280, 1, 1, 0, s_pw, True))
+    ops.append(Op("avgpool", "gap", last, 5))
+    ops.append(Op("fc", "fc", 5, 6, 1280, 1000, sparsity=s_fc, relu=False))
+    return ops
+
+
 def buffer_shapes(ops: Sequence[Op], input_shape: Tuple[int, int, int, int]) -> Dict[int, Tuple[int, ...]]:
     """Largest shape each buffer id takes, by walking the op list (shape inference only)."""
     cur: Dict[int, Tuple[int, ...]] = {0: tuple(input_shape)}
