@@ -243,9 +243,9 @@ def main() -> int:
     for i, op in enumerate(ops):
         if names[i] != "fused":
             continue
-        if op.kind == "avgpool":
-            # pooled in the epilogue of the convolution that feeds it: that layer's feature map
-            # is neither written nor read back; only the pooled vector is written
+        if op.kind in ("avgpool", "dwconv"):
+            # pooled (or depthwise-filtered) in the epilogue of the convolution that feeds it: that
+            # layer's feature map is neither written nor read back; only the fused op's output is
             j = max(k for k, o in enumerate(ops[:i]) if o.dst == op.src)
             map_bytes = float(np.prod(costs[i]["in"])) * elem
             costs[j]["flops"] += costs[i]["flops"]

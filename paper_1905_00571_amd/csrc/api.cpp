@@ -17,7 +17,8 @@ struct ConvGeom {
     const ConvExtra* ex = nullptr;   // fused 1x1 shortcut
     GeomKey key() const {
         return {n, xd.h, xd.w, stride, pad, xd.ph, xd.pw,
-                (xd.s2d ? 1 : 0) | (out_s2d ? 2 : 0) | ((ex && ex->w) ? 4 : 0) | ((ex && ex->pool_y) ? 8 : 0)};
+                (xd.s2d ? 1 : 0) | (out_s2d ? 2 : 0) | ((ex && ex->w) ? 4 : 0) | ((ex && ex->pool_y) ? 8 : 0) |
+                    ((ex && ex->dw) ? (ex->dw_stride == 2 ? 48 : 16) : 0)};
     }
 };
 
@@ -28,7 +29,14 @@ static cadnn_status check_conv(const char* who, const cadnn_weights* w, const Te
     if (stride <= 0 || pad < 0) return fail(CADNN_EINVAL, "%s: bad stride/pad", who);
     if (xd.c != w->cin) return fail(CADNN_EINVAL, "%s: %d input channels, weights take %d", who, xd.c, w->cin);
     g->n = n; g->stride = stride; g->pad = pad; g->xd = xd; g->out_s2d = out_s2d; g->ex = ex;
-    if (ex && !ex->w && !ex->pool_y) return fail(CADNN_EINVAL, "%s: empty fusion request", who);
+    if (ex && !ex->w && !ex->pool_y && !ex->dw) return fail(CADNN_EINVAL, "%s: empty fusion request", who);
+    if (ex && ex->dw) {
+        const cadnn_weights* d = ex->dw;
+        if (ex->w || ex->pool_y) return fail(CADNN_EINVAL, "%s: one fusion at a time", who);
+        if (d->cin != 1 || d->cout != w->cout || d->kh != 3 || d->kw != 3 || d->dtype != w->dtype ||
+            (ex->dw_stride != 1 && ex->dw_stride != 2))
+            return fail(CADNN_EINVAL, "%s: the fused depthwise layer must be 3x3, stride 1 or 2, one filter per output channel", who);
+    }
     if (ex && ex->w) {
         if (!ex->x) return fail(CADNN_EINVAL, "%s: NULL fused shortcut", who);
         if (ex->w->kh != 1 || ex->w->kw != 1 || ex->w->cout != w->cout || ex->w->dtype != w->dtype ||
@@ -74,8 +82,10 @@ static bool variant_fits(const ConvVariant& v, const cadnn_weights* w, const Con
         if (general != (v.s2d != 0)) return false;
         // a fused shortcut takes the dual-input instantiations; its input must be walkable
         // with one stride (plain layout, or de-interleaved and read with stride 2)
-        const bool shortcut = g.ex && g.ex->w, pooled = g.ex && g.ex->pool_y;
-        if (shortcut != (v.dual != 0) || pooled != (v.pool != 0)) return false;
+        const bool shortcut = g.ex && g.ex->w, pooled = g.ex && g.ex->pool_y, dwf = g.ex && g.ex->dw;
+        if (shortcut != (v.dual != 0) || pooled != (v.pool != 0) || dwf != (v.dw != 0)) return false;
+        // a fused depthwise layer needs the whole image, at most 16 x 16, in one pixel tile
+        if (dwf && (general || g.hout * g.wout > 64 * v.p || g.hout > 16 || g.wout > 16)) return false;
         // a fused pool needs the whole image in one pixel tile of the variant
         if (pooled && (general || shortcut || g.hout * g.wout > 64 * v.p)) return false;
         if (shortcut) {
@@ -192,6 +202,15 @@ static cadnn_status launch_variant(const cadnn_weights* w, const ConvVariant* v,
     if (g.ex && g.ex->pool_y) {
         a.pool_y = g.ex->pool_y;
         a.pool_scale = 1.0f / (float)(g.hout * g.wout);
+    }
+    if (g.ex && g.ex->dw) {
+        if (!g.ex->dw->dw_ready) return fail(CADNN_EINVAL, "fused depthwise filters were not prepared");
+        a.dw_y = g.ex->dw_y;
+        a.dw_w = (const float*)g.ex->dw->d_dw.p;
+        a.dw_bias = (const float*)g.ex->dw_bias;
+        a.dw_yd = g.ex->dw_yd;
+        a.dw_stride = g.ex->dw_stride;
+        a.dw_relu = g.ex->dw_relu;
     }
     if (g.ex && g.ex->w) {
         // the shortcut's input as a plain view walked with one stride from pixel (0, 0)

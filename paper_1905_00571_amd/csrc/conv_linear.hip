@@ -24,6 +24,7 @@
 
 namespace cadnn {
 
+constexpr int kDwPlaneMax = 18 * 18;            // fused depthwise: image sides up to 16, plus a 1-pixel halo
 constexpr uint32_t kLinOutOfRange = 0x7ffffff0u;   // beyond any buffer this library accepts
 
 // ADJ = 0: the P pixels of a lane are 64 apart (P wave-wide loads of one element each);
@@ -42,12 +43,13 @@ constexpr uint32_t kLinOutOfRange = 0x7ffffff0u;   // beyond any buffer this lib
 //          image: the epilogue averages the wave's pixels and writes the pooled vector;
 //          the feature map itself is never written.
 template <typename T_, int P_, int RPW_, int KS_, int NW_, int U_, int ADJ_ = 0, int S2D_ = 0, int DUAL_ = 0,
-          int POOL_ = 0>
+          int POOL_ = 0, int DW_ = 0>
 struct LinearCfg {
     using T = T_;
     static constexpr int P = P_, RPW = RPW_, KS = KS_, NW = NW_, U = U_, ADJ = ADJ_, S2D = S2D_, DUAL = DUAL_,
-                         POOL = POOL_;
+                         POOL = POOL_, DW = DW_;
     static_assert(!(S2D && DUAL) && !(POOL && (S2D || DUAL || ADJ)), "not combined");
+    static_assert(!(DW && (S2D || DUAL || POOL)), "not combined");
     static_assert(!(ADJ && S2D), "adjacent pixels are not adjacent in a de-interleaved tensor");
     static constexpr int RG = NW / KS;
     static constexpr int THREADS = NW * 64;
@@ -360,6 +362,58 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_linear_kernel(const ConvLa
         return;
     }
 
+    if constexpr (Cfg::DW) {
+        // ---- fused epilogue + 3x3 depthwise layer (padding 1): the whole image of each of the
+        //      wave's channels is in this wave.  It goes, rounded to the storage type as the
+        //      separate layer would have read it, into a zero-haloed LDS plane of the wave's
+        //      own; the lanes then take the depthwise outputs of the channel from there.
+        __shared__ float dwbuf[Cfg::RG][kDwPlaneMax];
+        float* pl = dwbuf[rg];
+        const int pitch = a.yd.w + 2;
+        for (int i = lane; i < (a.yd.h + 2) * pitch; i += 64) pl[i] = 0.0f;
+        T* __restrict__ y2 = (T*)a.dw_y + (size_t)n * a.dw_yd.image;
+        const int w2 = a.dw_yd.w, hw2 = a.dw_yd.h * w2;
+#pragma unroll
+        for (int r = 0; r < RPW; ++r) {
+            const int co = co_[r];
+            if (co < 0) continue;
+            // (the previous channel's reads are done before its plane is overwritten)
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int j = 0; j < P; ++j) {
+                if (oidx[j] >= 0) {
+                    const int q = ADJ ? lane * P + j : j * 64 + lane;
+                    const int oh = q / a.yd.w, ow = q - oh * a.yd.w;
+                    float v = acc[r][j] + bias_[r] + resv[r][j];
+                    if (a.relu) v = v > 0.0f ? v : 0.0f;
+                    pl[(oh + 1) * pitch + ow + 1] = (float)(T)v;
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            const float* __restrict__ wt = a.dw_w + (size_t)co * 9;
+            const float b2 = a.dw_bias ? a.dw_bias[co] : 0.0f;
+            for (int t = lane; t < hw2; t += 64) {
+                const int oh2 = t / w2, ow2 = t - oh2 * w2;
+                const float* tap = pl + oh2 * a.dw_stride * pitch + ow2 * a.dw_stride;
+                float sum = 0.0f;
+#pragma unroll
+                for (int i = 0; i < 3; ++i)
+#pragma unroll
+                    for (int k = 0; k < 3; ++k) {
+                        const float wv = wt[i * 3 + k];
+                        if (wv != 0.0f) sum = fmaf(wv, tap[i * pitch + k], sum);
+                    }
+                float v2 = sum + b2;
+                if (a.dw_relu) v2 = v2 > 0.0f ? v2 : 0.0f;
+                y2[(size_t)co * a.dw_yd.plane + a.dw_yd.origin + oh2 * a.dw_yd.pitch + ow2] = (T)v2;
+            }
+        }
+        return;
+    }
+
     // ---- fused epilogue: + bias, + residual, ReLU, store at the original channel
     T* __restrict__ y = (T*)a.y + (size_t)n * a.yd.image;
 #pragma unroll
@@ -400,6 +454,7 @@ static ConvVariant make_linear(const char* name) {
     v.s2d = Cfg::S2D;
     v.dual = Cfg::DUAL;
     v.pool = Cfg::POOL;
+    v.dw = Cfg::DW;
     v.lds_bytes = Cfg::KS > 1 ? (size_t)Cfg::NW * Cfg::RPW * Cfg::P * 64 * 4 : 0;
     v.launch = &launch_linear<Cfg>;
     return v;
@@ -423,7 +478,17 @@ static ConvVariant make_linear(const char* name) {
 #define CADNN_LINEAR_POOL(T, P, RPW, KS, NW, U) \
     make_linear<LinearCfg<T, P, RPW, KS, NW, U, 0, 0, 0, 1>>("slinear_" #T "_gp" #P "_r" #RPW "k" #KS "w" #NW "u" #U)
 
+#define CADNN_LINEAR_DW(T, P, RPW, KS, NW, U) \
+    make_linear<LinearCfg<T, P, RPW, KS, NW, U, 0, 0, 0, 0, 1>>("slinear_" #T "_dw" #P "_r" #RPW "k" #KS "w" #NW "u" #U)
+
 #define CADNN_LINEAR_SHAPES(T)          \
+    CADNN_LINEAR_DW(T, 1, 1, 1, 4, 4), \
+    CADNN_LINEAR_DW(T, 1, 1, 1, 4, 8), \
+    CADNN_LINEAR_DW(T, 1, 1, 2, 4, 4), \
+    CADNN_LINEAR_DW(T, 1, 1, 2, 4, 8), \
+    CADNN_LINEAR_DW(T, 1, 1, 4, 4, 4), \
+    CADNN_LINEAR_DW(T, 1, 1, 4, 4, 8), \
+    CADNN_LINEAR_DW(T, 1, 1, 8, 8, 4), \
     CADNN_LINEAR_POOL(T, 1, 1, 1, 4, 4), \
     CADNN_LINEAR_POOL(T, 1, 1, 1, 4, 8), \
     CADNN_LINEAR_POOL(T, 1, 1, 2, 4, 4), \

@@ -158,6 +158,7 @@ struct ConvVariant {
     int s2d;              // FAM_LINEAR: understands de-interleaved output / residual / pixel-wise input
     int dual;             // FAM_LINEAR: accumulates a fused 1x1 shortcut on a second input
     int pool;             // FAM_LINEAR: global average pool fused into the epilogue
+    int dw;               // FAM_LINEAR: a 3x3 depthwise layer fused into the epilogue
     int nz_cap;           // FAM_STILE: most stream entries per (row group, chunk) the kernel buffers
     size_t lds_bytes;
     hipError_t (*launch)(const ConvLaunch&, hipStream_t);
@@ -186,6 +187,12 @@ struct ConvLaunch {
     // fused global average pool (FAM_LINEAR pool instantiations): [n][cout] means
     void* pool_y;
     float pool_scale;
+    // fused depthwise layer (FAM_LINEAR dw instantiations): its filter table, bias, output
+    void* dw_y;
+    const float* dw_w;
+    const float* dw_bias;
+    TensorDesc dw_yd;
+    int dw_stride, dw_relu;
     // FAM_PTILE: geometry of the staged tile (see PtileGeom)
     int pt_pitch, pt_sub, pt_plane, pt_nphc, pt_nph, pt_in_rows, pt_in_cols, pt_cch, pt_nstp, pt_nchunks;
     uint32_t pt_lds_bytes;
@@ -238,7 +245,7 @@ constexpr int kFcTailEntries = 1024;   // 4 loads x 64 lanes x 4 entries
 typedef std::tuple<const ConvVariant*, int, int, const void*, int> PlanKey;
 // (n, h, w, stride, pad, input halo rows, input halo columns, flags: 1 = input
 // de-interleaved, 2 = output or residual de-interleaved, 4 = a shortcut is fused in,
-// 8 = a global average pool is fused in)
+// 8 = a global average pool is fused in, 16 = a depthwise layer is fused in, 32 = with stride 2)
 typedef std::array<int, 8> GeomKey;
 
 const std::vector<ConvVariant>& all_tile_variants();
@@ -291,6 +298,13 @@ struct ConvExtra {
     int stride;
     const void* bias;     // device, fp32, may be NULL
     void* pool_y;
+    // Or (dw != NULL) a 3x3 depthwise layer with padding 1 fused into the layer that produces
+    // its input: the layer's own feature map is not written, the depthwise output is.
+    const cadnn_weights* dw;
+    const void* dw_bias;  // device, fp32, may be NULL
+    int dw_stride, dw_relu;
+    void* dw_y;
+    TensorDesc dw_yd;
 };
 
 // stride / pad / wout matter to FAM_PTILE plans only.

@@ -34,7 +34,8 @@ struct NetOp {
     size_t y_off = 0;                        // byte offset of this op's output region
     int shortcut = -1;                       // conv: the 1x1 projection op fused into this one
     int pool_op = -1;                        // conv: the global average pool op fused into this one
-    int fused_into = -1;                     // projection / pool: the op that now computes it (it is skipped)
+    int dw_op = -1;                          // conv: the depthwise op fused into this one
+    int fused_into = -1;                     // projection / pool / depthwise: the op that now computes it (it is skipped)
 };
 
 }  // namespace
@@ -140,7 +141,7 @@ void layout(cadnn_net* net) {
     // A 1x1 projection shortcut whose only reader takes it as residual is computed inside
     // that reader (a second sparse matrix on a second input, same accumulators): one launch,
     // one output write and one residual read less (paper Section 4, layer fusion).
-    for (NetOp& op : net->ops) { op.shortcut = -1; op.pool_op = -1; op.fused_into = -1; }
+    for (NetOp& op : net->ops) { op.shortcut = -1; op.pool_op = -1; op.dw_op = -1; op.fused_into = -1; }
     if (net->allow_fusion) {
         std::vector<int> readers(nops, 0);
         for (const NetOp& op : net->ops) {
@@ -179,6 +180,26 @@ void layout(cadnn_net* net) {
                 a.fused_into = a.src_inst;
             }
         }
+        // A 3x3 depthwise layer (padding 1, stride 1 or 2) that is the only reader of a
+        // convolution whose image fits one wavefront (64 pixels) is computed in that
+        // convolution's epilogue: a wave holds a whole channel there, which is all a depthwise
+        // filter needs.  The convolution's own feature map is not written.  (Measured: with
+        // 14 x 14 images, four pixels per lane, the fused layer is slower than the two apart.)
+        for (int i = 0; i < nops; ++i) {
+            NetOp& d = net->ops[i];
+            if (d.kind != OP_DEPTHWISE || d.src_inst < 0) continue;
+            NetOp& c = net->ops[d.src_inst];
+            const bool c_one = c.kind == OP_CONV && c.w->kh == 1 && c.w->kw == 1;
+            const bool ok = c.kind == OP_CONV && readers[d.src_inst] == 1 && c.shortcut < 0 && c.pool_op < 0 &&
+                            c.fused_into < 0 && sparse_enough(c) && !c.yd.s2d && !c.xd.s2d && !(c.res >= 0 && c.rd.s2d) &&
+                            c.out.h <= 16 && c.out.w <= 16 && c.out.h * c.out.w <= 64 && d.w->kh == 3 && d.w->kw == 3 && d.pad == 1 &&
+                            (d.stride == 1 || d.stride == 2) && !d.yd.s2d &&
+                            (c_one ? c.pad == 0 : (c.xd.ph >= c.pad && c.xd.pw >= c.pad));
+            if (ok) {
+                c.dw_op = i;
+                d.fused_into = d.src_inst;
+            }
+        }
     }
     net->ws_bytes = off;
     net->laid_out = true;
@@ -213,6 +234,16 @@ bool shortcut_of(const cadnn_net* net, const NetOp& op, const void* x, ConvExtra
     }
     if (op.pool_op >= 0) {
         ex->pool_y = y ? out_ptr(net, (size_t)op.pool_op, y) : (void*)net;   // placeholder for geometry-only calls
+        return true;
+    }
+    if (op.dw_op >= 0) {
+        const NetOp& d = net->ops[op.dw_op];
+        ex->dw = d.w;
+        ex->dw_bias = d.bias;
+        ex->dw_stride = d.stride;
+        ex->dw_relu = d.relu;
+        ex->dw_yd = d.yd;
+        ex->dw_y = y ? out_ptr(net, (size_t)op.dw_op, y) : (void*)net;
         return true;
     }
     return false;
@@ -527,7 +558,7 @@ extern "C" cadnn_status cadnn_net_op_variant(const cadnn_net* net, int op_index,
             break;
         }
         case OP_FC: name = "sfc"; break;
-        case OP_DEPTHWISE: name = "dwconv"; break;
+        case OP_DEPTHWISE: name = op.fused_into >= 0 ? "fused" : "dwconv"; break;
         case OP_MAXPOOL: name = "maxpool"; break;
         case OP_AVGPOOL: name = op.fused_into >= 0 ? "fused" : "avgpool"; break;
     }
@@ -575,6 +606,8 @@ extern "C" cadnn_status cadnn_net_read_buffer(cadnn_net* net, int buf, void* hos
         return fail(CADNN_EINVAL, "cadnn_net_read_buffer: buffer %d is never materialised (its op is computed inside op %d)", buf, op.fused_into);
     if (op.pool_op >= 0)
         return fail(CADNN_EINVAL, "cadnn_net_read_buffer: buffer %d is never materialised (op %d pools it on the fly)", buf, it->second);
+    if (op.dw_op >= 0)
+        return fail(CADNN_EINVAL, "cadnn_net_read_buffer: buffer %d is never materialised (op %d filters it on the fly)", buf, it->second);
     const size_t e = net->elem();
     if (bytes != op.out.elems() * e)
         return fail(CADNN_EINVAL, "cadnn_net_read_buffer: buffer %d holds %zu bytes, %zu asked", buf, op.out.elems() * e, bytes);

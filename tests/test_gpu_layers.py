@@ -501,3 +501,51 @@ def test_fused_global_average_pool(cad, geom):
         assert np.abs(yu - ref.astype(np.float64)).max() <= tol * np.abs(ref).max()
         net.free()
         unfused.free()
+
+
+@pytest.mark.parametrize("geom", [(7, 7, 1, 1, 1), (8, 8, 2, 3, 2), (5, 9, 3, 1, 2), (4, 16, 1, 3, 1)])
+def test_fused_depthwise_epilogue(cad, geom):
+    """A 3x3 depthwise layer that is the only reader of a convolution whose image fits one
+    wavefront is computed in that convolution's epilogue: the depthwise op reports "fused",
+    the convolution's own map is never materialised, and every such variant of the convolution
+    must reproduce the oracle's depthwise output (checked element by element against the
+    depthwise layer's own bound on the oracle's input) and the layers behind it."""
+    h, w_, n, k, ds = geom
+    ops = [wl.Op("conv", "pre", 0, 1, 8, 24, 1, 1, 0, 0.8, True),
+           wl.Op("conv", "mid", 1, 2, 24, 40, k, 1, k // 2, 0.85, True),
+           wl.Op("dwconv", "dw", 2, 3, 40, 40, 3, ds, 1, 0.2, True),
+           wl.Op("conv", "post", 3, 4, 40, 16, 1, 1, 0, 0.5, False)]
+    shape = (n, 8, h, w_)
+    x, ws, bs = wl.net_tensors(ops, "dwf-%d-%d-%d-%d" % (h, w_, k, ds), shape, input_relu=True)
+    for dtype, npdt, tol in ((cad.F32, np.float32, TOL_F32), (cad.F16, np.float16, TOL_F16)):
+        f16 = dtype == cad.F16
+        xs = x.astype(npdt)
+        ref, ins, outs = oracle.run_net(ops, xs, ws, bs, dtype=npdt)
+        net = cad.build_net(ops, ws, bs, shape, dtype, use_graph=False)
+        unfused = cad.build_net(ops, ws, bs, shape, dtype, use_graph=False, fuse=False)
+        xd = dev(xs)
+        assert net.op_variant(2) == "fused" and unfused.op_variant(2) == "dwconv"
+        with pytest.raises(cad.CadnnError):
+            net.read_buffer(2, outs[1].shape)
+        names = net.op_candidates(1)
+        assert names and all("_dw" in nm for nm in names), names
+        dw_ref = outs[2].astype(np.float64)
+        # bound of the fused pair on the oracle's input to the pair: the depthwise layer's own
+        # condition sum plus what the first layer's rounding error becomes behind |filters|
+        wd = ws[2].astype(npdt)
+        cond_mid = cond_conv(ins[1], ws[1].astype(npdt), bs[1], None, 1, k // 2)
+        cond = cond_depthwise(outs[1], wd, bs[2], ds, 1) + cond_depthwise(cond_mid.astype(np.float32), wd, None, ds, 1)
+        if f16:   # the intermediate map is rounded to fp16 on both sides, possibly to neighbouring values
+            cond = cond + 2.0 ** -10 / 1e-4 * cond_depthwise(np.abs(outs[1]).astype(np.float32), wd, None, ds, 1)
+        for name in names:
+            net.set_op_variant(1, name)
+            y = net.run(xd)
+            torch.cuda.synchronize()
+            got = net.read_buffer(3, outs[2].shape)
+            assert_layer_close(got, dw_ref, cond, tol, f"{geom} {name}", f16=f16)
+            assert np.abs(y.cpu().numpy().astype(np.float64) - ref.astype(np.float64)).max() <= tol * np.abs(ref).max(), name
+        yu = unfused.run(xd).cpu().numpy().astype(np.float64)
+        torch.cuda.synchronize()
+        assert np.abs(yu - ref.astype(np.float64)).max() <= tol * np.abs(ref).max()
+        net.free()
+        unfused.free()

@@ -158,7 +158,10 @@ def test_mobilenet(cad, version, dtype_name, n):
     cond = cond_fc(ins[-1], ws[-1].astype(npdt), bs[-1])
     for kw in ({}, {"plain_layout": True, "fuse": False}):
         net = cad.build_net(ops, ws, bs, shape, dtype, use_graph=True, **kw)
-        assert [net.op_variant(i) for i, o in enumerate(ops) if o.kind == "dwconv"] == ["dwconv"] * ndw
+        names = [net.op_variant(i) for i, o in enumerate(ops) if o.kind == "dwconv"]
+        # depthwise layers on images of at most 64 pixels run inside the layer that feeds them
+        fused = 0 if kw else (1 if version == 1 else 3)
+        assert names.count("fused") == fused and names.count("dwconv") == ndw - fused, names
         xd = dev(xs)
         for rep in range(2):
             y = net.run(xd)
