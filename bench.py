@@ -252,7 +252,7 @@ def main() -> int:
             costs[j]["bytes"] += costs[i]["bytes"] - 2.0 * map_bytes
             costs[i]["flops"] = costs[i]["bytes"] = 0.0
             continue
-        j = next(k for k, o in enumerate(ops) if o.kind == "conv" and o.res == op.dst)
+        j = next(k for k in range(i + 1, len(ops)) if ops[k].kind == "conv" and ops[k].res == op.dst)
         out_bytes = float(np.prod(costs[i]["out"])) * elem
         costs[j]["flops"] += costs[i]["flops"]
         costs[j]["bytes"] += costs[i]["bytes"] - out_bytes - out_bytes
@@ -335,7 +335,7 @@ def main() -> int:
                 memo[key] = (t_mfma, t_mio)
             costs[i]["dense_mfma_us"], costs[i]["miopen_us"] = memo[key]
             if names[i] == "fused":            # compared together with the layer that computes it
-                j = next(k for k, o in enumerate(ops) if o.kind == "conv" and o.res == op.dst)
+                j = next(k for k in range(i + 1, len(ops)) if ops[k].kind == "conv" and ops[k].res == op.dst)
                 pending[j] = memo[key]
                 continue
             t_mfma, t_mio = memo[key][0] + pending.get(i, (0.0, 0.0))[0], memo[key][1] + pending.get(i, (0.0, 0.0))[1]
