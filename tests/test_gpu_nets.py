@@ -195,3 +195,34 @@ def test_config3_resnet50_fp16(cad, n, s):
     cond = cond_fc(ins[-1], ws[-1].astype(np.float16), bs[-1])
     print("resnet50 fp16 end-to-end", n, s, assert_chain_close(y.cpu().numpy(), ref, cond, TOL_F16, "fp16 chain"))
     net.free()
+
+
+@pytest.mark.parametrize("dtype_name", ["f32", "f16"])
+def test_factorized_7x7_branch(cad, dtype_name):
+    """Inception-V3's 1x7 / 7x1 layers (the paper's Table 2 names the model) through the same
+    ABI: each rectangular filter bank is centred in a 7x7 one with padding 3, whose extra taps
+    are exact zeros and are never stored.  Each layer alone on a plain tensor (LDS-staged
+    kernels) and the chain inside a net (halo layouts, linear-address kernels)."""
+    f16 = dtype_name == "f16"
+    dtype, npdt, tol = (cad.F16, np.float16, TOL_F16) if f16 else (cad.F32, np.float32, TOL_F32)
+    ops = wl.factorized_7x7_branch_ops()
+    shape = (2, 768, 17, 17)
+    x, ws, bs = wl.net_tensors(ops, "incep", shape, input_relu=True)
+    xs = x.astype(npdt)
+    ref, ins, outs = oracle.run_net(ops, xs, ws, bs, dtype=npdt)
+    for i, op in enumerate(ops):
+        if op.kh:
+            h = cad.cadnn_pack_weights(ws[i], dtype)
+            assert cad.cadnn_packed_nnz(h) == wl.keep_count(op.cout * op.cin * op.kh * op.kw, op.sparsity)
+            h.free()
+    check_layers_in_isolation(cad, ops, ws, bs, ins, outs, tol, dtype)
+    net = cad.build_net(ops, ws, bs, shape, dtype, use_graph=True)
+    names = [net.op_variant(i) for i in range(len(ops))]
+    assert all(n.startswith("slinear") for n in names), names
+    for rep in range(2):
+        y = net.run(dev(xs))
+        torch.cuda.synchronize()
+        cond = cond_conv(ins[-1], ws[-1].astype(npdt), bs[-1], None, 1, 3)
+        e = assert_chain_close(y.cpu().numpy(), ref, cond, tol, f"factorized branch (replay {rep})")
+    print("factorized 7x7 branch", names, e)
+    net.free()

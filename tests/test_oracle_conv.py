@@ -375,3 +375,27 @@ def test_depthwise_channels_do_not_mix_and_fp16_rounds_once():
     y16 = oracle.depthwise_conv2d(x16, w16, None, 1, 1, True, dtype=np.float16)
     assert y16.dtype == np.float16
     assert np.array_equal(y16, oracle.depthwise_conv2d_f64(x16, w16, None, 1, 1, True).astype(np.float16))
+
+
+# ---------------------------------------------------------------------------
+# Rectangular filters carried in square banks (Inception-V3's 1x7 / 7x1 layers)
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("kh,kw", [(1, 7), (7, 1), (1, 3), (3, 5)])
+def test_rectangular_filter_centred_in_a_square_one(kh, kw):
+    """A kh x kw filter with padding ((kh-1)/2, (kw-1)/2) equals the same filter centred in a
+    zero k x k one with padding (k-1)/2: checked against torch's float64 convolution with
+    rectangular padding, which never sees the square form."""
+    torch = pytest.importorskip("torch")
+    import workloads as wl
+    k = max(kh, kw)
+    x = rnd((2, 5, 11, 13), 200 + kh)
+    w = rnd((6, 5, kh, kw), 201 + kw, sparsity=0.4)
+    b = rnd((6,), 202)
+    for stride in (1, 2):
+        want = torch.nn.functional.conv2d(torch.from_numpy(x).double(), torch.from_numpy(w).double(),
+                                          torch.from_numpy(b).double(), stride=stride,
+                                          padding=((kh - 1) // 2, (kw - 1) // 2))
+        got = oracle.conv2d_f64(x, wl.embed_filter(w, k), b, None, stride, (k - 1) // 2, False)
+        np.testing.assert_allclose(got, want.numpy(), rtol=1e-12, atol=1e-12)
+    assert np.count_nonzero(wl.embed_filter(w, k)) == np.count_nonzero(w)

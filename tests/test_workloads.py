@@ -141,3 +141,23 @@ def test_mobilenet_v2_table():
         if o.res >= 0:
             blk = o.name.split("_")[0]
             assert all(p.dst != o.res for p in ops[:i + 1] if p.name.startswith(blk + "_"))
+
+
+def test_embed_filter_and_factorized_branch_table():
+    w = wl.pruned_weights(4, 3, 1, 7, 0.5, "emb", 1)
+    e = wl.embed_filter(w, 7)
+    assert e.shape == (4, 3, 7, 7) and np.array_equal(e[:, :, 3, :], w[:, :, 0, :])
+    assert np.count_nonzero(e) == np.count_nonzero(w)
+    e[:, :, 3, :] = 0
+    assert not e.any()
+    with np.testing.assert_raises(ValueError):
+        wl.embed_filter(wl.pruned_weights(2, 2, 2, 7, 0.0, "emb", 2), 7)      # even height cannot be centred
+    ops = wl.factorized_7x7_branch_ops()
+    assert [(o.kh, o.kw) for o in ops] == [(0, 0), (7, 1), (1, 7), (7, 1), (1, 7)]
+    x, ws, bs = wl.net_tensors(ops, "embt", (1, 768, 17, 17))
+    for o, wt in zip(ops[1:], ws[1:]):
+        assert wt.shape == (o.cout, o.cin, 7, 7)
+        rows = np.abs(wt).sum(axis=(0, 1, 3)) > 0
+        cols = np.abs(wt).sum(axis=(0, 1, 2)) > 0
+        assert rows.sum() == o.kh and cols.sum() == o.kw      # nonzeros only on the centred kh x kw taps
+    assert wl.buffer_shapes(ops, (1, 768, 17, 17))[ops[-1].dst] == (1, 192, 17, 17)

@@ -13,6 +13,7 @@ from .gen import (  # noqa: F401
     pruned_weights,
     keep_count,
     conv_out_size,
+    embed_filter,
 )
 from .nets import (  # noqa: F401
     Op,
@@ -20,6 +21,7 @@ from .nets import (  # noqa: F401
     vgg16_ops,
     mobilenet_v1_ops,
     mobilenet_v2_ops,
+    factorized_7x7_branch_ops,
     bottleneck_conv2x_ops,
     single_conv_ops,
     net_tensors,

@@ -90,3 +90,17 @@ def pruned_weights(cout: int, cin: int, kh: int, kw: int, sparsity: float, confi
             raise ValueError(mask)
     out = np.where(keep, flat, np.float32(0.0)).astype(np.float32)
     return np.ascontiguousarray(out.reshape(cout, cin, kh, kw))
+
+
+def embed_filter(w: np.ndarray, k: int) -> np.ndarray:
+    """Centres a [cout][cin][kh][kw] filter bank (kh, kw odd, <= k) in a zero [cout][cin][k][k]
+    one.  With padding (k-1)/2 the square bank computes what the rectangular one computes with
+    padding ((kh-1)/2, (kw-1)/2): the added taps are exact zeros, which a compact format does
+    not store.  This is how 1x7 / 7x1 filters are handed to an interface with one padding."""
+    cout, cin, kh, kw = w.shape
+    if kh > k or kw > k or (k - kh) % 2 or (k - kw) % 2:
+        raise ValueError("cannot centre a %dx%d filter in %dx%d" % (kh, kw, k, k))
+    out = np.zeros((cout, cin, k, k), dtype=w.dtype)
+    r0, c0 = (k - kh) // 2, (k - kw) // 2
+    out[:, :, r0:r0 + kh, c0:c0 + kw] = w
+    return np.ascontiguousarray(out)

@@ -18,7 +18,7 @@ from typing import Dict, List, Sequence, Tuple
 
 import numpy as np
 
-from .gen import activation, bias_vector, conv_out_size, pruned_weights
+from .gen import activation, bias_vector, conv_out_size, embed_filter, pruned_weights
 
 
 @dataclass(frozen=True)
@@ -35,6 +35,8 @@ class Op:
     sparsity: float = 0.0
     relu: bool = False
     res: int = -1          # buffer added before the activation, -1 = none
+    kh: int = 0            # rectangular filter kh x kw centred in the k x k one (0 = square k x k)
+    kw: int = 0
 
 
 def single_conv_ops(cin=64, cout=64, k=3, stride=1, pad=1, sparsity=0.9, relu=True) -> List[Op]:
@@ -159,6 +161,21 @@ def mobilenet_v2_ops(s_conv1: float = 0.0, s_dw: float = 0.0, s_pw: float = 0.8,
     return ops
 
 
+def factorized_7x7_branch_ops(cin: int = 768, mid: int = 128, cout: int = 192, sparsity: float = 0.8) -> List[Op]:
+    """The deepest branch of an Inception-V3 17x17 module (the paper's Table 2 names the model):
+    1x1, then 7x1, 1x7, 7x1, 1x7 filters with "same" padding (the published factorisation of a
+    7x7 convolution).  The rectangular filters are carried centred in 7x7 banks with padding 3."""
+    ops = [Op("conv", "b_1x1", 0, 1, cin, mid, 1, 1, 0, sparsity, True)]
+    shapes = [(7, 1), (1, 7), (7, 1), (1, 7)]
+    cur, c = 1, mid
+    for i, (kh, kw) in enumerate(shapes):
+        co = cout if i == len(shapes) - 1 else mid
+        nxt = 2 if cur == 1 else 1
+        ops.append(Op("conv", "b_%dx%d_%d" % (kh, kw, i + 1), cur, nxt, c, co, 7, 1, 3, sparsity, True, kh=kh, kw=kw))
+        cur, c = nxt, co
+    return ops
+
+
 def buffer_shapes(ops: Sequence[Op], input_shape: Tuple[int, int, int, int]) -> Dict[int, Tuple[int, ...]]:
     """Largest shape each buffer id takes, by walking the op list (shape inference only)."""
     cur: Dict[int, Tuple[int, ...]] = {0: tuple(input_shape)}
@@ -203,7 +220,11 @@ def net_tensors(ops: Sequence[Op], config: str, input_shape, input_relu: bool = 
     x = activation(input_shape, config, 0, relu=input_relu)
     weights, biases = [], []
     for i, op in enumerate(ops):
-        if op.kind == "conv":
+        if op.kind == "conv" and (op.kh or op.kw):
+            w = pruned_weights(op.cout, op.cin, op.kh or op.k, op.kw or op.k, op.sparsity, config, i + 1, mask)
+            weights.append(embed_filter(w, op.k))
+            biases.append(bias_vector(op.cout, config, i + 1))
+        elif op.kind == "conv":
             weights.append(pruned_weights(op.cout, op.cin, op.k, op.k, op.sparsity, config, i + 1, mask))
             biases.append(bias_vector(op.cout, config, i + 1))
         elif op.kind == "dwconv":
