@@ -58,6 +58,8 @@ def _load():
         lib.oracle_fc.restype = i
         lib.oracle_maxpool.argtypes = [fp, dp] + [i] * 7
         lib.oracle_maxpool.restype = i
+        lib.oracle_avgpool.argtypes = [fp, dp] + [i] * 7
+        lib.oracle_avgpool.restype = i
         lib.oracle_global_avgpool.argtypes = [fp, dp] + [i] * 4
         lib.oracle_global_avgpool.restype = i
         lib.oracle_num_threads.argtypes = []
@@ -180,6 +182,19 @@ def maxpool(x, k, stride, pad, dtype=None):
     return y.astype(dtype or np.asarray(x).dtype)
 
 
+def avgpool(x, k, stride, pad, dtype=None):
+    """Mean over the in-image part of each k x k window (padding neither summed nor counted)."""
+    xf = _f32(x)
+    n, c, h, wd = xf.shape
+    hout, wout = out_size(h, k, stride, pad), out_size(wd, k, stride, pad)
+    y = np.empty((n, c, hout, wout), dtype=np.float64)
+    rc = _load().oracle_avgpool(_ptr(xf, ctypes.c_float), _ptr(y, ctypes.c_double), n, c, h, wd,
+                                k, stride, pad)
+    if rc != 0:
+        raise RuntimeError("oracle_avgpool failed")
+    return y.astype(dtype or np.asarray(x).dtype)
+
+
 def global_avgpool(x, dtype=None):
     xf = _f32(x)
     n, c, h, wd = xf.shape
@@ -263,6 +278,10 @@ def run_net(ops: Sequence, x, weights: Sequence, biases: Sequence, dtype=np.floa
             y = maxpool(src, op.k, op.stride, op.pad, dtype)
         elif op.kind == "avgpool":
             y = global_avgpool(src, dtype)
+        elif op.kind == "avgpool2d":
+            y = avgpool(src, op.k, op.stride, op.pad, dtype)
+        elif op.kind == "concat":
+            y = np.concatenate([bufs[b] for b in op.srcs], axis=1)
         else:
             raise ValueError(op.kind)
         ins.append(src)

@@ -195,6 +195,36 @@ int oracle_maxpool(const float* x, double* y, int n, int c, int h, int wd, int k
     return 0;
 }
 
+/* Windowed average pooling (the 3x3 / stride 1 / padding 1 pools inside Inception-V3's
+ * modules): the mean over the in-image part of each k x k window, i.e. padding is neither
+ * summed nor counted.  A window with no in-image element gives 0. */
+int oracle_avgpool(const float* x, double* y, int n, int c, int h, int wd, int k, int stride,
+                   int pad) {
+    if (!x || !y || n <= 0 || c <= 0 || h <= 0 || wd <= 0 || k <= 0 || stride <= 0 || pad < 0)
+        return -1;
+    const int hout = out_size(h, k, stride, pad), wout = out_size(wd, k, stride, pad);
+    if (hout <= 0 || wout <= 0) return -1;
+#pragma omp parallel for schedule(static)
+    for (long nc = 0; nc < (long)n * c; ++nc) {
+        const float* xp = x + nc * h * wd;
+        double* yp = y + nc * hout * wout;
+        for (int oh = 0; oh < hout; ++oh)
+            for (int ow = 0; ow < wout; ++ow) {
+                int count = 0;
+                double sum = 0.0;
+                for (int r = 0; r < k; ++r)
+                    for (int q = 0; q < k; ++q) {
+                        const int ih = oh * stride + r - pad, iw = ow * stride + q - pad;
+                        if (ih < 0 || ih >= h || iw < 0 || iw >= wd) continue;
+                        sum += (double)xp[(long)ih * wd + iw];
+                        ++count;
+                    }
+                yp[(long)oh * wout + ow] = count ? sum / (double)count : 0.0;
+            }
+    }
+    return 0;
+}
+
 /* Global average pool: y[n][c] = mean over h*w. */
 int oracle_global_avgpool(const float* x, double* y, int n, int c, int h, int wd) {
     if (!x || !y || n <= 0 || c <= 0 || h <= 0 || wd <= 0) return -1;

@@ -399,3 +399,40 @@ def test_rectangular_filter_centred_in_a_square_one(kh, kw):
         got = oracle.conv2d_f64(x, wl.embed_filter(w, k), b, None, stride, (k - 1) // 2, False)
         np.testing.assert_allclose(got, want.numpy(), rtol=1e-12, atol=1e-12)
     assert np.count_nonzero(wl.embed_filter(w, k)) == np.count_nonzero(w)
+
+
+# ---------------------------------------------------------------------------
+# Windowed average pool and channel concatenation (Inception-V3 modules)
+# ---------------------------------------------------------------------------
+
+def test_avgpool_window_mean_excludes_padding():
+    torch = pytest.importorskip("torch")
+    x = rnd((2, 3, 9, 11), 300)
+    for k, s, p in [(3, 1, 1), (3, 2, 1), (2, 2, 0), (5, 1, 2)]:
+        want = torch.nn.functional.avg_pool2d(torch.from_numpy(x).double(), k, s, p, count_include_pad=False)
+        got = oracle.avgpool(x, k, s, p, dtype=np.float64)
+        np.testing.assert_allclose(got, want.numpy(), rtol=1e-13, atol=1e-13)
+    # brute force on a tiny case
+    k, s, p = 3, 1, 1
+    got = oracle.avgpool(x[:1, :1], k, s, p, dtype=np.float64)[0, 0]
+    for oh in range(9):
+        for ow in range(11):
+            vals = [float(x[0, 0, i, j]) for i in range(oh - 1, oh + 2) for j in range(ow - 1, ow + 2)
+                    if 0 <= i < 9 and 0 <= j < 11]
+            assert abs(got[oh, ow] - sum(vals) / len(vals)) < 1e-12
+    # a constant image stays constant (the border is not dimmed by the padding)
+    c = np.full((1, 2, 6, 5), 2.5, np.float32)
+    assert np.array_equal(oracle.avgpool(c, 3, 1, 1, dtype=np.float64), np.full((1, 2, 6, 5), 2.5))
+
+
+def test_run_net_concat_stacks_channels_in_order():
+    from workloads import Op
+    ops = [Op("maxpool", "a", 0, 1, k=3, stride=1, pad=1),
+           Op("avgpool2d", "b", 0, 2, k=3, stride=1, pad=1),
+           Op("concat", "cat", 1, 3, srcs=(1, 0, 2))]
+    x = rnd((2, 3, 5, 6), 301)
+    y, ins, outs = oracle.run_net(ops, x, [None] * 3, [None] * 3)
+    assert y.shape == (2, 9, 5, 6)
+    assert np.array_equal(y[:, 0:3], oracle.maxpool(x, 3, 1, 1))
+    assert np.array_equal(y[:, 3:6], x)
+    assert np.array_equal(y[:, 6:9], oracle.avgpool(x, 3, 1, 1))

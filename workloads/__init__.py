@@ -22,6 +22,7 @@ from .nets import (  # noqa: F401
     mobilenet_v1_ops,
     mobilenet_v2_ops,
     factorized_7x7_branch_ops,
+    inception_v3_ops,
     bottleneck_conv2x_ops,
     single_conv_ops,
     net_tensors,

@@ -23,7 +23,8 @@ from .gen import activation, bias_vector, conv_out_size, embed_filter, pruned_we
 
 @dataclass(frozen=True)
 class Op:
-    kind: str              # "conv" | "dwconv" (depthwise; cin == cout) | "fc" | "maxpool" | "avgpool"
+    kind: str              # "conv" | "dwconv" (depthwise; cin == cout) | "fc" | "maxpool" | "avgpool" (global)
+                           # | "avgpool2d" (k x k windows) | "concat"
     name: str
     src: int
     dst: int
@@ -37,6 +38,7 @@ class Op:
     res: int = -1          # buffer added before the activation, -1 = none
     kh: int = 0            # rectangular filter kh x kw centred in the k x k one (0 = square k x k)
     kw: int = 0
+    srcs: Tuple[int, ...] = ()   # "concat": the buffers stacked along the channel axis, in order
 
 
 def single_conv_ops(cin=64, cout=64, k=3, stride=1, pad=1, sparsity=0.9, relu=True) -> List[Op]:
@@ -176,6 +178,102 @@ def factorized_7x7_branch_ops(cin: int = 768, mid: int = 128, cout: int = 192, s
     return ops
 
 
+def inception_v3_ops(s_conv1: float = 0.0, s_conv: float = 0.8, s_fc: float = 0.9) -> List[Op]:
+    """Inception-V3 at 299x299 input (named in the paper's Table 2; the published module
+    ladder without the auxiliary head): a stem of five convolutions and two max pools, three
+    35x35 modules (1x1 / 5x5 / double 3x3 / pooled 1x1 branches), a grid reduction, four 17x17
+    modules whose 7x7 convolutions are factorised into 1x7 and 7x1 ones, a second reduction,
+    two 8x8 modules with 1x3 / 3x1 splits, global average pool, FC 2048->1000: 94
+    convolutions.  Every branch output is stacked along the channel axis by a "concat" op;
+    rectangular filters are carried centred in square banks (see `embed_filter`).  Each
+    convolution stands for convolution + folded batch-norm + ReLU."""
+    ops: List[Op] = []
+    fresh = iter(range(1, 10000))
+
+    def conv(name, src, cin, cout, k=1, stride=1, pad=0, kh=0, kw=0, first=False):
+        dst = next(fresh)
+        ops.append(Op("conv", name, src, dst, cin, cout, k, stride, pad, s_conv1 if first else s_conv, True,
+                      kh=kh, kw=kw))
+        return dst
+
+    def pool(kind, name, src, k, stride, pad):
+        dst = next(fresh)
+        ops.append(Op(kind, name, src, dst, k=k, stride=stride, pad=pad))
+        return dst
+
+    def cat(name, parts):
+        dst = next(fresh)
+        ops.append(Op("concat", name, parts[0], dst, srcs=tuple(parts)))
+        return dst
+
+    x = conv("stem1", 0, 3, 32, 3, 2, 0, first=True)
+    x = conv("stem2", x, 32, 32, 3, 1, 0)
+    x = conv("stem3", x, 32, 64, 3, 1, 1)
+    x = pool("maxpool", "stem_pool1", x, 3, 2, 0)
+    x = conv("stem4", x, 64, 80, 1)
+    x = conv("stem5", x, 80, 192, 3, 1, 0)
+    x = pool("maxpool", "stem_pool2", x, 3, 2, 0)
+    c = 192
+    for i, pf in enumerate([32, 64, 64]):                      # 35 x 35 modules
+        t = "a%d_" % (i + 1)
+        b1 = conv(t + "1x1", x, c, 64)
+        b5 = conv(t + "5x5b", conv(t + "5x5a", x, c, 48), 48, 64, 5, 1, 2)
+        b3 = conv(t + "3x3a", x, c, 64)
+        b3 = conv(t + "3x3b", b3, 64, 96, 3, 1, 1)
+        b3 = conv(t + "3x3c", b3, 96, 96, 3, 1, 1)
+        bp = conv(t + "pool1x1", pool("avgpool2d", t + "pool", x, 3, 1, 1), c, pf)
+        x = cat(t + "cat", [b1, b5, b3, bp])
+        c = 64 + 64 + 96 + pf
+    t = "b_"                                                    # 35 -> 17 reduction
+    b3 = conv(t + "3x3", x, c, 384, 3, 2, 0)
+    bd = conv(t + "dbl_a", x, c, 64)
+    bd = conv(t + "dbl_b", bd, 64, 96, 3, 1, 1)
+    bd = conv(t + "dbl_c", bd, 96, 96, 3, 2, 0)
+    bp = pool("maxpool", t + "pool", x, 3, 2, 0)
+    x = cat(t + "cat", [b3, bd, bp])
+    c = 384 + 96 + c
+    for i, c7 in enumerate([128, 160, 160, 192]):               # 17 x 17 modules
+        t = "c%d_" % (i + 1)
+        b1 = conv(t + "1x1", x, c, 192)
+        b7 = conv(t + "7a", x, c, c7)
+        b7 = conv(t + "7b", b7, c7, c7, 7, 1, 3, kh=1, kw=7)
+        b7 = conv(t + "7c", b7, c7, 192, 7, 1, 3, kh=7, kw=1)
+        bd = conv(t + "dbl_a", x, c, c7)
+        bd = conv(t + "dbl_b", bd, c7, c7, 7, 1, 3, kh=7, kw=1)
+        bd = conv(t + "dbl_c", bd, c7, c7, 7, 1, 3, kh=1, kw=7)
+        bd = conv(t + "dbl_d", bd, c7, c7, 7, 1, 3, kh=7, kw=1)
+        bd = conv(t + "dbl_e", bd, c7, 192, 7, 1, 3, kh=1, kw=7)
+        bp = conv(t + "pool1x1", pool("avgpool2d", t + "pool", x, 3, 1, 1), c, 192)
+        x = cat(t + "cat", [b1, b7, bd, bp])
+        c = 768
+    t = "d_"                                                    # 17 -> 8 reduction
+    b3 = conv(t + "3x3b", conv(t + "3x3a", x, c, 192), 192, 320, 3, 2, 0)
+    b7 = conv(t + "7a", x, c, 192)
+    b7 = conv(t + "7b", b7, 192, 192, 7, 1, 3, kh=1, kw=7)
+    b7 = conv(t + "7c", b7, 192, 192, 7, 1, 3, kh=7, kw=1)
+    b7 = conv(t + "7d", b7, 192, 192, 3, 2, 0)
+    bp = pool("maxpool", t + "pool", x, 3, 2, 0)
+    x = cat(t + "cat", [b3, b7, bp])
+    c = 320 + 192 + c
+    for i in range(2):                                          # 8 x 8 modules
+        t = "e%d_" % (i + 1)
+        b1 = conv(t + "1x1", x, c, 320)
+        b3 = conv(t + "3a", x, c, 384)
+        b3a = conv(t + "3b", b3, 384, 384, 3, 1, 1, kh=1, kw=3)
+        b3b = conv(t + "3c", b3, 384, 384, 3, 1, 1, kh=3, kw=1)
+        bd = conv(t + "dbl_a", x, c, 448)
+        bd = conv(t + "dbl_b", bd, 448, 384, 3, 1, 1)
+        bda = conv(t + "dbl_c", bd, 384, 384, 3, 1, 1, kh=1, kw=3)
+        bdb = conv(t + "dbl_d", bd, 384, 384, 3, 1, 1, kh=3, kw=1)
+        bp = conv(t + "pool1x1", pool("avgpool2d", t + "pool", x, 3, 1, 1), c, 192)
+        x = cat(t + "cat", [b1, b3a, b3b, bda, bdb, bp])
+        c = 320 + 768 + 768 + 192
+    g = next(fresh)
+    ops.append(Op("avgpool", "gap", x, g))
+    ops.append(Op("fc", "fc", g, next(fresh), 2048, 1000, sparsity=s_fc, relu=False))
+    return ops
+
+
 def buffer_shapes(ops: Sequence[Op], input_shape: Tuple[int, int, int, int]) -> Dict[int, Tuple[int, ...]]:
     """Largest shape each buffer id takes, by walking the op list (shape inference only)."""
     cur: Dict[int, Tuple[int, ...]] = {0: tuple(input_shape)}
@@ -196,6 +294,14 @@ def buffer_shapes(ops: Sequence[Op], input_shape: Tuple[int, int, int, int]) -> 
             n, c, h, w = s
             o = (n, c, conv_out_size(h, op.k, op.stride, op.pad),
                  conv_out_size(w, op.k, op.stride, op.pad))
+        elif op.kind == "avgpool2d":
+            n, c, h, w = s
+            o = (n, c, conv_out_size(h, op.k, op.stride, op.pad),
+                 conv_out_size(w, op.k, op.stride, op.pad))
+        elif op.kind == "concat":
+            parts = [cur[b] for b in op.srcs]
+            assert all(p[0] == parts[0][0] and p[2:] == parts[0][2:] for p in parts), (op, parts)
+            o = (parts[0][0], sum(p[1] for p in parts), parts[0][2], parts[0][3])
         elif op.kind == "avgpool":
             n, c, h, w = s
             o = (n, c, 1, 1)
