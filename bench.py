@@ -52,11 +52,16 @@ def layer_costs(ops, weights, in_shape, elem):
             out = (n, op.cout, 1, 1)
             flops = 2.0 * nnz * n
             byts = (n * c * h * w + n * op.cout) * elem + nnz * (elem + 2) + (op.cout + 1) * 4 + op.cout * 8
-        elif op.kind == "maxpool":
+        elif op.kind in ("maxpool", "avgpool2d"):
             ho, wo = conv_out_size(h, op.k, op.stride, op.pad), conv_out_size(w, op.k, op.stride, op.pad)
             out = (n, c, ho, wo)
             nnz, flops = 0, 0.0
             byts = (n * c * h * w + n * c * ho * wo) * elem
+        elif op.kind == "concat":
+            # its sources are written in place by their producers: nothing moves
+            c = sum(cur[b][1] for b in op.srcs)
+            out = (n, c, h, w)
+            nnz, flops, byts = 0, 0.0, 0.0
         else:
             out = (n, c, 1, 1)
             nnz, flops = 0, float(n * c * h * w)
@@ -69,8 +74,9 @@ def layer_costs(ops, weights, in_shape, elem):
 
 KERNEL_OF_PREFIX = {"slinear": "sconv_linear_kernel", "stile": "sconv_stile_kernel",
                     "sdirect": "sconv_direct_kernel", "sconv": "sconv_tile_kernel",
-                    "dense": "dense_conv_kernel", "sfc": "sfc_kernel", "dwconv": "dwconv_kernel", "maxpool": "maxpool_kernel",
-                    "avgpool": "avgpool_kernel", "fused": "(computed inside another op)"}
+                    "dense": "dense_conv_kernel", "sfc": "sfc_kernel", "dwconv": "dwconv_kernel", "maxpool": "windowpool_kernel",
+                    "avgpool": "avgpool_kernel", "avgpool2d": "windowpool_kernel", "concat": "windowpool_kernel",
+                    "fused": "(computed inside another op)", "in place": "(written by its producers)"}
 
 
 def kernel_of(variant: str) -> str:
@@ -97,11 +103,12 @@ def main() -> int:
                          "(written by paper_1905_00571_amd/profile_summary.py)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a 256 MiB device copy 10 times (known traffic, for counter calibration)")
-    ap.add_argument("--workload", choices=["c2", "c3", "c4", "mobilenet", "mobilenet2"], default="c2",
+    ap.add_argument("--workload", choices=["c2", "c3", "c4", "mobilenet", "mobilenet2", "inception"], default="c2",
                     help="c2 (default, the metric's workload): ResNet-50 fp32, conv1 dense / 3x3 80 %% / 1x1+FC 90 %%; "
                          "c3: ResNet-50 with uniform --sparsity in --dtype at --batch; c4: VGG-16 conv 90 %% / FC 96 %%; "
                          "mobilenet / mobilenet2: MobileNet-V1 / -V2, dense first layer and depthwise filters, "
-                         "pointwise 80 %% / FC 90 %%")
+                         "pointwise 80 %% / FC 90 %%; inception: Inception-V3 at 299x299, first layer dense, "
+                         "other convolutions 80 %% / FC 90 %%")
     ap.add_argument("--batch", type=int, default=1)
     ap.add_argument("--sparsity", type=float, default=0.8, help="uniform sparsity of workload c3")
     ap.add_argument("--dtype", choices=["f32", "f16"], default="", help="storage type (default f32; c3: f16)")
@@ -143,6 +150,11 @@ def main() -> int:
         ops, tag = wl.mobilenet_v1_ops(), "mbv1"
         desc = "mobilenet-v1-sparse %s batch %d: conv1 and 13 depthwise 3x3 dense, 13 pointwise 80 %%, FC 90 %% " \
                "unstructured sparsity" % (dt, n)
+    elif args.workload == "inception":
+        shape = (n, 3, 299, 299)
+        ops, tag = wl.inception_v3_ops(), "iv3"
+        desc = "inception-v3-sparse %s batch %d: first layer dense, 93 convolutions 80 %%, FC 90 %% unstructured " \
+               "sparsity, %dx3x299x299 input" % (dt, n, n)
     elif args.workload == "mobilenet2":
         ops, tag = wl.mobilenet_v2_ops(), "mbv2"
         desc = "mobilenet-v2-sparse %s batch %d: conv1 and 17 depthwise 3x3 dense, 34 pointwise 80 %%, FC 90 %% " \

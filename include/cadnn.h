@@ -158,8 +158,13 @@ cadnn_status cadnn_depthwise_prepare(const cadnn_weights* w);
 
 /* Pooling layers used between the convolutions of the benchmark networks.
  * Max pooling takes the maximum over the in-image part of each k x k window
- * (padding never wins); global average pooling writes y[n][c] = mean over h*w. */
+ * (padding never wins); windowed average pooling takes the mean over the in-image
+ * part of each window (padding is neither summed nor counted; the 3x3 / stride 1
+ * pools inside Inception-V3's modules); global average pooling writes
+ * y[n][c] = mean over h*w. */
 cadnn_status cadnn_maxpool2d(const void* x, void* y, int n, int c, int h, int wdt, int k,
+                             int stride, int pad, cadnn_dtype dtype, void* stream);
+cadnn_status cadnn_avgpool2d(const void* x, void* y, int n, int c, int h, int wdt, int k,
                              int stride, int pad, cadnn_dtype dtype, void* stream);
 cadnn_status cadnn_global_avgpool(const void* x, void* y, int n, int c, int h, int wdt,
                                   cadnn_dtype dtype, void* stream);
@@ -204,7 +209,15 @@ cadnn_status cadnn_net_add_depthwise(cadnn_net* net, const cadnn_weights* w, con
                                      int stride, int pad, int relu, int src_buf, int dst_buf);
 cadnn_status cadnn_net_add_maxpool(cadnn_net* net, int k, int stride, int pad, int src_buf,
                                    int dst_buf);
+cadnn_status cadnn_net_add_avgpool(cadnn_net* net, int k, int stride, int pad, int src_buf,
+                                   int dst_buf);
 cadnn_status cadnn_net_add_global_avgpool(cadnn_net* net, int src_buf, int dst_buf);
+/* Channel concatenation (the branches of an Inception module): dst_buf holds the `count`
+ * source buffers stacked along the channel axis in the given order; they must agree in batch,
+ * height and width.  A source whose only reader is this op is written in place, into its
+ * channel slice of dst_buf, by the op that produces it (no copy is launched for it); any
+ * other source is copied. */
+cadnn_status cadnn_net_add_concat(cadnn_net* net, const int* src_bufs, int count, int dst_buf);
 cadnn_status cadnn_net_add_fc(cadnn_net* net, const cadnn_weights* w, const void* bias_dev,
                               int relu, int src_buf, int dst_buf);
 cadnn_status cadnn_net_workspace_bytes(const cadnn_net* net, size_t* bytes);
@@ -235,8 +248,9 @@ cadnn_status cadnn_run_net(cadnn_net* net, const void* x, void* y, void* stream)
 cadnn_status cadnn_net_num_ops(const cadnn_net* net, int* num_ops);
 cadnn_status cadnn_net_profile(cadnn_net* net, const void* x, void* y, void* stream, int repeats,
                                float* ms_per_op);
-/* Name of the kernel serving op `op_index` (a conv variant name, "dwconv", "sfc", "maxpool"
- * or "avgpool"), NUL-terminated into buf. */
+/* Name of the kernel serving op `op_index` (a conv variant name, "dwconv", "sfc", "maxpool",
+ * "avgpool2d", "avgpool", "concat", or "fused" / "in place" for an op that launches nothing),
+ * NUL-terminated into buf. */
 cadnn_status cadnn_net_op_variant(const cadnn_net* net, int op_index, char* buf, size_t len);
 /* Newline-separated names of the variants that can serve convolution op `op_index` in
  * the layout the net gave its input (a halo opens the linear-address kernels to 3x3). */

@@ -30,6 +30,7 @@ from .binding import (  # noqa: F401
     cadnn_depthwise_prepare,
     cadnn_device_copy,
     cadnn_maxpool2d,
+    cadnn_avgpool2d,
     cadnn_global_avgpool,
     cadnn_dense_conv2d,
     cadnn_run_net,

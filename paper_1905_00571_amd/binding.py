@@ -66,6 +66,7 @@ def lib() -> ctypes.CDLL:
         "cadnn_depthwise_prepare": (_i, [_vp]),
         "cadnn_device_copy": (_i, [_vp, _vp, ctypes.c_size_t, _vp]),
         "cadnn_maxpool2d": (_i, [_vp, _vp, _i, _i, _i, _i, _i, _i, _i, _i, _vp]),
+        "cadnn_avgpool2d": (_i, [_vp, _vp, _i, _i, _i, _i, _i, _i, _i, _i, _vp]),
         "cadnn_global_avgpool": (_i, [_vp, _vp, _i, _i, _i, _i, _i, _vp]),
         "cadnn_dense_conv2d": (_i, [_vp, _vp, _vp] + [_i] * 9 + [_vp, _vp, _i, _i, _vp]),
         "cadnn_net_create": (_i, [_i, _i, _i, _i, _i, ctypes.POINTER(_vp)]),
@@ -73,6 +74,8 @@ def lib() -> ctypes.CDLL:
         "cadnn_net_add_depthwise": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i]),
         "cadnn_net_add_maxpool": (_i, [_vp, _i, _i, _i, _i, _i]),
         "cadnn_net_add_global_avgpool": (_i, [_vp, _i, _i]),
+        "cadnn_net_add_avgpool": (_i, [_vp, _i, _i, _i, _i, _i]),
+        "cadnn_net_add_concat": (_i, [_vp, ctypes.POINTER(_i), _i, _i]),
         "cadnn_net_add_fc": (_i, [_vp, _vp, _vp, _i, _i, _i]),
         "cadnn_net_workspace_bytes": (_i, [_vp, ctypes.POINTER(ctypes.c_size_t)]),
         "cadnn_net_finalize": (_i, [_vp, _vp, ctypes.c_size_t, _i]),
@@ -291,6 +294,17 @@ def cadnn_maxpool2d(x, k: int, stride: int, pad: int, stream=None):
     return out
 
 
+def cadnn_avgpool2d(x, k: int, stride: int, pad: int, stream=None):
+    import torch
+    assert x.is_cuda and x.is_contiguous()
+    dtype = F16 if x.dtype == torch.float16 else F32
+    n, c, h, wdt = x.shape
+    out = torch.empty((n, c, _out_size(h, k, stride, pad), _out_size(wdt, k, stride, pad)),
+                      dtype=x.dtype, device=x.device)
+    _check(lib().cadnn_avgpool2d(_dptr(x), _dptr(out), n, c, h, wdt, k, stride, pad, dtype, _stream_ptr(stream)))
+    return out
+
+
 def cadnn_global_avgpool(x, stream=None):
     import torch
     assert x.is_cuda and x.is_contiguous()
@@ -401,7 +415,7 @@ def build_net(ops: Sequence, weights: Sequence, biases: Sequence, input_shape, d
               plain_layout: bool = False, fuse: bool = True) -> Net:
     """Packs every layer's weights and wires the op list into a cadnn_net.
 
-    `ops` are records with .kind in {"conv", "dwconv", "fc", "maxpool", "avgpool"} and
+    `ops` are records with .kind in {"conv", "dwconv", "fc", "maxpool", "avgpool2d", "avgpool", "concat"} and
     .src/.dst/.res/.k/.stride/.pad/.relu fields (see workloads.nets.Op).
     """
     import torch
@@ -439,6 +453,16 @@ def build_net(ops: Sequence, weights: Sequence, biases: Sequence, input_shape, d
                 s = shapes[op.src]
                 shapes[op.dst] = (s[0], s[1], _out_size(s[2], op.k, op.stride, op.pad),
                                   _out_size(s[3], op.k, op.stride, op.pad))
+            elif op.kind == "avgpool2d":
+                _check(L.cadnn_net_add_avgpool(handle, op.k, op.stride, op.pad, op.src, op.dst))
+                s = shapes[op.src]
+                shapes[op.dst] = (s[0], s[1], _out_size(s[2], op.k, op.stride, op.pad),
+                                  _out_size(s[3], op.k, op.stride, op.pad))
+            elif op.kind == "concat":
+                arr = (ctypes.c_int * len(op.srcs))(*op.srcs)
+                _check(L.cadnn_net_add_concat(handle, arr, len(op.srcs), op.dst))
+                s = shapes[op.srcs[0]]
+                shapes[op.dst] = (s[0], sum(shapes[b][1] for b in op.srcs), s[2], s[3])
             elif op.kind == "avgpool":
                 _check(L.cadnn_net_add_global_avgpool(handle, op.src, op.dst))
                 s = shapes[op.src]

@@ -530,6 +530,19 @@ extern "C" cadnn_status cadnn_maxpool2d(const void* x, void* y, int n, int c, in
                           pad, dtype, (hipStream_t)stream);
 }
 
+extern "C" cadnn_status cadnn_avgpool2d(const void* x, void* y, int n, int c, int h, int wdt, int k,
+                                        int stride, int pad, cadnn_dtype dtype, void* stream) {
+    if (!x || !y) return fail(CADNN_EINVAL, "cadnn_avgpool2d: NULL tensor");
+    if (n <= 0 || c <= 0 || h <= 0 || wdt <= 0 || k <= 0 || stride <= 0 || pad < 0)
+        return fail(CADNN_EINVAL, "cadnn_avgpool2d: bad size");
+    if (dtype != CADNN_F32 && dtype != CADNN_F16) return fail(CADNN_EINVAL, "cadnn_avgpool2d: dtype");
+    if (conv_out(h, k, stride, pad) <= 0 || conv_out(wdt, k, stride, pad) <= 0)
+        return fail(CADNN_EINVAL, "cadnn_avgpool2d: empty output");
+    return launch_avgpool2d(x, make_desc(c, h, wdt), y,
+                            make_desc(c, conv_out(h, k, stride, pad), conv_out(wdt, k, stride, pad)), n, k, stride,
+                            pad, dtype, (hipStream_t)stream);
+}
+
 extern "C" cadnn_status cadnn_global_avgpool(const void* x, void* y, int n, int c, int h, int wdt,
                                              cadnn_dtype dtype, void* stream) {
     if (!x || !y) return fail(CADNN_EINVAL, "cadnn_global_avgpool: NULL tensor");

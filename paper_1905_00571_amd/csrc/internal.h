@@ -325,6 +325,8 @@ cadnn_status launch_depthwise(const cadnn_weights* w, const void* x, const Tenso
                               hipStream_t s);
 cadnn_status launch_maxpool(const void* x, const TensorDesc& xd, void* y, const TensorDesc& yd, int n,
                             int k, int stride, int pad, cadnn_dtype dt, hipStream_t s);
+cadnn_status launch_avgpool2d(const void* x, const TensorDesc& xd, void* y, const TensorDesc& yd, int n,
+                              int k, int stride, int pad, cadnn_dtype dt, hipStream_t s);
 cadnn_status launch_avgpool(const void* x, const TensorDesc& xd, void* y, int n, cadnn_dtype dt,
                             hipStream_t s);
 

@@ -223,10 +223,14 @@ cadnn_status launch_fc(const cadnn_weights* w, const void* x, void* y, int n, co
                                  : launch_fc_t<float>(w, x, y, n, bias, relu, s);
 }
 
-template <typename T>
-__global__ __launch_bounds__(256) void maxpool_kernel(const T* __restrict__ x, T* __restrict__ y,
-                                                      TensorDesc xd, TensorDesc yd, int n, int k,
-                                                      int stride, int pad) {
+// Window pooling, one thread per output: the maximum (AVG = false) or the mean (AVG = true) over
+// the in-image part of each k x k window; padding is never looked at, summed or counted.  With
+// k = 1, stride 1 and no padding the max form is a layout-to-layout copy, which is how a tensor
+// is moved into a channel slice of another.
+template <typename T, bool AVG>
+__global__ __launch_bounds__(256) void windowpool_kernel(const T* __restrict__ x, T* __restrict__ y,
+                                                         TensorDesc xd, TensorDesc yd, int n, int k,
+                                                         int stride, int pad) {
     const size_t per_image = (size_t)yd.c * yd.h * yd.w;
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= per_image * n) return;
@@ -236,7 +240,7 @@ __global__ __launch_bounds__(256) void maxpool_kernel(const T* __restrict__ x, T
     const int oh = (int)((r / yd.w) % yd.h);
     const int c = (int)(r / ((size_t)yd.w * yd.h));
     const T* xp = x + (size_t)img * xd.image + (size_t)c * xd.plane + xd.origin;
-    bool seen = false;
+    int seen = 0;
     float m = 0.0f;
     for (int a = 0; a < k; ++a) {
         const int ih = oh * stride + a - pad;
@@ -245,10 +249,12 @@ __global__ __launch_bounds__(256) void maxpool_kernel(const T* __restrict__ x, T
             const int iw = ow * stride + q - pad;
             if (iw < 0 || iw >= xd.w) continue;
             const float v = (float)xp[(size_t)ih * xd.pitch + iw];
-            if (!seen || v > m) m = v;
-            seen = true;
+            if (AVG) m += v;
+            else if (!seen || v > m) m = v;
+            ++seen;
         }
     }
+    if (AVG && seen) m /= (float)seen;
     y[(size_t)img * yd.image + (size_t)c * yd.plane + yd.origin + (size_t)oh * yd.pitch + ow] = (T)m;
 }
 
@@ -288,18 +294,30 @@ cadnn_status launch_copy(const void* src, void* dst, size_t bytes, hipStream_t s
     return CADNN_OK;
 }
 
-cadnn_status launch_maxpool(const void* x, const TensorDesc& xd, void* y, const TensorDesc& yd, int n,
-                            int k, int stride, int pad, cadnn_dtype dt, hipStream_t s) {
+template <bool AVG>
+static cadnn_status launch_windowpool(const void* x, const TensorDesc& xd, void* y, const TensorDesc& yd, int n,
+                                      int k, int stride, int pad, cadnn_dtype dt, hipStream_t s) {
     const size_t total = (size_t)n * yd.c * yd.h * yd.w;
+    if ((total + 255) / 256 > 0x7fffffffull) return fail(CADNN_EUNSUPPORTED, "pooling layer too large for one launch");
     const unsigned blocks = (unsigned)((total + 255) / 256);
     if (dt == CADNN_F16)
-        hipLaunchKernelGGL(maxpool_kernel<_Float16>, dim3(blocks), dim3(256), 0, s, (const _Float16*)x,
+        hipLaunchKernelGGL((windowpool_kernel<_Float16, AVG>), dim3(blocks), dim3(256), 0, s, (const _Float16*)x,
                            (_Float16*)y, xd, yd, n, k, stride, pad);
     else
-        hipLaunchKernelGGL(maxpool_kernel<float>, dim3(blocks), dim3(256), 0, s, (const float*)x,
+        hipLaunchKernelGGL((windowpool_kernel<float, AVG>), dim3(blocks), dim3(256), 0, s, (const float*)x,
                            (float*)y, xd, yd, n, k, stride, pad);
     CADNN_HIP(hipGetLastError());
     return CADNN_OK;
+}
+
+cadnn_status launch_maxpool(const void* x, const TensorDesc& xd, void* y, const TensorDesc& yd, int n,
+                            int k, int stride, int pad, cadnn_dtype dt, hipStream_t s) {
+    return launch_windowpool<false>(x, xd, y, yd, n, k, stride, pad, dt, s);
+}
+
+cadnn_status launch_avgpool2d(const void* x, const TensorDesc& xd, void* y, const TensorDesc& yd, int n,
+                              int k, int stride, int pad, cadnn_dtype dt, hipStream_t s) {
+    return launch_windowpool<true>(x, xd, y, yd, n, k, stride, pad, dt, s);
 }
 
 cadnn_status launch_avgpool(const void* x, const TensorDesc& xd, void* y, int n, cadnn_dtype dt,

@@ -11,7 +11,7 @@ using namespace cadnn;
 
 namespace {
 
-enum OpKind { OP_CONV, OP_FC, OP_MAXPOOL, OP_AVGPOOL, OP_DEPTHWISE };
+enum OpKind { OP_CONV, OP_FC, OP_MAXPOOL, OP_AVGPOOL, OP_DEPTHWISE, OP_AVGPOOL2D, OP_CONCAT };
 
 struct Shape {
     int n = 0, c = 0, h = 0, w = 0;
@@ -36,7 +36,19 @@ struct NetOp {
     int pool_op = -1;                        // conv: the global average pool op fused into this one
     int dw_op = -1;                          // conv: the depthwise op fused into this one
     int fused_into = -1;                     // projection / pool / depthwise: the op that now computes it (it is skipped)
+    // concatenation: its sources (src / src_inst repeat the first), the first output channel of
+    // each, and whether the source's producer writes its slice of this op's region itself
+    std::vector<int> srcs, src_insts, ch_off;
+    std::vector<char> in_place;
+    int slice_of = -1;                       // producer: the concatenation whose region it writes into ...
+    int slice_ch = 0;                        // ... starting at this channel
 };
+
+// Every op whose output `op` reads as an activation input (not as residual).
+std::vector<int> input_insts(const NetOp& op) {
+    if (op.kind == OP_CONCAT) return op.src_insts;
+    return std::vector<int>{op.src_inst};
+}
 
 }  // namespace
 
@@ -92,6 +104,30 @@ void layout(cadnn_net* net) {
             halo[op.src_inst] = std::max(halo[op.src_inst], op.pad);
     }
     if (nops) flat[nops - 1] = true;
+    // A source of a concatenation that nothing else reads is written by its producer straight
+    // into its channel slice of the concatenation's region (not when that region is the
+    // caller's output tensor, and not for a producer that is itself a concatenation).
+    std::vector<int> all_readers(nops, 0);
+    for (const NetOp& op : net->ops) {
+        for (int i : input_insts(op)) if (i >= 0) ++all_readers[i];
+        if (op.res_inst >= 0) ++all_readers[op.res_inst];
+    }
+    for (NetOp& op : net->ops) { op.slice_of = -1; op.slice_ch = 0; }
+    for (int k = 0; k < nops; ++k) {
+        NetOp& cat = net->ops[k];
+        if (cat.kind != OP_CONCAT) continue;
+        cat.in_place.assign(cat.src_insts.size(), 0);
+        for (size_t j = 0; j < cat.src_insts.size(); ++j) {
+            const int p = cat.src_insts[j];
+            if (p < 0 || k == nops - 1 || all_readers[p] != 1) continue;
+            NetOp& prod = net->ops[p];
+            if (prod.kind != OP_CONV && prod.kind != OP_DEPTHWISE && prod.kind != OP_MAXPOOL && prod.kind != OP_AVGPOOL2D)
+                continue;
+            cat.in_place[j] = 1;
+            prod.slice_of = k;
+            prod.slice_ch = cat.ch_off[j];
+        }
+    }
     // (Layers dense enough for the matrix-core kernels stay on plain layouts, which is all
     // those kernels read and write.)
     auto sparse_enough = [](const NetOp& o) {
@@ -115,6 +151,10 @@ void layout(cadnn_net* net) {
     }
     for (const NetOp& op : net->ops) {
         if (op.res_inst >= 0) s2d[op.res_inst] = 0;
+        if (op.kind == OP_CONCAT) {
+            for (int i : op.src_insts) if (i >= 0) s2d[i] = 0;
+            continue;
+        }
         if (op.src_inst < 0) continue;
         const int i = op.src_inst;
         if (op.kind != OP_CONV || !sparse_enough(op)) { s2d[i] = 0; continue; }
@@ -125,11 +165,20 @@ void layout(cadnn_net* net) {
     size_t off = 0;
     for (int i = 0; i < nops; ++i) {
         NetOp& op = net->ops[i];
+        if (op.slice_of >= 0) continue;          // lives inside a later op's region, see below
         const int hp = flat[i] ? 0 : halo[i];
         op.yd = (s2d[i] && strided[i] && net->allow_s2d) ? make_desc_s2d(op.out.c, op.out.h, op.out.w, hp, hp)
                                                         : make_desc(op.out.c, op.out.h, op.out.w, hp, hp);
         op.y_off = off;
         if (i != nops - 1) off += ((size_t)op.out.n * op.yd.image * net->elem() + 255) / 256 * 256;
+    }
+    for (NetOp& op : net->ops) {
+        if (op.slice_of < 0) continue;
+        // a channel slice of the concatenation's region: its planes, its halo, its image stride
+        const NetOp& cat = net->ops[op.slice_of];
+        op.yd = cat.yd;
+        op.yd.c = op.out.c;
+        op.y_off = cat.y_off + (size_t)op.slice_ch * cat.yd.plane * net->elem();
     }
     for (NetOp& op : net->ops) {
         op.xd = op.src_inst < 0 ? make_desc(op.in.c, op.in.h, op.in.w) : net->ops[op.src_inst].yd;
@@ -143,11 +192,7 @@ void layout(cadnn_net* net) {
     // one output write and one residual read less (paper Section 4, layer fusion).
     for (NetOp& op : net->ops) { op.shortcut = -1; op.pool_op = -1; op.dw_op = -1; op.fused_into = -1; }
     if (net->allow_fusion) {
-        std::vector<int> readers(nops, 0);
-        for (const NetOp& op : net->ops) {
-            if (op.src_inst >= 0) ++readers[op.src_inst];
-            if (op.res_inst >= 0) ++readers[op.res_inst];
-        }
+        const std::vector<int>& readers = all_readers;
         for (int i = 0; i < nops; ++i) {
             NetOp& c = net->ops[i];
             if (c.kind != OP_CONV || c.res_inst < 0) continue;
@@ -273,6 +318,22 @@ cadnn_status launch_one(cadnn_net* net, size_t i, const void* x, void* y, hipStr
             return launch_fc(op.w, src, dst, op.in.n, (const float*)op.bias, op.relu, s);
         case OP_MAXPOOL:
             return launch_maxpool(src, op.xd, dst, op.yd, op.in.n, op.k, op.stride, op.pad, net->dtype, s);
+        case OP_AVGPOOL2D:
+            return launch_avgpool2d(src, op.xd, dst, op.yd, op.in.n, op.k, op.stride, op.pad, net->dtype, s);
+        case OP_CONCAT: {
+            // only the sources that were not written in place need moving
+            for (size_t j = 0; j < op.srcs.size(); ++j) {
+                if (op.in_place[j]) continue;
+                const int p = op.src_insts[j];
+                const TensorDesc from = p < 0 ? make_desc(net->input.c, net->input.h, net->input.w) : net->ops[p].yd;
+                TensorDesc to = op.yd;
+                to.c = from.c;
+                char* slice = (char*)dst + (size_t)op.ch_off[j] * op.yd.plane * net->elem();
+                cadnn_status st = launch_maxpool(in_ptr(net, p, x), from, slice, to, op.in.n, 1, 1, 0, net->dtype, s);
+                if (st != CADNN_OK) return st;
+            }
+            return CADNN_OK;
+        }
         case OP_AVGPOOL:
             return launch_avgpool(src, op.xd, dst, op.in.n, net->dtype, s);
     }
@@ -370,6 +431,56 @@ extern "C" cadnn_status cadnn_net_add_maxpool(cadnn_net* net, int k, int stride,
     if (op.out.h <= 0 || op.out.w <= 0) return fail(CADNN_EINVAL, "cadnn_net_add_maxpool: empty output");
     op.kind = OP_MAXPOOL; op.k = k; op.stride = stride; op.pad = pad; op.src = src; op.dst = dst;
     if ((st = note_output(net, dst, op.out)) != CADNN_OK) return st;
+    net->ops.push_back(op);
+    return CADNN_OK;
+}
+
+extern "C" cadnn_status cadnn_net_add_avgpool(cadnn_net* net, int k, int stride, int pad, int src,
+                                              int dst) {
+    if (!net) return fail(CADNN_EINVAL, "cadnn_net_add_avgpool: NULL net");
+    if (net->finalized) return fail(CADNN_EINVAL, "cadnn_net_add_avgpool: net already finalized");
+    if (k <= 0 || stride <= 0 || pad < 0 || src == dst) return fail(CADNN_EINVAL, "cadnn_net_add_avgpool: bad argument");
+    NetOp op;
+    cadnn_status st = src_shape(net, src, &op.in, &op.src_inst);
+    if (st != CADNN_OK) return st;
+    op.out = Shape{op.in.n, op.in.c, conv_out(op.in.h, k, stride, pad), conv_out(op.in.w, k, stride, pad)};
+    if (op.out.h <= 0 || op.out.w <= 0) return fail(CADNN_EINVAL, "cadnn_net_add_avgpool: empty output");
+    op.kind = OP_AVGPOOL2D; op.k = k; op.stride = stride; op.pad = pad; op.src = src; op.dst = dst;
+    if ((st = note_output(net, dst, op.out)) != CADNN_OK) return st;
+    net->ops.push_back(op);
+    return CADNN_OK;
+}
+
+extern "C" cadnn_status cadnn_net_add_concat(cadnn_net* net, const int* srcs, int count, int dst) {
+    if (!net || !srcs) return fail(CADNN_EINVAL, "cadnn_net_add_concat: NULL pointer");
+    if (net->finalized) return fail(CADNN_EINVAL, "cadnn_net_add_concat: net already finalized");
+    if (count <= 0) return fail(CADNN_EINVAL, "cadnn_net_add_concat: no sources");
+    NetOp op;
+    int channels = 0;
+    for (int j = 0; j < count; ++j) {
+        if (srcs[j] == dst) return fail(CADNN_EINVAL, "cadnn_net_add_concat: dst aliases a source");
+        Shape sh;
+        int inst = -1;
+        cadnn_status st = src_shape(net, srcs[j], &sh, &inst);
+        if (st != CADNN_OK) return st;
+        if (j == 0) {
+            op.in = sh;
+            op.src = srcs[0];
+            op.src_inst = inst;
+        } else if (sh.n != op.in.n || sh.h != op.in.h || sh.w != op.in.w) {
+            return fail(CADNN_EINVAL, "cadnn_net_add_concat: source %d is %dx%dx%d, the first is %dx%dx%d", j, sh.n,
+                        sh.h, sh.w, op.in.n, op.in.h, op.in.w);
+        }
+        op.srcs.push_back(srcs[j]);
+        op.src_insts.push_back(inst);
+        op.ch_off.push_back(channels);
+        channels += sh.c;
+    }
+    op.in_place.assign((size_t)count, 0);
+    op.out = Shape{op.in.n, channels, op.in.h, op.in.w};
+    op.kind = OP_CONCAT; op.dst = dst;
+    cadnn_status st = note_output(net, dst, op.out);
+    if (st != CADNN_OK) return st;
     net->ops.push_back(op);
     return CADNN_OK;
 }
@@ -561,6 +672,10 @@ extern "C" cadnn_status cadnn_net_op_variant(const cadnn_net* net, int op_index,
         case OP_DEPTHWISE: name = op.fused_into >= 0 ? "fused" : "dwconv"; break;
         case OP_MAXPOOL: name = "maxpool"; break;
         case OP_AVGPOOL: name = op.fused_into >= 0 ? "fused" : "avgpool"; break;
+        case OP_AVGPOOL2D: name = "avgpool2d"; break;
+        case OP_CONCAT:
+            name = std::all_of(op.in_place.begin(), op.in_place.end(), [](char c) { return c != 0; }) ? "in place" : "concat";
+            break;
     }
     if (!name) return CADNN_EUNSUPPORTED;
     std::strncpy(buf, name, len - 1);

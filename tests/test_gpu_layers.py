@@ -219,6 +219,13 @@ def test_pools(cad):
     x16 = x.astype(np.float16)
     y = cad.cadnn_maxpool2d(dev(x16), 3, 2, 1)
     assert np.array_equal(y.cpu().numpy(), oracle.maxpool(x16, 3, 2, 1))
+    for k, s, p in [(3, 1, 1), (3, 2, 0), (2, 2, 0), (5, 1, 2)]:
+        y = cad.cadnn_avgpool2d(dev(x), k, s, p)
+        # an fp32 sum of at most k*k terms against the mean of their magnitudes
+        d = np.abs(y.cpu().numpy().astype(np.float64) - oracle.avgpool(x, k, s, p, dtype=np.float64))
+        assert (d <= 2e-6 * oracle.avgpool(np.abs(x), k, s, p, dtype=np.float64) + 1e-30).all(), (k, s, p, d.max())
+    y = cad.cadnn_avgpool2d(dev(x16), 3, 1, 1)
+    assert_close(y.cpu().numpy(), oracle.avgpool(x16, 3, 1, 1), 1e-3, "avgpool2d fp16")
 
 
 def test_fp16_storage_variant(cad):
@@ -549,3 +556,42 @@ def test_fused_depthwise_epilogue(cad, geom):
         assert np.abs(yu - ref.astype(np.float64)).max() <= tol * np.abs(ref).max()
         net.free()
         unfused.free()
+
+
+@pytest.mark.parametrize("dtype_name", ["f32", "f16"])
+def test_concat_in_place_and_copied(cad, dtype_name):
+    """Channel concatenation inside a net: branch outputs that only the concatenation reads are
+    written by their producers (convolution, depthwise, max pool, average pool) straight into
+    their channel slices, whose zero halo the 3x3 reader behind relies on; a source with another
+    reader, the net input, and a nested concatenation are copied.  Every intermediate buffer and
+    the output are compared with the oracle."""
+    f16 = dtype_name == "f16"
+    dtype, npdt, tol = (cad.F16, np.float16, TOL_F16) if f16 else (cad.F32, np.float32, TOL_F32)
+    Op = wl.Op
+    ops = [Op("conv", "b1", 0, 1, 6, 10, 1, 1, 0, 0.5, True),
+           Op("conv", "b2a", 0, 2, 6, 8, 1, 1, 0, 0.5, True),
+           Op("conv", "b2b", 2, 3, 8, 12, 3, 1, 1, 0.7, True),
+           Op("dwconv", "b3", 2, 4, 8, 8, 3, 1, 1, 0.0, True),          # buffer 2 has two readers
+           Op("maxpool", "b4", 0, 5, k=3, stride=1, pad=1),
+           Op("avgpool2d", "b5", 0, 6, k=3, stride=1, pad=1),
+           Op("concat", "inner", 5, 7, srcs=(5, 6)),
+           Op("concat", "cat", 1, 8, srcs=(1, 3, 4, 7, 0, 2)),          # 10 + 12 + 8 + 12 + 6 + 8 = 56
+           Op("conv", "post", 8, 9, 56, 16, 3, 1, 1, 0.8, True),
+           Op("concat", "tail", 9, 10, srcs=(9, 9))]                      # the last op: copies into y
+    shape = (3, 6, 11, 13)
+    x, ws, bs = wl.net_tensors(ops, "cat", shape, input_relu=True)
+    xs = x.astype(npdt)
+    ref, ins, outs = oracle.run_net(ops, xs, ws, bs, dtype=npdt)
+    assert ref.shape == (3, 32, 11, 13)
+    for kw in ({}, {"plain_layout": True, "fuse": False}):
+        net = cad.build_net(ops, ws, bs, shape, dtype, use_graph=True, **kw)
+        names = [net.op_variant(i) for i in range(len(ops))]
+        assert names[6] == "in place" and names[7] == "concat" and names[9] == "concat", names
+        for rep in range(2):
+            y = net.run(dev(xs))
+            torch.cuda.synchronize()
+            assert_close(y.cpu().numpy(), ref, tol, f"concat net {kw} (replay {rep})")
+        for i in (0, 2, 3, 4, 5, 6, 7):
+            got = net.read_buffer(ops[i].dst, outs[i].shape)
+            assert_close(got, outs[i], tol, f"buffer of {ops[i].name}")
+        net.free()

@@ -55,6 +55,11 @@ def check_layers_in_isolation(cad, ops, ws, bs, ins, outs, tol, dtype, which=Non
         elif op.kind == "maxpool":
             y = cad.cadnn_maxpool2d(dev(ins[i]), op.k, op.stride, op.pad)
             h = None
+        elif op.kind == "avgpool2d":
+            y = cad.cadnn_avgpool2d(dev(ins[i]), op.k, op.stride, op.pad)
+            h = None
+        elif op.kind == "concat":
+            continue
         else:
             y = cad.cadnn_global_avgpool(dev(ins[i]))
             h = None
@@ -225,4 +230,33 @@ def test_factorized_7x7_branch(cad, dtype_name):
         cond = cond_conv(ins[-1], ws[-1].astype(npdt), bs[-1], None, 1, 3)
         e = assert_chain_close(y.cpu().numpy(), ref, cond, tol, f"factorized branch (replay {rep})")
     print("factorized 7x7 branch", names, e)
+    net.free()
+
+
+def test_inception_v3(cad):
+    """The fourth model of the paper's Table 2: 94 convolutions (5x5, 3x3, strided, and 1x7 / 7x1 /
+    1x3 / 3x1 filters carried in square banks), 9 windowed average pools, 4 max pools and 11
+    channel concatenations whose sources are written in place.  A sample of layers in isolation on
+    the oracle's inputs, then the whole net."""
+    ops = wl.inception_v3_ops()
+    shape = (1, 3, 299, 299)
+    x, ws, bs = wl.net_tensors(ops, "iv3", shape)
+    ref, ins, outs = oracle.run_net(ops, x, ws, bs)
+    which = set(range(0, len(ops), 5)) | {i for i, o in enumerate(ops) if o.kind == "avgpool2d"}
+    worst = check_layers_in_isolation(cad, ops, ws, bs, ins, outs, TOL_F32, cad.F32, which=which)
+    print("inception per-layer worst E_inf", worst)
+    net = cad.build_net(ops, ws, bs, shape, cad.F32, use_graph=True)
+    names = [net.op_variant(i) for i in range(len(ops))]
+    assert [n for n, o in zip(names, ops) if o.kind == "concat"] == ["in place"] * 11, names
+    xd = dev(x)
+    cond = cond_fc(ins[-1], ws[-1], bs[-1])
+    for rep in range(2):
+        y = net.run(xd)
+        torch.cuda.synchronize()
+        e = assert_chain_close(y.cpu().numpy(), ref, cond, TOL_F32, f"inception end to end (replay {rep})")
+    for name in ("a3_cat", "c2_cat", "e1_cat"):
+        i = next(k for k, o in enumerate(ops) if o.name == name)
+        got = net.read_buffer(ops[i].dst, outs[i].shape)
+        assert_close(got, outs[i], 1e-3, name + " inside the net")
+    print("inception end-to-end", e)
     net.free()
