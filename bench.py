@@ -167,8 +167,8 @@ def main() -> int:
     npdt = np.float16 if dt == "f16" else np.float32
     tdt = torch.float16 if dt == "f16" else torch.float32
     elem = 2 if dt == "f16" else 4
-    if args.retune or args.no_tune or not is_default:
-        args.load_tune = ""
+    if args.retune or args.no_tune or (not is_default and args.load_tune == DEFAULT_TUNE):
+        args.load_tune = ""     # (the saved choice that ships with the package is for the default workload)
     def make_net(live_tune):
         return cad.build_net(ops, ws, bs, shape, cad.F16 if dt == "f16" else cad.F32, use_graph=not args.no_graph,
                              tune=live_tune)
