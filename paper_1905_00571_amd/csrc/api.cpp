@@ -94,9 +94,15 @@ static bool variant_fits(const ConvVariant& v, const cadnn_weights* w, const Con
             const int unit2 = g.ex->xd.s2d ? 2 : 1;
             if (v.adjacent && g.ex->stride != unit2) return false;
         }
-        // a lane's adjacent pixels must be adjacent in memory, on both sides
+        // a lane's adjacent pixels must be adjacent in memory, on both sides; rows that split
+        // evenly into groups take the plain instantiations, the others the ragged-row ones
         const int unit = g.xd.s2d ? 2 : 1;
-        if (v.adjacent && (g.stride != unit || g.wout % v.p != 0)) return false;
+        if (v.adjacent && (g.stride != unit || (g.wout % v.p != 0) != (v.adjacent == 2))) return false;
+        // The last group of a ragged row reads up to P-1 elements past its row.  Past the end
+        // of the image that reads as zero dword by dword, which is fine for 4-byte storage; in
+        // 2-byte storage the dword holding the image's last element would be dropped whole,
+        // so there the input must end in a halo row instead.
+        if (v.adjacent == 2 && v.is_f16 && g.xd.ph < 1) return false;
         // 1x1 filters read only the image proper; larger filters need the zero halo
         if (one) return g.pad == 0;
         return g.xd.ph >= g.pad && g.xd.pw >= g.pad;
@@ -146,7 +152,8 @@ static const ConvVariant* heuristic_variant(const cadnn_weights* w, const ConvGe
             continue;   // chosen by tuning only
         } else if (v->family != FAM_TILE) {
             const int P = v->p;
-            const double tiles = std::ceil(pixels / (64.0 * P)) * g.n;
+            const double walked = v->adjacent == 2 ? (double)g.hout * ((g.wout + P - 1) / P * P) : pixels;
+            const double tiles = std::ceil(walked / (64.0 * P)) * g.n;
             const double blocks = tiles * std::ceil((double)w->cout / v->rows_per_block());
             const double waves = blocks * v->nw;
             const double iters = v->rpw * nnz_row / v->ks;
@@ -250,7 +257,9 @@ static cadnn_status launch_variant(const cadnn_weights* w, const ConvVariant* v,
         a.tiles_x = (g.wout + v->tw - 1) / v->tw;
         a.tiles_y = (g.hout + v->th - 1) / v->th;
     } else {
-        a.tiles_x = (a.hwout + 64 * v->p - 1) / (64 * v->p);
+        a.wq = (v->family == FAM_LINEAR && v->adjacent == 2) ? (g.wout + v->p - 1) / v->p * v->p : g.wout;
+        a.hwq = g.hout * a.wq;
+        a.tiles_x = (a.hwq + 64 * v->p - 1) / (64 * v->p);
         a.tiles_y = 1;
     }
     a.row_groups = plan->rows_padded / v->rows_per_block();

@@ -31,6 +31,11 @@ constexpr uint32_t kLinOutOfRange = 0x7ffffff0u;   // beyond any buffer this lib
 // ADJ = 1: they are P adjacent pixels of one output row fetched with ONE P-element load
 //          (stride-1 layers whose output width is a multiple of P): fewer, wider loads and
 //          fewer cache lines touched per useful byte.
+// ADJ = 2: the same for rows that do NOT split into groups of P ("ragged"): the pixels are
+//          enumerated over rows of wq = width rounded up to P positions, so a lane's group
+//          never straddles two rows; the positions past a row's end are computed (their
+//          loads stay inside the buffer or read as zero) and not stored.  Kept apart
+//          because the extra bookkeeping costs the even-width layers about 1 %.
 // S2D = 1: the instantiation understands de-interleaved tensors (TensorDesc::s2d) on its
 //          output, residual and -- for pixel-wise layers -- input.  Kept apart because the
 //          general address arithmetic costs every launch a fraction of a microsecond.
@@ -51,6 +56,7 @@ struct LinearCfg {
     static_assert(!(S2D && DUAL) && !(POOL && (S2D || DUAL || ADJ)), "not combined");
     static_assert(!(DW && (S2D || DUAL || POOL)), "not combined");
     static_assert(!(ADJ && S2D), "adjacent pixels are not adjacent in a de-interleaved tensor");
+    static_assert(ADJ != 2 || (!DUAL && !POOL), "not combined");
     static constexpr int RG = NW / KS;
     static constexpr int THREADS = NW * 64;
     static_assert(NW % KS == 0, "KS must divide the waves of a workgroup");
@@ -230,6 +236,15 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_linear_kernel(const ConvLa
             voff[j] = q < a.hwout
                           ? (uint32_t)tensor_off(a.xd, oh * a.stride - a.pad, ow * a.stride - a.pad) * (uint32_t)sizeof(T)
                           : kLinOutOfRange;
+        } else if constexpr (ADJ == 2) {
+            // ragged rows: the lane's one wide load starts at its first pixel, which is always
+            // in the row; later pixels of the group may lie past the row's end
+            oh = q / a.wq;
+            ow = q - oh * a.wq;
+            oidx[j] = (q < a.hwq && (j == 0 || ow < a.yd.w)) ? a.yd.origin + oh * a.yd.pitch + ow : -1;
+            voff[j] = q < a.hwq
+                          ? (uint32_t)(base + oh * a.stride * a.xd.pitch + ow * a.stride) * (uint32_t)sizeof(T)
+                          : kLinOutOfRange;
         } else {
             oh = q / a.yd.w;
             ow = q - oh * a.yd.w;
@@ -300,8 +315,9 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_linear_kernel(const ConvLa
             lin_pixel(a, q, oh, ow);
             ridx = tensor_off(a.rd, oh, ow);
         } else {
-            oh = q / a.yd.w;
-            ow = q - oh * a.yd.w;
+            const int wq = ADJ == 2 ? a.wq : a.yd.w;
+            oh = q / wq;
+            ow = q - oh * wq;
             ridx = a.rd.origin + oh * a.rd.pitch + ow;
         }
 #pragma unroll
@@ -466,6 +482,9 @@ static ConvVariant make_linear(const char* name) {
 #define CADNN_LINEAR_ADJ(T, P, RPW, KS, NW, U) \
     make_linear<LinearCfg<T, P, RPW, KS, NW, U, 1>>("slinear_" #T "_a" #P "_r" #RPW "k" #KS "w" #NW "u" #U)
 
+#define CADNN_LINEAR_RAGGED(T, P, RPW, KS, NW, U) \
+    make_linear<LinearCfg<T, P, RPW, KS, NW, U, 2>>("slinear_" #T "_g" #P "_r" #RPW "k" #KS "w" #NW "u" #U)
+
 #define CADNN_LINEAR_S2D(T, P, RPW, KS, NW, U) \
     make_linear<LinearCfg<T, P, RPW, KS, NW, U, 0, 1>>("slinear_" #T "_d" #P "_r" #RPW "k" #KS "w" #NW "u" #U)
 
@@ -482,6 +501,22 @@ static ConvVariant make_linear(const char* name) {
     make_linear<LinearCfg<T, P, RPW, KS, NW, U, 0, 0, 0, 0, 1>>("slinear_" #T "_dw" #P "_r" #RPW "k" #KS "w" #NW "u" #U)
 
 #define CADNN_LINEAR_SHAPES(T)          \
+    CADNN_LINEAR_RAGGED(T, 2, 1, 1, 4, 4), \
+    CADNN_LINEAR_RAGGED(T, 2, 1, 1, 4, 8), \
+    CADNN_LINEAR_RAGGED(T, 2, 1, 2, 4, 4), \
+    CADNN_LINEAR_RAGGED(T, 2, 1, 2, 4, 8), \
+    CADNN_LINEAR_RAGGED(T, 2, 1, 4, 4, 4), \
+    CADNN_LINEAR_RAGGED(T, 2, 1, 4, 4, 8), \
+    CADNN_LINEAR_RAGGED(T, 2, 1, 8, 8, 4), \
+    CADNN_LINEAR_RAGGED(T, 2, 2, 1, 4, 4), \
+    CADNN_LINEAR_RAGGED(T, 4, 1, 1, 4, 4), \
+    CADNN_LINEAR_RAGGED(T, 4, 1, 1, 4, 8), \
+    CADNN_LINEAR_RAGGED(T, 4, 1, 2, 4, 4), \
+    CADNN_LINEAR_RAGGED(T, 4, 1, 2, 4, 8), \
+    CADNN_LINEAR_RAGGED(T, 4, 1, 4, 4, 4), \
+    CADNN_LINEAR_RAGGED(T, 4, 1, 4, 4, 8), \
+    CADNN_LINEAR_RAGGED(T, 4, 1, 8, 8, 4), \
+    CADNN_LINEAR_RAGGED(T, 4, 2, 1, 4, 4), \
     CADNN_LINEAR_DW(T, 1, 1, 1, 4, 4), \
     CADNN_LINEAR_DW(T, 1, 1, 1, 4, 8), \
     CADNN_LINEAR_DW(T, 1, 1, 2, 4, 4), \

@@ -154,7 +154,7 @@ struct ConvVariant {
     int pitch, plane;     // LDS floats per tile row / per channel
     int elem_bytes;       // size of one staged tile element in LDS
     int unroll;           // nonzeros per scalar fetch; segments are padded to a multiple of it
-    int adjacent;         // FAM_LINEAR: a lane's P pixels are adjacent in one output row (unit stride only)
+    int adjacent;           // FAM_LINEAR: a lane's P pixels are adjacent in one output row (unit stride only)
     int s2d;              // FAM_LINEAR: understands de-interleaved output / residual / pixel-wise input
     int dual;             // FAM_LINEAR: accumulates a fused 1x1 shortcut on a second input
     int pool;             // FAM_LINEAR: global average pool fused into the epilogue
@@ -178,6 +178,10 @@ struct ConvLaunch {
     int kh, kw, is_f16;
     int tiles_x, tiles_y, row_groups;
     int hwout;                // yd.h * yd.w
+    // FAM_LINEAR ragged-row instantiations: output pixels are enumerated over rows of wq
+    // positions, wq = yd.w rounded up to the adjacent pixels a lane takes, so that a lane's
+    // group never straddles two rows; positions at or beyond yd.w are computed and not stored
+    int wq, hwq;              // hwq = yd.h * wq
     // fused 1x1 shortcut (FAM_LINEAR dual instantiations): second input, plain view
     const void* x2;
     const float* bias2;
