@@ -241,6 +241,24 @@ cadnn_status cadnn_net_workspace_bytes(const cadnn_net* net, size_t* bytes);
 #define CADNN_NET_PLAIN_LAYOUT 4
 #define CADNN_NET_NO_FUSION 8
 cadnn_status cadnn_net_finalize(cadnn_net* net, void* workspace_dev, size_t bytes, int flags);
+/* Where the runner puts op `op_index`'s output and what it does with the op, as decided for
+ * `flags` (the CADNN_NET_PLAIN_LAYOUT / CADNN_NET_NO_FUSION bits matter).  Pure host work: it
+ * may be called before cadnn_net_finalize and needs no GPU.  cadnn_net_workspace_bytes reports
+ * the size for the flags of the most recent of cadnn_net_op_info / cadnn_net_finalize (default
+ * 0). */
+typedef struct {
+    int halo_h, halo_w;      /* zero halo rows / columns around every channel plane */
+    int pitch;               /* elements per stored row */
+    int64_t plane;           /* elements per stored channel plane */
+    int64_t image;           /* elements from one image to the next */
+    int deinterleaved;       /* 1 = split by row / column parity (read by stride-2 layers) */
+    int64_t offset;          /* byte offset of channel 0 of image 0 in the workspace (the last
+                                op writes the caller's y: its offset is 0 and means nothing) */
+    int fused_into;          /* >= 0: the op is computed inside that op and launches nothing */
+    int slice_of;            /* >= 0: the op writes in place into that concatenation's region */
+    int slice_channel;       /* ... starting at this channel of it */
+} cadnn_op_info;
+cadnn_status cadnn_net_op_info(cadnn_net* net, int op_index, int flags, cadnn_op_info* out);
 cadnn_status cadnn_run_net(cadnn_net* net, const void* x, void* y, void* stream);
 /* Number of ops, and per-op device time: op i is launched `repeats` times back
  * to back between two HIP events on `stream` and the average is written to

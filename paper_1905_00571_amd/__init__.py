@@ -35,4 +35,6 @@ from .binding import (  # noqa: F401
     cadnn_dense_conv2d,
     cadnn_run_net,
     build_net,
+    plan_net,
+    OpInfo,
 )

@@ -29,6 +29,14 @@ class CadnnError(RuntimeError):
         self.text = text
 
 
+class OpInfo(ctypes.Structure):
+    """Mirror of cadnn_op_info."""
+    _fields_ = [("halo_h", ctypes.c_int), ("halo_w", ctypes.c_int), ("pitch", ctypes.c_int),
+                ("plane", ctypes.c_int64), ("image", ctypes.c_int64), ("deinterleaved", ctypes.c_int),
+                ("offset", ctypes.c_int64), ("fused_into", ctypes.c_int), ("slice_of", ctypes.c_int),
+                ("slice_channel", ctypes.c_int)]
+
+
 def lib_path() -> str:
     return _LIB_PATH
 
@@ -79,6 +87,7 @@ def lib() -> ctypes.CDLL:
         "cadnn_net_add_fc": (_i, [_vp, _vp, _vp, _i, _i, _i]),
         "cadnn_net_workspace_bytes": (_i, [_vp, ctypes.POINTER(ctypes.c_size_t)]),
         "cadnn_net_finalize": (_i, [_vp, _vp, ctypes.c_size_t, _i]),
+        "cadnn_net_op_info": (_i, [_vp, _i, _i, ctypes.POINTER(OpInfo)]),
         "cadnn_run_net": (_i, [_vp, _vp, _vp, _vp]),
         "cadnn_net_num_ops": (_i, [_vp, ctypes.POINTER(_i)]),
         "cadnn_net_profile": (_i, [_vp, _vp, _vp, _vp, _i, _f32p]),
@@ -410,6 +419,84 @@ def cadnn_run_net(net: Net, x, y=None, stream=None):
     return net.run(x, y, stream)
 
 
+def _add_ops(L, handle, ops, weights, biases, input_shape, dtype, keep, to_device):
+    """Packs the weights and adds every op of the table to the net; returns the buffer shapes.
+    `to_device` turns a host bias vector into a device tensor (None: the ops get no bias, which
+    is enough for calls that only look at shapes and layouts)."""
+    shapes = {0: tuple(input_shape)}
+    for i, op in enumerate(ops):
+        if op.kind in ("conv", "fc", "dwconv"):
+            pw = cadnn_pack_weights(np.asarray(weights[i], dtype=np.float32), dtype)
+            b = None
+            if to_device is not None and biases[i] is not None:
+                b = to_device(biases[i])
+            keep += [pw, b]
+            if op.kind == "conv":
+                _check(L.cadnn_net_add_conv(handle, pw.handle, _dptr(b), op.stride, op.pad,
+                                            int(bool(op.relu)), op.src, op.dst, op.res))
+                s = shapes[op.src]
+                shapes[op.dst] = (s[0], pw.cout, _out_size(s[2], pw.kh, op.stride, op.pad),
+                                  _out_size(s[3], pw.kw, op.stride, op.pad))
+            elif op.kind == "dwconv":
+                _check(L.cadnn_net_add_depthwise(handle, pw.handle, _dptr(b), op.stride, op.pad,
+                                                 int(bool(op.relu)), op.src, op.dst))
+                s = shapes[op.src]
+                shapes[op.dst] = (s[0], s[1], _out_size(s[2], pw.kh, op.stride, op.pad),
+                                  _out_size(s[3], pw.kw, op.stride, op.pad))
+            else:
+                _check(L.cadnn_net_add_fc(handle, pw.handle, _dptr(b), int(bool(op.relu)), op.src, op.dst))
+                shapes[op.dst] = (shapes[op.src][0], pw.cout, 1, 1)
+        elif op.kind == "maxpool":
+            _check(L.cadnn_net_add_maxpool(handle, op.k, op.stride, op.pad, op.src, op.dst))
+            s = shapes[op.src]
+            shapes[op.dst] = (s[0], s[1], _out_size(s[2], op.k, op.stride, op.pad),
+                              _out_size(s[3], op.k, op.stride, op.pad))
+        elif op.kind == "avgpool2d":
+            _check(L.cadnn_net_add_avgpool(handle, op.k, op.stride, op.pad, op.src, op.dst))
+            s = shapes[op.src]
+            shapes[op.dst] = (s[0], s[1], _out_size(s[2], op.k, op.stride, op.pad),
+                              _out_size(s[3], op.k, op.stride, op.pad))
+        elif op.kind == "concat":
+            arr = (ctypes.c_int * len(op.srcs))(*op.srcs)
+            _check(L.cadnn_net_add_concat(handle, arr, len(op.srcs), op.dst))
+            s = shapes[op.srcs[0]]
+            shapes[op.dst] = (s[0], sum(shapes[b][1] for b in op.srcs), s[2], s[3])
+        elif op.kind == "avgpool":
+            _check(L.cadnn_net_add_global_avgpool(handle, op.src, op.dst))
+            s = shapes[op.src]
+            shapes[op.dst] = (s[0], s[1], 1, 1)
+        else:
+            raise ValueError(op.kind)
+    return shapes
+
+
+def plan_net(ops: Sequence, weights: Sequence, input_shape, dtype: int = F32, plain_layout: bool = False,
+             fuse: bool = True):
+    """Host-only: wires the op list into a cadnn_net and returns (per-op cadnn_op_info records as
+    dicts, workspace bytes) for the given layout flags.  Needs no GPU and runs nothing."""
+    L = lib()
+    n, c, h, w = input_shape
+    handle = _vp()
+    _check(L.cadnn_net_create(dtype, n, c, h, w, ctypes.byref(handle)))
+    keep: list = []
+    try:
+        _add_ops(L, handle, ops, weights, [None] * len(ops), input_shape, dtype, keep, None)
+        flags = (4 if plain_layout else 0) | (0 if fuse else 8)
+        infos = []
+        for i in range(len(ops)):
+            info = OpInfo()
+            _check(L.cadnn_net_op_info(handle, i, flags, ctypes.byref(info)))
+            infos.append({name: getattr(info, name) for name, _ in OpInfo._fields_})
+        nbytes = ctypes.c_size_t()
+        _check(L.cadnn_net_workspace_bytes(handle, ctypes.byref(nbytes)))
+    finally:
+        L.cadnn_net_free(handle)
+        for k in keep:
+            if isinstance(k, Weights):
+                k.free()
+    return infos, int(nbytes.value)
+
+
 def build_net(ops: Sequence, weights: Sequence, biases: Sequence, input_shape, dtype: int = F32,
               use_graph: bool = True, tune: bool = False, device: str = "cuda:0",
               plain_layout: bool = False, fuse: bool = True) -> Net:
@@ -425,50 +512,8 @@ def build_net(ops: Sequence, weights: Sequence, biases: Sequence, input_shape, d
     _check(L.cadnn_net_create(dtype, n, c, h, w, ctypes.byref(handle)))
     keep: list = []
     try:
-        shapes = {0: tuple(input_shape)}
-        for i, op in enumerate(ops):
-            if op.kind in ("conv", "fc", "dwconv"):
-                pw = cadnn_pack_weights(np.asarray(weights[i], dtype=np.float32), dtype)
-                b = None
-                if biases[i] is not None:
-                    b = torch.from_numpy(np.ascontiguousarray(biases[i], dtype=np.float32)).to(device)
-                keep += [pw, b]
-                if op.kind == "conv":
-                    _check(L.cadnn_net_add_conv(handle, pw.handle, _dptr(b), op.stride, op.pad,
-                                                int(bool(op.relu)), op.src, op.dst, op.res))
-                    s = shapes[op.src]
-                    shapes[op.dst] = (s[0], pw.cout, _out_size(s[2], pw.kh, op.stride, op.pad),
-                                      _out_size(s[3], pw.kw, op.stride, op.pad))
-                elif op.kind == "dwconv":
-                    _check(L.cadnn_net_add_depthwise(handle, pw.handle, _dptr(b), op.stride, op.pad,
-                                                     int(bool(op.relu)), op.src, op.dst))
-                    s = shapes[op.src]
-                    shapes[op.dst] = (s[0], s[1], _out_size(s[2], pw.kh, op.stride, op.pad),
-                                      _out_size(s[3], pw.kw, op.stride, op.pad))
-                else:
-                    _check(L.cadnn_net_add_fc(handle, pw.handle, _dptr(b), int(bool(op.relu)), op.src, op.dst))
-                    shapes[op.dst] = (shapes[op.src][0], pw.cout, 1, 1)
-            elif op.kind == "maxpool":
-                _check(L.cadnn_net_add_maxpool(handle, op.k, op.stride, op.pad, op.src, op.dst))
-                s = shapes[op.src]
-                shapes[op.dst] = (s[0], s[1], _out_size(s[2], op.k, op.stride, op.pad),
-                                  _out_size(s[3], op.k, op.stride, op.pad))
-            elif op.kind == "avgpool2d":
-                _check(L.cadnn_net_add_avgpool(handle, op.k, op.stride, op.pad, op.src, op.dst))
-                s = shapes[op.src]
-                shapes[op.dst] = (s[0], s[1], _out_size(s[2], op.k, op.stride, op.pad),
-                                  _out_size(s[3], op.k, op.stride, op.pad))
-            elif op.kind == "concat":
-                arr = (ctypes.c_int * len(op.srcs))(*op.srcs)
-                _check(L.cadnn_net_add_concat(handle, arr, len(op.srcs), op.dst))
-                s = shapes[op.srcs[0]]
-                shapes[op.dst] = (s[0], sum(shapes[b][1] for b in op.srcs), s[2], s[3])
-            elif op.kind == "avgpool":
-                _check(L.cadnn_net_add_global_avgpool(handle, op.src, op.dst))
-                s = shapes[op.src]
-                shapes[op.dst] = (s[0], s[1], 1, 1)
-            else:
-                raise ValueError(op.kind)
+        shapes = _add_ops(L, handle, ops, weights, biases, input_shape, dtype, keep,
+                          lambda b: torch.from_numpy(np.ascontiguousarray(b, dtype=np.float32)).to(device))
         nbytes = ctypes.c_size_t()
         _check(L.cadnn_net_workspace_bytes(handle, ctypes.byref(nbytes)))
         ws = torch.empty(max(int(nbytes.value), 256), dtype=torch.uint8, device=device)

@@ -527,11 +527,8 @@ extern "C" cadnn_status cadnn_net_workspace_bytes(const cadnn_net* net, size_t* 
     return CADNN_OK;
 }
 
-extern "C" cadnn_status cadnn_net_finalize(cadnn_net* net, void* ws, size_t bytes, int flags) {
-    if (!net) return fail(CADNN_EINVAL, "cadnn_net_finalize: NULL net");
-    if (net->ops.empty()) return fail(CADNN_EINVAL, "cadnn_net_finalize: empty net");
-    // (a plain layout never needs more room than the de-interleaved one that
-    // cadnn_net_workspace_bytes reports)
+// (Re)does the layout if the flags that matter to it changed.
+static void layout_for(cadnn_net* net, int flags) {
     const bool allow = (flags & CADNN_NET_PLAIN_LAYOUT) == 0;
     const bool fuse = (flags & CADNN_NET_NO_FUSION) == 0;
     if (!net->laid_out || allow != net->allow_s2d || fuse != net->allow_fusion) {
@@ -539,6 +536,38 @@ extern "C" cadnn_status cadnn_net_finalize(cadnn_net* net, void* ws, size_t byte
         net->allow_fusion = fuse;
         layout(net);
     }
+}
+
+extern "C" cadnn_status cadnn_net_op_info(cadnn_net* net, int op_index, int flags, cadnn_op_info* out) {
+    if (!net || !out) return fail(CADNN_EINVAL, "cadnn_net_op_info: NULL pointer");
+    if (op_index < 0 || op_index >= (int)net->ops.size()) return fail(CADNN_EINVAL, "cadnn_net_op_info: no op %d", op_index);
+    if (net->finalized) {
+        const int now = (net->allow_s2d ? 0 : CADNN_NET_PLAIN_LAYOUT) | (net->allow_fusion ? 0 : CADNN_NET_NO_FUSION);
+        if ((flags & (CADNN_NET_PLAIN_LAYOUT | CADNN_NET_NO_FUSION)) != now)
+            return fail(CADNN_EINVAL, "cadnn_net_op_info: the net was finalized with other flags");
+    } else {
+        layout_for(net, flags);
+    }
+    const NetOp& op = net->ops[op_index];
+    out->halo_h = op.yd.ph;
+    out->halo_w = op.yd.pw;
+    out->pitch = op.yd.pitch;
+    out->plane = op.yd.plane;
+    out->image = op.yd.image;
+    out->deinterleaved = op.yd.s2d;
+    out->offset = (int64_t)op.y_off + (op.yd.s2d ? 0 : (int64_t)op.yd.origin * (int64_t)net->elem());
+    out->fused_into = op.fused_into;
+    out->slice_of = op.slice_of;
+    out->slice_channel = op.slice_ch;
+    return CADNN_OK;
+}
+
+extern "C" cadnn_status cadnn_net_finalize(cadnn_net* net, void* ws, size_t bytes, int flags) {
+    if (!net) return fail(CADNN_EINVAL, "cadnn_net_finalize: NULL net");
+    if (net->ops.empty()) return fail(CADNN_EINVAL, "cadnn_net_finalize: empty net");
+    // (a plain layout never needs more room than the de-interleaved one that
+    // cadnn_net_workspace_bytes reports)
+    layout_for(net, flags);
     if (net->ws_bytes > 0 && !ws) return fail(CADNN_EINVAL, "cadnn_net_finalize: NULL workspace");
     if (bytes < net->ws_bytes) return fail(CADNN_EINVAL, "cadnn_net_finalize: workspace of %zu bytes, %zu needed", bytes, net->ws_bytes);
     drop_graph(net);

@@ -1,0 +1,136 @@
+"""CPU-only checks of the net runner's layout decisions (no GPU): halos, de-interleaved
+tensors, fusions and in-place concatenation, through cadnn_net_op_info."""
+import numpy as np
+import pytest
+
+import workloads as wl
+import paper_1905_00571_amd as cad
+
+
+def plan(ops, shape, tag, **kw):
+    _, ws, _ = wl.net_tensors(ops, tag, shape)
+    return cad.plan_net(ops, ws, shape, **kw)
+
+
+def region_bytes(info, n, elem=4):
+    return (n * info["image"] * elem + 255) // 256 * 256
+
+
+def test_resnet50_layout():
+    ops = wl.resnet50_ops()
+    infos, nbytes = plan(ops, (1, 3, 224, 224), "c2")
+    by = {o.name: i for o, i in zip(ops, infos)}
+    idx = {o.name: k for k, o in enumerate(ops)}
+    # a zero halo of the reader's padding around everything a 3x3 layer reads, none elsewhere
+    for o, i in zip(ops, infos):
+        readers = [r for r in ops if r.src == o.dst and ops.index(r) > ops.index(o)]
+        nxt = next((r for r in ops[idx[o.name] + 1:] if r.src == o.dst), None)
+        if nxt is not None and nxt.kind == "conv" and nxt.k == 3:
+            assert (i["halo_h"], i["halo_w"]) == (1, 1), o.name
+        elif o.name != "conv1":
+            assert (i["halo_h"], i["halo_w"]) == (0, 0), o.name
+    # the four projection shortcuts are computed inside the layers that add them, the pool inside the last layer
+    fused = {o.name: ops[i["fused_into"]].name for o, i in zip(ops, infos) if i["fused_into"] >= 0}
+    assert fused == {"conv2_1p": "conv2_1c", "conv3_1p": "conv3_1c", "conv4_1p": "conv4_1c",
+                     "conv5_1p": "conv5_1c", "gap": "conv5_3c"}
+    # tensors read by stride-2 layers are de-interleaved: a block input read by a strided
+    # projection (through the layer it is fused into) and the 1x1 output read by a strided 3x3
+    s2d = sorted(o.name for o, i in zip(ops, infos) if i["deinterleaved"])
+    assert s2d == sorted(["conv2_3c", "conv3_1a", "conv3_4c", "conv4_1a", "conv4_6c", "conv5_1a"])
+    assert by["conv3_1a"]["pitch"] == (56 + 2 + 1) // 2
+    # regions back to back, 256-byte aligned, in op order; the last op writes the caller's tensor
+    off = 0
+    for o, i in zip(ops[:-1], infos[:-1]):
+        origin = 0 if i["deinterleaved"] else (i["halo_h"] * i["pitch"] + i["halo_w"]) * 4
+        assert i["offset"] == off + origin, o.name
+        off += region_bytes(i, 1)
+    assert nbytes == off
+    assert all(i["slice_of"] == -1 for i in infos)
+
+
+def test_layout_flags_turn_the_options_off():
+    ops = wl.resnet50_ops()
+    infos, nbytes = plan(ops, (2, 3, 224, 224), "c2", plain_layout=True, fuse=False)
+    assert not any(i["deinterleaved"] for i in infos)
+    assert all(i["fused_into"] == -1 for i in infos)
+    full, nfull = plan(ops, (2, 3, 224, 224), "c2")
+    assert nbytes <= nfull          # a plain layout never needs more room
+
+
+def test_mobilenet_layout():
+    for ops, fused_names in ((wl.mobilenet_v1_ops(), ["dw13"]),
+                             (wl.mobilenet_v2_ops(), ["b15_dw", "b16_dw", "b17_dw"])):
+        infos, _ = plan(ops, (1, 3, 224, 224), "mb")
+        got = [o.name for o, i in zip(ops, infos) if o.kind == "dwconv" and i["fused_into"] >= 0]
+        assert got == fused_names
+        for o, i in zip(ops, infos):
+            if o.kind == "dwconv" and i["fused_into"] >= 0:
+                assert ops[i["fused_into"]].dst == o.src          # computed by the layer that feeds it
+            nxt = next((r for r in ops[ops.index(o) + 1:] if r.src == o.dst), None)
+            if nxt is not None and nxt.kind == "dwconv":
+                assert (i["halo_h"], i["halo_w"]) == (1, 1), o.name
+        assert not any(i["deinterleaved"] for i in infos)         # depthwise readers take plain tensors
+
+
+def test_inception_concatenations_are_written_in_place():
+    ops = wl.inception_v3_ops()
+    infos, nbytes = plan(ops, (1, 3, 299, 299), "iv3")
+    idx_of_dst = {o.dst: k for k, o in enumerate(ops)}
+    cats = [k for k, o in enumerate(ops) if o.kind == "concat"]
+    assert len(cats) == 11
+    shapes = wl.buffer_shapes(ops, (1, 3, 299, 299))
+    total_slices = 0
+    for k in cats:
+        cat, ci = ops[k], infos[k]
+        ch = 0
+        for b in cat.srcs:
+            p = idx_of_dst[b]
+            pi = infos[p]
+            assert pi["slice_of"] == k and pi["slice_channel"] == ch, (cat.name, ops[p].name)
+            # same planes, same halo, same image stride; starts ch planes into the region
+            assert (pi["halo_h"], pi["halo_w"], pi["pitch"], pi["plane"], pi["image"]) == \
+                   (ci["halo_h"], ci["halo_w"], ci["pitch"], ci["plane"], ci["image"])
+            assert pi["offset"] == ci["offset"] + ch * ci["plane"] * 4
+            ch += shapes[b][1]
+            total_slices += 1
+        assert ch == shapes[cat.dst][1] and ci["image"] == ch * ci["plane"]
+    assert total_slices == 46
+    # concatenations are read by 1x1 layers and pools only: no halo; the halo of a branch's
+    # intermediate tensor is the padding of the filter that reads it (5x5: 2, 7 taps: 3, 3x3: 1)
+    assert all(infos[k]["halo_h"] == 0 and infos[k]["halo_w"] == 0 for k in cats)
+    halo = {o.name: (i["halo_h"], i["halo_w"]) for o, i in zip(ops, infos)}
+    assert halo["a1_5x5a"] == (2, 2) and halo["c1_7a"] == (3, 3) and halo["a1_3x3a"] == (1, 1)
+    assert halo["e1_3a"] == (1, 1) and halo["stem3"] == (0, 0) and halo["stem2"] == (1, 1)
+    # the workspace holds every region that is not a slice of another
+    off = sum(region_bytes(i, 1) for i in infos[:-1] if i["slice_of"] < 0)
+    assert nbytes == off
+
+
+def test_concat_copy_cases_are_not_in_place():
+    Op = wl.Op
+    ops = [Op("conv", "a", 0, 1, 4, 6, 1, 1, 0, 0.5, True),
+           Op("conv", "b", 1, 2, 6, 6, 3, 1, 1, 0.5, True),            # buffer 1 has a second reader
+           Op("concat", "inner", 1, 3, srcs=(1, 2)),
+           Op("concat", "outer", 3, 4, srcs=(3, 0))]                    # a concatenation and the net input
+    infos, _ = plan(ops, (1, 4, 8, 8), "cc")
+    assert infos[0]["slice_of"] == -1            # two readers
+    assert infos[1]["slice_of"] == 2 and infos[1]["slice_channel"] == 6
+    assert infos[2]["slice_of"] == -1            # a nested concatenation is copied
+
+
+def test_op_info_errors():
+    L = cad.lib()
+    import ctypes
+    net = ctypes.c_void_p()
+    assert L.cadnn_net_create(0, 1, 4, 8, 8, ctypes.byref(net)) == 0
+    assert L.cadnn_net_add_maxpool(net, 2, 2, 0, 0, 1) == 0
+    info = cad.OpInfo()
+    assert L.cadnn_net_op_info(net, 1, 0, ctypes.byref(info)) == 1
+    assert L.cadnn_net_op_info(net, 0, 0, None) == 1
+    assert L.cadnn_net_op_info(net, 0, 0, ctypes.byref(info)) == 0 and info.pitch == 4
+    srcs = (ctypes.c_int * 2)(0, 1)
+    assert L.cadnn_net_add_concat(net, srcs, 2, 2) == 1           # 8x8 and 4x4 do not stack
+    assert L.cadnn_net_add_concat(net, srcs, 0, 2) == 1
+    assert L.cadnn_net_add_avgpool(net, 3, 1, 1, 1, 1) == 1       # dst aliases src
+    assert L.cadnn_net_add_avgpool(net, 3, 1, 1, 1, 2) == 0
+    assert L.cadnn_net_free(net) == 0
