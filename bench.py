@@ -116,6 +116,8 @@ def main() -> int:
                     help="also time every distinct convolution of the workload as a DENSE layer on the same GPU: "
                          "the library's own MFMA implicit GEMM and MIOpen through torch.nn.functional.conv2d "
                          "(the only use of torch compute anywhere: a comparator)")
+    ap.add_argument("--no-fusion", action="store_true", help="launch every op on its own (CADNN_NET_NO_FUSION)")
+    ap.add_argument("--plain-layout", action="store_true", help="no de-interleaved tensors (CADNN_NET_PLAIN_LAYOUT)")
     ap.add_argument("--no-layer-profile", action="store_true",
                     help="skip the per-op event pass (for clean rocprofv3 kernel statistics)")
     args = ap.parse_args()
@@ -171,7 +173,7 @@ def main() -> int:
         args.load_tune = ""     # (the saved choice that ships with the package is for the default workload)
     def make_net(live_tune):
         return cad.build_net(ops, ws, bs, shape, cad.F16 if dt == "f16" else cad.F32, use_graph=not args.no_graph,
-                             tune=live_tune)
+                             tune=live_tune, fuse=not args.no_fusion, plain_layout=args.plain_layout)
 
     net = make_net(not (args.no_tune or args.load_tune))
     tuning = "none" if args.no_tune else "live"

@@ -111,29 +111,76 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 
-// Activations of one nonzero for the P pixels of a lane.
+// Activations of one nonzero for the P pixels of a lane: fp32 values, or -- in 2-byte storage --
+// the raw halves as loaded (one per register when the pixels are 64 apart, packed pairs when
+// they are adjacent), which the mixed-precision FMA below consumes without a conversion.
+template <typename T, int P, int ADJ>
+struct LinX {
+    float v[P];
+};
+template <int P, int ADJ>
+struct LinX<_Float16, P, ADJ> {
+    uint32_t r[(ADJ != 0 && P > 1) ? P / 2 : P];
+};
+
 template <typename T, int P, int ADJ>
 __device__ __forceinline__ void lin_fetch(__amdgpu_buffer_rsrc_t r, const uint32_t (&voff)[P], uint32_t soff,
-                                          float (&x)[P]) {
-    if constexpr (ADJ == 0 || P == 1) {
+                                          LinX<T, P, ADJ>& x) {
+    if constexpr (sizeof(T) == 4) {
+        if constexpr (ADJ == 0 || P == 1) {
 #pragma unroll
-        for (int j = 0; j < P; ++j) x[j] = lin_load<T>(r, voff[j], soff);
-    } else if constexpr (sizeof(T) == 4 && P == 2) {
-        const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(r, voff[0], soff, 0);
-        x[0] = __uint_as_float(v[0]); x[1] = __uint_as_float(v[1]);
-    } else if constexpr (sizeof(T) == 4 && P == 4) {
-        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, voff[0], soff, 0);
-        x[0] = __uint_as_float(v[0]); x[1] = __uint_as_float(v[1]);
-        x[2] = __uint_as_float(v[2]); x[3] = __uint_as_float(v[3]);
-    } else if constexpr (sizeof(T) == 2 && P == 2) {
-        const uint32_t v = __builtin_amdgcn_raw_buffer_load_b32(r, voff[0], soff, 0);
-        const f16x2 h = __builtin_bit_cast(f16x2, v);
-        x[0] = (float)h[0]; x[1] = (float)h[1];
+            for (int j = 0; j < P; ++j) x.v[j] = lin_load<T>(r, voff[j], soff);
+        } else if constexpr (P == 2) {
+            const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(r, voff[0], soff, 0);
+            x.v[0] = __uint_as_float(v[0]); x.v[1] = __uint_as_float(v[1]);
+        } else {
+            static_assert(P == 4, "unsupported adjacent-pixel width");
+            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, voff[0], soff, 0);
+            x.v[0] = __uint_as_float(v[0]); x.v[1] = __uint_as_float(v[1]);
+            x.v[2] = __uint_as_float(v[2]); x.v[3] = __uint_as_float(v[3]);
+        }
     } else {
-        static_assert(sizeof(T) == 2 && P == 4, "unsupported adjacent-pixel width");
-        const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(r, voff[0], soff, 0);
-        const f16x4 h = __builtin_bit_cast(f16x4, v);
-        x[0] = (float)h[0]; x[1] = (float)h[1]; x[2] = (float)h[2]; x[3] = (float)h[3];
+        if constexpr (ADJ == 0 || P == 1) {
+#pragma unroll
+            for (int j = 0; j < P; ++j) x.r[j] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(r, voff[j], soff, 0);
+        } else if constexpr (P == 2) {
+            x.r[0] = __builtin_amdgcn_raw_buffer_load_b32(r, voff[0], soff, 0);
+        } else {
+            static_assert(P == 4, "unsupported adjacent-pixel width");
+            const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(r, voff[0], soff, 0);
+            x.r[0] = v[0]; x.r[1] = v[1];
+        }
+    }
+}
+
+// acc + w * (the low / high half of xh as binary16), one instruction, the product and sum in
+// fp32: what a conversion followed by an fp32 FMA computes, bit for bit.
+__device__ __forceinline__ float fma_mix_lo(float w, uint32_t xh, float acc) {
+    float d;
+    asm("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[0,0,0] op_sel_hi:[0,1,0]" : "=v"(d) : "s"(w), "v"(xh), "v"(acc));
+    return d;
+}
+__device__ __forceinline__ float fma_mix_hi(float w, uint32_t xh, float acc) {
+    float d;
+    asm("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[0,1,0] op_sel_hi:[0,1,0]" : "=v"(d) : "s"(w), "v"(xh), "v"(acc));
+    return d;
+}
+
+// acc[j] += w * x[j] for the P pixels of a lane (w is wave-uniform).
+template <typename T, int P, int ADJ>
+__device__ __forceinline__ void lin_mac(float w, const LinX<T, P, ADJ>& x, float (&acc)[P]) {
+    if constexpr (sizeof(T) == 4) {
+#pragma unroll
+        for (int j = 0; j < P; ++j) acc[j] = fmaf(w, x.v[j], acc[j]);
+    } else if constexpr (ADJ == 0 || P == 1) {
+#pragma unroll
+        for (int j = 0; j < P; ++j) acc[j] = fma_mix_lo(w, x.r[j], acc[j]);
+    } else {
+#pragma unroll
+        for (int k = 0; k < P / 2; ++k) {
+            acc[2 * k] = fma_mix_lo(w, x.r[k], acc[2 * k]);
+            acc[2 * k + 1] = fma_mix_hi(w, x.r[k], acc[2 * k + 1]);
+        }
     }
 }
 
@@ -147,7 +194,8 @@ __device__ __forceinline__ void lin_accumulate(__amdgpu_buffer_rsrc_t rsrc, cons
     constexpr int P = Cfg::P, U = Cfg::U, ADJ = Cfg::ADJ;
     win.seek(i);
     int groups = (end - i) / U;
-    float wa[U], xa[U][P], wb[U], xb[U][P];
+    float wa[U], wb[U];
+    LinX<T, P, ADJ> xa[U], xb[U];
     uint32_t oa[U], ob[U];
     win.group<U>(i, wa, oa);
 #pragma unroll
@@ -155,32 +203,24 @@ __device__ __forceinline__ void lin_accumulate(__amdgpu_buffer_rsrc_t rsrc, cons
     while (true) {
         if (groups == 1) {
 #pragma unroll
-            for (int u = 0; u < U; ++u)
-#pragma unroll
-                for (int j = 0; j < P; ++j) acc[j] = fmaf(wa[u], xa[u][j], acc[j]);
+            for (int u = 0; u < U; ++u) lin_mac<T, P, ADJ>(wa[u], xa[u], acc);
             break;
         }
         win.group<U>(i + U, wb, ob);
 #pragma unroll
         for (int u = 0; u < U; ++u) lin_fetch<T, P, ADJ>(rsrc, voff, ob[u], xb[u]);
 #pragma unroll
-        for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int j = 0; j < P; ++j) acc[j] = fmaf(wa[u], xa[u][j], acc[j]);
+        for (int u = 0; u < U; ++u) lin_mac<T, P, ADJ>(wa[u], xa[u], acc);
         if (groups == 2) {
 #pragma unroll
-            for (int u = 0; u < U; ++u)
-#pragma unroll
-                for (int j = 0; j < P; ++j) acc[j] = fmaf(wb[u], xb[u][j], acc[j]);
+            for (int u = 0; u < U; ++u) lin_mac<T, P, ADJ>(wb[u], xb[u], acc);
             break;
         }
         win.group<U>(i + 2 * U, wa, oa);
 #pragma unroll
         for (int u = 0; u < U; ++u) lin_fetch<T, P, ADJ>(rsrc, voff, oa[u], xa[u]);
 #pragma unroll
-        for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int j = 0; j < P; ++j) acc[j] = fmaf(wb[u], xb[u][j], acc[j]);
+        for (int u = 0; u < U; ++u) lin_mac<T, P, ADJ>(wb[u], xb[u], acc);
         groups -= 2;
         i += 2 * U;
     }
