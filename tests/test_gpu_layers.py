@@ -273,6 +273,7 @@ VARIANT_GEOMS = [
     (37, 70, 3, 2, 1, 21, 17, 0.5, 2),    # dense enough for the matrix-core fallback too
     (19, 33, 1, 1, 0, 9, 9, 0.0, 1),
     (40, 24, 1, 1, 0, 12, 20, 0.8, 2),    # even width: adjacent-pixel wide loads
+    (40, 3, 3, 2, 1, 30, 27, 0.0, 2),     # unpruned, few input channels (a network's first layer)
 ]
 
 
