@@ -341,6 +341,8 @@ def test_dense_comparator(cad, geom):
 
 
 @pytest.mark.parametrize("geom", [(24, 20, 3, 1, 1, 18, 20, 0.8, 2), (16, 12, 3, 2, 1, 15, 17, 0.7, 1),
+                                  # odd widths over several pixel tiles: the ragged-row variants
+                                  (24, 20, 3, 1, 1, 13, 19, 0.8, 2), (10, 14, 5, 1, 2, 21, 35, 0.8, 1),
                                   (130, 9, 3, 1, 1, 7, 7, 0.9, 1), (12, 10, 3, 1, 1, 14, 14, 0.5, 1),
                                   # enough channels that the LDS families stage them chunk by chunk
                                   (600, 12, 3, 1, 1, 14, 14, 0.9, 1), (520, 8, 3, 2, 1, 14, 14, 0.9, 2)])
@@ -362,6 +364,8 @@ def test_every_variant_on_a_haloed_input(cad, geom):
         net = cad.build_net(ops, ws, bs, shape, dtype, use_graph=False)
         names = net.op_candidates(1)
         assert any(nm.startswith("slinear") for nm in names), names
+        if stride == 1 and w_ % 2 == 1:
+            assert any("_g2_" in nm for nm in names) and any("_g4_" in nm for nm in names), names
         xd = dev(xs)
         for name in names:
             net.set_op_variant(1, name)
