@@ -1,0 +1,146 @@
+"""GPU parity on seeded random op graphs: convolutions (1x1 / 3x3, strides 1 and 2, residuals),
+depthwise layers, pools and concatenations wired at random, so that the runner's layout
+decisions (halos, de-interleaved tensors, fusions, in-place concatenation) meet in combinations
+the hand-written nets do not contain.  Every buffer that is still materialised and the output
+are compared with the oracle, with the default options and with them turned off."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+from util import TOL_F32, TOL_F16, rel_errors
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def cad():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_1905_00571_amd as cad
+    cad.lib()
+    return cad
+
+
+def out_hw(h, k, s, p):
+    return (h + 2 * p - k) // s + 1
+
+
+def random_net(seed):
+    g = np.random.default_rng(1000 + seed)
+    n = int(g.integers(1, 3))
+    even = g.random() < 0.6           # even sizes open the de-interleaved layout to stride-2 readers
+    dim = lambda: int(g.integers(5, 11)) * 2 if even else int(g.integers(9, 21))
+    shape = (n, int(g.integers(3, 9)), dim(), dim())
+    shapes = {0: shape}
+    ops = []
+    nxt = 1
+    cur = 0
+    for step in range(int(g.integers(8, 15))):
+        # mostly continue from the newest buffer, sometimes branch from an older one
+        src = cur if g.random() < 0.75 else int(g.choice(list(shapes)))
+        _, c, h, w = shapes[src]
+        kind = g.choice(["conv", "conv", "conv", "conv", "block", "block", "dwconv", "maxpool", "avgpool2d", "concat"])
+        dst = nxt
+        if kind == "block":
+            # a bottleneck: 1x1 -> 3x3 (stride s) -> 1x1 + shortcut (a 1x1 / stride s projection,
+            # or the block input when the shapes agree), the pattern of the residual networks
+            s_ = int(g.choice([1, 2])) if min(h, w) >= 8 else 1
+            mid, cout = int(g.integers(4, 13)), int(g.integers(8, 25))
+            sp = float(g.choice([0.8, 0.85, 0.9]))
+            project = s_ == 2 or g.random() < 0.5
+            if not project:
+                cout = c
+            a_, b_, p_, c_ = nxt, nxt + 1, nxt + 2, nxt + 3
+            ho, wo = out_hw(h, 3, s_, 1), out_hw(w, 3, s_, 1)
+            ops.append(wl.Op("conv", f"blk{step}a", src, a_, c, mid, 1, 1, 0, sp, True))
+            ops.append(wl.Op("conv", f"blk{step}b", a_, b_, mid, mid, 3, s_, 1, sp, True))
+            shapes[a_] = (n, mid, h, w)
+            shapes[b_] = (n, mid, ho, wo)
+            if project:
+                ops.append(wl.Op("conv", f"blk{step}p", src, p_, c, cout, 1, s_, 0, sp, False))
+                shapes[p_] = (n, cout, ho, wo)
+            ops.append(wl.Op("conv", f"blk{step}c", b_, c_, mid, cout, 1, 1, 0, sp, True, p_ if project else src))
+            shapes[c_] = (n, cout, ho, wo)
+            cur = c_
+            nxt += 4
+            continue
+        if kind == "conv":
+            k = int(g.choice([1, 1, 3]))
+            s = int(g.choice([1, 1, 2])) if min(h, w) >= 6 else 1
+            cout = int(g.integers(4, 25))
+            o = (n, cout, out_hw(h, k, s, k // 2), out_hw(w, k, s, k // 2))
+            res = -1
+            same = [b for b, sh in shapes.items() if sh == o and b != src]
+            if same and g.random() < 0.5:
+                res = int(g.choice(same))
+            ops.append(wl.Op("conv", f"conv{step}", src, dst, c, cout, k, s, k // 2,
+                             float(g.choice([0.5, 0.8, 0.85, 0.9])), bool(g.random() < 0.7), res))
+        elif kind == "dwconv":
+            s = int(g.choice([1, 2])) if min(h, w) >= 6 else 1
+            o = (n, c, out_hw(h, 3, s, 1), out_hw(w, 3, s, 1))
+            ops.append(wl.Op("dwconv", f"dw{step}", src, dst, c, c, 3, s, 1, 0.0, True))
+        elif kind in ("maxpool", "avgpool2d"):
+            k, s, p = [(2, 2, 0), (3, 2, 1), (3, 1, 1)][int(g.integers(0, 3))]
+            if min(h, w) < 4:
+                k, s, p = 3, 1, 1
+            o = (n, c, out_hw(h, k, s, p), out_hw(w, k, s, p))
+            ops.append(wl.Op(kind, f"{kind}{step}", src, dst, k=k, stride=s, pad=p))
+        else:
+            mates = [b for b, sh in shapes.items() if sh[0] == n and sh[2:] == (h, w) and b != src]
+            if not mates:
+                continue
+            parts = [src] + [int(b) for b in g.choice(mates, size=min(len(mates), int(g.integers(1, 3))), replace=False)]
+            o = (n, sum(shapes[b][1] for b in parts), h, w)
+            ops.append(wl.Op("concat", f"cat{step}", parts[0], dst, srcs=tuple(parts)))
+        shapes[dst] = o
+        cur = dst
+        nxt += 1
+    _, c, h, w = shapes[cur]
+    ops.append(wl.Op("avgpool", "gap", cur, nxt))
+    ops.append(wl.Op("fc", "fc", nxt, nxt + 1, c, 7, sparsity=0.5, relu=False))
+    return ops, shape
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_net(cad, seed):
+    ops, shape = random_net(seed)
+    f16 = seed % 4 == 3
+    dtype, npdt, tol = (cad.F16, np.float16, TOL_F16) if f16 else (cad.F32, np.float32, TOL_F32)
+    x, ws, bs = wl.net_tensors(ops, f"rnd{seed}", shape, input_relu=True)
+    xs = x.astype(npdt)
+    ref, ins, outs = oracle.run_net(ops, xs, ws, bs, dtype=npdt)
+    last_writer = {}
+    for i, o in enumerate(ops):
+        last_writer[o.dst] = i
+    # intermediate maps: a chain gate on the whole tensor (each is several layers deep)
+    mid_tol = 5e-2 if f16 else 1e-3
+    configs = [{}, {"plain_layout": True, "fuse": False}, {"use_graph": False}]
+    if seed % 5 == 0:
+        configs.append({"tune": True})      # every layer's candidates timed on the net's own buffers first
+    for kw in configs:
+        args = dict(use_graph=True)
+        args.update(kw)
+        net = cad.build_net(ops, ws, bs, shape, dtype, **args)
+        for rep in range(2):
+            y = net.run(torch.from_numpy(xs).cuda())
+            torch.cuda.synchronize()
+            got = y.cpu().numpy()
+            assert np.isfinite(got).all()
+            e = rel_errors(got, ref)[0]
+            assert e <= (tol * 5 if f16 else tol), (seed, kw, rep, e, [o.kind for o in ops])
+        checked = 0
+        for i, o in enumerate(ops[:-1]):
+            if last_writer[o.dst] != i:
+                continue                       # the id was reused: the runner reports the last writer
+            try:
+                mid = net.read_buffer(o.dst, outs[i].shape)
+            except cad.CadnnError:
+                continue                       # never materialised (computed inside another op)
+            e = rel_errors(mid, outs[i])[0]
+            assert np.isfinite(mid).all() and e <= mid_tol, (seed, kw, o.name, e)
+            checked += 1
+        assert checked >= len(ops) // 2
+        net.free()
