@@ -132,8 +132,9 @@ static std::vector<const ConvVariant*> candidates(const cadnn_weights* w, const 
 // a wave's own latency chain times the rounds of waves the chip needs, the vector issue
 // slots all waves consume (prologue + instructions per nonzero), and the L1 cache-line
 // traffic (32 bytes per cycle per CU; a stride-2 lane pattern touches twice the lines) --
-// with constants fitted to the tuner's timings of every variant on ResNet-50 and VGG-16
-// at batch 1 and ResNet-50 at batch 8 (its pick costs 7-10 % over the tuned choice).
+// with constants fitted to the tuner's timings of every variant on ResNet-50, VGG-16,
+// MobileNet-V1 and Inception-V3 at batch 1 and ResNet-50 at batch 8 (its pick costs 8-15 %
+// over the tuned choice; the fit leaves the L1 term almost no weight).
 static const ConvVariant* heuristic_variant(const cadnn_weights* w, const ConvGeom& g) {
     const std::vector<const ConvVariant*> cand = candidates(w, g);
     if (cand.empty()) return nullptr;
@@ -160,11 +161,11 @@ static const ConvVariant* heuristic_variant(const cadnn_weights* w, const ConvGe
             const double line_bytes = 256.0 * P * ((g.stride == 2 && !g.xd.s2d) ? 2.0 : 1.0);
             const double t_l1 = waves * iters * line_bytes / 32.0 / 256.0;
             const double instrs = v->adjacent ? 3.0 + P : 2.0 + 2.0 * P;
-            const double t_issue = waves * (1156.0 + iters * instrs * 1.33) / 1024.0;
-            const double per_nz = 68.7 * (1.0 + 0.65 * (P - 1)) / (1.0 + 0.277 * std::log2(v->unroll / 4.0));
-            const double t_wave = 250.0 + iters * per_nz + (v->ks > 1 ? 486.0 * std::log2((double)v->ks) : 0.0);
+            const double t_issue = waves * (1787.0 + iters * instrs * 1.21) / 1024.0;
+            const double per_nz = 77.4 * (1.0 + 0.51 * (P - 1)) / (1.0 + 0.079 * std::log2(v->unroll / 4.0));
+            const double t_wave = 382.0 + iters * per_nz + (v->ks > 1 ? 338.0 * std::log2((double)v->ks) : 0.0);
             const double rounds = std::ceil(waves / (1024.0 * 2.3));
-            cost = std::max(std::max(t_wave * rounds, t_issue), 0.52 * t_l1);
+            cost = std::max(std::max(t_wave * rounds, t_issue), 0.078 * t_l1);
             if (v->family == FAM_DIRECT) cost *= 1.3;   // per-lane tap offsets, bounds by range check
         } else {
             const double tiles = std::ceil((double)g.wout / v->tw) * std::ceil((double)g.hout / v->th) * g.n;
