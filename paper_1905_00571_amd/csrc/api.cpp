@@ -85,7 +85,8 @@ static bool variant_fits(const ConvVariant& v, const cadnn_weights* w, const Con
         const bool shortcut = g.ex && g.ex->w, pooled = g.ex && g.ex->pool_y, dwf = g.ex && g.ex->dw;
         if (shortcut != (v.dual != 0) || pooled != (v.pool != 0) || dwf != (v.dw != 0)) return false;
         // a fused depthwise layer needs the whole image, at most 16 x 16, in one pixel tile
-        if (dwf && (general || g.hout * g.wout > 64 * v.p || g.hout > 16 || g.wout > 16)) return false;
+        // (one wavefront's pixels, or -- tile-per-wave instantiations -- the four waves' of a workgroup)
+        if (dwf && (general || g.hout * g.wout > 64 * v.p * (v.dw == 2 ? 4 : 1) || g.hout > 16 || g.wout > 16)) return false;
         // a fused pool needs the whole image in one pixel tile of the variant
         if (pooled && (general || shortcut || g.hout * g.wout > 64 * v.p)) return false;
         if (shortcut) {
@@ -261,6 +262,7 @@ static cadnn_status launch_variant(const cadnn_weights* w, const ConvVariant* v,
         a.wq = (v->family == FAM_LINEAR && v->adjacent == 2) ? (g.wout + v->p - 1) / v->p * v->p : g.wout;
         a.hwq = g.hout * a.wq;
         a.tiles_x = (a.hwq + 64 * v->p - 1) / (64 * v->p);
+        if (v->family == FAM_LINEAR && v->dw == 2) a.tiles_x = 1;    // the workgroup's waves are the tiles
         a.tiles_y = 1;
     }
     a.row_groups = plan->rows_padded / v->rows_per_block();

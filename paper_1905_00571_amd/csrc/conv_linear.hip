@@ -55,6 +55,7 @@ struct LinearCfg {
                          POOL = POOL_, DW = DW_;
     static_assert(!(S2D && DUAL) && !(POOL && (S2D || DUAL || ADJ)), "not combined");
     static_assert(!(DW && (S2D || DUAL || POOL)), "not combined");
+    static_assert(DW != 2 || (KS == 1 && ADJ == 0), "tile-per-wave depthwise fusion takes whole rows per wave");
     static_assert(!(ADJ && S2D), "adjacent pixels are not adjacent in a de-interleaved tensor");
     static_assert(ADJ != 2 || (!DUAL && !POOL), "not combined");
     static constexpr int RG = NW / KS;
@@ -251,15 +252,18 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_linear_kernel(const ConvLa
 
     const int lane = threadIdx.x & 63;
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int rg = wv / KS, ks = wv % KS;
+    // (DW = 2: the waves of a workgroup take the pixel tiles of ONE group of rows instead of
+    // different rows of one pixel tile, so that a channel's whole image meets in LDS)
+    constexpr bool TW = Cfg::DW == 2;
+    const int rg = TW ? 0 : wv / KS, ks = TW ? 0 : wv % KS;
     const int n = blockIdx.z;
     // Workgroups in plain launch order.  (Die-aware placements were measured -- workgroup
     // L runs on die L % 8: giving each die its own pixel tiles leaves most of the chip idle
     // on layers with few tiles and gains nothing on the others, and giving each die its
     // own rows changes nothing.)
-    const int tile = blockIdx.x, grp = blockIdx.y;
+    const int tile = TW ? wv : (int)blockIdx.x, grp = blockIdx.y;
     const int q0 = tile * (64 * P);
-    const int row0 = (grp * RG + rg) * RPW;
+    const int row0 = TW ? grp * RPW : (grp * RG + rg) * RPW;
 
     // byte offset of tap (0,0) of each of the lane's pixels inside the padded image (in a
     // de-interleaved input the taps of a stride-2 layer follow at the plan's offsets too)
@@ -423,35 +427,44 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_linear_kernel(const ConvLa
         //      wave's channels is in this wave.  It goes, rounded to the storage type as the
         //      separate layer would have read it, into a zero-haloed LDS plane of the wave's
         //      own; the lanes then take the depthwise outputs of the channel from there.
-        __shared__ float dwbuf[Cfg::RG][kDwPlaneMax];
+        __shared__ float dwbuf[TW ? 1 : Cfg::RG][kDwPlaneMax];
         float* pl = dwbuf[rg];
         const int pitch = a.yd.w + 2;
-        for (int i = lane; i < (a.yd.h + 2) * pitch; i += 64) pl[i] = 0.0f;
+        // who shares a plane: the wave alone, or (tile per wave) the whole workgroup
+        const int me = TW ? (int)threadIdx.x : lane, team = TW ? Cfg::THREADS : 64;
+        auto team_sync = [&]() {
+            if constexpr (TW) {
+                __syncthreads();
+            } else {
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            }
+        };
+        for (int i = me; i < (a.yd.h + 2) * pitch; i += team) pl[i] = 0.0f;
         T* __restrict__ y2 = (T*)a.dw_y + (size_t)n * a.dw_yd.image;
         const int w2 = a.dw_yd.w, hw2 = a.dw_yd.h * w2;
 #pragma unroll
         for (int r = 0; r < RPW; ++r) {
             const int co = co_[r];
             if (co < 0) continue;
-            // (the previous channel's reads are done before its plane is overwritten)
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
+            // (the previous channel's reads are done before its plane is overwritten; co is the
+            // same for every wave that shares the plane, so they all come here)
+            team_sync();
 #pragma unroll
             for (int j = 0; j < P; ++j) {
                 if (oidx[j] >= 0) {
-                    const int q = ADJ ? lane * P + j : j * 64 + lane;
+                    const int q = q0 + (ADJ ? lane * P + j : j * 64 + lane);
                     const int oh = q / a.yd.w, ow = q - oh * a.yd.w;
                     float v = acc[r][j] + bias_[r] + resv[r][j];
                     if (a.relu) v = v > 0.0f ? v : 0.0f;
                     pl[(oh + 1) * pitch + ow + 1] = (float)(T)v;
                 }
             }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            team_sync();
             const float* __restrict__ wt = a.dw_w + (size_t)co * 9;
             const float b2 = a.dw_bias ? a.dw_bias[co] : 0.0f;
-            for (int t = lane; t < hw2; t += 64) {
+            for (int t = me; t < hw2; t += team) {
                 const int oh2 = t / w2, ow2 = t - oh2 * w2;
                 const float* tap = pl + oh2 * a.dw_stride * pitch + ow2 * a.dw_stride;
                 float sum = 0.0f;
@@ -511,6 +524,7 @@ static ConvVariant make_linear(const char* name) {
     v.dual = Cfg::DUAL;
     v.pool = Cfg::POOL;
     v.dw = Cfg::DW;
+    if (Cfg::DW == 2) v.nw = 1;      // rows per workgroup = RPW: its waves split the pixels, not the rows
     v.lds_bytes = Cfg::KS > 1 ? (size_t)Cfg::NW * Cfg::RPW * Cfg::P * 64 * 4 : 0;
     v.launch = &launch_linear<Cfg>;
     return v;
@@ -540,7 +554,15 @@ static ConvVariant make_linear(const char* name) {
 #define CADNN_LINEAR_DW(T, P, RPW, KS, NW, U) \
     make_linear<LinearCfg<T, P, RPW, KS, NW, U, 0, 0, 0, 0, 1>>("slinear_" #T "_dw" #P "_r" #RPW "k" #KS "w" #NW "u" #U)
 
+#define CADNN_LINEAR_DW_TILES(T, RPW, U) \
+    make_linear<LinearCfg<T, 1, RPW, 1, 4, U, 0, 0, 0, 0, 2>>("slinear_" #T "_dt1_r" #RPW "k1w4u" #U)
+
 #define CADNN_LINEAR_SHAPES(T)          \
+    CADNN_LINEAR_DW_TILES(T, 1, 4), \
+    CADNN_LINEAR_DW_TILES(T, 1, 8), \
+    CADNN_LINEAR_DW_TILES(T, 1, 16), \
+    CADNN_LINEAR_DW_TILES(T, 2, 4), \
+    CADNN_LINEAR_DW_TILES(T, 2, 8), \
     CADNN_LINEAR_RAGGED(T, 2, 1, 1, 4, 4), \
     CADNN_LINEAR_RAGGED(T, 2, 1, 1, 4, 8), \
     CADNN_LINEAR_RAGGED(T, 2, 1, 2, 4, 4), \

@@ -515,10 +515,12 @@ def test_fused_global_average_pool(cad, geom):
         unfused.free()
 
 
-@pytest.mark.parametrize("geom", [(7, 7, 1, 1, 1), (8, 8, 2, 3, 2), (5, 9, 3, 1, 2), (4, 16, 1, 3, 1)])
+@pytest.mark.parametrize("geom", [(7, 7, 1, 1, 1), (8, 8, 2, 3, 2), (5, 9, 3, 1, 2), (4, 16, 1, 3, 1),
+                                  (14, 14, 1, 1, 1), (14, 14, 2, 3, 2), (16, 16, 1, 3, 1), (9, 13, 2, 1, 2)])
 def test_fused_depthwise_epilogue(cad, geom):
-    """A 3x3 depthwise layer that is the only reader of a convolution whose image fits one
-    wavefront is computed in that convolution's epilogue: the depthwise op reports "fused",
+    """A 3x3 depthwise layer that is the only reader of a convolution whose image is at most
+    16 x 16 (one wavefront's pixels, or the four waves' of a workgroup) is computed in that
+    convolution's epilogue: the depthwise op reports "fused",
     the convolution's own map is never materialised, and every such variant of the convolution
     must reproduce the oracle's depthwise output (checked element by element against the
     depthwise layer's own bound on the oracle's input) and the layers behind it."""
@@ -540,7 +542,7 @@ def test_fused_depthwise_epilogue(cad, geom):
         with pytest.raises(cad.CadnnError):
             net.read_buffer(2, outs[1].shape)
         names = net.op_candidates(1)
-        assert names and all("_dw" in nm for nm in names), names
+        assert names and all("_dw" in nm or "_dt" in nm for nm in names), names
         dw_ref = outs[2].astype(np.float64)
         # bound of the fused pair on the oracle's input to the pair: the depthwise layer's own
         # condition sum plus what the first layer's rounding error becomes behind |filters|
