@@ -233,7 +233,7 @@ cadnn_status cadnn_net_workspace_bytes(const cadnn_net* net, size_t* bytes);
  * whose only reader adds it as residual is computed inside that reader, and a global
  * average pool that is the only reader of a small-image convolution is computed in that
  * convolution's epilogue, and so is a 3x3 depthwise layer (padding 1, stride 1 or 2) that is
- * the only reader of a convolution with an image of at most 16 x 16 (the skipped op's
+ * the only reader of a convolution with an image of at most 28 x 28 (the skipped op's
  * profile time is zero and its variant name is "fused"; the buffer that is no longer
  * written is refused by cadnn_net_read_buffer). */
 #define CADNN_NET_GRAPH 1

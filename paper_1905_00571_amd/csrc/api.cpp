@@ -85,8 +85,8 @@ static bool variant_fits(const ConvVariant& v, const cadnn_weights* w, const Con
         const bool shortcut = g.ex && g.ex->w, pooled = g.ex && g.ex->pool_y, dwf = g.ex && g.ex->dw;
         if (shortcut != (v.dual != 0) || pooled != (v.pool != 0) || dwf != (v.dw != 0)) return false;
         // a fused depthwise layer needs the whole image, at most 16 x 16, in one pixel tile
-        // (one wavefront's pixels, or -- tile-per-wave instantiations -- the four waves' of a workgroup)
-        if (dwf && (general || g.hout * g.wout > 64 * v.p * (v.dw == 2 ? 4 : 1) || g.hout > 16 || g.wout > 16)) return false;
+        // (one wavefront's pixels, or -- tile-per-wave instantiations -- those of all the waves of a workgroup)
+        if (dwf && (general || g.hout * g.wout > 64 * v.p * (v.dw == 2 ? v.tw : 1) || g.hout > 28 || g.wout > 28)) return false;
         // a fused pool needs the whole image in one pixel tile of the variant
         if (pooled && (general || shortcut || g.hout * g.wout > 64 * v.p)) return false;
         if (shortcut) {

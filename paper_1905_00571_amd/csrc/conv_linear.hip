@@ -24,7 +24,7 @@
 
 namespace cadnn {
 
-constexpr int kDwPlaneMax = 18 * 18;            // fused depthwise: image sides up to 16, plus a 1-pixel halo
+constexpr int kDwPlaneMax = 30 * 30;            // fused depthwise: image sides up to 28, plus a 1-pixel halo
 constexpr uint32_t kLinOutOfRange = 0x7ffffff0u;   // beyond any buffer this library accepts
 
 // ADJ = 0: the P pixels of a lane are 64 apart (P wave-wide loads of one element each);
@@ -524,7 +524,10 @@ static ConvVariant make_linear(const char* name) {
     v.dual = Cfg::DUAL;
     v.pool = Cfg::POOL;
     v.dw = Cfg::DW;
-    if (Cfg::DW == 2) v.nw = 1;      // rows per workgroup = RPW: its waves split the pixels, not the rows
+    if (Cfg::DW == 2) {
+        v.nw = 1;                    // rows per workgroup = RPW: its waves split the pixels, not the rows
+        v.tw = Cfg::NW;              // ... this many waves, i.e. pixel tiles
+    }
     v.lds_bytes = Cfg::KS > 1 ? (size_t)Cfg::NW * Cfg::RPW * Cfg::P * 64 * 4 : 0;
     v.launch = &launch_linear<Cfg>;
     return v;
@@ -554,15 +557,18 @@ static ConvVariant make_linear(const char* name) {
 #define CADNN_LINEAR_DW(T, P, RPW, KS, NW, U) \
     make_linear<LinearCfg<T, P, RPW, KS, NW, U, 0, 0, 0, 0, 1>>("slinear_" #T "_dw" #P "_r" #RPW "k" #KS "w" #NW "u" #U)
 
-#define CADNN_LINEAR_DW_TILES(T, RPW, U) \
-    make_linear<LinearCfg<T, 1, RPW, 1, 4, U, 0, 0, 0, 0, 2>>("slinear_" #T "_dt1_r" #RPW "k1w4u" #U)
+#define CADNN_LINEAR_DW_TILES(T, RPW, NW, U) \
+    make_linear<LinearCfg<T, 1, RPW, 1, NW, U, 0, 0, 0, 0, 2>>("slinear_" #T "_dt1_r" #RPW "k1w" #NW "u" #U)
 
 #define CADNN_LINEAR_SHAPES(T)          \
-    CADNN_LINEAR_DW_TILES(T, 1, 4), \
-    CADNN_LINEAR_DW_TILES(T, 1, 8), \
-    CADNN_LINEAR_DW_TILES(T, 1, 16), \
-    CADNN_LINEAR_DW_TILES(T, 2, 4), \
-    CADNN_LINEAR_DW_TILES(T, 2, 8), \
+    CADNN_LINEAR_DW_TILES(T, 1, 4, 4), \
+    CADNN_LINEAR_DW_TILES(T, 1, 4, 8), \
+    CADNN_LINEAR_DW_TILES(T, 1, 4, 16), \
+    CADNN_LINEAR_DW_TILES(T, 2, 4, 4), \
+    CADNN_LINEAR_DW_TILES(T, 2, 4, 8), \
+    CADNN_LINEAR_DW_TILES(T, 1, 16, 4), \
+    CADNN_LINEAR_DW_TILES(T, 1, 16, 8), \
+    CADNN_LINEAR_DW_TILES(T, 2, 16, 4), \
     CADNN_LINEAR_RAGGED(T, 2, 1, 1, 4, 4), \
     CADNN_LINEAR_RAGGED(T, 2, 1, 1, 4, 8), \
     CADNN_LINEAR_RAGGED(T, 2, 1, 2, 4, 4), \

@@ -226,8 +226,8 @@ void layout(cadnn_net* net) {
             }
         }
         // A 3x3 depthwise layer (padding 1, stride 1 or 2) that is the only reader of a
-        // convolution whose image is at most 16 x 16 is computed in that convolution's
-        // epilogue: a wave (images of up to 64 pixels) or the four waves of a workgroup hold a
+        // convolution whose image is at most 28 x 28 is computed in that convolution's
+        // epilogue: a wave (images of up to 64 pixels) or the 4 or 16 waves of a workgroup hold a
         // whole channel there, which is all a depthwise filter needs.  The convolution's own
         // feature map is not written.
         for (int i = 0; i < nops; ++i) {
@@ -237,7 +237,7 @@ void layout(cadnn_net* net) {
             const bool c_one = c.kind == OP_CONV && c.w->kh == 1 && c.w->kw == 1;
             const bool ok = c.kind == OP_CONV && readers[d.src_inst] == 1 && c.shortcut < 0 && c.pool_op < 0 &&
                             c.fused_into < 0 && sparse_enough(c) && !c.yd.s2d && !c.xd.s2d && !(c.res >= 0 && c.rd.s2d) &&
-                            c.out.h <= 16 && c.out.w <= 16 && d.w->kh == 3 && d.w->kw == 3 && d.pad == 1 &&
+                            c.out.h <= 28 && c.out.w <= 28 && d.w->kh == 3 && d.w->kw == 3 && d.pad == 1 &&
                             (d.stride == 1 || d.stride == 2) && !d.yd.s2d &&
                             (c_one ? c.pad == 0 : (c.xd.ph >= c.pad && c.xd.pw >= c.pad));
             if (ok) {

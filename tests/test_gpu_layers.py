@@ -516,11 +516,12 @@ def test_fused_global_average_pool(cad, geom):
 
 
 @pytest.mark.parametrize("geom", [(7, 7, 1, 1, 1), (8, 8, 2, 3, 2), (5, 9, 3, 1, 2), (4, 16, 1, 3, 1),
-                                  (14, 14, 1, 1, 1), (14, 14, 2, 3, 2), (16, 16, 1, 3, 1), (9, 13, 2, 1, 2)])
+                                  (14, 14, 1, 1, 1), (14, 14, 2, 3, 2), (16, 16, 1, 3, 1), (9, 13, 2, 1, 2),
+                                  (28, 28, 1, 1, 2), (20, 27, 2, 3, 1)])
 def test_fused_depthwise_epilogue(cad, geom):
     """A 3x3 depthwise layer that is the only reader of a convolution whose image is at most
-    16 x 16 (one wavefront's pixels, or the four waves' of a workgroup) is computed in that
-    convolution's epilogue: the depthwise op reports "fused",
+    28 x 28 (one wavefront's pixels, or those of the 4 or 16 waves of a workgroup) is computed
+    in that convolution's epilogue: the depthwise op reports "fused",
     the convolution's own map is never materialised, and every such variant of the convolution
     must reproduce the oracle's depthwise output (checked element by element against the
     depthwise layer's own bound on the oracle's input) and the layers behind it."""

@@ -58,8 +58,8 @@ def test_layout_flags_turn_the_options_off():
 
 
 def test_mobilenet_layout():
-    for ops, fused_names in ((wl.mobilenet_v1_ops(), ["dw%d" % i for i in range(7, 14)]),
-                             (wl.mobilenet_v2_ops(), ["b%d_dw" % i for i in range(8, 18)])):
+    for ops, fused_names in ((wl.mobilenet_v1_ops(), ["dw%d" % i for i in range(5, 14)]),
+                             (wl.mobilenet_v2_ops(), ["b%d_dw" % i for i in range(5, 18)])):
         infos, _ = plan(ops, (1, 3, 224, 224), "mb")
         got = [o.name for o, i in zip(ops, infos) if o.kind == "dwconv" and i["fused_into"] >= 0]
         assert got == fused_names
