@@ -260,3 +260,25 @@ def test_inception_v3(cad):
         assert_close(got, outs[i], 1e-3, name + " inside the net")
     print("inception end-to-end", e)
     net.free()
+
+
+def test_runs_are_bit_identical(cad):
+    """Nothing on the path uses atomics or depends on scheduling: repeated graph replays, a run
+    without a graph and a second net built from the same tensors give the same bits."""
+    ops = wl.resnet50_ops()
+    shape = (2, 3, 224, 224)
+    x, ws, bs = wl.net_tensors(ops, "c2", shape)
+    xd = dev(x)
+    net = cad.build_net(ops, ws, bs, shape, cad.F32, use_graph=True)
+    first = net.run(xd).clone()
+    torch.cuda.synchronize()
+    for _ in range(20):
+        y = net.run(xd)
+    torch.cuda.synchronize()
+    assert torch.equal(y, first)
+    eager = cad.build_net(ops, ws, bs, shape, cad.F32, use_graph=False)
+    y2 = eager.run(xd)
+    torch.cuda.synchronize()
+    assert torch.equal(y2, first)
+    net.free()
+    eager.free()
