@@ -266,7 +266,17 @@ def main() -> int:
             costs[j]["bytes"] += costs[i]["bytes"] - 2.0 * map_bytes
             costs[i]["flops"] = costs[i]["bytes"] = 0.0
             continue
-        j = next(k for k in range(i + 1, len(ops)) if ops[k].kind == "conv" and ops[k].res == op.dst)
+        j = next((k for k in range(i + 1, len(ops)) if ops[k].kind == "conv" and ops[k].res == op.dst), None)
+        if j is None:
+            # a 1x1 layer merged into an earlier 1x1 layer on the same input (one launch over the
+            # rows of both): its work moves there; the shared input is read once
+            j = next(k for k in range(i) if ops[k].kind == "conv" and ops[k].src == op.src and ops[k].k == 1
+                     and names[k] != "fused" and costs[k]["in"] == costs[i]["in"])
+            costs[j]["flops"] += costs[i]["flops"]
+            costs[j]["bytes"] += costs[i]["bytes"] - float(np.prod(costs[i]["in"])) * elem
+            costs[j]["nnz"] += costs[i]["nnz"]
+            costs[i]["flops"] = costs[i]["bytes"] = 0.0
+            continue
         out_bytes = float(np.prod(costs[i]["out"])) * elem
         costs[j]["flops"] += costs[i]["flops"]
         costs[j]["bytes"] += costs[i]["bytes"] - out_bytes - out_bytes
@@ -349,8 +359,9 @@ def main() -> int:
                 memo[key] = (t_mfma, t_mio)
             costs[i]["dense_mfma_us"], costs[i]["miopen_us"] = memo[key]
             if names[i] == "fused":            # compared together with the layer that computes it
-                j = next(k for k in range(i + 1, len(ops)) if ops[k].kind == "conv" and ops[k].res == op.dst)
-                pending[j] = memo[key]
+                j = next((k for k in range(i + 1, len(ops)) if ops[k].kind == "conv" and ops[k].res == op.dst), None)
+                if j is not None:
+                    pending[j] = memo[key]
                 continue
             t_mfma, t_mio = memo[key][0] + pending.get(i, (0.0, 0.0))[0], memo[key][1] + pending.get(i, (0.0, 0.0))[1]
             density = np.count_nonzero(ws[i]) / float(ws[i].size)

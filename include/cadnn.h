@@ -235,7 +235,11 @@ cadnn_status cadnn_net_workspace_bytes(const cadnn_net* net, size_t* bytes);
  * convolution's epilogue, and so is a 3x3 depthwise layer (padding 1, stride 1 or 2) that is
  * the only reader of a convolution with an image of at most 28 x 28 (the skipped op's
  * profile time is zero and its variant name is "fused"; the buffer that is no longer
- * written is refused by cadnn_net_read_buffer). */
+ * written is refused by cadnn_net_read_buffer).  Also by default, 1x1 stride-1 sparse
+ * convolutions with the same activation and no residual that read the same tensor are
+ * launched as one layer over the rows of all of them: the later ones report fused_into =
+ * the first one, variant "fused" and time zero, their outputs are channel slices of the
+ * first one's region, from channel slice_channel on, and stay readable. */
 #define CADNN_NET_GRAPH 1
 #define CADNN_NET_TUNE 2
 #define CADNN_NET_PLAIN_LAYOUT 4
@@ -256,7 +260,8 @@ typedef struct {
                                 op writes the caller's y: its offset is 0 and means nothing) */
     int fused_into;          /* >= 0: the op is computed inside that op and launches nothing */
     int slice_of;            /* >= 0: the op writes in place into that concatenation's region */
-    int slice_channel;       /* ... starting at this channel of it */
+    int slice_channel;       /* ... starting at this channel of it (for a sibling layer: of
+                                the region of the op named by fused_into) */
 } cadnn_op_info;
 cadnn_status cadnn_net_op_info(cadnn_net* net, int op_index, int flags, cadnn_op_info* out);
 cadnn_status cadnn_run_net(cadnn_net* net, const void* x, void* y, void* stream);

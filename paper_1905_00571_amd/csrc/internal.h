@@ -316,6 +316,9 @@ cadnn_status get_conv_plan(const cadnn_weights* w, const ConvVariant* v, const T
                            int pad, int wout, const ConvPlan** out, const ConvExtra* ex = nullptr);
 void drop_unpinned_plans(const cadnn_weights* w);
 cadnn_status ensure_fc_device(const cadnn_weights* w);
+// A new handle whose rows are the rows of `parts` stacked in order (same cin, 1x1, same type):
+// the layers that read one tensor pixel by pixel, merged into one layer with more channels.
+cadnn_status merge_weights(const std::vector<const cadnn_weights*>& parts, cadnn_weights** out);
 cadnn_status ensure_dw_device(const cadnn_weights* w);
 uint16_t f32_to_f16_rne(float f);
 float f16_to_f32(uint16_t h);

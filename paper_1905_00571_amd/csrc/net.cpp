@@ -42,7 +42,23 @@ struct NetOp {
     std::vector<char> in_place;
     int slice_of = -1;                       // producer: the concatenation whose region it writes into ...
     int slice_ch = 0;                        // ... starting at this channel
+    // 1x1 layers that read the same tensor pixel by pixel are merged into ONE launch with the
+    // rows of all of them (a horizontal fusion): the first carries the others as `siblings`
+    // and writes a region with the channels of all; a sibling is skipped (fused_into = the
+    // first) and its output is the channel slice [sib_ch, sib_ch + cout) of that region
+    std::vector<int> siblings;
+    int sibling_of = -1, sib_ch = 0, launch_c = 0;   // launch_c: channels the launch writes (own + siblings')
 };
+
+// Weights, bias and output layout an op is launched with: its own, or -- first op of a sibling
+// group -- the merged ones.
+const cadnn_weights* eff_w(const cadnn_net* net, const NetOp& op);
+const void* eff_bias(const cadnn_net* net, const NetOp& op);
+TensorDesc launch_yd(const NetOp& op) {
+    TensorDesc d = op.yd;
+    if (!op.siblings.empty()) d.c = op.launch_c;
+    return d;
+}
 
 // Every op whose output `op` reads as an activation input (not as residual).
 std::vector<int> input_insts(const NetOp& op) {
@@ -66,6 +82,8 @@ struct cadnn_net {
     bool allow_s2d = true;
     bool allow_fusion = true;
     char* ws = nullptr;
+    std::map<int, std::unique_ptr<cadnn_weights>> merged_w;   // per first op of a sibling group
+    std::map<int, std::unique_ptr<DevBuf>> merged_bias;
     hipGraphExec_t exec = nullptr;
     const void* cap_x = nullptr;
     void* cap_y = nullptr;
@@ -73,6 +91,18 @@ struct cadnn_net {
 };
 
 namespace {
+
+const cadnn_weights* eff_w(const cadnn_net* net, const NetOp& op) {
+    if (op.siblings.empty()) return op.w;
+    auto it = net->merged_w.find((int)(&op - net->ops.data()));
+    return it == net->merged_w.end() ? op.w : it->second.get();
+}
+
+const void* eff_bias(const cadnn_net* net, const NetOp& op) {
+    if (op.siblings.empty()) return op.bias;
+    auto it = net->merged_bias.find((int)(&op - net->ops.data()));
+    return it == net->merged_bias.end() ? nullptr : it->second->p;
+}
 
 cadnn_status note_output(cadnn_net* net, int dst, const Shape& s) {
     if (dst <= 0) return fail(CADNN_EINVAL, "cadnn_net: dst buffer must be >= 1 (0 is the input)");
@@ -133,6 +163,50 @@ void layout(cadnn_net* net) {
     auto sparse_enough = [](const NetOp& o) {
         return (double)o.w->nnz < 0.25 * (double)o.w->cout * o.w->cin * o.w->kh * o.w->kw;
     };
+    // Sibling groups: pixel-wise (1x1, stride 1) sparse layers without residual that read the
+    // same tensor and are not concatenation slices become one launch over the rows of all of
+    // them (the reduce layers of an Inception module's branches).  Their outputs share one
+    // region, so they share its halo: the largest any of their readers needs.
+    for (NetOp& op : net->ops) { op.siblings.clear(); op.sibling_of = -1; op.sib_ch = 0; op.launch_c = op.out.c; }
+    net->merged_w.clear();
+    if (net->allow_fusion) {
+        auto eligible = [&](int k) {
+            const NetOp& o = net->ops[k];
+            return o.kind == OP_CONV && o.w->kh == 1 && o.w->kw == 1 && o.stride == 1 && o.pad == 0 && o.res < 0 &&
+                   o.slice_of < 0 && o.sibling_of < 0 && o.siblings.empty() && !flat[k] && k != nops - 1 && sparse_enough(o);
+        };
+        for (int i = 0; i < nops; ++i) {
+            if (!eligible(i)) continue;
+            std::vector<const cadnn_weights*> parts{net->ops[i].w};
+            std::vector<int> group;
+            for (int j = i + 1; j < nops; ++j) {
+                const NetOp& a = net->ops[i];
+                const NetOp& b = net->ops[j];
+                if (!eligible(j) || b.src_inst != a.src_inst || b.src != a.src || b.relu != a.relu || b.w->cin != a.w->cin ||
+                    (a.bias == nullptr) != (b.bias == nullptr))
+                    continue;
+                parts.push_back(b.w);
+                group.push_back(j);
+            }
+            if (group.empty()) continue;
+            cadnn_weights* merged = nullptr;
+            if (merge_weights(parts, &merged) != CADNN_OK) continue;
+            net->merged_w[i].reset(merged);
+            NetOp& first = net->ops[i];
+            int ch = first.out.c, h = halo[i];
+            for (int j : group) {
+                NetOp& sib = net->ops[j];
+                sib.sibling_of = i;
+                sib.sib_ch = ch;
+                ch += sib.out.c;
+                h = std::max(h, halo[j]);
+                first.siblings.push_back(j);
+            }
+            first.launch_c = ch;
+            halo[i] = h;
+            for (int j : group) halo[j] = h;
+        }
+    }
     // De-interleaved layout for the output of a convolution whose readers are all
     // convolutions, at least one of them with stride 2: every reader must be either a
     // stride-2 layer whose taps start on an even padded position (any 1x1; larger filters
@@ -141,7 +215,8 @@ void layout(cadnn_net* net) {
     std::vector<int> s2d(nops, 0), strided(nops, 0);
     for (int i = 0; i < nops; ++i) {
         const NetOp& p = net->ops[i];
-        bool ok = p.kind == OP_CONV && !flat[i] && (p.out.h % 2 == 0) && (p.out.w % 2 == 0) && sparse_enough(p);
+        bool ok = p.kind == OP_CONV && !flat[i] && (p.out.h % 2 == 0) && (p.out.w % 2 == 0) && sparse_enough(p) &&
+                  p.siblings.empty() && p.sibling_of < 0;
         if (ok) {
             const bool one = p.w->kh == 1 && p.w->kw == 1;
             const int src_halo = p.src_inst < 0 ? 0 : (flat[p.src_inst] ? 0 : halo[p.src_inst]);
@@ -165,12 +240,21 @@ void layout(cadnn_net* net) {
     size_t off = 0;
     for (int i = 0; i < nops; ++i) {
         NetOp& op = net->ops[i];
-        if (op.slice_of >= 0) continue;          // lives inside a later op's region, see below
+        if (op.slice_of >= 0 || op.sibling_of >= 0) continue;   // lives inside another op's region, see below
         const int hp = flat[i] ? 0 : halo[i];
         op.yd = (s2d[i] && strided[i] && net->allow_s2d) ? make_desc_s2d(op.out.c, op.out.h, op.out.w, hp, hp)
-                                                        : make_desc(op.out.c, op.out.h, op.out.w, hp, hp);
+                                                        : make_desc(op.launch_c, op.out.h, op.out.w, hp, hp);
+        op.yd.c = op.out.c;                      // (with siblings the region holds launch_c channels; readers see the op's own)
         op.y_off = off;
         if (i != nops - 1) off += ((size_t)op.out.n * op.yd.image * net->elem() + 255) / 256 * 256;
+    }
+    for (NetOp& op : net->ops) {
+        if (op.sibling_of < 0) continue;
+        // a channel slice of the region the first op of the group writes
+        const NetOp& first = net->ops[op.sibling_of];
+        op.yd = first.yd;
+        op.yd.c = op.out.c;
+        op.y_off = first.y_off + (size_t)op.sib_ch * first.yd.plane * net->elem();
     }
     for (NetOp& op : net->ops) {
         if (op.slice_of < 0) continue;
@@ -190,7 +274,8 @@ void layout(cadnn_net* net) {
     // A 1x1 projection shortcut whose only reader takes it as residual is computed inside
     // that reader (a second sparse matrix on a second input, same accumulators): one launch,
     // one output write and one residual read less (paper Section 4, layer fusion).
-    for (NetOp& op : net->ops) { op.shortcut = -1; op.pool_op = -1; op.dw_op = -1; op.fused_into = -1; }
+    for (NetOp& op : net->ops) { op.shortcut = -1; op.pool_op = -1; op.dw_op = -1; op.fused_into = op.sibling_of; }
+    auto grouped = [](const NetOp& o) { return o.sibling_of >= 0 || !o.siblings.empty(); };
     if (net->allow_fusion) {
         const std::vector<int>& readers = all_readers;
         for (int i = 0; i < nops; ++i) {
@@ -198,7 +283,7 @@ void layout(cadnn_net* net) {
             if (c.kind != OP_CONV || c.res_inst < 0) continue;
             NetOp& p = net->ops[c.res_inst];
             const bool c_one = c.w->kh == 1 && c.w->kw == 1;
-            const bool ok = p.kind == OP_CONV && p.w->kh == 1 && p.w->kw == 1 && p.pad == 0 && !p.relu && p.res < 0 &&
+            const bool ok = p.kind == OP_CONV && !grouped(p) && p.w->kh == 1 && p.w->kw == 1 && p.pad == 0 && !p.relu && p.res < 0 &&
                             readers[c.res_inst] == 1 && c.res_inst != nops - 1 && p.w->cout == c.w->cout &&
                             sparse_enough(c) && sparse_enough(p) && !c.yd.s2d && !(c.xd.s2d && c.stride == 1) &&
                             (c_one ? c.pad == 0 : (c.xd.ph >= c.pad && c.xd.pw >= c.pad)) &&
@@ -216,7 +301,7 @@ void layout(cadnn_net* net) {
             if (a.kind != OP_AVGPOOL || a.src_inst < 0) continue;
             NetOp& c = net->ops[a.src_inst];
             const bool c_one = c.kind == OP_CONV && c.w->kh == 1 && c.w->kw == 1;
-            const bool ok = c.kind == OP_CONV && readers[a.src_inst] == 1 && c.shortcut < 0 && c.fused_into < 0 &&
+            const bool ok = c.kind == OP_CONV && !grouped(c) && readers[a.src_inst] == 1 && c.shortcut < 0 && c.fused_into < 0 &&
                             sparse_enough(c) && !c.yd.s2d && !c.xd.s2d && !(c.res >= 0 && c.rd.s2d) &&
                             c.out.h * c.out.w <= 256 &&
                             (c_one ? c.pad == 0 : (c.xd.ph >= c.pad && c.xd.pw >= c.pad));
@@ -235,7 +320,7 @@ void layout(cadnn_net* net) {
             if (d.kind != OP_DEPTHWISE || d.src_inst < 0) continue;
             NetOp& c = net->ops[d.src_inst];
             const bool c_one = c.kind == OP_CONV && c.w->kh == 1 && c.w->kw == 1;
-            const bool ok = c.kind == OP_CONV && readers[d.src_inst] == 1 && c.shortcut < 0 && c.pool_op < 0 &&
+            const bool ok = c.kind == OP_CONV && !grouped(c) && readers[d.src_inst] == 1 && c.shortcut < 0 && c.pool_op < 0 &&
                             c.fused_into < 0 && sparse_enough(c) && !c.yd.s2d && !c.xd.s2d && !(c.res >= 0 && c.rd.s2d) &&
                             c.out.h <= 28 && c.out.w <= 28 && d.w->kh == 3 && d.w->kw == 3 && d.pad == 1 &&
                             (d.stride == 1 || d.stride == 2) && !d.yd.s2d &&
@@ -308,9 +393,9 @@ cadnn_status launch_one(cadnn_net* net, size_t i, const void* x, void* y, hipStr
     const bool fused = shortcut_of(net, op, x, &ex, y);
     switch (op.kind) {
         case OP_CONV:
-            return conv2d_impl(op.w, src, op.xd, dst, op.yd,
+            return conv2d_impl(eff_w(net, op), src, op.xd, dst, launch_yd(op),
                                (op.res >= 0 && op.shortcut < 0) ? in_ptr(net, op.res_inst, x) : nullptr, op.rd, op.in.n,
-                               op.stride, op.pad, op.bias, op.relu, s, fused ? &ex : nullptr);
+                               op.stride, op.pad, eff_bias(net, op), op.relu, s, fused ? &ex : nullptr);
         case OP_DEPTHWISE:
             return launch_depthwise(op.w, src, op.xd, dst, op.yd, op.in.n, op.stride, op.pad, (const float*)op.bias,
                                     op.relu, s);
@@ -558,7 +643,7 @@ extern "C" cadnn_status cadnn_net_op_info(cadnn_net* net, int op_index, int flag
     out->offset = (int64_t)op.y_off + (op.yd.s2d ? 0 : (int64_t)op.yd.origin * (int64_t)net->elem());
     out->fused_into = op.fused_into;
     out->slice_of = op.slice_of;
-    out->slice_channel = op.slice_ch;
+    out->slice_channel = op.sibling_of >= 0 ? op.sib_ch : op.slice_ch;
     return CADNN_OK;
 }
 
@@ -577,11 +662,27 @@ extern "C" cadnn_status cadnn_net_finalize(cadnn_net* net, void* ws, size_t byte
         CADNN_HIP(hipMemset(ws, 0, net->ws_bytes));
         CADNN_HIP(hipDeviceSynchronize());
     }
+    // biases of a sibling group, stacked like the rows of its merged weights
+    net->merged_bias.clear();
+    for (size_t i = 0; i < net->ops.size(); ++i) {
+        const NetOp& op = net->ops[i];
+        if (op.siblings.empty() || !op.bias) continue;
+        std::vector<float> zeros((size_t)op.launch_c, 0.0f);
+        std::unique_ptr<DevBuf> buf(new DevBuf());
+        cadnn_status st = buf->upload(zeros.data(), zeros.size() * 4);
+        if (st != CADNN_OK) return st;
+        CADNN_HIP(hipMemcpy(buf->p, op.bias, (size_t)op.out.c * 4, hipMemcpyDeviceToDevice));
+        for (int j : op.siblings) {
+            const NetOp& sib = net->ops[j];
+            CADNN_HIP(hipMemcpy((char*)buf->p + (size_t)sib.sib_ch * 4, sib.bias, (size_t)sib.out.c * 4, hipMemcpyDeviceToDevice));
+        }
+        net->merged_bias[(int)i] = std::move(buf);
+    }
     for (const NetOp& op : net->ops) {
         cadnn_status st = CADNN_OK;
         ConvExtra ex;
         if (op.kind == OP_CONV && op.fused_into < 0)
-            st = conv2d_prepare_impl(op.w, op.xd, op.in.n, op.stride, op.pad, out_s2d(op), shortcut_geom(net, op, &ex));
+            st = conv2d_prepare_impl(eff_w(net, op), op.xd, op.in.n, op.stride, op.pad, out_s2d(op), shortcut_geom(net, op, &ex));
         if (op.kind == OP_FC) st = cadnn_fc_prepare(op.w);
         if (op.kind == OP_DEPTHWISE) st = ensure_dw_device(op.w);
         if (st != CADNN_OK) return st;
@@ -607,9 +708,9 @@ extern "C" cadnn_status cadnn_run_net(cadnn_net* net, const void* x, void* y, vo
             };
             ConvExtra ex;
             const bool fused = shortcut_of(net, op, x, &ex, y);
-            st = conv2d_tune_impl(op.w, in_ptr(net, op.src_inst, x), op.xd, out_ptr(net, i, y), op.yd,
+            st = conv2d_tune_impl(eff_w(net, op), in_ptr(net, op.src_inst, x), op.xd, out_ptr(net, i, y), launch_yd(op),
                                   (op.res >= 0 && op.shortcut < 0) ? in_ptr(net, op.res_inst, x) : nullptr, op.rd, op.in.n,
-                                  op.stride, op.pad, op.bias, op.relu, s, 20, nullptr, &producer,
+                                  op.stride, op.pad, eff_bias(net, op), op.relu, s, 20, nullptr, &producer,
                                   fused ? &ex : nullptr);
         }
         if (st != CADNN_OK) return st;
@@ -693,7 +794,7 @@ extern "C" cadnn_status cadnn_net_op_variant(const cadnn_net* net, int op_index,
         case OP_CONV: {
             ConvExtra ex;
             name = op.fused_into >= 0 ? "fused"
-                                      : conv2d_variant_name_impl(op.w, op.xd, op.in.n, op.stride, op.pad, out_s2d(op),
+                                      : conv2d_variant_name_impl(eff_w(net, op), op.xd, op.in.n, op.stride, op.pad, out_s2d(op),
                                                                  shortcut_geom(net, op, &ex));
             break;
         }
@@ -720,7 +821,7 @@ extern "C" cadnn_status cadnn_net_op_candidates(const cadnn_net* net, int op_ind
     if (op.kind != OP_CONV) return fail(CADNN_EINVAL, "cadnn_net_op_candidates: op %d is not a convolution", op_index);
     if (op.fused_into >= 0) return fail(CADNN_EINVAL, "cadnn_net_op_candidates: op %d is computed inside op %d", op_index, op.fused_into);
     ConvExtra ex;
-    return conv2d_list_variants_impl(op.w, op.xd, op.in.n, op.stride, op.pad, buf, len, out_s2d(op), shortcut_geom(net, op, &ex));
+    return conv2d_list_variants_impl(eff_w(net, op), op.xd, op.in.n, op.stride, op.pad, buf, len, out_s2d(op), shortcut_geom(net, op, &ex));
 }
 
 extern "C" cadnn_status cadnn_net_set_op_variant(cadnn_net* net, int op_index, const char* name) {
@@ -731,10 +832,10 @@ extern "C" cadnn_status cadnn_net_set_op_variant(cadnn_net* net, int op_index, c
     if (op.kind != OP_CONV) return fail(CADNN_EINVAL, "cadnn_net_set_op_variant: op %d is not a convolution", op_index);
     if (op.fused_into >= 0) return CADNN_OK;     // nothing to pin: computed inside another op
     ConvExtra ex;
-    cadnn_status st = conv2d_set_variant_impl(op.w, op.xd, op.in.n, op.stride, op.pad, name, out_s2d(op), shortcut_geom(net, op, &ex));
+    cadnn_status st = conv2d_set_variant_impl(eff_w(net, op), op.xd, op.in.n, op.stride, op.pad, name, out_s2d(op), shortcut_geom(net, op, &ex));
     if (st != CADNN_OK) return st;
     drop_graph(net);
-    return conv2d_prepare_impl(op.w, op.xd, op.in.n, op.stride, op.pad, out_s2d(op), shortcut_geom(net, op, &ex));
+    return conv2d_prepare_impl(eff_w(net, op), op.xd, op.in.n, op.stride, op.pad, out_s2d(op), shortcut_geom(net, op, &ex));
 }
 
 extern "C" cadnn_status cadnn_net_read_buffer(cadnn_net* net, int buf, void* host_out, size_t bytes,
@@ -746,7 +847,7 @@ extern "C" cadnn_status cadnn_net_read_buffer(cadnn_net* net, int buf, void* hos
         return fail(CADNN_EINVAL, "cadnn_net_read_buffer: buffer %d is not in the workspace", buf);
     const NetOp& op = net->ops[it->second];
     // (a fused pool's vector is written, by the convolution; a fused projection's map is not)
-    if (op.fused_into >= 0 && op.kind == OP_CONV)
+    if (op.fused_into >= 0 && op.kind == OP_CONV && op.sibling_of < 0)
         return fail(CADNN_EINVAL, "cadnn_net_read_buffer: buffer %d is never materialised (its op is computed inside op %d)", buf, op.fused_into);
     if (op.pool_op >= 0)
         return fail(CADNN_EINVAL, "cadnn_net_read_buffer: buffer %d is never materialised (op %d pools it on the fly)", buf, it->second);

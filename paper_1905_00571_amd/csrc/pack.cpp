@@ -612,6 +612,59 @@ cadnn_status ensure_fc_device(const cadnn_weights* w) {
     return CADNN_OK;
 }
 
+cadnn_status merge_weights(const std::vector<const cadnn_weights*>& parts, cadnn_weights** out) {
+    *out = nullptr;
+    if (parts.empty()) return fail(CADNN_EINVAL, "merge_weights: nothing to merge");
+    std::unique_ptr<cadnn_weights> m;
+    try {
+        m.reset(new cadnn_weights());
+        m->cin = parts[0]->cin;
+        m->kh = m->kw = 1;
+        m->dtype = parts[0]->dtype;
+        int64_t cout = 0, nnz = 0;
+        for (const cadnn_weights* p : parts) {
+            if (p->cin != m->cin || p->kh != 1 || p->kw != 1 || p->dtype != m->dtype)
+                return fail(CADNN_EINVAL, "merge_weights: layers of different shape or type");
+            cout += p->cout;
+            nnz += p->nnz;
+        }
+        if (cout > (1 << 24) || nnz > (int64_t)INT32_MAX) return fail(CADNN_EUNSUPPORTED, "merge_weights: too large");
+        m->cout = (int)cout;
+        m->nnz = nnz;
+        // (part, packed row) of every merged channel, then the canonical order again: rows by
+        // nonzero count, descending, ties by ascending (merged) channel
+        struct Src { const cadnn_weights* p; int row; int32_t count; };
+        std::vector<Src> src((size_t)cout);
+        int base = 0;
+        for (const cadnn_weights* p : parts) {
+            for (int r = 0; r < p->cout; ++r)
+                src[(size_t)base + p->perm[r]] = Src{p, r, p->row_ptr[r + 1] - p->row_ptr[r]};
+            base += p->cout;
+        }
+        m->perm.resize((size_t)cout);
+        std::iota(m->perm.begin(), m->perm.end(), 0);
+        std::stable_sort(m->perm.begin(), m->perm.end(),
+                         [&](int32_t a, int32_t b) { return src[a].count > src[b].count; });
+        m->row_ptr.assign((size_t)cout + 1, 0);
+        for (int i = 0; i < m->cout; ++i) m->row_ptr[i + 1] = m->row_ptr[i] + src[m->perm[i]].count;
+        m->col_idx.resize((size_t)nnz);
+        m->vals.resize((size_t)nnz);
+        if (m->dtype == CADNN_F16) m->vals16.resize((size_t)nnz);
+        for (int i = 0; i < m->cout; ++i) {
+            const Src& s = src[m->perm[i]];
+            const int32_t from = s.p->row_ptr[s.row];
+            std::copy_n(s.p->col_idx.begin() + from, s.count, m->col_idx.begin() + m->row_ptr[i]);
+            std::copy_n(s.p->vals.begin() + from, s.count, m->vals.begin() + m->row_ptr[i]);
+            if (m->dtype == CADNN_F16)
+                std::copy_n(s.p->vals16.begin() + from, s.count, m->vals16.begin() + m->row_ptr[i]);
+        }
+    } catch (const std::bad_alloc&) {
+        return fail(CADNN_ENOMEM, "merge_weights: out of host memory");
+    }
+    *out = m.release();
+    return CADNN_OK;
+}
+
 // Depthwise filters as a dense fp32 table [cout][kh*kw] (pruned taps are zeros, which the
 // kernel skips); a depthwise handle is packed from [channels][1][kh][kw], so a row's column
 // index is the tap index itself.

@@ -603,3 +603,51 @@ def test_concat_in_place_and_copied(cad, dtype_name):
             got = net.read_buffer(ops[i].dst, outs[i].shape)
             assert_close(got, outs[i], tol, f"buffer of {ops[i].name}")
         net.free()
+
+
+@pytest.mark.parametrize("dtype_name", ["f32", "f16"])
+def test_sibling_layers_in_one_launch(cad, dtype_name):
+    """Pixel-wise sparse layers that read the same tensor are merged into one launch over the
+    rows of all of them, their outputs channel slices of one region whose halo serves the most
+    demanding reader (5x5 here).  Every variant of the merged layer, tuned or not, must leave
+    each sibling's output and everything behind it as the oracle has them; a layer with a
+    different activation, a concatenation slice and a residual layer stay out of the group."""
+    f16 = dtype_name == "f16"
+    dtype, npdt, tol = (cad.F16, np.float16, TOL_F16) if f16 else (cad.F32, np.float32, TOL_F32)
+    Op = wl.Op
+    ops = [Op("conv", "stem", 0, 1, 6, 32, 1, 1, 0, 0.8, True),
+           Op("conv", "s1", 1, 2, 32, 12, 1, 1, 0, 0.8, True),          # group of three: s1, s2, s3
+           Op("conv", "s2", 1, 3, 32, 20, 1, 1, 0, 0.9, True),
+           Op("conv", "lin", 1, 4, 32, 8, 1, 1, 0, 0.8, False),         # no ReLU: not in the group
+           Op("conv", "s3", 1, 5, 32, 9, 1, 1, 0, 0.85, True),
+           Op("conv", "slice", 1, 6, 32, 10, 1, 1, 0, 0.8, True),       # only read by the concatenation: in place there
+           Op("conv", "r3", 2, 7, 12, 16, 3, 1, 1, 0.8, True),          # halo 1
+           Op("conv", "r5", 3, 8, 20, 16, 5, 1, 2, 0.9, True),          # halo 2: the group's halo
+           Op("conv", "r1", 5, 9, 9, 16, 1, 1, 0, 0.8, True),
+           Op("conv", "rl", 4, 10, 8, 16, 1, 1, 0, 0.8, True),
+           Op("concat", "cat", 7, 11, srcs=(7, 8, 9, 10, 6)),
+           Op("conv", "post", 11, 12, 74, 12, 1, 1, 0, 0.8, False)]
+    shape = (2, 6, 13, 11)
+    x, ws, bs = wl.net_tensors(ops, "sib", shape, input_relu=True)
+    xs = x.astype(npdt)
+    ref, ins, outs = oracle.run_net(ops, xs, ws, bs, dtype=npdt)
+    infos, _ = cad.plan_net(ops, ws, shape, dtype)
+    assert [i["fused_into"] for i in infos[:6]] == [-1, -1, 1, -1, 1, -1]
+    assert infos[1]["halo_h"] == infos[2]["halo_h"] == infos[4]["halo_h"] == 2 and infos[5]["slice_of"] == 10
+    for kw in ({}, {"tune": True}, {"fuse": False}):
+        net = cad.build_net(ops, ws, bs, shape, dtype, use_graph=True, **kw)
+        merged = kw.get("fuse", True)
+        assert (net.op_variant(2) == "fused") == merged and (net.op_variant(4) == "fused") == merged
+        names = [net.op_variant(1)] if kw else net.op_candidates(1)
+        assert names
+        for name in names:
+            net.set_op_variant(1, name)
+            y = net.run(dev(xs))
+            torch.cuda.synchronize()
+            assert_close(y.cpu().numpy(), ref, tol * (3 if f16 else 1), f"sibling net {kw} {name}")
+            for i in (1, 2, 3, 4, 5):
+                cond = cond_conv(ins[i], ws[i].astype(npdt), bs[i], None, 1, 0)
+                got = net.read_buffer(ops[i].dst, outs[i].shape)
+                assert_layer_close(got, outs[i], cond + (2.0 ** -10 / 1e-4 * np.abs(outs[i]) if f16 else 0), tol,
+                                   f"{ops[i].name} {kw} {name}", f16=f16)
+        net.free()

@@ -99,10 +99,13 @@ def test_inception_concatenations_are_written_in_place():
     # intermediate tensor is the padding of the filter that reads it (5x5: 2, 7 taps: 3, 3x3: 1)
     assert all(infos[k]["halo_h"] == 0 and infos[k]["halo_w"] == 0 for k in cats)
     halo = {o.name: (i["halo_h"], i["halo_w"]) for o, i in zip(ops, infos)}
-    assert halo["a1_5x5a"] == (2, 2) and halo["c1_7a"] == (3, 3) and halo["a1_3x3a"] == (1, 1)
-    assert halo["e1_3a"] == (1, 1) and halo["stem3"] == (0, 0) and halo["stem2"] == (1, 1)
-    # the workspace holds every region that is not a slice of another
-    off = sum(region_bytes(i, 1) for i in infos[:-1] if i["slice_of"] < 0)
+    # (a1_3x3a shares the region of a1_5x5a, see the sibling test below, hence its halo)
+    assert halo["a1_5x5a"] == (2, 2) and halo["c1_7a"] == (3, 3) and halo["a1_3x3a"] == (2, 2)
+    assert halo["a1_3x3b"] == (1, 1) and halo["e1_3a"] == (1, 1) and halo["stem3"] == (0, 0) and halo["stem2"] == (1, 1)
+    # the workspace holds every region that is not a slice of another (a concatenation's, or
+    # the region of the first layer of a sibling group)
+    off = sum(region_bytes(i, 1) for o, i in zip(ops[:-1], infos[:-1])
+              if i["slice_of"] < 0 and not (o.kind == "conv" and i["fused_into"] >= 0))
     assert nbytes == off
 
 
@@ -134,3 +137,36 @@ def test_op_info_errors():
     assert L.cadnn_net_add_avgpool(net, 3, 1, 1, 1, 1) == 1       # dst aliases src
     assert L.cadnn_net_add_avgpool(net, 3, 1, 1, 1, 2) == 0
     assert L.cadnn_net_free(net) == 0
+
+
+def test_inception_sibling_layers_share_a_launch():
+    """The 1x1 reduce layers of an Inception module's branches read the same tensor pixel by
+    pixel: those that are not concatenation slices become one launch and one region."""
+    ops = wl.inception_v3_ops()
+    infos, _ = plan(ops, (1, 3, 299, 299), "iv3")
+    name_of = [o.name for o in ops]
+    merged = {o.name: name_of[i["fused_into"]] for o, i in zip(ops, infos)
+              if o.kind == "conv" and i["fused_into"] >= 0}
+    want = {}
+    for m in ("a1", "a2", "a3"):
+        want[m + "_3x3a"] = m + "_5x5a"
+    for m in ("c1", "c2", "c3", "c4"):
+        want[m + "_dbl_a"] = m + "_7a"
+    want["d_7a"] = "d_3x3a"
+    want["e1_dbl_a"] = "e1_3a"
+    want["e2_dbl_a"] = "e2_3a"
+    assert merged == want
+    by = {o.name: i for o, i in zip(ops, infos)}
+    shapes = wl.buffer_shapes(ops, (1, 3, 299, 299))
+    for sib, first in want.items():
+        a, b = by[first], by[sib]
+        c_first = next(o.cout for o in ops if o.name == first)
+        # one region: same planes and halo (the larger of the two readers' paddings), the
+        # sibling's slice behind the first layer's channels
+        assert (b["halo_h"], b["pitch"], b["plane"], b["image"]) == (a["halo_h"], a["pitch"], a["plane"], a["image"])
+        assert b["offset"] == a["offset"] + c_first * a["plane"] * 4
+        assert b["slice_channel"] == c_first and b["slice_of"] == -1
+    assert by["a1_5x5a"]["halo_h"] == 2 and by["c1_7a"]["halo_h"] == 3 and by["d_3x3a"]["halo_h"] == 3
+    # without fusion nothing is merged
+    plain, _ = plan(ops, (1, 3, 299, 299), "iv3", fuse=False)
+    assert all(i["fused_into"] == -1 for i in plain)
