@@ -220,6 +220,10 @@ cadnn_status cadnn_net_add_global_avgpool(cadnn_net* net, int src_buf, int dst_b
 cadnn_status cadnn_net_add_concat(cadnn_net* net, const int* src_bufs, int count, int dst_buf);
 cadnn_status cadnn_net_add_fc(cadnn_net* net, const cadnn_weights* w, const void* bias_dev,
                               int relu, int src_buf, int dst_buf);
+/* Size of the workspace cadnn_net_finalize needs.  It depends on the layout flags below
+ * (CADNN_NET_PLAIN_LAYOUT, CADNN_NET_NO_FUSION): the value is for flags 0 unless
+ * cadnn_net_op_info has been called with other flags since the last op was added; finalize
+ * refuses a workspace smaller than its own flags need. */
 cadnn_status cadnn_net_workspace_bytes(const cadnn_net* net, size_t* bytes);
 /* flags: CADNN_NET_GRAPH -- cadnn_run_net replays a captured HIP graph (re-captured
  * when x / y change between calls); CADNN_NET_TUNE -- the first cadnn_run_net call

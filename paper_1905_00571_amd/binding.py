@@ -514,13 +514,14 @@ def build_net(ops: Sequence, weights: Sequence, biases: Sequence, input_shape, d
     try:
         shapes = _add_ops(L, handle, ops, weights, biases, input_shape, dtype, keep,
                           lambda b: torch.from_numpy(np.ascontiguousarray(b, dtype=np.float32)).to(device))
+        flags = (1 if use_graph else 0) | (2 if tune else 0) | (4 if plain_layout else 0) | (0 if fuse else 8)
+        # the workspace size depends on the layout flags: have the library lay the net out for them first
+        _check(L.cadnn_net_op_info(handle, 0, flags, ctypes.byref(OpInfo())))
         nbytes = ctypes.c_size_t()
         _check(L.cadnn_net_workspace_bytes(handle, ctypes.byref(nbytes)))
         ws = torch.empty(max(int(nbytes.value), 256), dtype=torch.uint8, device=device)
         keep.append(ws)
-        _check(L.cadnn_net_finalize(handle, _dptr(ws), int(nbytes.value),
-                                    (1 if use_graph else 0) | (2 if tune else 0) | (4 if plain_layout else 0) |
-                                    (0 if fuse else 8)))
+        _check(L.cadnn_net_finalize(handle, _dptr(ws), int(nbytes.value), flags))
     except Exception:
         L.cadnn_net_free(handle)
         raise

@@ -2,7 +2,11 @@
 depthwise layers, pools and concatenations wired at random, so that the runner's layout
 decisions (halos, de-interleaved tensors, fusions, in-place concatenation) meet in combinations
 the hand-written nets do not contain.  Every buffer that is still materialised and the output
-are compared with the oracle, with the default options and with them turned off."""
+are compared with the oracle, with the default options and with them turned off.  Seeds from 16
+on also draw Inception-like modules (sibling 1x1 heads, larger filters behind them, a pooled
+branch, a concatenation).  CADNN_RANDOM_NETS=<count> runs more seeds than the default 24."""
+import os
+
 import numpy as np
 import pytest
 
@@ -42,8 +46,42 @@ def random_net(seed):
         # mostly continue from the newest buffer, sometimes branch from an older one
         src = cur if g.random() < 0.75 else int(g.choice(list(shapes)))
         _, c, h, w = shapes[src]
-        kind = g.choice(["conv", "conv", "conv", "conv", "block", "block", "dwconv", "maxpool", "avgpool2d", "concat"])
+        kinds = ["conv", "conv", "conv", "conv", "block", "block", "dwconv", "maxpool", "avgpool2d", "concat"]
+        if seed >= 16:
+            kinds += ["module", "module", "module"]
+        kind = g.choice(kinds)
         dst = nxt
+        if kind == "module":
+            # branches that start with 1x1 layers on the same tensor (some followed by a larger
+            # filter, one behind a 3x3 mean pool) and meet in a concatenation: the heads that
+            # are not concatenation slices themselves share one launch
+            sp = float(g.choice([0.8, 0.85, 0.9]))
+            relu_heads = bool(g.random() < 0.8)
+            tails = []
+            for b in range(int(g.integers(2, 5))):
+                mid = int(g.integers(4, 17))
+                ops.append(wl.Op("conv", f"mod{step}h{b}", src, nxt, c, mid, 1, 1, 0, sp, relu_heads or b == 1))
+                shapes[nxt] = (n, mid, h, w)
+                nxt += 1
+                k = int(g.choice([1, 3, 3, 5]))
+                if k > 1:
+                    co = int(g.integers(4, 17))
+                    ops.append(wl.Op("conv", f"mod{step}t{b}", nxt - 1, nxt, mid, co, k, 1, k // 2, sp, True))
+                    shapes[nxt] = (n, co, h, w)
+                    nxt += 1
+                tails.append(nxt - 1)
+            if g.random() < 0.5:
+                ops.append(wl.Op("avgpool2d", f"mod{step}pool", src, nxt, k=3, stride=1, pad=1))
+                shapes[nxt] = (n, c, h, w)
+                ops.append(wl.Op("conv", f"mod{step}pp", nxt, nxt + 1, c, 6, 1, 1, 0, sp, True))
+                shapes[nxt + 1] = (n, 6, h, w)
+                nxt += 2
+                tails.append(nxt - 1)
+            ops.append(wl.Op("concat", f"mod{step}cat", tails[0], nxt, srcs=tuple(tails)))
+            shapes[nxt] = (n, sum(shapes[b][1] for b in tails), h, w)
+            cur = nxt
+            nxt += 1
+            continue
         if kind == "block":
             # a bottleneck: 1x1 -> 3x3 (stride s) -> 1x1 + shortcut (a 1x1 / stride s projection,
             # or the block input when the shapes agree), the pattern of the residual networks
@@ -104,7 +142,7 @@ def random_net(seed):
     return ops, shape
 
 
-@pytest.mark.parametrize("seed", range(16))
+@pytest.mark.parametrize("seed", range(int(os.environ.get("CADNN_RANDOM_NETS", "24"))))
 def test_random_net(cad, seed):
     ops, shape = random_net(seed)
     f16 = seed % 4 == 3

@@ -168,5 +168,7 @@ def test_inception_sibling_layers_share_a_launch():
         assert b["slice_channel"] == c_first and b["slice_of"] == -1
     assert by["a1_5x5a"]["halo_h"] == 2 and by["c1_7a"]["halo_h"] == 3 and by["d_3x3a"]["halo_h"] == 3
     # without fusion nothing is merged
-    plain, _ = plan(ops, (1, 3, 299, 299), "iv3", fuse=False)
+    plain, nplain = plan(ops, (1, 3, 299, 299), "iv3", fuse=False)
     assert all(i["fused_into"] == -1 for i in plain)
+    # ... and every layer has a region of its own again: the workspace size follows the flags
+    assert nplain == sum(region_bytes(i, 1) for i in plain[:-1] if i["slice_of"] < 0)
