@@ -100,8 +100,12 @@ cadnn_status cadnn_unpack_weights(const cadnn_weights* w, float* w_host_out);
  * The first call with a new (h, wdt, stride, pad, n) geometry may build and
  * upload a device layout (allocates, synchronous); call cadnn_conv2d_prepare
  * beforehand to keep the timed call allocation-free.
+ * Sparse kernels serve 1x1 and 3x3 filters at any stride, 7x7 filters at strides 1 and 2,
+ * other filter sizes while a tile of the input fits the LDS, and every filter size inside a
+ * net (whose tensors carry zero halos); a geometry none of them serves, and any layer with
+ * at least a quarter of its weights nonzero, may take the dense matrix-core kernel.
  * Errors: EINVAL (NULL x/y/w, sizes <= 0, stride <= 0, pad < 0, empty output);
- * EUNSUPPORTED (no kernel variant for the geometry); EHIP.
+ * EUNSUPPORTED (sizes beyond the launch limits); EHIP.
  * ------------------------------------------------------------------------- */
 cadnn_status cadnn_sparse_conv2d(const cadnn_weights* w, const void* x, void* y, int n, int h,
                                  int wdt, int stride, int pad, const void* bias,

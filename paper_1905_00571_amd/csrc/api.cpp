@@ -55,14 +55,14 @@ static cadnn_status check_conv(const char* who, const cadnn_weights* w, const Te
     return CADNN_OK;
 }
 
-static bool variant_fits(const ConvVariant& v, const cadnn_weights* w, const ConvGeom& g) {
+static bool variant_fits(const ConvVariant& v, const cadnn_weights* w, const ConvGeom& g, bool any_density = false) {
     if (v.is_f16 != (w->dtype == CADNN_F16)) return false;
     if (v.stride != 0 && v.stride != g.stride) return false;
     if ((w->cout + v.rows_per_block() - 1) / v.rows_per_block() > 65535) return false;
     // de-interleaved tensors and fused shortcuts are understood by the linear-address kernels only
     if ((g.xd.s2d || g.out_s2d || g.ex) && v.family != FAM_LINEAR) return false;
     if (v.family == FAM_DENSE)
-        return (double)w->nnz >= 0.25 * (double)w->cout * w->cin * w->kh * w->kw;
+        return any_density || (double)w->nnz >= 0.25 * (double)w->cout * w->cin * w->kh * w->kw;
     if (v.family == FAM_LINEAR) {
         const bool one = w->kh == 1 && w->kw == 1;
         if (g.xd.s2d) {
@@ -114,7 +114,9 @@ static bool variant_fits(const ConvVariant& v, const cadnn_weights* w, const Con
         const PtileGeom pg = ptile_geom(v, w->cin, w->kh, w->kw, g.stride, g.pad, g.wout);
         return pg.nstp <= kPtileMaxSteps && (int64_t)pg.plane * 4 <= (int64_t)kLdsBytesPerCU;
     }
-    return v.kh == w->kh && v.kw == w->kw;
+    if (v.kh != w->kh || v.kw != w->kw) return false;
+    // the wave-sliced LDS kernel buffers the stream of a (row group, channel chunk)
+    return v.family != FAM_STILE || stile_streams_fit(w, &v);
 }
 
 static std::vector<const ConvVariant*> candidates(const cadnn_weights* w, const ConvGeom& g) {
@@ -125,6 +127,11 @@ static std::vector<const ConvVariant*> candidates(const cadnn_weights* w, const 
     for (const ConvVariant& v : all_dense_variants()) if (variant_fits(v, w, g)) out.push_back(&v);
     for (const ConvVariant& v : all_stile_variants()) if (variant_fits(v, w, g)) out.push_back(&v);
     for (const ConvVariant& v : all_ptile_variants()) if (variant_fits(v, w, g)) out.push_back(&v);
+    // No sparse kernel is instantiated for the geometry (say a 5x5 or a stride-3 7x7 filter on
+    // an input without halo): the matrix-core kernel, which takes any geometry, serves it
+    // whatever the density, so that every valid layer runs.
+    if (out.empty())
+        for (const ConvVariant& v : all_dense_variants()) if (variant_fits(v, w, g, true)) out.push_back(&v);
     return out;
 }
 
@@ -179,6 +186,14 @@ static const ConvVariant* heuristic_variant(const cadnn_weights* w, const ConvGe
             cost = t_block * rounds * 2.0;   // until tuned, prefer the staging-free families
         }
         if (!best || cost < best_cost) { best = v; best_cost = cost; }
+    }
+    if (!best) {
+        // only LDS-staged variants serve the geometry (a 5x5 filter on a plain tensor): take
+        // the one whose waves walk the fewest nonzeros each, the channel split priced as above
+        for (const ConvVariant* v : cand) {
+            const double cost = v->rpw * nnz_row / v->ks + (v->ks > 1 ? 338.0 / 77.4 * std::log2((double)v->ks) : 0.0);
+            if (!best || cost < best_cost) { best = v; best_cost = cost; }
+        }
     }
     return best;
 }

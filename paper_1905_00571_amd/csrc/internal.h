@@ -287,6 +287,10 @@ struct cadnn_weights {
     mutable std::map<cadnn::PlanKey, std::unique_ptr<cadnn::ConvPlan>> plans;
     // variant pinned for a geometry by tuning or by the caller
     mutable std::map<cadnn::GeomKey, const cadnn::ConvVariant*> chosen;
+    // FAM_STILE variants whose per-(row group, chunk) stream was measured against the kernel's buffer
+    // (its own lock: candidates are also listed by callers that hold `mu`)
+    mutable std::mutex stile_mu;
+    mutable std::map<const cadnn::ConvVariant*, bool> stile_ok;
     size_t elem() const { return dtype == CADNN_F16 ? 2 : 4; }
 };
 
@@ -312,6 +316,9 @@ struct ConvExtra {
 };
 
 // stride / pad / wout matter to FAM_PTILE plans only.
+// Whether every (row group, channel chunk) stream of these weights fits the buffer of a
+// FAM_STILE variant (exact; cached on the handle).
+bool stile_streams_fit(const cadnn_weights* w, const ConvVariant* v);
 cadnn_status get_conv_plan(const cadnn_weights* w, const ConvVariant* v, const TensorDesc& xd, int stride,
                            int pad, int wout, const ConvPlan** out, const ConvExtra* ex = nullptr);
 void drop_unpinned_plans(const cadnn_weights* w);

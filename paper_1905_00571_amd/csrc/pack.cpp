@@ -424,6 +424,39 @@ static cadnn_status build_ptile_plan(const cadnn_weights* w, const ConvVariant* 
     return CADNN_OK;
 }
 
+bool stile_streams_fit(const cadnn_weights* w, const ConvVariant* v) {
+    const int G = v->rpw, taps = w->kh * w->kw, U = v->unroll;
+    const int nchunks = (w->cin + v->cch - 1) / v->cch;
+    // a dense layer's stream is the longest possible one
+    const int64_t dense_row = ((int64_t)std::min(w->cin, v->cch) * taps + U - 1) / U * U;
+    if (dense_row * G <= v->nz_cap) return true;
+    std::lock_guard<std::mutex> lock(w->stile_mu);
+    auto it = w->stile_ok.find(v);
+    if (it != w->stile_ok.end()) return it->second;
+    bool ok = true;
+    std::vector<int64_t> len(nchunks);
+    for (int g0 = 0; g0 < w->cout && ok; g0 += G) {
+        std::fill(len.begin(), len.end(), 0);
+        for (int i = g0; i < std::min(g0 + G, w->cout); ++i) {
+            int c = 0;
+            int64_t run = 0;
+            for (int32_t j = w->row_ptr[i]; j < w->row_ptr[i + 1]; ++j) {
+                const int cj = (w->col_idx[j] / taps) / v->cch;
+                if (cj != c) {
+                    len[c] += (run + U - 1) / U * U;
+                    run = 0;
+                    c = cj;
+                }
+                ++run;
+            }
+            len[c] += (run + U - 1) / U * U;
+        }
+        for (int c = 0; c < nchunks; ++c) ok = ok && len[c] <= v->nz_cap;
+    }
+    w->stile_ok[v] = ok;
+    return ok;
+}
+
 // Device copy of the nonzero stream for a wave-sliced tile (FAM_STILE) variant.
 //
 // Packed rows are taken G at a time (G = rows per workgroup).  For group g and channel

@@ -277,6 +277,35 @@ VARIANT_GEOMS = [
 ]
 
 
+@pytest.mark.parametrize("geom", [(12, 9, 5, 1, 2, 19, 23, 0.8, 2), (5, 11, 7, 3, 3, 19, 9, 0.9, 1),
+                                  (6, 4, 5, 2, 0, 11, 13, 1.0, 1), (7, 5, 2, 1, 1, 9, 8, 0.85, 1)])
+def test_geometries_without_a_sparse_kernel_run_dense(cad, geom):
+    """Filter sizes and strides off the beaten track on a plain tensor (5x5, 7x7 at stride 3,
+    2x2): whatever serves them -- the LDS-staged family while a tile of the input fits, else
+    the matrix-core kernel at any sparsity, an all-zero filter bank included -- every valid
+    geometry has at least one variant and each of them meets the bar."""
+    cin, cout, k, stride, pad, h, w_, s, n = geom
+    tag = "odd-%d-%d-%d-%d" % (cin, cout, k, stride)
+    x = wl.activation((n, cin, h, w_), tag, 0, relu=False)
+    w = wl.pruned_weights(cout, cin, k, k, s, tag, 1)
+    b = wl.bias_vector(cout, tag, 1, sigma=0.5)
+    for dtype, npdt, tol in ((cad.F32, np.float32, TOL_F32), (cad.F16, np.float16, TOL_F16)):
+        xs = x.astype(npdt)
+        hnd = cad.cadnn_pack_weights(w, dtype)
+        names = cad.cadnn_conv2d_list_variants(hnd, n, h, w_, stride, pad)
+        assert names, geom
+        if stride == 3:
+            assert all(nm.startswith("dense_mfma") for nm in names), names
+        ref = oracle.conv2d(xs, w.astype(npdt), b, None, stride, pad, True, npdt)
+        cond = cond_conv(xs, w.astype(npdt), b, None, stride, pad)
+        for name in [None] + names:
+            cad.cadnn_conv2d_set_variant(hnd, n, h, w_, stride, pad, name)
+            y = cad.cadnn_sparse_conv2d(hnd, dev(xs), stride, pad, dev(b), None, True)
+            torch.cuda.synchronize()
+            assert_layer_close(y.cpu().numpy(), ref, cond, tol, f"{geom} {name}", f16=dtype == cad.F16)
+        hnd.free()
+
+
 @pytest.mark.parametrize("geom", VARIANT_GEOMS)
 def test_every_kernel_variant(cad, geom):
     """Each instantiated kernel variant that can serve a layer is pinned in turn and must

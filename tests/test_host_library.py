@@ -122,8 +122,7 @@ def test_layer_argument_checks_without_a_gpu():
     assert L.cadnn_sparse_conv2d(h.handle, None, None, 1, 8, 8, 0, 1, None, None, 0, None) == 1
     assert L.cadnn_sparse_conv2d(h.handle, None, None, 1, 2, 2, 1, 0, None, None, 0, None) == 1   # empty output
     h5 = cad.cadnn_pack_weights(wl.pruned_weights(8, 4, 5, 5, 0.9, "packtest", 4))
-    assert L.cadnn_conv2d_prepare(h5.handle, 1, 8, 8, 1, 2) == 2                                    # no sparse 5x5 kernel
-    assert b"5x5" in L.cadnn_last_error()
+    assert cad.cadnn_conv2d_list_variants(h5, 1, 8, 8, 1, 2)                                         # 5x5: LDS-staged or dense kernels
     buf = ctypes.create_string_buffer(4096)
     assert L.cadnn_conv2d_list_variants(h.handle, 1, 8, 8, 1, 1, buf, 4096) == 0
     names = buf.value.decode().split("\n")
@@ -172,6 +171,34 @@ def test_depthwise_argument_checks_without_a_gpu():
     assert nbytes.value >= 4 * 10 * 10 * 4           # first output: 4 planes of 8x8 inside a 1-pixel zero halo
     assert L.cadnn_net_free(net) == 0
     for h in (dw, full, dw8):
+        h.free()
+
+
+def test_listed_variants_can_all_serve_the_layer():
+    """Listing and pinning variants is host work.  A variant of the wave-sliced LDS family
+    buffers the nonzeros of a (row group, channel chunk): it is listed only for weights whose
+    longest such stream fits its buffer, so a dense 3x3 bank loses the 16-row x 8-channel one
+    that an 80 % sparse bank keeps; every geometry has some variant (5x5 and stride-3 7x7
+    filters on a plain tensor included) and every listed name can be pinned."""
+    counts = {}
+    for s in (0.0, 0.8, 1.0):
+        h = cad.cadnn_pack_weights(wl.pruned_weights(75, 332, 3, 3, s, "variants", 1))
+        names = cad.cadnn_conv2d_list_variants(h, 2, 34, 11, 1, 1)
+        counts[s] = {nm for nm in names if nm.startswith("stile")}
+        for nm in names:
+            cad.cadnn_conv2d_set_variant(h, 2, 34, 11, 1, 1, nm)
+        assert cad.cadnn_conv2d_variant_name(h, 2, 34, 11, 1, 1) == names[-1]
+        cad.cadnn_conv2d_set_variant(h, 2, 34, 11, 1, 1, None)
+        assert cad.cadnn_conv2d_variant_name(h, 2, 34, 11, 1, 1) in names     # the untuned pick
+        h.free()
+    assert counts[0.8] == counts[1.0] and counts[0.0] < counts[0.8]
+    assert any("g16c8" in nm for nm in counts[0.8]) and not any("g16c8" in nm for nm in counts[0.0])
+    for (cin, cout, k, stride, pad, hh, ww, s) in [(12, 9, 5, 1, 2, 19, 23, 0.8), (5, 11, 7, 3, 3, 19, 9, 0.9),
+                                                  (6, 4, 2, 1, 1, 9, 8, 0.85), (300, 8, 5, 2, 2, 40, 40, 0.9)]:
+        h = cad.cadnn_pack_weights(wl.pruned_weights(cout, cin, k, k, s, "variants", 2))
+        names = cad.cadnn_conv2d_list_variants(h, 1, hh, ww, stride, pad)
+        assert names, (cin, cout, k, stride)
+        assert cad.cadnn_conv2d_variant_name(h, 1, hh, ww, stride, pad) in names
         h.free()
 
 
