@@ -105,7 +105,8 @@ cadnn_status cadnn_unpack_weights(const cadnn_weights* w, float* w_host_out);
  * net (whose tensors carry zero halos); a geometry none of them serves, and any layer with
  * at least a quarter of its weights nonzero, may take the dense matrix-core kernel.
  * Errors: EINVAL (NULL x/y/w, sizes <= 0, stride <= 0, pad < 0, empty output);
- * EUNSUPPORTED (sizes beyond the launch limits); EHIP.
+ * EUNSUPPORTED (batch above 65535, a channel plane of 2^30 elements or more, or one
+ * image of x or y of 2 GiB or more: the kernels address an image with 32-bit offsets); EHIP.
  * ------------------------------------------------------------------------- */
 cadnn_status cadnn_sparse_conv2d(const cadnn_weights* w, const void* x, void* y, int n, int h,
                                  int wdt, int stride, int pad, const void* bias,

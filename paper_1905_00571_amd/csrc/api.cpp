@@ -28,6 +28,7 @@ static cadnn_status check_conv(const char* who, const cadnn_weights* w, const Te
     if (n <= 0 || xd.h <= 0 || xd.w <= 0) return fail(CADNN_EINVAL, "%s: non-positive size", who);
     if (stride <= 0 || pad < 0) return fail(CADNN_EINVAL, "%s: bad stride/pad", who);
     if (xd.c != w->cin) return fail(CADNN_EINVAL, "%s: %d input channels, weights take %d", who, xd.c, w->cin);
+    if (desc_too_large(xd)) return fail(CADNN_EUNSUPPORTED, "%s: a channel plane of 2^30 elements or more", who);
     g->n = n; g->stride = stride; g->pad = pad; g->xd = xd; g->out_s2d = out_s2d; g->ex = ex;
     if (ex && !ex->w && !ex->pool_y && !ex->dw) return fail(CADNN_EINVAL, "%s: empty fusion request", who);
     if (ex && ex->dw) {
@@ -517,6 +518,8 @@ static cadnn_status check_depthwise(const char* who, const cadnn_weights* w, int
     if (n <= 0 || h <= 0 || wdt <= 0 || stride <= 0 || pad < 0) return fail(CADNN_EINVAL, "%s: bad size", who);
     if (conv_out(h, w->kh, stride, pad) <= 0 || conv_out(wdt, w->kw, stride, pad) <= 0)
         return fail(CADNN_EINVAL, "%s: empty output", who);
+    if (desc_too_large(make_desc(1, h, wdt)) || desc_too_large(make_desc(1, conv_out(h, w->kh, stride, pad), conv_out(wdt, w->kw, stride, pad))))
+        return fail(CADNN_EUNSUPPORTED, "%s: a channel plane of 2^30 elements or more", who);
     return CADNN_OK;
 }
 
@@ -552,6 +555,8 @@ extern "C" cadnn_status cadnn_maxpool2d(const void* x, void* y, int n, int c, in
     if (dtype != CADNN_F32 && dtype != CADNN_F16) return fail(CADNN_EINVAL, "cadnn_maxpool2d: dtype");
     if (conv_out(h, k, stride, pad) <= 0 || conv_out(wdt, k, stride, pad) <= 0)
         return fail(CADNN_EINVAL, "cadnn_maxpool2d: empty output");
+    if (desc_too_large(make_desc(c, h, wdt)) || desc_too_large(make_desc(c, conv_out(h, k, stride, pad), conv_out(wdt, k, stride, pad))))
+        return fail(CADNN_EUNSUPPORTED, "cadnn_maxpool2d: a channel plane of 2^30 elements or more");
     return launch_maxpool(x, make_desc(c, h, wdt), y,
                           make_desc(c, conv_out(h, k, stride, pad), conv_out(wdt, k, stride, pad)), n, k, stride,
                           pad, dtype, (hipStream_t)stream);
@@ -565,6 +570,8 @@ extern "C" cadnn_status cadnn_avgpool2d(const void* x, void* y, int n, int c, in
     if (dtype != CADNN_F32 && dtype != CADNN_F16) return fail(CADNN_EINVAL, "cadnn_avgpool2d: dtype");
     if (conv_out(h, k, stride, pad) <= 0 || conv_out(wdt, k, stride, pad) <= 0)
         return fail(CADNN_EINVAL, "cadnn_avgpool2d: empty output");
+    if (desc_too_large(make_desc(c, h, wdt)) || desc_too_large(make_desc(c, conv_out(h, k, stride, pad), conv_out(wdt, k, stride, pad))))
+        return fail(CADNN_EUNSUPPORTED, "cadnn_avgpool2d: a channel plane of 2^30 elements or more");
     return launch_avgpool2d(x, make_desc(c, h, wdt), y,
                             make_desc(c, conv_out(h, k, stride, pad), conv_out(wdt, k, stride, pad)), n, k, stride,
                             pad, dtype, (hipStream_t)stream);
@@ -575,5 +582,6 @@ extern "C" cadnn_status cadnn_global_avgpool(const void* x, void* y, int n, int 
     if (!x || !y) return fail(CADNN_EINVAL, "cadnn_global_avgpool: NULL tensor");
     if (n <= 0 || c <= 0 || h <= 0 || wdt <= 0) return fail(CADNN_EINVAL, "cadnn_global_avgpool: bad size");
     if (dtype != CADNN_F32 && dtype != CADNN_F16) return fail(CADNN_EINVAL, "cadnn_global_avgpool: dtype");
+    if (desc_too_large(make_desc(c, h, wdt))) return fail(CADNN_EUNSUPPORTED, "cadnn_global_avgpool: a channel plane of 2^30 elements or more");
     return launch_avgpool(x, make_desc(c, h, wdt), y, n, dtype, (hipStream_t)stream);
 }

@@ -223,6 +223,11 @@ cadnn_status dense_conv2d_impl(const void* w_dev, const void* x, void* y, int n,
     if (n > 65535 || (cout + BM - 1) / BM > 65535) return fail(CADNN_EUNSUPPORTED, "cadnn_dense_conv2d: too large");
     if ((int64_t)cin * kh * kw > (1 << 24)) return fail(CADNN_EUNSUPPORTED, "cadnn_dense_conv2d: cin*kh*kw above 2^24");
     const TensorDesc yd = make_desc(cout, hout, wout);
+    const int64_t elem = dtype == CADNN_F16 ? 2 : 4;
+    // (the kernel addresses one image with 32-bit element offsets)
+    if (desc_too_large(make_desc(cin, h, wdt)) || desc_too_large(yd) || (int64_t)cin * h * wdt * elem >= 0x7ffffff0ll ||
+        yd.image * elem >= 0x7ffffff0ll)
+        return fail(CADNN_EUNSUPPORTED, "cadnn_dense_conv2d: one image of a tensor is 2 GiB or more");
     return dense_conv2d_desc(w_dev, x, make_desc(cin, h, wdt), y, yd, residual, yd, n, cout, kh, kw, stride,
                              pad, bias, relu, dtype, s);
 }

@@ -32,8 +32,8 @@ void clear_error();
     } while (0)
 
 inline int conv_out(int size, int k, int stride, int pad) {
-    const int t = size + 2 * pad - k;
-    return t < 0 ? 0 : t / stride + 1;
+    const int64_t t = (int64_t)size + 2 * (int64_t)pad - k;
+    return t < 0 ? 0 : (int)std::min<int64_t>(t / stride + 1, INT32_MAX);
 }
 
 // ---- device buffer with RAII -------------------------------------------------
@@ -81,17 +81,27 @@ __host__ __device__ inline int tensor_off(const TensorDesc& d, int row, int col)
     return d.s2d ? ((R & 1) * 2 + (C & 1)) * d.sub + (R >> 1) * d.pitch + (C >> 1) : R * d.pitch + C;
 }
 
+// A plane of kMaxPlane elements or more does not fit the 32-bit element offsets the kernels
+// use: its descriptor is clamped there (never used for addressing) and every entry point
+// refuses it through desc_too_large.
+constexpr int kMaxPlane = 1 << 30;
 inline TensorDesc make_desc(int c, int h, int w, int ph = 0, int pw = 0) {
     TensorDesc d;
     d.c = c; d.h = h; d.w = w; d.ph = ph; d.pw = pw;
-    d.pitch = w + 2 * pw;
-    d.plane = (h + 2 * ph) * d.pitch;
-    d.origin = ph * d.pitch + pw;
+    const int64_t pitch = (int64_t)w + 2 * (int64_t)pw;
+    const int64_t plane = ((int64_t)h + 2 * (int64_t)ph) * pitch;
+    const bool fits = plane < kMaxPlane;
+    d.pitch = fits ? (int)pitch : 0;
+    d.plane = fits ? (int)plane : kMaxPlane;
+    d.origin = fits ? ph * d.pitch + pw : 0;
     d.image = (int64_t)c * d.plane;
     d.s2d = 0; d.sub = 0;
     return d;
 }
+inline bool desc_too_large(const TensorDesc& d) { return d.plane >= kMaxPlane; }
 
+// (callers have checked the plain descriptor of the same tensor with desc_too_large: the
+// rounding up of odd sizes adds less than a row and a column)
 inline TensorDesc make_desc_s2d(int c, int h, int w, int ph, int pw) {
     TensorDesc d;
     d.c = c; d.h = h; d.w = w; d.ph = ph; d.pw = pw;

@@ -104,8 +104,17 @@ const void* eff_bias(const cadnn_net* net, const NetOp& op) {
     return it == net->merged_bias.end() ? nullptr : it->second->p;
 }
 
+// One image of a tensor, with the zero halo a reader asks for, must stay addressable with the
+// kernels' 32-bit offsets (with room for the rounding of the de-interleaved layout).
+bool tensor_fits(const cadnn_net* net, const Shape& s, int halo) {
+    if (halo > 65535) return false;
+    const TensorDesc d = make_desc(s.c, s.h, s.w, halo, halo);
+    return !desc_too_large(d) && d.image * (int64_t)net->elem() < 0x70000000ll;
+}
+
 cadnn_status note_output(cadnn_net* net, int dst, const Shape& s) {
     if (dst <= 0) return fail(CADNN_EINVAL, "cadnn_net: dst buffer must be >= 1 (0 is the input)");
+    if (!tensor_fits(net, s, 0)) return fail(CADNN_EUNSUPPORTED, "cadnn_net: one image of buffer %d would be 1.75 GiB or more", dst);
     net->cur[dst] = s;
     net->producer[dst] = (int)net->ops.size();
     net->laid_out = false;
@@ -185,6 +194,11 @@ void layout(cadnn_net* net) {
                 if (!eligible(j) || b.src_inst != a.src_inst || b.src != a.src || b.relu != a.relu || b.w->cin != a.w->cin ||
                     (a.bias == nullptr) != (b.bias == nullptr))
                     continue;
+                // (the shared region must stay addressable like any tensor, under any reader's halo)
+                int total_c = b.out.c, h = std::max(halo[i], halo[j]);
+                for (const cadnn_weights* p : parts) total_c += p->cout;
+                for (int g : group) h = std::max(h, halo[g]);
+                if (!tensor_fits(net, Shape{a.out.n, total_c, a.out.h, a.out.w}, h)) continue;
                 parts.push_back(b.w);
                 group.push_back(j);
             }
@@ -448,6 +462,8 @@ extern "C" cadnn_status cadnn_net_create(cadnn_dtype dtype, int n, int c, int h,
     if (!out) return fail(CADNN_EINVAL, "cadnn_net_create: NULL out");
     if (n <= 0 || c <= 0 || h <= 0 || w <= 0) return fail(CADNN_EINVAL, "cadnn_net_create: bad shape");
     if (dtype != CADNN_F32 && dtype != CADNN_F16) return fail(CADNN_EINVAL, "cadnn_net_create: dtype");
+    if (desc_too_large(make_desc(c, h, w)) || (int64_t)c * h * w * (dtype == CADNN_F16 ? 2 : 4) >= 0x7ffffff0ll)
+        return fail(CADNN_EUNSUPPORTED, "cadnn_net_create: one input image is 2 GiB or more");
     cadnn_net* net = new (std::nothrow) cadnn_net();
     if (!net) return fail(CADNN_ENOMEM, "cadnn_net_create: out of memory");
     net->dtype = dtype;
@@ -469,6 +485,7 @@ extern "C" cadnn_status cadnn_net_add_conv(cadnn_net* net, const cadnn_weights* 
     if (st != CADNN_OK) return st;
     if (op.in.c != w->cin) return fail(CADNN_EINVAL, "cadnn_net_add_conv: %d input channels, weights take %d", op.in.c, w->cin);
     if (stride <= 0 || pad < 0) return fail(CADNN_EINVAL, "cadnn_net_add_conv: bad stride/pad");
+    if (!tensor_fits(net, op.in, pad)) return fail(CADNN_EUNSUPPORTED, "cadnn_net_add_conv: one padded input image would be 1.75 GiB or more");
     op.out = Shape{op.in.n, w->cout, conv_out(op.in.h, w->kh, stride, pad), conv_out(op.in.w, w->kw, stride, pad)};
     if (op.out.h <= 0 || op.out.w <= 0) return fail(CADNN_EINVAL, "cadnn_net_add_conv: empty output");
     if (res >= 0) {
@@ -495,6 +512,7 @@ extern "C" cadnn_status cadnn_net_add_depthwise(cadnn_net* net, const cadnn_weig
     if (st != CADNN_OK) return st;
     if (op.in.c != w->cout) return fail(CADNN_EINVAL, "cadnn_net_add_depthwise: %d channels, %d filters", op.in.c, w->cout);
     if (stride <= 0 || pad < 0) return fail(CADNN_EINVAL, "cadnn_net_add_depthwise: bad stride/pad");
+    if (!tensor_fits(net, op.in, pad)) return fail(CADNN_EUNSUPPORTED, "cadnn_net_add_depthwise: one padded input image would be 1.75 GiB or more");
     op.out = Shape{op.in.n, op.in.c, conv_out(op.in.h, w->kh, stride, pad), conv_out(op.in.w, w->kw, stride, pad)};
     if (op.out.h <= 0 || op.out.w <= 0) return fail(CADNN_EINVAL, "cadnn_net_add_depthwise: empty output");
     op.kind = OP_DEPTHWISE; op.w = w; op.bias = bias; op.stride = stride; op.pad = pad; op.relu = relu;

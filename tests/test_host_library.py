@@ -174,6 +174,38 @@ def test_depthwise_argument_checks_without_a_gpu():
         h.free()
 
 
+def test_sizes_beyond_32_bit_offsets_are_refused_on_the_host():
+    """Tensors whose channel plane or image does not fit the kernels' 32-bit offsets, and
+    paddings that would overflow the size arithmetic, are refused (CADNN_EUNSUPPORTED = 2, or
+    EINVAL = 1 for an empty output) before anything touches a device."""
+    L = cad.lib()
+    h = cad.cadnn_pack_weights(wl.pruned_weights(4, 2, 3, 3, 0.5, "big", 1))
+    one = ctypes.c_void_p(16)          # never dereferenced: the checks come first
+    big = 1 << 16
+    assert L.cadnn_sparse_conv2d(h.handle, one, one, 1, big, big, 1, 1, None, None, 0, None) == 2
+    assert L.cadnn_sparse_conv2d(h.handle, one, one, 1, 8, 8, 1, 1 << 30, None, None, 0, None) == 2
+    assert L.cadnn_conv2d_prepare(h.handle, 1, 40000, 40000, 1, 1) == 2
+    assert L.cadnn_conv2d_prepare(h.handle, 1, 20000, 20000, 1, 1) == 2          # 2 x 4e8 x 4 bytes: above 2 GiB
+    assert L.cadnn_maxpool2d(one, one, 1, 1, big, big, 2, 2, 0, 0, None) == 2
+    assert L.cadnn_avgpool2d(one, one, 1, 1, big, big, 3, 1, 1, 0, None) == 2
+    assert L.cadnn_global_avgpool(one, one, 1, 1, big, big, 0, None) == 2
+    assert L.cadnn_dense_conv2d(one, one, ctypes.c_void_p(32), 1, 2, big, big, 4, 3, 3, 1, 1, None, None, 0, 0, None) == 2
+    dw = cad.cadnn_pack_weights(wl.pruned_weights(2, 1, 3, 3, 0.0, "big", 2))
+    assert L.cadnn_depthwise_conv2d(dw.handle, one, one, 1, big, big, 1, 1, None, 0, None) == 2
+    net = ctypes.c_void_p()
+    assert L.cadnn_net_create(0, 1, 64, 4096, 4096, ctypes.byref(net)) == 2 and not net.value
+    assert L.cadnn_net_create(0, 1, 2, 4096, 4096, ctypes.byref(net)) == 0
+    assert L.cadnn_net_add_conv(net, h.handle, None, 1, 70000, 1, 0, 1, -1) == 2       # halo beyond the limit
+    assert L.cadnn_net_add_conv(net, h.handle, None, 1, 8000, 1, 0, 1, -1) == 2        # padded image above the limit
+    assert L.cadnn_net_add_conv(net, h.handle, None, 1, 1, 1, 0, 1, -1) == 0
+    wide = cad.cadnn_pack_weights(wl.pruned_weights(64, 4, 1, 1, 0.5, "big", 3))
+    assert L.cadnn_net_add_conv(net, wide.handle, None, 1, 0, 1, 1, 2, -1) == 2        # 64 x 4096 x 4096 x 4 bytes
+    assert b"GiB" in L.cadnn_last_error()
+    assert L.cadnn_net_free(net) == 0
+    for x in (h, dw, wide):
+        x.free()
+
+
 def test_listed_variants_can_all_serve_the_layer():
     """Listing and pinning variants is host work.  A variant of the wave-sliced LDS family
     buffers the nonzeros of a (row group, channel chunk): it is listed only for weights whose
