@@ -266,14 +266,17 @@ def main() -> int:
             costs[j]["bytes"] += costs[i]["bytes"] - 2.0 * map_bytes
             costs[i]["flops"] = costs[i]["bytes"] = 0.0
             continue
-        j = next((k for k in range(i + 1, len(ops)) if ops[k].kind == "conv" and ops[k].res == op.dst), None)
-        if j is None:
-            # a 1x1 layer merged into an earlier 1x1 layer on the same input (one launch over the
-            # rows of both): its work moves there; the shared input is read once
-            j = next(k for k in range(i) if ops[k].kind == "conv" and ops[k].src == op.src and ops[k].k == 1
-                     and names[k] != "fused" and costs[k]["in"] == costs[i]["in"])
+        info = net.op_info(i)
+        j = info["fused_into"]
+        if j < i:
+            # launched by an earlier layer's kernel: as rows of a 1x1 layer on the same input
+            # (the shared input is read once), or as an independent layer in the same launch
+            # (nothing saved but the launch); its work moves there
+            shared_in = 0.0 if info["launched_with"] else float(np.prod(costs[i]["in"])) * elem
+            while names[j] == "fused":       # (the first layer of a sibling group may itself ride on another launch)
+                j = net.op_info(j)["fused_into"]
             costs[j]["flops"] += costs[i]["flops"]
-            costs[j]["bytes"] += costs[i]["bytes"] - float(np.prod(costs[i]["in"])) * elem
+            costs[j]["bytes"] += costs[i]["bytes"] - shared_in
             costs[j]["nnz"] += costs[i]["nnz"]
             costs[i]["flops"] = costs[i]["bytes"] = 0.0
             continue

@@ -248,7 +248,13 @@ cadnn_status cadnn_net_workspace_bytes(const cadnn_net* net, size_t* bytes);
  * convolutions with the same activation and no residual that read the same tensor are
  * launched as one layer over the rows of all of them: the later ones report fused_into =
  * the first one, variant "fused" and time zero, their outputs are channel slices of the
- * first one's region, from channel slice_channel on, and stay readable. */
+ * first one's region, from channel slice_channel on, and stay readable.  And sparse
+ * convolutions on plain tensors whose inputs are all ready when an earlier one runs (the
+ * branches of an Inception module at the same depth, up to eight) are launched with it as one
+ * kernel over a table of launch records, while one variant serves them all: they report
+ * fused_into = that op and launched_with = 1, the op's variant name is the group's, and
+ * cadnn_net_op_candidates / cadnn_net_set_op_variant on it list / pin variants for the whole
+ * group.  Tuning (CADNN_NET_TUNE) keeps a group only if it beats its layers launched apart. */
 #define CADNN_NET_GRAPH 1
 #define CADNN_NET_TUNE 2
 #define CADNN_NET_PLAIN_LAYOUT 4
@@ -267,10 +273,13 @@ typedef struct {
     int deinterleaved;       /* 1 = split by row / column parity (read by stride-2 layers) */
     int64_t offset;          /* byte offset of channel 0 of image 0 in the workspace (the last
                                 op writes the caller's y: its offset is 0 and means nothing) */
-    int fused_into;          /* >= 0: the op is computed inside that op and launches nothing */
+    int fused_into;          /* >= 0: the op launches nothing of its own: it is computed inside
+                                that op, or (launched_with = 1) by the same kernel launch */
     int slice_of;            /* >= 0: the op writes in place into that concatenation's region */
     int slice_channel;       /* ... starting at this channel of it (for a sibling layer: of
                                 the region of the op named by fused_into) */
+    int launched_with;       /* 1: an independent layer that shares the kernel launch of op
+                                fused_into; its tensors and its region are its own */
 } cadnn_op_info;
 cadnn_status cadnn_net_op_info(cadnn_net* net, int op_index, int flags, cadnn_op_info* out);
 cadnn_status cadnn_run_net(cadnn_net* net, const void* x, void* y, void* stream);

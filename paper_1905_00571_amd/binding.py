@@ -34,7 +34,7 @@ class OpInfo(ctypes.Structure):
     _fields_ = [("halo_h", ctypes.c_int), ("halo_w", ctypes.c_int), ("pitch", ctypes.c_int),
                 ("plane", ctypes.c_int64), ("image", ctypes.c_int64), ("deinterleaved", ctypes.c_int),
                 ("offset", ctypes.c_int64), ("fused_into", ctypes.c_int), ("slice_of", ctypes.c_int),
-                ("slice_channel", ctypes.c_int)]
+                ("slice_channel", ctypes.c_int), ("launched_with", ctypes.c_int)]
 
 
 def lib_path() -> str:
@@ -346,13 +346,21 @@ def cadnn_dense_conv2d(w_dev, x, stride: int = 1, pad: int = 0, bias=None, resid
 class Net:
     """Owner of a cadnn_net handle plus the tensors it points into."""
 
-    def __init__(self, handle: int, dtype: int, in_shape, out_shape, keep: list, ops: Sequence):
+    def __init__(self, handle: int, dtype: int, in_shape, out_shape, keep: list, ops: Sequence, flags: int = 0):
         self.handle = handle
+        self.flags = flags
         self.dtype = dtype
         self.in_shape = tuple(in_shape)
         self.out_shape = tuple(out_shape)
         self._keep = keep
         self.ops = list(ops)
+
+    def op_info(self, op_index: int) -> dict:
+        """Where op `op_index` puts its output and whether it launches (cadnn_net_op_info, for the
+        flags the net was finalized with; after live tuning it shows the groups that were kept)."""
+        info = OpInfo()
+        _check(lib().cadnn_net_op_info(self.handle, op_index, self.flags, ctypes.byref(info)))
+        return {name: getattr(info, name) for name, _ in OpInfo._fields_}
 
     def num_ops(self) -> int:
         n = _i()
@@ -525,4 +533,4 @@ def build_net(ops: Sequence, weights: Sequence, biases: Sequence, input_shape, d
     except Exception:
         L.cadnn_net_free(handle)
         raise
-    return Net(handle.value, dtype, input_shape, shapes[ops[-1].dst], keep, ops)
+    return Net(handle.value, dtype, input_shape, shapes[ops[-1].dst], keep, ops, flags)

@@ -144,48 +144,57 @@ static std::vector<const ConvVariant*> candidates(const cadnn_weights* w, const 
 // with constants fitted to the tuner's timings of every variant on ResNet-50, VGG-16,
 // MobileNet-V1 and Inception-V3 at batch 1 and ResNet-50 at batch 8 (its pick costs 8-15 %
 // over the tuned choice; the fit leaves the L1 term almost no weight).
+// Modelled cycles of one launch of variant v on the layer; negative: not modelled (the
+// LDS-staged families, chosen by tuning only).
+static double variant_cost(const cadnn_weights* w, const ConvGeom& g, const ConvVariant* v) {
+    const double nnz_row = w->cout ? (double)w->nnz / w->cout : 0.0;
+    const double pixels = (double)g.hout * g.wout;
+    double cost;
+    if (v->family == FAM_DENSE) {
+        // matrix cores: 64 x 64 tiles, ~1024 cycles per 32-deep chunk of K per tile
+        const double blocks = std::ceil(pixels / 64.0) * g.n * std::ceil(w->cout / 64.0);
+        const double K = (double)w->cin * w->kh * w->kw;
+        cost = 2500.0 + std::ceil(blocks / 256.0) * std::ceil(K / 32.0) * 1100.0;
+    } else if (v->family == FAM_STILE || v->family == FAM_PTILE) {
+        return -1.0;
+    } else if (v->family != FAM_TILE) {
+        const int P = v->p;
+        const double walked = v->adjacent == 2 ? (double)g.hout * ((g.wout + P - 1) / P * P) : pixels;
+        const double tiles = std::ceil(walked / (64.0 * P)) * g.n;
+        const double blocks = tiles * std::ceil((double)w->cout / v->rows_per_block());
+        const double waves = blocks * v->nw;
+        const double iters = v->rpw * nnz_row / v->ks;
+        const double line_bytes = 256.0 * P * ((g.stride == 2 && !g.xd.s2d) ? 2.0 : 1.0);
+        const double t_l1 = waves * iters * line_bytes / 32.0 / 256.0;
+        const double instrs = v->adjacent ? 3.0 + P : 2.0 + 2.0 * P;
+        const double t_issue = waves * (1787.0 + iters * instrs * 1.21) / 1024.0;
+        const double per_nz = 77.4 * (1.0 + 0.51 * (P - 1)) / (1.0 + 0.079 * std::log2(v->unroll / 4.0));
+        const double t_wave = 382.0 + iters * per_nz + (v->ks > 1 ? 338.0 * std::log2((double)v->ks) : 0.0);
+        const double rounds = std::ceil(waves / (1024.0 * 2.3));
+        cost = std::max(std::max(t_wave * rounds, t_issue), 0.078 * t_l1);
+        if (v->family == FAM_DIRECT) cost *= 1.3;   // per-lane tap offsets, bounds by range check
+    } else {
+        const double tiles = std::ceil((double)g.wout / v->tw) * std::ceil((double)g.hout / v->th) * g.n;
+        const double blocks = tiles * std::ceil((double)w->cout / v->rows_per_block());
+        const double nchunks = std::ceil((double)w->cin / v->cch);
+        const double stage = nchunks * (1500.0 + (double)std::min(w->cin, v->cch) * v->plane / (v->nw * 64.0) * 24.0);
+        const double iters = v->rpw * nnz_row;
+        const double t_block = stage + iters * (10.0 + 6.0 * v->p);
+        const double rounds = std::ceil(blocks / 256.0);
+        cost = t_block * rounds * 2.0;   // until tuned, prefer the staging-free families
+    }
+    return cost;
+}
+
 static const ConvVariant* heuristic_variant(const cadnn_weights* w, const ConvGeom& g) {
     const std::vector<const ConvVariant*> cand = candidates(w, g);
     if (cand.empty()) return nullptr;
     const double nnz_row = w->cout ? (double)w->nnz / w->cout : 0.0;
-    const double pixels = (double)g.hout * g.wout;
     const ConvVariant* best = nullptr;
     double best_cost = 0.0;
     for (const ConvVariant* v : cand) {
-        double cost;
-        if (v->family == FAM_DENSE) {
-            // matrix cores: 64 x 64 tiles, ~1024 cycles per 32-deep chunk of K per tile
-            const double blocks = std::ceil(pixels / 64.0) * g.n * std::ceil(w->cout / 64.0);
-            const double K = (double)w->cin * w->kh * w->kw;
-            cost = 2500.0 + std::ceil(blocks / 256.0) * std::ceil(K / 32.0) * 1100.0;
-        } else if (v->family == FAM_STILE || v->family == FAM_PTILE) {
-            continue;   // chosen by tuning only
-        } else if (v->family != FAM_TILE) {
-            const int P = v->p;
-            const double walked = v->adjacent == 2 ? (double)g.hout * ((g.wout + P - 1) / P * P) : pixels;
-            const double tiles = std::ceil(walked / (64.0 * P)) * g.n;
-            const double blocks = tiles * std::ceil((double)w->cout / v->rows_per_block());
-            const double waves = blocks * v->nw;
-            const double iters = v->rpw * nnz_row / v->ks;
-            const double line_bytes = 256.0 * P * ((g.stride == 2 && !g.xd.s2d) ? 2.0 : 1.0);
-            const double t_l1 = waves * iters * line_bytes / 32.0 / 256.0;
-            const double instrs = v->adjacent ? 3.0 + P : 2.0 + 2.0 * P;
-            const double t_issue = waves * (1787.0 + iters * instrs * 1.21) / 1024.0;
-            const double per_nz = 77.4 * (1.0 + 0.51 * (P - 1)) / (1.0 + 0.079 * std::log2(v->unroll / 4.0));
-            const double t_wave = 382.0 + iters * per_nz + (v->ks > 1 ? 338.0 * std::log2((double)v->ks) : 0.0);
-            const double rounds = std::ceil(waves / (1024.0 * 2.3));
-            cost = std::max(std::max(t_wave * rounds, t_issue), 0.078 * t_l1);
-            if (v->family == FAM_DIRECT) cost *= 1.3;   // per-lane tap offsets, bounds by range check
-        } else {
-            const double tiles = std::ceil((double)g.wout / v->tw) * std::ceil((double)g.hout / v->th) * g.n;
-            const double blocks = tiles * std::ceil((double)w->cout / v->rows_per_block());
-            const double nchunks = std::ceil((double)w->cin / v->cch);
-            const double stage = nchunks * (1500.0 + (double)std::min(w->cin, v->cch) * v->plane / (v->nw * 64.0) * 24.0);
-            const double iters = v->rpw * nnz_row;
-            const double t_block = stage + iters * (10.0 + 6.0 * v->p);
-            const double rounds = std::ceil(blocks / 256.0);
-            cost = t_block * rounds * 2.0;   // until tuned, prefer the staging-free families
-        }
+        const double cost = variant_cost(w, g, v);
+        if (cost < 0.0) continue;   // chosen by tuning only
         if (!best || cost < best_cost) { best = v; best_cost = cost; }
     }
     if (!best) {
@@ -208,11 +217,13 @@ static const ConvVariant* pick_variant(const cadnn_weights* w, const ConvGeom& g
     return heuristic_variant(w, g);
 }
 
-static cadnn_status launch_variant(const cadnn_weights* w, const ConvVariant* v, const ConvGeom& g,
-                                   const void* x, void* y, const TensorDesc& yd, const void* residual,
-                                   const TensorDesc& rd, const void* bias, int relu, hipStream_t s) {
+// The launch record of variant v on the layer (builds and uploads the variant's plan on first use).
+static cadnn_status make_launch(const cadnn_weights* w, const ConvVariant* v, const ConvGeom& g,
+                                const void* x, void* y, const TensorDesc& yd, const void* residual,
+                                const TensorDesc& rd, const void* bias, int relu, ConvLaunch* out,
+                                std::shared_ptr<ConvPlan>* keep = nullptr) {
     const ConvPlan* plan = nullptr;
-    cadnn_status st = get_conv_plan(w, v, g.xd, g.stride, g.pad, g.wout, &plan, g.ex);
+    cadnn_status st = get_conv_plan(w, v, g.xd, g.stride, g.pad, g.wout, &plan, g.ex, keep);
     if (st != CADNN_OK) return st;
     ConvLaunch a{};
     a.x = x;
@@ -282,8 +293,141 @@ static cadnn_status launch_variant(const cadnn_weights* w, const ConvVariant* v,
         a.tiles_y = 1;
     }
     a.row_groups = plan->rows_padded / v->rows_per_block();
+    *out = a;
+    return CADNN_OK;
+}
+
+static cadnn_status launch_variant(const cadnn_weights* w, const ConvVariant* v, const ConvGeom& g,
+                                   const void* x, void* y, const TensorDesc& yd, const void* residual,
+                                   const TensorDesc& rd, const void* bias, int relu, hipStream_t s) {
+    ConvLaunch a;
+    cadnn_status st = make_launch(w, v, g, x, y, yd, residual, rd, bias, relu, &a);
+    if (st != CADNN_OK) return st;
     CADNN_HIP(v->launch(a, s));
     return CADNN_OK;
+}
+
+// ---- independent layers in one launch ---------------------------------------------
+static cadnn_status check_io(const char* who, const cadnn_weights* w, const ConvGeom& g, const void* x,
+                             void* y, const TensorDesc& yd, const void* residual, const TensorDesc& rd);
+static cadnn_status member_geom(const ConvMember& m, int n, ConvGeom* g) {
+    cadnn_status st = check_conv("cadnn_net (co-launched layers)", m.w, m.xd, n, m.stride, m.pad, g,
+                                 m.yd.s2d || (m.residual && m.rd.s2d), nullptr);
+    if (st != CADNN_OK) return st;
+    return check_io("cadnn_net (co-launched layers)", m.w, *g, m.x, m.y, m.yd, m.residual, m.rd);
+}
+
+cadnn_status conv2d_group_candidates(const std::vector<ConvMember>& members, int n,
+                                     std::vector<const ConvVariant*>* out, const ConvVariant** pick) {
+    out->clear();
+    if (pick) *pick = nullptr;
+    std::vector<ConvGeom> geoms(members.size());
+    for (size_t k = 0; k < members.size(); ++k) {
+        cadnn_status st = member_geom(members[k], n, &geoms[k]);
+        if (st != CADNN_OK) return st;
+    }
+    if (members.empty()) return CADNN_OK;
+    for (const ConvVariant* v : candidates(members[0].w, geoms[0])) {
+        if (!v->launch_multi) continue;
+        bool all = true;
+        for (size_t k = 1; k < members.size() && all; ++k) all = variant_fits(*v, members[k].w, geoms[k]);
+        if (all) out->push_back(v);
+    }
+    // untuned pick: the layers run side by side, so the slowest of them decides
+    double best = 0.0;
+    for (const ConvVariant* v : *out) {
+        double worst = 0.0;
+        for (size_t k = 0; k < members.size(); ++k) worst = std::max(worst, variant_cost(members[k].w, geoms[k], v));
+        if (pick && (!*pick || worst < best)) { *pick = v; best = worst; }
+    }
+    return CADNN_OK;
+}
+
+cadnn_status conv2d_group_records(const std::vector<ConvMember>& members, int n, const ConvVariant* v,
+                                  std::vector<ConvLaunch>* records, int* tiles_x, int* row_groups,
+                                  std::vector<std::shared_ptr<ConvPlan>>* keep) {
+    records->resize(members.size());
+    if (keep) keep->assign(members.size(), nullptr);
+    *tiles_x = 0;
+    *row_groups = 0;
+    if (!v || !v->launch_multi) return fail(CADNN_EINVAL, "cadnn_net: variant cannot launch several layers");
+    for (size_t k = 0; k < members.size(); ++k) {
+        const ConvMember& m = members[k];
+        ConvGeom g;
+        cadnn_status st = member_geom(m, n, &g);
+        if (st != CADNN_OK) return st;
+        if (!variant_fits(*v, m.w, g)) return fail(CADNN_EINVAL, "cadnn_net: '%s' does not serve every co-launched layer", v->name);
+        if ((st = make_launch(m.w, v, g, m.x, m.y, m.yd, m.residual, m.rd, m.bias, m.relu, &(*records)[k],
+                              keep ? &(*keep)[k] : nullptr)) != CADNN_OK) return st;
+        *tiles_x = std::max(*tiles_x, (*records)[k].tiles_x);
+        *row_groups = std::max(*row_groups, (*records)[k].row_groups);
+    }
+    if ((int64_t)members.size() * n > 65535 || *row_groups > 65535)
+        return fail(CADNN_EUNSUPPORTED, "cadnn_net: co-launched layers exceed the grid limits");
+    return CADNN_OK;
+}
+
+// Times every variant that serves all members in one launch, the way conv2d_tune_impl times a
+// single layer (caches swept, `before` launched, one event-timed launch per repeat).
+cadnn_status conv2d_group_tune(const std::vector<ConvMember>& members, int n, hipStream_t s, int reps,
+                               const std::function<cadnn_status()>* before, const ConvVariant** best_v,
+                               float* best_us) {
+    *best_v = nullptr;
+    if (reps <= 0) return fail(CADNN_EINVAL, "cadnn_net: reps must be positive");
+    std::vector<const ConvVariant*> cand;
+    cadnn_status st = conv2d_group_candidates(members, n, &cand, nullptr);
+    if (st != CADNN_OK) return st;
+    if (cand.empty()) return CADNN_OK;
+    DevBuf sweep;
+    const size_t sweep_bytes = (size_t)64 << 20;
+    if (hipMalloc(&sweep.p, 2 * sweep_bytes) != hipSuccess) {
+        sweep.p = nullptr;
+        return fail(CADNN_ENOMEM, "cadnn_net: no memory for the cache sweep buffer");
+    }
+    sweep.bytes = 2 * sweep_bytes;
+    if (hipMemsetAsync(sweep.p, 0, 2 * sweep_bytes, s) != hipSuccess) return fail(CADNN_EHIP, "hipMemsetAsync failed");
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    CADNN_HIP(hipEventCreate(&e0));
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return fail(CADNN_EHIP, "hipEventCreate failed"); }
+    float best_ms = 0.0f;
+    std::vector<ConvLaunch> recs;
+    for (const ConvVariant* v : cand) {
+        int tx = 0, rg = 0;
+        if (conv2d_group_records(members, n, v, &recs, &tx, &rg) != CADNN_OK) continue;   // does not fit these weights
+        DevBuf table;
+        if ((st = table.upload(recs.data(), recs.size() * sizeof(ConvLaunch))) != CADNN_OK) break;
+        const ConvLaunch* tab = (const ConvLaunch*)table.p;
+        if (v->launch_multi(tab, (int)recs.size(), tx, rg, n, s) != hipSuccess) { st = fail(CADNN_EHIP, "co-launch failed"); break; }
+        float total_ms = 0.0f;
+        for (int i = 0; i < reps && st == CADNN_OK; ++i) {
+            st = launch_copy(sweep.p, (char*)sweep.p + sweep_bytes, sweep_bytes, s);
+            if (st != CADNN_OK) break;
+            if (before && (st = (*before)()) != CADNN_OK) break;
+            if (hipEventRecord(e0, s) != hipSuccess) { st = fail(CADNN_EHIP, "hipEventRecord failed"); break; }
+            if (v->launch_multi(tab, (int)recs.size(), tx, rg, n, s) != hipSuccess) { st = fail(CADNN_EHIP, "co-launch failed"); break; }
+            if (hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess) { st = fail(CADNN_EHIP, "event wait failed"); break; }
+            float ms = 0.0f;
+            if (hipEventElapsedTime(&ms, e0, e1) != hipSuccess) { st = fail(CADNN_EHIP, "hipEventElapsedTime failed"); break; }
+            total_ms += ms;
+        }
+        if (st != CADNN_OK) break;
+        if (hipStreamSynchronize(s) != hipSuccess) { st = fail(CADNN_EHIP, "hipStreamSynchronize failed"); break; }   // before the table goes
+        if (std::getenv("CADNN_TUNE_LOG"))
+            std::fprintf(stderr, "[cadnn tune] %zu layers at once %-44s %8.2f us\n", members.size(), v->name, total_ms * 1e3f / reps);
+        if (!*best_v || total_ms < best_ms) { *best_v = v; best_ms = total_ms; }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (st != CADNN_OK) return st;
+    for (const ConvMember& m : members) drop_unpinned_plans(m.w);
+    if (best_us) *best_us = best_ms * 1e3f / reps;
+    return CADNN_OK;
+}
+
+const ConvVariant* conv2d_variant_by_name(const char* name) {
+    if (!name) return nullptr;
+    for (const ConvVariant& v : all_linear_variants()) if (std::strcmp(v.name, name) == 0) return &v;
+    return nullptr;
 }
 
 static cadnn_status check_io(const char* who, const cadnn_weights* w, const ConvGeom& g, const void* x,

@@ -244,8 +244,9 @@ __device__ __forceinline__ void lin_pixel(const ConvLaunch& a, int q, int& oh, i
     }
 }
 
+// One workgroup of one layer: pixel tile bx, row group by, image n.
 template <class Cfg>
-__global__ __launch_bounds__(Cfg::THREADS) void sconv_linear_kernel(const ConvLaunch a) {
+__device__ __forceinline__ void sconv_linear_block(const ConvLaunch& a, const int bx, const int by, const int n) {
     using T = typename Cfg::T;
     constexpr int P = Cfg::P, RPW = Cfg::RPW, KS = Cfg::KS, RG = Cfg::RG, ADJ = Cfg::ADJ;
     __shared__ float red[KS > 1 ? Cfg::NW * RPW * P * 64 : 1];
@@ -256,12 +257,11 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_linear_kernel(const ConvLa
     // different rows of one pixel tile, so that a channel's whole image meets in LDS)
     constexpr bool TW = Cfg::DW == 2;
     const int rg = TW ? 0 : wv / KS, ks = TW ? 0 : wv % KS;
-    const int n = blockIdx.z;
     // Workgroups in plain launch order.  (Die-aware placements were measured -- workgroup
     // L runs on die L % 8: giving each die its own pixel tiles leaves most of the chip idle
     // on layers with few tiles and gains nothing on the others, and giving each die its
     // own rows changes nothing.)
-    const int tile = TW ? wv : (int)blockIdx.x, grp = blockIdx.y;
+    const int tile = TW ? wv : bx, grp = by;
     const int q0 = tile * (64 * P);
     const int row0 = TW ? grp * RPW : (grp * RG + rg) * RPW;
 
@@ -503,10 +503,36 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_linear_kernel(const ConvLa
 }
 
 template <class Cfg>
+__global__ __launch_bounds__(Cfg::THREADS) void sconv_linear_kernel(const ConvLaunch a) {
+    sconv_linear_block<Cfg>(a, (int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z);
+}
+
+// Several independent layers in one launch (the branches of an Inception module at the same
+// depth): blockIdx.z counts (layer, image), the layer's launch record is read from a table in
+// device memory -- a wave-uniform address, so it arrives through the scalar cache like the
+// kernel arguments would -- and workgroups beyond a smaller layer's own grid leave at once.
+template <class Cfg>
+__global__ __launch_bounds__(Cfg::THREADS) void sconv_linear_multi_kernel(const ConvLaunch* __restrict__ table, const int images) {
+    const int layer = (int)blockIdx.z / images;
+    const ConvLaunch a = table[layer];
+    if ((int)blockIdx.x >= a.tiles_x || (int)blockIdx.y >= a.row_groups) return;
+    sconv_linear_block<Cfg>(a, (int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z - layer * images);
+}
+
+template <class Cfg>
 static hipError_t launch_linear(const ConvLaunch& a, hipStream_t s) {
     dim3 grid((unsigned)a.tiles_x, (unsigned)a.row_groups, (unsigned)a.n);
     dim3 block(Cfg::THREADS);
     hipLaunchKernelGGL(sconv_linear_kernel<Cfg>, grid, block, 0, s, a);
+    return hipGetLastError();
+}
+
+template <class Cfg>
+static hipError_t launch_linear_multi(const ConvLaunch* table, int layers, int tiles_x, int row_groups, int images,
+                                      hipStream_t s) {
+    dim3 grid((unsigned)tiles_x, (unsigned)row_groups, (unsigned)(layers * images));
+    dim3 block(Cfg::THREADS);
+    hipLaunchKernelGGL(sconv_linear_multi_kernel<Cfg>, grid, block, 0, s, table, images);
     return hipGetLastError();
 }
 
@@ -530,6 +556,9 @@ static ConvVariant make_linear(const char* name) {
     }
     v.lds_bytes = Cfg::KS > 1 ? (size_t)Cfg::NW * Cfg::RPW * Cfg::P * 64 * 4 : 0;
     v.launch = &launch_linear<Cfg>;
+    // (plain instantiations only: a fused second input, pool or depthwise epilogue, or a
+    // de-interleaved tensor keeps a layer on a launch of its own)
+    if constexpr (!Cfg::S2D && !Cfg::DUAL && !Cfg::POOL && !Cfg::DW) v.launch_multi = &launch_linear_multi<Cfg>;
     return v;
 }
 

@@ -3,6 +3,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <array>
 #include <cstdarg>
 #include <cstdint>
@@ -172,6 +173,9 @@ struct ConvVariant {
     int nz_cap;           // FAM_STILE: most stream entries per (row group, chunk) the kernel buffers
     size_t lds_bytes;
     hipError_t (*launch)(const ConvLaunch&, hipStream_t);
+    // several layers at once from a device table of launch records (NULL: not offered);
+    // the grid is the largest tiles_x / row_groups among them
+    hipError_t (*launch_multi)(const ConvLaunch* table_dev, int layers, int tiles_x, int row_groups, int images, hipStream_t);
     int rows_per_block() const { return family == FAM_TILE || family == FAM_DENSE ? nw * rpw : (nw / ks) * rpw; }
 };
 
@@ -294,7 +298,8 @@ struct cadnn_weights {
     mutable bool dw_ready = false;
     // conv plans, built lazily
     mutable std::mutex mu;
-    mutable std::map<cadnn::PlanKey, std::unique_ptr<cadnn::ConvPlan>> plans;
+    // (shared: a co-launch table of the net runner holds the plans its records point into)
+    mutable std::map<cadnn::PlanKey, std::shared_ptr<cadnn::ConvPlan>> plans;
     // variant pinned for a geometry by tuning or by the caller
     mutable std::map<cadnn::GeomKey, const cadnn::ConvVariant*> chosen;
     // FAM_STILE variants whose per-(row group, chunk) stream was measured against the kernel's buffer
@@ -330,7 +335,8 @@ struct ConvExtra {
 // FAM_STILE variant (exact; cached on the handle).
 bool stile_streams_fit(const cadnn_weights* w, const ConvVariant* v);
 cadnn_status get_conv_plan(const cadnn_weights* w, const ConvVariant* v, const TensorDesc& xd, int stride,
-                           int pad, int wout, const ConvPlan** out, const ConvExtra* ex = nullptr);
+                           int pad, int wout, const ConvPlan** out, const ConvExtra* ex = nullptr,
+                           std::shared_ptr<ConvPlan>* keep = nullptr);
 void drop_unpinned_plans(const cadnn_weights* w);
 cadnn_status ensure_fc_device(const cadnn_weights* w);
 // A new handle whose rows are the rows of `parts` stacked in order (same cin, 1x1, same type):
@@ -364,6 +370,33 @@ cadnn_status conv2d_tune_impl(const cadnn_weights* w, const void* x, const Tenso
                               int stride, int pad, const void* bias, int relu, hipStream_t s, int reps,
                               float* best_us, const std::function<cadnn_status()>* before = nullptr,
                               const ConvExtra* ex = nullptr);
+// Independent layers launched as one kernel (the net runner's co-launch): one member.
+struct ConvMember {
+    const cadnn_weights* w;
+    const void* x;
+    TensorDesc xd;
+    void* y;
+    TensorDesc yd;
+    const void* residual;   // may be NULL
+    TensorDesc rd;
+    int stride, pad;
+    const void* bias;
+    int relu;
+};
+// Variants that can serve all members in one launch (none: they cannot share one) and the
+// untuned pick among them.
+cadnn_status conv2d_group_candidates(const std::vector<ConvMember>& members, int n,
+                                     std::vector<const ConvVariant*>* out, const ConvVariant** pick);
+// The members' launch records for variant v (plans are built on first use) and the grid
+// that covers the largest of them; `keep` receives the plans the records point into.
+cadnn_status conv2d_group_records(const std::vector<ConvMember>& members, int n, const ConvVariant* v,
+                                  std::vector<ConvLaunch>* records, int* tiles_x, int* row_groups,
+                                  std::vector<std::shared_ptr<ConvPlan>>* keep = nullptr);
+// Times every such variant on the members' own buffers; *best_v stays NULL if none serves them.
+cadnn_status conv2d_group_tune(const std::vector<ConvMember>& members, int n, hipStream_t s, int reps,
+                               const std::function<cadnn_status()>* before, const ConvVariant** best_v,
+                               float* best_us);
+const ConvVariant* conv2d_variant_by_name(const char* name);
 // Name of the variant that would serve the layer (NULL if none).
 // `out_s2d`: the layer's output or residual is in the de-interleaved layout.
 const char* conv2d_variant_name_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad,

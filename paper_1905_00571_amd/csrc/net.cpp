@@ -48,6 +48,22 @@ struct NetOp {
     // first) and its output is the channel slice [sib_ch, sib_ch + cout) of that region
     std::vector<int> siblings;
     int sibling_of = -1, sib_ch = 0, launch_c = 0;   // launch_c: channels the launch writes (own + siblings')
+    // Independent layers (different inputs, different weights) whose inputs are all ready when
+    // the first of them runs are launched with it as ONE kernel: the first carries the others
+    // as `comates`; a comate is skipped (fused_into = colaunch_of = the first).  Its tensors are
+    // its own, untouched by this.
+    std::vector<int> comates;
+    int colaunch_of = -1;
+};
+
+// The one kernel of a group of co-launched layers: the variant that serves them all, the
+// members' launch records in device memory (with the plans they point into) and the grid
+// that covers the largest member.
+struct CoLaunch {
+    const ConvVariant* v = nullptr;
+    DevBuf table;
+    std::vector<std::shared_ptr<ConvPlan>> plans;
+    int layers = 0, tiles_x = 0, row_groups = 0;
 };
 
 // Weights, bias and output layout an op is launched with: its own, or -- first op of a sibling
@@ -84,6 +100,7 @@ struct cadnn_net {
     char* ws = nullptr;
     std::map<int, std::unique_ptr<cadnn_weights>> merged_w;   // per first op of a sibling group
     std::map<int, std::unique_ptr<DevBuf>> merged_bias;
+    std::map<int, std::unique_ptr<CoLaunch>> colaunch;        // per first op of a group of co-launched layers
     hipGraphExec_t exec = nullptr;
     const void* cap_x = nullptr;
     void* cap_y = nullptr;
@@ -345,6 +362,49 @@ void layout(cadnn_net* net) {
             }
         }
     }
+    // Independent layers in one launch: sparse convolutions on plain tensors with nothing fused
+    // into them, none of them touching the caller's x or y, whose inputs are all produced
+    // before the first of them runs (the branches of an Inception module at the same depth).
+    // Launched apart each would leave most of the chip idle and pay a launch of its own;
+    // together they take about as long as the slowest.  A layer joins only while one kernel
+    // variant still serves the whole group.
+    for (NetOp& op : net->ops) { op.comates.clear(); op.colaunch_of = -1; }
+    if (net->allow_fusion) {
+        auto member_of = [&](const NetOp& o) {
+            // (pointers only have to be distinct and non-NULL here: nothing is launched)
+            ConvMember m{};
+            m.w = eff_w(net, o); m.x = (const void*)16; m.xd = o.xd; m.y = (void*)32; m.yd = launch_yd(o);
+            m.residual = o.res >= 0 ? (const void*)48 : nullptr; m.rd = o.rd;
+            m.stride = o.stride; m.pad = o.pad; m.bias = eff_bias(net, o); m.relu = o.relu;
+            return m;
+        };
+        auto solo = [&](int k) {
+            const NetOp& o = net->ops[k];
+            return o.kind == OP_CONV && o.fused_into < 0 && o.shortcut < 0 && o.pool_op < 0 && o.dw_op < 0 &&
+                   o.colaunch_of < 0 && o.comates.empty() && sparse_enough(o) && !o.yd.s2d && !o.xd.s2d &&
+                   !(o.res >= 0 && o.rd.s2d) && o.src_inst >= 0 && k != nops - 1 && (o.res < 0 || o.res_inst >= 0);
+        };
+        // the op at whose launch op k's output becomes available: k itself, or the op that
+        // computes it (a sibling's or comate's first layer, the layer a pool is fused into)
+        auto ready_at = [&](int k) { return net->ops[k].fused_into >= 0 ? net->ops[k].fused_into : k; };
+        for (int i = 0; i < nops; ++i) {
+            if (!solo(i)) continue;
+            std::vector<ConvMember> members{member_of(net->ops[i])};
+            std::vector<const ConvVariant*> common;
+            for (int j = i + 1; j < nops && members.size() < 8; ++j) {
+                const NetOp& b = net->ops[j];
+                if (!solo(j) || ready_at(b.src_inst) >= i || (b.res >= 0 && ready_at(b.res_inst) >= i)) continue;
+                members.push_back(member_of(b));
+                if (conv2d_group_candidates(members, b.in.n, &common, nullptr) != CADNN_OK || common.empty()) {
+                    members.pop_back();
+                    continue;
+                }
+                net->ops[i].comates.push_back(j);
+                net->ops[j].colaunch_of = i;
+                net->ops[j].fused_into = i;
+            }
+        }
+    }
     net->ws_bytes = off;
     net->laid_out = true;
 }
@@ -398,9 +458,67 @@ const ConvExtra* shortcut_geom(const cadnn_net* net, const NetOp& op, ConvExtra*
     return shortcut_of(net, op, (const void*)net, ex) ? ex : nullptr;
 }
 
+// The layers launched together with op i (itself first), on their own tensors: all of them
+// live in the workspace, none reads the caller's x or writes the caller's y.
+std::vector<ConvMember> colaunch_members(const cadnn_net* net, size_t i) {
+    std::vector<int> idx{(int)i};
+    idx.insert(idx.end(), net->ops[i].comates.begin(), net->ops[i].comates.end());
+    std::vector<ConvMember> members;
+    for (int k : idx) {
+        const NetOp& o = net->ops[k];
+        ConvMember m{};
+        m.w = eff_w(net, o);
+        m.x = net->ws + net->ops[o.src_inst].y_off; m.xd = o.xd;
+        m.y = net->ws + o.y_off; m.yd = launch_yd(o);
+        m.residual = o.res >= 0 ? net->ws + net->ops[o.res_inst].y_off : nullptr; m.rd = o.rd;
+        m.stride = o.stride; m.pad = o.pad; m.bias = eff_bias(net, o); m.relu = o.relu;
+        members.push_back(m);
+    }
+    return members;
+}
+
+// Builds the launch records of the group led by op i for variant v (NULL: the untuned pick)
+// and puts them on the device.
+cadnn_status set_colaunch_variant(cadnn_net* net, size_t i, const ConvVariant* v) {
+    const std::vector<ConvMember> members = colaunch_members(net, i);
+    const int n = net->ops[i].in.n;
+    if (!v) {
+        std::vector<const ConvVariant*> common;
+        cadnn_status st = conv2d_group_candidates(members, n, &common, &v);
+        if (st != CADNN_OK) return st;
+        if (!v) return fail(CADNN_EUNSUPPORTED, "cadnn_net: no kernel variant serves the layers launched with op %zu", i);
+    }
+    std::unique_ptr<CoLaunch> c(new CoLaunch());
+    std::vector<ConvLaunch> records;
+    cadnn_status st = conv2d_group_records(members, n, v, &records, &c->tiles_x, &c->row_groups, &c->plans);
+    if (st != CADNN_OK) return st;
+    if ((st = c->table.upload(records.data(), records.size() * sizeof(ConvLaunch))) != CADNN_OK) return st;
+    c->v = v;
+    c->layers = (int)records.size();
+    net->colaunch[(int)i] = std::move(c);
+    return CADNN_OK;
+}
+
+// Back to one launch per layer (tuning found the group slower than its members apart).
+void disband_colaunch(cadnn_net* net, size_t i) {
+    for (int j : net->ops[i].comates) {
+        net->ops[j].colaunch_of = -1;
+        net->ops[j].fused_into = -1;
+    }
+    net->ops[i].comates.clear();
+    net->colaunch.erase((int)i);
+}
+
 cadnn_status launch_one(cadnn_net* net, size_t i, const void* x, void* y, hipStream_t s) {
     const NetOp& op = net->ops[i];
-    if (op.fused_into >= 0) return CADNN_OK;     // computed inside the op that reads it
+    if (op.fused_into >= 0) return CADNN_OK;     // computed inside (or launched with) another op
+    if (!op.comates.empty()) {
+        auto it = net->colaunch.find((int)i);
+        if (it == net->colaunch.end()) return fail(CADNN_EINVAL, "cadnn_net: co-launch table of op %zu is missing", i);
+        const CoLaunch& c = *it->second;
+        CADNN_HIP(c.v->launch_multi((const ConvLaunch*)c.table.p, c.layers, c.tiles_x, c.row_groups, op.in.n, s));
+        return CADNN_OK;
+    }
     const void* src = in_ptr(net, op.src_inst, x);
     void* dst = out_ptr(net, i, y);
     ConvExtra ex;
@@ -662,6 +780,7 @@ extern "C" cadnn_status cadnn_net_op_info(cadnn_net* net, int op_index, int flag
     out->fused_into = op.fused_into;
     out->slice_of = op.slice_of;
     out->slice_channel = op.sibling_of >= 0 ? op.sib_ch : op.slice_ch;
+    out->launched_with = op.colaunch_of >= 0 ? 1 : 0;
     return CADNN_OK;
 }
 
@@ -705,6 +824,12 @@ extern "C" cadnn_status cadnn_net_finalize(cadnn_net* net, void* ws, size_t byte
         if (op.kind == OP_DEPTHWISE) st = ensure_dw_device(op.w);
         if (st != CADNN_OK) return st;
     }
+    net->colaunch.clear();
+    for (size_t i = 0; i < net->ops.size(); ++i) {
+        if (net->ops[i].comates.empty()) continue;
+        cadnn_status st = set_colaunch_variant(net, i, nullptr);
+        if (st != CADNN_OK) return st;
+    }
     net->use_graph = (flags & CADNN_NET_GRAPH) != 0;
     net->want_tune = (flags & CADNN_NET_TUNE) != 0;
     net->finalized = true;
@@ -718,9 +843,11 @@ extern "C" cadnn_status cadnn_run_net(cadnn_net* net, const void* x, void* y, vo
     if (net->want_tune) {
         // every layer is timed on the data an ordinary pass leaves in its input region
         cadnn_status st = launch_all(net, x, y, s);
+        std::vector<float> alone_us(net->ops.size(), 0.0f);
         for (size_t i = 0; i < net->ops.size() && st == CADNN_OK; ++i) {
             const NetOp& op = net->ops[i];
-            if (op.kind != OP_CONV || op.fused_into >= 0) continue;
+            // (co-launched layers are timed one by one too: the group must beat their sum)
+            if (op.kind != OP_CONV || (op.fused_into >= 0 && op.colaunch_of < 0)) continue;
             const std::function<cadnn_status()> producer = [&]() {
                 return op.src_inst >= 0 ? launch_one(net, (size_t)op.src_inst, x, y, s) : CADNN_OK;
             };
@@ -728,8 +855,23 @@ extern "C" cadnn_status cadnn_run_net(cadnn_net* net, const void* x, void* y, vo
             const bool fused = shortcut_of(net, op, x, &ex, y);
             st = conv2d_tune_impl(eff_w(net, op), in_ptr(net, op.src_inst, x), op.xd, out_ptr(net, i, y), launch_yd(op),
                                   (op.res >= 0 && op.shortcut < 0) ? in_ptr(net, op.res_inst, x) : nullptr, op.rd, op.in.n,
-                                  op.stride, op.pad, eff_bias(net, op), op.relu, s, 20, nullptr, &producer,
+                                  op.stride, op.pad, eff_bias(net, op), op.relu, s, 20, &alone_us[i], &producer,
                                   fused ? &ex : nullptr);
+        }
+        // then every group as a whole, over the variants that serve all its layers
+        for (size_t i = 0; i < net->ops.size() && st == CADNN_OK; ++i) {
+            if (net->ops[i].comates.empty()) continue;
+            float apart = alone_us[i];
+            for (int j : net->ops[i].comates) apart += alone_us[(size_t)j];
+            const std::function<cadnn_status()> producer = [&]() {
+                return launch_one(net, (size_t)net->ops[i].src_inst, x, y, s);
+            };
+            const ConvVariant* best = nullptr;
+            float together = 0.0f;
+            st = conv2d_group_tune(colaunch_members(net, i), net->ops[i].in.n, s, 20, &producer, &best, &together);
+            if (st != CADNN_OK) break;
+            if (best && together < apart) st = set_colaunch_variant(net, i, best);
+            else disband_colaunch(net, i);
         }
         if (st != CADNN_OK) return st;
         net->want_tune = false;
@@ -811,7 +953,9 @@ extern "C" cadnn_status cadnn_net_op_variant(const cadnn_net* net, int op_index,
     switch (op.kind) {
         case OP_CONV: {
             ConvExtra ex;
+            auto co = net->colaunch.find(op_index);
             name = op.fused_into >= 0 ? "fused"
+                   : (!op.comates.empty() && co != net->colaunch.end()) ? co->second->v->name
                                       : conv2d_variant_name_impl(eff_w(net, op), op.xd, op.in.n, op.stride, op.pad, out_s2d(op),
                                                                  shortcut_geom(net, op, &ex));
             break;
@@ -838,6 +982,20 @@ extern "C" cadnn_status cadnn_net_op_candidates(const cadnn_net* net, int op_ind
     const NetOp& op = net->ops[op_index];
     if (op.kind != OP_CONV) return fail(CADNN_EINVAL, "cadnn_net_op_candidates: op %d is not a convolution", op_index);
     if (op.fused_into >= 0) return fail(CADNN_EINVAL, "cadnn_net_op_candidates: op %d is computed inside op %d", op_index, op.fused_into);
+    if (!op.comates.empty()) {
+        // the variants that serve the whole group
+        std::vector<const ConvVariant*> common;
+        cadnn_status st = conv2d_group_candidates(colaunch_members(net, (size_t)op_index), op.in.n, &common, nullptr);
+        if (st != CADNN_OK) return st;
+        std::string all;
+        for (const ConvVariant* v : common) {
+            if (!all.empty()) all += "\n";
+            all += v->name;
+        }
+        if (all.size() + 1 > len) return fail(CADNN_EINVAL, "cadnn_net_op_candidates: buffer of %zu bytes, %zu needed", len, all.size() + 1);
+        std::memcpy(buf, all.c_str(), all.size() + 1);
+        return CADNN_OK;
+    }
     ConvExtra ex;
     return conv2d_list_variants_impl(eff_w(net, op), op.xd, op.in.n, op.stride, op.pad, buf, len, out_s2d(op), shortcut_geom(net, op, &ex));
 }
@@ -848,7 +1006,21 @@ extern "C" cadnn_status cadnn_net_set_op_variant(cadnn_net* net, int op_index, c
     if (op_index < 0 || op_index >= (int)net->ops.size()) return fail(CADNN_EINVAL, "cadnn_net_set_op_variant: no op %d", op_index);
     const NetOp& op = net->ops[op_index];
     if (op.kind != OP_CONV) return fail(CADNN_EINVAL, "cadnn_net_set_op_variant: op %d is not a convolution", op_index);
-    if (op.fused_into >= 0) return CADNN_OK;     // nothing to pin: computed inside another op
+    if (op.fused_into >= 0) return CADNN_OK;     // nothing to pin: computed inside, or launched with, another op
+    if (!op.comates.empty()) {
+        const ConvVariant* v = nullptr;
+        if (name && *name) {
+            std::vector<const ConvVariant*> common;
+            cadnn_status st = conv2d_group_candidates(colaunch_members(net, (size_t)op_index), op.in.n, &common, nullptr);
+            if (st != CADNN_OK) return st;
+            for (const ConvVariant* c : common) if (std::strcmp(c->name, name) == 0) v = c;
+            if (!v) return fail(CADNN_EINVAL, "cadnn_net_set_op_variant: '%s' does not serve every layer launched with op %d", name, op_index);
+        }
+        drop_graph(net);
+        // (the stream may still be running the old table's launches)
+        CADNN_HIP(hipDeviceSynchronize());
+        return set_colaunch_variant(net, (size_t)op_index, v);
+    }
     ConvExtra ex;
     cadnn_status st = conv2d_set_variant_impl(eff_w(net, op), op.xd, op.in.n, op.stride, op.pad, name, out_s2d(op), shortcut_geom(net, op, &ex));
     if (st != CADNN_OK) return st;
@@ -865,7 +1037,7 @@ extern "C" cadnn_status cadnn_net_read_buffer(cadnn_net* net, int buf, void* hos
         return fail(CADNN_EINVAL, "cadnn_net_read_buffer: buffer %d is not in the workspace", buf);
     const NetOp& op = net->ops[it->second];
     // (a fused pool's vector is written, by the convolution; a fused projection's map is not)
-    if (op.fused_into >= 0 && op.kind == OP_CONV && op.sibling_of < 0)
+    if (op.fused_into >= 0 && op.kind == OP_CONV && op.sibling_of < 0 && op.colaunch_of < 0)
         return fail(CADNN_EINVAL, "cadnn_net_read_buffer: buffer %d is never materialised (its op is computed inside op %d)", buf, op.fused_into);
     if (op.pool_op >= 0)
         return fail(CADNN_EINVAL, "cadnn_net_read_buffer: buffer %d is never materialised (op %d pools it on the fly)", buf, it->second);

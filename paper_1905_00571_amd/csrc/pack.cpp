@@ -580,12 +580,13 @@ void drop_unpinned_plans(const cadnn_weights* w) {
 }
 
 cadnn_status get_conv_plan(const cadnn_weights* w, const ConvVariant* v, const TensorDesc& xd, int stride,
-                           int pad, int wout, const ConvPlan** out, const ConvExtra* ex) {
+                           int pad, int wout, const ConvPlan** out, const ConvExtra* ex,
+                           std::shared_ptr<ConvPlan>* keep) {
     std::lock_guard<std::mutex> lock(w->mu);
     const PlanKey key = plan_key(w, v, xd, stride, pad, wout, ex);
     auto it = w->plans.find(key);
     if (it == w->plans.end()) {
-        std::unique_ptr<ConvPlan> plan(new (std::nothrow) ConvPlan());
+        std::shared_ptr<ConvPlan> plan(new (std::nothrow) ConvPlan());
         if (!plan) return fail(CADNN_ENOMEM, "out of host memory");
         cadnn_status st;
         try {
@@ -597,6 +598,7 @@ cadnn_status get_conv_plan(const cadnn_weights* w, const ConvVariant* v, const T
         it = w->plans.emplace(key, std::move(plan)).first;
     }
     *out = it->second.get();
+    if (keep) *keep = it->second;
     return CADNN_OK;
 }
 

@@ -661,7 +661,10 @@ def test_sibling_layers_in_one_launch(cad, dtype_name):
     xs = x.astype(npdt)
     ref, ins, outs = oracle.run_net(ops, xs, ws, bs, dtype=npdt)
     infos, _ = cad.plan_net(ops, ws, shape, dtype)
-    assert [i["fused_into"] for i in infos[:6]] == [-1, -1, 1, -1, 1, -1]
+    # s2 and s3 are rows of s1's launch; lin and slice, which could not be, are independent layers
+    # that share its kernel launch all the same (with r3 / r5 / r1 / rl one level down)
+    assert [(i["fused_into"], i["launched_with"]) for i in infos[:6]] == [(-1, 0), (-1, 0), (1, 0), (1, 1), (1, 0), (1, 1)]
+    assert [(i["fused_into"], i["launched_with"]) for i in infos[6:10]] == [(-1, 0), (6, 1), (6, 1), (6, 1)]
     assert infos[1]["halo_h"] == infos[2]["halo_h"] == infos[4]["halo_h"] == 2 and infos[5]["slice_of"] == 10
     for kw in ({}, {"tune": True}, {"fuse": False}):
         net = cad.build_net(ops, ws, bs, shape, dtype, use_graph=True, **kw)
@@ -679,4 +682,20 @@ def test_sibling_layers_in_one_launch(cad, dtype_name):
                 got = net.read_buffer(ops[i].dst, outs[i].shape)
                 assert_layer_close(got, outs[i], cond + (2.0 ** -10 / 1e-4 * np.abs(outs[i]) if f16 else 0), tol,
                                    f"{ops[i].name} {kw} {name}", f16=f16)
+        if not kw:
+            # the second level: a 3x3, a 5x5 and two 1x1 layers on four different tensors share
+            # every launch; each variant that serves all four must leave the concatenation right
+            assert [net.op_variant(i) for i in (7, 8, 9)] == ["fused"] * 3
+            names = net.op_candidates(6)
+            assert len(names) > 4 and net.op_variant(6) in names
+            cat = np.concatenate([outs[i] for i in (6, 7, 8, 9, 5)], axis=1)
+            for name in names:
+                net.set_op_variant(6, name)
+                assert net.op_variant(6) == name
+                y = net.run(dev(xs))
+                torch.cuda.synchronize()
+                assert_close(net.read_buffer(11, cat.shape), cat, tol * (3 if f16 else 1), f"co-launched {name}")
+                assert_close(y.cpu().numpy(), ref, tol * (3 if f16 else 1), f"co-launched net {name}")
+            with pytest.raises(cad.CadnnError):
+                net.set_op_variant(6, "slinear_float_d1_r1k1w4u4")        # not a variant for several layers
         net.free()

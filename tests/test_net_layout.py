@@ -105,7 +105,7 @@ def test_inception_concatenations_are_written_in_place():
     # the workspace holds every region that is not a slice of another (a concatenation's, or
     # the region of the first layer of a sibling group)
     off = sum(region_bytes(i, 1) for o, i in zip(ops[:-1], infos[:-1])
-              if i["slice_of"] < 0 and not (o.kind == "conv" and i["fused_into"] >= 0))
+              if i["slice_of"] < 0 and not (o.kind == "conv" and i["fused_into"] >= 0 and not i["launched_with"]))
     assert nbytes == off
 
 
@@ -146,7 +146,7 @@ def test_inception_sibling_layers_share_a_launch():
     infos, _ = plan(ops, (1, 3, 299, 299), "iv3")
     name_of = [o.name for o in ops]
     merged = {o.name: name_of[i["fused_into"]] for o, i in zip(ops, infos)
-              if o.kind == "conv" and i["fused_into"] >= 0}
+              if o.kind == "conv" and i["fused_into"] >= 0 and not i["launched_with"]}
     want = {}
     for m in ("a1", "a2", "a3"):
         want[m + "_3x3a"] = m + "_5x5a"
@@ -172,3 +172,35 @@ def test_inception_sibling_layers_share_a_launch():
     assert all(i["fused_into"] == -1 for i in plain)
     # ... and every layer has a region of its own again: the workspace size follows the flags
     assert nplain == sum(region_bytes(i, 1) for i in plain[:-1] if i["slice_of"] < 0)
+
+
+def test_inception_independent_layers_share_a_launch():
+    """Layers of different branches whose inputs are ready at the same point are launched as one
+    kernel (up to eight, while one variant serves them all): they keep their own regions, and
+    a layer joins the launch of an EARLIER op only -- never one that produces its input."""
+    ops = wl.inception_v3_ops()
+    infos, _ = plan(ops, (1, 3, 299, 299), "iv3")
+    idx = {o.name: k for k, o in enumerate(ops)}
+    groups = {}
+    for o, i in zip(ops, infos):
+        if i["launched_with"]:
+            groups.setdefault(ops[i["fused_into"]].name, []).append(o.name)
+    assert groups["c1_7b"] == ["c1_dbl_b"] and groups["c1_7c"] == ["c1_dbl_c"] and groups["c1_1x1"] == ["c1_7a"]
+    assert groups["e1_3b"] == ["e1_3c", "e1_dbl_b"] and groups["e2_dbl_c"] == ["e2_dbl_d"]
+    assert groups["a1_5x5b"] == ["a1_3x3b"] and groups["d_3x3b"] == ["d_7b"]
+    assert sum(len(m) for m in groups.values()) == 28
+    ready = lambda k: infos[k]["fused_into"] if infos[k]["fused_into"] >= 0 else k
+    producer = {}
+    for k, o in enumerate(ops):
+        if o.kind == "conv" and infos[k]["launched_with"]:
+            lead = infos[k]["fused_into"]
+            assert lead < k and ops[lead].kind == "conv" and infos[lead]["fused_into"] < 0
+            assert ready(producer[o.src]) < lead, o.name           # its input is complete before the shared launch
+            assert infos[k]["slice_of"] >= 0 or infos[k]["offset"] != infos[lead]["offset"]   # a region of its own
+        producer[o.dst] = k
+    # chains have nothing to launch together; without fusion nothing is
+    for other in (wl.resnet50_ops(), wl.mobilenet_v1_ops()):
+        inf, _ = plan(other, (1, 3, 224, 224), "chain")
+        assert not any(i["launched_with"] for i in inf)
+    plain, _ = plan(ops, (1, 3, 299, 299), "iv3", fuse=False)
+    assert not any(i["launched_with"] for i in plain)
