@@ -254,7 +254,8 @@ cadnn_status cadnn_net_workspace_bytes(const cadnn_net* net, size_t* bytes);
  * kernel over a table of launch records, while one variant serves them all: they report
  * fused_into = that op and launched_with = 1, the op's variant name is the group's, and
  * cadnn_net_op_candidates / cadnn_net_set_op_variant on it list / pin variants for the whole
- * group.  Tuning (CADNN_NET_TUNE) keeps a group only if it beats its layers launched apart. */
+ * group.  Tuning (CADNN_NET_TUNE) keeps a group only if it beats its layers launched apart.
+ * Window pools move up in the launch order to where their input completes (launched_after). */
 #define CADNN_NET_GRAPH 1
 #define CADNN_NET_TUNE 2
 #define CADNN_NET_PLAIN_LAYOUT 4
@@ -280,6 +281,9 @@ typedef struct {
                                 the region of the op named by fused_into) */
     int launched_with;       /* 1: an independent layer that shares the kernel launch of op
                                 fused_into; its tensors and its region are its own */
+    int launched_after;      /* >= 0: a window pool that is launched right behind that op (the
+                                one that completes its input) instead of at its place in the
+                                op list, so that its reader can share an earlier launch */
 } cadnn_op_info;
 cadnn_status cadnn_net_op_info(cadnn_net* net, int op_index, int flags, cadnn_op_info* out);
 cadnn_status cadnn_run_net(cadnn_net* net, const void* x, void* y, void* stream);

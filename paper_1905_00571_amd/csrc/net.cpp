@@ -54,6 +54,11 @@ struct NetOp {
     // its own, untouched by this.
     std::vector<int> comates;
     int colaunch_of = -1;
+    // A window pool is launched right after the op that completes its input (hoisted_to; that op
+    // lists it in `hoisted`) instead of at its place in the op list, so that the layer reading
+    // it can join the launch of layers that come before the pool in the list.
+    int hoisted_to = -1;
+    std::vector<int> hoisted;
 };
 
 // The one kernel of a group of co-launched layers: the variant that serves them all, the
@@ -368,8 +373,21 @@ void layout(cadnn_net* net) {
     // Launched apart each would leave most of the chip idle and pay a launch of its own;
     // together they take about as long as the slowest.  A layer joins only while one kernel
     // variant still serves the whole group.
-    for (NetOp& op : net->ops) { op.comates.clear(); op.colaunch_of = -1; }
+    for (NetOp& op : net->ops) { op.comates.clear(); op.colaunch_of = -1; op.hoisted_to = -1; op.hoisted.clear(); }
+    // the op at whose launch op k's output becomes available: k itself, the op that computes
+    // it (a sibling's or comate's first layer, the layer a pool is fused into), or the op a
+    // hoisted pool is launched behind
+    std::function<int(int)> ready_at = [&](int k) {
+        const NetOp& o = net->ops[k];
+        return o.hoisted_to >= 0 ? ready_at(o.hoisted_to) : o.fused_into >= 0 ? ready_at(o.fused_into) : k;
+    };
     if (net->allow_fusion) {
+        for (int p = 0; p + 1 < nops; ++p) {
+            NetOp& o = net->ops[p];
+            if ((o.kind == OP_MAXPOOL || o.kind == OP_AVGPOOL2D) && o.fused_into < 0 && o.src_inst >= 0 &&
+                ready_at(o.src_inst) < p - 1)
+                o.hoisted_to = o.src_inst;
+        }
         auto member_of = [&](const NetOp& o) {
             // (pointers only have to be distinct and non-NULL here: nothing is launched)
             ConvMember m{};
@@ -384,9 +402,6 @@ void layout(cadnn_net* net) {
                    o.colaunch_of < 0 && o.comates.empty() && sparse_enough(o) && !o.yd.s2d && !o.xd.s2d &&
                    !(o.res >= 0 && o.rd.s2d) && o.src_inst >= 0 && k != nops - 1 && (o.res < 0 || o.res_inst >= 0);
         };
-        // the op at whose launch op k's output becomes available: k itself, or the op that
-        // computes it (a sibling's or comate's first layer, the layer a pool is fused into)
-        auto ready_at = [&](int k) { return net->ops[k].fused_into >= 0 ? net->ops[k].fused_into : k; };
         for (int i = 0; i < nops; ++i) {
             if (!solo(i)) continue;
             std::vector<ConvMember> members{member_of(net->ops[i])};
@@ -404,6 +419,12 @@ void layout(cadnn_net* net) {
                 net->ops[j].fused_into = i;
             }
         }
+        // every hoisted pool goes behind the op that really launches when its input completes
+        for (int p = 0; p < nops; ++p)
+            if (net->ops[p].hoisted_to >= 0) {
+                net->ops[p].hoisted_to = ready_at(p);
+                net->ops[net->ops[p].hoisted_to].hoisted.push_back(p);
+            }
     }
     net->ws_bytes = off;
     net->laid_out = true;
@@ -557,9 +578,13 @@ cadnn_status launch_one(cadnn_net* net, size_t i, const void* x, void* y, hipStr
     return fail(CADNN_EINVAL, "cadnn_net: unknown op kind");
 }
 
+// The ops in launch order: the op list's, but for the hoisted pools.
 cadnn_status launch_all(cadnn_net* net, const void* x, void* y, hipStream_t s) {
     for (size_t i = 0; i < net->ops.size(); ++i) {
+        if (net->ops[i].hoisted_to >= 0) continue;
         cadnn_status st = launch_one(net, i, x, y, s);
+        for (size_t k = 0; k < net->ops[i].hoisted.size() && st == CADNN_OK; ++k)
+            st = launch_one(net, (size_t)net->ops[i].hoisted[k], x, y, s);
         if (st != CADNN_OK) return st;
     }
     return CADNN_OK;
@@ -781,6 +806,7 @@ extern "C" cadnn_status cadnn_net_op_info(cadnn_net* net, int op_index, int flag
     out->slice_of = op.slice_of;
     out->slice_channel = op.sibling_of >= 0 ? op.sib_ch : op.slice_ch;
     out->launched_with = op.colaunch_of >= 0 ? 1 : 0;
+    out->launched_after = op.hoisted_to;
     return CADNN_OK;
 }
 

@@ -185,11 +185,15 @@ def test_inception_independent_layers_share_a_launch():
     for o, i in zip(ops, infos):
         if i["launched_with"]:
             groups.setdefault(ops[i["fused_into"]].name, []).append(o.name)
-    assert groups["c1_7b"] == ["c1_dbl_b"] and groups["c1_7c"] == ["c1_dbl_c"] and groups["c1_1x1"] == ["c1_7a"]
+    # (the pooled branch's 1x1 layer rides along because its pool moved up to the module's input)
+    assert groups["c1_7b"] == ["c1_dbl_b"] and groups["c1_7c"] == ["c1_dbl_c"] and groups["c1_1x1"] == ["c1_7a", "c1_pool1x1"]
+    assert infos[idx["c1_pool"]]["launched_after"] == idx["c1_1x1"] - 1 and ops[idx["c1_1x1"] - 1].kind == "concat"
     assert groups["e1_3b"] == ["e1_3c", "e1_dbl_b"] and groups["e2_dbl_c"] == ["e2_dbl_d"]
     assert groups["a1_5x5b"] == ["a1_3x3b"] and groups["d_3x3b"] == ["d_7b"]
-    assert sum(len(m) for m in groups.values()) == 28
-    ready = lambda k: infos[k]["fused_into"] if infos[k]["fused_into"] >= 0 else k
+    assert sum(len(m) for m in groups.values()) == 37
+    def ready(k):
+        nxt = infos[k]["launched_after"] if infos[k]["launched_after"] >= 0 else infos[k]["fused_into"]
+        return ready(nxt) if nxt >= 0 else k
     producer = {}
     for k, o in enumerate(ops):
         if o.kind == "conv" and infos[k]["launched_with"]:
@@ -203,4 +207,4 @@ def test_inception_independent_layers_share_a_launch():
         inf, _ = plan(other, (1, 3, 224, 224), "chain")
         assert not any(i["launched_with"] for i in inf)
     plain, _ = plan(ops, (1, 3, 299, 299), "iv3", fuse=False)
-    assert not any(i["launched_with"] for i in plain)
+    assert not any(i["launched_with"] or i["launched_after"] >= 0 for i in plain)
