@@ -327,11 +327,11 @@ cadnn_status conv2d_group_candidates(const std::vector<ConvMember>& members, int
         if (st != CADNN_OK) return st;
     }
     if (members.empty()) return CADNN_OK;
-    for (const ConvVariant* v : candidates(members[0].w, geoms[0])) {
-        if (!v->launch_multi) continue;
+    for (const ConvVariant& v : all_linear_variants()) {   // (the only family that offers it)
+        if (!v.launch_multi) continue;
         bool all = true;
-        for (size_t k = 1; k < members.size() && all; ++k) all = variant_fits(*v, members[k].w, geoms[k]);
-        if (all) out->push_back(v);
+        for (size_t k = 0; k < members.size() && all; ++k) all = variant_fits(v, members[k].w, geoms[k]);
+        if (all) out->push_back(&v);
     }
     // untuned pick: the layers run side by side, so the slowest of them decides
     double best = 0.0;

@@ -5,6 +5,8 @@
 #include <cstdlib>
 #include <cstring>
 
+#include <iterator>
+
 #include "internal.h"
 
 using namespace cadnn;
@@ -402,18 +404,30 @@ void layout(cadnn_net* net) {
                    o.colaunch_of < 0 && o.comates.empty() && sparse_enough(o) && !o.yd.s2d && !o.xd.s2d &&
                    !(o.res >= 0 && o.rd.s2d) && o.src_inst >= 0 && k != nops - 1 && (o.res < 0 || o.res_inst >= 0);
         };
+        // the variants that can launch op k among several layers (sorted; listed once per op)
+        std::vector<std::vector<const ConvVariant*>> multi(nops);
+        std::vector<char> listed(nops, 0);
+        auto multi_of = [&](int k) -> const std::vector<const ConvVariant*>& {
+            if (!listed[k]) {
+                listed[k] = 1;
+                if (conv2d_group_candidates({member_of(net->ops[k])}, net->ops[k].in.n, &multi[k], nullptr) != CADNN_OK)
+                    multi[k].clear();
+                std::sort(multi[k].begin(), multi[k].end());
+            }
+            return multi[k];
+        };
         for (int i = 0; i < nops; ++i) {
             if (!solo(i)) continue;
-            std::vector<ConvMember> members{member_of(net->ops[i])};
-            std::vector<const ConvVariant*> common;
-            for (int j = i + 1; j < nops && members.size() < 8; ++j) {
+            std::vector<const ConvVariant*> common = multi_of(i), narrowed;
+            // (partners are looked for among the next 64 ops: a module's branches lie close together)
+            for (int j = i + 1; j < std::min(nops, i + 65) && net->ops[i].comates.size() < 7 && !common.empty(); ++j) {
                 const NetOp& b = net->ops[j];
                 if (!solo(j) || ready_at(b.src_inst) >= i || (b.res >= 0 && ready_at(b.res_inst) >= i)) continue;
-                members.push_back(member_of(b));
-                if (conv2d_group_candidates(members, b.in.n, &common, nullptr) != CADNN_OK || common.empty()) {
-                    members.pop_back();
-                    continue;
-                }
+                const std::vector<const ConvVariant*>& theirs = multi_of(j);
+                narrowed.clear();
+                std::set_intersection(common.begin(), common.end(), theirs.begin(), theirs.end(), std::back_inserter(narrowed));
+                if (narrowed.empty()) continue;
+                common.swap(narrowed);
                 net->ops[i].comates.push_back(j);
                 net->ops[j].colaunch_of = i;
                 net->ops[j].fused_into = i;
