@@ -257,6 +257,15 @@ def main() -> int:
     for i, op in enumerate(ops):
         if names[i] != "fused":
             continue
+        info = net.op_info(i)
+        if info["launched_with"]:
+            # an independent layer (or a pool riding along) in another op's kernel launch: nothing
+            # is saved but the launch; its work is accounted where it runs
+            j = info["fused_into"]
+            for key in ("flops", "bytes", "nnz"):
+                costs[j][key] = costs[j].get(key, 0) + costs[i].get(key, 0)
+            costs[i]["flops"] = costs[i]["bytes"] = 0.0
+            continue
         if op.kind in ("avgpool", "dwconv"):
             # pooled (or depthwise-filtered) in the epilogue of the convolution that feeds it: that
             # layer's feature map is neither written nor read back; only the fused op's output is
@@ -266,13 +275,11 @@ def main() -> int:
             costs[j]["bytes"] += costs[i]["bytes"] - 2.0 * map_bytes
             costs[i]["flops"] = costs[i]["bytes"] = 0.0
             continue
-        info = net.op_info(i)
         j = info["fused_into"]
         if j < i:
-            # launched by an earlier layer's kernel: as rows of a 1x1 layer on the same input
-            # (the shared input is read once), or as an independent layer in the same launch
-            # (nothing saved but the launch); its work moves there
-            shared_in = 0.0 if info["launched_with"] else float(np.prod(costs[i]["in"])) * elem
+            # rows of an earlier 1x1 layer's launch on the same input, which is read once; its
+            # work moves there
+            shared_in = float(np.prod(costs[i]["in"])) * elem
             while names[j] == "fused":       # (the first layer of a sibling group may itself ride on another launch)
                 j = net.op_info(j)["fused_into"]
             costs[j]["flops"] += costs[i]["flops"]

@@ -281,9 +281,10 @@ typedef struct {
                                 the region of the op named by fused_into) */
     int launched_with;       /* 1: an independent layer that shares the kernel launch of op
                                 fused_into; its tensors and its region are its own */
-    int launched_after;      /* >= 0: a window pool that is launched right behind that op (the
-                                one that completes its input) instead of at its place in the
-                                op list, so that its reader can share an earlier launch */
+    int launched_after;      /* >= 0: the op is launched right behind that op instead of at its
+                                place in the op list: a window pool moved up to where its
+                                input completes (so that its reader can share an earlier
+                                launch), or a member of a group that tuning took apart */
 } cadnn_op_info;
 cadnn_status cadnn_net_op_info(cadnn_net* net, int op_index, int flags, cadnn_op_info* out);
 cadnn_status cadnn_run_net(cadnn_net* net, const void* x, void* y, void* stream);
@@ -302,7 +303,9 @@ cadnn_status cadnn_net_op_variant(const cadnn_net* net, int op_index, char* buf,
 cadnn_status cadnn_net_op_candidates(const cadnn_net* net, int op_index, char* buf, size_t len);
 /* Pins the kernel variant of convolution op `op_index` by name (as reported by
  * cadnn_net_op_variant after tuning), e.g. to replay a saved tuning result.  NULL or ""
- * returns the op to the built-in heuristic.  The net must be finalized. */
+ * returns the op to the built-in heuristic.  The net must be finalized.  On the first op of
+ * a group of layers that share a launch the name pins the group's variant; "apart" there
+ * takes the group apart for good: its layers are launched one by one, right behind that op. */
 cadnn_status cadnn_net_set_op_variant(cadnn_net* net, int op_index, const char* name);
 /* Copies the current contents of activation buffer `buf` (as left by the last
  * run) to a HOST array of `bytes` bytes; synchronises `stream`. */

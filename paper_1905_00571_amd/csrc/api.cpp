@@ -311,6 +311,15 @@ static cadnn_status launch_variant(const cadnn_weights* w, const ConvVariant* v,
 static cadnn_status check_io(const char* who, const cadnn_weights* w, const ConvGeom& g, const void* x,
                              void* y, const TensorDesc& yd, const void* residual, const TensorDesc& rd);
 static cadnn_status member_geom(const ConvMember& m, int n, ConvGeom* g) {
+    if (m.pool_kind != 0) {
+        // a window pool: only its tensors are checked, it constrains no variant
+        if (!m.x || !m.y || m.x == m.y || m.pool_k <= 0 || m.stride <= 0 || m.pad < 0 || m.xd.s2d || m.yd.s2d ||
+            m.yd.c != m.xd.c || m.yd.h != conv_out(m.xd.h, m.pool_k, m.stride, m.pad) ||
+            m.yd.w != conv_out(m.xd.w, m.pool_k, m.stride, m.pad) || m.yd.h <= 0 || m.yd.w <= 0 || n <= 0)
+            return fail(CADNN_EINVAL, "cadnn_net (co-launched layers): bad pool member");
+        *g = ConvGeom{};
+        return CADNN_OK;
+    }
     cadnn_status st = check_conv("cadnn_net (co-launched layers)", m.w, m.xd, n, m.stride, m.pad, g,
                                  m.yd.s2d || (m.residual && m.rd.s2d), nullptr);
     if (st != CADNN_OK) return st;
@@ -329,15 +338,20 @@ cadnn_status conv2d_group_candidates(const std::vector<ConvMember>& members, int
     if (members.empty()) return CADNN_OK;
     for (const ConvVariant& v : all_linear_variants()) {   // (the only family that offers it)
         if (!v.launch_multi) continue;
-        bool all = true;
-        for (size_t k = 0; k < members.size() && all; ++k) all = variant_fits(v, members[k].w, geoms[k]);
-        if (all) out->push_back(&v);
+        bool all = true, any = false;
+        for (size_t k = 0; k < members.size() && all; ++k) {
+            if (members[k].pool_kind != 0) continue;
+            any = true;
+            all = variant_fits(v, members[k].w, geoms[k]);
+        }
+        if (all && any) out->push_back(&v);
     }
     // untuned pick: the layers run side by side, so the slowest of them decides
     double best = 0.0;
     for (const ConvVariant* v : *out) {
         double worst = 0.0;
-        for (size_t k = 0; k < members.size(); ++k) worst = std::max(worst, variant_cost(members[k].w, geoms[k], v));
+        for (size_t k = 0; k < members.size(); ++k)
+            if (members[k].pool_kind == 0) worst = std::max(worst, variant_cost(members[k].w, geoms[k], v));
         if (pick && (!*pick || worst < best)) { *pick = v; best = worst; }
     }
     return CADNN_OK;
@@ -356,6 +370,22 @@ cadnn_status conv2d_group_records(const std::vector<ConvMember>& members, int n,
         ConvGeom g;
         cadnn_status st = member_geom(m, n, &g);
         if (st != CADNN_OK) return st;
+        if (m.pool_kind != 0) {
+            ConvLaunch a{};
+            a.x = m.x; a.y = m.y; a.xd = m.xd; a.yd = m.yd; a.n = n; a.stride = m.stride; a.pad = m.pad;
+            a.op_type = m.pool_kind; a.pool_k = m.pool_k;
+            // one thread per output element of an image, the workgroups spread over a (<= 8) x rows grid
+            const int64_t threads = (int64_t)v->nw * 64;
+            const int64_t blocks = ((int64_t)m.yd.c * m.yd.h * m.yd.w + threads - 1) / threads;
+            a.tiles_x = (int)std::min<int64_t>(blocks, 8);
+            a.tiles_y = 1;
+            if ((blocks + a.tiles_x - 1) / a.tiles_x > 65535) return fail(CADNN_EUNSUPPORTED, "cadnn_net: pool too large to ride along");
+            a.row_groups = (int)((blocks + a.tiles_x - 1) / a.tiles_x);
+            (*records)[k] = a;
+            *tiles_x = std::max(*tiles_x, a.tiles_x);
+            *row_groups = std::max(*row_groups, a.row_groups);
+            continue;
+        }
         if (!variant_fits(*v, m.w, g)) return fail(CADNN_EINVAL, "cadnn_net: '%s' does not serve every co-launched layer", v->name);
         if ((st = make_launch(m.w, v, g, m.x, m.y, m.yd, m.residual, m.rd, m.bias, m.relu, &(*records)[k],
                               keep ? &(*keep)[k] : nullptr)) != CADNN_OK) return st;
@@ -419,7 +449,7 @@ cadnn_status conv2d_group_tune(const std::vector<ConvMember>& members, int n, hi
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
     if (st != CADNN_OK) return st;
-    for (const ConvMember& m : members) drop_unpinned_plans(m.w);
+    for (const ConvMember& m : members) if (m.w) drop_unpinned_plans(m.w);
     if (best_us) *best_us = best_ms * 1e3f / reps;
     return CADNN_OK;
 }

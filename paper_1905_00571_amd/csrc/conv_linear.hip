@@ -516,7 +516,16 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_linear_multi_kernel(const 
     const int layer = (int)blockIdx.z / images;
     const ConvLaunch a = table[layer];
     if ((int)blockIdx.x >= a.tiles_x || (int)blockIdx.y >= a.row_groups) return;
-    sconv_linear_block<Cfg>(a, (int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z - layer * images);
+    const int n = (int)blockIdx.z - layer * images;
+    if (a.op_type != 0) {
+        // a window pool riding along (a module's pooled branch): one output element per thread
+        using T = typename Cfg::T;
+        const size_t r = ((size_t)blockIdx.y * a.tiles_x + blockIdx.x) * Cfg::THREADS + threadIdx.x;
+        if (r < (size_t)a.yd.c * a.yd.h * a.yd.w)
+            windowpool_element<T>((const T*)a.x, (T*)a.y, a.xd, a.yd, n, r, a.pool_k, a.stride, a.pad, a.op_type == 2);
+        return;
+    }
+    sconv_linear_block<Cfg>(a, (int)blockIdx.x, (int)blockIdx.y, n);
 }
 
 template <class Cfg>

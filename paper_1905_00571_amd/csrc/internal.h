@@ -115,6 +115,34 @@ inline TensorDesc make_desc_s2d(int c, int h, int w, int ph, int pw) {
     return d;
 }
 
+// One output element of a k x k window pool (maximum, or the mean over the in-image part of
+// the window): flat index r = (c * yd.h + oh) * yd.w + ow inside image `img`.
+template <typename T>
+__device__ __forceinline__ void windowpool_element(const T* __restrict__ x, T* __restrict__ y, const TensorDesc& xd,
+                                                   const TensorDesc& yd, int img, size_t r, int k, int stride, int pad,
+                                                   bool mean) {
+    const int ow = (int)(r % yd.w);
+    const int oh = (int)((r / yd.w) % yd.h);
+    const int c = (int)(r / ((size_t)yd.w * yd.h));
+    const T* xp = x + (size_t)img * xd.image + (size_t)c * xd.plane + xd.origin;
+    int seen = 0;
+    float m = 0.0f;
+    for (int a = 0; a < k; ++a) {
+        const int ih = oh * stride + a - pad;
+        if (ih < 0 || ih >= xd.h) continue;
+        for (int q = 0; q < k; ++q) {
+            const int iw = ow * stride + q - pad;
+            if (iw < 0 || iw >= xd.w) continue;
+            const float v = (float)xp[(size_t)ih * xd.pitch + iw];
+            if (mean) m += v;
+            else if (!seen || v > m) m = v;
+            ++seen;
+        }
+    }
+    if (mean && seen) m /= (float)seen;
+    y[(size_t)img * yd.image + (size_t)c * yd.plane + yd.origin + (size_t)oh * yd.pitch + ow] = (T)m;
+}
+
 // ---- convolution kernel variants ------------------------------------------------
 // A variant is one instantiation of a sparse convolution kernel.  Its compile-time
 // geometry decides how a canonical column index k = (ci*KH + r)*KW + c is laid out in the
@@ -216,6 +244,11 @@ struct ConvLaunch {
     uint32_t pt_lds_bytes;
     int pt_nbuf;
     uint32_t image_bytes;     // xd.image * sizeof(element)
+    // launches of several layers (launch_multi) may carry window pools among them: 0 = a
+    // convolution, 1 = a k x k maximum pool, 2 = a k x k mean pool (x, y, xd, yd, stride, pad
+    // as for a layer; one thread per output element, workgroup by * tiles_x + bx takes the
+    // next blockDim.x elements of image n)
+    int op_type, pool_k;
 };
 
 struct ConvPlan {
@@ -382,6 +415,7 @@ struct ConvMember {
     int stride, pad;
     const void* bias;
     int relu;
+    int pool_kind, pool_k;  // pool_kind 1 / 2: not a layer but a maximum / mean window pool (w = NULL) riding along
 };
 // Variants that can serve all members in one launch (none: they cannot share one) and the
 // untuned pick among them.

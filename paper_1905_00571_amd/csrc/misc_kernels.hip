@@ -235,27 +235,7 @@ __global__ __launch_bounds__(256) void windowpool_kernel(const T* __restrict__ x
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= per_image * n) return;
     const int img = (int)(i / per_image);
-    const size_t r = i - (size_t)img * per_image;
-    const int ow = (int)(r % yd.w);
-    const int oh = (int)((r / yd.w) % yd.h);
-    const int c = (int)(r / ((size_t)yd.w * yd.h));
-    const T* xp = x + (size_t)img * xd.image + (size_t)c * xd.plane + xd.origin;
-    int seen = 0;
-    float m = 0.0f;
-    for (int a = 0; a < k; ++a) {
-        const int ih = oh * stride + a - pad;
-        if (ih < 0 || ih >= xd.h) continue;
-        for (int q = 0; q < k; ++q) {
-            const int iw = ow * stride + q - pad;
-            if (iw < 0 || iw >= xd.w) continue;
-            const float v = (float)xp[(size_t)ih * xd.pitch + iw];
-            if (AVG) m += v;
-            else if (!seen || v > m) m = v;
-            ++seen;
-        }
-    }
-    if (AVG && seen) m /= (float)seen;
-    y[(size_t)img * yd.image + (size_t)c * yd.plane + yd.origin + (size_t)oh * yd.pitch + ow] = (T)m;
+    windowpool_element<T>(x, y, xd, yd, img, i - (size_t)img * per_image, k, stride, pad, AVG);
 }
 
 // One wave per (n, c) plane; lanes stride over the plane, shuffle reduction at the end.

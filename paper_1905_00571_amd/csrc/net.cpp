@@ -58,7 +58,8 @@ struct NetOp {
     int colaunch_of = -1;
     // A window pool is launched right after the op that completes its input (hoisted_to; that op
     // lists it in `hoisted`) instead of at its place in the op list, so that the layer reading
-    // it can join the launch of layers that come before the pool in the list.
+    // it can join the launch of layers that come before the pool in the list.  The members of
+    // a group that tuning disbanded stay behind its first op the same way.
     int hoisted_to = -1;
     std::vector<int> hoisted;
 };
@@ -398,6 +399,13 @@ void layout(cadnn_net* net) {
             m.stride = o.stride; m.pad = o.pad; m.bias = eff_bias(net, o); m.relu = o.relu;
             return m;
         };
+        // a window pool on workspace tensors can ride along with such a group (it takes no part
+        // in the choice of the variant): the pooled branch of a module
+        auto solo_pool = [&](int k) {
+            const NetOp& o = net->ops[k];
+            return (o.kind == OP_MAXPOOL || o.kind == OP_AVGPOOL2D) && o.fused_into < 0 && o.colaunch_of < 0 &&
+                   o.src_inst >= 0 && k != nops - 1 && !o.xd.s2d && !o.yd.s2d;
+        };
         auto solo = [&](int k) {
             const NetOp& o = net->ops[k];
             return o.kind == OP_CONV && o.fused_into < 0 && o.shortcut < 0 && o.pool_op < 0 && o.dw_op < 0 &&
@@ -421,7 +429,14 @@ void layout(cadnn_net* net) {
             std::vector<const ConvVariant*> common = multi_of(i), narrowed;
             // (partners are looked for among the next 64 ops: a module's branches lie close together)
             for (int j = i + 1; j < std::min(nops, i + 65) && net->ops[i].comates.size() < 7 && !common.empty(); ++j) {
-                const NetOp& b = net->ops[j];
+                NetOp& b = net->ops[j];
+                if (solo_pool(j) && ready_at(b.src_inst) < i) {
+                    b.hoisted_to = -1;
+                    net->ops[i].comates.push_back(j);
+                    b.colaunch_of = i;
+                    b.fused_into = i;
+                    continue;
+                }
                 if (!solo(j) || ready_at(b.src_inst) >= i || (b.res >= 0 && ready_at(b.res_inst) >= i)) continue;
                 const std::vector<const ConvVariant*>& theirs = multi_of(j);
                 narrowed.clear();
@@ -502,6 +517,15 @@ std::vector<ConvMember> colaunch_members(const cadnn_net* net, size_t i) {
     for (int k : idx) {
         const NetOp& o = net->ops[k];
         ConvMember m{};
+        if (o.kind != OP_CONV) {
+            m.pool_kind = o.kind == OP_MAXPOOL ? 1 : 2;
+            m.pool_k = o.k;
+            m.x = net->ws + net->ops[o.src_inst].y_off; m.xd = o.xd;
+            m.y = net->ws + o.y_off; m.yd = o.yd;
+            m.stride = o.stride; m.pad = o.pad;
+            members.push_back(m);
+            continue;
+        }
         m.w = eff_w(net, o);
         m.x = net->ws + net->ops[o.src_inst].y_off; m.xd = o.xd;
         m.y = net->ws + o.y_off; m.yd = launch_yd(o);
@@ -534,13 +558,18 @@ cadnn_status set_colaunch_variant(cadnn_net* net, size_t i, const ConvVariant* v
     return CADNN_OK;
 }
 
-// Back to one launch per layer (tuning found the group slower than its members apart).
+// Back to one launch per layer (tuning found the group slower than its members apart).  The
+// members keep their place in the launch order, right behind op i and ahead of anything
+// already queued there: later groups were formed knowing their outputs complete at op i.
 void disband_colaunch(cadnn_net* net, size_t i) {
-    for (int j : net->ops[i].comates) {
+    NetOp& lead = net->ops[i];
+    for (int j : lead.comates) {
         net->ops[j].colaunch_of = -1;
         net->ops[j].fused_into = -1;
+        net->ops[j].hoisted_to = (int)i;
     }
-    net->ops[i].comates.clear();
+    lead.hoisted.insert(lead.hoisted.begin(), lead.comates.begin(), lead.comates.end());
+    lead.comates.clear();
     net->colaunch.erase((int)i);
 }
 
@@ -901,8 +930,9 @@ extern "C" cadnn_status cadnn_run_net(cadnn_net* net, const void* x, void* y, vo
         // then every group as a whole, over the variants that serve all its layers
         for (size_t i = 0; i < net->ops.size() && st == CADNN_OK; ++i) {
             if (net->ops[i].comates.empty()) continue;
+            // (a pool that rides along would cost a launch of its own: about 3.5 us at these sizes)
             float apart = alone_us[i];
-            for (int j : net->ops[i].comates) apart += alone_us[(size_t)j];
+            for (int j : net->ops[i].comates) apart += net->ops[j].kind == OP_CONV ? alone_us[(size_t)j] : 3.5f;
             const std::function<cadnn_status()> producer = [&]() {
                 return launch_one(net, (size_t)net->ops[i].src_inst, x, y, s);
             };
@@ -1002,9 +1032,9 @@ extern "C" cadnn_status cadnn_net_op_variant(const cadnn_net* net, int op_index,
         }
         case OP_FC: name = "sfc"; break;
         case OP_DEPTHWISE: name = op.fused_into >= 0 ? "fused" : "dwconv"; break;
-        case OP_MAXPOOL: name = "maxpool"; break;
+        case OP_MAXPOOL: name = op.fused_into >= 0 ? "fused" : "maxpool"; break;
         case OP_AVGPOOL: name = op.fused_into >= 0 ? "fused" : "avgpool"; break;
-        case OP_AVGPOOL2D: name = "avgpool2d"; break;
+        case OP_AVGPOOL2D: name = op.fused_into >= 0 ? "fused" : "avgpool2d"; break;
         case OP_CONCAT:
             name = std::all_of(op.in_place.begin(), op.in_place.end(), [](char c) { return c != 0; }) ? "in place" : "concat";
             break;
@@ -1047,6 +1077,20 @@ extern "C" cadnn_status cadnn_net_set_op_variant(cadnn_net* net, int op_index, c
     const NetOp& op = net->ops[op_index];
     if (op.kind != OP_CONV) return fail(CADNN_EINVAL, "cadnn_net_set_op_variant: op %d is not a convolution", op_index);
     if (op.fused_into >= 0) return CADNN_OK;     // nothing to pin: computed inside, or launched with, another op
+    if (!op.comates.empty() && name && std::strcmp(name, "apart") == 0) {
+        // the group's layers one launch each from now on (what tuning does to a group that loses)
+        drop_graph(net);
+        CADNN_HIP(hipDeviceSynchronize());
+        const std::vector<int> members = op.comates;
+        disband_colaunch(net, (size_t)op_index);
+        for (int j : members) {
+            const NetOp& m = net->ops[(size_t)j];
+            if (m.kind != OP_CONV) continue;
+            cadnn_status st = conv2d_prepare_impl(eff_w(net, m), m.xd, m.in.n, m.stride, m.pad, out_s2d(m), nullptr);
+            if (st != CADNN_OK) return st;
+        }
+        return CADNN_OK;
+    }
     if (!op.comates.empty()) {
         const ConvVariant* v = nullptr;
         if (name && *name) {

@@ -699,3 +699,44 @@ def test_sibling_layers_in_one_launch(cad, dtype_name):
             with pytest.raises(cad.CadnnError):
                 net.set_op_variant(6, "slinear_float_d1_r1k1w4u4")        # not a variant for several layers
         net.free()
+
+
+@pytest.mark.parametrize("dtype_name", ["f32", "f16"])
+def test_group_taken_apart_keeps_the_launch_order(cad, dtype_name):
+    """A pooled branch: the pool rides along with the module's first layers and its 1x1 layer
+    with the second ones, whose launch comes BEFORE the pool's place in the op list.  When the
+    first group is taken apart (as tuning does to a group that loses) the pool must still run
+    ahead of that second launch.  Checked on two different inputs in a row: on a repeated
+    input the stale pool output of the previous run would hide a wrong order."""
+    f16 = dtype_name == "f16"
+    dtype, npdt, tol = (cad.F16, np.float16, TOL_F16) if f16 else (cad.F32, np.float32, TOL_F32)
+    Op = wl.Op
+    ops = [Op("conv", "stem", 0, 1, 6, 24, 1, 1, 0, 0.8, True),
+           Op("conv", "a", 1, 2, 24, 12, 1, 1, 0, 0.8, True),            # leads the first launch: a, b (no ReLU: not a sibling), pool
+           Op("conv", "b", 1, 3, 24, 10, 1, 1, 0, 0.8, False),
+           Op("conv", "a2", 2, 4, 12, 16, 3, 1, 1, 0.8, True),           # leads the second: a2, b2, p1
+           Op("conv", "b2", 3, 5, 10, 16, 1, 1, 0, 0.8, True),
+           Op("avgpool2d", "pool", 1, 6, k=3, stride=1, pad=1),
+           Op("conv", "p1", 6, 7, 24, 8, 1, 1, 0, 0.8, True),
+           Op("concat", "cat", 4, 8, srcs=(4, 5, 7)),
+           Op("conv", "post", 8, 9, 40, 9, 1, 1, 0, 0.8, False)]
+    shape = (2, 6, 12, 10)
+    x, ws, bs = wl.net_tensors(ops, "apart", shape, input_relu=True)
+    xs = x.astype(npdt)
+    xs2 = wl.activation(shape, "apart", 99, relu=True).astype(npdt)
+    refs = [oracle.run_net(ops, v, ws, bs, dtype=npdt)[0] for v in (xs, xs2)]
+    net = cad.build_net(ops, ws, bs, shape, dtype, use_graph=True)
+    info = [net.op_info(i) for i in range(len(ops))]
+    assert [(info[i]["fused_into"], info[i]["launched_with"]) for i in (2, 5, 4, 6)] == [(1, 1), (1, 1), (3, 1), (3, 1)]
+    for step in ("together", "apart"):
+        if step == "apart":
+            net.set_op_variant(1, "apart")
+            info = [net.op_info(i) for i in range(len(ops))]
+            assert [(info[i]["fused_into"], info[i]["launched_after"]) for i in (2, 5)] == [(-1, 1), (-1, 1)]
+            assert info[6]["fused_into"] == 3                     # the second group is untouched
+            assert net.op_variant(5) == "avgpool2d" and net.op_variant(2).startswith("slinear")
+        for v, ref in ((xs, refs[0]), (xs2, refs[1]), (xs, refs[0])):
+            y = net.run(dev(v))
+            torch.cuda.synchronize()
+            assert_close(y.cpu().numpy(), ref, tol * (3 if f16 else 1), f"{step}")
+    net.free()

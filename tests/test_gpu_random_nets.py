@@ -158,16 +158,21 @@ def test_random_net(cad, seed):
     configs = [{}, {"plain_layout": True, "fuse": False}, {"use_graph": False}]
     if seed % 5 == 0:
         configs.append({"tune": True})      # every layer's candidates timed on the net's own buffers first
+    # a second input: a run must not lean on what the previous one left in the workspace (an op
+    # launched before its input is written would go unnoticed on a repeated input)
+    xs2 = wl.activation(shape, f"rnd{seed}", 99, relu=True).astype(npdt)
+    ref2 = oracle.run_net(ops, xs2, ws, bs, dtype=npdt)[0]
     for kw in configs:
         args = dict(use_graph=True)
         args.update(kw)
         net = cad.build_net(ops, ws, bs, shape, dtype, **args)
-        for rep in range(2):
-            y = net.run(torch.from_numpy(xs).cuda())
+        for rep in range(3):
+            inp, want = (xs2, ref2) if rep == 1 else (xs, ref)
+            y = net.run(torch.from_numpy(inp).cuda())
             torch.cuda.synchronize()
             got = y.cpu().numpy()
             assert np.isfinite(got).all()
-            e = rel_errors(got, ref)[0]
+            e = rel_errors(got, want)[0]
             assert e <= (tol * 5 if f16 else tol), (seed, kw, rep, e, [o.kind for o in ops])
         checked = 0
         for i, o in enumerate(ops[:-1]):

@@ -185,18 +185,19 @@ def test_inception_independent_layers_share_a_launch():
     for o, i in zip(ops, infos):
         if i["launched_with"]:
             groups.setdefault(ops[i["fused_into"]].name, []).append(o.name)
-    # (the pooled branch's 1x1 layer rides along because its pool moved up to the module's input)
-    assert groups["c1_7b"] == ["c1_dbl_b"] and groups["c1_7c"] == ["c1_dbl_c"] and groups["c1_1x1"] == ["c1_7a", "c1_pool1x1"]
-    assert infos[idx["c1_pool"]]["launched_after"] == idx["c1_1x1"] - 1 and ops[idx["c1_1x1"] - 1].kind == "concat"
-    assert groups["e1_3b"] == ["e1_3c", "e1_dbl_b"] and groups["e2_dbl_c"] == ["e2_dbl_d"]
-    assert groups["a1_5x5b"] == ["a1_3x3b"] and groups["d_3x3b"] == ["d_7b"]
-    assert sum(len(m) for m in groups.values()) == 37
+    # (a module's pool rides along with its first layers, the pooled branch's 1x1 layer with the second ones)
+    assert groups["c1_1x1"] == ["c1_7a", "c1_pool"] and groups["c1_7b"] == ["c1_dbl_b", "c1_pool1x1"]
+    assert groups["c1_7c"] == ["c1_dbl_c"] and groups["b_3x3"] == ["b_dbl_a", "b_pool"] and groups["d_3x3a"] == ["d_pool"]
+    assert groups["e1_3b"] == ["e1_3c", "e1_dbl_b", "e1_pool1x1"] and groups["e2_dbl_c"] == ["e2_dbl_d"]
+    assert groups["a1_5x5b"] == ["a1_3x3b", "a1_pool1x1"] and groups["d_3x3b"] == ["d_7b"]
+    assert sum(len(m) for m in groups.values()) == 48
     def ready(k):
         nxt = infos[k]["launched_after"] if infos[k]["launched_after"] >= 0 else infos[k]["fused_into"]
         return ready(nxt) if nxt >= 0 else k
     producer = {}
     for k, o in enumerate(ops):
-        if o.kind == "conv" and infos[k]["launched_with"]:
+        if infos[k]["launched_with"]:
+            assert o.kind in ("conv", "maxpool", "avgpool2d")
             lead = infos[k]["fused_into"]
             assert lead < k and ops[lead].kind == "conv" and infos[lead]["fused_into"] < 0
             assert ready(producer[o.src]) < lead, o.name           # its input is complete before the shared launch
