@@ -399,9 +399,17 @@ class Net:
         return [self.op_variant(i) for i in range(self.num_ops())]
 
     def set_variants(self, names: Sequence[str]) -> None:
-        """Pins every convolution op to the named variant (a saved tuning result)."""
+        """Pins every convolution op to the named variant (a saved tuning result: the list
+        `variants()` returned).  An op that shares another op's launch here but had a launch of
+        its own when the list was saved belongs to a group that tuning took apart: the group
+        is taken apart first."""
+        infos = [self.op_info(i) for i in range(len(self.ops))]
+        apart = sorted({infos[i]["fused_into"] for i, name in enumerate(names)
+                        if infos[i]["launched_with"] and name != "fused"})
+        for lead in apart:
+            self.set_op_variant(lead, "apart")
         for i, (op, name) in enumerate(zip(self.ops, names)):
-            if op.kind == "conv":
+            if op.kind == "conv" and name != "fused":
                 self.set_op_variant(i, name)
 
     def read_buffer(self, buf: int, shape, stream=None) -> np.ndarray:
