@@ -154,308 +154,351 @@ cadnn_status src_shape(cadnn_net* net, int src, Shape* s, int* inst) {
     return CADNN_OK;
 }
 
-// Chooses the halo of every op output (the largest padding among the convolutions with
-// filters larger than 1x1 that read it; none if a fully connected layer reads it or if it
-// is the net's output) and lays the regions out back to back.
-void layout(cadnn_net* net) {
-    const int nops = (int)net->ops.size();
-    std::vector<int> halo(nops, 0);
-    std::vector<bool> flat(nops, false);
-    for (const NetOp& op : net->ops) {
-        if (op.src_inst < 0) continue;
-        if (op.kind == OP_FC) flat[op.src_inst] = true;
-        if ((op.kind == OP_CONV || op.kind == OP_DEPTHWISE) && (op.w->kh > 1 || op.w->kw > 1))
-            halo[op.src_inst] = std::max(halo[op.src_inst], op.pad);
-    }
-    if (nops) flat[nops - 1] = true;
-    // A source of a concatenation that nothing else reads is written by its producer straight
-    // into its channel slice of the concatenation's region (not when that region is the
-    // caller's output tensor, and not for a producer that is itself a concatenation).
-    std::vector<int> all_readers(nops, 0);
-    for (const NetOp& op : net->ops) {
-        for (int i : input_insts(op)) if (i >= 0) ++all_readers[i];
-        if (op.res_inst >= 0) ++all_readers[op.res_inst];
-    }
-    for (NetOp& op : net->ops) { op.slice_of = -1; op.slice_ch = 0; }
-    for (int k = 0; k < nops; ++k) {
-        NetOp& cat = net->ops[k];
-        if (cat.kind != OP_CONCAT) continue;
-        cat.in_place.assign(cat.src_insts.size(), 0);
-        for (size_t j = 0; j < cat.src_insts.size(); ++j) {
-            const int p = cat.src_insts[j];
-            if (p < 0 || k == nops - 1 || all_readers[p] != 1) continue;
-            NetOp& prod = net->ops[p];
-            if (prod.kind != OP_CONV && prod.kind != OP_DEPTHWISE && prod.kind != OP_MAXPOOL && prod.kind != OP_AVGPOOL2D)
-                continue;
-            cat.in_place[j] = 1;
-            prod.slice_of = k;
-            prod.slice_ch = cat.ch_off[j];
-        }
-    }
+// The layout of a net: where every op's output lives, what is fused into what and what is
+// launched together.  The steps run in the order below; each reads what the ones before it
+// decided.
+struct Layout {
+    cadnn_net* net;
+    const int nops;
+    std::vector<int> halo;          // zero halo rows / columns around every op's output
+    std::vector<bool> flat;         // output kept without halo (read by an FC layer, or the net's output)
+    std::vector<int> all_readers;   // ops that read each op's output (as input or as residual)
+    std::vector<int> s2d, strided;  // de-interleaved layout: allowed for / wanted by the readers of each output
+    size_t off = 0;                 // bytes of workspace handed out so far
+
+    explicit Layout(cadnn_net* n)
+        : net(n), nops((int)n->ops.size()), halo(nops, 0), flat(nops, false), all_readers(nops, 0), s2d(nops, 0),
+          strided(nops, 0) {}
+
     // (Layers dense enough for the matrix-core kernels stay on plain layouts, which is all
     // those kernels read and write.)
-    auto sparse_enough = [](const NetOp& o) {
+    static bool sparse_enough(const NetOp& o) {
         return (double)o.w->nnz < 0.25 * (double)o.w->cout * o.w->cin * o.w->kh * o.w->kw;
-    };
-    // Sibling groups: pixel-wise (1x1, stride 1) sparse layers without residual that read the
-    // same tensor and are not concatenation slices become one launch over the rows of all of
-    // them (the reduce layers of an Inception module's branches).  Their outputs share one
-    // region, so they share its halo: the largest any of their readers needs.
-    for (NetOp& op : net->ops) { op.siblings.clear(); op.sibling_of = -1; op.sib_ch = 0; op.launch_c = op.out.c; }
-    net->merged_w.clear();
-    if (net->allow_fusion) {
-        auto eligible = [&](int k) {
-            const NetOp& o = net->ops[k];
-            return o.kind == OP_CONV && o.w->kh == 1 && o.w->kw == 1 && o.stride == 1 && o.pad == 0 && o.res < 0 &&
-                   o.slice_of < 0 && o.sibling_of < 0 && o.siblings.empty() && !flat[k] && k != nops - 1 && sparse_enough(o);
-        };
-        for (int i = 0; i < nops; ++i) {
-            if (!eligible(i)) continue;
-            std::vector<const cadnn_weights*> parts{net->ops[i].w};
-            std::vector<int> group;
-            for (int j = i + 1; j < nops; ++j) {
-                const NetOp& a = net->ops[i];
-                const NetOp& b = net->ops[j];
-                if (!eligible(j) || b.src_inst != a.src_inst || b.src != a.src || b.relu != a.relu || b.w->cin != a.w->cin ||
-                    (a.bias == nullptr) != (b.bias == nullptr))
+    }
+    static bool grouped(const NetOp& o) { return o.sibling_of >= 0 || !o.siblings.empty(); }
+
+    // The halo of every op output: the largest padding among the convolutions with filters
+    // larger than 1x1 that read it; none if a fully connected layer reads it or if it is the
+    // net's output.
+    void choose_halos() {
+        for (const NetOp& op : net->ops) {
+            if (op.src_inst < 0) continue;
+            if (op.kind == OP_FC) flat[op.src_inst] = true;
+            if ((op.kind == OP_CONV || op.kind == OP_DEPTHWISE) && (op.w->kh > 1 || op.w->kw > 1))
+                halo[op.src_inst] = std::max(halo[op.src_inst], op.pad);
+        }
+        if (nops) flat[nops - 1] = true;
+    }
+
+    void place_concat_slices() {
+        // A source of a concatenation that nothing else reads is written by its producer straight
+        // into its channel slice of the concatenation's region (not when that region is the
+        // caller's output tensor, and not for a producer that is itself a concatenation).
+        for (const NetOp& op : net->ops) {
+            for (int i : input_insts(op)) if (i >= 0) ++all_readers[i];
+            if (op.res_inst >= 0) ++all_readers[op.res_inst];
+        }
+        for (NetOp& op : net->ops) { op.slice_of = -1; op.slice_ch = 0; }
+        for (int k = 0; k < nops; ++k) {
+            NetOp& cat = net->ops[k];
+            if (cat.kind != OP_CONCAT) continue;
+            cat.in_place.assign(cat.src_insts.size(), 0);
+            for (size_t j = 0; j < cat.src_insts.size(); ++j) {
+                const int p = cat.src_insts[j];
+                if (p < 0 || k == nops - 1 || all_readers[p] != 1) continue;
+                NetOp& prod = net->ops[p];
+                if (prod.kind != OP_CONV && prod.kind != OP_DEPTHWISE && prod.kind != OP_MAXPOOL && prod.kind != OP_AVGPOOL2D)
                     continue;
-                // (the shared region must stay addressable like any tensor, under any reader's halo)
-                int total_c = b.out.c, h = std::max(halo[i], halo[j]);
-                for (const cadnn_weights* p : parts) total_c += p->cout;
-                for (int g : group) h = std::max(h, halo[g]);
-                if (!tensor_fits(net, Shape{a.out.n, total_c, a.out.h, a.out.w}, h)) continue;
-                parts.push_back(b.w);
-                group.push_back(j);
-            }
-            if (group.empty()) continue;
-            cadnn_weights* merged = nullptr;
-            if (merge_weights(parts, &merged) != CADNN_OK) continue;
-            net->merged_w[i].reset(merged);
-            NetOp& first = net->ops[i];
-            int ch = first.out.c, h = halo[i];
-            for (int j : group) {
-                NetOp& sib = net->ops[j];
-                sib.sibling_of = i;
-                sib.sib_ch = ch;
-                ch += sib.out.c;
-                h = std::max(h, halo[j]);
-                first.siblings.push_back(j);
-            }
-            first.launch_c = ch;
-            halo[i] = h;
-            for (int j : group) halo[j] = h;
-        }
-    }
-    // De-interleaved layout for the output of a convolution whose readers are all
-    // convolutions, at least one of them with stride 2: every reader must be either a
-    // stride-2 layer whose taps start on an even padded position (any 1x1; larger filters
-    // when halo - pad is even) or a pixel-wise stride-1 layer, and both the producer and
-    // the readers must be servable by the linear-address kernels.
-    std::vector<int> s2d(nops, 0), strided(nops, 0);
-    for (int i = 0; i < nops; ++i) {
-        const NetOp& p = net->ops[i];
-        bool ok = p.kind == OP_CONV && !flat[i] && (p.out.h % 2 == 0) && (p.out.w % 2 == 0) && sparse_enough(p) &&
-                  p.siblings.empty() && p.sibling_of < 0;
-        if (ok) {
-            const bool one = p.w->kh == 1 && p.w->kw == 1;
-            const int src_halo = p.src_inst < 0 ? 0 : (flat[p.src_inst] ? 0 : halo[p.src_inst]);
-            ok = one ? p.pad == 0 : src_halo >= p.pad;
-        }
-        s2d[i] = ok ? 1 : 0;
-    }
-    for (const NetOp& op : net->ops) {
-        if (op.res_inst >= 0) s2d[op.res_inst] = 0;
-        if (op.kind == OP_CONCAT) {
-            for (int i : op.src_insts) if (i >= 0) s2d[i] = 0;
-            continue;
-        }
-        if (op.src_inst < 0) continue;
-        const int i = op.src_inst;
-        if (op.kind != OP_CONV || !sparse_enough(op)) { s2d[i] = 0; continue; }
-        const bool one = op.w->kh == 1 && op.w->kw == 1;
-        if (op.stride == 2 && (one ? op.pad == 0 : ((halo[i] - op.pad) & 1) == 0)) strided[i] = 1;
-        else if (!(op.stride == 1 && one && op.pad == 0)) s2d[i] = 0;
-    }
-    size_t off = 0;
-    for (int i = 0; i < nops; ++i) {
-        NetOp& op = net->ops[i];
-        if (op.slice_of >= 0 || op.sibling_of >= 0) continue;   // lives inside another op's region, see below
-        const int hp = flat[i] ? 0 : halo[i];
-        op.yd = (s2d[i] && strided[i] && net->allow_s2d) ? make_desc_s2d(op.out.c, op.out.h, op.out.w, hp, hp)
-                                                        : make_desc(op.launch_c, op.out.h, op.out.w, hp, hp);
-        op.yd.c = op.out.c;                      // (with siblings the region holds launch_c channels; readers see the op's own)
-        op.y_off = off;
-        if (i != nops - 1) off += ((size_t)op.out.n * op.yd.image * net->elem() + 255) / 256 * 256;
-    }
-    for (NetOp& op : net->ops) {
-        if (op.sibling_of < 0) continue;
-        // a channel slice of the region the first op of the group writes
-        const NetOp& first = net->ops[op.sibling_of];
-        op.yd = first.yd;
-        op.yd.c = op.out.c;
-        op.y_off = first.y_off + (size_t)op.sib_ch * first.yd.plane * net->elem();
-    }
-    for (NetOp& op : net->ops) {
-        if (op.slice_of < 0) continue;
-        // a channel slice of the concatenation's region: its planes, its halo, its image stride
-        const NetOp& cat = net->ops[op.slice_of];
-        op.yd = cat.yd;
-        op.yd.c = op.out.c;
-        op.y_off = cat.y_off + (size_t)op.slice_ch * cat.yd.plane * net->elem();
-    }
-    for (NetOp& op : net->ops) {
-        op.xd = op.src_inst < 0 ? make_desc(op.in.c, op.in.h, op.in.w) : net->ops[op.src_inst].yd;
-        if (op.res >= 0)
-            op.rd = op.res_inst < 0 ? make_desc(net->input.c, net->input.h, net->input.w) : net->ops[op.res_inst].yd;
-        else
-            op.rd = op.yd;
-    }
-    // A 1x1 projection shortcut whose only reader takes it as residual is computed inside
-    // that reader (a second sparse matrix on a second input, same accumulators): one launch,
-    // one output write and one residual read less (paper Section 4, layer fusion).
-    for (NetOp& op : net->ops) { op.shortcut = -1; op.pool_op = -1; op.dw_op = -1; op.fused_into = op.sibling_of; }
-    auto grouped = [](const NetOp& o) { return o.sibling_of >= 0 || !o.siblings.empty(); };
-    if (net->allow_fusion) {
-        const std::vector<int>& readers = all_readers;
-        for (int i = 0; i < nops; ++i) {
-            NetOp& c = net->ops[i];
-            if (c.kind != OP_CONV || c.res_inst < 0) continue;
-            NetOp& p = net->ops[c.res_inst];
-            const bool c_one = c.w->kh == 1 && c.w->kw == 1;
-            const bool ok = p.kind == OP_CONV && !grouped(p) && p.w->kh == 1 && p.w->kw == 1 && p.pad == 0 && !p.relu && p.res < 0 &&
-                            readers[c.res_inst] == 1 && c.res_inst != nops - 1 && p.w->cout == c.w->cout &&
-                            sparse_enough(c) && sparse_enough(p) && !c.yd.s2d && !(c.xd.s2d && c.stride == 1) &&
-                            (c_one ? c.pad == 0 : (c.xd.ph >= c.pad && c.xd.pw >= c.pad)) &&
-                            (!c.xd.s2d || c_one || (((c.xd.ph - c.pad) & 1) == 0 && ((c.xd.pw - c.pad) & 1) == 0)) &&
-                            (!p.xd.s2d || p.stride == 2);
-            if (ok) {
-                c.shortcut = c.res_inst;
-                p.fused_into = i;
-            }
-        }
-        // A global average pool that is the only reader of a convolution whose image fits one
-        // pixel tile is computed in that convolution's epilogue; the feature map is not written.
-        for (int i = 0; i < nops; ++i) {
-            NetOp& a = net->ops[i];
-            if (a.kind != OP_AVGPOOL || a.src_inst < 0) continue;
-            NetOp& c = net->ops[a.src_inst];
-            const bool c_one = c.kind == OP_CONV && c.w->kh == 1 && c.w->kw == 1;
-            const bool ok = c.kind == OP_CONV && !grouped(c) && readers[a.src_inst] == 1 && c.shortcut < 0 && c.fused_into < 0 &&
-                            sparse_enough(c) && !c.yd.s2d && !c.xd.s2d && !(c.res >= 0 && c.rd.s2d) &&
-                            c.out.h * c.out.w <= 256 &&
-                            (c_one ? c.pad == 0 : (c.xd.ph >= c.pad && c.xd.pw >= c.pad));
-            if (ok) {
-                c.pool_op = i;
-                a.fused_into = a.src_inst;
-            }
-        }
-        // A 3x3 depthwise layer (padding 1, stride 1 or 2) that is the only reader of a
-        // convolution whose image is at most 28 x 28 is computed in that convolution's
-        // epilogue: a wave (images of up to 64 pixels) or the 4 or 16 waves of a workgroup hold a
-        // whole channel there, which is all a depthwise filter needs.  The convolution's own
-        // feature map is not written.
-        for (int i = 0; i < nops; ++i) {
-            NetOp& d = net->ops[i];
-            if (d.kind != OP_DEPTHWISE || d.src_inst < 0) continue;
-            NetOp& c = net->ops[d.src_inst];
-            const bool c_one = c.kind == OP_CONV && c.w->kh == 1 && c.w->kw == 1;
-            const bool ok = c.kind == OP_CONV && !grouped(c) && readers[d.src_inst] == 1 && c.shortcut < 0 && c.pool_op < 0 &&
-                            c.fused_into < 0 && sparse_enough(c) && !c.yd.s2d && !c.xd.s2d && !(c.res >= 0 && c.rd.s2d) &&
-                            c.out.h <= 28 && c.out.w <= 28 && d.w->kh == 3 && d.w->kw == 3 && d.pad == 1 &&
-                            (d.stride == 1 || d.stride == 2) && !d.yd.s2d &&
-                            (c_one ? c.pad == 0 : (c.xd.ph >= c.pad && c.xd.pw >= c.pad));
-            if (ok) {
-                c.dw_op = i;
-                d.fused_into = d.src_inst;
+                cat.in_place[j] = 1;
+                prod.slice_of = k;
+                prod.slice_ch = cat.ch_off[j];
             }
         }
     }
-    // Independent layers in one launch: sparse convolutions on plain tensors with nothing fused
-    // into them, none of them touching the caller's x or y, whose inputs are all produced
-    // before the first of them runs (the branches of an Inception module at the same depth).
-    // Launched apart each would leave most of the chip idle and pay a launch of its own;
-    // together they take about as long as the slowest.  A layer joins only while one kernel
-    // variant still serves the whole group.
-    for (NetOp& op : net->ops) { op.comates.clear(); op.colaunch_of = -1; op.hoisted_to = -1; op.hoisted.clear(); }
-    // the op at whose launch op k's output becomes available: k itself, the op that computes
-    // it (a sibling's or comate's first layer, the layer a pool is fused into), or the op a
-    // hoisted pool is launched behind
-    std::function<int(int)> ready_at = [&](int k) {
-        const NetOp& o = net->ops[k];
-        return o.hoisted_to >= 0 ? ready_at(o.hoisted_to) : o.fused_into >= 0 ? ready_at(o.fused_into) : k;
-    };
-    if (net->allow_fusion) {
-        for (int p = 0; p + 1 < nops; ++p) {
-            NetOp& o = net->ops[p];
-            if ((o.kind == OP_MAXPOOL || o.kind == OP_AVGPOOL2D) && o.fused_into < 0 && o.src_inst >= 0 &&
-                ready_at(o.src_inst) < p - 1)
-                o.hoisted_to = o.src_inst;
-        }
-        auto member_of = [&](const NetOp& o) {
-            // (pointers only have to be distinct and non-NULL here: nothing is launched)
-            ConvMember m{};
-            m.w = eff_w(net, o); m.x = (const void*)16; m.xd = o.xd; m.y = (void*)32; m.yd = launch_yd(o);
-            m.residual = o.res >= 0 ? (const void*)48 : nullptr; m.rd = o.rd;
-            m.stride = o.stride; m.pad = o.pad; m.bias = eff_bias(net, o); m.relu = o.relu;
-            return m;
-        };
-        // a window pool on workspace tensors can ride along with such a group (it takes no part
-        // in the choice of the variant): the pooled branch of a module
-        auto solo_pool = [&](int k) {
-            const NetOp& o = net->ops[k];
-            return (o.kind == OP_MAXPOOL || o.kind == OP_AVGPOOL2D) && o.fused_into < 0 && o.colaunch_of < 0 &&
-                   o.src_inst >= 0 && k != nops - 1 && !o.xd.s2d && !o.yd.s2d;
-        };
-        auto solo = [&](int k) {
-            const NetOp& o = net->ops[k];
-            return o.kind == OP_CONV && o.fused_into < 0 && o.shortcut < 0 && o.pool_op < 0 && o.dw_op < 0 &&
-                   o.colaunch_of < 0 && o.comates.empty() && sparse_enough(o) && !o.yd.s2d && !o.xd.s2d &&
-                   !(o.res >= 0 && o.rd.s2d) && o.src_inst >= 0 && k != nops - 1 && (o.res < 0 || o.res_inst >= 0);
-        };
-        // the variants that can launch op k among several layers (sorted; listed once per op)
-        std::vector<std::vector<const ConvVariant*>> multi(nops);
-        std::vector<char> listed(nops, 0);
-        auto multi_of = [&](int k) -> const std::vector<const ConvVariant*>& {
-            if (!listed[k]) {
-                listed[k] = 1;
-                if (conv2d_group_candidates({member_of(net->ops[k])}, net->ops[k].in.n, &multi[k], nullptr) != CADNN_OK)
-                    multi[k].clear();
-                std::sort(multi[k].begin(), multi[k].end());
-            }
-            return multi[k];
-        };
-        for (int i = 0; i < nops; ++i) {
-            if (!solo(i)) continue;
-            std::vector<const ConvVariant*> common = multi_of(i), narrowed;
-            // (partners are looked for among the next 64 ops: a module's branches lie close together)
-            for (int j = i + 1; j < std::min(nops, i + 65) && net->ops[i].comates.size() < 7 && !common.empty(); ++j) {
-                NetOp& b = net->ops[j];
-                if (solo_pool(j) && ready_at(b.src_inst) < i) {
-                    b.hoisted_to = -1;
-                    net->ops[i].comates.push_back(j);
-                    b.colaunch_of = i;
-                    b.fused_into = i;
-                    continue;
+
+    void merge_siblings() {
+        // Sibling groups: pixel-wise (1x1, stride 1) sparse layers without residual that read the
+        // same tensor and are not concatenation slices become one launch over the rows of all of
+        // them (the reduce layers of an Inception module's branches).  Their outputs share one
+        // region, so they share its halo: the largest any of their readers needs.
+        for (NetOp& op : net->ops) { op.siblings.clear(); op.sibling_of = -1; op.sib_ch = 0; op.launch_c = op.out.c; }
+        net->merged_w.clear();
+        if (net->allow_fusion) {
+            auto eligible = [&](int k) {
+                const NetOp& o = net->ops[k];
+                return o.kind == OP_CONV && o.w->kh == 1 && o.w->kw == 1 && o.stride == 1 && o.pad == 0 && o.res < 0 &&
+                       o.slice_of < 0 && o.sibling_of < 0 && o.siblings.empty() && !flat[k] && k != nops - 1 && sparse_enough(o);
+            };
+            for (int i = 0; i < nops; ++i) {
+                if (!eligible(i)) continue;
+                std::vector<const cadnn_weights*> parts{net->ops[i].w};
+                std::vector<int> group;
+                for (int j = i + 1; j < nops; ++j) {
+                    const NetOp& a = net->ops[i];
+                    const NetOp& b = net->ops[j];
+                    if (!eligible(j) || b.src_inst != a.src_inst || b.src != a.src || b.relu != a.relu || b.w->cin != a.w->cin ||
+                        (a.bias == nullptr) != (b.bias == nullptr))
+                        continue;
+                    // (the shared region must stay addressable like any tensor, under any reader's halo)
+                    int total_c = b.out.c, h = std::max(halo[i], halo[j]);
+                    for (const cadnn_weights* p : parts) total_c += p->cout;
+                    for (int g : group) h = std::max(h, halo[g]);
+                    if (!tensor_fits(net, Shape{a.out.n, total_c, a.out.h, a.out.w}, h)) continue;
+                    parts.push_back(b.w);
+                    group.push_back(j);
                 }
-                if (!solo(j) || ready_at(b.src_inst) >= i || (b.res >= 0 && ready_at(b.res_inst) >= i)) continue;
-                const std::vector<const ConvVariant*>& theirs = multi_of(j);
-                narrowed.clear();
-                std::set_intersection(common.begin(), common.end(), theirs.begin(), theirs.end(), std::back_inserter(narrowed));
-                if (narrowed.empty()) continue;
-                common.swap(narrowed);
-                net->ops[i].comates.push_back(j);
-                net->ops[j].colaunch_of = i;
-                net->ops[j].fused_into = i;
+                if (group.empty()) continue;
+                cadnn_weights* merged = nullptr;
+                if (merge_weights(parts, &merged) != CADNN_OK) continue;
+                net->merged_w[i].reset(merged);
+                NetOp& first = net->ops[i];
+                int ch = first.out.c, h = halo[i];
+                for (int j : group) {
+                    NetOp& sib = net->ops[j];
+                    sib.sibling_of = i;
+                    sib.sib_ch = ch;
+                    ch += sib.out.c;
+                    h = std::max(h, halo[j]);
+                    first.siblings.push_back(j);
+                }
+                first.launch_c = ch;
+                halo[i] = h;
+                for (int j : group) halo[j] = h;
             }
         }
-        // every hoisted pool goes behind the op that really launches when its input completes
-        for (int p = 0; p < nops; ++p)
-            if (net->ops[p].hoisted_to >= 0) {
-                net->ops[p].hoisted_to = ready_at(p);
-                net->ops[net->ops[p].hoisted_to].hoisted.push_back(p);
-            }
     }
-    net->ws_bytes = off;
+
+    void choose_deinterleaved() {
+        // De-interleaved layout for the output of a convolution whose readers are all
+        // convolutions, at least one of them with stride 2: every reader must be either a
+        // stride-2 layer whose taps start on an even padded position (any 1x1; larger filters
+        // when halo - pad is even) or a pixel-wise stride-1 layer, and both the producer and
+        // the readers must be servable by the linear-address kernels.
+        for (int i = 0; i < nops; ++i) {
+            const NetOp& p = net->ops[i];
+            bool ok = p.kind == OP_CONV && !flat[i] && (p.out.h % 2 == 0) && (p.out.w % 2 == 0) && sparse_enough(p) &&
+                      p.siblings.empty() && p.sibling_of < 0;
+            if (ok) {
+                const bool one = p.w->kh == 1 && p.w->kw == 1;
+                const int src_halo = p.src_inst < 0 ? 0 : (flat[p.src_inst] ? 0 : halo[p.src_inst]);
+                ok = one ? p.pad == 0 : src_halo >= p.pad;
+            }
+            s2d[i] = ok ? 1 : 0;
+        }
+        for (const NetOp& op : net->ops) {
+            if (op.res_inst >= 0) s2d[op.res_inst] = 0;
+            if (op.kind == OP_CONCAT) {
+                for (int i : op.src_insts) if (i >= 0) s2d[i] = 0;
+                continue;
+            }
+            if (op.src_inst < 0) continue;
+            const int i = op.src_inst;
+            if (op.kind != OP_CONV || !sparse_enough(op)) { s2d[i] = 0; continue; }
+            const bool one = op.w->kh == 1 && op.w->kw == 1;
+            if (op.stride == 2 && (one ? op.pad == 0 : ((halo[i] - op.pad) & 1) == 0)) strided[i] = 1;
+            else if (!(op.stride == 1 && one && op.pad == 0)) s2d[i] = 0;
+        }
+    }
+
+    // The regions back to back, 256-byte aligned, in op order; slices take their place inside.
+    void place_regions() {
+        for (int i = 0; i < nops; ++i) {
+            NetOp& op = net->ops[i];
+            if (op.slice_of >= 0 || op.sibling_of >= 0) continue;   // lives inside another op's region, see below
+            const int hp = flat[i] ? 0 : halo[i];
+            op.yd = (s2d[i] && strided[i] && net->allow_s2d) ? make_desc_s2d(op.out.c, op.out.h, op.out.w, hp, hp)
+                                                            : make_desc(op.launch_c, op.out.h, op.out.w, hp, hp);
+            op.yd.c = op.out.c;                      // (with siblings the region holds launch_c channels; readers see the op's own)
+            op.y_off = off;
+            if (i != nops - 1) off += ((size_t)op.out.n * op.yd.image * net->elem() + 255) / 256 * 256;
+        }
+        for (NetOp& op : net->ops) {
+            if (op.sibling_of < 0) continue;
+            // a channel slice of the region the first op of the group writes
+            const NetOp& first = net->ops[op.sibling_of];
+            op.yd = first.yd;
+            op.yd.c = op.out.c;
+            op.y_off = first.y_off + (size_t)op.sib_ch * first.yd.plane * net->elem();
+        }
+        for (NetOp& op : net->ops) {
+            if (op.slice_of < 0) continue;
+            // a channel slice of the concatenation's region: its planes, its halo, its image stride
+            const NetOp& cat = net->ops[op.slice_of];
+            op.yd = cat.yd;
+            op.yd.c = op.out.c;
+            op.y_off = cat.y_off + (size_t)op.slice_ch * cat.yd.plane * net->elem();
+        }
+        for (NetOp& op : net->ops) {
+            op.xd = op.src_inst < 0 ? make_desc(op.in.c, op.in.h, op.in.w) : net->ops[op.src_inst].yd;
+            if (op.res >= 0)
+                op.rd = op.res_inst < 0 ? make_desc(net->input.c, net->input.h, net->input.w) : net->ops[op.res_inst].yd;
+            else
+                op.rd = op.yd;
+        }
+    }
+
+    void fuse() {
+        // A 1x1 projection shortcut whose only reader takes it as residual is computed inside
+        // that reader (a second sparse matrix on a second input, same accumulators): one launch,
+        // one output write and one residual read less (paper Section 4, layer fusion).
+        for (NetOp& op : net->ops) { op.shortcut = -1; op.pool_op = -1; op.dw_op = -1; op.fused_into = op.sibling_of; }
+        if (net->allow_fusion) {
+            const std::vector<int>& readers = all_readers;
+            for (int i = 0; i < nops; ++i) {
+                NetOp& c = net->ops[i];
+                if (c.kind != OP_CONV || c.res_inst < 0) continue;
+                NetOp& p = net->ops[c.res_inst];
+                const bool c_one = c.w->kh == 1 && c.w->kw == 1;
+                const bool ok = p.kind == OP_CONV && !grouped(p) && p.w->kh == 1 && p.w->kw == 1 && p.pad == 0 && !p.relu && p.res < 0 &&
+                                readers[c.res_inst] == 1 && c.res_inst != nops - 1 && p.w->cout == c.w->cout &&
+                                sparse_enough(c) && sparse_enough(p) && !c.yd.s2d && !(c.xd.s2d && c.stride == 1) &&
+                                (c_one ? c.pad == 0 : (c.xd.ph >= c.pad && c.xd.pw >= c.pad)) &&
+                                (!c.xd.s2d || c_one || (((c.xd.ph - c.pad) & 1) == 0 && ((c.xd.pw - c.pad) & 1) == 0)) &&
+                                (!p.xd.s2d || p.stride == 2);
+                if (ok) {
+                    c.shortcut = c.res_inst;
+                    p.fused_into = i;
+                }
+            }
+            // A global average pool that is the only reader of a convolution whose image fits one
+            // pixel tile is computed in that convolution's epilogue; the feature map is not written.
+            for (int i = 0; i < nops; ++i) {
+                NetOp& a = net->ops[i];
+                if (a.kind != OP_AVGPOOL || a.src_inst < 0) continue;
+                NetOp& c = net->ops[a.src_inst];
+                const bool c_one = c.kind == OP_CONV && c.w->kh == 1 && c.w->kw == 1;
+                const bool ok = c.kind == OP_CONV && !grouped(c) && readers[a.src_inst] == 1 && c.shortcut < 0 && c.fused_into < 0 &&
+                                sparse_enough(c) && !c.yd.s2d && !c.xd.s2d && !(c.res >= 0 && c.rd.s2d) &&
+                                c.out.h * c.out.w <= 256 &&
+                                (c_one ? c.pad == 0 : (c.xd.ph >= c.pad && c.xd.pw >= c.pad));
+                if (ok) {
+                    c.pool_op = i;
+                    a.fused_into = a.src_inst;
+                }
+            }
+            // A 3x3 depthwise layer (padding 1, stride 1 or 2) that is the only reader of a
+            // convolution whose image is at most 28 x 28 is computed in that convolution's
+            // epilogue: a wave (images of up to 64 pixels) or the 4 or 16 waves of a workgroup hold a
+            // whole channel there, which is all a depthwise filter needs.  The convolution's own
+            // feature map is not written.
+            for (int i = 0; i < nops; ++i) {
+                NetOp& d = net->ops[i];
+                if (d.kind != OP_DEPTHWISE || d.src_inst < 0) continue;
+                NetOp& c = net->ops[d.src_inst];
+                const bool c_one = c.kind == OP_CONV && c.w->kh == 1 && c.w->kw == 1;
+                const bool ok = c.kind == OP_CONV && !grouped(c) && readers[d.src_inst] == 1 && c.shortcut < 0 && c.pool_op < 0 &&
+                                c.fused_into < 0 && sparse_enough(c) && !c.yd.s2d && !c.xd.s2d && !(c.res >= 0 && c.rd.s2d) &&
+                                c.out.h <= 28 && c.out.w <= 28 && d.w->kh == 3 && d.w->kw == 3 && d.pad == 1 &&
+                                (d.stride == 1 || d.stride == 2) && !d.yd.s2d &&
+                                (c_one ? c.pad == 0 : (c.xd.ph >= c.pad && c.xd.pw >= c.pad));
+                if (ok) {
+                    c.dw_op = i;
+                    d.fused_into = d.src_inst;
+                }
+            }
+        }
+    }
+
+    void share_launches() {
+        // Independent layers in one launch: sparse convolutions on plain tensors with nothing fused
+        // into them, none of them touching the caller's x or y, whose inputs are all produced
+        // before the first of them runs (the branches of an Inception module at the same depth).
+        // Launched apart each would leave most of the chip idle and pay a launch of its own;
+        // together they take about as long as the slowest.  A layer joins only while one kernel
+        // variant still serves the whole group.
+        for (NetOp& op : net->ops) { op.comates.clear(); op.colaunch_of = -1; op.hoisted_to = -1; op.hoisted.clear(); }
+        // the op at whose launch op k's output becomes available: k itself, the op that computes
+        // it (a sibling's or comate's first layer, the layer a pool is fused into), or the op a
+        // hoisted pool is launched behind
+        std::function<int(int)> ready_at = [&](int k) {
+            const NetOp& o = net->ops[k];
+            return o.hoisted_to >= 0 ? ready_at(o.hoisted_to) : o.fused_into >= 0 ? ready_at(o.fused_into) : k;
+        };
+        if (net->allow_fusion) {
+            for (int p = 0; p + 1 < nops; ++p) {
+                NetOp& o = net->ops[p];
+                if ((o.kind == OP_MAXPOOL || o.kind == OP_AVGPOOL2D) && o.fused_into < 0 && o.src_inst >= 0 &&
+                    ready_at(o.src_inst) < p - 1)
+                    o.hoisted_to = o.src_inst;
+            }
+            auto member_of = [&](const NetOp& o) {
+                // (pointers only have to be distinct and non-NULL here: nothing is launched)
+                ConvMember m{};
+                m.w = eff_w(net, o); m.x = (const void*)16; m.xd = o.xd; m.y = (void*)32; m.yd = launch_yd(o);
+                m.residual = o.res >= 0 ? (const void*)48 : nullptr; m.rd = o.rd;
+                m.stride = o.stride; m.pad = o.pad; m.bias = eff_bias(net, o); m.relu = o.relu;
+                return m;
+            };
+            // a window pool on workspace tensors can ride along with such a group (it takes no part
+            // in the choice of the variant): the pooled branch of a module
+            auto solo_pool = [&](int k) {
+                const NetOp& o = net->ops[k];
+                return (o.kind == OP_MAXPOOL || o.kind == OP_AVGPOOL2D) && o.fused_into < 0 && o.colaunch_of < 0 &&
+                       o.src_inst >= 0 && k != nops - 1 && !o.xd.s2d && !o.yd.s2d;
+            };
+            auto solo = [&](int k) {
+                const NetOp& o = net->ops[k];
+                return o.kind == OP_CONV && o.fused_into < 0 && o.shortcut < 0 && o.pool_op < 0 && o.dw_op < 0 &&
+                       o.colaunch_of < 0 && o.comates.empty() && sparse_enough(o) && !o.yd.s2d && !o.xd.s2d &&
+                       !(o.res >= 0 && o.rd.s2d) && o.src_inst >= 0 && k != nops - 1 && (o.res < 0 || o.res_inst >= 0);
+            };
+            // the variants that can launch op k among several layers (sorted; listed once per op)
+            std::vector<std::vector<const ConvVariant*>> multi(nops);
+            std::vector<char> listed(nops, 0);
+            auto multi_of = [&](int k) -> const std::vector<const ConvVariant*>& {
+                if (!listed[k]) {
+                    listed[k] = 1;
+                    if (conv2d_group_candidates({member_of(net->ops[k])}, net->ops[k].in.n, &multi[k], nullptr) != CADNN_OK)
+                        multi[k].clear();
+                    std::sort(multi[k].begin(), multi[k].end());
+                }
+                return multi[k];
+            };
+            for (int i = 0; i < nops; ++i) {
+                if (!solo(i)) continue;
+                std::vector<const ConvVariant*> common = multi_of(i), narrowed;
+                // (partners are looked for among the next 64 ops: a module's branches lie close together)
+                for (int j = i + 1; j < std::min(nops, i + 65) && net->ops[i].comates.size() < 7 && !common.empty(); ++j) {
+                    NetOp& b = net->ops[j];
+                    if (solo_pool(j) && ready_at(b.src_inst) < i) {
+                        b.hoisted_to = -1;
+                        net->ops[i].comates.push_back(j);
+                        b.colaunch_of = i;
+                        b.fused_into = i;
+                        continue;
+                    }
+                    if (!solo(j) || ready_at(b.src_inst) >= i || (b.res >= 0 && ready_at(b.res_inst) >= i)) continue;
+                    const std::vector<const ConvVariant*>& theirs = multi_of(j);
+                    narrowed.clear();
+                    std::set_intersection(common.begin(), common.end(), theirs.begin(), theirs.end(), std::back_inserter(narrowed));
+                    if (narrowed.empty()) continue;
+                    common.swap(narrowed);
+                    net->ops[i].comates.push_back(j);
+                    net->ops[j].colaunch_of = i;
+                    net->ops[j].fused_into = i;
+                }
+            }
+            // every hoisted pool goes behind the op that really launches when its input completes
+            for (int p = 0; p < nops; ++p)
+                if (net->ops[p].hoisted_to >= 0) {
+                    net->ops[p].hoisted_to = ready_at(p);
+                    net->ops[net->ops[p].hoisted_to].hoisted.push_back(p);
+                }
+        }
+    }
+
+};
+
+void layout(cadnn_net* net) {
+    Layout l(net);
+    l.choose_halos();
+    l.place_concat_slices();
+    l.merge_siblings();
+    l.choose_deinterleaved();
+    l.place_regions();
+    l.fuse();
+    l.share_launches();
+    net->ws_bytes = l.off;
     net->laid_out = true;
 }
 
