@@ -683,6 +683,46 @@ void drop_graph(cadnn_net* net) {
     net->cap_y = nullptr;
 }
 
+// Live tuning (CADNN_NET_TUNE, on the first run): every convolution's candidates are timed on
+// the data an ordinary pass leaves in its input region, then every group of co-launched layers
+// as a whole; a group stays only if it beats its layers launched apart.
+cadnn_status tune_net(cadnn_net* net, const void* x, void* y, hipStream_t s) {
+    // every layer is timed on the data an ordinary pass leaves in its input region
+    cadnn_status st = launch_all(net, x, y, s);
+    std::vector<float> alone_us(net->ops.size(), 0.0f);
+    for (size_t i = 0; i < net->ops.size() && st == CADNN_OK; ++i) {
+        const NetOp& op = net->ops[i];
+        // (co-launched layers are timed one by one too: the group must beat their sum)
+        if (op.kind != OP_CONV || (op.fused_into >= 0 && op.colaunch_of < 0)) continue;
+        const std::function<cadnn_status()> producer = [&]() {
+            return op.src_inst >= 0 ? launch_one(net, (size_t)op.src_inst, x, y, s) : CADNN_OK;
+        };
+        ConvExtra ex;
+        const bool fused = shortcut_of(net, op, x, &ex, y);
+        st = conv2d_tune_impl(eff_w(net, op), in_ptr(net, op.src_inst, x), op.xd, out_ptr(net, i, y), launch_yd(op),
+                              (op.res >= 0 && op.shortcut < 0) ? in_ptr(net, op.res_inst, x) : nullptr, op.rd, op.in.n,
+                              op.stride, op.pad, eff_bias(net, op), op.relu, s, 20, &alone_us[i], &producer,
+                              fused ? &ex : nullptr);
+    }
+    // then every group as a whole, over the variants that serve all its layers
+    for (size_t i = 0; i < net->ops.size() && st == CADNN_OK; ++i) {
+        if (net->ops[i].comates.empty()) continue;
+        // (a pool that rides along would cost a launch of its own: about 3.5 us at these sizes)
+        float apart = alone_us[i];
+        for (int j : net->ops[i].comates) apart += net->ops[j].kind == OP_CONV ? alone_us[(size_t)j] : 3.5f;
+        const std::function<cadnn_status()> producer = [&]() {
+            return launch_one(net, (size_t)net->ops[i].src_inst, x, y, s);
+        };
+        const ConvVariant* best = nullptr;
+        float together = 0.0f;
+        st = conv2d_group_tune(colaunch_members(net, i), net->ops[i].in.n, s, 20, &producer, &best, &together);
+        if (st != CADNN_OK) break;
+        if (best && together < apart) st = set_colaunch_variant(net, i, best);
+        else disband_colaunch(net, i);
+    }
+    return st;
+}
+
 }  // namespace
 
 extern "C" cadnn_status cadnn_net_create(cadnn_dtype dtype, int n, int c, int h, int w,
@@ -953,39 +993,7 @@ extern "C" cadnn_status cadnn_run_net(cadnn_net* net, const void* x, void* y, vo
     if (!net->finalized) return fail(CADNN_EINVAL, "cadnn_run_net: net not finalized");
     hipStream_t s = (hipStream_t)stream;
     if (net->want_tune) {
-        // every layer is timed on the data an ordinary pass leaves in its input region
-        cadnn_status st = launch_all(net, x, y, s);
-        std::vector<float> alone_us(net->ops.size(), 0.0f);
-        for (size_t i = 0; i < net->ops.size() && st == CADNN_OK; ++i) {
-            const NetOp& op = net->ops[i];
-            // (co-launched layers are timed one by one too: the group must beat their sum)
-            if (op.kind != OP_CONV || (op.fused_into >= 0 && op.colaunch_of < 0)) continue;
-            const std::function<cadnn_status()> producer = [&]() {
-                return op.src_inst >= 0 ? launch_one(net, (size_t)op.src_inst, x, y, s) : CADNN_OK;
-            };
-            ConvExtra ex;
-            const bool fused = shortcut_of(net, op, x, &ex, y);
-            st = conv2d_tune_impl(eff_w(net, op), in_ptr(net, op.src_inst, x), op.xd, out_ptr(net, i, y), launch_yd(op),
-                                  (op.res >= 0 && op.shortcut < 0) ? in_ptr(net, op.res_inst, x) : nullptr, op.rd, op.in.n,
-                                  op.stride, op.pad, eff_bias(net, op), op.relu, s, 20, &alone_us[i], &producer,
-                                  fused ? &ex : nullptr);
-        }
-        // then every group as a whole, over the variants that serve all its layers
-        for (size_t i = 0; i < net->ops.size() && st == CADNN_OK; ++i) {
-            if (net->ops[i].comates.empty()) continue;
-            // (a pool that rides along would cost a launch of its own: about 3.5 us at these sizes)
-            float apart = alone_us[i];
-            for (int j : net->ops[i].comates) apart += net->ops[j].kind == OP_CONV ? alone_us[(size_t)j] : 3.5f;
-            const std::function<cadnn_status()> producer = [&]() {
-                return launch_one(net, (size_t)net->ops[i].src_inst, x, y, s);
-            };
-            const ConvVariant* best = nullptr;
-            float together = 0.0f;
-            st = conv2d_group_tune(colaunch_members(net, i), net->ops[i].in.n, s, 20, &producer, &best, &together);
-            if (st != CADNN_OK) break;
-            if (best && together < apart) st = set_colaunch_variant(net, i, best);
-            else disband_colaunch(net, i);
-        }
+        cadnn_status st = tune_net(net, x, y, s);
         if (st != CADNN_OK) return st;
         net->want_tune = false;
         drop_graph(net);
