@@ -72,6 +72,7 @@ struct CoLaunch {
     DevBuf table;
     std::vector<std::shared_ptr<ConvPlan>> plans;
     int layers = 0, tiles_x = 0, row_groups = 0;
+    int64_t used_blocks = 0;      // workgroups inside some member's own grid (the others leave at once)
 };
 
 // Weights, bias and output layout an op is launched with: its own, or -- first op of a sibling
@@ -597,6 +598,7 @@ cadnn_status set_colaunch_variant(cadnn_net* net, size_t i, const ConvVariant* v
     if ((st = c->table.upload(records.data(), records.size() * sizeof(ConvLaunch))) != CADNN_OK) return st;
     c->v = v;
     c->layers = (int)records.size();
+    for (const ConvLaunch& r : records) c->used_blocks += (int64_t)r.tiles_x * r.row_groups;
     net->colaunch[(int)i] = std::move(c);
     return CADNN_OK;
 }
@@ -614,6 +616,19 @@ void disband_colaunch(cadnn_net* net, size_t i) {
     lead.hoisted.insert(lead.hoisted.begin(), lead.comates.begin(), lead.comates.end());
     lead.comates.clear();
     net->colaunch.erase((int)i);
+}
+
+// ... outside tuning, where the members have no plans of their own yet.
+cadnn_status take_apart(cadnn_net* net, size_t i) {
+    const std::vector<int> members = net->ops[i].comates;
+    disband_colaunch(net, i);
+    for (int j : members) {
+        const NetOp& m = net->ops[(size_t)j];
+        if (m.kind != OP_CONV) continue;
+        cadnn_status st = conv2d_prepare_impl(eff_w(net, m), m.xd, m.in.n, m.stride, m.pad, out_s2d(m), nullptr);
+        if (st != CADNN_OK) return st;
+    }
+    return CADNN_OK;
 }
 
 cadnn_status launch_one(cadnn_net* net, size_t i, const void* x, void* y, hipStream_t s) {
@@ -981,6 +996,11 @@ extern "C" cadnn_status cadnn_net_finalize(cadnn_net* net, void* ws, size_t byte
         if (net->ops[i].comates.empty()) continue;
         cadnn_status st = set_colaunch_variant(net, i, nullptr);
         if (st != CADNN_OK) return st;
+        // members of very different shapes (many pixel tiles x few rows beside few tiles x many
+        // rows) would share a grid made mostly of workgroups that leave at once: not worth it
+        const CoLaunch& c = *net->colaunch[(int)i];
+        const int64_t grid = (int64_t)c.tiles_x * c.row_groups * c.layers;
+        if (grid > 4096 && grid > 8 * c.used_blocks && (st = take_apart(net, i)) != CADNN_OK) return st;
     }
     net->use_graph = (flags & CADNN_NET_GRAPH) != 0;
     net->want_tune = (flags & CADNN_NET_TUNE) != 0;
@@ -1132,15 +1152,7 @@ extern "C" cadnn_status cadnn_net_set_op_variant(cadnn_net* net, int op_index, c
         // the group's layers one launch each from now on (what tuning does to a group that loses)
         drop_graph(net);
         CADNN_HIP(hipDeviceSynchronize());
-        const std::vector<int> members = op.comates;
-        disband_colaunch(net, (size_t)op_index);
-        for (int j : members) {
-            const NetOp& m = net->ops[(size_t)j];
-            if (m.kind != OP_CONV) continue;
-            cadnn_status st = conv2d_prepare_impl(eff_w(net, m), m.xd, m.in.n, m.stride, m.pad, out_s2d(m), nullptr);
-            if (st != CADNN_OK) return st;
-        }
-        return CADNN_OK;
+        return take_apart(net, (size_t)op_index);
     }
     if (!op.comates.empty()) {
         const ConvVariant* v = nullptr;
