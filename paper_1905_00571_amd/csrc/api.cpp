@@ -381,9 +381,10 @@ cadnn_status conv2d_group_records(const std::vector<ConvMember>& members, int n,
             ConvLaunch a{};
             a.x = m.x; a.y = m.y; a.xd = m.xd; a.yd = m.yd; a.n = n; a.stride = m.stride; a.pad = m.pad;
             a.op_type = m.pool_kind; a.pool_k = m.pool_k;
-            // one thread per output element of an image, the workgroups spread over a (<= 8) x rows grid
+            // the output elements of an image dealt round robin to the threads of at most 256
+            // workgroups (one per compute unit), spread over a (<= 8) x rows grid
             const int64_t threads = (int64_t)v->nw * 64;
-            const int64_t blocks = ((int64_t)m.yd.c * m.yd.h * m.yd.w + threads - 1) / threads;
+            const int64_t blocks = std::min<int64_t>(((int64_t)m.yd.c * m.yd.h * m.yd.w + threads - 1) / threads, 256);
             a.tiles_x = (int)std::min<int64_t>(blocks, 8);
             a.tiles_y = 1;
             if ((blocks + a.tiles_x - 1) / a.tiles_x > 65535) return fail(CADNN_EUNSUPPORTED, "cadnn_net: pool too large to ride along");

@@ -520,8 +520,8 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_linear_multi_kernel(const 
     if (a.op_type != 0) {
         // a window pool riding along (a module's pooled branch): one output element per thread
         using T = typename Cfg::T;
-        const size_t r = ((size_t)blockIdx.y * a.tiles_x + blockIdx.x) * Cfg::THREADS + threadIdx.x;
-        if (r < (size_t)a.yd.c * a.yd.h * a.yd.w)
+        const size_t elems = (size_t)a.yd.c * a.yd.h * a.yd.w, step = (size_t)a.tiles_x * a.row_groups * Cfg::THREADS;
+        for (size_t r = ((size_t)blockIdx.y * a.tiles_x + blockIdx.x) * Cfg::THREADS + threadIdx.x; r < elems; r += step)
             windowpool_element<T>((const T*)a.x, (T*)a.y, a.xd, a.yd, n, r, a.pool_k, a.stride, a.pad, a.op_type == 2);
         return;
     }

@@ -246,8 +246,8 @@ struct ConvLaunch {
     uint32_t image_bytes;     // xd.image * sizeof(element)
     // launches of several layers (launch_multi) may carry window pools among them: 0 = a
     // convolution, 1 = a k x k maximum pool, 2 = a k x k mean pool (x, y, xd, yd, stride, pad
-    // as for a layer; one thread per output element, workgroup by * tiles_x + bx takes the
-    // next blockDim.x elements of image n)
+    // as for a layer; the output elements of image n are dealt round robin to the threads of
+    // the tiles_x * row_groups workgroups)
     int op_type, pool_k;
 };
 
