@@ -462,12 +462,6 @@ cadnn_status conv2d_group_tune(const std::vector<ConvMember>& members, int n, hi
     return CADNN_OK;
 }
 
-const ConvVariant* conv2d_variant_by_name(const char* name) {
-    if (!name) return nullptr;
-    for (const ConvVariant& v : all_linear_variants()) if (std::strcmp(v.name, name) == 0) return &v;
-    return nullptr;
-}
-
 static cadnn_status check_io(const char* who, const cadnn_weights* w, const ConvGeom& g, const void* x,
                              void* y, const TensorDesc& yd, const void* residual, const TensorDesc& rd) {
     if (!x || !y) return fail(CADNN_EINVAL, "%s: NULL tensor", who);

@@ -430,7 +430,6 @@ cadnn_status conv2d_group_records(const std::vector<ConvMember>& members, int n,
 cadnn_status conv2d_group_tune(const std::vector<ConvMember>& members, int n, hipStream_t s, int reps,
                                const std::function<cadnn_status()>* before, const ConvVariant** best_v,
                                float* best_us);
-const ConvVariant* conv2d_variant_by_name(const char* name);
 // Name of the variant that would serve the layer (NULL if none).
 // `out_s2d`: the layer's output or residual is in the de-interleaved layout.
 const char* conv2d_variant_name_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad,
