@@ -209,3 +209,71 @@ def test_inception_independent_layers_share_a_launch():
         assert not any(i["launched_with"] for i in inf)
     plain, _ = plan(ops, (1, 3, 299, 299), "iv3", fuse=False)
     assert not any(i["launched_with"] or i["launched_after"] >= 0 for i in plain)
+
+
+def test_random_net_layouts_keep_their_invariants():
+    """Host-only properties of the layout of 150 seeded random op graphs (the generator of the
+    GPU parity test), with every combination of the layout flags: materialised regions do not
+    overlap and lie inside the workspace; a slice lies inside the region it belongs to; an op
+    that rides on another op's launch does so on an EARLIER op that really launches, and
+    everything it reads is complete by then; an op moved in the launch order goes behind an op
+    that launches."""
+    import importlib.util
+    import os
+    spec = importlib.util.spec_from_file_location("random_nets", os.path.join(os.path.dirname(__file__), "test_gpu_random_nets.py"))
+    rnd = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(rnd)
+    seen = {"launched_with": 0, "launched_after": 0, "slices": 0}
+    for seed in range(150):
+        ops, shape = rnd.random_net(seed)
+        _, ws, _ = wl.net_tensors(ops, f"rnd{seed}", shape)
+        n = shape[0]
+        for kw in ({}, {"fuse": False}, {"plain_layout": True}):
+            infos, nbytes = cad.plan_net(ops, ws, shape, **kw)
+
+            def ready(k):
+                nxt = infos[k]["launched_after"] if infos[k]["launched_after"] >= 0 else infos[k]["fused_into"]
+                return ready(nxt) if 0 <= nxt < k else k     # (a projection is fused into a LATER op: not a launch it rides on)
+
+            producer = {0: -1}
+            spans = []
+            for k, (o, i) in enumerate(zip(ops, infos)):
+                srcs = list(o.srcs) if o.kind == "concat" else [o.src]
+                if o.kind == "conv" and o.res >= 0:
+                    srcs.append(o.res)
+                seen["launched_with"] += i["launched_with"]
+                seen["launched_after"] += i["launched_after"] >= 0
+                seen["slices"] += i["slice_of"] >= 0
+                if i["launched_with"]:
+                    lead = i["fused_into"]
+                    assert 0 <= lead < k and infos[lead]["fused_into"] < 0 and ops[lead].kind == "conv", (seed, kw, o.name)
+                    assert all(producer[b] >= 0 and ready(producer[b]) < lead for b in srcs), (seed, kw, o.name)
+                if i["launched_after"] >= 0:
+                    host = i["launched_after"]
+                    assert host < k and infos[host]["fused_into"] < 0 and infos[host]["launched_after"] < 0, (seed, kw, o.name)
+                    assert all(producer[b] >= 0 and ready(producer[b]) <= host for b in srcs), (seed, kw, o.name)
+                producer[o.dst] = k
+                if k == len(ops) - 1:
+                    continue
+                start = i["offset"] - (0 if i["deinterleaved"] else (i["halo_h"] * i["pitch"] + i["halo_w"]) * 4)
+                spans.append((k, start, i))
+            shapes = wl.buffer_shapes(ops, shape)
+            regions = []
+            for k, start, i in spans:
+                o = ops[k]
+                c = shapes[o.dst][1]
+                end = start + ((n - 1) * i["image"] + c * i["plane"]) * 4
+                assert 0 <= start and end <= nbytes, (seed, kw, o.name)
+                sibling = o.kind == "conv" and i["fused_into"] >= 0 and not i["launched_with"] and i["fused_into"] < k
+                never_written = i["fused_into"] > k       # a projection computed inside the layer that adds it
+                if i["slice_of"] >= 0 or sibling:
+                    host = i["slice_of"] if i["slice_of"] >= 0 else i["fused_into"]
+                    hs = next(s for kk, s, _ in spans if kk == host)
+                    hi = infos[host]
+                    assert hs <= start and end <= hs + n * hi["image"] * 4, (seed, kw, o.name)
+                elif not never_written:
+                    regions.append((start, start + n * i["image"] * 4, o.name))
+            regions.sort()
+            for (a0, a1, an), (b0, b1, bn) in zip(regions, regions[1:]):
+                assert a1 <= b0, (seed, kw, an, bn)
+    assert min(seen.values()) >= 20, seen         # the nets do contain what is being checked
