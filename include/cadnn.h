@@ -254,9 +254,7 @@ cadnn_status cadnn_net_workspace_bytes(const cadnn_net* net, size_t* bytes);
  * kernel over a table of launch records, while one variant serves them all: they report
  * fused_into = that op and launched_with = 1, the op's variant name is the group's, and
  * cadnn_net_op_candidates / cadnn_net_set_op_variant on it list / pin variants for the whole
- * group.  cadnn_net_finalize takes a group apart whose shared grid would be mostly empty
- * (members of very different shapes), and tuning (CADNN_NET_TUNE) keeps a group only if it
- * beats its layers launched apart.
+ * group.  Tuning (CADNN_NET_TUNE) keeps a group only if it beats its layers launched apart.
  * Window pools move up in the launch order to where their input completes (launched_after). */
 #define CADNN_NET_GRAPH 1
 #define CADNN_NET_TUNE 2

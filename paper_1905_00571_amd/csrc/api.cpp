@@ -346,16 +346,9 @@ cadnn_status conv2d_group_candidates(const std::vector<ConvMember>& members, int
         }
         if (all && any) out->push_back(&v);
     }
-    // untuned pick: the layers run side by side, so the slowest of them decides.  (With a pool
-    // riding along only one-pixel-per-lane variants are picked without tuning: measured on a
-    // 768-channel 17x17 module, the pool adds about 3 us to those and 9-12 us to the wider
-    // ones, against 3.8 us for a launch of its own.)
-    bool has_pool = false, has_narrow = false;
-    for (const ConvMember& m : members) has_pool = has_pool || m.pool_kind != 0;
-    for (const ConvVariant* v : *out) has_narrow = has_narrow || v->p == 1;
+    // untuned pick: the layers run side by side, so the slowest of them decides
     double best = 0.0;
     for (const ConvVariant* v : *out) {
-        if (has_pool && has_narrow && v->p != 1) continue;
         double worst = 0.0;
         for (size_t k = 0; k < members.size(); ++k)
             if (members[k].pool_kind == 0) worst = std::max(worst, variant_cost(members[k].w, geoms[k], v));
@@ -365,12 +358,11 @@ cadnn_status conv2d_group_candidates(const std::vector<ConvMember>& members, int
 }
 
 cadnn_status conv2d_group_records(const std::vector<ConvMember>& members, int n, const ConvVariant* v,
-                                  std::vector<ConvLaunch>* records, int* tiles_x, int* row_groups,
-                                  std::vector<std::shared_ptr<ConvPlan>>* keep) {
+                                  std::vector<ConvLaunch>* records, std::vector<std::shared_ptr<ConvPlan>>* keep) {
     records->resize(members.size());
     if (keep) keep->assign(members.size(), nullptr);
-    *tiles_x = 0;
-    *row_groups = 0;
+    if (members.size() > (size_t)kMaxCoLaunch) return fail(CADNN_EINVAL, "cadnn_net: more than %d layers in one launch", kMaxCoLaunch);
+    int64_t total = 0;
     if (!v || !v->launch_multi) return fail(CADNN_EINVAL, "cadnn_net: variant cannot launch several layers");
     for (size_t k = 0; k < members.size(); ++k) {
         const ConvMember& m = members[k];
@@ -382,25 +374,21 @@ cadnn_status conv2d_group_records(const std::vector<ConvMember>& members, int n,
             a.x = m.x; a.y = m.y; a.xd = m.xd; a.yd = m.yd; a.n = n; a.stride = m.stride; a.pad = m.pad;
             a.op_type = m.pool_kind; a.pool_k = m.pool_k;
             // the output elements of an image dealt round robin to the threads of at most 256
-            // workgroups (one per compute unit), spread over a (<= 8) x rows grid
+            // workgroups (one per compute unit)
             const int64_t threads = (int64_t)v->nw * 64;
-            const int64_t blocks = std::min<int64_t>(((int64_t)m.yd.c * m.yd.h * m.yd.w + threads - 1) / threads, 256);
-            a.tiles_x = (int)std::min<int64_t>(blocks, 8);
+            a.tiles_x = 1;
             a.tiles_y = 1;
-            if ((blocks + a.tiles_x - 1) / a.tiles_x > 65535) return fail(CADNN_EUNSUPPORTED, "cadnn_net: pool too large to ride along");
-            a.row_groups = (int)((blocks + a.tiles_x - 1) / a.tiles_x);
+            a.row_groups = (int)std::min<int64_t>(((int64_t)m.yd.c * m.yd.h * m.yd.w + threads - 1) / threads, 256);
             (*records)[k] = a;
-            *tiles_x = std::max(*tiles_x, a.tiles_x);
-            *row_groups = std::max(*row_groups, a.row_groups);
+            total += (int64_t)a.tiles_x * a.row_groups;
             continue;
         }
         if (!variant_fits(*v, m.w, g)) return fail(CADNN_EINVAL, "cadnn_net: '%s' does not serve every co-launched layer", v->name);
         if ((st = make_launch(m.w, v, g, m.x, m.y, m.yd, m.residual, m.rd, m.bias, m.relu, &(*records)[k],
                               keep ? &(*keep)[k] : nullptr)) != CADNN_OK) return st;
-        *tiles_x = std::max(*tiles_x, (*records)[k].tiles_x);
-        *row_groups = std::max(*row_groups, (*records)[k].row_groups);
+        total += (int64_t)(*records)[k].tiles_x * (*records)[k].row_groups;
     }
-    if ((int64_t)members.size() * n > 65535 || *row_groups > 65535)
+    if (n > 65535 || total > 0x7fffffffll)
         return fail(CADNN_EUNSUPPORTED, "cadnn_net: co-launched layers exceed the grid limits");
     return CADNN_OK;
 }
@@ -430,19 +418,18 @@ cadnn_status conv2d_group_tune(const std::vector<ConvMember>& members, int n, hi
     float best_ms = 0.0f;
     std::vector<ConvLaunch> recs;
     for (const ConvVariant* v : cand) {
-        int tx = 0, rg = 0;
-        if (conv2d_group_records(members, n, v, &recs, &tx, &rg) != CADNN_OK) continue;   // does not fit these weights
+        if (conv2d_group_records(members, n, v, &recs) != CADNN_OK) continue;   // does not fit these weights
         DevBuf table;
         if ((st = table.upload(recs.data(), recs.size() * sizeof(ConvLaunch))) != CADNN_OK) break;
         const ConvLaunch* tab = (const ConvLaunch*)table.p;
-        if (v->launch_multi(tab, (int)recs.size(), tx, rg, n, s) != hipSuccess) { st = fail(CADNN_EHIP, "co-launch failed"); break; }
+        if (v->launch_multi(tab, recs.data(), (int)recs.size(), n, s) != hipSuccess) { st = fail(CADNN_EHIP, "co-launch failed"); break; }
         float total_ms = 0.0f;
         for (int i = 0; i < reps && st == CADNN_OK; ++i) {
             st = launch_copy(sweep.p, (char*)sweep.p + sweep_bytes, sweep_bytes, s);
             if (st != CADNN_OK) break;
             if (before && (st = (*before)()) != CADNN_OK) break;
             if (hipEventRecord(e0, s) != hipSuccess) { st = fail(CADNN_EHIP, "hipEventRecord failed"); break; }
-            if (v->launch_multi(tab, (int)recs.size(), tx, rg, n, s) != hipSuccess) { st = fail(CADNN_EHIP, "co-launch failed"); break; }
+            if (v->launch_multi(tab, recs.data(), (int)recs.size(), n, s) != hipSuccess) { st = fail(CADNN_EHIP, "co-launch failed"); break; }
             if (hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess) { st = fail(CADNN_EHIP, "event wait failed"); break; }
             float ms = 0.0f;
             if (hipEventElapsedTime(&ms, e0, e1) != hipSuccess) { st = fail(CADNN_EHIP, "hipEventElapsedTime failed"); break; }

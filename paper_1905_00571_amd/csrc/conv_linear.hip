@@ -508,24 +508,38 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_linear_kernel(const ConvLa
 }
 
 // Several independent layers in one launch (the branches of an Inception module at the same
-// depth): blockIdx.z counts (layer, image), the layer's launch record is read from a table in
-// device memory -- a wave-uniform address, so it arrives through the scalar cache like the
-// kernel arguments would -- and workgroups beyond a smaller layer's own grid leave at once.
+// depth).  blockIdx.x runs over the workgroups of all layers, layer after layer -- first[k] is
+// the first workgroup of layer k, first[layers] the total, at most kMaxCoLaunch layers --
+// and blockIdx.y is the image, so no workgroup is launched in vain (a common bounding grid
+// was measured first: 5000 workgroups outside their layer's own grid cost a 17x17 module 8 us).
+// The layer's launch record is read from a table in device memory: a wave-uniform address,
+// so it arrives through the scalar cache like the kernel arguments would.
+struct CoLaunchHeader {
+    int first[kMaxCoLaunch + 1];
+};
+
 template <class Cfg>
-__global__ __launch_bounds__(Cfg::THREADS) void sconv_linear_multi_kernel(const ConvLaunch* __restrict__ table, const int images) {
-    const int layer = (int)blockIdx.z / images;
+__global__ __launch_bounds__(Cfg::THREADS) void sconv_linear_multi_kernel(const ConvLaunch* __restrict__ table,
+                                                                         const CoLaunchHeader h, const int layers) {
+    const int b = (int)blockIdx.x;
+    int layer = 0, base = 0;
+#pragma unroll
+    for (int k = 1; k < kMaxCoLaunch; ++k)
+        if (k < layers && b >= h.first[k]) { layer = k; base = h.first[k]; }
     const ConvLaunch a = table[layer];
-    if ((int)blockIdx.x >= a.tiles_x || (int)blockIdx.y >= a.row_groups) return;
-    const int n = (int)blockIdx.z - layer * images;
+    const int local = b - base;
+    const int by = local / a.tiles_x, bx = local - by * a.tiles_x;
+    const int n = (int)blockIdx.y;
     if (a.op_type != 0) {
-        // a window pool riding along (a module's pooled branch): one output element per thread
+        // a window pool riding along (a module's pooled branch): its output elements dealt
+        // round robin to the threads of its workgroups
         using T = typename Cfg::T;
         const size_t elems = (size_t)a.yd.c * a.yd.h * a.yd.w, step = (size_t)a.tiles_x * a.row_groups * Cfg::THREADS;
-        for (size_t r = ((size_t)blockIdx.y * a.tiles_x + blockIdx.x) * Cfg::THREADS + threadIdx.x; r < elems; r += step)
+        for (size_t r = (size_t)local * Cfg::THREADS + threadIdx.x; r < elems; r += step)
             windowpool_element<T>((const T*)a.x, (T*)a.y, a.xd, a.yd, n, r, a.pool_k, a.stride, a.pad, a.op_type == 2);
         return;
     }
-    sconv_linear_block<Cfg>(a, (int)blockIdx.x, (int)blockIdx.y, n);
+    sconv_linear_block<Cfg>(a, bx, by, n);
 }
 
 template <class Cfg>
@@ -537,11 +551,18 @@ static hipError_t launch_linear(const ConvLaunch& a, hipStream_t s) {
 }
 
 template <class Cfg>
-static hipError_t launch_linear_multi(const ConvLaunch* table, int layers, int tiles_x, int row_groups, int images,
+static hipError_t launch_linear_multi(const ConvLaunch* table, const ConvLaunch* host_records, int layers, int images,
                                       hipStream_t s) {
-    dim3 grid((unsigned)tiles_x, (unsigned)row_groups, (unsigned)(layers * images));
+    CoLaunchHeader h{};
+    int total = 0;
+    for (int k = 0; k < layers; ++k) {
+        h.first[k] = total;
+        total += host_records[k].tiles_x * host_records[k].row_groups;
+    }
+    for (int k = layers; k <= kMaxCoLaunch; ++k) h.first[k] = total;
+    dim3 grid((unsigned)total, (unsigned)images, 1);
     dim3 block(Cfg::THREADS);
-    hipLaunchKernelGGL(sconv_linear_multi_kernel<Cfg>, grid, block, 0, s, table, images);
+    hipLaunchKernelGGL(sconv_linear_multi_kernel<Cfg>, grid, block, 0, s, table, h, layers);
     return hipGetLastError();
 }
 

@@ -174,6 +174,7 @@ __device__ __forceinline__ void windowpool_element(const T* __restrict__ x, T* _
 enum ConvFamily { FAM_TILE = 0, FAM_DIRECT = 1, FAM_LINEAR = 2, FAM_DENSE = 3, FAM_STILE = 4, FAM_PTILE = 5 };
 
 struct ConvLaunch;
+constexpr int kMaxCoLaunch = 8;   // layers (and riding pools) one launch can hold
 
 struct ConvVariant {
     const char* name;
@@ -201,9 +202,10 @@ struct ConvVariant {
     int nz_cap;           // FAM_STILE: most stream entries per (row group, chunk) the kernel buffers
     size_t lds_bytes;
     hipError_t (*launch)(const ConvLaunch&, hipStream_t);
-    // several layers at once from a device table of launch records (NULL: not offered);
-    // the grid is the largest tiles_x / row_groups among them
-    hipError_t (*launch_multi)(const ConvLaunch* table_dev, int layers, int tiles_x, int row_groups, int images, hipStream_t);
+    // several layers (at most kMaxCoLaunch) at once from a device table of launch records, of
+    // which host_records is the host copy (NULL: not offered)
+    hipError_t (*launch_multi)(const ConvLaunch* table_dev, const ConvLaunch* host_records, int layers, int images,
+                               hipStream_t);
     int rows_per_block() const { return family == FAM_TILE || family == FAM_DENSE ? nw * rpw : (nw / ks) * rpw; }
 };
 
@@ -421,10 +423,10 @@ struct ConvMember {
 // untuned pick among them.
 cadnn_status conv2d_group_candidates(const std::vector<ConvMember>& members, int n,
                                      std::vector<const ConvVariant*>* out, const ConvVariant** pick);
-// The members' launch records for variant v (plans are built on first use) and the grid
-// that covers the largest of them; `keep` receives the plans the records point into.
+// The members' launch records for variant v (plans are built on first use); `keep` receives
+// the plans the records point into.
 cadnn_status conv2d_group_records(const std::vector<ConvMember>& members, int n, const ConvVariant* v,
-                                  std::vector<ConvLaunch>* records, int* tiles_x, int* row_groups,
+                                  std::vector<ConvLaunch>* records,
                                   std::vector<std::shared_ptr<ConvPlan>>* keep = nullptr);
 // Times every such variant on the members' own buffers; *best_v stays NULL if none serves them.
 cadnn_status conv2d_group_tune(const std::vector<ConvMember>& members, int n, hipStream_t s, int reps,

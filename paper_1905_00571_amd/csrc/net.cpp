@@ -64,15 +64,13 @@ struct NetOp {
     std::vector<int> hoisted;
 };
 
-// The one kernel of a group of co-launched layers: the variant that serves them all, the
-// members' launch records in device memory (with the plans they point into) and the grid
-// that covers the largest member.
+// The one kernel of a group of co-launched layers: the variant that serves them all and the
+// members' launch records in device memory (with the plans they point into).
 struct CoLaunch {
     const ConvVariant* v = nullptr;
     DevBuf table;
     std::vector<std::shared_ptr<ConvPlan>> plans;
-    int layers = 0, tiles_x = 0, row_groups = 0;
-    int64_t used_blocks = 0;      // workgroups inside some member's own grid (the others leave at once)
+    std::vector<ConvLaunch> records;   // host copy of the table (the launch derives the grid from it)
 };
 
 // Weights, bias and output layout an op is launched with: its own, or -- first op of a sibling
@@ -459,7 +457,7 @@ struct Layout {
                 if (!solo(i)) continue;
                 std::vector<const ConvVariant*> common = multi_of(i), narrowed;
                 // (partners are looked for among the next 64 ops: a module's branches lie close together)
-                for (int j = i + 1; j < std::min(nops, i + 65) && net->ops[i].comates.size() < 7 && !common.empty(); ++j) {
+                for (int j = i + 1; j < std::min(nops, i + 65) && net->ops[i].comates.size() < (size_t)kMaxCoLaunch - 1 && !common.empty(); ++j) {
                     NetOp& b = net->ops[j];
                     if (solo_pool(j) && ready_at(b.src_inst) < i) {
                         b.hoisted_to = -1;
@@ -592,13 +590,10 @@ cadnn_status set_colaunch_variant(cadnn_net* net, size_t i, const ConvVariant* v
         if (!v) return fail(CADNN_EUNSUPPORTED, "cadnn_net: no kernel variant serves the layers launched with op %zu", i);
     }
     std::unique_ptr<CoLaunch> c(new CoLaunch());
-    std::vector<ConvLaunch> records;
-    cadnn_status st = conv2d_group_records(members, n, v, &records, &c->tiles_x, &c->row_groups, &c->plans);
+    cadnn_status st = conv2d_group_records(members, n, v, &c->records, &c->plans);
     if (st != CADNN_OK) return st;
-    if ((st = c->table.upload(records.data(), records.size() * sizeof(ConvLaunch))) != CADNN_OK) return st;
+    if ((st = c->table.upload(c->records.data(), c->records.size() * sizeof(ConvLaunch))) != CADNN_OK) return st;
     c->v = v;
-    c->layers = (int)records.size();
-    for (const ConvLaunch& r : records) c->used_blocks += (int64_t)r.tiles_x * r.row_groups;
     net->colaunch[(int)i] = std::move(c);
     return CADNN_OK;
 }
@@ -638,7 +633,7 @@ cadnn_status launch_one(cadnn_net* net, size_t i, const void* x, void* y, hipStr
         auto it = net->colaunch.find((int)i);
         if (it == net->colaunch.end()) return fail(CADNN_EINVAL, "cadnn_net: co-launch table of op %zu is missing", i);
         const CoLaunch& c = *it->second;
-        CADNN_HIP(c.v->launch_multi((const ConvLaunch*)c.table.p, c.layers, c.tiles_x, c.row_groups, op.in.n, s));
+        CADNN_HIP(c.v->launch_multi((const ConvLaunch*)c.table.p, c.records.data(), (int)c.records.size(), op.in.n, s));
         return CADNN_OK;
     }
     const void* src = in_ptr(net, op.src_inst, x);
@@ -996,11 +991,6 @@ extern "C" cadnn_status cadnn_net_finalize(cadnn_net* net, void* ws, size_t byte
         if (net->ops[i].comates.empty()) continue;
         cadnn_status st = set_colaunch_variant(net, i, nullptr);
         if (st != CADNN_OK) return st;
-        // members of very different shapes (many pixel tiles x few rows beside few tiles x many
-        // rows) would share a grid made mostly of workgroups that leave at once: not worth it
-        const CoLaunch& c = *net->colaunch[(int)i];
-        const int64_t grid = (int64_t)c.tiles_x * c.row_groups * c.layers;
-        if (grid > 4096 && grid > 8 * c.used_blocks && (st = take_apart(net, i)) != CADNN_OK) return st;
     }
     net->use_graph = (flags & CADNN_NET_GRAPH) != 0;
     net->want_tune = (flags & CADNN_NET_TUNE) != 0;
