@@ -237,7 +237,9 @@ cadnn_status cadnn_net_workspace_bytes(const cadnn_net* net, size_t* bytes);
  * as they will be (that first call synchronises and takes a fraction of a second);
  * CADNN_NET_PLAIN_LAYOUT -- keep every intermediate tensor in plain (haloed) NCHW; by
  * default the output of a convolution that is read by stride-2 convolutions is kept
- * de-interleaved by row/column parity, so those layers read it with unit stride;
+ * de-interleaved by row/column parity, so those layers read it with unit stride (and a
+ * large stride-2 layer whose input cannot be kept that way reads a de-interleaved copy made
+ * right before it: cadnn_op_info.input_copy);
  * CADNN_NET_NO_FUSION -- launch every op on its own; by default a 1x1 projection shortcut
  * whose only reader adds it as residual is computed inside that reader, and a global
  * average pool that is the only reader of a small-image convolution is computed in that
@@ -285,6 +287,10 @@ typedef struct {
                                 place in the op list: a window pool moved up to where its
                                 input completes (so that its reader can share an earlier
                                 launch), or a member of a group that tuning took apart */
+    int64_t input_copy;      /* >= 0: a large stride-2 layer (filter wider than 1x1) whose input is
+                                not de-interleaved where it is produced reads a de-interleaved
+                                copy of it, made right before the layer at this byte offset of
+                                the workspace (not with CADNN_NET_PLAIN_LAYOUT) */
 } cadnn_op_info;
 cadnn_status cadnn_net_op_info(cadnn_net* net, int op_index, int flags, cadnn_op_info* out);
 cadnn_status cadnn_run_net(cadnn_net* net, const void* x, void* y, void* stream);

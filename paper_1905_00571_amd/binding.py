@@ -34,7 +34,8 @@ class OpInfo(ctypes.Structure):
     _fields_ = [("halo_h", ctypes.c_int), ("halo_w", ctypes.c_int), ("pitch", ctypes.c_int),
                 ("plane", ctypes.c_int64), ("image", ctypes.c_int64), ("deinterleaved", ctypes.c_int),
                 ("offset", ctypes.c_int64), ("fused_into", ctypes.c_int), ("slice_of", ctypes.c_int),
-                ("slice_channel", ctypes.c_int), ("launched_with", ctypes.c_int), ("launched_after", ctypes.c_int)]
+                ("slice_channel", ctypes.c_int), ("launched_with", ctypes.c_int), ("launched_after", ctypes.c_int),
+                ("input_copy", ctypes.c_int64)]
 
 
 def lib_path() -> str:

@@ -140,7 +140,8 @@ __device__ __forceinline__ void windowpool_element(const T* __restrict__ x, T* _
         }
     }
     if (mean && seen) m /= (float)seen;
-    y[(size_t)img * yd.image + (size_t)c * yd.plane + yd.origin + (size_t)oh * yd.pitch + ow] = (T)m;
+    // (tensor_off: the output may be a de-interleaved tensor -- a k = 1 pool is how one is made from a plain one)
+    y[(size_t)img * yd.image + (size_t)c * yd.plane + tensor_off(yd, oh, ow)] = (T)m;
 }
 
 // ---- convolution kernel variants ------------------------------------------------

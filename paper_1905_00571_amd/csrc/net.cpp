@@ -62,6 +62,13 @@ struct NetOp {
     // a group that tuning disbanded stay behind its first op the same way.
     int hoisted_to = -1;
     std::vector<int> hoisted;
+    // A large stride-2 layer with a filter wider than 1x1 whose input could not be kept
+    // de-interleaved where it is produced (odd sizes, other readers, a concatenation) reads a
+    // de-interleaved copy made right before it: xd describes the copy at x_off, src_d the
+    // tensor it is made from.
+    bool restaged = false;
+    size_t x_off = 0;
+    TensorDesc src_d;
 };
 
 // The one kernel of a group of co-launched layers: the variant that serves them all and the
@@ -334,6 +341,21 @@ struct Layout {
             else
                 op.rd = op.yd;
         }
+        // De-interleaved copies: a stride-2 lane pattern on a plain tensor touches twice the
+        // cache lines per load, which is what bounds a big layer (Inception-V3's 288 -> 384
+        // 3x3/2 on 35 x 35: 35 us); a copy costs one small launch.
+        for (NetOp& op : net->ops) {
+            op.restaged = false;
+            if (!net->allow_s2d || op.kind != OP_CONV || op.stride != 2 || (op.w->kh == 1 && op.w->kw == 1) || op.src_inst < 0 ||
+                op.xd.s2d || !sparse_enough(op) || (double)op.w->nnz * op.out.h * op.out.w < 4e7 ||
+                !tensor_fits(net, op.in, op.pad + 1))
+                continue;
+            op.restaged = true;
+            op.src_d = op.xd;
+            op.xd = make_desc_s2d(op.in.c, op.in.h, op.in.w, op.pad, op.pad);
+            op.x_off = off;
+            off += ((size_t)op.in.n * op.xd.image * net->elem() + 255) / 256 * 256;
+        }
     }
 
     void fuse() {
@@ -438,7 +460,7 @@ struct Layout {
             auto solo = [&](int k) {
                 const NetOp& o = net->ops[k];
                 return o.kind == OP_CONV && o.fused_into < 0 && o.shortcut < 0 && o.pool_op < 0 && o.dw_op < 0 &&
-                       o.colaunch_of < 0 && o.comates.empty() && sparse_enough(o) && !o.yd.s2d && !o.xd.s2d &&
+                       o.colaunch_of < 0 && o.comates.empty() && sparse_enough(o) && !o.yd.s2d && !(o.xd.s2d && !o.restaged) &&
                        !(o.res >= 0 && o.rd.s2d) && o.src_inst >= 0 && k != nops - 1 && (o.res < 0 || o.res_inst >= 0);
             };
             // the variants that can launch op k among several layers (sorted; listed once per op)
@@ -569,7 +591,7 @@ std::vector<ConvMember> colaunch_members(const cadnn_net* net, size_t i) {
             continue;
         }
         m.w = eff_w(net, o);
-        m.x = net->ws + net->ops[o.src_inst].y_off; m.xd = o.xd;
+        m.x = o.restaged ? net->ws + o.x_off : net->ws + net->ops[o.src_inst].y_off; m.xd = o.xd;
         m.y = net->ws + o.y_off; m.yd = launch_yd(o);
         m.residual = o.res >= 0 ? net->ws + net->ops[o.res_inst].y_off : nullptr; m.rd = o.rd;
         m.stride = o.stride; m.pad = o.pad; m.bias = eff_bias(net, o); m.relu = o.relu;
@@ -626,9 +648,18 @@ cadnn_status take_apart(cadnn_net* net, size_t i) {
     return CADNN_OK;
 }
 
+// The de-interleaved copy a restaged layer reads (a k = 1 pool from the source's layout).
+cadnn_status restage_input(cadnn_net* net, const NetOp& op, const void* x, hipStream_t s) {
+    if (!op.restaged) return CADNN_OK;
+    return launch_maxpool(in_ptr(net, op.src_inst, x), op.src_d, net->ws + op.x_off, op.xd, op.in.n, 1, 1, 0, net->dtype, s);
+}
+
 cadnn_status launch_one(cadnn_net* net, size_t i, const void* x, void* y, hipStream_t s) {
     const NetOp& op = net->ops[i];
     if (op.fused_into >= 0) return CADNN_OK;     // computed inside (or launched with) another op
+    cadnn_status rs = restage_input(net, op, x, s);
+    for (size_t k = 0; k < op.comates.size() && rs == CADNN_OK; ++k) rs = restage_input(net, net->ops[(size_t)op.comates[k]], x, s);
+    if (rs != CADNN_OK) return rs;
     if (!op.comates.empty()) {
         auto it = net->colaunch.find((int)i);
         if (it == net->colaunch.end()) return fail(CADNN_EINVAL, "cadnn_net: co-launch table of op %zu is missing", i);
@@ -636,7 +667,7 @@ cadnn_status launch_one(cadnn_net* net, size_t i, const void* x, void* y, hipStr
         CADNN_HIP(c.v->launch_multi((const ConvLaunch*)c.table.p, c.records.data(), (int)c.records.size(), op.in.n, s));
         return CADNN_OK;
     }
-    const void* src = in_ptr(net, op.src_inst, x);
+    const void* src = op.restaged ? (const void*)(net->ws + op.x_off) : in_ptr(net, op.src_inst, x);
     void* dst = out_ptr(net, i, y);
     ConvExtra ex;
     const bool fused = shortcut_of(net, op, x, &ex, y);
@@ -709,7 +740,8 @@ cadnn_status tune_net(cadnn_net* net, const void* x, void* y, hipStream_t s) {
         };
         ConvExtra ex;
         const bool fused = shortcut_of(net, op, x, &ex, y);
-        st = conv2d_tune_impl(eff_w(net, op), in_ptr(net, op.src_inst, x), op.xd, out_ptr(net, i, y), launch_yd(op),
+        st = conv2d_tune_impl(eff_w(net, op), op.restaged ? (const void*)(net->ws + op.x_off) : in_ptr(net, op.src_inst, x), op.xd,
+                              out_ptr(net, i, y), launch_yd(op),
                               (op.res >= 0 && op.shortcut < 0) ? in_ptr(net, op.res_inst, x) : nullptr, op.rd, op.in.n,
                               op.stride, op.pad, eff_bias(net, op), op.relu, s, 20, &alone_us[i], &producer,
                               fused ? &ex : nullptr);
@@ -943,6 +975,7 @@ extern "C" cadnn_status cadnn_net_op_info(cadnn_net* net, int op_index, int flag
     out->slice_channel = op.sibling_of >= 0 ? op.sib_ch : op.slice_ch;
     out->launched_with = op.colaunch_of >= 0 ? 1 : 0;
     out->launched_after = op.hoisted_to;
+    out->input_copy = op.restaged ? (int64_t)op.x_off : -1;
     return CADNN_OK;
 }
 

@@ -740,3 +740,45 @@ def test_group_taken_apart_keeps_the_launch_order(cad, dtype_name):
             torch.cuda.synchronize()
             assert_close(y.cpu().numpy(), ref, tol * (3 if f16 else 1), f"{step}")
     net.free()
+
+
+@pytest.mark.parametrize("dtype_name", ["f32", "f16"])
+def test_big_strided_layer_reads_a_deinterleaved_copy(cad, dtype_name):
+    """A large 3x3 stride-2 layer on an odd-sized tensor (Inception-V3's 288 -> 384 on 35 x 35)
+    cannot have its input de-interleaved where it is produced; the runner makes a de-interleaved
+    copy right before it.  Every variant that serves the layer there, on two inputs in a row,
+    and the same net in plain layout."""
+    f16 = dtype_name == "f16"
+    dtype, npdt, tol = (cad.F16, np.float16, TOL_F16) if f16 else (cad.F32, np.float32, TOL_F32)
+    Op = wl.Op
+    ops = [Op("conv", "pre", 0, 1, 8, 288, 1, 1, 0, 0.5, True),
+           Op("conv", "main", 1, 2, 288, 384, 3, 2, 0, 0.8, True),
+           Op("maxpool", "pool", 1, 3, k=3, stride=2, pad=0),            # a second reader of the same tensor
+           Op("concat", "cat", 2, 4, srcs=(2, 3)),
+           Op("conv", "post", 4, 5, 672, 6, 1, 1, 0, 0.8, False)]
+    shape = (2, 8, 35, 35)
+    x, ws, bs = wl.net_tensors(ops, "restage", shape, input_relu=True)
+    xs = x.astype(npdt)
+    xs2 = wl.activation(shape, "restage", 99, relu=True).astype(npdt)
+    refs = [oracle.run_net(ops, v, ws, bs, dtype=npdt) for v in (xs, xs2)]
+    net = cad.build_net(ops, ws, bs, shape, dtype, use_graph=True)
+    plain = cad.build_net(ops, ws, bs, shape, dtype, use_graph=True, plain_layout=True)
+    assert net.op_info(1)["input_copy"] >= 0 and plain.op_info(1)["input_copy"] == -1
+    assert all(net.op_info(i)["input_copy"] == -1 for i in (0, 2, 4))
+    names = net.op_candidates(1)
+    assert any("_a4_" in nm or "_g4_" in nm for nm in names) or f16, names     # unit-stride wide loads on the copy
+    for name in [None] + names:
+        net.set_op_variant(1, name)
+        for v, (ref, ins, outs) in ((xs, refs[0]), (xs2, refs[1])):
+            y = net.run(dev(v))
+            torch.cuda.synchronize()
+            cond = cond_conv(ins[1], ws[1].astype(npdt), bs[1], None, 2, 0)
+            got = net.read_buffer(2, outs[1].shape)
+            assert_layer_close(got, outs[1], cond + (2.0 ** -10 / 1e-4 * np.abs(outs[1]) if f16 else 0), tol,
+                               f"restaged {name}", f16=f16)
+            assert_close(y.cpu().numpy(), ref, tol * (3 if f16 else 1), f"restaged net {name}")
+    y = plain.run(dev(xs2))
+    torch.cuda.synchronize()
+    assert_close(y.cpu().numpy(), refs[1][0], tol * (3 if f16 else 1), "plain layout")
+    net.free()
+    plain.free()
