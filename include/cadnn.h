@@ -240,24 +240,27 @@ cadnn_status cadnn_net_workspace_bytes(const cadnn_net* net, size_t* bytes);
  * de-interleaved by row/column parity, so those layers read it with unit stride (and a
  * large stride-2 layer whose input cannot be kept that way reads a de-interleaved copy made
  * right before it: cadnn_op_info.input_copy);
- * CADNN_NET_NO_FUSION -- launch every op on its own; by default a 1x1 projection shortcut
- * whose only reader adds it as residual is computed inside that reader, and a global
- * average pool that is the only reader of a small-image convolution is computed in that
- * convolution's epilogue, and so is a 3x3 depthwise layer (padding 1, stride 1 or 2) that is
- * the only reader of a convolution with an image of at most 28 x 28 (the skipped op's
- * profile time is zero and its variant name is "fused"; the buffer that is no longer
- * written is refused by cadnn_net_read_buffer).  Also by default, 1x1 stride-1 sparse
- * convolutions with the same activation and no residual that read the same tensor are
- * launched as one layer over the rows of all of them: the later ones report fused_into =
- * the first one, variant "fused" and time zero, their outputs are channel slices of the
- * first one's region, from channel slice_channel on, and stay readable.  And sparse
- * convolutions on plain tensors whose inputs are all ready when an earlier one runs (the
- * branches of an Inception module at the same depth, up to eight) are launched with it as one
- * kernel over a table of launch records, while one variant serves them all: they report
- * fused_into = that op and launched_with = 1, the op's variant name is the group's, and
- * cadnn_net_op_candidates / cadnn_net_set_op_variant on it list / pin variants for the whole
- * group.  Tuning (CADNN_NET_TUNE) keeps a group only if it beats its layers launched apart.
- * Window pools move up in the launch order to where their input completes (launched_after). */
+ * CADNN_NET_NO_FUSION -- launch every op on its own, in op-list order.  By default:
+ *   - a 1x1 projection shortcut whose only reader adds it as residual is computed inside
+ *     that reader; a global average pool that is the only reader of a small-image
+ *     convolution is computed in that convolution's epilogue, and so is a 3x3 depthwise layer
+ *     (padding 1, stride 1 or 2) that is the only reader of a convolution with an image of at
+ *     most 28 x 28.  The skipped op reports fused_into, profile time zero and variant name
+ *     "fused"; a buffer that is no longer written is refused by cadnn_net_read_buffer.
+ *   - 1x1 stride-1 sparse convolutions with the same activation and no residual that read
+ *     the same tensor are launched as one layer over the rows of all of them: the later ones
+ *     report fused_into = the first one; their outputs are channel slices of the first
+ *     one's region, from channel slice_channel on, and stay readable.
+ *   - sparse convolutions on plain tensors whose inputs are all ready when an earlier one
+ *     runs (the branches of an Inception module at the same depth; up to eight, window pools
+ *     on workspace tensors included) are launched with it as one kernel over a table of
+ *     launch records, while one variant serves all the layers: they report fused_into = that
+ *     op and launched_with = 1; the op's variant name is the group's, and
+ *     cadnn_net_op_candidates / cadnn_net_set_op_variant on it list / pin variants for the
+ *     whole group.  Tuning (CADNN_NET_TUNE) keeps a group only if it beats its layers
+ *     launched apart.
+ *   - a window pool that rides on no launch moves up in the launch order to where its input
+ *     completes (launched_after). */
 #define CADNN_NET_GRAPH 1
 #define CADNN_NET_TUNE 2
 #define CADNN_NET_PLAIN_LAYOUT 4
