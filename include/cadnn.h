@@ -42,7 +42,11 @@ typedef enum {
 
 typedef enum {
     CADNN_F32 = 0,           /* fp32 storage, fp32 accumulate */
-    CADNN_F16 = 1            /* fp16 storage (weights, activations, residual, output), fp32 accumulate */
+    CADNN_F16 = 1,           /* fp16 storage (weights, activations, residual, output), fp32 accumulate */
+    /* (not storage types: these two give the enumeration the range of int, so that any value
+     * a caller passes is an argument the library can check and refuse with CADNN_EINVAL) */
+    CADNN_DTYPE_RANGE_LO_ = -0x7fffffff - 1,
+    CADNN_DTYPE_RANGE_HI_ = 0x7fffffff
 } cadnn_dtype;
 
 typedef struct cadnn_weights cadnn_weights;
@@ -124,7 +128,11 @@ cadnn_status cadnn_conv2d_prepare(const cadnn_weights* w, int n, int h, int wdt,
  * inside a network a layer always starts cold (allocates 128 MiB for the duration).
  * cadnn_conv2d_list_variants writes the newline-separated names of the variants that
  * can serve the layer; cadnn_conv2d_set_variant pins one by name (NULL or "" removes
- * the pin, returning to the built-in heuristic). */
+ * the pin, returning to the built-in heuristic).
+ * Tuning frees only the trial layouts it built itself: a device layout that an ordinary
+ * launch (or a finalized net, whose captured graph holds its address) has used stays
+ * alive until cadnn_free_weights, so a handle may be tuned while a net uses it.  Launches
+ * and tuning of ONE handle from several threads at once are serialised by the caller. */
 cadnn_status cadnn_conv2d_tune(const cadnn_weights* w, const void* x, void* y, int n, int h,
                                int wdt, int stride, int pad, const void* bias,
                                const void* residual, int relu, void* stream, int reps,
@@ -135,7 +143,15 @@ cadnn_status cadnn_conv2d_set_variant(const cadnn_weights* w, int n, int h, int 
                                       int pad, const char* name);
 
 /* Sparse fully connected layer: y[n][o] = act( sum_i W[o][i]*x[n][i] + bias[o] ).
- * w must have kh = kw = 1; x: device [n][cin]; y: device [n][cout]. */
+ * (Section 3: the fully connected layers are pruned like the convolutions and kept as
+ * values with indices; Section 4: a 1x1 convolution is a matrix product -- this is that
+ * product on a one-pixel image, the classifier that ends each network of Section 5's
+ * model table.)
+ * w must have kh = kw = 1; x: device [n][cin]; y: device [n][cout]; bias: device fp32
+ * [cout] or NULL.  Asynchronous on `stream`.  A zero weight (pruned, or the padding of the
+ * device layout) never meets an activation its row does not read.  Errors: NULL pointer,
+ * n <= 0, a handle that is a filter bank (CADNN_EINVAL); n above 8 * 65535
+ * (CADNN_EUNSUPPORTED). */
 cadnn_status cadnn_sparse_fc(const cadnn_weights* w, const void* x, void* y, int n,
                              const void* bias, int relu, void* stream);
 /* Uploads the device arrays cadnn_sparse_fc needs (otherwise done on its first call). */
@@ -162,6 +178,9 @@ cadnn_status cadnn_depthwise_conv2d(const cadnn_weights* w, const void* x, void*
 cadnn_status cadnn_depthwise_prepare(const cadnn_weights* w);
 
 /* Pooling layers used between the convolutions of the benchmark networks.
+ * (The paper describes no pooling operation; these are the layers that the published
+ * architectures of the models in Section 5's model table place between convolutions.
+ * No passage to cite.)
  * Max pooling takes the maximum over the in-image part of each k x k window
  * (padding never wins); windowed average pooling takes the mean over the in-image
  * part of each window (padding is neither summed nor counted; the 3x3 / stride 1

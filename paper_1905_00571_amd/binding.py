@@ -11,7 +11,8 @@ F32 = 0
 F16 = 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libcadnn.so")
+# CADNN_LIB_PATH: another build of the same library (the host-sanitizer build); never a fallback
+_LIB_PATH = os.environ.get("CADNN_LIB_PATH") or os.path.join(_HERE, "libcadnn.so")
 _lib = None
 
 _vp = ctypes.c_void_p

@@ -36,13 +36,21 @@ def _newer(a: str, deps) -> bool:
     return all(os.path.getmtime(d) <= t for d in deps)
 
 
-def _compile(src: str, force: bool) -> str:
+# Host-code sanitizers (the device code is compiled as always): each -fsanitize= directly
+# after -Xarch_host, so that only the host pass sees it.
+ASAN_FLAGS = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+              "-Xarch_host", "-fno-sanitize-recover=undefined", "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+ASAN_OBJDIR = os.path.join(OBJDIR, "asan")
+ASAN_LIB = os.path.join(ASAN_OBJDIR, "libcadnn_asan.so")
+
+
+def _compile(src: str, force: bool, asan: bool = False) -> str:
     path = os.path.join(CSRC, src)
-    obj = os.path.join(OBJDIR, src + ".o")
+    obj = os.path.join(ASAN_OBJDIR if asan else OBJDIR, src + ".o")
     deps = [path, os.path.join(CSRC, "internal.h"), os.path.join(INCLUDE, "cadnn.h")]
     if not force and _newer(obj, deps):
         return obj
-    cmd = [HIPCC, "-x", "hip", "-c", path, "-o", obj] + FLAGS
+    cmd = [HIPCC, "-x", "hip", "-c", path, "-o", obj] + FLAGS + (ASAN_FLAGS if asan else [])
     r = subprocess.run(cmd, capture_output=True, text=True)
     out = "\n".join(l for l in (r.stdout + r.stderr).splitlines()
                     if "packed-fp32-ops" not in l)
@@ -66,5 +74,39 @@ def build(force: bool = True, jobs: int = 6) -> str:
     return LIB
 
 
+def asan_runtime() -> str:
+    """The shared AddressSanitizer runtime of the compiler that built the library (a process
+    that loads the instrumented library must have it loaded first)."""
+    r = subprocess.run([HIPCC, "--print-file-name=libclang_rt.asan-x86_64.so"], capture_output=True, text=True)
+    path = r.stdout.strip()
+    if not os.path.isabs(path):
+        clang = os.path.join(os.path.dirname(os.path.dirname(HIPCC)), "lib", "llvm", "bin", "clang")
+        r = subprocess.run([clang, "--print-file-name=libclang_rt.asan-x86_64.so"], capture_output=True, text=True)
+        path = r.stdout.strip()
+    return path if os.path.isabs(path) and os.path.exists(path) else ""
+
+
+def build_asan(force: bool = False, jobs: int = 6) -> str:
+    """The same library with AddressSanitizer and UndefinedBehaviorSanitizer on its HOST code
+    (packer, plan builders, net layout: index arithmetic that runs without a GPU), as
+    _build/asan/libcadnn_asan.so.  CADNN_LIB_PATH makes the binding load it; the process needs
+    the runtime preloaded (asan_runtime())."""
+    os.makedirs(ASAN_OBJDIR, exist_ok=True)
+    with ThreadPoolExecutor(max_workers=jobs) as ex:
+        objs = list(ex.map(lambda s: _compile(s, force, True), SOURCES))
+    tmp = ASAN_LIB + f".tmp{os.getpid()}"
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-shared-libsan", "-fsanitize=address",
+           "-fsanitize=undefined", "-o", tmp] + objs
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("link failed:\n" + r.stdout + r.stderr)
+    os.replace(tmp, ASAN_LIB)
+    return ASAN_LIB
+
+
 if __name__ == "__main__":
-    print(build(force="--incremental" not in sys.argv))
+    if "--asan" in sys.argv:
+        print(build_asan(force="--incremental" not in sys.argv))
+        print("runtime:", asan_runtime())
+    else:
+        print(build(force="--incremental" not in sys.argv))

@@ -51,7 +51,7 @@ static cadnn_status check_conv(const char* who, const cadnn_weights* w, const Te
     if (g->hout <= 0 || g->wout <= 0) return fail(CADNN_EINVAL, "%s: empty output", who);
     if (n > 65535) return fail(CADNN_EUNSUPPORTED, "%s: batch above 65535", who);
     if (xd.image * (int64_t)w->elem() >= 0x7ffffff0ll ||
-        (int64_t)w->cout * (g->hout + 64) * (g->wout + 64) * (int64_t)w->elem() >= 0x7ffffff0ll)
+        (double)w->cout * ((double)g->hout + 64.0) * ((double)g->wout + 64.0) * (double)w->elem() >= (double)0x7ffffff0ll)
         return fail(CADNN_EUNSUPPORTED, "%s: one image of the tensor is 2 GiB or more", who);
     return CADNN_OK;
 }
@@ -417,6 +417,7 @@ cadnn_status conv2d_group_tune(const std::vector<ConvMember>& members, int n, hi
     if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return fail(CADNN_EHIP, "hipEventCreate failed"); }
     float best_ms = 0.0f;
     std::vector<ConvLaunch> recs;
+    const TrialPlans trial;
     for (const ConvVariant* v : cand) {
         if (conv2d_group_records(members, n, v, &recs) != CADNN_OK) continue;   // does not fit these weights
         DevBuf table;
@@ -563,6 +564,7 @@ cadnn_status conv2d_tune_impl(const cadnn_weights* w, const void* x, const Tenso
     if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return fail(CADNN_EHIP, "hipEventCreate failed"); }
     const ConvVariant* best = nullptr;
     float best_ms = 0.0f;
+    const TrialPlans trial;
     for (const ConvVariant* v : cand) {
         {
             const ConvPlan* probe = nullptr;

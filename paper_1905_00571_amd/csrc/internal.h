@@ -260,6 +260,18 @@ struct ConvPlan {
     int nchunks = 0;
     int rows_padded = 0;
     int64_t nz_padded = 0;
+    // handed out for an ordinary launch (not only timed by a tuning pass): a captured graph or
+    // a launch in flight may hold its device pointers, so it lives as long as the handle
+    mutable bool in_use = false;
+};
+
+// While one of these is alive on a thread, the plans that thread asks for are trial plans of a
+// tuning pass: they may be freed again when the pass ends (drop_unpinned_plans).
+struct TrialPlans {
+    TrialPlans();
+    ~TrialPlans();
+    TrialPlans(const TrialPlans&) = delete;
+    TrialPlans& operator=(const TrialPlans&) = delete;
 };
 
 // Staged tile of the FAM_PTILE kernels for one layer geometry.  Two lane arrangements:

@@ -84,11 +84,13 @@ __device__ __forceinline__ void fc_use(const typename FcVec<T>::type (&v)[U], co
 }
 
 // Loads U x 64 groups of four entries starting at group `first` (this lane's), whole, and
-// zeroes the values of the groups at or past e4, the end of the row.
+// zeroes the values of the groups at or past e4, the end of the row; their columns become
+// `safe`, columns of the row itself, so that the zero never meets an activation the row does
+// not read (0 * Inf would be NaN).
 template <typename T, int NB, int U>
 __device__ __forceinline__ void fc_chunk(const typename FcVec<T>::type* __restrict__ val4,
                                          const fc_u4* __restrict__ col4, const T* xs, int cin, int nb,
-                                         int first, int e4, float (&acc)[NB]) {
+                                         int first, int e4, const fc_u4 safe, float (&acc)[NB]) {
     typename FcVec<T>::type v[U];
     fc_u4 c[U];
 #pragma unroll
@@ -98,7 +100,7 @@ __device__ __forceinline__ void fc_chunk(const typename FcVec<T>::type* __restri
     }
 #pragma unroll
     for (int u = 0; u < U; ++u)
-        if (first + u * 64 >= e4) v[u] = 0;
+        if (first + u * 64 >= e4) { v[u] = 0; c[u] = safe; }
     fc_use<T, NB, U>(v, c, xs, cin, nb, acc);
 }
 
@@ -129,12 +131,13 @@ __global__ __launch_bounds__(THREADS) void sfc_lds_kernel(const int32_t* __restr
 #pragma unroll
         for (int b = 0; b < NB; ++b) acc[b] = 0.0f;
         int base = s4;
+        const fc_u4 safe = col4[s4];      // (the arrays end in spare entries: in range for an empty last row too)
         for (; e4 - base > 128; base += 256)
-            fc_chunk<T, NB, 4>(val4, col4, xs, cin, nb, base + lane, e4, acc);
+            fc_chunk<T, NB, 4>(val4, col4, xs, cin, nb, base + lane, e4, safe, acc);
         if (e4 - base > 64)
-            fc_chunk<T, NB, 2>(val4, col4, xs, cin, nb, base + lane, e4, acc);
+            fc_chunk<T, NB, 2>(val4, col4, xs, cin, nb, base + lane, e4, safe, acc);
         else if (e4 - base > 0)
-            fc_chunk<T, NB, 1>(val4, col4, xs, cin, nb, base + lane, e4, acc);
+            fc_chunk<T, NB, 1>(val4, col4, xs, cin, nb, base + lane, e4, safe, acc);
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
             float v = acc[b];

@@ -93,13 +93,22 @@ float f16_to_f32(uint16_t h) {
     return f;
 }
 
+// Pads a segment of a nonzero stream (its entries start at `first`) to a multiple of `unroll`
+// with zero-valued entries that REPEAT the address word of the segment's last real entry: a
+// padding entry then multiplies 0 with an activation the row reads anyway, never with one the
+// definition of the layer does not touch (which could be Inf or NaN: 0 * Inf is NaN).
+static void pad_segment(std::vector<uint2>& nz, size_t first, int unroll) {
+    const uint32_t where = nz.size() > first ? nz.back().y : 0u;
+    while (nz.size() % (size_t)unroll) nz.push_back(make_uint2(0u, where));
+}
+
 // Builds the device copy of the nonzero stream for one tile-kernel variant.
 //
 // Layout: packed rows are padded up to a multiple of the variant's rows-per-workgroup.
 // For packed row i and channel chunk c, seg_ptr[i*(nchunks+1) + c .. + c+1] delimits that
 // row's nonzeros whose input channel lies in [c*cch, (c+1)*cch); every segment is padded
-// with (0.0f, offset 0) pairs to a multiple of `unroll` entries so the kernel can fetch
-// fixed-size groups.  Each entry is (fp32 value bits, byte offset of the tap inside the
+// with zero-valued pairs to a multiple of `unroll` entries so the kernel can fetch
+// fixed-size groups (see pad_segment).  Each entry is (fp32 value bits, byte offset of the tap inside the
 // staged tile for output pixel (0,0) of the tile).
 static cadnn_status build_tile_plan(const cadnn_weights* w, const ConvVariant* v, ConvPlan* plan) {
     const int g = v->nw * v->rpw;
@@ -116,6 +125,7 @@ static cadnn_status build_tile_plan(const cadnn_weights* w, const ConvVariant* v
         const int32_t end = i < w->cout ? w->row_ptr[i + 1] : 0;
         for (int c = 0; c < nchunks; ++c) {
             seg[(size_t)i * (nchunks + 1) + c] = (int32_t)nz.size();
+            const size_t seg_first = nz.size();
             const int32_t k_end = (int32_t)std::min<int64_t>((int64_t)(c + 1) * v->cch, w->cin) * taps;
             while (cur < end && w->col_idx[cur] < k_end) {
                 const int32_t k = w->col_idx[cur];
@@ -130,7 +140,7 @@ static cadnn_status build_tile_plan(const cadnn_weights* w, const ConvVariant* v
                 nz.push_back(make_uint2(bits, off));
                 ++cur;
             }
-            while (nz.size() % (size_t)v->unroll) nz.push_back(make_uint2(0u, 0u));
+            pad_segment(nz, seg_first, v->unroll);
         }
         seg[(size_t)i * (nchunks + 1) + nchunks] = (int32_t)nz.size();
     }
@@ -152,7 +162,7 @@ static cadnn_status build_tile_plan(const cadnn_weights* w, const ConvVariant* v
 // input channels are cut into KS equal slices; inside a slice the entries are regrouped
 // tap-major (tap t = r*KW + c), ascending channel inside a tap.  seg_ptr[((i*KS + s)*(T+1)
 // + t .. t+1] delimits the entries of packed row i, slice s, tap t; every such segment is
-// padded to a multiple of `unroll` with (0.0f, channel 0) entries.  An entry is (fp32
+// padded to a multiple of `unroll` with zero-valued entries (see pad_segment).  An entry is (fp32
 // value bits, input channel).
 static cadnn_status build_direct_plan(const cadnn_weights* w, const ConvVariant* v, ConvPlan* plan) {
     const int g = v->rows_per_block();
@@ -181,9 +191,10 @@ static cadnn_status build_direct_plan(const cadnn_weights* w, const ConvVariant*
             int32_t* sp = &seg[((size_t)i * ks + s) * (taps + 1)];
             for (int t = 0; t < taps; ++t) {
                 sp[t] = (int32_t)nz.size();
+                const size_t seg_first = nz.size();
                 const auto& b = bucket[(size_t)s * taps + t];
                 nz.insert(nz.end(), b.begin(), b.end());
-                while (nz.size() % (size_t)v->unroll) nz.push_back(make_uint2(0u, 0u));
+                pad_segment(nz, seg_first, v->unroll);
             }
             sp[taps] = (int32_t)nz.size();
         }
@@ -203,8 +214,8 @@ static cadnn_status build_direct_plan(const cadnn_weights* w, const ConvVariant*
 // Device copy of the nonzero stream for a linear-address (FAM_LINEAR) variant.
 //
 // Entries stay in canonical order.  A packed row's entries are cut into KS contiguous
-// parts of (nearly) equal length, each padded to a multiple of `unroll` with (0.0f, 0)
-// entries.  Part s of packed row i starts at entry (i*KS + s)*stride, where `stride` is the
+// parts of (nearly) equal length, each padded to a multiple of `unroll` with zero-valued
+// entries that repeat the last real entry's offset.  Part s of packed row i starts at entry (i*KS + s)*stride, where `stride` is the
 // longest padded part of the layer: the start of a part is therefore computable from the
 // row number alone, and its first entries can be fetched together with its header instead
 // of one memory round trip after it.  The header table (stored in the plan's segment
@@ -271,6 +282,8 @@ static cadnn_status build_linear_plan(const cadnn_weights* w, const ConvVariant*
                 out[j - pb] = make_uint2(bits, (uint32_t)off);
             }
             const int32_t len1 = (pe - pb + U - 1) / U * U;
+            // (padding repeats the last real entry's offset with a zero weight: see pad_segment)
+            for (int32_t j = pe - pb; j < len1 && pe > pb; ++j) out[j] = make_uint2(0u, out[pe - pb - 1].y);
             hdr[((size_t)i * ks + s) * hw + 0] = len1;
             hdr[((size_t)i * ks + s) * hw + 1] = perm[i];
             if (ex && i < w->cout) {
@@ -286,7 +299,9 @@ static cadnn_status build_linear_plan(const cadnn_weights* w, const ConvVariant*
                     std::memcpy(&bits, &ex->w->vals[j], 4);
                     out[len1 + (j - qb)] = make_uint2(bits, (uint32_t)off);
                 }
-                hdr[((size_t)i * ks + s) * hw + 2] = (qe - qb + U - 1) / U * U;
+                const int32_t len2 = (qe - qb + U - 1) / U * U;
+                for (int32_t j = qe - qb; j < len2 && qe > qb; ++j) out[len1 + j] = make_uint2(0u, out[len1 + qe - qb - 1].y);
+                hdr[((size_t)i * ks + s) * hw + 2] = len2;
             }
         }
     }
@@ -410,7 +425,9 @@ static cadnn_status build_ptile_plan(const cadnn_weights* w, const ConvVariant* 
                     std::memcpy(&bits, &w->vals[j], 4);
                     out[j - pb] = make_uint2(bits, (uint32_t)off);
                 }
-                out += lens[((size_t)ws * g.nchunks + c) * rpw + r];
+                const int32_t padded = lens[((size_t)ws * g.nchunks + c) * rpw + r];
+                for (int32_t j = pe - pb; j < padded && pe > pb; ++j) out[j] = make_uint2(0u, out[pe - pb - 1].y);
+                out += padded;
             }
     }
     plan->variant = v;
@@ -461,7 +478,7 @@ bool stile_streams_fit(const cadnn_weights* w, const ConvVariant* v) {
 //
 // Packed rows are taken G at a time (G = rows per workgroup).  For group g and channel
 // chunk c the entries of the G rows whose channel lies in the chunk are laid out row after
-// row, each row's run padded to a multiple of `unroll` with (0.0f, offset 0);
+// row, each row's run padded to a multiple of `unroll` with zero-valued entries (see pad_segment);
 // seg_ptr[(g*nchunks + c)*(G+1) + r .. + 1] delimits row r's run.  An entry is (fp32 value
 // bits, byte offset of the tap inside the wave's staged slice for pixel (0,0) of the tile).
 // A (group, chunk) stream longer than the kernel's buffer makes the variant unusable for
@@ -490,6 +507,7 @@ static cadnn_status build_stile_plan(const cadnn_weights* w, const ConvVariant* 
             const int32_t k_end = (int32_t)std::min<int64_t>((int64_t)(c + 1) * v->cch, w->cin) * taps;
             for (int r = 0; r < G; ++r) {
                 sp[r] = (int32_t)nz.size();
+                const size_t seg_first = nz.size();
                 while (cur[r] < end[r] && w->col_idx[cur[r]] < k_end) {
                     const int32_t k = w->col_idx[cur[r]];
                     const int ci = k / taps - c * v->cch;
@@ -502,7 +520,7 @@ static cadnn_status build_stile_plan(const cadnn_weights* w, const ConvVariant* 
                     nz.push_back(make_uint2(bits, off));
                     ++cur[r];
                 }
-                while (nz.size() % (size_t)v->unroll) nz.push_back(make_uint2(0u, 0u));
+                pad_segment(nz, seg_first, v->unroll);
             }
             sp[G] = (int32_t)nz.size();
             if (nz.size() - start > (size_t)v->nz_cap)
@@ -569,11 +587,16 @@ static PlanKey plan_key(const cadnn_weights* w, const ConvVariant* v, const Tens
     return PlanKey(v, 0, 0, nullptr, 0);
 }
 
-// Frees every plan whose variant is not pinned for some geometry of this handle.
+static thread_local int g_trial_plans = 0;
+TrialPlans::TrialPlans() { ++g_trial_plans; }
+TrialPlans::~TrialPlans() { --g_trial_plans; }
+
+// Frees the trial plans of a tuning pass: every plan that was never handed out for an ordinary
+// launch and whose variant is not pinned for some geometry of this handle.
 void drop_unpinned_plans(const cadnn_weights* w) {
     std::lock_guard<std::mutex> lock(w->mu);
     for (auto it = w->plans.begin(); it != w->plans.end();) {
-        bool pinned = false;
+        bool pinned = it->second->in_use;
         for (const auto& c : w->chosen) pinned = pinned || c.second == std::get<0>(it->first);
         if (pinned) ++it; else it = w->plans.erase(it);
     }
@@ -597,6 +620,7 @@ cadnn_status get_conv_plan(const cadnn_weights* w, const ConvVariant* v, const T
         if (st != CADNN_OK) return st;
         it = w->plans.emplace(key, std::move(plan)).first;
     }
+    if (g_trial_plans == 0) it->second->in_use = true;
     *out = it->second.get();
     if (keep) *keep = it->second;
     return CADNN_OK;
@@ -632,6 +656,10 @@ cadnn_status ensure_fc_device(const cadnn_weights* w) {
                     if (half) fval16[o] = w->vals16[i];
                     else fval[o] = w->vals[i];
                 }
+                // the zero entries that fill the row's last group repeat its last column (a
+                // zero weight must not meet an activation the row does not read)
+                if (w->row_ptr[r + 1] > w->row_ptr[r])
+                    for (; o < (size_t)frow[r + 1] * 4; ++o) fcol[o] = fcol[o - 1];
             }
             if ((st = w->d_frow.upload(frow.data(), frow.size() * 4)) != CADNN_OK) return st;
             if ((st = w->d_fcol.upload(fcol.data(), fcol.size() * 2)) != CADNN_OK) return st;

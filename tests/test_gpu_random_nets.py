@@ -12,7 +12,7 @@ import pytest
 
 import oracle
 import workloads as wl
-from util import TOL_F32, TOL_F16, rel_errors
+from util import TOL_F32, TOL_F16, rel_errors, chain_bounds, assert_within_bound
 
 pytestmark = pytest.mark.gpu
 
@@ -153,27 +153,33 @@ def test_random_net(cad, seed):
     last_writer = {}
     for i, o in enumerate(ops):
         last_writer[o.dst] = i
-    # intermediate maps: a chain gate on the whole tensor (each is several layers deep)
-    mid_tol = 5e-2 if f16 else 1e-3
+    # every tensor of the net against the bound a forward error analysis gives for it
+    # (util.chain_bounds): no tolerance is chosen here
+    bounds = chain_bounds(ops, ins, outs, ws, bs, f16)
     configs = [{}, {"plain_layout": True, "fuse": False}, {"use_graph": False}]
     if seed % 5 == 0:
         configs.append({"tune": True})      # every layer's candidates timed on the net's own buffers first
     # a second input: a run must not lean on what the previous one left in the workspace (an op
     # launched before its input is written would go unnoticed on a repeated input)
     xs2 = wl.activation(shape, f"rnd{seed}", 99, relu=True).astype(npdt)
-    ref2 = oracle.run_net(ops, xs2, ws, bs, dtype=npdt)[0]
+    ref2, ins2, outs2 = oracle.run_net(ops, xs2, ws, bs, dtype=npdt)
+    bound2 = chain_bounds(ops, ins2, outs2, ws, bs, f16)[-1]
     for kw in configs:
         args = dict(use_graph=True)
         args.update(kw)
         net = cad.build_net(ops, ws, bs, shape, dtype, **args)
         for rep in range(3):
-            inp, want = (xs2, ref2) if rep == 1 else (xs, ref)
+            inp, want, lim = (xs2, ref2, bound2) if rep == 1 else (xs, ref, bounds[-1])
             y = net.run(torch.from_numpy(inp).cuda())
             torch.cuda.synchronize()
             got = y.cpu().numpy()
-            assert np.isfinite(got).all()
+            assert_within_bound(got, want, lim, f"random net {seed} {kw} run {rep}")
             e = rel_errors(got, want)[0]
-            assert e <= (tol * 5 if f16 else tol), (seed, kw, rep, e, [o.kind for o in ops])
+            # the stated bar on the whole tensor as well: always in fp32; in fp16 storage
+            # wherever the net is conditioned well enough for the propagated bound to imply it
+            # (a 7-element output of a random graph whose terms cancel need not be)
+            if not f16 or lim.max() <= tol * np.abs(want).max():
+                assert e <= tol, (seed, kw, rep, e)
         checked = 0
         for i, o in enumerate(ops[:-1]):
             if last_writer[o.dst] != i:
@@ -182,8 +188,7 @@ def test_random_net(cad, seed):
                 mid = net.read_buffer(o.dst, outs[i].shape)
             except cad.CadnnError:
                 continue                       # never materialised (computed inside another op)
-            e = rel_errors(mid, outs[i])[0]
-            assert np.isfinite(mid).all() and e <= mid_tol, (seed, kw, o.name, e)
+            assert_within_bound(mid, outs[i], bounds[i], f"random net {seed} {kw} {o.name}")
             checked += 1
         assert checked >= len(ops) // 2
         net.free()

@@ -114,3 +114,110 @@ def test_run_net_matches_manual_composition():
     np.testing.assert_allclose(y[:, :, 0, 0], ref.numpy(), rtol=2e-5, atol=2e-6)
     assert len(ins) == len(outs) == len(ops)
     assert np.array_equal(ins[5], outs[3])
+
+
+def _torch_fp16_net(ops, x, ws, bs, jitter=None):
+    """The same op list evaluated with torch float64 primitives and an explicit rounding of
+    every weight tensor and every layer output to IEEE binary16 (bias stays fp32): the fp16
+    storage semantics written out independently of oracle.run_net.  `jitter`, if given,
+    perturbs every pre-rounding layer result relatively (a stand-in for another summation
+    order) and is used to exercise the propagated error bound."""
+    torch = pytest.importorskip("torch")
+    F = torch.nn.functional
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).double()
+    h16 = lambda v: v.to(torch.float16).double()
+    bufs = {0: h16(t(x))}
+    outs = []
+    rng = np.random.default_rng(5)
+    for i, op in enumerate(ops):
+        src = bufs[op.src]
+        if op.kind == "conv":
+            y = F.conv2d(src, h16(t(ws[i])), t(bs[i]), stride=op.stride, padding=op.pad)
+            if op.res >= 0:
+                y = y + bufs[op.res]
+        elif op.kind == "dwconv":
+            y = F.conv2d(src, h16(t(ws[i])), t(bs[i]), stride=op.stride, padding=op.pad, groups=src.shape[1])
+        elif op.kind == "fc":
+            y = src.reshape(src.shape[0], -1) @ h16(t(ws[i])).reshape(op.cout, -1).T + t(bs[i])
+            y = y.reshape(y.shape[0], y.shape[1], 1, 1)
+        elif op.kind == "maxpool":
+            y = F.max_pool2d(src, op.k, op.stride, op.pad)
+        elif op.kind == "avgpool2d":
+            y = F.avg_pool2d(src, op.k, op.stride, op.pad, count_include_pad=False)
+        elif op.kind == "avgpool":
+            y = src.mean(dim=(2, 3), keepdim=True)
+        elif op.kind == "concat":
+            y = torch.cat([bufs[b] for b in op.srcs], dim=1)
+        if op.kind in ("conv", "dwconv", "fc") and op.relu:
+            y = torch.relu(y)
+        if jitter and op.kind in ("conv", "dwconv", "fc"):
+            y = y * t(1.0 + jitter * rng.uniform(-1.0, 1.0, size=tuple(y.shape)))
+        y = h16(y)
+        bufs[op.dst] = y
+        outs.append(y.numpy())
+    return outs
+
+
+def _fp16_dw_net():
+    ops = [
+        wl.Op("conv", "stem", 0, 1, 3, 8, 3, 2, 1, 0.0, True),
+        wl.Op("dwconv", "dw1", 1, 2, 8, 8, 3, 1, 1, 0.0, True),
+        wl.Op("conv", "pw1", 2, 3, 8, 12, 1, 1, 0, 0.5, False),
+        wl.Op("dwconv", "dw2", 3, 4, 12, 12, 3, 2, 1, 0.3, True),
+        wl.Op("conv", "pw2", 4, 5, 12, 12, 1, 1, 0, 0.5, True),
+        wl.Op("conv", "b", 5, 6, 12, 12, 3, 1, 1, 0.6, True, res=4),
+        wl.Op("avgpool2d", "ap", 6, 7, k=3, stride=1, pad=1),
+        wl.Op("maxpool", "mp", 6, 8, k=3, stride=1, pad=1),
+        wl.Op("concat", "cat", 7, 9, srcs=(7, 8, 5)),
+        wl.Op("avgpool", "g", 9, 10),
+        wl.Op("fc", "fc", 10, 11, 36, 5, sparsity=0.5, relu=False),
+    ]
+    return ops, (2, 3, 19, 17)
+
+
+def test_run_net_fp16_with_depthwise_matches_explicit_rounding():
+    """Pins the interpreter's fp16 mode and its depthwise dispatch: weights and every
+    activation rounded to binary16, sums in higher precision, one rounding per layer."""
+    ops, shape = _fp16_dw_net()
+    x, ws, bs = wl.net_tensors(ops, "unit-net-16", shape)
+    y, ins, outs = oracle.run_net(ops, x.astype(np.float16), ws, bs, dtype=np.float16)
+    assert y.dtype == np.float16 and all(o.dtype == np.float16 for o in outs)
+    want = _torch_fp16_net(ops, x, ws, bs)
+    for i, op in enumerate(ops):
+        a, b = outs[i].astype(np.float64), want[i]
+        assert a.shape == b.shape, op.name
+        # both are a correctly rounded value of the same exact sum up to float64 noise: equal,
+        # except where that noise straddles a rounding boundary (one fp16 step, rarely)
+        step = 2.0 ** -10 * np.maximum(np.abs(a), 2.0 ** -14)
+        assert (np.abs(a - b) <= step).all(), op.name
+        assert (a == b).mean() > 0.995, (op.name, (a == b).mean())
+    # the fp32 mode of the same graph, for the depthwise dispatch alone
+    y32, _, outs32 = oracle.run_net(ops, x, ws, bs)
+    torch = pytest.importorskip("torch")
+    F = torch.nn.functional
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).double()
+    ref_dw1 = torch.relu(F.conv2d(t(outs32[0]), t(ws[1]), t(bs[1]), padding=1, groups=8)).numpy()
+    np.testing.assert_allclose(outs32[1], ref_dw1, rtol=1e-6, atol=1e-7)
+
+
+def test_propagated_chain_bound_holds_and_is_not_vacuous():
+    """util.chain_bounds (the gate of the chained GPU tests): an independent evaluation whose
+    every layer is off by up to 3e-5 relative before rounding -- what another summation order
+    may do -- stays inside the bound, in both storage types; an evaluation with a dropped
+    term does not; and the bound is a small fraction of the tensor's scale."""
+    from util import chain_bounds, assert_within_bound
+    ops, shape = _fp16_dw_net()
+    x, ws, bs = wl.net_tensors(ops, "unit-net-16", shape)
+    y, ins, outs = oracle.run_net(ops, x.astype(np.float16), ws, bs, dtype=np.float16)
+    bounds = chain_bounds(ops, ins, outs, ws, bs, True)
+    other = _torch_fp16_net(ops, x, ws, bs, jitter=3e-5)
+    for i, op in enumerate(ops):
+        assert_within_bound(other[i], outs[i], bounds[i], op.name)
+    assert bounds[-1].max() < 0.05 * np.abs(outs[-1].astype(np.float64)).max()
+    broken = [w.copy() for w in ws[:5]] + list(ws[5:])
+    nz = np.flatnonzero(broken[2])
+    broken[2].reshape(-1)[nz[0]] = 0.0                         # one pointwise weight dropped
+    bad = _torch_fp16_net(ops, x, broken, bs)
+    with pytest.raises(AssertionError):
+        for i, op in enumerate(ops):
+            assert_within_bound(bad[i], outs[i], bounds[i], op.name)
