@@ -193,6 +193,39 @@ cadnn_status cadnn_avgpool2d(const void* x, void* y, int n, int c, int h, int wd
 cadnn_status cadnn_global_avgpool(const void* x, void* y, int n, int c, int h, int wdt,
                                   cadnn_dtype dtype, void* stream);
 
+/* Host-only view of the device layout ("plan") a kernel variant would read for this layer
+ * (Section 3 counts the storage of a pruned model with and without its indices; Section 4
+ * transforms the filter layout per device): no GPU is needed, nothing is uploaded or cached.
+ * `variant` is a name from cadnn_conv2d_list_variants (NULL or "": the variant
+ * cadnn_sparse_conv2d would launch).
+ *   entries          stream entries the kernels walk: the nonzeros plus the zero-valued
+ *                    entries that pad every part of a row to the kernels' unroll
+ *   stream_bytes     bytes of values + indices of those entries as stored on the device
+ *   alloc_bytes      device bytes of the stream arrays (parts start at a fixed stride in
+ *                    some layouts; the gaps between them are allocated and never read)
+ *   table_bytes      bytes of the per-row / per-part tables beside the stream
+ *   bytes_per_nonzero  stream_bytes / nonzeros of the layer (0 if it has none)
+ *   chunks           input-channel chunks an LDS-staged variant works through (else 1)
+ *   lds_bytes        dynamic LDS of one workgroup (0: none or compiled in)
+ * Errors: as cadnn_sparse_conv2d; CADNN_EINVAL if the name does not serve the layer. */
+typedef struct cadnn_plan_info {
+    int64_t entries;
+    int64_t stream_bytes;
+    int64_t alloc_bytes;
+    int64_t table_bytes;
+    double bytes_per_nonzero;
+    int chunks;
+    int lds_bytes;
+} cadnn_plan_info;
+cadnn_status cadnn_conv2d_plan_info(const cadnn_weights* w, int n, int h, int wdt, int stride, int pad,
+                                    const char* variant, cadnn_plan_info* out);
+/* The inverse of that layout transformation, for the variants with the compact 16-bit
+ * tile-offset stream ("swide_*"): rebuilds the dense [cout][cin][kh][kw] fp32 tensor on the
+ * HOST from the stream the kernel would read.  Equal to cadnn_unpack_weights element by
+ * element when the layout loses nothing.  CADNN_EUNSUPPORTED for the other variants. */
+cadnn_status cadnn_conv2d_plan_unpack(const cadnn_weights* w, int n, int h, int wdt, int stride, int pad,
+                                      const char* variant, float* w_host_out);
+
 /* Measurement aid, not part of the paper's method: a plain device-to-device streaming copy
  * of `bytes` bytes (a multiple of 16; 16-byte aligned pointers), whose memory traffic is
  * known exactly and against which hardware traffic counters are calibrated. */

@@ -39,6 +39,12 @@ class OpInfo(ctypes.Structure):
                 ("input_copy", ctypes.c_int64)]
 
 
+class PlanInfo(ctypes.Structure):
+    """Mirror of cadnn_plan_info."""
+    _fields_ = [("entries", ctypes.c_int64), ("stream_bytes", ctypes.c_int64), ("alloc_bytes", ctypes.c_int64), ("table_bytes", ctypes.c_int64),
+                ("bytes_per_nonzero", ctypes.c_double), ("chunks", ctypes.c_int), ("lds_bytes", ctypes.c_int)]
+
+
 def lib_path() -> str:
     return _LIB_PATH
 
@@ -70,6 +76,8 @@ def lib() -> ctypes.CDLL:
         "cadnn_conv2d_tune": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _vp, _vp, _i, _vp, _i, _f32p]),
         "cadnn_conv2d_list_variants": (_i, [_vp, _i, _i, _i, _i, _i, ctypes.c_char_p, ctypes.c_size_t]),
         "cadnn_conv2d_set_variant": (_i, [_vp, _i, _i, _i, _i, _i, ctypes.c_char_p]),
+        "cadnn_conv2d_plan_info": (_i, [_vp, _i, _i, _i, _i, _i, ctypes.c_char_p, ctypes.POINTER(PlanInfo)]),
+        "cadnn_conv2d_plan_unpack": (_i, [_vp, _i, _i, _i, _i, _i, ctypes.c_char_p, _f32p]),
         "cadnn_sparse_fc": (_i, [_vp, _vp, _vp, _i, _vp, _i, _vp]),
         "cadnn_fc_prepare": (_i, [_vp]),
         "cadnn_depthwise_conv2d": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _vp, _i, _vp]),
@@ -201,6 +209,22 @@ def cadnn_conv2d_list_variants(w: Weights, n: int, h: int, wdt: int, stride: int
     _check(lib().cadnn_conv2d_list_variants(w.handle, n, h, wdt, stride, pad, buf, 1 << 16))
     text = buf.value.decode()
     return text.split("\n") if text else []
+
+
+def cadnn_conv2d_plan_info(w: Weights, n: int, h: int, wdt: int, stride: int, pad: int,
+                           variant: Optional[str] = None) -> dict:
+    info = PlanInfo()
+    _check(lib().cadnn_conv2d_plan_info(w.handle, n, h, wdt, stride, pad, None if not variant else variant.encode(),
+                                        ctypes.byref(info)))
+    return {k: getattr(info, k) for k, _ in PlanInfo._fields_}
+
+
+def cadnn_conv2d_plan_unpack(w: Weights, n: int, h: int, wdt: int, stride: int, pad: int,
+                             variant: Optional[str] = None) -> np.ndarray:
+    out = np.empty((w.cout, w.cin, w.kh, w.kw), np.float32)
+    _check(lib().cadnn_conv2d_plan_unpack(w.handle, n, h, wdt, stride, pad, None if not variant else variant.encode(),
+                                          out.ctypes.data_as(_f32p)))
+    return out
 
 
 def cadnn_conv2d_set_variant(w: Weights, n: int, h: int, wdt: int, stride: int, pad: int,

@@ -61,7 +61,10 @@ static bool variant_fits(const ConvVariant& v, const cadnn_weights* w, const Con
     if (v.stride != 0 && v.stride != g.stride) return false;
     if ((w->cout + v.rows_per_block() - 1) / v.rows_per_block() > 65535) return false;
     // de-interleaved tensors and fused shortcuts are understood by the linear-address kernels only
-    if ((g.xd.s2d || g.out_s2d || g.ex) && v.family != FAM_LINEAR) return false;
+    // (the wide-tile family computes every address through the general layout function, so it
+    // reads and writes de-interleaved tensors as well; it fuses nothing)
+    if (g.ex && v.family != FAM_LINEAR) return false;
+    if ((g.xd.s2d || g.out_s2d) && v.family != FAM_LINEAR && v.family != FAM_WTILE) return false;
     if (v.family == FAM_DENSE)
         return any_density || (double)w->nnz >= 0.25 * (double)w->cout * w->cin * w->kh * w->kw;
     if (v.family == FAM_LINEAR) {
@@ -115,6 +118,18 @@ static bool variant_fits(const ConvVariant& v, const cadnn_weights* w, const Con
         const PtileGeom pg = ptile_geom(v, w->cin, w->kh, w->kw, g.stride, g.pad, g.wout);
         return pg.nstp <= kPtileMaxSteps && (int64_t)pg.plane * 4 <= (int64_t)kLdsBytesPerCU;
     }
+    if (v.family == FAM_WTILE) {
+        // pixel-wise layers take the flattened-pixel instantiations, filters with taps the lane grids
+        if ((w->kh * w->kw == 1) != (v.flat != 0)) return false;
+        if (v.flat && g.pad != 0) return false;
+        const WtileGeom wg = wtile_geom(v, w->cin, w->kh, w->kw, g.stride);
+        if (wg.nstp > kWtileMaxSteps || wg.lds_bytes > kLdsBytesPerCU) return false;
+        // a flattened tile runs over the images of the batch: the whole tensor behind one 32-bit offset
+        if (v.flat && (g.xd.image * (int64_t)w->elem() * g.n >= 0x7ffffff0ll ||
+                       (int64_t)w->cout * (g.hout + 64) * (g.wout + 64) * (int64_t)w->elem() * g.n >= 0x7ffffff0ll))
+            return false;
+        return true;
+    }
     if (v.kh != w->kh || v.kw != w->kw) return false;
     // the wave-sliced LDS kernel buffers the stream of a (row group, channel chunk)
     return v.family != FAM_STILE || stile_streams_fit(w, &v);
@@ -128,6 +143,7 @@ static std::vector<const ConvVariant*> candidates(const cadnn_weights* w, const 
     for (const ConvVariant& v : all_dense_variants()) if (variant_fits(v, w, g)) out.push_back(&v);
     for (const ConvVariant& v : all_stile_variants()) if (variant_fits(v, w, g)) out.push_back(&v);
     for (const ConvVariant& v : all_ptile_variants()) if (variant_fits(v, w, g)) out.push_back(&v);
+    for (const ConvVariant& v : all_wtile_variants()) if (variant_fits(v, w, g)) out.push_back(&v);
     // No sparse kernel is instantiated for the geometry (say a 5x5 or a stride-3 7x7 filter on
     // an input without halo): the matrix-core kernel, which takes any geometry, serves it
     // whatever the density, so that every valid layer runs.
@@ -155,7 +171,7 @@ static double variant_cost(const cadnn_weights* w, const ConvGeom& g, const Conv
         const double blocks = std::ceil(pixels / 64.0) * g.n * std::ceil(w->cout / 64.0);
         const double K = (double)w->cin * w->kh * w->kw;
         cost = 2500.0 + std::ceil(blocks / 256.0) * std::ceil(K / 32.0) * 1100.0;
-    } else if (v->family == FAM_STILE || v->family == FAM_PTILE) {
+    } else if (v->family == FAM_STILE || v->family == FAM_PTILE || v->family == FAM_WTILE) {
         return -1.0;
     } else if (v->family != FAM_TILE) {
         const int P = v->p;
@@ -231,6 +247,7 @@ static cadnn_status make_launch(const cadnn_weights* w, const ConvVariant* v, co
     a.bias = (const float*)bias;
     a.residual = residual;
     a.nz = (const uint2*)plan->nz.p;
+    a.nz_off = (const uint16_t*)plan->nz_off.p;
     a.seg_ptr = (const int32_t*)plan->seg_ptr.p;
     a.perm = (const int32_t*)plan->perm.p;
     a.xd = g.xd; a.yd = yd; a.rd = rd;
@@ -282,6 +299,22 @@ static cadnn_status make_launch(const cadnn_weights* w, const ConvVariant* v, co
         a.pt_cch = pg.cch; a.pt_nstp = pg.nstp; a.pt_nchunks = pg.nchunks;
         a.pt_lds_bytes = (uint32_t)pg.lds_bytes;
         a.pt_nbuf = pg.nbuf;
+    } else if (v->family == FAM_WTILE) {
+        const WtileGeom wg = wtile_geom(*v, w->cin, w->kh, w->kw, g.stride);
+        if (wg.flat) {
+            a.tiles_x = (int)(((int64_t)g.n * g.hout * g.wout + wg.tile_w - 1) / wg.tile_w);
+            a.tiles_y = 1;
+        } else {
+            a.tiles_x = (g.wout + wg.tile_w - 1) / wg.tile_w;
+            a.tiles_y = (g.hout + wg.tile_h - 1) / wg.tile_h;
+        }
+        a.wt_tiles = a.tiles_x * a.tiles_y;
+        a.wt_lc = wg.lc; a.wt_ns = wg.ns; a.wt_pitch = wg.pitch; a.wt_sub = wg.sub; a.wt_plane = wg.plane;
+        a.wt_nphc = wg.nphc; a.wt_nph = wg.nphr * wg.nphc; a.wt_cch = wg.cch; a.wt_nstp = wg.nstp;
+        a.wt_nchunks = wg.nchunks; a.wt_nbuf = wg.nbuf;
+        a.wt_lds_bytes = (uint32_t)wg.lds_bytes;
+        auto magic = [](int d) { return (uint32_t)((((uint64_t)1 << 32) + (uint64_t)d - 1) / (uint64_t)d); };
+        a.wt_m_sub = magic(wg.sub); a.wt_m_pitch = magic(wg.pitch); a.wt_m_nphc = magic(wg.nphc);
     } else if (v->family == FAM_TILE || v->family == FAM_STILE) {
         a.tiles_x = (g.wout + v->tw - 1) / v->tw;
         a.tiles_y = (g.hout + v->th - 1) / v->th;
@@ -656,6 +689,67 @@ extern "C" cadnn_status cadnn_conv2d_list_variants(const cadnn_weights* w, int n
 extern "C" cadnn_status cadnn_conv2d_set_variant(const cadnn_weights* w, int n, int h, int wdt,
                                                  int stride, int pad, const char* name) {
     return conv2d_set_variant_impl(w, make_desc(w ? w->cin : 0, h, wdt), n, stride, pad, name);
+}
+
+// The variant `name` among those that serve the layer (NULL / "": the one that would be launched).
+static cadnn_status named_variant(const char* who, const cadnn_weights* w, const ConvGeom& g, const char* name,
+                                  const ConvVariant** out) {
+    *out = nullptr;
+    if (!name || !*name) {
+        *out = pick_variant(w, g);
+        if (!*out) return fail(CADNN_EUNSUPPORTED, "%s: no kernel for %dx%d filters with stride %d", who, w->kh, w->kw, g.stride);
+        return CADNN_OK;
+    }
+    for (const ConvVariant* v : candidates(w, g))
+        if (std::strcmp(v->name, name) == 0) { *out = v; return CADNN_OK; }
+    return fail(CADNN_EINVAL, "%s: '%s' does not serve this layer", who, name);
+}
+
+extern "C" cadnn_status cadnn_conv2d_plan_info(const cadnn_weights* w, int n, int h, int wdt, int stride, int pad,
+                                               const char* variant, cadnn_plan_info* out) {
+    if (!out) return fail(CADNN_EINVAL, "cadnn_conv2d_plan_info: NULL pointer");
+    ConvGeom g;
+    cadnn_status st = check_conv("cadnn_conv2d_plan_info", w, make_desc(w ? w->cin : 0, h, wdt), n, stride, pad, &g);
+    if (st != CADNN_OK) return st;
+    const ConvVariant* v = nullptr;
+    if ((st = named_variant("cadnn_conv2d_plan_info", w, g, variant, &v)) != CADNN_OK) return st;
+    ConvPlan plan;
+    if ((st = build_host_plan(w, v, g.xd, g.stride, g.pad, g.wout, &plan)) != CADNN_OK) return st;
+    cadnn_plan_info info{};
+    info.entries = plan.walked;
+    info.stream_bytes = plan.walked * plan.entry_bytes;
+    info.alloc_bytes = (int64_t)plan.nz.bytes + (int64_t)plan.nz_off.bytes;
+    info.table_bytes = (int64_t)plan.seg_ptr.bytes + (int64_t)plan.perm.bytes;
+    info.bytes_per_nonzero = w->nnz ? (double)info.stream_bytes / (double)w->nnz : 0.0;
+    info.chunks = 1;
+    info.lds_bytes = (int)v->lds_bytes;
+    if (v->family == FAM_WTILE) {
+        const WtileGeom wg = wtile_geom(*v, w->cin, w->kh, w->kw, g.stride);
+        info.chunks = wg.nchunks;
+        info.lds_bytes = (int)wg.lds_bytes;
+    } else if (v->family == FAM_PTILE) {
+        const PtileGeom pg = ptile_geom(*v, w->cin, w->kh, w->kw, g.stride, g.pad, g.wout);
+        info.chunks = pg.nchunks;
+        info.lds_bytes = (int)pg.lds_bytes;
+    } else if (v->family == FAM_TILE || v->family == FAM_STILE) {
+        info.chunks = plan.nchunks;
+    }
+    *out = info;
+    return CADNN_OK;
+}
+
+extern "C" cadnn_status cadnn_conv2d_plan_unpack(const cadnn_weights* w, int n, int h, int wdt, int stride, int pad,
+                                                 const char* variant, float* w_host_out) {
+    if (!w_host_out) return fail(CADNN_EINVAL, "cadnn_conv2d_plan_unpack: NULL pointer");
+    ConvGeom g;
+    cadnn_status st = check_conv("cadnn_conv2d_plan_unpack", w, make_desc(w ? w->cin : 0, h, wdt), n, stride, pad, &g);
+    if (st != CADNN_OK) return st;
+    const ConvVariant* v = nullptr;
+    if ((st = named_variant("cadnn_conv2d_plan_unpack", w, g, variant, &v)) != CADNN_OK) return st;
+    if (v->family != FAM_WTILE) return fail(CADNN_EUNSUPPORTED, "cadnn_conv2d_plan_unpack: '%s' has no compact tile-offset stream", v->name);
+    ConvPlan plan;
+    if ((st = build_host_plan(w, v, g.xd, g.stride, g.pad, g.wout, &plan)) != CADNN_OK) return st;
+    return wtile_plan_unpack(w, v, g.stride, plan, w_host_out);
 }
 
 extern "C" cadnn_status cadnn_sparse_fc(const cadnn_weights* w, const void* x, void* y, int n,

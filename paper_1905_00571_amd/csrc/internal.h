@@ -41,15 +41,12 @@ inline int conv_out(int size, int k, int stride, int pad) {
 struct DevBuf {
     void* p = nullptr;
     size_t bytes = 0;
+    bool on_host = false;     // filled while a HostPlans scope was alive: p is host memory
     DevBuf() = default;
     DevBuf(const DevBuf&) = delete;
     DevBuf& operator=(const DevBuf&) = delete;
     ~DevBuf() { release(); }
-    void release() {
-        if (p) (void)hipFree(p);
-        p = nullptr;
-        bytes = 0;
-    }
+    void release();
     // Allocates (at least 16 bytes so that p is never NULL) and uploads `n` bytes from host.
     cadnn_status upload(const void* host, size_t n);
 };
@@ -172,7 +169,14 @@ __device__ __forceinline__ void windowpool_element(const T* __restrict__ x, T* _
 //               the waves split G rows and each row's nonzeros between them, so a staged
 //               element is reused by every row of the group; entries are (value, byte
 //               offset of the tap in the staged tile).
-enum ConvFamily { FAM_TILE = 0, FAM_DIRECT = 1, FAM_LINEAR = 2, FAM_DENSE = 3, FAM_STILE = 4, FAM_PTILE = 5 };
+//  FAM_WTILE  : ("wide" tile) the workgroup stages one input tile in LDS as FAM_PTILE does, but
+//               a lane owns P = 4 or 8 output pixels whose activations lie side by side in the
+//               staged tile and arrive with ONE 128-bit LDS read per nonzero; the weight and
+//               the tile offset of a nonzero reach the FMAs and the address add as lane
+//               broadcasts inside those instructions (no scalar copy), and the stream is the
+//               compact one: 32-bit value + 16-bit tile offset (fp32 storage), or 16-bit value +
+//               16-bit tile offset (fp16 storage).
+enum ConvFamily { FAM_TILE = 0, FAM_DIRECT = 1, FAM_LINEAR = 2, FAM_DENSE = 3, FAM_STILE = 4, FAM_PTILE = 5, FAM_WTILE = 6 };
 
 struct ConvLaunch;
 constexpr int kMaxCoLaunch = 8;   // layers (and riding pools) one launch can hold
@@ -201,6 +205,8 @@ struct ConvVariant {
     int pool;             // FAM_LINEAR: global average pool fused into the epilogue
     int dw;               // FAM_LINEAR: a 3x3 depthwise layer fused into the epilogue
     int nz_cap;           // FAM_STILE: most stream entries per (row group, chunk) the kernel buffers
+    int flat;             // FAM_WTILE: 1 = pixel-wise layers (1x1 filters), pixels flattened over the batch;
+                          //            0 = filters with taps, lanes in an (rw x 64/rw) grid over a 2-D tile
     size_t lds_bytes;
     hipError_t (*launch)(const ConvLaunch&, hipStream_t);
     // several layers (at most kMaxCoLaunch) at once from a device table of launch records, of
@@ -216,6 +222,7 @@ struct ConvLaunch {
     const float* bias;
     const void* residual;
     const uint2* nz;          // plan entries, segment-padded
+    const uint16_t* nz_off;   // FAM_WTILE, fp32 storage: the entries' 16-bit tile offsets (nz holds the values)
     const int32_t* seg_ptr;   // plan segment table
     const int32_t* perm;      // [rows_padded] original channel, -1 for padding rows
     TensorDesc xd, yd, rd;    // layouts of x, y and residual
@@ -246,6 +253,11 @@ struct ConvLaunch {
     int pt_pitch, pt_sub, pt_plane, pt_nphc, pt_nph, pt_in_rows, pt_in_cols, pt_cch, pt_nstp, pt_nchunks;
     uint32_t pt_lds_bytes;
     int pt_nbuf;
+    // FAM_WTILE: geometry of the staged tile (see WtileGeom)
+    int wt_lc, wt_ns, wt_pitch, wt_sub, wt_plane, wt_nphc, wt_nph, wt_cch, wt_nstp, wt_nchunks, wt_nbuf;
+    int wt_tiles;             // pixel tiles per image (2-D tiles) or over the whole batch (flattened pixels)
+    uint32_t wt_m_sub, wt_m_pitch, wt_m_nphc;   // ceil(2^32 / d) for d = wt_sub, wt_pitch, wt_nphc: n / d = mulhi(n, m) for n < 2^16
+    uint32_t wt_lds_bytes;
     uint32_t image_bytes;     // xd.image * sizeof(element)
     // launches of several layers (launch_multi) may carry window pools among them: 0 = a
     // convolution, 1 = a k x k maximum pool, 2 = a k x k mean pool (x, y, xd, yd, stride, pad
@@ -257,12 +269,26 @@ struct ConvLaunch {
 struct ConvPlan {
     const ConvVariant* variant = nullptr;
     DevBuf nz, seg_ptr, perm;
+    DevBuf nz_off;            // FAM_WTILE, fp32 storage: 16-bit tile offsets, one per entry of nz
+    int64_t walked = 0;       // stream entries the kernels walk (real entries + the padding of the parts); the
+                              // fixed stride between the parts of some layouts leaves gaps that are never read
+    int entry_bytes = 8;      // bytes of one entry (value + index) as stored on the device
     int nchunks = 0;
     int rows_padded = 0;
     int64_t nz_padded = 0;
     // handed out for an ordinary launch (not only timed by a tuning pass): a captured graph or
     // a launch in flight may hold its device pointers, so it lives as long as the handle
     mutable bool in_use = false;
+};
+
+// While one of these is alive on a thread, DevBuf::upload keeps the data in host memory instead
+// of sending it to the device: device layouts can then be built, measured and decoded without
+// a GPU (cadnn_conv2d_plan_info, cadnn_conv2d_plan_unpack).
+struct HostPlans {
+    HostPlans();
+    ~HostPlans();
+    HostPlans(const HostPlans&) = delete;
+    HostPlans& operator=(const HostPlans&) = delete;
 };
 
 // While one of these is alive on a thread, the plans that thread asks for are trial plans of a
@@ -301,6 +327,37 @@ struct PtileGeom {
     size_t lds_bytes;
 };
 PtileGeom ptile_geom(const ConvVariant& v, int cin, int kh, int kw, int stride, int pad, int wout);   // v.is_f16 matters
+
+// Staged tile of the FAM_WTILE kernels for one layer geometry.  A lane owns P output pixels.
+//   flat = 1 (1x1 filters): the output pixels of the whole batch are numbered n * hout * wout + q and a
+//            tile is 64 * P consecutive ones, lane l owning pixels P*l .. P*l + P-1; a channel plane of
+//            the tile is those pixels' 64 * P activations in the same order.
+//   flat = 0: the lanes form an lr x lc grid (lane l -> row l % lr, column l / lr); pixel j of a lane
+//            lies lc * j columns to the right, so a tile is lr rows x lc * P columns of one image.  The
+//            staged region is de-interleaved by the stride into nphr x nphc phases; a row of a phase
+//            holds `ns` slots of P words -- word j of slot s is the phase's element at column
+//            s + lc * j -- so the P activations a lane needs for a tap are the 16 or 32 consecutive
+//            bytes of slot (lane column + tap column / stride).  Columns that two slots share are
+//            staged twice.  Rows are `nsp` >= ns slots apart, chosen so that 16 consecutive lanes
+//            read 16 different 16-byte bank groups.
+// A tap's offset in a chunk is a multiple of 16 bytes and is stored divided by 16, in 16 bits.
+struct WtileGeom {
+    int flat, S, P;
+    int lr, lc;               // lane grid (flat: 64 x 1)
+    int tile_h, tile_w;       // output pixels of a tile (flat: 1 x 64*P)
+    int nphr, nphc;           // phases used
+    int ph_rows, ns, nsp;     // rows per phase, slots used per row, slots between rows
+    int pitch, sub, plane;    // words per phase row / per phase / per channel
+    int nstp;                 // 64-word staging steps per channel
+    int cch, nchunks, nbuf;   // channels staged at a time, number of chunks, LDS buffers
+    size_t lds_bytes;
+};
+WtileGeom wtile_geom(const ConvVariant& v, int cin, int kh, int kw, int stride);
+constexpr int kWtileMaxSteps = 10;
+// LDS a workgroup may take: half of a compute unit's for the 8-wave instantiations (two
+// workgroups then share a compute unit and one computes while the other waits at a barrier),
+// all of it for the 16-wave ones (fewer, larger channel chunks)
+inline size_t wtile_lds_budget(const ConvVariant& v) { return v.nw >= 16 ? (size_t)160 * 1024 : (size_t)80 * 1024; }
 constexpr int kPtileMaxSteps = 9;
 constexpr size_t kLdsBytesPerCU = 160 * 1024;
 constexpr int kFcTailEntries = 1024;   // 4 loads x 64 lanes x 4 entries
@@ -320,6 +377,7 @@ const std::vector<ConvVariant>& all_linear_variants();
 const std::vector<ConvVariant>& all_dense_variants();
 const std::vector<ConvVariant>& all_stile_variants();
 const std::vector<ConvVariant>& all_ptile_variants();
+const std::vector<ConvVariant>& all_wtile_variants();
 
 }  // namespace cadnn
 
@@ -386,6 +444,11 @@ cadnn_status get_conv_plan(const cadnn_weights* w, const ConvVariant* v, const T
                            int pad, int wout, const ConvPlan** out, const ConvExtra* ex = nullptr,
                            std::shared_ptr<ConvPlan>* keep = nullptr);
 void drop_unpinned_plans(const cadnn_weights* w);
+// The plan of variant v for the layer, built in HOST memory (inside a HostPlans scope), never cached.
+cadnn_status build_host_plan(const cadnn_weights* w, const ConvVariant* v, const TensorDesc& xd, int stride,
+                             int pad, int wout, ConvPlan* plan);
+// Dense [cout][cin*kh*kw] tensor rebuilt from the stream of a host-built FAM_WTILE plan.
+cadnn_status wtile_plan_unpack(const cadnn_weights* w, const ConvVariant* v, int stride, const ConvPlan& plan, float* out);
 cadnn_status ensure_fc_device(const cadnn_weights* w);
 // A new handle whose rows are the rows of `parts` stacked in order (same cin, 1x1, same type):
 // the layers that read one tensor pixel by pixel, merged into one layer with more channels.

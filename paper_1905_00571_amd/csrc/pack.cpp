@@ -2,6 +2,7 @@
 // (paper Section 3: pruned weights are exact zeros kept with their indices; Section 4:
 // filter memory layout is transformed for the device) and the per-variant device plans.
 #include <algorithm>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <numeric>
@@ -23,9 +24,31 @@ cadnn_status fail(cadnn_status code, const char* fmt, ...) {
 }
 void clear_error() { g_last_error.clear(); }
 
+static thread_local int g_host_plans = 0;
+HostPlans::HostPlans() { ++g_host_plans; }
+HostPlans::~HostPlans() { --g_host_plans; }
+
+void DevBuf::release() {
+    if (p) {
+        if (on_host) std::free(p);
+        else (void)hipFree(p);
+    }
+    p = nullptr;
+    bytes = 0;
+    on_host = false;
+}
+
 cadnn_status DevBuf::upload(const void* host, size_t n) {
     release();
     const size_t alloc = n < 16 ? 16 : n;
+    if (g_host_plans > 0) {
+        p = std::calloc(alloc, 1);
+        if (!p) return fail(CADNN_ENOMEM, "out of host memory (%zu bytes)", alloc);
+        on_host = true;
+        bytes = alloc;
+        if (n) std::memcpy(p, host, n);
+        return CADNN_OK;
+    }
     hipError_t e = hipMalloc(&p, alloc);
     if (e != hipSuccess) {
         p = nullptr;
@@ -145,10 +168,12 @@ static cadnn_status build_tile_plan(const cadnn_weights* w, const ConvVariant* v
         seg[(size_t)i * (nchunks + 1) + nchunks] = (int32_t)nz.size();
     }
     if (nz.size() > (size_t)INT32_MAX) return fail(CADNN_EUNSUPPORTED, "plan too large");
+    const int64_t walked_entries = (int64_t)nz.size();
     plan->variant = v;
     plan->nchunks = nchunks;
     plan->rows_padded = rows_padded;
     plan->nz_padded = (int64_t)nz.size();
+    plan->walked = walked_entries;
     cadnn_status st;
     if ((st = plan->nz.upload(nz.data(), nz.size() * sizeof(uint2))) != CADNN_OK) return st;
     if ((st = plan->seg_ptr.upload(seg.data(), seg.size() * 4)) != CADNN_OK) return st;
@@ -200,10 +225,12 @@ static cadnn_status build_direct_plan(const cadnn_weights* w, const ConvVariant*
         }
     }
     if (nz.size() > (size_t)INT32_MAX) return fail(CADNN_EUNSUPPORTED, "plan too large");
+    const int64_t walked_entries = (int64_t)nz.size();
     plan->variant = v;
     plan->nchunks = 1;
     plan->rows_padded = rows_padded;
     plan->nz_padded = (int64_t)nz.size();
+    plan->walked = walked_entries;
     cadnn_status st;
     if ((st = plan->nz.upload(nz.data(), nz.size() * sizeof(uint2))) != CADNN_OK) return st;
     if ((st = plan->seg_ptr.upload(seg.data(), seg.size() * 4)) != CADNN_OK) return st;
@@ -261,6 +288,7 @@ static cadnn_status build_linear_plan(const cadnn_weights* w, const ConvVariant*
     std::vector<int32_t> hdr((size_t)rows_padded * ks * hw, 0);
     std::vector<int32_t> perm(rows_padded, -1);
     std::vector<uint2> nz((size_t)total, make_uint2(0u, 0u));
+    int64_t walked_entries = 0;
     for (int i = 0; i < rows_padded; ++i) {
         const int32_t b = i < w->cout ? w->row_ptr[i] : 0;
         const int32_t e = i < w->cout ? w->row_ptr[i + 1] : 0;
@@ -282,6 +310,7 @@ static cadnn_status build_linear_plan(const cadnn_weights* w, const ConvVariant*
                 out[j - pb] = make_uint2(bits, (uint32_t)off);
             }
             const int32_t len1 = (pe - pb + U - 1) / U * U;
+            walked_entries += len1;
             // (padding repeats the last real entry's offset with a zero weight: see pad_segment)
             for (int32_t j = pe - pb; j < len1 && pe > pb; ++j) out[j] = make_uint2(0u, out[pe - pb - 1].y);
             hdr[((size_t)i * ks + s) * hw + 0] = len1;
@@ -302,6 +331,7 @@ static cadnn_status build_linear_plan(const cadnn_weights* w, const ConvVariant*
                 const int32_t len2 = (qe - qb + U - 1) / U * U;
                 for (int32_t j = qe - qb; j < len2 && qe > qb; ++j) out[len1 + j] = make_uint2(0u, out[len1 + qe - qb - 1].y);
                 hdr[((size_t)i * ks + s) * hw + 2] = len2;
+                walked_entries += len2;
             }
         }
     }
@@ -309,6 +339,7 @@ static cadnn_status build_linear_plan(const cadnn_weights* w, const ConvVariant*
     plan->nchunks = (int)stride;
     plan->rows_padded = rows_padded;
     plan->nz_padded = (int64_t)nz.size();
+    plan->walked = walked_entries;
     cadnn_status st;
     if ((st = plan->nz.upload(nz.data(), nz.size() * sizeof(uint2))) != CADNN_OK) return st;
     if ((st = plan->seg_ptr.upload(hdr.data(), hdr.size() * 4)) != CADNN_OK) return st;
@@ -409,6 +440,8 @@ static cadnn_status build_ptile_plan(const cadnn_weights* w, const ConvVariant* 
     std::vector<int32_t> perm(rows_padded, -1);
     for (int i = 0; i < w->cout; ++i) perm[i] = w->perm[i];
     std::vector<uint2> nz((size_t)total, make_uint2(0u, 0u));
+    int64_t walked_entries = 0;
+    for (int32_t l : lens) walked_entries += l;
     for (int ws = 0; ws < nstreams; ++ws) {
         const int row0 = (ws / ks) * rpw, s = ws % ks;
         uint2* out = &nz[(size_t)ws * (size_t)stride];
@@ -434,10 +467,180 @@ static cadnn_status build_ptile_plan(const cadnn_weights* w, const ConvVariant* 
     plan->nchunks = (int)stride;
     plan->rows_padded = rows_padded;
     plan->nz_padded = (int64_t)nz.size();
+    plan->walked = walked_entries;
     cadnn_status st;
     if ((st = plan->nz.upload(nz.data(), nz.size() * sizeof(uint2))) != CADNN_OK) return st;
     if ((st = plan->seg_ptr.upload(lens.data(), lens.size() * 4)) != CADNN_OK) return st;
     if ((st = plan->perm.upload(perm.data(), perm.size() * 4)) != CADNN_OK) return st;
+    return CADNN_OK;
+}
+
+// Geometry of the staged tile of a FAM_WTILE variant for one layer (see WtileGeom).
+WtileGeom wtile_geom(const ConvVariant& v, int cin, int kh, int kw, int stride) {
+    WtileGeom g{};
+    g.flat = v.flat;
+    g.S = stride;
+    g.P = v.p;
+    if (g.flat) {
+        g.lr = 64; g.lc = 1;
+        g.tile_h = 1; g.tile_w = 64 * g.P;
+        g.nphr = g.nphc = 1;
+        g.ph_rows = 1;
+        g.ns = g.nsp = 64;
+        g.pitch = g.sub = g.plane = 64 * g.P;
+    } else {
+        g.lr = v.rw; g.lc = 64 / v.rw;
+        g.tile_h = g.lr; g.tile_w = g.lc * g.P;
+        g.nphr = std::min(stride, kh);
+        g.nphc = std::min(stride, kw);
+        g.ph_rows = g.lr + (kh - 1) / stride;
+        g.ns = g.lc + (kw - 1) / stride;
+        // 16 consecutive lanes are min(lr, 16) rows x 16 / min(lr, 16) columns of the lane grid and
+        // read slots (row * nsp + column + tap): they fall into 16 different 16-byte bank groups
+        // when nsp is an odd multiple of 16 / min(lr, 16), modulo 16
+        const int rows16 = std::min(g.lr, 16);
+        const int unit = 16 / rows16;
+        g.nsp = g.ns;
+        while (g.nsp % (2 * unit) != unit % (2 * unit)) ++g.nsp;
+        g.pitch = g.nsp * g.P;
+        g.sub = g.ph_rows * g.pitch;
+        g.plane = g.nphr * g.nphc * g.sub;
+    }
+    g.nstp = (g.plane + 63) / 64;
+    const size_t plane_bytes = (size_t)g.plane * 4;
+    const size_t budget = wtile_lds_budget(v);
+    if ((size_t)cin * plane_bytes <= budget) {
+        g.nbuf = 1; g.nchunks = 1; g.cch = cin;
+    } else {
+        // several chunks: chunk c+1 is staged into a second buffer while chunk c is consumed
+        g.nbuf = 2;
+        const int cch_max = (int)std::max<size_t>(1, budget / g.nbuf / plane_bytes);
+        g.nchunks = (cin + cch_max - 1) / cch_max;
+        g.cch = (cin + g.nchunks - 1) / g.nchunks;
+    }
+    g.lds_bytes = (size_t)g.nbuf * g.cch * plane_bytes;
+    return g;
+}
+
+// Packed row number r of wave stream ws: the rows of a workgroup (nw * rpw consecutive packed
+// rows, sorted by length) are dealt out to its waves round robin.
+static inline size_t wtile_row(int ws, int r, int nw, int rpw) {
+    return (size_t)(ws / nw) * (size_t)(nw * rpw) + (size_t)(ws % nw) + (size_t)nw * r;
+}
+
+// Host form of the nonzero stream of a FAM_WTILE variant (see build_wtile_plan).
+struct WtileStream {
+    WtileGeom g;
+    int rows_padded = 0, nstreams = 0;
+    int64_t stride = 0, total = 0;            // entries per wave stream, entries in all (spare blocks included)
+    std::vector<int32_t> lens;                // [stream][chunk][row of the wave] padded part lengths
+    std::vector<int32_t> perm;
+    std::vector<uint32_t> vals;               // fp32 storage: value bits; fp16 storage: value | offset << 16
+    std::vector<uint16_t> offs;               // fp32 storage only
+};
+
+// The input channels are cut into `nchunks` chunks of `cch`.  A wave serves RPW packed rows
+// (wtile_row); its
+// parts -- chunk by chunk, row by row within a chunk, each padded to 4 entries with zero-valued
+// entries that repeat the last real entry's offset -- lie back to back in one stream; stream w
+// starts at w * stride entries, stride = the longest stream rounded up to a block of 16, and
+// the table holds the padded part lengths [w][chunk][row].  An entry is the value and the
+// position of its tap in the staged chunk in units of 16 bytes (16 bits): two arrays in fp32
+// storage (6 bytes per entry), one word holding the binary16 value and the offset in fp16
+// storage (4 bytes).  Five spare blocks end the arrays: a wave reads two blocks ahead.
+static cadnn_status make_wtile_stream(const cadnn_weights* w, const ConvVariant* v, int conv_stride, WtileStream* out) {
+    WtileStream& st = *out;
+    const WtileGeom g = wtile_geom(*v, w->cin, w->kh, w->kw, conv_stride);
+    st.g = g;
+    const int rb = v->rows_per_block();
+    const int rows_padded = (w->cout + rb - 1) / rb * rb;
+    const int taps = w->kh * w->kw;
+    const int rpw = v->rpw;
+    const int nstreams = rows_padded / rpw;
+    const bool half = w->dtype == CADNN_F16;
+    st.rows_padded = rows_padded;
+    st.nstreams = nstreams;
+    std::vector<int32_t> cut((size_t)rows_padded * (g.nchunks + 1), 0);
+    for (int i = 0; i < w->cout; ++i) {
+        int32_t j = w->row_ptr[i];
+        const int32_t e = w->row_ptr[i + 1];
+        for (int c = 0; c < g.nchunks; ++c) {
+            cut[(size_t)i * (g.nchunks + 1) + c] = j;
+            const int32_t k_end = (int32_t)std::min<int64_t>((int64_t)(c + 1) * g.cch, w->cin) * taps;
+            while (j < e && w->col_idx[j] < k_end) ++j;
+        }
+        cut[(size_t)i * (g.nchunks + 1) + g.nchunks] = e;
+    }
+    st.lens.assign((size_t)nstreams * g.nchunks * rpw, 0);
+    int64_t stride = 16;
+    for (int ws = 0; ws < nstreams; ++ws) {
+        int64_t total = 0;
+        for (int c = 0; c < g.nchunks; ++c)
+            for (int r = 0; r < rpw; ++r) {
+                const size_t row = wtile_row(ws, r, v->nw, rpw);
+                const int32_t cnt = cut[row * (g.nchunks + 1) + c + 1] - cut[row * (g.nchunks + 1) + c];
+                const int32_t padded = (cnt + 3) / 4 * 4;
+                st.lens[((size_t)ws * g.nchunks + c) * rpw + r] = padded;
+                total += padded;
+            }
+        stride = std::max(stride, (total + 15) / 16 * 16);
+    }
+    const int64_t total = (int64_t)nstreams * stride + 80;
+    if (total > (int64_t)INT32_MAX / 2) return fail(CADNN_EUNSUPPORTED, "plan too large");
+    st.stride = stride;
+    st.total = total;
+    st.perm.assign(rows_padded, -1);
+    for (int i = 0; i < w->cout; ++i) st.perm[i] = w->perm[i];
+    st.vals.assign((size_t)total, 0u);
+    if (!half) st.offs.assign((size_t)total, 0);
+    for (int ws = 0; ws < nstreams; ++ws) {
+        size_t o = (size_t)ws * (size_t)stride;
+        for (int c = 0; c < g.nchunks; ++c)
+            for (int r = 0; r < rpw; ++r) {
+                const size_t row = wtile_row(ws, r, v->nw, rpw);
+                const int32_t pb = cut[row * (g.nchunks + 1) + c], pe = cut[row * (g.nchunks + 1) + c + 1];
+                const int32_t padded = st.lens[((size_t)ws * g.nchunks + c) * rpw + r];
+                uint32_t last_off = 0;
+                for (int32_t j = pb; j < pb + padded; ++j, ++o) {
+                    uint32_t bits = 0, hbits = 0;
+                    if (j < pe) {
+                        const int32_t k = w->col_idx[j];
+                        const int ci = k / taps - c * g.cch, tr = (k % taps) / w->kw, tc = k % w->kw;
+                        const int64_t word = g.flat ? (int64_t)ci * g.plane
+                                                    : (int64_t)ci * g.plane + (int64_t)((tr % g.S) * g.nphc + (tc % g.S)) * g.sub +
+                                                          (int64_t)(tr / g.S) * g.pitch + (int64_t)(tc / g.S) * g.P;
+                        if (word % 4 != 0 || word / 4 > 0xffff) return fail(CADNN_EUNSUPPORTED, "tile offset does not fit 16 bits");
+                        last_off = (uint32_t)(word / 4);
+                        std::memcpy(&bits, &w->vals[j], 4);
+                        if (half) hbits = w->vals16[j];
+                    }
+                    if (half) {
+                        st.vals[o] = hbits | (last_off << 16);
+                    } else {
+                        st.vals[o] = bits;
+                        st.offs[o] = (uint16_t)last_off;
+                    }
+                }
+            }
+    }
+    return CADNN_OK;
+}
+
+static cadnn_status build_wtile_plan(const cadnn_weights* w, const ConvVariant* v, int conv_stride, ConvPlan* plan) {
+    WtileStream st;
+    cadnn_status rc = make_wtile_stream(w, v, conv_stride, &st);
+    if (rc != CADNN_OK) return rc;
+    plan->variant = v;
+    plan->nchunks = (int)st.stride;
+    plan->rows_padded = st.rows_padded;
+    plan->nz_padded = st.total;
+    plan->walked = 0;
+    for (int32_t l : st.lens) plan->walked += l;
+    plan->entry_bytes = w->dtype == CADNN_F16 ? 4 : 6;
+    if ((rc = plan->nz.upload(st.vals.data(), st.vals.size() * 4)) != CADNN_OK) return rc;
+    if ((rc = plan->nz_off.upload(st.offs.data(), st.offs.size() * 2)) != CADNN_OK) return rc;
+    if ((rc = plan->seg_ptr.upload(st.lens.data(), st.lens.size() * 4)) != CADNN_OK) return rc;
+    if ((rc = plan->perm.upload(st.perm.data(), st.perm.size() * 4)) != CADNN_OK) return rc;
     return CADNN_OK;
 }
 
@@ -529,10 +732,12 @@ static cadnn_status build_stile_plan(const cadnn_weights* w, const ConvVariant* 
         }
     }
     if (nz.size() > (size_t)INT32_MAX) return fail(CADNN_EUNSUPPORTED, "plan too large");
+    const int64_t walked_entries = (int64_t)nz.size();
     plan->variant = v;
     plan->nchunks = nchunks;
     plan->rows_padded = rows_padded;
     plan->nz_padded = (int64_t)nz.size();
+    plan->walked = walked_entries;
     cadnn_status st;
     if ((st = plan->nz.upload(nz.data(), nz.size() * sizeof(uint2))) != CADNN_OK) return st;
     if ((st = plan->seg_ptr.upload(seg.data(), seg.size() * 4)) != CADNN_OK) return st;
@@ -547,6 +752,8 @@ static cadnn_status build_dense_plan(const cadnn_weights* w, const ConvVariant* 
     plan->nchunks = 1;
     plan->rows_padded = (w->cout + 63) / 64 * 64;
     plan->nz_padded = (int64_t)((size_t)w->cout * K);
+    plan->walked = plan->nz_padded;
+    plan->entry_bytes = (int)w->elem();
     cadnn_status st;
     if (w->dtype == CADNN_F16) {
         std::vector<uint16_t> dense((size_t)w->cout * K, 0);
@@ -569,12 +776,68 @@ static cadnn_status build_plan(const cadnn_weights* w, const ConvVariant* v, con
     if (ex && v->family != FAM_LINEAR) return fail(CADNN_EINVAL, "a fused shortcut or pool needs a linear-address kernel");
     switch (v->family) {
         case FAM_PTILE: return build_ptile_plan(w, v, stride, pad, wout, plan);
+        case FAM_WTILE: return build_wtile_plan(w, v, stride, plan);
         case FAM_DENSE: return build_dense_plan(w, v, plan);
         case FAM_STILE: return build_stile_plan(w, v, plan);
         case FAM_DIRECT: return build_direct_plan(w, v, plan);
         case FAM_LINEAR: return build_linear_plan(w, v, xd, plan, ex);
         default: return build_tile_plan(w, v, plan);
     }
+}
+
+cadnn_status build_host_plan(const cadnn_weights* w, const ConvVariant* v, const TensorDesc& xd, int stride,
+                             int pad, int wout, ConvPlan* plan) {
+    const HostPlans host;
+    try {
+        return build_plan(w, v, xd, stride, pad, wout, plan, nullptr);
+    } catch (const std::bad_alloc&) {
+        return fail(CADNN_ENOMEM, "out of host memory building a conv plan");
+    }
+}
+
+// The inverse of make_wtile_stream's layout transformation: every entry's 16-bit tile offset is
+// taken apart into (channel, tap) again and its value added to that position of the row (the
+// zero-valued padding entries add nothing).
+cadnn_status wtile_plan_unpack(const cadnn_weights* w, const ConvVariant* v, int stride, const ConvPlan& plan, float* out) {
+    if (v->family != FAM_WTILE || !plan.nz.on_host) return fail(CADNN_EINVAL, "not a host-built wide-tile plan");
+    const WtileGeom g = wtile_geom(*v, w->cin, w->kh, w->kw, stride);
+    const int64_t K = (int64_t)w->cin * w->kh * w->kw;
+    std::memset(out, 0, (size_t)w->cout * K * sizeof(float));
+    const bool half = w->dtype == CADNN_F16;
+    const uint32_t* vals = (const uint32_t*)plan.nz.p;
+    const uint16_t* offs = (const uint16_t*)plan.nz_off.p;
+    const int32_t* lens = (const int32_t*)plan.seg_ptr.p;
+    const int32_t* perm = (const int32_t*)plan.perm.p;
+    const int rpw = v->rpw, nstreams = plan.rows_padded / rpw;
+    for (int ws = 0; ws < nstreams; ++ws) {
+        size_t o = (size_t)ws * (size_t)plan.nchunks;
+        for (int c = 0; c < g.nchunks; ++c)
+            for (int r = 0; r < rpw; ++r) {
+                const int co = perm[wtile_row(ws, r, v->nw, rpw)];
+                const int32_t len = lens[((size_t)ws * g.nchunks + c) * rpw + r];
+                for (int32_t j = 0; j < len; ++j, ++o) {
+                    const uint32_t off16 = half ? vals[o] >> 16 : offs[o];
+                    const float val = half ? f16_to_f32((uint16_t)(vals[o] & 0xffffu)) : [&] { float f; std::memcpy(&f, &vals[o], 4); return f; }();
+                    if (co < 0) {
+                        if (val != 0.0f) return fail(CADNN_EINVAL, "a padding row carries a value");
+                        continue;
+                    }
+                    const int64_t word = (int64_t)off16 * 4;
+                    const int ci = (int)(word / g.plane) + c * g.cch;
+                    int tr = 0, tc = 0;
+                    if (!g.flat) {
+                        const int64_t rem = word % g.plane;
+                        const int phase = (int)(rem / g.sub), q = (int)(rem % g.sub);
+                        tr = (q / g.pitch) * g.S + phase / g.nphc;
+                        tc = ((q % g.pitch) / g.P) * g.S + phase % g.nphc;
+                        if ((q % g.pitch) % g.P != 0) return fail(CADNN_EINVAL, "an offset does not point at a slot");
+                    }
+                    if (ci >= w->cin || tr >= w->kh || tc >= w->kw) return fail(CADNN_EINVAL, "an offset decodes to no tap of the filter");
+                    out[(int64_t)co * K + ((int64_t)ci * w->kh + tr) * w->kw + tc] += val;
+                }
+            }
+    }
+    return CADNN_OK;
 }
 
 static PlanKey plan_key(const cadnn_weights* w, const ConvVariant* v, const TensorDesc& xd, int stride, int pad,
@@ -584,6 +847,7 @@ static PlanKey plan_key(const cadnn_weights* w, const ConvVariant* v, const Tens
                        (ex && ex->w) ? ex->xd.plane : 0);
     if (v->family == FAM_PTILE)
         return PlanKey(v, stride, ptile_geom(*v, w->cin, w->kh, w->kw, stride, pad, wout).alias, nullptr, 0);
+    if (v->family == FAM_WTILE) return PlanKey(v, stride, 0, nullptr, 0);
     return PlanKey(v, 0, 0, nullptr, 0);
 }
 
