@@ -72,7 +72,8 @@ def layer_costs(ops, weights, in_shape, elem):
     return rows
 
 
-KERNEL_OF_PREFIX = {"slinear": "sconv_linear_kernel", "stile": "sconv_stile_kernel",
+KERNEL_OF_PREFIX = {"slinear": "sconv_linear_kernel", "stile": "sconv_stile_kernel", "sptile": "sconv_ptile_kernel",
+                    "swide": "sconv_wtile_kernel",
                     "sdirect": "sconv_direct_kernel", "sconv": "sconv_tile_kernel",
                     "dense": "dense_conv_kernel", "sfc": "sfc_kernel", "dwconv": "dwconv_kernel", "maxpool": "windowpool_kernel",
                     "avgpool": "avgpool_kernel", "avgpool2d": "windowpool_kernel", "concat": "windowpool_kernel",
@@ -112,10 +113,12 @@ def main() -> int:
     ap.add_argument("--batch", type=int, default=1)
     ap.add_argument("--sparsity", type=float, default=0.8, help="uniform sparsity of workload c3")
     ap.add_argument("--dtype", choices=["f32", "f16"], default="", help="storage type (default f32; c3: f16)")
-    ap.add_argument("--dense-compare", action="store_true",
-                    help="also time every distinct convolution of the workload as a DENSE layer on the same GPU: "
-                         "the library's own MFMA implicit GEMM and MIOpen through torch.nn.functional.conv2d "
-                         "(the only use of torch compute anywhere: a comparator)")
+    ap.add_argument("--dense-compare", action="store_true", default=None,
+                    help="also time every distinct convolution shape of the workload as a DENSE layer on the same "
+                         "GPU: the library's own MFMA implicit GEMM and MIOpen through torch.nn.functional.conv2d "
+                         "(the only use of torch compute anywhere: a comparator).  On by default for the metric's "
+                         "workload (a few seconds)")
+    ap.add_argument("--no-dense-compare", dest="dense_compare", action="store_false")
     ap.add_argument("--no-fusion", action="store_true", help="launch every op on its own (CADNN_NET_NO_FUSION)")
     ap.add_argument("--plain-layout", action="store_true", help="no de-interleaved tensors (CADNN_NET_PLAIN_LAYOUT)")
     ap.add_argument("--no-layer-profile", action="store_true",
@@ -190,6 +193,8 @@ def main() -> int:
     y = torch.empty(net.out_shape, dtype=tdt, device="cuda")
     stream = torch.cuda.current_stream()
 
+    if args.dense_compare is None:
+        args.dense_compare = is_default
     for _ in range(max(args.warmup, 1)):
         net.run(xd, y, stream)
     torch.cuda.synchronize()
@@ -199,6 +204,17 @@ def main() -> int:
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    # the spread of single passes: one event between consecutive passes of a second, untimed run
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(min(args.steps, 500) + 1)]
+    marks[0].record(stream)
+    for m in marks[1:]:
+        net.run(xd, y, stream)
+        m.record(stream)
+    torch.cuda.synchronize()
+    per_pass = np.array([a_.elapsed_time(b_) for a_, b_ in zip(marks[:-1], marks[1:])])
+    pass_ms = {"p10": float(np.percentile(per_pass, 10)), "median": float(np.median(per_pass)),
+               "p90": float(np.percentile(per_pass, 90))}
 
     # single-inference latency with a host sync after every pass (median)
     lat = []
@@ -248,7 +264,14 @@ def main() -> int:
     copy_gbs = 2.0 * (512 << 20) / (float(np.median(copy_ms)) * 1e-3) / 1e9
     del big_a, big_b
 
-    per_op_ms = net.profile(xd, y, repeats=20, stream=stream)
+    # per-op device time, two ways: every op 20 times back to back (warm caches), and the ops in
+    # launch order as a forward pass runs them, every kernel carrying its own start and stop
+    # marks.  The second is what the kernels take inside a pass -- the figure a rocprofv3 kernel
+    # trace of this command reports -- and is the one used below.
+    per_op_ms_warm = net.profile(xd, y, repeats=20, stream=stream)
+    per_op_ms = net.profile_in_order(xd, y, repeats=30, stream=stream)
+    scratch = torch.zeros(64, dtype=torch.uint8, device="cuda")
+    floor_us = cad.cadnn_graph_launch_floor(scratch, 64, 20, stream)
     costs = layer_costs(ops, ws, shape, elem)
     groups = {}
     names = [net.op_variant(i) for i in range(len(ops))]
@@ -295,14 +318,18 @@ def main() -> int:
     for i, op in enumerate(ops):
         name = names[i]
         costs[i]["kernel"] = name
+        if name in ("fused", "in place"):
+            per_op_ms[i] = 0.0
         costs[i]["ms"] = float(per_op_ms[i])
+        costs[i]["ms_warm"] = float(per_op_ms_warm[i])
         t = costs[i]["ms"] * 1e-3
         costs[i]["gflops"] = costs[i]["flops"] / t / 1e9 if t > 0 else 0.0
         costs[i]["gbs"] = costs[i]["bytes"] / t / 1e9 if t > 0 else 0.0
         costs[i]["frac_hbm"] = costs[i]["gbs"] / HBM_PEAK_GBS
         costs[i]["frac_fp32"] = costs[i]["gflops"] / (FP32_VECTOR_TFLOPS * 1e3)
-        g = groups.setdefault(kernel_of(name), {"ms": 0.0, "launches": 0, "flops": 0.0, "bytes": 0.0})
+        g = groups.setdefault(kernel_of(name), {"ms": 0.0, "ms_warm": 0.0, "launches": 0, "flops": 0.0, "bytes": 0.0})
         g["ms"] += costs[i]["ms"]
+        g["ms_warm"] += costs[i]["ms_warm"]
         g["launches"] += 1
         g["flops"] += costs[i]["flops"]
         g["bytes"] += costs[i]["bytes"]
@@ -323,8 +350,13 @@ def main() -> int:
             measured = json.load(f).get("kernels", {})
         if dom_name in measured:
             roofline["traffic"] = measured[dom_name]["hbm_bytes_per_launch"]
+            roofline["traffic_source"] = ("not measured in this run: FETCH_SIZE + WRITE_SIZE of the committed rocprofv3 "
+                                          "--pmc runs of this command (profiles/), read from " + os.path.relpath(args.traffic, ROOT))
     roofline.update({"kernel": dom_name, "launches_per_step": dom["launches"],
                      "avg_launch_us": avg_s * 1e6,
+                     "avg_launch_us_warm": dom["ms_warm"] * 1e3 / dom["launches"],
+                     "timing": "ops in launch order, each kernel's own start/stop marks "
+                               "(avg_launch_us_warm: each op 20x back to back between two events)",
                      "algorithmic_flops_per_launch": dom["flops"] / dom["launches"],
                      "algorithmic_bytes_per_launch": dom["bytes"] / dom["launches"]})
 
@@ -333,9 +365,7 @@ def main() -> int:
     # ---- the same layers as dense convolutions on this GPU (comparators)
     dense_cmp = None
     if args.dense_compare:
-        torch.backends.cudnn.benchmark = True
-
-        def time_us(fn, reps=30):
+        def time_us(fn, reps=10):
             for _ in range(5):
                 fn()
             a_ = torch.cuda.Event(enable_timing=True)
@@ -435,6 +465,10 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": desc, "graph": not args.no_graph, "per_layer_kernel_tuning": tuning},
         "images_per_s": n * 1e3 / ms_per_step,
+        "ms_per_step_spread": pass_ms,
+        "launches_per_step": int(sum(1 for nm in names if nm not in ("fused", "in place"))),
+        "graph_kernel_boundary_us": floor_us,
+        "launch_floor_ms": floor_us * 1e-3 * sum(1 for nm in names if nm not in ("fused", "in place")),
         "latency_with_host_sync_ms": lat_sync_ms,
         "latency_cold_caches_ms": lat_cold_ms,
         "measured_copy_rate_gbs": copy_gbs,
@@ -442,6 +476,7 @@ def main() -> int:
         "effective_gflops_nonzero_macs": total_flops / (ms_per_step * 1e-3) / 1e9,
         "effective_gbs_algorithmic": total_bytes / (ms_per_step * 1e-3) / 1e9,
         "sum_of_kernel_ms": float(per_op_ms.sum()),
+        "sum_of_kernel_ms_warm": float(per_op_ms_warm.sum()),
         "roofline": roofline,
         "cpu_baseline": cpu,
         "paper_context": "26 ms (title) / 21 ms (text) ResNet-50 on a Snapdragon 835 phone; other hardware, not a target",

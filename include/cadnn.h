@@ -231,6 +231,13 @@ cadnn_status cadnn_conv2d_plan_unpack(const cadnn_weights* w, int n, int h, int 
  * known exactly and against which hardware traffic counters are calibrated. */
 cadnn_status cadnn_device_copy(const void* src, void* dst, size_t bytes, void* stream);
 
+/* Measurement aid: the cost of one kernel boundary inside a replayed HIP graph, in
+ * microseconds: `launches` (1..4096) dependent 16-byte copies are captured into a graph that
+ * is replayed `reps` times on `stream` between two events.  scratch32: 32 bytes of device
+ * memory the copies may overwrite.  Synchronises. */
+cadnn_status cadnn_graph_launch_floor(void* scratch32, int launches, int reps, void* stream,
+                                      float* us_per_launch);
+
 /* Dense comparator on the same ABI (implicit-GEMM convolution over the dense
  * [cout][cin][kh][kw] DEVICE weight tensor, same fused epilogue), used for the
  * dense-vs-compressed comparison the paper reports (Section 5) and as the
@@ -355,6 +362,14 @@ cadnn_status cadnn_run_net(cadnn_net* net, const void* x, void* y, void* stream)
 cadnn_status cadnn_net_num_ops(const cadnn_net* net, int* num_ops);
 cadnn_status cadnn_net_profile(cadnn_net* net, const void* x, void* y, void* stream, int repeats,
                                float* ms_per_op);
+/* The same per-op times with the ops in launch order, as a forward pass runs them: an op then
+ * finds the caches as the real pass leaves them (input just written by its producer, weights
+ * last touched a pass ago) and not warm from its own previous launch.  Every kernel is
+ * launched with start and stop marks of its own, so ms_per_op[i] is the device time of op i's
+ * kernels and nothing else (what a kernel trace of the same pass reports), averaged over
+ * `repeats` passes; 0 for ops that launch nothing.  Synchronises the stream. */
+cadnn_status cadnn_net_profile_in_order(cadnn_net* net, const void* x, void* y, void* stream, int repeats,
+                                        float* ms_per_op);
 /* Name of the kernel serving op `op_index` (a conv variant name, "dwconv", "sfc", "maxpool",
  * "avgpool2d", "avgpool", "concat", or "fused" / "in place" for an op that launches nothing),
  * NUL-terminated into buf. */

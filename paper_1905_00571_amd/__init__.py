@@ -23,6 +23,7 @@ from .binding import (  # noqa: F401
     cadnn_conv2d_variant_name,
     cadnn_conv2d_list_variants,
     cadnn_conv2d_plan_info,
+    cadnn_graph_launch_floor,
     cadnn_conv2d_plan_unpack,
     cadnn_conv2d_set_variant,
     cadnn_conv2d_tune,

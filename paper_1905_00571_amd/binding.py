@@ -100,7 +100,9 @@ def lib() -> ctypes.CDLL:
         "cadnn_net_op_info": (_i, [_vp, _i, _i, ctypes.POINTER(OpInfo)]),
         "cadnn_run_net": (_i, [_vp, _vp, _vp, _vp]),
         "cadnn_net_num_ops": (_i, [_vp, ctypes.POINTER(_i)]),
+        "cadnn_graph_launch_floor": (_i, [_vp, _i, _i, _vp, _f32p]),
         "cadnn_net_profile": (_i, [_vp, _vp, _vp, _vp, _i, _f32p]),
+        "cadnn_net_profile_in_order": (_i, [_vp, _vp, _vp, _vp, _i, _f32p]),
         "cadnn_net_op_variant": (_i, [_vp, _i, ctypes.c_char_p, ctypes.c_size_t]),
         "cadnn_net_op_candidates": (_i, [_vp, _i, ctypes.c_char_p, ctypes.c_size_t]),
         "cadnn_net_set_op_variant": (_i, [_vp, _i, ctypes.c_char_p]),
@@ -209,6 +211,13 @@ def cadnn_conv2d_list_variants(w: Weights, n: int, h: int, wdt: int, stride: int
     _check(lib().cadnn_conv2d_list_variants(w.handle, n, h, wdt, stride, pad, buf, 1 << 16))
     text = buf.value.decode()
     return text.split("\n") if text else []
+
+
+def cadnn_graph_launch_floor(scratch, launches: int = 64, reps: int = 20, stream=None) -> float:
+    """Microseconds per kernel boundary inside a replayed graph (scratch: >= 32 bytes on the device)."""
+    us = ctypes.c_float(0.0)
+    _check(lib().cadnn_graph_launch_floor(_dptr(scratch), launches, reps, _stream_ptr(stream), ctypes.byref(us)))
+    return float(us.value)
 
 
 def cadnn_conv2d_plan_info(w: Weights, n: int, h: int, wdt: int, stride: int, pad: int,
@@ -405,6 +414,13 @@ class Net:
         ms = np.zeros(self.num_ops(), np.float32)
         _check(lib().cadnn_net_profile(self.handle, _dptr(x), _dptr(y), _stream_ptr(stream), repeats,
                                        ms.ctypes.data_as(_f32p)))
+        return ms
+
+    def profile_in_order(self, x, y, repeats: int = 10, stream=None) -> np.ndarray:
+        """ms per op with the ops in launch order (each kernel's own device time)."""
+        ms = np.zeros(self.num_ops(), np.float32)
+        _check(lib().cadnn_net_profile_in_order(self.handle, _dptr(x), _dptr(y), _stream_ptr(stream), repeats,
+                                                ms.ctypes.data_as(_f32p)))
         return ms
 
     def op_variant(self, op_index: int) -> str:

@@ -806,6 +806,46 @@ extern "C" cadnn_status cadnn_device_copy(const void* src, void* dst, size_t byt
     return launch_copy(src, dst, bytes, (hipStream_t)stream);
 }
 
+// Measurement aid: what one kernel boundary costs inside a replayed HIP graph.  `launches`
+// dependent 16-byte copies (the smallest kernel of the library) are captured into one graph,
+// which is replayed `reps` times between two events.
+extern "C" cadnn_status cadnn_graph_launch_floor(void* scratch32, int launches, int reps, void* stream,
+                                                 float* us_per_launch) {
+    if (!scratch32 || !us_per_launch) return fail(CADNN_EINVAL, "cadnn_graph_launch_floor: NULL pointer");
+    if (launches <= 0 || launches > 4096 || reps <= 0) return fail(CADNN_EINVAL, "cadnn_graph_launch_floor: bad count");
+    hipStream_t s = (hipStream_t)stream;
+    hipStream_t cs = nullptr;
+    CADNN_HIP(hipStreamCreateWithFlags(&cs, hipStreamNonBlocking));
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t exec = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    cadnn_status st = CADNN_OK;
+    hipError_t e = hipStreamBeginCapture(cs, hipStreamCaptureModeThreadLocal);
+    if (e != hipSuccess) st = fail(CADNN_EHIP, "hipStreamBeginCapture failed: %s", hipGetErrorString(e));
+    if (st == CADNN_OK) {
+        for (int i = 0; i < launches && st == CADNN_OK; ++i) st = launch_copy(scratch32, (char*)scratch32 + 16, 16, cs);
+        e = hipStreamEndCapture(cs, &graph);
+        if (st == CADNN_OK && e != hipSuccess) st = fail(CADNN_EHIP, "hipStreamEndCapture failed: %s", hipGetErrorString(e));
+    }
+    if (st == CADNN_OK && hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0) != hipSuccess) st = fail(CADNN_EHIP, "hipGraphInstantiate failed");
+    if (st == CADNN_OK && (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)) st = fail(CADNN_EHIP, "hipEventCreate failed");
+    if (st == CADNN_OK) {
+        bool ok = hipGraphLaunch(exec, s) == hipSuccess && hipEventRecord(e0, s) == hipSuccess;
+        for (int r = 0; r < reps && ok; ++r) ok = hipGraphLaunch(exec, s) == hipSuccess;
+        ok = ok && hipEventRecord(e1, s) == hipSuccess && hipEventSynchronize(e1) == hipSuccess;
+        float ms = 0.0f;
+        ok = ok && hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
+        if (!ok) st = fail(CADNN_EHIP, "cadnn_graph_launch_floor: replay failed");
+        else *us_per_launch = ms * 1e3f / (float)reps / (float)launches;
+    }
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (exec) (void)hipGraphExecDestroy(exec);
+    if (graph) (void)hipGraphDestroy(graph);
+    (void)hipStreamDestroy(cs);
+    return st;
+}
+
 extern "C" cadnn_status cadnn_maxpool2d(const void* x, void* y, int n, int c, int h, int wdt, int k,
                                         int stride, int pad, cadnn_dtype dtype, void* stream) {
     if (!x || !y) return fail(CADNN_EINVAL, "cadnn_maxpool2d: NULL tensor");

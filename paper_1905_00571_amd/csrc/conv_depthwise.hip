@@ -94,7 +94,7 @@ __global__ __launch_bounds__(256) void dwconv_kernel(DwLaunch a) {
 template <typename T, int KH, int KW, int S, int P, bool HALO>
 static hipError_t launch_dw(const DwLaunch& a, hipStream_t s) {
     const long long blocks = (a.waves + 3) / 4;
-    hipLaunchKernelGGL((dwconv_kernel<T, KH, KW, S, P, HALO>), dim3((unsigned)blocks), dim3(256), 0, s, a);
+    CADNN_LAUNCH((dwconv_kernel<T, KH, KW, S, P, HALO>), dim3((unsigned)blocks), dim3(256), 0, s, a);
     return hipGetLastError();
 }
 

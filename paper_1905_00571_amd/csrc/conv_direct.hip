@@ -163,7 +163,7 @@ template <class Cfg>
 static hipError_t launch_direct(const ConvLaunch& a, hipStream_t s) {
     dim3 grid((unsigned)a.tiles_x, (unsigned)a.row_groups, (unsigned)a.n);
     dim3 block(Cfg::THREADS);
-    hipLaunchKernelGGL(sconv_direct_kernel<Cfg>, grid, block, 0, s, a);
+    CADNN_LAUNCH(sconv_direct_kernel<Cfg>, grid, block, 0, s, a);
     return hipGetLastError();
 }
 

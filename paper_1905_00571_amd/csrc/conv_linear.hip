@@ -546,7 +546,7 @@ template <class Cfg>
 static hipError_t launch_linear(const ConvLaunch& a, hipStream_t s) {
     dim3 grid((unsigned)a.tiles_x, (unsigned)a.row_groups, (unsigned)a.n);
     dim3 block(Cfg::THREADS);
-    hipLaunchKernelGGL(sconv_linear_kernel<Cfg>, grid, block, 0, s, a);
+    CADNN_LAUNCH(sconv_linear_kernel<Cfg>, grid, block, 0, s, a);
     return hipGetLastError();
 }
 
@@ -562,7 +562,7 @@ static hipError_t launch_linear_multi(const ConvLaunch* table, const ConvLaunch*
     for (int k = layers; k <= kMaxCoLaunch; ++k) h.first[k] = total;
     dim3 grid((unsigned)total, (unsigned)images, 1);
     dim3 block(Cfg::THREADS);
-    hipLaunchKernelGGL(sconv_linear_multi_kernel<Cfg>, grid, block, 0, s, table, h, layers);
+    CADNN_LAUNCH(sconv_linear_multi_kernel<Cfg>, grid, block, 0, s, table, h, layers);
     return hipGetLastError();
 }
 

@@ -315,7 +315,7 @@ static hipError_t launch_ptile(const ConvLaunch& a, hipStream_t s) {
     if (attr != hipSuccess) return attr;
     dim3 grid((unsigned)(a.tiles_x * a.tiles_y), (unsigned)a.row_groups, (unsigned)a.n);
     dim3 block(Cfg::THREADS);
-    hipLaunchKernelGGL(sconv_ptile_kernel<Cfg>, grid, block, a.pt_lds_bytes, s, a);
+    CADNN_LAUNCH(sconv_ptile_kernel<Cfg>, grid, block, a.pt_lds_bytes, s, a);
     return hipGetLastError();
 }
 

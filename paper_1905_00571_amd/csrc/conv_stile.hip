@@ -284,7 +284,7 @@ hipError_t launch_stile(const ConvLaunch& a, hipStream_t s) {
     }
     dim3 grid((unsigned)(a.tiles_x * a.tiles_y), (unsigned)a.row_groups, (unsigned)a.n);
     dim3 block(Cfg::THREADS);
-    hipLaunchKernelGGL(sconv_stile_kernel<Cfg>, grid, block, Cfg::LDS_BYTES, s, a);
+    CADNN_LAUNCH(sconv_stile_kernel<Cfg>, grid, block, Cfg::LDS_BYTES, s, a);
     return hipGetLastError();
 }
 

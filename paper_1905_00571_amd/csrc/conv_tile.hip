@@ -191,7 +191,7 @@ template <class Cfg>
 static hipError_t launch_tile(const ConvLaunch& a, hipStream_t s) {
     dim3 grid((unsigned)(a.tiles_x * a.tiles_y), (unsigned)a.row_groups, (unsigned)a.n);
     dim3 block(Cfg::THREADS);
-    hipLaunchKernelGGL(sconv_tile_kernel<Cfg>, grid, block, 0, s, a);
+    CADNN_LAUNCH(sconv_tile_kernel<Cfg>, grid, block, 0, s, a);
     return hipGetLastError();
 }
 

@@ -390,7 +390,7 @@ static hipError_t launch_wtile(const ConvLaunch& a, hipStream_t s) {
     if (attr != hipSuccess) return attr;
     dim3 grid((unsigned)a.wt_tiles, (unsigned)a.row_groups, Cfg::FLAT ? 1u : (unsigned)a.n);
     dim3 block(Cfg::THREADS);
-    hipLaunchKernelGGL(sconv_wtile_kernel<Cfg>, grid, block, a.wt_lds_bytes, s, a);
+    CADNN_LAUNCH(sconv_wtile_kernel<Cfg>, grid, block, a.wt_lds_bytes, s, a);
     return hipGetLastError();
 }
 

@@ -193,9 +193,9 @@ cadnn_status dense_conv2d_desc(const void* w_dev, const void* x, const TensorDes
     a.magic_kw = magic_for((uint32_t)kw);
     dim3 grid((unsigned)((a.hwout + BN - 1) / BN), (unsigned)((cout + BM - 1) / BM), (unsigned)n);
     if (dtype == CADNN_F16)
-        hipLaunchKernelGGL(dense_conv_kernel<_Float16>, grid, dim3(256), 0, s, a);
+        CADNN_LAUNCH(dense_conv_kernel<_Float16>, grid, dim3(256), 0, s, a);
     else
-        hipLaunchKernelGGL(dense_conv_kernel<float>, grid, dim3(256), 0, s, a);
+        CADNN_LAUNCH(dense_conv_kernel<float>, grid, dim3(256), 0, s, a);
     CADNN_HIP(hipGetLastError());
     return CADNN_OK;
 }

@@ -37,6 +37,32 @@ inline int conv_out(int size, int k, int stride, int pad) {
     return t < 0 ? 0 : (int)std::min<int64_t>(t / stride + 1, INT32_MAX);
 }
 
+// ---- kernel launches -----------------------------------------------------------
+// Every kernel of the library is launched through CADNN_LAUNCH.  Normally that is a plain
+// launch.  While a LaunchTimer is installed on the thread (the in-order profile of a net), the
+// launch takes the next pair of its events as the kernel's own start and stop marks, so that
+// the elapsed time between them is the kernel's duration on the device and nothing else.
+struct LaunchTimer {
+    static constexpr int kMax = 8;                 // kernels one op may launch while timed
+    hipEvent_t start[kMax], stop[kMax];
+    int used = 0;
+};
+extern thread_local LaunchTimer* g_launch_timer;
+}  // namespace cadnn
+#include <hip/hip_ext.h>
+#define CADNN_LAUNCH(kernel, grid, block, shmem, stream, ...)                                                  \
+    do {                                                                                                       \
+        ::cadnn::LaunchTimer* lt_ = ::cadnn::g_launch_timer;                                                   \
+        if (lt_ && lt_->used < ::cadnn::LaunchTimer::kMax) {                                                   \
+            hipExtLaunchKernelGGL(kernel, grid, block, shmem, stream, lt_->start[lt_->used], lt_->stop[lt_->used], \
+                                  0, __VA_ARGS__);                                                             \
+            ++lt_->used;                                                                                       \
+        } else {                                                                                               \
+            hipLaunchKernelGGL(kernel, grid, block, shmem, stream, __VA_ARGS__);                               \
+        }                                                                                                      \
+    } while (0)
+namespace cadnn {
+
 // ---- device buffer with RAII -------------------------------------------------
 struct DevBuf {
     void* p = nullptr;

@@ -172,7 +172,7 @@ static hipError_t launch_fc_lds(const cadnn_weights* w, const void* x, void* y, 
     constexpr int WPB = THREADS / 64;
     const int per_cu = (int)std::min<size_t>(2048 / THREADS, std::max<size_t>(1, kLdsBytesPerCU / std::max<size_t>(lds, 1)));
     const int gx = std::min((w->cout + WPB - 1) / WPB, 256 * per_cu);
-    hipLaunchKernelGGL((sfc_lds_kernel<T, NB, THREADS>), dim3((unsigned)gx, (unsigned)((n + NB - 1) / NB)),
+    CADNN_LAUNCH((sfc_lds_kernel<T, NB, THREADS>), dim3((unsigned)gx, (unsigned)((n + NB - 1) / NB)),
                        dim3(THREADS), lds, s, (const int32_t*)w->d_frow.p, (const int32_t*)w->d_perm.p,
                        w->d_fcol.p, w->d_fval.p, (const T*)x, (T*)y, bias, n, w->cin, w->cout, relu);
     return hipGetLastError();
@@ -209,11 +209,11 @@ static cadnn_status launch_fc_t(const cadnn_weights* w, const void* x, void* y, 
     const int32_t* cl = (const int32_t*)w->d_col.p;
     const float* vl = (const float*)w->d_val.p;
     if (n == 1) {
-        hipLaunchKernelGGL((sfc_kernel<T, 1>), dim3(gx, 1), dim3(256), 0, s, rp, pm, cl, vl,
+        CADNN_LAUNCH((sfc_kernel<T, 1>), dim3(gx, 1), dim3(256), 0, s, rp, pm, cl, vl,
                            (const T*)x, (T*)y, bias, n, w->cin, w->cout, relu);
     } else {
         constexpr int NB = 8;
-        hipLaunchKernelGGL((sfc_kernel<T, NB>), dim3(gx, (unsigned)((n + NB - 1) / NB)), dim3(256),
+        CADNN_LAUNCH((sfc_kernel<T, NB>), dim3(gx, (unsigned)((n + NB - 1) / NB)), dim3(256),
                            0, s, rp, pm, cl, vl, (const T*)x, (T*)y, bias, n, w->cin, w->cout, relu);
     }
     CADNN_HIP(hipGetLastError());
@@ -272,7 +272,7 @@ cadnn_status launch_copy(const void* src, void* dst, size_t bytes, hipStream_t s
     const size_t n16 = bytes / 16;
     if (n16 == 0) return CADNN_OK;
     const unsigned blocks = (unsigned)std::min<size_t>((n16 + 255) / 256, 256 * 16);
-    hipLaunchKernelGGL(copy_kernel, dim3(blocks), dim3(256), 0, s, (const uint4*)src, (uint4*)dst, n16);
+    CADNN_LAUNCH(copy_kernel, dim3(blocks), dim3(256), 0, s, (const uint4*)src, (uint4*)dst, n16);
     CADNN_HIP(hipGetLastError());
     return CADNN_OK;
 }
@@ -284,10 +284,10 @@ static cadnn_status launch_windowpool(const void* x, const TensorDesc& xd, void*
     if ((total + 255) / 256 > 0x7fffffffull) return fail(CADNN_EUNSUPPORTED, "pooling layer too large for one launch");
     const unsigned blocks = (unsigned)((total + 255) / 256);
     if (dt == CADNN_F16)
-        hipLaunchKernelGGL((windowpool_kernel<_Float16, AVG>), dim3(blocks), dim3(256), 0, s, (const _Float16*)x,
+        CADNN_LAUNCH((windowpool_kernel<_Float16, AVG>), dim3(blocks), dim3(256), 0, s, (const _Float16*)x,
                            (_Float16*)y, xd, yd, n, k, stride, pad);
     else
-        hipLaunchKernelGGL((windowpool_kernel<float, AVG>), dim3(blocks), dim3(256), 0, s, (const float*)x,
+        CADNN_LAUNCH((windowpool_kernel<float, AVG>), dim3(blocks), dim3(256), 0, s, (const float*)x,
                            (float*)y, xd, yd, n, k, stride, pad);
     CADNN_HIP(hipGetLastError());
     return CADNN_OK;
@@ -308,10 +308,10 @@ cadnn_status launch_avgpool(const void* x, const TensorDesc& xd, void* y, int n,
     const int nc = n * xd.c;
     const unsigned blocks = (unsigned)((nc + 3) / 4);
     if (dt == CADNN_F16)
-        hipLaunchKernelGGL(avgpool_kernel<_Float16>, dim3(blocks), dim3(256), 0, s, (const _Float16*)x,
+        CADNN_LAUNCH(avgpool_kernel<_Float16>, dim3(blocks), dim3(256), 0, s, (const _Float16*)x,
                            (_Float16*)y, xd, n);
     else
-        hipLaunchKernelGGL(avgpool_kernel<float>, dim3(blocks), dim3(256), 0, s, (const float*)x,
+        CADNN_LAUNCH(avgpool_kernel<float>, dim3(blocks), dim3(256), 0, s, (const float*)x,
                            (float*)y, xd, n);
     CADNN_HIP(hipGetLastError());
     return CADNN_OK;

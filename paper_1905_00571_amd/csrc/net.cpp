@@ -1108,6 +1108,59 @@ extern "C" cadnn_status cadnn_net_profile(cadnn_net* net, const void* x, void* y
     return st;
 }
 
+// Per-op device time with the ops IN LAUNCH ORDER, as a forward pass runs them: every op finds
+// the caches as the real pass leaves them (its input just written by its producer, its weights
+// last touched a whole pass ago) instead of warm from its own previous launch.  Every kernel
+// carries its own start and stop marks (LaunchTimer), so an op's figure is the device time of
+// its kernels and nothing else -- what a kernel trace of the same pass reports.
+extern "C" cadnn_status cadnn_net_profile_in_order(cadnn_net* net, const void* x, void* y, void* stream,
+                                                   int repeats, float* ms_per_op) {
+    if (!net || !x || !y || !ms_per_op) return fail(CADNN_EINVAL, "cadnn_net_profile_in_order: NULL pointer");
+    if (!net->finalized) return fail(CADNN_EINVAL, "cadnn_net_profile_in_order: net not finalized");
+    if (repeats <= 0) return fail(CADNN_EINVAL, "cadnn_net_profile_in_order: repeats must be positive");
+    hipStream_t s = (hipStream_t)stream;
+    const size_t nops = net->ops.size();
+    std::vector<size_t> order;
+    for (size_t i = 0; i < nops; ++i) {
+        if (net->ops[i].hoisted_to >= 0) continue;
+        order.push_back(i);
+        for (int h : net->ops[i].hoisted) order.push_back((size_t)h);
+    }
+    std::vector<LaunchTimer> timers(order.size());
+    cadnn_status st = CADNN_OK;
+    for (LaunchTimer& t : timers)
+        for (int k = 0; k < LaunchTimer::kMax; ++k) { t.start[k] = nullptr; t.stop[k] = nullptr; }
+    for (LaunchTimer& t : timers)
+        for (int k = 0; k < LaunchTimer::kMax && st == CADNN_OK; ++k)
+            if (hipEventCreate(&t.start[k]) != hipSuccess || hipEventCreate(&t.stop[k]) != hipSuccess)
+                st = fail(CADNN_EHIP, "hipEventCreate failed");
+    std::vector<double> sum(nops, 0.0);
+    for (int r = 0; r < repeats && st == CADNN_OK; ++r) {
+        for (size_t k = 0; k < order.size() && st == CADNN_OK; ++k) {
+            timers[k].used = 0;
+            g_launch_timer = &timers[k];
+            st = launch_one(net, order[k], x, y, s);
+            g_launch_timer = nullptr;
+        }
+        if (st == CADNN_OK && hipStreamSynchronize(s) != hipSuccess) st = fail(CADNN_EHIP, "hipStreamSynchronize failed");
+        for (size_t k = 0; k < order.size() && st == CADNN_OK; ++k)
+            for (int q = 0; q < timers[k].used; ++q) {
+                float ms = 0.0f;
+                if (hipEventElapsedTime(&ms, timers[k].start[q], timers[k].stop[q]) != hipSuccess) { st = fail(CADNN_EHIP, "hipEventElapsedTime failed"); break; }
+                sum[order[k]] += ms;
+            }
+    }
+    g_launch_timer = nullptr;
+    for (LaunchTimer& t : timers)
+        for (int k = 0; k < LaunchTimer::kMax; ++k) {
+            if (t.start[k]) (void)hipEventDestroy(t.start[k]);
+            if (t.stop[k]) (void)hipEventDestroy(t.stop[k]);
+        }
+    if (st != CADNN_OK) return st;
+    for (size_t i = 0; i < nops; ++i) ms_per_op[i] = (float)(sum[i] / repeats);
+    return CADNN_OK;
+}
+
 extern "C" cadnn_status cadnn_net_op_variant(const cadnn_net* net, int op_index, char* buf, size_t len) {
     if (!net || !buf || len == 0) return fail(CADNN_EINVAL, "cadnn_net_op_variant: NULL pointer");
     if (!net->finalized) return fail(CADNN_EINVAL, "cadnn_net_op_variant: net not finalized");

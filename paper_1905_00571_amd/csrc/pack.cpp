@@ -12,6 +12,7 @@
 namespace cadnn {
 
 static thread_local std::string g_last_error;
+thread_local LaunchTimer* g_launch_timer = nullptr;
 
 cadnn_status fail(cadnn_status code, const char* fmt, ...) {
     char buf[512];
