@@ -324,6 +324,9 @@ cadnn_status cadnn_net_workspace_bytes(const cadnn_net* net, size_t* bytes);
 #define CADNN_NET_TUNE 2
 #define CADNN_NET_PLAIN_LAYOUT 4
 #define CADNN_NET_NO_FUSION 8
+/* CADNN_NET_STATIC_WORKSPACE -- the net's workspace is the library's own static device array
+ * (workspace_dev and bytes are ignored): see cadnn_run_net_noalloc. */
+#define CADNN_NET_STATIC_WORKSPACE 16
 cadnn_status cadnn_net_finalize(cadnn_net* net, void* workspace_dev, size_t bytes, int flags);
 /* Where the runner puts op `op_index`'s output and what it does with the op, as decided for
  * `flags` (the CADNN_NET_PLAIN_LAYOUT / CADNN_NET_NO_FUSION bits matter).  Pure host work: it
@@ -356,6 +359,20 @@ typedef struct {
 } cadnn_op_info;
 cadnn_status cadnn_net_op_info(cadnn_net* net, int op_index, int flags, cadnn_op_info* out);
 cadnn_status cadnn_run_net(cadnn_net* net, const void* x, void* y, void* stream);
+/* cadnn_run_net for callers that cannot allocate: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  It allocates nothing, on the device or through any
+ * allocating library routine, and launches the net's kernels one by one on `stream` (no graph
+ * of its own).  The net's workspace -- every intermediate tensor -- is a static device array
+ * of the library, 16 MiB per GPU, held until the process ends: the net must have been
+ * finalized with CADNN_NET_STATIC_WORKSPACE (on the device that is current now), which
+ * refuses a net that needs more with CADNN_EUNSUPPORTED and builds every device layout the
+ * net's layers use.  x and y are the caller's, as in cadnn_run_net.  Every such net on a GPU
+ * shares that one array, which keeps what the last call left: each call clears the part it
+ * uses first (with a kernel), and calls that overlap on one GPU -- two streams, two threads --
+ * race and must be serialised by the caller.  Errors: CADNN_EINVAL (NULL pointer, a net that
+ * is not finalized, not finalized with CADNN_NET_STATIC_WORKSPACE, finalized on another
+ * device or still waiting to be tuned, or a layer whose device layout is missing). */
+cadnn_status cadnn_run_net_noalloc(cadnn_net* net, const void* x, void* y, void* stream);
 /* Number of ops, and per-op device time: op i is launched `repeats` times back
  * to back between two HIP events on `stream` and the average is written to
  * ms_per_op[i] (cadnn_net_num_ops entries).  Synchronises the stream. */

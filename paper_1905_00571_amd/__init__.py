@@ -37,6 +37,7 @@ from .binding import (  # noqa: F401
     cadnn_global_avgpool,
     cadnn_dense_conv2d,
     cadnn_run_net,
+    cadnn_run_net_noalloc,
     build_net,
     plan_net,
     OpInfo,

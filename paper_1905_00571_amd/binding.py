@@ -101,6 +101,7 @@ def lib() -> ctypes.CDLL:
         "cadnn_run_net": (_i, [_vp, _vp, _vp, _vp]),
         "cadnn_net_num_ops": (_i, [_vp, ctypes.POINTER(_i)]),
         "cadnn_graph_launch_floor": (_i, [_vp, _i, _i, _vp, _f32p]),
+        "cadnn_run_net_noalloc": (_i, [_vp, _vp, _vp, _vp]),
         "cadnn_net_profile": (_i, [_vp, _vp, _vp, _vp, _i, _f32p]),
         "cadnn_net_profile_in_order": (_i, [_vp, _vp, _vp, _vp, _i, _f32p]),
         "cadnn_net_op_variant": (_i, [_vp, _i, ctypes.c_char_p, ctypes.c_size_t]),
@@ -410,6 +411,13 @@ class Net:
         _check(lib().cadnn_run_net(self.handle, _dptr(x), _dptr(y), _stream_ptr(stream)))
         return y
 
+    def run_noalloc(self, x, y, stream=None):
+        """cadnn_run_net_noalloc: y is the caller's (nothing is allocated, here or in the library)."""
+        assert x.is_cuda and x.is_contiguous() and tuple(x.shape) == self.in_shape
+        assert y.is_cuda and y.is_contiguous() and tuple(y.shape) == self.out_shape
+        _check(lib().cadnn_run_net_noalloc(self.handle, _dptr(x), _dptr(y), _stream_ptr(stream)))
+        return y
+
     def profile(self, x, y, repeats: int = 10, stream=None) -> np.ndarray:
         ms = np.zeros(self.num_ops(), np.float32)
         _check(lib().cadnn_net_profile(self.handle, _dptr(x), _dptr(y), _stream_ptr(stream), repeats,
@@ -475,6 +483,10 @@ class Net:
 
 def cadnn_run_net(net: Net, x, y=None, stream=None):
     return net.run(x, y, stream)
+
+
+def cadnn_run_net_noalloc(net: Net, x, y, stream=None):
+    return net.run_noalloc(x, y, stream)
 
 
 def _add_ops(L, handle, ops, weights, biases, input_shape, dtype, keep, to_device):
@@ -557,8 +569,10 @@ def plan_net(ops: Sequence, weights: Sequence, input_shape, dtype: int = F32, pl
 
 def build_net(ops: Sequence, weights: Sequence, biases: Sequence, input_shape, dtype: int = F32,
               use_graph: bool = True, tune: bool = False, device: str = "cuda:0",
-              plain_layout: bool = False, fuse: bool = True) -> Net:
+              plain_layout: bool = False, fuse: bool = True, static_workspace: bool = False) -> Net:
     """Packs every layer's weights and wires the op list into a cadnn_net.
+    static_workspace: the net's intermediate tensors live in the library's static device array
+    (CADNN_NET_STATIC_WORKSPACE), which is what Net.run_noalloc needs.
 
     `ops` are records with .kind in {"conv", "dwconv", "fc", "maxpool", "avgpool2d", "avgpool", "concat"} and
     .src/.dst/.res/.k/.stride/.pad/.relu fields (see workloads.nets.Op).
@@ -577,9 +591,13 @@ def build_net(ops: Sequence, weights: Sequence, biases: Sequence, input_shape, d
         _check(L.cadnn_net_op_info(handle, 0, flags, ctypes.byref(OpInfo())))
         nbytes = ctypes.c_size_t()
         _check(L.cadnn_net_workspace_bytes(handle, ctypes.byref(nbytes)))
-        ws = torch.empty(max(int(nbytes.value), 256), dtype=torch.uint8, device=device)
-        keep.append(ws)
-        _check(L.cadnn_net_finalize(handle, _dptr(ws), int(nbytes.value), flags))
+        if static_workspace:
+            flags |= 16
+            _check(L.cadnn_net_finalize(handle, None, 0, flags))
+        else:
+            ws = torch.empty(max(int(nbytes.value), 256), dtype=torch.uint8, device=device)
+            keep.append(ws)
+            _check(L.cadnn_net_finalize(handle, _dptr(ws), int(nbytes.value), flags))
     except Exception:
         L.cadnn_net_free(handle)
         raise

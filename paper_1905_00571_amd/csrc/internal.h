@@ -317,6 +317,15 @@ struct HostPlans {
     HostPlans& operator=(const HostPlans&) = delete;
 };
 
+// While one of these is alive on a thread, nothing may be allocated on the device: a device
+// layout that is not there yet is an error (CADNN_EINVAL) instead of being built.
+struct NoDeviceAlloc {
+    NoDeviceAlloc();
+    ~NoDeviceAlloc();
+    NoDeviceAlloc(const NoDeviceAlloc&) = delete;
+    NoDeviceAlloc& operator=(const NoDeviceAlloc&) = delete;
+};
+
 // While one of these is alive on a thread, the plans that thread asks for are trial plans of a
 // tuning pass: they may be freed again when the pass ends (drop_unpinned_plans).
 struct TrialPlans {
@@ -486,6 +495,7 @@ float f16_to_f32(uint16_t h);
 cadnn_status launch_fc(const cadnn_weights* w, const void* x, void* y, int n, const float* bias,
                        int relu, hipStream_t s);
 cadnn_status launch_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
+cadnn_status launch_zero(void* dst, size_t bytes, hipStream_t s);
 // Depthwise layer on plain (possibly haloed) tensors; yd carries the output size.
 cadnn_status launch_depthwise(const cadnn_weights* w, const void* x, const TensorDesc& xd, void* y,
                               const TensorDesc& yd, int n, int stride, int pad, const float* bias, int relu,

@@ -268,6 +268,22 @@ __global__ __launch_bounds__(256) void copy_kernel(const uint4* __restrict__ src
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
 }
 
+__global__ __launch_bounds__(256) void zero_kernel(uint4* __restrict__ dst, size_t n16) {
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = make_uint4(0u, 0u, 0u, 0u);
+}
+
+// Zeroes `bytes` bytes (a multiple of 16, 16-byte aligned) with a kernel: usable where a memset
+// node must not be recorded.
+cadnn_status launch_zero(void* dst, size_t bytes, hipStream_t s) {
+    const size_t n16 = bytes / 16;
+    if (n16 == 0) return CADNN_OK;
+    const unsigned blocks = (unsigned)std::min<size_t>((n16 + 255) / 256, 256 * 16);
+    CADNN_LAUNCH(zero_kernel, dim3(blocks), dim3(256), 0, s, (uint4*)dst, n16);
+    CADNN_HIP(hipGetLastError());
+    return CADNN_OK;
+}
+
 cadnn_status launch_copy(const void* src, void* dst, size_t bytes, hipStream_t s) {
     const size_t n16 = bytes / 16;
     if (n16 == 0) return CADNN_OK;

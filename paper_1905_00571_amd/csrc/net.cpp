@@ -98,6 +98,34 @@ std::vector<int> input_insts(const NetOp& op) {
 
 }  // namespace
 
+// The workspace of nets that may not allocate (cadnn_run_net_noalloc): one array per GPU, held
+// by the library until the process ends and shared by every such net on that GPU.  In host
+// code the array's name is only a stand-in; its device address comes from static_workspace().
+constexpr size_t kStaticWorkspaceBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticWorkspaceBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (looked up once per device).
+cadnn_status static_workspace(void** ptr) {
+    int dev = -1;
+    CADNN_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(CADNN_EUNSUPPORTED, "device %d: more than %d devices", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        CADNN_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(CADNN_EHIP, "hipGetSymbolAddress returned no address for the static workspace");
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return CADNN_OK;
+}
+}  // namespace
+
 struct cadnn_net {
     cadnn_dtype dtype = CADNN_F32;
     Shape input;
@@ -112,6 +140,7 @@ struct cadnn_net {
     bool allow_s2d = true;
     bool allow_fusion = true;
     char* ws = nullptr;
+    bool static_ws = false;          // the workspace is the library's static array (CADNN_NET_STATIC_WORKSPACE)
     std::map<int, std::unique_ptr<cadnn_weights>> merged_w;   // per first op of a sibling group
     std::map<int, std::unique_ptr<DevBuf>> merged_bias;
     std::map<int, std::unique_ptr<CoLaunch>> colaunch;        // per first op of a group of co-launched layers
@@ -985,6 +1014,15 @@ extern "C" cadnn_status cadnn_net_finalize(cadnn_net* net, void* ws, size_t byte
     // (a plain layout never needs more room than the de-interleaved one that
     // cadnn_net_workspace_bytes reports)
     layout_for(net, flags);
+    net->static_ws = (flags & CADNN_NET_STATIC_WORKSPACE) != 0;
+    if (net->static_ws) {
+        if (net->ws_bytes > kStaticWorkspaceBytes)
+            return fail(CADNN_EUNSUPPORTED, "cadnn_net_finalize: the net needs %zu bytes of workspace, the static workspace holds %zu",
+                        net->ws_bytes, kStaticWorkspaceBytes);
+        cadnn_status st = static_workspace(&ws);
+        if (st != CADNN_OK) return st;
+        bytes = kStaticWorkspaceBytes;
+    }
     if (net->ws_bytes > 0 && !ws) return fail(CADNN_EINVAL, "cadnn_net_finalize: NULL workspace");
     if (bytes < net->ws_bytes) return fail(CADNN_EINVAL, "cadnn_net_finalize: workspace of %zu bytes, %zu needed", bytes, net->ws_bytes);
     drop_graph(net);
@@ -1072,6 +1110,25 @@ extern "C" cadnn_status cadnn_run_net(cadnn_net* net, const void* x, void* y, vo
     }
     CADNN_HIP(hipGraphLaunch(net->exec, s));
     return CADNN_OK;
+}
+
+extern "C" cadnn_status cadnn_run_net_noalloc(cadnn_net* net, const void* x, void* y, void* stream) {
+    if (!net || !x || !y) return fail(CADNN_EINVAL, "cadnn_run_net_noalloc: NULL pointer");
+    if (!net->finalized) return fail(CADNN_EINVAL, "cadnn_run_net_noalloc: net not finalized");
+    if (!net->static_ws) return fail(CADNN_EINVAL, "cadnn_run_net_noalloc: the net was not finalized with CADNN_NET_STATIC_WORKSPACE");
+    if (net->want_tune) return fail(CADNN_EINVAL, "cadnn_run_net_noalloc: tuning (CADNN_NET_TUNE) allocates; run cadnn_run_net once first");
+    if (net->ws_bytes > kStaticWorkspaceBytes) return fail(CADNN_EUNSUPPORTED, "cadnn_run_net_noalloc: workspace above the static limit");
+    hipStream_t s = (hipStream_t)stream;
+    void* ptr = nullptr;
+    cadnn_status st = static_workspace(&ptr);
+    if (st != CADNN_OK) return st;
+    if (ptr != (void*)net->ws) return fail(CADNN_EINVAL, "cadnn_run_net_noalloc: the net was finalized on another device");
+    const NoDeviceAlloc guard;
+    // The array is shared by every such net on this GPU and keeps what the last call left: the
+    // halos this net reads as zero padding are cleared again (with a kernel, so that a caller
+    // under graph capture records no memset node).
+    if (net->ws_bytes && (st = launch_zero(ptr, (net->ws_bytes + 15) / 16 * 16, s)) != CADNN_OK) return st;
+    return launch_all(net, x, y, s);
 }
 
 extern "C" cadnn_status cadnn_net_num_ops(const cadnn_net* net, int* num_ops) {

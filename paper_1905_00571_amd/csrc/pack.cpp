@@ -25,6 +25,10 @@ cadnn_status fail(cadnn_status code, const char* fmt, ...) {
 }
 void clear_error() { g_last_error.clear(); }
 
+static thread_local int g_no_device_alloc = 0;
+NoDeviceAlloc::NoDeviceAlloc() { ++g_no_device_alloc; }
+NoDeviceAlloc::~NoDeviceAlloc() { --g_no_device_alloc; }
+
 static thread_local int g_host_plans = 0;
 HostPlans::HostPlans() { ++g_host_plans; }
 HostPlans::~HostPlans() { --g_host_plans; }
@@ -40,6 +44,7 @@ void DevBuf::release() {
 }
 
 cadnn_status DevBuf::upload(const void* host, size_t n) {
+    if (g_no_device_alloc > 0 && g_host_plans == 0) return fail(CADNN_EINVAL, "this call may not allocate device memory");
     release();
     const size_t alloc = n < 16 ? 16 : n;
     if (g_host_plans > 0) {
@@ -874,6 +879,8 @@ cadnn_status get_conv_plan(const cadnn_weights* w, const ConvVariant* v, const T
     const PlanKey key = plan_key(w, v, xd, stride, pad, wout, ex);
     auto it = w->plans.find(key);
     if (it == w->plans.end()) {
+        if (g_no_device_alloc > 0)
+            return fail(CADNN_EINVAL, "the device layout of '%s' for this layer was not prepared, and this call may not allocate", v->name);
         std::shared_ptr<ConvPlan> plan(new (std::nothrow) ConvPlan());
         if (!plan) return fail(CADNN_ENOMEM, "out of host memory");
         cadnn_status st;
