@@ -181,10 +181,12 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_wtile_kernel(const ConvLau
 #pragma unroll
     for (int r = 0; r < RPW; ++r) bias_[r] = (a.bias && co_[r] >= 0) ? a.bias[co_[r]] : 0.0f;
 
-    // ---- lane -> output pixels (element offsets inside y / the residual, channel plane excluded; -1: none;
-    //      flattened tiles run over the batch, whose tensors stay below 2^31 bytes)
+    // ---- lane -> output pixels: byte offsets inside y / the residual with the channel plane
+    //      left out (it enters as the scalar part of the address); a pixel outside the tensor gets
+    //      an out-of-range offset, which makes its loads read zero and drops its stores.
+    //      (Flattened tiles run over the batch, whose tensors stay below 2^31 bytes.)
     const int hw = a.hwout;
-    int oidx[P], ridx[P];
+    uint32_t yoff[P], roff[P];
     uint32_t lane_base = (uint32_t)(uintptr_t)(wt_lds_ptr_t)wt_tile;
     int ty = 0, tx = 0;
     if constexpr (FLAT) {
@@ -194,8 +196,8 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_wtile_kernel(const ConvLau
             const int Q = (int)blockIdx.x * (64 * P) + lane * P + j;
             const int img = wt_divf(Q, hw), q = Q - img * hw;
             const int oh = wt_divf(q, a.yd.w), ow = q - oh * a.yd.w;
-            oidx[j] = Q < total ? img * (int)a.yd.image + tensor_off(a.yd, oh, ow) : -1;
-            ridx[j] = Q < total ? img * (int)a.rd.image + tensor_off(a.rd, oh, ow) : -1;
+            yoff[j] = Q < total ? (uint32_t)(img * (int)a.yd.image + tensor_off(a.yd, oh, ow)) * (uint32_t)sizeof(T) : kWtOutOfRange;
+            roff[j] = Q < total ? (uint32_t)(img * (int)a.rd.image + tensor_off(a.rd, oh, ow)) * (uint32_t)sizeof(T) : kWtOutOfRange;
         }
         lane_base += (uint32_t)(lane * P * 4);
     } else {
@@ -207,30 +209,60 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_wtile_kernel(const ConvLau
         for (int j = 0; j < P; ++j) {
             const int ocol = tx * (LC * P) + lc + LC * j;
             const bool in = orow < a.yd.h && ocol < a.yd.w;
-            oidx[j] = in ? tensor_off(a.yd, orow, ocol) : -1;
-            ridx[j] = in ? tensor_off(a.rd, orow, ocol) : -1;
+            yoff[j] = in ? (uint32_t)tensor_off(a.yd, orow, ocol) * (uint32_t)sizeof(T) : kWtOutOfRange;
+            roff[j] = in ? (uint32_t)tensor_off(a.rd, orow, ocol) * (uint32_t)sizeof(T) : kWtOutOfRange;
         }
         lane_base += (uint32_t)((lr * a.wt_pitch + lc * P) * 4);
     }
+    const uint32_t yspan = (uint32_t)(a.yd.image * (int64_t)sizeof(T)) * (FLAT ? (uint32_t)a.n : 1u);
+    const uint32_t rspan = (uint32_t)(a.rd.image * (int64_t)sizeof(T)) * (FLAT ? (uint32_t)a.n : 1u);
+    const __amdgpu_buffer_rsrc_t yrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)((char*)a.y + (size_t)n * a.yd.image * sizeof(T)), 0, yspan, 0x00020000);
 
     // ---- residual up front: one more round trip off the tail
-    const T* __restrict__ res = a.residual ? (const T*)a.residual + (size_t)n * a.rd.image : nullptr;
     float resv[RPW][P];
+    {
+        const __amdgpu_buffer_rsrc_t rrsrc = __builtin_amdgcn_make_buffer_rsrc(
+            a.residual ? (void*)((const char*)a.residual + (size_t)n * a.rd.image * sizeof(T)) : (void*)a.y, 0,
+            a.residual ? rspan : 0u, 0x00020000);
 #pragma unroll
-    for (int j = 0; j < P; ++j)
+        for (int r = 0; r < RPW; ++r) {
+            // (the scalar part of an address takes no part in the range check, so it is always a
+            // real plane offset; a padding row -- a wave-uniform condition -- reads nothing)
+            const uint32_t plane_off = (uint32_t)(co_[r] >= 0 ? co_[r] : 0) * (uint32_t)a.rd.plane * (uint32_t)sizeof(T);
 #pragma unroll
-        for (int r = 0; r < RPW; ++r)
-            resv[r][j] = (res && co_[r] >= 0 && oidx[j] >= 0) ? (float)res[(size_t)co_[r] * a.rd.plane + ridx[j]] : 0.0f;
+            for (int j = 0; j < P; ++j) {
+                if (co_[r] < 0) {
+                    resv[r][j] = 0.0f;
+                } else if constexpr (sizeof(T) == 4) {
+                    resv[r][j] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rrsrc, roff[j], plane_off, 0));
+                } else {
+                    resv[r][j] = (float)__builtin_bit_cast(_Float16, __builtin_amdgcn_raw_buffer_load_b16(rrsrc, roff[j], plane_off, 0));
+                }
+            }
+        }
+    }
 
-    // ---- staging offsets: word p = lane + 64*t of a channel plane of the tile comes from here
-    uint32_t goff[kWtileMaxSteps];
+    // ---- staging: a channel plane of the tile is `nstp` runs of 64 words, and a wave stages
+    //      the SAME runs of every channel it is given -- run t = wave % nstp (and t + NW where
+    //      there are more runs than waves) of the channels congruent to wave / nstp -- so that it
+    //      needs the global offsets of one or two runs, not of the whole plane.
+    constexpr int SPW = (kWtileMaxSteps + NW - 1) / NW;       // runs a wave may have to take
+    const int nstp = a.wt_nstp;
+    const int sets = nstp >= NW ? 1 : NW / nstp;              // waves that share a run split the channels
+    const int my_set = nstp >= NW ? 0 : wv_id / nstp;
+    const bool stages = nstp >= NW || wv_id < sets * nstp;
+    uint32_t goff[SPW];
+    int gword[SPW];
     {
         const int total = a.n * hw;
 #pragma unroll
-        for (int t = 0; t < kWtileMaxSteps; ++t) {
+        for (int k = 0; k < SPW; ++k) {
+            const int t = (nstp >= NW ? wv_id : wv_id % nstp) + k * NW;
             const int p = lane + 64 * t;
+            gword[k] = (stages && t < nstp && p < a.wt_plane) ? p : -1;
             uint32_t off = kWtOutOfRange;
-            if (t < a.wt_nstp && p < a.wt_plane) {
+            if (gword[k] >= 0) {
                 if constexpr (FLAT) {
                     const int Q = (int)blockIdx.x * (64 * P) + p;
                     if (Q < total) {
@@ -249,7 +281,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_wtile_kernel(const ConvLau
                         off = (uint32_t)tensor_off(a.xd, row, col) * (uint32_t)sizeof(T);
                 }
             }
-            goff[t] = off;
+            goff[k] = off;
         }
     }
     // flat tiles run over the images of the batch, so the buffer spans the whole tensor
@@ -273,35 +305,42 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_wtile_kernel(const ConvLau
     auto stage = [&](int c, float* buf) {
         const int ch0 = c * a.wt_cch;
         const int cch = min(a.wt_cch, cin - ch0);
-        for (int ch = wv_id; ch < cch; ch += NW) {
+        for (int ch = my_set; ch < cch; ch += sets) {
             const uint32_t soff = (uint32_t)(ch0 + ch) * plane_bytes;
 #pragma unroll
-            for (int t = 0; t < kWtileMaxSteps; ++t)
-                if (t < a.wt_nstp && lane + 64 * t < a.wt_plane) {
+            for (int k = 0; k < SPW; ++k)
+                if (gword[k] >= 0) {
+                    float* dst = buf + ch * a.wt_plane + (gword[k] - lane);
                     if constexpr (sizeof(T) == 4)
-                        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (wt_lds_ptr_t)(buf + ch * a.wt_plane + 64 * t), 4, goff[t], soff, 0, 0);
+                        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (wt_lds_ptr_t)dst, 4, goff[k], soff, 0, 0);
                     else
-                        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (wt_lds_ptr_t)(buf + ch * a.wt_plane + 64 * t), 2, goff[t], soff, 0, 0);
+                        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (wt_lds_ptr_t)dst, 2, goff[k], soff, 0, 0);
                 }
         }
     };
 
     // 2-byte storage: once a wave's own share of a chunk has landed it widens it to fp32 in
-    // place, four words per lane and step (the inner loop then runs the plain fp32 FMA, which
-    // issues faster than the mixed-precision one: 27 against 34 clocks per nonzero measured).
+    // place (the inner loop then runs the plain fp32 FMA, which issues faster than the
+    // mixed-precision one: 27 against 34 clocks per nonzero measured).  A run is 16 groups of four
+    // words, so the 64 lanes take the same run of four channels at a time.
     auto widen = [&](int c, float* buf) {
         if constexpr (sizeof(T) == 2) {
             const int cch = min(a.wt_cch, cin - c * a.wt_cch);
-            const int quads = a.wt_plane >> 2;          // (a plane is a whole number of 4-word slots)
-            for (int ch = wv_id; ch < cch; ch += NW) {
-                wt_u4* pl = (wt_u4*)(buf + ch * a.wt_plane);
-                for (int i = lane; i < quads; i += 64) {
-                    const wt_u4 h = pl[i];
+            const int quad = lane & 15, sub = lane >> 4;
+#pragma unroll
+            for (int k = 0; k < SPW; ++k) {
+                const int t = (nstp >= NW ? wv_id : wv_id % nstp) + k * NW;
+                if (!stages || t >= nstp) continue;
+                const int word = 64 * t + 4 * quad;             // (a plane is a whole number of 4-word slots)
+                if (word >= a.wt_plane) continue;
+                for (int ch = my_set + sub * sets; ch < cch; ch += 4 * sets) {
+                    wt_u4* q = (wt_u4*)(buf + ch * a.wt_plane + word);
+                    const wt_u4 h = *q;
                     wt_u4 f;
 #pragma unroll
-                    for (int k = 0; k < 4; ++k)
-                        f[k] = __float_as_uint((float)__builtin_bit_cast(_Float16, (unsigned short)h[k]));
-                    pl[i] = f;
+                    for (int e = 0; e < 4; ++e)
+                        f[e] = __float_as_uint((float)__builtin_bit_cast(_Float16, (unsigned short)h[e]));
+                    *q = f;
                 }
             }
         }
@@ -364,20 +403,21 @@ __global__ __launch_bounds__(Cfg::THREADS) void sconv_wtile_kernel(const ConvLau
     }
 
     // ---- fused epilogue: + bias, + residual, ReLU, store at the original channel
-    T* __restrict__ y = (T*)a.y + (size_t)n * a.yd.image;
 #pragma unroll
     for (int r = 0; r < RPW; ++r) {
         const int co = co_[r];
         if (co < 0) continue;
         const float b = bias_[r];
+        const uint32_t plane_off = (uint32_t)co * (uint32_t)a.yd.plane * (uint32_t)sizeof(T);
 #pragma unroll
         for (int j = 0; j < P; ++j) {
-            if (oidx[j] >= 0) {
-                float v = acc[r][j] + b;
-                v += resv[r][j];
-                if (a.relu) v = v > 0.0f ? v : 0.0f;
-                y[(size_t)co * a.yd.plane + oidx[j]] = (T)v;
-            }
+            float v = acc[r][j] + b;
+            v += resv[r][j];
+            if (a.relu) v = v > 0.0f ? v : 0.0f;
+            if constexpr (sizeof(T) == 4)
+                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), yrsrc, yoff[j], plane_off, 0);
+            else
+                __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, (_Float16)v), yrsrc, yoff[j], plane_off, 0);
         }
     }
 }
@@ -421,23 +461,34 @@ static ConvVariant make_wtile(const char* name) {
     CADNN_WTILE_FLAT(T, 2, 8),        \
     CADNN_WTILE_FLAT(T, 4, 8),        \
     CADNN_WTILE_FLAT(T, 8, 8),        \
+    CADNN_WTILE_FLAT(T, 1, 16),       \
     CADNN_WTILE_FLAT(T, 2, 16),       \
     CADNN_WTILE_FLAT(T, 4, 16),       \
+    CADNN_WTILE_FLAT(T, 8, 16),       \
     CADNN_WTILE_GRID(T, 1, 8, 4),     \
     CADNN_WTILE_GRID(T, 2, 8, 4),     \
     CADNN_WTILE_GRID(T, 4, 8, 4),     \
     CADNN_WTILE_GRID(T, 8, 8, 4),     \
+    CADNN_WTILE_GRID(T, 1, 16, 4),    \
+    CADNN_WTILE_GRID(T, 2, 16, 4),    \
     CADNN_WTILE_GRID(T, 4, 16, 4),    \
+    CADNN_WTILE_GRID(T, 8, 16, 4),    \
     CADNN_WTILE_GRID(T, 1, 8, 8),     \
     CADNN_WTILE_GRID(T, 2, 8, 8),     \
     CADNN_WTILE_GRID(T, 4, 8, 8),     \
     CADNN_WTILE_GRID(T, 8, 8, 8),     \
+    CADNN_WTILE_GRID(T, 1, 16, 8),    \
+    CADNN_WTILE_GRID(T, 2, 16, 8),    \
     CADNN_WTILE_GRID(T, 4, 16, 8),    \
+    CADNN_WTILE_GRID(T, 8, 16, 8),    \
     CADNN_WTILE_GRID(T, 1, 8, 16),    \
     CADNN_WTILE_GRID(T, 2, 8, 16),    \
     CADNN_WTILE_GRID(T, 4, 8, 16),    \
     CADNN_WTILE_GRID(T, 8, 8, 16),    \
-    CADNN_WTILE_GRID(T, 4, 16, 16)
+    CADNN_WTILE_GRID(T, 1, 16, 16),   \
+    CADNN_WTILE_GRID(T, 2, 16, 16),   \
+    CADNN_WTILE_GRID(T, 4, 16, 16),   \
+    CADNN_WTILE_GRID(T, 8, 16, 16)
 
 const std::vector<ConvVariant>& all_wtile_variants() {
     static const std::vector<ConvVariant> v = {CADNN_WTILE_SHAPES(float), CADNN_WTILE_SHAPES(_Float16)};
