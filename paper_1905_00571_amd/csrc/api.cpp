@@ -60,13 +60,35 @@ static bool variant_fits(const ConvVariant& v, const cadnn_weights* w, const Con
     if (v.is_f16 != (w->dtype == CADNN_F16)) return false;
     if (v.stride != 0 && v.stride != g.stride) return false;
     if ((w->cout + v.rows_per_block() - 1) / v.rows_per_block() > 65535) return false;
-    // de-interleaved tensors and fused shortcuts are understood by the linear-address kernels only
-    // (the wide-tile family computes every address through the general layout function, so it
-    // reads and writes de-interleaved tensors as well; it fuses nothing)
-    if (g.ex && v.family != FAM_LINEAR) return false;
-    if ((g.xd.s2d || g.out_s2d) && v.family != FAM_LINEAR && v.family != FAM_WTILE) return false;
-    if (v.family == FAM_DENSE)
-        return any_density || (double)w->nnz >= 0.25 * (double)w->cout * w->cin * w->kh * w->kw;
+    // de-interleaved tensors and fused shortcuts are understood by the linear-address kernels
+    // and by the large-tile matrix-core kernel (which fuses a projection shortcut as more of
+    // K); the wide-tile family computes every address through the general layout function, so
+    // it reads and writes de-interleaved tensors as well, and fuses nothing
+    const bool wide_dense = v.family == FAM_DENSE && v.tw == 128;
+    if (g.ex && v.family != FAM_LINEAR && !(wide_dense && g.ex->w && !g.ex->pool_y && !g.ex->dw)) return false;
+    if ((g.xd.s2d || g.out_s2d) && v.family != FAM_LINEAR && v.family != FAM_WTILE && !wide_dense) return false;
+    if (v.family == FAM_DENSE) {
+        const bool dense_enough = (double)w->nnz >= 0.25 * (double)w->cout * w->cin * w->kh * w->kw;
+        const int64_t pixels = (int64_t)g.n * g.hout * g.wout;
+        // in 2-byte storage a candidate for the measured selection at any density, once the batch
+        // of pixels gives the matrix cores a few tiles
+        const bool by_tuning = v.is_f16 && pixels >= 256;
+        if (!wide_dense) return any_density || dense_enough || by_tuning;
+        int64_t in_bytes = g.xd.image * 2 * g.n;
+        if (g.ex) {
+            // (a de-interleaved shortcut input is handed over as the plain view of one phase)
+            if (g.ex->w->cin % 32 != 0 || (g.ex->xd.s2d && g.ex->stride != 2)) return false;
+            in_bytes = std::max<int64_t>(in_bytes, g.ex->xd.image * 2 * g.n);
+        }
+        if (!dense_wide_serves(v.is_f16, w->cin, w->kh * w->kw, in_bytes,
+                               (int64_t)w->cout * (g.hout + 64) * (g.wout + 64) * 2 * g.n, pixels))
+            return false;
+        // a de-interleaved input is walked phase by phase (stride 2, taps starting inside the
+        // halo) or pixel by pixel (stride 1, 1x1)
+        if (g.xd.s2d && !(g.stride == 2 ? (g.xd.ph >= g.pad && g.xd.pw >= g.pad) : (g.stride == 1 && w->kh * w->kw == 1 && g.pad == 0)))
+            return false;
+        return any_density || dense_enough || by_tuning;
+    }
     if (v.family == FAM_LINEAR) {
         const bool one = w->kh == 1 && w->kw == 1;
         if (g.xd.s2d) {
@@ -141,6 +163,7 @@ static std::vector<const ConvVariant*> candidates(const cadnn_weights* w, const 
     for (const ConvVariant& v : all_direct_variants()) if (variant_fits(v, w, g)) out.push_back(&v);
     for (const ConvVariant& v : all_tile_variants()) if (variant_fits(v, w, g)) out.push_back(&v);
     for (const ConvVariant& v : all_dense_variants()) if (variant_fits(v, w, g)) out.push_back(&v);
+    for (const ConvVariant& v : all_dense_wide_variants()) if (variant_fits(v, w, g)) out.push_back(&v);
     for (const ConvVariant& v : all_stile_variants()) if (variant_fits(v, w, g)) out.push_back(&v);
     for (const ConvVariant& v : all_ptile_variants()) if (variant_fits(v, w, g)) out.push_back(&v);
     for (const ConvVariant& v : all_wtile_variants()) if (variant_fits(v, w, g)) out.push_back(&v);
@@ -166,8 +189,16 @@ static double variant_cost(const cadnn_weights* w, const ConvGeom& g, const Conv
     const double nnz_row = w->cout ? (double)w->nnz / w->cout : 0.0;
     const double pixels = (double)g.hout * g.wout;
     double cost;
-    if (v->family == FAM_DENSE) {
+    if (v->family == FAM_DENSE && v->tw == 128) {
+        // large tiles, two workgroups per CU; for a pruned layer the measured selection decides
+        if ((double)w->nnz < 0.25 * (double)w->cout * w->cin * w->kh * w->kw) return -1.0;
+        const double tm = v->rows_per_block(), tn = 64.0 * v->p;
+        const double blocks = std::ceil(pixels * g.n / tn) * std::ceil(w->cout / tm);
+        const double K = (double)w->cin * w->kh * w->kw;
+        cost = 4000.0 + std::ceil(blocks / 512.0) * std::ceil(K / 32.0) * (300.0 + 1200.0 * tm * tn / 16384.0);
+    } else if (v->family == FAM_DENSE) {
         // matrix cores: 64 x 64 tiles, ~1024 cycles per 32-deep chunk of K per tile
+        if ((double)w->nnz < 0.25 * (double)w->cout * w->cin * w->kh * w->kw) return -1.0;   // by measurement only
         const double blocks = std::ceil(pixels / 64.0) * g.n * std::ceil(w->cout / 64.0);
         const double K = (double)w->cin * w->kh * w->kw;
         cost = 2500.0 + std::ceil(blocks / 256.0) * std::ceil(K / 32.0) * 1100.0;
@@ -278,7 +309,7 @@ static cadnn_status make_launch(const cadnn_weights* w, const ConvVariant* v, co
         }
         a.image2_bytes = (uint32_t)(g.ex->xd.image * (int64_t)w->elem());
     }
-    if (g.xd.s2d && g.stride == 2) {
+    if (g.xd.s2d && g.stride == 2 && v->family != FAM_DENSE) {
         // plain view for the kernel: unit stride over the rows of one phase, starting at the
         // position of tap (0, 0) of output pixel (0, 0); the plan's tap offsets pick the phase
         a.xd.origin = tensor_off(g.xd, -g.pad, -g.pad);

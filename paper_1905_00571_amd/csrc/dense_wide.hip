@@ -1,0 +1,370 @@
+// Dense implicit-GEMM convolution on the matrix cores for fp16 storage, large tiles (gfx950).
+//
+// Y[Cout x pixels] = W[Cout x K] * X~[K x pixels] with K ordered tap-major, k = tap * Cin + ci,
+// so that the eight consecutive k values an MFMA lane supplies are eight consecutive input
+// channels of one filter tap.  It is the dense side of the dense-vs-compressed comparison
+// (paper Section 5) at the batch sizes where a layer is a real contraction, and a candidate
+// the per-layer selection may pick for any layer in fp16 storage (Section 4, parameter
+// selection by measurement), whatever its sparsity: a pruned layer run densely does 1 / density
+// times the multiply-adds, at 32 times the vector-ALU rate.
+//
+// A fused 1x1 projection shortcut (Section 4, layer fusion) is more of K: its weights follow the
+// layer's own in every row of the matrix and its input is gathered, with its own stride, for
+// the steps behind the layer's own.  De-interleaved tensors are written and read in place.
+//
+// One workgroup (4 waves, 2 x 2) computes 128 output channels x 128 output pixels; a wave owns
+// 64 x 64 as 2 x 2 accumulators of v_mfma_f32_32x32x16_f16 (instantiations with 64 channels
+// and/or 64 pixels serve the layers too small to fill the chip with the large tile).  The pixels of a tile are numbered
+// over the whole batch (n * Hout * Wout + q), so small images fill their tiles.  K is walked in
+// steps of 32 = 32 channels of one tap:
+//   * weights [128][32] arrive as 16-byte loads from the reordered matrix and lie in LDS with
+//     rows 80 bytes apart (the 16-byte fragment reads of 16 lanes hit 16 different bank groups);
+//   * activations [32][128]: lane l of wave w gathers pixels l and l + 64 of channels
+//     8w .. 8w+7 with 2-byte loads -- address = pixel's own offset + tap offset, in the vector
+//     part, + channel plane, in the scalar part; a tap that falls outside the image for a
+//     pixel gets an out-of-range offset and reads zero, so any padding works with or without
+//     a halo in memory.  The eight channels of a pixel are packed into one 16-byte LDS write,
+//     [pixel][k] with rows 80 bytes apart like the weights: the transposition NCHW needs on
+//     the way to the matrix cores happens in registers, and both MFMA operands are single
+//     16-byte LDS reads.
+// Global loads run D steps ahead in D register sets (2 for the largest tile, 8 for the
+// smallest): those of step s+D are issued before the MFMAs of step s, after which step s+1 is
+// written to the other LDS buffer: one barrier per step.  Epilogue: bias, residual, ReLU fused (Section 4).
+#include <type_traits>
+
+#include "internal.h"
+
+namespace cadnn {
+
+namespace {
+
+constexpr int WK = 32;
+constexpr int PITCH = 40;         // halves between the rows of both operands in LDS (80 bytes)
+constexpr uint32_t kWideOutOfRange = 0x7ffffff0u;
+
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef float f32x16w __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4w __attribute__((ext_vector_type(4)));
+
+struct WideArgs {
+    const _Float16* w;        // [cout rounded up to 128][K] reordered tap-major, zero rows beyond cout
+    const _Float16* x;
+    _Float16* y;
+    const float* bias;
+    const _Float16* residual;
+    TensorDesc xd, yd, rd;
+    int n, cout, cin, kh, kw, stride, pad, relu;
+    int hwout, total, K, csteps;   // total = n * hwout; csteps = cin / 32; K = row length of w
+    // a fused 1x1 projection shortcut (x2 != NULL): csteps2 more steps of K read from x2, a
+    // plain view walked with stride2 from pixel (0, 0); its bias is added as well
+    const _Float16* x2;
+    const float* bias2;
+    TensorDesc x2d;
+    int stride2, csteps2;
+};
+
+template <int I, int N, class F>
+__device__ __forceinline__ void wide_static_for(F&& f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>());
+        wide_static_for<I + 1, N>(f);
+    }
+}
+
+// MI x NI accumulators of 32 x 32 per wave: a workgroup's tile is 64 MI channels x 64 NI pixels.
+// D (even): register sets, that is how many steps ahead of the MFMAs the global loads run.
+template <int MI, int NI, int D>
+__global__ __launch_bounds__(256) void dense_wide_kernel(const WideArgs a) {
+    constexpr int TM = 64 * MI, TN = 64 * NI;
+    __shared__ __attribute__((aligned(16))) _Float16 As[2][TM * PITCH];
+    __shared__ __attribute__((aligned(16))) _Float16 Bs[2][TN * PITCH];
+
+    const int lane = threadIdx.x & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wv >> 1, wn = wv & 1;
+    const int n0 = (int)blockIdx.x * TN, m0 = (int)blockIdx.y * TM;
+
+    // ---- gather side: pixels n0 + lane (+ 64) -- byte offset of their own input position (tap
+    //      offsets are added per step) and the taps that fall inside the image
+    uint32_t gbase[NI], gbase2[NI];
+    uint64_t gmask[NI];
+#pragma unroll
+    for (int h = 0; h < NI; ++h) {
+        const int Q = n0 + lane + 64 * h;
+        gbase[h] = 0;
+        gbase2[h] = kWideOutOfRange;
+        gmask[h] = 0;
+        if (Q < a.total) {
+            const int img = Q / a.hwout, q = Q - img * a.hwout;
+            const int oh = q / a.yd.w, ow = q - oh * a.yd.w;
+            // (de-interleaved input: a stride-2 layer walks the phase planes with unit stride,
+            // a pixel-wise stride-1 layer takes each pixel's own place)
+            const int at = !a.xd.s2d ? a.xd.origin + oh * a.stride * a.xd.pitch + ow * a.stride
+                           : a.stride == 2 ? oh * a.xd.pitch + ow : tensor_off(a.xd, oh, ow);
+            gbase[h] = (uint32_t)(img * (int)a.xd.image + at) * 2u;
+            if (a.x2)
+                gbase2[h] = (uint32_t)(img * (int)a.x2d.image + a.x2d.origin + oh * a.stride2 * a.x2d.pitch + ow * a.stride2) * 2u;
+            for (int r = 0; r < a.kh; ++r)
+                for (int c = 0; c < a.kw; ++c) {
+                    const int ih = oh * a.stride + r - a.pad, iw = ow * a.stride + c - a.pad;
+                    if (ih >= 0 && ih < a.xd.h && iw >= 0 && iw < a.xd.w) gmask[h] |= (uint64_t)1 << (r * a.kw + c);
+                }
+        }
+    }
+    // (readfirstlane: the compiler must keep the buffer descriptors in scalar registers)
+    const uint32_t xspan = __builtin_amdgcn_readfirstlane((uint32_t)(a.xd.image * 2) * (uint32_t)a.n);
+    const uint32_t x2span = __builtin_amdgcn_readfirstlane(a.x2 ? (uint32_t)(a.x2d.image * 2) * (uint32_t)a.n : 0u);
+    const uint32_t plane2_bytes = (uint32_t)a.x2d.plane * 2u;
+    const int taps = a.kh * a.kw;
+    const uint32_t plane_bytes = (uint32_t)a.xd.plane * 2u;
+
+    // ---- weight side: thread t fetches 16-byte pieces t (+ 256) of the [TM][32] tile
+    const int apart = (int)threadIdx.x & 3;
+    const _Float16* wrow[MI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i) wrow[i] = a.w + (size_t)(m0 + (((int)threadIdx.x + 256 * i) >> 2)) * a.K + apart * 8;
+
+    // D register sets: the loads of step s + D are issued while step s is multiplied and step
+    // s + 1, fetched D - 1 steps earlier, is written to LDS.  Steps are fetched in order, so
+    // the (tap, channel block) of the next fetch is carried along instead of divided out.
+    u32x4w areg[D][MI];
+    uint32_t breg[D][NI][8];
+    // Past the last step the last one is fetched again (never used): no branch around the
+    // loads, so that the counts of loads in flight stay known at compile time.
+    const int steps = taps * a.csteps + a.csteps2;
+    int f_tap = 0, f_cb = 0, f_r = 0, f_c = 0, f_step = 0;      // (scalar)
+    auto fetch = [&](auto SET) {
+        constexpr int S = decltype(SET)::value;
+        const bool second = f_tap >= taps;       // the shortcut's part of K
+        const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
+            second ? (void*)a.x2 : (void*)a.x, 0, second ? x2span : xspan, 0x00020000);
+        const int Rt = f_r - a.pad + a.xd.ph, Ct = f_c - a.pad + a.xd.pw;
+        const int tap_el = !a.xd.s2d ? (f_r - a.pad) * a.xd.pitch + (f_c - a.pad)
+                           : a.stride == 2 ? ((Rt & 1) * 2 + (Ct & 1)) * a.xd.sub + (Rt >> 1) * a.xd.pitch + (Ct >> 1) : 0;
+        const uint32_t tap_off = second ? 0u : (uint32_t)(tap_el * 2);
+        const uint32_t pb = second ? plane2_bytes : plane_bytes;
+#pragma unroll
+        for (int i = 0; i < MI; ++i) areg[S][i] = *(const u32x4w*)(wrow[i] + (size_t)f_step * WK);
+        const uint32_t soff0 = (uint32_t)(f_cb * WK + wv * 8) * pb;
+#pragma unroll
+        for (int h = 0; h < NI; ++h) {
+            const uint32_t voff = second ? gbase2[h] : ((gmask[h] >> f_tap) & 1) ? gbase[h] + tap_off : kWideOutOfRange;
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                breg[S][h][k] = __builtin_amdgcn_raw_buffer_load_b16(xrsrc, voff, soff0 + (uint32_t)k * pb, 0);
+        }
+        const bool more = f_step + 1 < steps;
+        const bool wrap_c = f_cb + 1 == (second ? a.csteps2 : a.csteps);
+        const bool wrap_r = wrap_c && f_c + 1 == a.kw;
+        f_step += more ? 1 : 0;
+        f_cb = !more ? f_cb : wrap_c ? 0 : f_cb + 1;
+        f_tap += more && wrap_c ? 1 : 0;
+        f_c = !(more && wrap_c) ? f_c : wrap_r ? 0 : f_c + 1;
+        f_r += more && wrap_r ? 1 : 0;
+    };
+    auto stash = [&](int buf, auto SET) {
+        constexpr int S = decltype(SET)::value;
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+            *(u32x4w*)(&As[buf][(((int)threadIdx.x + 256 * i) >> 2) * PITCH + apart * 8]) = areg[S][i];
+#pragma unroll
+        for (int h = 0; h < NI; ++h) {
+            u32x4w pk;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) pk[k] = (breg[S][h][2 * k] & 0xffffu) | (breg[S][h][2 * k + 1] << 16);
+            *(u32x4w*)(&Bs[buf][(lane + 64 * h) * PITCH + wv * 8]) = pk;
+        }
+    };
+
+    f32x16w acc[MI][NI];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.0f;
+
+    const int fm = lane & 31, fk = lane >> 5;
+    // step s: LDS buffer s % 2 holds it; register set (s + j) % D holds step s + j, 0 < j < D
+    auto body = [&](auto PAR) {
+        constexpr int P = decltype(PAR)::value;
+        fetch(std::integral_constant<int, P>());
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            h8 af[MI], bf[NI];
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+                af[mi] = *(const h8*)(&As[P & 1][(wm * 32 * MI + mi * 32 + fm) * PITCH + ks * 16 + fk * 8]);
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+                bf[ni] = *(const h8*)(&Bs[P & 1][(wn * 32 * NI + ni * 32 + fm) * PITCH + ks * 16 + fk * 8]);
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni)
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[mi], bf[ni], acc[mi][ni], 0, 0, 0);
+        }
+        stash((P + 1) & 1, std::integral_constant<int, (P + 1) % D>());
+        __syncthreads();
+    };
+    wide_static_for<0, D>([&](auto J) { fetch(J); });
+    stash(0, std::integral_constant<int, 0>());
+    __syncthreads();
+    int s = 0;
+    for (; s + D <= steps; s += D) wide_static_for<0, D>([&](auto J) { body(J); });
+    wide_static_for<0, D - 1>([&](auto J) {
+        if (s + decltype(J)::value < steps) body(J);
+    });
+
+    // ---- fused epilogue.  Lane l holds, per accumulator, pixel column l % 32 and the 16 rows
+    //      8 * (i / 4) + 4 * (l / 32) + i % 4.
+    const uint32_t yspan = __builtin_amdgcn_readfirstlane((uint32_t)(a.yd.image * 2) * (uint32_t)a.n);
+    const uint32_t rspan = __builtin_amdgcn_readfirstlane(a.residual ? (uint32_t)(a.rd.image * 2) * (uint32_t)a.n : 0u);
+    const __amdgpu_buffer_rsrc_t yrsrc = __builtin_amdgcn_make_buffer_rsrc((void*)a.y, 0, yspan, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        a.residual ? (void*)a.residual : (void*)a.y, 0, rspan, 0x00020000);
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) {
+        const int Q = n0 + wn * 32 * NI + ni * 32 + fm;
+        uint32_t yoff = kWideOutOfRange, roff = kWideOutOfRange;
+        if (Q < a.total) {
+            const int img = Q / a.hwout, q = Q - img * a.hwout;
+            const int oh = q / a.yd.w, ow = q - oh * a.yd.w;
+            yoff = (uint32_t)(img * (int)a.yd.image + tensor_off(a.yd, oh, ow)) * 2u;
+            roff = (uint32_t)(img * (int)a.rd.image + tensor_off(a.rd, oh, ow)) * 2u;
+        }
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int co = m0 + wm * 32 * MI + mi * 32 + (i >> 2) * 8 + fk * 4 + (i & 3);
+                const bool live = co < a.cout;
+                const int cc = live ? co : 0;
+                float v = acc[mi][ni][i] + (a.bias ? a.bias[cc] : 0.0f) + (a.bias2 ? a.bias2[cc] : 0.0f);
+                if (a.residual)
+                    v += (float)__builtin_bit_cast(
+                        _Float16, __builtin_amdgcn_raw_buffer_load_b16(rrsrc, live ? roff + (uint32_t)cc * (uint32_t)a.rd.plane * 2u : kWideOutOfRange, 0u, 0));
+                if (a.relu) v = v > 0.0f ? v : 0.0f;
+                __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, (_Float16)v), yrsrc,
+                                                      live ? yoff + (uint32_t)cc * (uint32_t)a.yd.plane * 2u : kWideOutOfRange, 0u, 0);
+            }
+    }
+}
+
+// [cout][cin][kh][kw] -> [cout rounded up to 128][tap * cin + ci], fp16, zero rows beyond cout.
+__global__ __launch_bounds__(256) void dense_wide_reorder_kernel(const _Float16* __restrict__ w, _Float16* __restrict__ out,
+                                                                 int cout, int cin, int taps, size_t total) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+        const size_t K = (size_t)cin * taps;
+        const int m = (int)(i / K);
+        const int k = (int)(i - (size_t)m * K);
+        const int tap = k / cin, ci = k - tap * cin;
+        out[i] = m < cout ? w[((size_t)m * cin + ci) * taps + tap] : (_Float16)0.0f;
+    }
+}
+
+template <int MI, int NI>
+hipError_t launch_wide_tile(const WideArgs& a, hipStream_t s) {
+    // (the smaller the tile, the fewer registers a set takes and the more a wave needs in flight)
+    constexpr int D = MI * NI == 4 ? 2 : MI * NI == 2 ? 4 : 8;
+    dim3 grid((unsigned)((a.total + 64 * NI - 1) / (64 * NI)), (unsigned)((a.cout + 64 * MI - 1) / (64 * MI)), 1);
+    CADNN_LAUNCH((dense_wide_kernel<MI, NI, D>), grid, dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_wide_args(const WideArgs& a, int tm, int tn, hipStream_t s) {
+    if (tm == 128) return tn == 128 ? launch_wide_tile<2, 2>(a, s) : launch_wide_tile<2, 1>(a, s);
+    return tn == 128 ? launch_wide_tile<1, 2>(a, s) : launch_wide_tile<1, 1>(a, s);
+}
+
+WideArgs wide_args(const void* w, const void* x, const TensorDesc& xd, void* y, const TensorDesc& yd, const void* residual,
+                   const TensorDesc& rd, int n, int cout, int kh, int kw, int stride, int pad, const void* bias, int relu) {
+    WideArgs a{};
+    a.w = (const _Float16*)w; a.x = (const _Float16*)x; a.y = (_Float16*)y; a.bias = (const float*)bias;
+    a.residual = (const _Float16*)residual;
+    a.xd = xd; a.yd = yd; a.rd = rd;
+    a.n = n; a.cout = cout; a.cin = xd.c; a.kh = kh; a.kw = kw; a.stride = stride; a.pad = pad; a.relu = relu ? 1 : 0;
+    a.hwout = yd.h * yd.w;
+    a.total = n * a.hwout;
+    a.K = xd.c * kh * kw;
+    a.csteps = xd.c / WK;
+    return a;
+}
+
+WideArgs wide_args(const ConvLaunch& l) {
+    WideArgs a = wide_args(l.nz, l.x, l.xd, l.y, l.yd, l.residual, l.rd, l.n, l.cout, l.kh, l.kw, l.stride, l.pad, l.bias, l.relu);
+    if (l.x2) {
+        a.x2 = (const _Float16*)l.x2;
+        a.bias2 = l.bias2;
+        a.x2d = l.x2d;
+        a.stride2 = l.stride2;
+        a.csteps2 = l.x2d.c / WK;
+        a.K += l.x2d.c;
+    }
+    return a;
+}
+
+template <int TM, int TN>
+hipError_t launch_wide_variant(const ConvLaunch& l, hipStream_t s) {
+    return launch_wide_args(wide_args(l), TM, TN, s);
+}
+
+}  // namespace
+
+bool dense_wide_serves(bool is_f16, int cin, int taps, int64_t in_bytes, int64_t out_bytes, int64_t pixels) {
+    // (the whole batch sits behind 32-bit byte offsets)
+    return is_f16 && cin % WK == 0 && taps <= 64 && in_bytes < 0x7ffffff0ll && out_bytes < 0x7ffffff0ll && pixels < 0x7fffff00ll;
+}
+
+// tw == 128 marks the tap-major weight matrix with rows padded to 128 (build_dense_plan); the
+// tile is rpw * nw channels x 64 p pixels.
+const std::vector<ConvVariant>& all_dense_wide_variants() {
+    static const std::vector<ConvVariant> v = [] {
+        std::vector<ConvVariant> out;
+        auto add = [&](const char* name, int tm, int tn, hipError_t (*launch)(const ConvLaunch&, hipStream_t)) {
+            ConvVariant d{};
+            d.name = name;
+            d.family = FAM_DENSE;
+            d.is_f16 = true;
+            d.nw = 4; d.rpw = tm / 4; d.ks = 1; d.p = tn / 64; d.unroll = 1;
+            d.tw = 128;
+            d.launch = launch;
+            out.push_back(d);
+        };
+        add("dense_mfma__Float16_128x128x32", 128, 128, &launch_wide_variant<128, 128>);
+        add("dense_mfma__Float16_128x64x32", 128, 64, &launch_wide_variant<128, 64>);
+        add("dense_mfma__Float16_64x128x32", 64, 128, &launch_wide_variant<64, 128>);
+        add("dense_mfma__Float16_64x64x32w", 64, 64, &launch_wide_variant<64, 64>);
+        return out;
+    }();
+    return v;
+}
+
+// The comparator on raw device weights [cout][cin][kh][kw] (fp16).  The tap-major copy of the
+// weights is made on every call, in stream order (a caller that times the kernel alone packs
+// the dense tensor into a weight handle and pins one of the variants above: then the copy is
+// part of the plan).  The tile is the largest that still gives every CU two workgroups.
+cadnn_status dense_wide_conv2d_raw(const void* w_dev, const void* x, const TensorDesc& xd, void* y, const TensorDesc& yd,
+                                   const void* residual, const TensorDesc& rd, int n, int cout, int kh, int kw, int stride,
+                                   int pad, const void* bias, int relu, hipStream_t s) {
+    const size_t rows = (size_t)(cout + 127) / 128 * 128, K = (size_t)xd.c * kh * kw, total = rows * K;
+    void* wr = nullptr;
+    hipError_t e = hipMallocAsync(&wr, total * 2, s);
+    if (e != hipSuccess) return fail(CADNN_ENOMEM, "hipMallocAsync(%zu) failed: %s", total * 2, hipGetErrorString(e));
+    const unsigned blocks = (unsigned)std::min<size_t>((total + 255) / 256, 4096);
+    CADNN_LAUNCH(dense_wide_reorder_kernel, dim3(blocks), dim3(256), 0, s, (const _Float16*)w_dev, (_Float16*)wr, cout, xd.c,
+                 kh * kw, total);
+    const WideArgs a = wide_args(wr, x, xd, y, yd, residual, rd, n, cout, kh, kw, stride, pad, bias, relu);
+    int tm = 128, tn = 128;
+    auto blocks_of = [&](int m, int nn) { return (int64_t)((a.total + nn - 1) / nn) * ((cout + m - 1) / m); };
+    if (blocks_of(tm, tn) < 512 && cout <= 64) tm = 64;
+    if (blocks_of(tm, tn) < 512) tn = 64;
+    if (blocks_of(tm, tn) < 512) tm = 64;
+    e = launch_wide_args(a, tm, tn, s);
+    const hipError_t e2 = hipFreeAsync(wr, s);
+    CADNN_HIP(e);
+    CADNN_HIP(e2);
+    return CADNN_OK;
+}
+
+}  // namespace cadnn

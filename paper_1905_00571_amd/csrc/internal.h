@@ -410,6 +410,13 @@ const std::vector<ConvVariant>& all_tile_variants();
 const std::vector<ConvVariant>& all_direct_variants();
 const std::vector<ConvVariant>& all_linear_variants();
 const std::vector<ConvVariant>& all_dense_variants();
+// fp16 storage, 128 x 128 tiles, tap-major weight matrix (marked by tw == 128)
+const std::vector<ConvVariant>& all_dense_wide_variants();
+// (in_bytes / out_bytes: the whole batch of the largest tensor on each side)
+bool dense_wide_serves(bool is_f16, int cin, int taps, int64_t in_bytes, int64_t out_bytes, int64_t pixels);
+cadnn_status dense_wide_conv2d_raw(const void* w_dev, const void* x, const TensorDesc& xd, void* y, const TensorDesc& yd,
+                                   const void* residual, const TensorDesc& rd, int n, int cout, int kh, int kw, int stride,
+                                   int pad, const void* bias, int relu, hipStream_t s);
 const std::vector<ConvVariant>& all_stile_variants();
 const std::vector<ConvVariant>& all_ptile_variants();
 const std::vector<ConvVariant>& all_wtile_variants();

@@ -751,9 +751,15 @@ static cadnn_status build_stile_plan(const cadnn_weights* w, const ConvVariant* 
     return CADNN_OK;
 }
 
-// Plan of the dense fallback: the unpacked [cout][K] matrix in the storage type.
-static cadnn_status build_dense_plan(const cadnn_weights* w, const ConvVariant* v, ConvPlan* plan) {
-    const size_t K = (size_t)w->cin * w->kh * w->kw;
+// Plan of the dense kernels: the unpacked [cout][K] matrix in the storage type; for the
+// 128 x 128-tile kernel with K ordered tap-major and the rows padded with zeros to whole tiles.
+static cadnn_status build_dense_plan(const cadnn_weights* w, const ConvVariant* v, ConvPlan* plan, const ConvExtra* ex) {
+    if (ex && !ex->w) ex = nullptr;
+    if (ex && (v->tw != 128 || ex->w->cout != w->cout || ex->w->kh != 1 || ex->w->kw != 1 || ex->w->dtype != w->dtype))
+        return fail(CADNN_EINVAL, "fused shortcut and kernel variant do not match");
+    // (a fused 1x1 shortcut's weights follow the layer's own in every row)
+    const size_t K1 = (size_t)w->cin * w->kh * w->kw;
+    const size_t K = K1 + (ex ? (size_t)ex->w->cin : 0);
     plan->variant = v;
     plan->nchunks = 1;
     plan->rows_padded = (w->cout + 63) / 64 * 64;
@@ -761,7 +767,23 @@ static cadnn_status build_dense_plan(const cadnn_weights* w, const ConvVariant* 
     plan->walked = plan->nz_padded;
     plan->entry_bytes = (int)w->elem();
     cadnn_status st;
-    if (w->dtype == CADNN_F16) {
+    if (v->tw == 128) {
+        const int taps = w->kh * w->kw;
+        plan->rows_padded = (w->cout + 127) / 128 * 128;
+        plan->nz_padded = (int64_t)((size_t)plan->rows_padded * K);
+        plan->walked = plan->nz_padded;
+        std::vector<uint16_t> dense((size_t)plan->rows_padded * K, 0);
+        for (int i = 0; i < w->cout; ++i)
+            for (int32_t j = w->row_ptr[i]; j < w->row_ptr[i + 1]; ++j) {
+                const int ci = w->col_idx[j] / taps, tap = w->col_idx[j] - ci * taps;
+                dense[(size_t)w->perm[i] * K + (size_t)tap * w->cin + ci] = w->vals16[j];
+            }
+        if (ex)
+            for (int i = 0; i < ex->w->cout; ++i)
+                for (int32_t j = ex->w->row_ptr[i]; j < ex->w->row_ptr[i + 1]; ++j)
+                    dense[(size_t)ex->w->perm[i] * K + K1 + (size_t)ex->w->col_idx[j]] = ex->w->vals16[j];
+        st = plan->nz.upload(dense.data(), dense.size() * 2);
+    } else if (w->dtype == CADNN_F16) {
         std::vector<uint16_t> dense((size_t)w->cout * K, 0);
         for (int i = 0; i < w->cout; ++i)
             for (int32_t j = w->row_ptr[i]; j < w->row_ptr[i + 1]; ++j)
@@ -779,11 +801,12 @@ static cadnn_status build_dense_plan(const cadnn_weights* w, const ConvVariant* 
 
 static cadnn_status build_plan(const cadnn_weights* w, const ConvVariant* v, const TensorDesc& xd, int stride,
                                int pad, int wout, ConvPlan* plan, const ConvExtra* ex) {
-    if (ex && v->family != FAM_LINEAR) return fail(CADNN_EINVAL, "a fused shortcut or pool needs a linear-address kernel");
+    if (ex && v->family != FAM_LINEAR && !(v->family == FAM_DENSE && v->tw == 128 && ex->w && !ex->pool_y && !ex->dw))
+        return fail(CADNN_EINVAL, "a fused shortcut or pool needs a linear-address kernel");
     switch (v->family) {
         case FAM_PTILE: return build_ptile_plan(w, v, stride, pad, wout, plan);
         case FAM_WTILE: return build_wtile_plan(w, v, stride, plan);
-        case FAM_DENSE: return build_dense_plan(w, v, plan);
+        case FAM_DENSE: return build_dense_plan(w, v, plan, ex);
         case FAM_STILE: return build_stile_plan(w, v, plan);
         case FAM_DIRECT: return build_direct_plan(w, v, plan);
         case FAM_LINEAR: return build_linear_plan(w, v, xd, plan, ex);
@@ -854,6 +877,7 @@ static PlanKey plan_key(const cadnn_weights* w, const ConvVariant* v, const Tens
     if (v->family == FAM_PTILE)
         return PlanKey(v, stride, ptile_geom(*v, w->cin, w->kh, w->kw, stride, pad, wout).alias, nullptr, 0);
     if (v->family == FAM_WTILE) return PlanKey(v, stride, 0, nullptr, 0);
+    if (v->family == FAM_DENSE) return PlanKey(v, 0, 0, (ex && ex->w) ? (const void*)ex->w : nullptr, 0);
     return PlanKey(v, 0, 0, nullptr, 0);
 }
 

@@ -5,7 +5,7 @@ import pytest
 import oracle
 import workloads as wl
 from util import (TOL_F32, TOL_F16, F16_ULP, SUM_TOL, assert_close, assert_layer_close, assert_chain_close,
-                  assert_net_close, cond_conv, cond_fc, cond_depthwise)
+                  assert_net_close, cond_conv, cond_fc, cond_depthwise, chain_bounds, assert_within_bound)
 
 pytestmark = pytest.mark.gpu
 
@@ -325,6 +325,11 @@ VARIANT_GEOMS = [
     (19, 33, 1, 1, 0, 9, 9, 0.0, 1),
     (40, 24, 1, 1, 0, 12, 20, 0.8, 2),    # even width: adjacent-pixel wide loads
     (40, 3, 3, 2, 1, 30, 27, 0.0, 2),     # unpruned, few input channels (a network's first layer)
+    # whole 32-channel steps and a few thousand pixels: the 128 x 128-tile matrix-core kernel
+    # is a candidate too (fp16 storage), whatever the sparsity
+    (64, 150, 3, 1, 1, 30, 25, 0.8, 3),
+    (32, 40, 3, 2, 1, 41, 37, 0.6, 4),
+    (96, 130, 1, 1, 0, 29, 31, 0.85, 3),
 ]
 
 
@@ -375,6 +380,8 @@ def test_every_kernel_variant(cad, geom):
         hnd = cad.cadnn_pack_weights(w, dtype)
         names = cad.cadnn_conv2d_list_variants(hnd, n, h, w_, stride, pad)
         assert names, geom
+        if dtype == cad.F16 and cin % 32 == 0 and n * hout * wout >= 2048:
+            assert "dense_mfma__Float16_128x128x32" in names, names
         xd, rd, bd = dev(xs), dev(rs), dev(b)
         for name in names:
             cad.cadnn_conv2d_set_variant(hnd, n, h, w_, stride, pad, name)
@@ -396,7 +403,11 @@ def test_every_kernel_variant(cad, geom):
 
 @pytest.mark.parametrize("geom", [(3, 64, 7, 2, 3, 56, 56, 1), (64, 64, 3, 1, 1, 28, 28, 2),
                                   (100, 70, 1, 1, 0, 13, 13, 1), (33, 40, 3, 2, 1, 19, 23, 1),
-                                  (16, 8, 5, 1, 2, 11, 11, 1)])
+                                  (16, 8, 5, 1, 2, 11, 11, 1),
+                                  # whole 32-channel steps: in fp16 storage the 128 x 128-tile kernel
+                                  (32, 200, 3, 2, 1, 19, 23, 3), (96, 130, 1, 1, 0, 13, 13, 2),
+                                  (32, 16, 7, 2, 3, 30, 30, 1), (64, 70, 5, 1, 2, 11, 11, 1),
+                                  (128, 129, 3, 1, 2, 9, 14, 5)])
 def test_dense_comparator(cad, geom):
     """cadnn_dense_conv2d (matrix-core implicit GEMM over the dense tensor) meets the same bar."""
     cin, cout, k, stride, pad, h, w_, n = geom
@@ -550,6 +561,49 @@ def test_fused_projection_shortcut(cad, geom):
         assert np.abs(yf - yu).max() <= tol * np.abs(ref).max()
         net.free()
         unfused.free()
+
+
+@pytest.mark.parametrize("geom", [(20, 28, 2, 2), (13, 11, 7, 2), (14, 14, 2, 1)])
+def test_matrix_core_variants_in_a_bottleneck(cad, geom):
+    """In 2-byte storage the large-tile matrix-core kernels are candidates for every layer with
+    whole 32-channel steps, whatever its sparsity.  A downsampling bottleneck with such channel
+    counts puts them in every role a net has: writing and reading de-interleaved tensors
+    (pixel-wise, with a strided 3x3 and with a strided 1x1), reading a haloed input, adding a
+    residual, and computing a fused projection shortcut as more of the contraction.  Each is
+    pinned in turn and the layer's output compared with the oracle."""
+    h, w_, n, stride = geom
+    ops = [wl.Op("conv", "t", 0, 1, 8, 64, 1, 1, 0, 0.5, True),
+           wl.Op("conv", "a", 1, 2, 64, 32, 1, 1, 0, 0.8, True),
+           wl.Op("conv", "b", 2, 3, 32, 32, 3, stride, 1, 0.85, True),
+           wl.Op("conv", "p", 1, 4, 64, 136, 1, stride, 0, 0.8, False),
+           wl.Op("conv", "c", 3, 5, 32, 136, 1, 1, 0, 0.8, True, 4),
+           wl.Op("conv", "post", 5, 6, 136, 6, 1, 1, 0, 0.2, False)]
+    shape = (n, 8, h, w_)
+    x, ws, bs = wl.net_tensors(ops, "mfma-%d-%d-%d" % (h, w_, stride), shape, input_relu=True)
+    npdt, tol = np.float16, TOL_F16
+    xs = x.astype(npdt)
+    ref, ins, outs = oracle.run_net(ops, xs, ws, bs, dtype=npdt)
+    bounds = chain_bounds(ops, ins, outs, ws, bs, True)
+    xd = dev(xs)
+    for fuse in (False, True):
+        net = cad.build_net(ops, ws, bs, shape, cad.F16, use_graph=False, fuse=fuse)
+        assert (net.op_variant(3) == "fused") == fuse
+        for i in (1, 2, 3, 4):
+            if fuse and i == 3:
+                continue
+            names = [nm for nm in net.op_candidates(i) if nm.startswith("dense_mfma__Float16_") and not nm.endswith("_64x64x32")]
+            assert len(names) == 4, (i, net.op_candidates(i))
+            for name in names:
+                net.set_op_variant(i, name)
+                assert net.op_variant(i) == name
+                net.run(xd)
+                torch.cuda.synchronize()
+                got = net.read_buffer(ops[i].dst, outs[i].shape)
+                # (the layer's input is what the net's own earlier layers left: the bound of
+                # the chain up to here, not of the layer alone)
+                assert_within_bound(got, outs[i], bounds[i], f"{geom} fuse={fuse} op {ops[i].name} {name}")
+                assert np.abs(got.astype(np.float64) - outs[i].astype(np.float64)).max() <= tol * np.abs(outs[i]).max()
+        net.free()
 
 
 @pytest.mark.parametrize("geom", [(7, 7, 1, 1), (7, 7, 3, 3), (14, 14, 2, 1), (9, 5, 2, 3)])
