@@ -73,8 +73,13 @@ __device__ __forceinline__ void wide_static_for(F&& f) {
 
 // MI x NI accumulators of 32 x 32 per wave: a workgroup's tile is 64 MI channels x 64 NI pixels.
 // D (even): register sets, that is how many steps ahead of the MFMAs the global loads run.
-template <int MI, int NI, int D>
+// PAIR (NI = 2, output and residual laid out so that pixels 2j and 2j+1 of the batch-wide
+// numbering are neighbours at an even element offset): column c of a wave's two accumulators
+// holds pixels 2c and 2c+1, so a lane writes -- and reads the residual of -- two pixels with one
+// 4-byte access and a wave's store covers 128 contiguous bytes per channel instead of 64.
+template <int MI, int NI, int D, bool PAIR>
 __global__ __launch_bounds__(256) void dense_wide_kernel(const WideArgs a) {
+    static_assert(!PAIR || NI == 2, "pixel pairs take the two accumulators of a wave");
     constexpr int TM = 64 * MI, TN = 64 * NI;
     __shared__ __attribute__((aligned(16))) _Float16 As[2][TM * PITCH];
     __shared__ __attribute__((aligned(16))) _Float16 Bs[2][TN * PITCH];
@@ -90,7 +95,8 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(const WideArgs a) {
     uint64_t gmask[NI];
 #pragma unroll
     for (int h = 0; h < NI; ++h) {
-        const int Q = n0 + lane + 64 * h;
+        // (LDS row lane + 64 h feeds MFMA column lane % 32 of accumulator lane / 32 of wave h)
+        const int Q = n0 + 64 * h + (PAIR ? 2 * (lane & 31) + (lane >> 5) : lane);
         gbase[h] = 0;
         gbase2[h] = kWideOutOfRange;
         gmask[h] = 0;
@@ -223,16 +229,19 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(const WideArgs a) {
     const __amdgpu_buffer_rsrc_t yrsrc = __builtin_amdgcn_make_buffer_rsrc((void*)a.y, 0, yspan, 0x00020000);
     const __amdgpu_buffer_rsrc_t rrsrc = __builtin_amdgcn_make_buffer_rsrc(
         a.residual ? (void*)a.residual : (void*)a.y, 0, rspan, 0x00020000);
-#pragma unroll
-    for (int ni = 0; ni < NI; ++ni) {
-        const int Q = n0 + wn * 32 * NI + ni * 32 + fm;
-        uint32_t yoff = kWideOutOfRange, roff = kWideOutOfRange;
+    auto place = [&](int Q, uint32_t& yoff, uint32_t& roff) {
+        yoff = kWideOutOfRange;
+        roff = kWideOutOfRange;
         if (Q < a.total) {
             const int img = Q / a.hwout, q = Q - img * a.hwout;
             const int oh = q / a.yd.w, ow = q - oh * a.yd.w;
             yoff = (uint32_t)(img * (int)a.yd.image + tensor_off(a.yd, oh, ow)) * 2u;
             roff = (uint32_t)(img * (int)a.rd.image + tensor_off(a.rd, oh, ow)) * 2u;
         }
+    };
+    if constexpr (PAIR) {
+        uint32_t yoff, roff;
+        place(n0 + wn * 64 + 2 * fm, yoff, roff);       // (the number of pixels is even: both or neither)
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
@@ -240,14 +249,40 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(const WideArgs a) {
                 const int co = m0 + wm * 32 * MI + mi * 32 + (i >> 2) * 8 + fk * 4 + (i & 3);
                 const bool live = co < a.cout;
                 const int cc = live ? co : 0;
-                float v = acc[mi][ni][i] + (a.bias ? a.bias[cc] : 0.0f) + (a.bias2 ? a.bias2[cc] : 0.0f);
-                if (a.residual)
-                    v += (float)__builtin_bit_cast(
-                        _Float16, __builtin_amdgcn_raw_buffer_load_b16(rrsrc, live ? roff + (uint32_t)cc * (uint32_t)a.rd.plane * 2u : kWideOutOfRange, 0u, 0));
-                if (a.relu) v = v > 0.0f ? v : 0.0f;
-                __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, (_Float16)v), yrsrc,
-                                                      live ? yoff + (uint32_t)cc * (uint32_t)a.yd.plane * 2u : kWideOutOfRange, 0u, 0);
+                const float b = (a.bias ? a.bias[cc] : 0.0f) + (a.bias2 ? a.bias2[cc] : 0.0f);
+                float v0 = acc[mi][0][i] + b, v1 = acc[mi][1][i] + b;
+                if (a.residual) {
+                    const uint32_t r = __builtin_amdgcn_raw_buffer_load_b32(
+                        rrsrc, live ? roff + (uint32_t)cc * (uint32_t)a.rd.plane * 2u : kWideOutOfRange, 0u, 0);
+                    v0 += (float)__builtin_bit_cast(_Float16, (unsigned short)(r & 0xffffu));
+                    v1 += (float)__builtin_bit_cast(_Float16, (unsigned short)(r >> 16));
+                }
+                if (a.relu) { v0 = v0 > 0.0f ? v0 : 0.0f; v1 = v1 > 0.0f ? v1 : 0.0f; }
+                const uint32_t pk = (uint32_t)__builtin_bit_cast(unsigned short, (_Float16)v0) |
+                                    ((uint32_t)__builtin_bit_cast(unsigned short, (_Float16)v1) << 16);
+                __builtin_amdgcn_raw_buffer_store_b32(pk, yrsrc, live ? yoff + (uint32_t)cc * (uint32_t)a.yd.plane * 2u : kWideOutOfRange, 0u, 0);
             }
+    } else {
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) {
+            uint32_t yoff, roff;
+            place(n0 + wn * 32 * NI + ni * 32 + fm, yoff, roff);
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int co = m0 + wm * 32 * MI + mi * 32 + (i >> 2) * 8 + fk * 4 + (i & 3);
+                    const bool live = co < a.cout;
+                    const int cc = live ? co : 0;
+                    float v = acc[mi][ni][i] + (a.bias ? a.bias[cc] : 0.0f) + (a.bias2 ? a.bias2[cc] : 0.0f);
+                    if (a.residual)
+                        v += (float)__builtin_bit_cast(
+                            _Float16, __builtin_amdgcn_raw_buffer_load_b16(rrsrc, live ? roff + (uint32_t)cc * (uint32_t)a.rd.plane * 2u : kWideOutOfRange, 0u, 0));
+                    if (a.relu) v = v > 0.0f ? v : 0.0f;
+                    __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, (_Float16)v), yrsrc,
+                                                          live ? yoff + (uint32_t)cc * (uint32_t)a.yd.plane * 2u : kWideOutOfRange, 0u, 0);
+                }
+        }
     }
 }
 
@@ -268,7 +303,17 @@ hipError_t launch_wide_tile(const WideArgs& a, hipStream_t s) {
     // (the smaller the tile, the fewer registers a set takes and the more a wave needs in flight)
     constexpr int D = MI * NI == 4 ? 2 : MI * NI == 2 ? 4 : 8;
     dim3 grid((unsigned)((a.total + 64 * NI - 1) / (64 * NI)), (unsigned)((a.cout + 64 * MI - 1) / (64 * MI)), 1);
-    CADNN_LAUNCH((dense_wide_kernel<MI, NI, D>), grid, dim3(256), 0, s, a);
+    if constexpr (NI == 2) {
+        // pixel pairs: neighbours in memory, at even element offsets, in the output and the residual
+        auto pairs = [](const TensorDesc& d) {
+            return !d.s2d && d.w % 2 == 0 && d.pitch % 2 == 0 && d.origin % 2 == 0 && d.plane % 2 == 0 && d.image % 2 == 0;
+        };
+        if (pairs(a.yd) && (!a.residual || pairs(a.rd))) {
+            CADNN_LAUNCH((dense_wide_kernel<MI, NI, D, true>), grid, dim3(256), 0, s, a);
+            return hipGetLastError();
+        }
+    }
+    CADNN_LAUNCH((dense_wide_kernel<MI, NI, D, false>), grid, dim3(256), 0, s, a);
     return hipGetLastError();
 }
 

@@ -417,9 +417,14 @@ struct Layout {
                 if (a.kind != OP_AVGPOOL || a.src_inst < 0) continue;
                 NetOp& c = net->ops[a.src_inst];
                 const bool c_one = c.kind == OP_CONV && c.w->kh == 1 && c.w->kw == 1;
+                // (2-byte storage, whole 32-channel steps and a batch of a thousand pixels or more:
+                // the matrix-core kernels, which fuse no pool, are the likely pick for the layer --
+                // about three times the fused kernel's rate there -- so the pool keeps its launch)
+                const bool mfma_likely = c.kind == OP_CONV && net->dtype == CADNN_F16 && c.w->cin % 32 == 0 &&
+                                         (int64_t)c.out.n * c.out.h * c.out.w >= 1024;
                 const bool ok = c.kind == OP_CONV && !grouped(c) && readers[a.src_inst] == 1 && c.shortcut < 0 && c.fused_into < 0 &&
                                 sparse_enough(c) && !c.yd.s2d && !c.xd.s2d && !(c.res >= 0 && c.rd.s2d) &&
-                                c.out.h * c.out.w <= 256 &&
+                                c.out.h * c.out.w <= 256 && !mfma_likely &&
                                 (c_one ? c.pad == 0 : (c.xd.ph >= c.pad && c.xd.pw >= c.pad));
                 if (ok) {
                     c.pool_op = i;
