@@ -39,7 +39,6 @@ namespace cadnn {
 namespace {
 
 constexpr int WK = 32;
-constexpr int PITCH = 40;         // halves between the rows of both operands in LDS (80 bytes)
 constexpr uint32_t kWideOutOfRange = 0x7ffffff0u;
 
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
@@ -72,15 +71,19 @@ __device__ __forceinline__ void wide_static_for(F&& f) {
 }
 
 // MI x NI accumulators of 32 x 32 per wave: a workgroup's tile is 64 MI channels x 64 NI pixels.
-// D (even): register sets, that is how many steps ahead of the MFMAs the global loads run.
+// HS: 32-deep steps of K per stage, i.e. per barrier (a stage's LDS tile is 32 HS deep); with
+// one or two workgroups on a CU the chain LDS write - barrier - LDS read - MFMA of a stage is
+// not hidden by anything, so it has to be paid as seldom as the LDS size allows.
+// D (even): register sets, that is how many stages ahead of the MFMAs the global loads run.
 // PAIR (NI = 2, output and residual laid out so that pixels 2j and 2j+1 of the batch-wide
 // numbering are neighbours at an even element offset): column c of a wave's two accumulators
 // holds pixels 2c and 2c+1, so a lane writes -- and reads the residual of -- two pixels with one
 // 4-byte access and a wave's store covers 128 contiguous bytes per channel instead of 64.
-template <int MI, int NI, int D, bool PAIR>
+template <int MI, int NI, int HS, int D, bool PAIR>
 __global__ __launch_bounds__(256) void dense_wide_kernel(const WideArgs a) {
     static_assert(!PAIR || NI == 2, "pixel pairs take the two accumulators of a wave");
     constexpr int TM = 64 * MI, TN = 64 * NI;
+    constexpr int PITCH = WK * HS + 8;      // halves between rows in LDS: 80, 144 or 272 bytes, all conflict-free
     __shared__ __attribute__((aligned(16))) _Float16 As[2][TM * PITCH];
     __shared__ __attribute__((aligned(16))) _Float16 Bs[2][TN * PITCH];
 
@@ -124,61 +127,112 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(const WideArgs a) {
     const int taps = a.kh * a.kw;
     const uint32_t plane_bytes = (uint32_t)a.xd.plane * 2u;
 
-    // ---- weight side: thread t fetches 16-byte pieces t (+ 256) of the [TM][32] tile
+    // ---- weight side: thread t fetches 16-byte pieces t (+ 256) of a step's [TM][32] tile
     const int apart = (int)threadIdx.x & 3;
-    const _Float16* wrow[MI];
+    const uint32_t wspan = __builtin_amdgcn_readfirstlane((uint32_t)(((a.cout + 127) / 128 * 128) * a.K * 2));
+    const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc((void*)a.w, 0, wspan, 0x00020000);
+    uint32_t wrow[MI];
 #pragma unroll
-    for (int i = 0; i < MI; ++i) wrow[i] = a.w + (size_t)(m0 + (((int)threadIdx.x + 256 * i) >> 2)) * a.K + apart * 8;
+    for (int i = 0; i < MI; ++i) wrow[i] = (uint32_t)((m0 + (((int)threadIdx.x + 256 * i) >> 2)) * a.K + apart * 8) * 2u;
 
-    // D register sets: the loads of step s + D are issued while step s is multiplied and step
-    // s + 1, fetched D - 1 steps earlier, is written to LDS.  Steps are fetched in order, so
-    // the (tap, channel block) of the next fetch is carried along instead of divided out.
-    u32x4w areg[D][MI];
-    uint32_t breg[D][NI][8];
-    // Past the last step the last one is fetched again (never used): no branch around the
-    // loads, so that the counts of loads in flight stay known at compile time.
+    // ---- the bias lines of the tile are touched now: the epilogue's loads then hit in cache
+    //      instead of adding a memory round trip to the tail
+    if (a.bias && threadIdx.x < TM && m0 + (int)threadIdx.x < a.cout) {
+        float touch;
+        asm volatile("global_load_dword %0, %1, off" : "=v"(touch) : "v"(a.bias + m0 + threadIdx.x) : "memory");
+        asm volatile("s_waitcnt vmcnt(0)" : "+v"(touch));
+    }
+
+    // D register sets: the loads of stage s + D are issued while stage s is multiplied and stage
+    // s + 1, fetched D - 1 stages earlier, is written to LDS.
+    u32x4w areg[D][HS][MI];
+    unsigned short breg[D][HS][NI][8];      // (widened only when the set is used: see stash)
+    // Steps are fetched in order and a wave is one serial instruction stream, so what a step
+    // costs in scalar bookkeeping it costs in time: the state of the walk over K is carried
+    // along -- per step nine scalar additions and a counter -- and everything that depends on
+    // the tap (its offset, which pixels it reaches, the switch to a fused shortcut's input) is
+    // redone only when the tap changes, behind a scalar branch that issues no load.  Past the
+    // last step zeros are fetched (out-of-range offsets on both sides) rather than nothing, so
+    // that the number of loads in flight is known at compile time.
     const int steps = taps * a.csteps + a.csteps2;
-    int f_tap = 0, f_cb = 0, f_r = 0, f_c = 0, f_step = 0;      // (scalar)
-    auto fetch = [&](auto SET) {
-        constexpr int S = decltype(SET)::value;
-        const bool second = f_tap >= taps;       // the shortcut's part of K
-        const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
-            second ? (void*)a.x2 : (void*)a.x, 0, second ? x2span : xspan, 0x00020000);
+    const int stages = (steps + HS - 1) / HS;
+    int f_tap = -1, f_r = 0, f_c = -1, f_left = 0;          // (scalar)
+    bool f_second = false;
+    uint32_t f_soffA = 0, f_inc = 0, f_soffB[8];
+    uint32_t f_vA[MI], f_vB[NI];
+    auto next_tap = [&]() __attribute__((always_inline)) {
+        ++f_tap;
+        if (++f_c == a.kw) { f_c = 0; ++f_r; }
+        const bool live = f_tap < taps + (a.csteps2 ? 1 : 0);
+        f_second = f_tap >= taps;
         const int Rt = f_r - a.pad + a.xd.ph, Ct = f_c - a.pad + a.xd.pw;
         const int tap_el = !a.xd.s2d ? (f_r - a.pad) * a.xd.pitch + (f_c - a.pad)
                            : a.stride == 2 ? ((Rt & 1) * 2 + (Ct & 1)) * a.xd.sub + (Rt >> 1) * a.xd.pitch + (Ct >> 1) : 0;
-        const uint32_t tap_off = second ? 0u : (uint32_t)(tap_el * 2);
-        const uint32_t pb = second ? plane2_bytes : plane_bytes;
+        const uint32_t pb = f_second ? plane2_bytes : plane_bytes;
+        f_inc = live ? WK * pb : 0u;
+        f_left = !live ? 0x7fffffff : f_second ? a.csteps2 : a.csteps;
 #pragma unroll
-        for (int i = 0; i < MI; ++i) areg[S][i] = *(const u32x4w*)(wrow[i] + (size_t)f_step * WK);
-        const uint32_t soff0 = (uint32_t)(f_cb * WK + wv * 8) * pb;
+        for (int k = 0; k < 8; ++k) f_soffB[k] = live ? (uint32_t)(wv * 8 + k) * pb : 0u;
 #pragma unroll
-        for (int h = 0; h < NI; ++h) {
-            const uint32_t voff = second ? gbase2[h] : ((gmask[h] >> f_tap) & 1) ? gbase[h] + tap_off : kWideOutOfRange;
+        for (int h = 0; h < NI; ++h)
+            f_vB[h] = !live ? kWideOutOfRange : f_second ? gbase2[h]
+                      : ((gmask[h] >> f_tap) & 1) ? gbase[h] + (uint32_t)(tap_el * 2) : kWideOutOfRange;
+        if (!live) {
+            f_soffA = 0;
 #pragma unroll
-            for (int k = 0; k < 8; ++k)
-                breg[S][h][k] = __builtin_amdgcn_raw_buffer_load_b16(xrsrc, voff, soff0 + (uint32_t)k * pb, 0);
+            for (int i = 0; i < MI; ++i) f_vA[i] = kWideOutOfRange;
         }
-        const bool more = f_step + 1 < steps;
-        const bool wrap_c = f_cb + 1 == (second ? a.csteps2 : a.csteps);
-        const bool wrap_r = wrap_c && f_c + 1 == a.kw;
-        f_step += more ? 1 : 0;
-        f_cb = !more ? f_cb : wrap_c ? 0 : f_cb + 1;
-        f_tap += more && wrap_c ? 1 : 0;
-        f_c = !(more && wrap_c) ? f_c : wrap_r ? 0 : f_c + 1;
-        f_r += more && wrap_r ? 1 : 0;
     };
-    auto stash = [&](int buf, auto SET) {
+#pragma unroll
+    for (int i = 0; i < MI; ++i) f_vA[i] = wrow[i];
+    next_tap();
+    auto fetch = [&](auto SET) __attribute__((always_inline)) {
         constexpr int S = decltype(SET)::value;
 #pragma unroll
-        for (int i = 0; i < MI; ++i)
-            *(u32x4w*)(&As[buf][(((int)threadIdx.x + 256 * i) >> 2) * PITCH + apart * 8]) = areg[S][i];
+        for (int hs = 0; hs < HS; ++hs) {
+            const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
+                f_second ? (void*)a.x2 : (void*)a.x, 0, f_second ? x2span : xspan, 0x00020000);
 #pragma unroll
-        for (int h = 0; h < NI; ++h) {
-            u32x4w pk;
+            for (int i = 0; i < MI; ++i) areg[S][hs][i] = __builtin_amdgcn_raw_buffer_load_b128(wrsrc, f_vA[i], f_soffA, 0);
 #pragma unroll
-            for (int k = 0; k < 4; ++k) pk[k] = (breg[S][h][2 * k] & 0xffffu) | (breg[S][h][2 * k + 1] << 16);
-            *(u32x4w*)(&Bs[buf][(lane + 64 * h) * PITCH + wv * 8]) = pk;
+            for (int h = 0; h < NI; ++h)
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+                    breg[S][hs][h][k] = __builtin_amdgcn_raw_buffer_load_b16(xrsrc, f_vB[h], f_soffB[k], 0);
+            f_soffA += WK * 2;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) f_soffB[k] += f_inc;
+            if (--f_left == 0) next_tap();
+        }
+    };
+    auto stash = [&](int buf, auto SET) __attribute__((always_inline)) {
+        constexpr int S = decltype(SET)::value;
+        // The set is opaque to the compiler up to here, and its 2-byte elements are kept as
+        // such: otherwise the first operation on every loaded register (the widening) -- and
+        // with it the wait for the load -- is placed at the end of the loop iteration that
+        // issued the load, which drains the loads in flight once per D stages.
+#pragma unroll
+        for (int hs = 0; hs < HS; ++hs) {
+#pragma unroll
+            for (int i = 0; i < MI; ++i) asm volatile("" : "+v"(areg[S][hs][i]));
+#pragma unroll
+            for (int h = 0; h < NI; ++h)
+#pragma unroll
+                for (int k = 0; k < 8; ++k) asm volatile("" : "+v"(breg[S][hs][h][k]));
+        }
+#pragma unroll
+        for (int hs = 0; hs < HS; ++hs) {
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+                *(u32x4w*)(&As[buf][(((int)threadIdx.x + 256 * i) >> 2) * PITCH + hs * WK + apart * 8]) = areg[S][hs][i];
+#pragma unroll
+            for (int h = 0; h < NI; ++h) {
+                u32x4w pk;
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    pk[k] = (uint32_t)breg[S][hs][h][2 * k] | ((uint32_t)breg[S][hs][h][2 * k + 1] << 16);
+                *(u32x4w*)(&Bs[buf][(lane + 64 * h) * PITCH + hs * WK + wv * 8]) = pk;
+            }
         }
     };
 
@@ -191,12 +245,15 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(const WideArgs a) {
             for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.0f;
 
     const int fm = lane & 31, fk = lane >> 5;
-    // step s: LDS buffer s % 2 holds it; register set (s + j) % D holds step s + j, 0 < j < D
-    auto body = [&](auto PAR) {
+    // stage s: LDS buffer s % 2 holds it; register set (s + j) % D holds stage s + j, 0 < j < D
+    auto body = [&](auto PAR) __attribute__((always_inline)) {
         constexpr int P = decltype(PAR)::value;
         fetch(std::integral_constant<int, P>());
+        // (the scheduler keeps the three phases in this order: loads issued, products, then
+        // the wait for the oldest set and its way to LDS)
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
+        for (int ks = 0; ks < 2 * HS; ++ks) {
             h8 af[MI], bf[NI];
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi)
@@ -210,6 +267,7 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(const WideArgs a) {
                 for (int ni = 0; ni < NI; ++ni)
                     acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[mi], bf[ni], acc[mi][ni], 0, 0, 0);
         }
+        __builtin_amdgcn_sched_barrier(0);
         stash((P + 1) & 1, std::integral_constant<int, (P + 1) % D>());
         __syncthreads();
     };
@@ -217,9 +275,9 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(const WideArgs a) {
     stash(0, std::integral_constant<int, 0>());
     __syncthreads();
     int s = 0;
-    for (; s + D <= steps; s += D) wide_static_for<0, D>([&](auto J) { body(J); });
+    for (; s + D <= stages; s += D) wide_static_for<0, D>([&](auto J) { body(J); });
     wide_static_for<0, D - 1>([&](auto J) {
-        if (s + decltype(J)::value < steps) body(J);
+        if (s + decltype(J)::value < stages) body(J);
     });
 
     // ---- fused epilogue.  Lane l holds, per accumulator, pixel column l % 32 and the 16 rows
@@ -298,10 +356,15 @@ __global__ __launch_bounds__(256) void dense_wide_reorder_kernel(const _Float16*
     }
 }
 
+#ifndef WIDE_HS
+#define WIDE_HS(MI, NI) ((MI) * (NI) == 4 ? 1 : 2)
+#define WIDE_D(MI, NI) 2
+#endif
+
 template <int MI, int NI>
 hipError_t launch_wide_tile(const WideArgs& a, hipStream_t s) {
-    // (the smaller the tile, the fewer registers a set takes and the more a wave needs in flight)
-    constexpr int D = MI * NI == 4 ? 2 : MI * NI == 2 ? 4 : 8;
+    // (the smaller the tile, the fewer registers a set takes: deeper stages, more of them in flight)
+    constexpr int HS = WIDE_HS(MI, NI), D = WIDE_D(MI, NI);
     dim3 grid((unsigned)((a.total + 64 * NI - 1) / (64 * NI)), (unsigned)((a.cout + 64 * MI - 1) / (64 * MI)), 1);
     if constexpr (NI == 2) {
         // pixel pairs: neighbours in memory, at even element offsets, in the output and the residual
@@ -309,11 +372,11 @@ hipError_t launch_wide_tile(const WideArgs& a, hipStream_t s) {
             return !d.s2d && d.w % 2 == 0 && d.pitch % 2 == 0 && d.origin % 2 == 0 && d.plane % 2 == 0 && d.image % 2 == 0;
         };
         if (pairs(a.yd) && (!a.residual || pairs(a.rd))) {
-            CADNN_LAUNCH((dense_wide_kernel<MI, NI, D, true>), grid, dim3(256), 0, s, a);
+            CADNN_LAUNCH((dense_wide_kernel<MI, NI, HS, D, true>), grid, dim3(256), 0, s, a);
             return hipGetLastError();
         }
     }
-    CADNN_LAUNCH((dense_wide_kernel<MI, NI, D, false>), grid, dim3(256), 0, s, a);
+    CADNN_LAUNCH((dense_wide_kernel<MI, NI, HS, D, false>), grid, dim3(256), 0, s, a);
     return hipGetLastError();
 }
 

@@ -29,7 +29,21 @@ COPY_BYTES = 256 << 20
 
 def kernel_of(symbol: str) -> str:
     m = re.search(r"(\w+_kernel)\b", symbol)
-    return m.group(1) if m else symbol.split("(")[0].split("<")[0]
+    if m:
+        return m.group(1)
+    if symbol.startswith("_Z"):
+        # (rocprofv3 leaves the instantiations on _Float16 mangled: <length><name> pieces)
+        i = 3 if symbol.startswith("_ZN") else 2
+        while True:
+            d = re.match(r"\d+", symbol[i:])
+            if not d:
+                break
+            i += d.end()
+            name = symbol[i:i + int(d.group())]
+            if name.endswith("_kernel"):
+                return name
+            i += int(d.group())
+    return symbol.split("(")[0].split("<")[0]
 
 
 def read_stats(path):
