@@ -44,6 +44,9 @@ constexpr uint32_t kWideOutOfRange = 0x7ffffff0u;
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 typedef float f32x16w __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4w __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2w __attribute__((ext_vector_type(2)));
+typedef float f32x4w __attribute__((ext_vector_type(4)));
+typedef float f32x2w __attribute__((ext_vector_type(2)));
 
 struct WideArgs {
     const _Float16* w;        // [cout rounded up to 128][K] reordered tap-major, zero rows beyond cout
@@ -60,6 +63,9 @@ struct WideArgs {
     const float* bias2;
     TensorDesc x2d;
     int stride2, csteps2;
+    // pixels a thread of the epilogue writes with one store (8, 4 or 2: they lie side by side
+    // in the output and the residual, suitably aligned), or 0: one pixel per store
+    int group;
 };
 
 template <int I, int N, class F>
@@ -75,17 +81,16 @@ __device__ __forceinline__ void wide_static_for(F&& f) {
 // one or two workgroups on a CU the chain LDS write - barrier - LDS read - MFMA of a stage is
 // not hidden by anything, so it has to be paid as seldom as the LDS size allows.
 // D (even): register sets, that is how many stages ahead of the MFMAs the global loads run.
-// PAIR (NI = 2, output and residual laid out so that pixels 2j and 2j+1 of the batch-wide
-// numbering are neighbours at an even element offset): column c of a wave's two accumulators
-// holds pixels 2c and 2c+1, so a lane writes -- and reads the residual of -- two pixels with one
-// 4-byte access and a wave's store covers 128 contiguous bytes per channel instead of 64.
-template <int MI, int NI, int HS, int D, bool PAIR>
+template <int MI, int NI, int HS, int D>
 __global__ __launch_bounds__(256) void dense_wide_kernel(const WideArgs a) {
-    static_assert(!PAIR || NI == 2, "pixel pairs take the two accumulators of a wave");
     constexpr int TM = 64 * MI, TN = 64 * NI;
     constexpr int PITCH = WK * HS + 8;      // halves between rows in LDS: 80, 144 or 272 bytes, all conflict-free
-    __shared__ __attribute__((aligned(16))) _Float16 As[2][TM * PITCH];
-    __shared__ __attribute__((aligned(16))) _Float16 Bs[2][TN * PITCH];
+    // (the two stage buffers of both operands; the epilogue reuses them for the output tile)
+    constexpr int CPITCH = TN + 8;          // words between rows of the fp32 output tile
+    constexpr int MAIN_BYTES = 2 * (TM + TN) * PITCH * 2, TILE_BYTES = 64 * CPITCH * 4, EPI_BYTES = TILE_BYTES + TM * 4;
+    __shared__ __attribute__((aligned(16))) char smem[MAIN_BYTES > EPI_BYTES ? MAIN_BYTES : EPI_BYTES];
+    _Float16 (*As)[TM * PITCH] = (_Float16 (*)[TM * PITCH])smem;
+    _Float16 (*Bs)[TN * PITCH] = (_Float16 (*)[TN * PITCH])(smem + 2 * TM * PITCH * 2);
 
     const int lane = threadIdx.x & 63;
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -99,7 +104,7 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(const WideArgs a) {
 #pragma unroll
     for (int h = 0; h < NI; ++h) {
         // (LDS row lane + 64 h feeds MFMA column lane % 32 of accumulator lane / 32 of wave h)
-        const int Q = n0 + 64 * h + (PAIR ? 2 * (lane & 31) + (lane >> 5) : lane);
+        const int Q = n0 + 64 * h + lane;
         gbase[h] = 0;
         gbase2[h] = kWideOutOfRange;
         gmask[h] = 0;
@@ -135,12 +140,14 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(const WideArgs a) {
 #pragma unroll
     for (int i = 0; i < MI; ++i) wrow[i] = (uint32_t)((m0 + (((int)threadIdx.x + 256 * i) >> 2)) * a.K + apart * 8) * 2u;
 
-    // ---- the bias lines of the tile are touched now: the epilogue's loads then hit in cache
-    //      instead of adding a memory round trip to the tail
-    if (a.bias && threadIdx.x < TM && m0 + (int)threadIdx.x < a.cout) {
-        float touch;
-        asm volatile("global_load_dword %0, %1, off" : "=v"(touch) : "v"(a.bias + m0 + threadIdx.x) : "memory");
-        asm volatile("s_waitcnt vmcnt(0)" : "+v"(touch));
+    // ---- the tile's bias values are requested now, one per thread: the epilogue finds them
+    //      in a register instead of adding a memory round trip to the tail
+    float my_bias = 0.0f;
+    {
+        // (row t of the tile in the order the epilogue walks it: pass t / 64, local row t % 64)
+        const int t = (int)threadIdx.x, pass = t >> 6, r = t & 63;
+        const int co = m0 + (r >> 5) * 32 * MI + pass * 32 + (r & 31);
+        if (t < TM && co < a.cout) my_bias = (a.bias ? a.bias[co] : 0.0f) + (a.bias2 ? a.bias2[co] : 0.0f);
     }
 
     // D register sets: the loads of stage s + D are issued while stage s is multiplied and stage
@@ -297,29 +304,80 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(const WideArgs a) {
             roff = (uint32_t)(img * (int)a.rd.image + tensor_off(a.rd, oh, ow)) * 2u;
         }
     };
-    if constexpr (PAIR) {
-        uint32_t yoff, roff;
-        place(n0 + wn * 64 + 2 * fm, yoff, roff);       // (the number of pixels is even: both or neither)
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int co = m0 + wm * 32 * MI + mi * 32 + (i >> 2) * 8 + fk * 4 + (i & 3);
-                const bool live = co < a.cout;
-                const int cc = live ? co : 0;
-                const float b = (a.bias ? a.bias[cc] : 0.0f) + (a.bias2 ? a.bias2[cc] : 0.0f);
-                float v0 = acc[mi][0][i] + b, v1 = acc[mi][1][i] + b;
-                if (a.residual) {
-                    const uint32_t r = __builtin_amdgcn_raw_buffer_load_b32(
-                        rrsrc, live ? roff + (uint32_t)cc * (uint32_t)a.rd.plane * 2u : kWideOutOfRange, 0u, 0);
-                    v0 += (float)__builtin_bit_cast(_Float16, (unsigned short)(r & 0xffffu));
-                    v1 += (float)__builtin_bit_cast(_Float16, (unsigned short)(r >> 16));
-                }
-                if (a.relu) { v0 = v0 > 0.0f ? v0 : 0.0f; v1 = v1 > 0.0f ? v1 : 0.0f; }
-                const uint32_t pk = (uint32_t)__builtin_bit_cast(unsigned short, (_Float16)v0) |
-                                    ((uint32_t)__builtin_bit_cast(unsigned short, (_Float16)v1) << 16);
-                __builtin_amdgcn_raw_buffer_store_b32(pk, yrsrc, live ? yoff + (uint32_t)cc * (uint32_t)a.yd.plane * 2u : kWideOutOfRange, 0u, 0);
+    if (a.group) {
+        // Through LDS: the accumulators of 64 channels at a time are laid out [channel][pixel]
+        // as fp32 and a thread takes `group` neighbouring pixels of one channel -- bias, residual,
+        // ReLU, one rounding, ONE store of 4 to 16 bytes.  (A wave's own accumulator layout puts
+        // 32 pixels of a channel side by side: 64-byte pieces written 2 bytes per lane, which
+        // the memory pipeline takes at a fraction of the rate: 6 us per workgroup measured.)
+        float* ct = (float*)smem;
+        float* bl = (float*)(smem + TILE_BYTES);            // [pass][local row]
+        auto run = [&](auto GG) __attribute__((always_inline)) {
+            constexpr int G = decltype(GG)::value, per_row = TN / G, rows_per_sweep = 256 / per_row, sweeps = 64 / rows_per_sweep;
+            const int cg = (int)threadIdx.x % per_row, r0 = (int)threadIdx.x / per_row;
+            const int Q = n0 + cg * G;
+            uint32_t yoff = kWideOutOfRange, roff = kWideOutOfRange;
+            if (Q < a.total) {          // (the images' pixel counts are multiples of the group: all of it or none)
+                const int img = Q / a.hwout, q = Q - img * a.hwout;
+                yoff = (uint32_t)(img * (int)a.yd.image + q) * 2u;
+                roff = (uint32_t)(img * (int)a.rd.image + q) * 2u;
             }
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) {
+                __syncthreads();        // the tile's last readers (the K loop, the previous pass) are done
+                if (mi == 0 && threadIdx.x < TM) bl[threadIdx.x] = my_bias;
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i)
+                        ct[(wm * 32 + (i >> 2) * 8 + fk * 4 + (i & 3)) * CPITCH + wn * 32 * NI + ni * 32 + fm] = acc[mi][ni][i];
+                __syncthreads();
+#pragma unroll
+                for (int k = 0; k < sweeps; ++k) {
+                    const int r = r0 + k * rows_per_sweep;
+                    const int co = m0 + (r >> 5) * 32 * MI + mi * 32 + (r & 31);
+                    const bool live = co < a.cout && yoff != kWideOutOfRange;
+                    const int cc = co < a.cout ? co : 0;
+                    const float b = bl[mi * 64 + r];
+                    const float* src = ct + r * CPITCH + cg * G;
+                    const uint32_t yo = live ? yoff + (uint32_t)cc * (uint32_t)a.yd.plane * 2u : kWideOutOfRange;
+                    const uint32_t ro = live ? roff + (uint32_t)cc * (uint32_t)a.rd.plane * 2u : kWideOutOfRange;
+                    auto finish = [&](float v, uint32_t rbits) __attribute__((always_inline)) {
+                        v += b;
+                        if (a.residual) v += (float)__builtin_bit_cast(_Float16, (unsigned short)rbits);
+                        if (a.relu) v = v > 0.0f ? v : 0.0f;
+                        return (uint32_t)__builtin_bit_cast(unsigned short, (_Float16)v);
+                    };
+                    if constexpr (G == 8) {
+                        const f32x4w lo = *(const f32x4w*)src, hi = *(const f32x4w*)(src + 4);
+                        u32x4w rr = {0u, 0u, 0u, 0u};
+                        if (a.residual) rr = __builtin_amdgcn_raw_buffer_load_b128(rrsrc, ro, 0u, 0);
+                        u32x4w o;
+                        o[0] = finish(lo[0], rr[0]) | (finish(lo[1], rr[0] >> 16) << 16);
+                        o[1] = finish(lo[2], rr[1]) | (finish(lo[3], rr[1] >> 16) << 16);
+                        o[2] = finish(hi[0], rr[2]) | (finish(hi[1], rr[2] >> 16) << 16);
+                        o[3] = finish(hi[2], rr[3]) | (finish(hi[3], rr[3] >> 16) << 16);
+                        __builtin_amdgcn_raw_buffer_store_b128(o, yrsrc, yo, 0u, 0);
+                    } else if constexpr (G == 4) {
+                        const f32x4w lo = *(const f32x4w*)src;
+                        u32x2w rr = {0u, 0u};
+                        if (a.residual) rr = __builtin_amdgcn_raw_buffer_load_b64(rrsrc, ro, 0u, 0);
+                        u32x2w o;
+                        o[0] = finish(lo[0], rr[0]) | (finish(lo[1], rr[0] >> 16) << 16);
+                        o[1] = finish(lo[2], rr[1]) | (finish(lo[3], rr[1] >> 16) << 16);
+                        __builtin_amdgcn_raw_buffer_store_b64(o, yrsrc, yo, 0u, 0);
+                    } else {
+                        const f32x2w lo = *(const f32x2w*)src;
+                        uint32_t rr = 0u;
+                        if (a.residual) rr = __builtin_amdgcn_raw_buffer_load_b32(rrsrc, ro, 0u, 0);
+                        __builtin_amdgcn_raw_buffer_store_b32(finish(lo[0], rr) | (finish(lo[1], rr >> 16) << 16), yrsrc, yo, 0u, 0);
+                    }
+                }
+            }
+        };
+        if (a.group == 8) run(std::integral_constant<int, 8>());
+        else if (a.group == 4) run(std::integral_constant<int, 4>());
+        else run(std::integral_constant<int, 2>());
     } else {
 #pragma unroll
         for (int ni = 0; ni < NI; ++ni) {
@@ -332,7 +390,7 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(const WideArgs a) {
                     const int co = m0 + wm * 32 * MI + mi * 32 + (i >> 2) * 8 + fk * 4 + (i & 3);
                     const bool live = co < a.cout;
                     const int cc = live ? co : 0;
-                    float v = acc[mi][ni][i] + (a.bias ? a.bias[cc] : 0.0f) + (a.bias2 ? a.bias2[cc] : 0.0f);
+                    float v = acc[mi][ni][i] + ((a.bias ? a.bias[cc] : 0.0f) + (a.bias2 ? a.bias2[cc] : 0.0f));
                     if (a.residual)
                         v += (float)__builtin_bit_cast(
                             _Float16, __builtin_amdgcn_raw_buffer_load_b16(rrsrc, live ? roff + (uint32_t)cc * (uint32_t)a.rd.plane * 2u : kWideOutOfRange, 0u, 0));
@@ -366,17 +424,7 @@ hipError_t launch_wide_tile(const WideArgs& a, hipStream_t s) {
     // (the smaller the tile, the fewer registers a set takes: deeper stages, more of them in flight)
     constexpr int HS = WIDE_HS(MI, NI), D = WIDE_D(MI, NI);
     dim3 grid((unsigned)((a.total + 64 * NI - 1) / (64 * NI)), (unsigned)((a.cout + 64 * MI - 1) / (64 * MI)), 1);
-    if constexpr (NI == 2) {
-        // pixel pairs: neighbours in memory, at even element offsets, in the output and the residual
-        auto pairs = [](const TensorDesc& d) {
-            return !d.s2d && d.w % 2 == 0 && d.pitch % 2 == 0 && d.origin % 2 == 0 && d.plane % 2 == 0 && d.image % 2 == 0;
-        };
-        if (pairs(a.yd) && (!a.residual || pairs(a.rd))) {
-            CADNN_LAUNCH((dense_wide_kernel<MI, NI, HS, D, true>), grid, dim3(256), 0, s, a);
-            return hipGetLastError();
-        }
-    }
-    CADNN_LAUNCH((dense_wide_kernel<MI, NI, HS, D, false>), grid, dim3(256), 0, s, a);
+    CADNN_LAUNCH((dense_wide_kernel<MI, NI, HS, D>), grid, dim3(256), 0, s, a);
     return hipGetLastError();
 }
 
@@ -396,6 +444,16 @@ WideArgs wide_args(const void* w, const void* x, const TensorDesc& xd, void* y, 
     a.total = n * a.hwout;
     a.K = xd.c * kh * kw;
     a.csteps = xd.c / WK;
+    // the widest store the layouts allow: an image's pixels contiguous (no halo, not
+    // de-interleaved), groups that neither straddle images nor leave their alignment
+    auto group_of = [&](const TensorDesc& d, const void* p) {
+        if (d.s2d || d.ph || d.pw || d.pitch != d.w) return 0;
+        for (int g = 8; g >= 2; g >>= 1)
+            if (a.hwout % g == 0 && d.plane % g == 0 && d.image % g == 0 && (uintptr_t)p % (2 * g) == 0) return g;
+        return 0;
+    };
+    a.group = group_of(yd, y);
+    if (residual) a.group = std::min(a.group, group_of(rd, residual));
     return a;
 }
 
