@@ -56,6 +56,37 @@ static cadnn_status check_conv(const char* who, const cadnn_weights* w, const Te
     return CADNN_OK;
 }
 
+// K split over workgroups (large-tile matrix-core variants with splitk > 1): the number of
+// slices in use -- every slice gets at least one 32-deep step -- the output tiles, and the
+// scratch the slices meet in: per (variant, layer geometry), allocated on first use and kept.
+struct SplitK { int sk = 1; int64_t tiles = 0; };
+static SplitK splitk_of(const ConvVariant& v, const cadnn_weights* w, const ConvGeom& g) {
+    SplitK r;
+    const int tm = v.rows_per_block(), tn = 64 * v.p;
+    r.tiles = (((int64_t)g.n * g.hout * g.wout + tn - 1) / tn) * ((w->cout + tm - 1) / tm);
+    const int steps = w->cin / 32 * w->kh * w->kw + ((g.ex && g.ex->w) ? g.ex->w->cin / 32 : 0);
+    if (v.splitk > 1 && steps > 0) {
+        const int per = (steps + v.splitk - 1) / v.splitk;
+        r.sk = (steps + per - 1) / per;
+    }
+    return r;
+}
+static cadnn_status ensure_sk_scratch(const cadnn_weights* w, const ConvVariant* v, const ConvGeom& g, ConvLaunch* out) {
+    const SplitK k = splitk_of(*v, w, g);
+    if (k.sk <= 1) return CADNN_OK;
+    float* part = nullptr;
+    int* count = nullptr;
+    const size_t tile_bytes = (size_t)v->rows_per_block() * 64 * v->p * sizeof(float);
+    cadnn_status st = get_sk_scratch(w, v, g.key(), (size_t)k.tiles * k.sk * tile_bytes, (size_t)k.tiles * sizeof(int), &part, &count);
+    if (st != CADNN_OK) return st;
+    if (out) {
+        out->sk = k.sk;
+        out->sk_part = part;
+        out->sk_count = count;
+    }
+    return CADNN_OK;
+}
+
 static bool variant_fits(const ConvVariant& v, const cadnn_weights* w, const ConvGeom& g, bool any_density = false) {
     if (v.is_f16 != (w->dtype == CADNN_F16)) return false;
     if (v.stride != 0 && v.stride != g.stride) return false;
@@ -87,6 +118,15 @@ static bool variant_fits(const ConvVariant& v, const cadnn_weights* w, const Con
         // halo) or pixel by pixel (stride 1, 1x1)
         if (g.xd.s2d && !(g.stride == 2 ? (g.xd.ph >= g.pad && g.xd.pw >= g.pad) : (g.stride == 1 && w->kh * w->kw == 1 && g.pad == 0)))
             return false;
+        if (v.splitk > 1) {
+            // K is split over workgroups where the tiles alone leave most of the chip idle and
+            // every slice still gets a few stages; the scratch stays below 256 MiB
+            const SplitK k = splitk_of(v, w, g);
+            const int steps = w->cin / 32 * w->kh * w->kw + (g.ex ? g.ex->w->cin / 32 : 0);
+            if (k.sk != v.splitk || k.tiles > 384 || steps < 8 * v.splitk ||
+                k.tiles * k.sk * (int64_t)v.rows_per_block() * 64 * v.p * 4 > (256ll << 20))
+                return false;
+        }
         return any_density || dense_enough || by_tuning;
     }
     if (v.family == FAM_LINEAR) {
@@ -190,8 +230,9 @@ static double variant_cost(const cadnn_weights* w, const ConvGeom& g, const Conv
     const double pixels = (double)g.hout * g.wout;
     double cost;
     if (v->family == FAM_DENSE && v->tw == 128) {
-        // large tiles, two workgroups per CU; for a pruned layer the measured selection decides
-        if ((double)w->nnz < 0.25 * (double)w->cout * w->cin * w->kh * w->kw) return -1.0;
+        // large tiles, two workgroups per CU; for a pruned layer, and for K split over
+        // workgroups, the measured selection decides
+        if ((double)w->nnz < 0.25 * (double)w->cout * w->cin * w->kh * w->kw || v->splitk > 1) return -1.0;
         const double tm = v->rows_per_block(), tn = 64.0 * v->p;
         const double blocks = std::ceil(pixels * g.n / tn) * std::ceil(w->cout / tm);
         const double K = (double)w->cin * w->kh * w->kw;
@@ -357,6 +398,8 @@ static cadnn_status make_launch(const cadnn_weights* w, const ConvVariant* v, co
         a.tiles_y = 1;
     }
     a.row_groups = plan->rows_padded / v->rows_per_block();
+    a.sk = 1;
+    if (v->family == FAM_DENSE && v->splitk > 1 && (st = ensure_sk_scratch(w, v, g, &a)) != CADNN_OK) return st;
     *out = a;
     return CADNN_OK;
 }
@@ -548,7 +591,8 @@ cadnn_status conv2d_prepare_impl(const cadnn_weights* w, const TensorDesc& xd, i
         return fail(CADNN_EUNSUPPORTED, "cadnn_conv2d_prepare: no kernel for %dx%d filters with stride %d",
                     w->kh, w->kw, stride);
     const ConvPlan* plan = nullptr;
-    return get_conv_plan(w, v, xd, g.stride, g.pad, g.wout, &plan, g.ex);
+    if ((st = get_conv_plan(w, v, xd, g.stride, g.pad, g.wout, &plan, g.ex)) != CADNN_OK) return st;
+    return ensure_sk_scratch(w, v, g, nullptr);
 }
 
 const char* conv2d_variant_name_impl(const cadnn_weights* w, const TensorDesc& xd, int n, int stride, int pad,

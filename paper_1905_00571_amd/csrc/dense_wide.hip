@@ -66,6 +66,12 @@ struct WideArgs {
     // pixels a thread of the epilogue writes with one store (8, 4 or 2: they lie side by side
     // in the output and the residual, suitably aligned), or 0: one pixel per store
     int group;
+    // K split over `sk` workgroups per output tile (blockIdx.z): each writes its fp32 partial
+    // tile to `part`, the last to arrive (counted in `count`, which it leaves at zero) adds them
+    // up in slice order and finishes the tile
+    int sk;
+    float* part;
+    int* count;
 };
 
 template <int I, int N, class F>
@@ -156,43 +162,61 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(const WideArgs a) {
     unsigned short breg[D][HS][NI][8];      // (widened only when the set is used: see stash)
     // Steps are fetched in order and a wave is one serial instruction stream, so what a step
     // costs in scalar bookkeeping it costs in time: the state of the walk over K is carried
-    // along -- per step nine scalar additions and a counter -- and everything that depends on
+    // along -- per step about ten scalar additions and a counter -- and everything that depends on
     // the tap (its offset, which pixels it reaches, the switch to a fused shortcut's input) is
     // redone only when the tap changes, behind a scalar branch that issues no load.  Past the
     // last step zeros are fetched (out-of-range offsets on both sides) rather than nothing, so
     // that the number of loads in flight is known at compile time.
-    const int steps = taps * a.csteps + a.csteps2;
+    const int steps_all = taps * a.csteps + a.csteps2;
+    // this workgroup's slice of K: steps [s_first, s_first + steps)
+    // (integer divisions run on the vector ALU: their results are made scalar again, or every
+    // address derived from them would be a per-lane value to the compiler)
+    const int per_slice = __builtin_amdgcn_readfirstlane((steps_all + a.sk - 1) / a.sk);
+    const int s_first = (int)blockIdx.z * per_slice;
+    const int steps = min(per_slice, steps_all - s_first);
     const int stages = (steps + HS - 1) / HS;
-    int f_tap = -1, f_r = 0, f_c = -1, f_left = 0;          // (scalar)
+    int f_tap = 0, f_r = 0, f_c = 0, f_left = 0, f_todo = steps;          // (scalar)
     bool f_second = false;
-    uint32_t f_soffA = 0, f_inc = 0, f_soffB[8];
+    uint32_t f_soffA = 0, f_inc = 0, f_pb = 0, f_soffB = 0;
     uint32_t f_vA[MI], f_vB[NI];
-    auto next_tap = [&]() __attribute__((always_inline)) {
-        ++f_tap;
-        if (++f_c == a.kw) { f_c = 0; ++f_r; }
-        const bool live = f_tap < taps + (a.csteps2 ? 1 : 0);
+    // (past the slice only the per-lane parts of the addresses change, to out of range, which is
+    // what the range check looks at; the scalar parts run on)
+    auto end_walk = [&]() __attribute__((always_inline)) {
+        f_left = 0x7fffffff;
+#pragma unroll
+        for (int h = 0; h < NI; ++h) f_vB[h] = kWideOutOfRange;
+#pragma unroll
+        for (int i = 0; i < MI; ++i) f_vA[i] = kWideOutOfRange;
+    };
+    // state of tap f_tap (f_r, f_c), entered at its channel block cb
+    auto load_tap = [&](int cb) __attribute__((always_inline)) {
         f_second = f_tap >= taps;
         const int Rt = f_r - a.pad + a.xd.ph, Ct = f_c - a.pad + a.xd.pw;
         const int tap_el = !a.xd.s2d ? (f_r - a.pad) * a.xd.pitch + (f_c - a.pad)
                            : a.stride == 2 ? ((Rt & 1) * 2 + (Ct & 1)) * a.xd.sub + (Rt >> 1) * a.xd.pitch + (Ct >> 1) : 0;
-        const uint32_t pb = f_second ? plane2_bytes : plane_bytes;
-        f_inc = live ? WK * pb : 0u;
-        f_left = !live ? 0x7fffffff : f_second ? a.csteps2 : a.csteps;
-#pragma unroll
-        for (int k = 0; k < 8; ++k) f_soffB[k] = live ? (uint32_t)(wv * 8 + k) * pb : 0u;
+        f_pb = f_second ? plane2_bytes : plane_bytes;
+        f_inc = WK * f_pb;
+        f_left = (f_second ? a.csteps2 : a.csteps) - cb;
+        f_soffB = (uint32_t)(cb * WK + wv * 8) * f_pb;
 #pragma unroll
         for (int h = 0; h < NI; ++h)
-            f_vB[h] = !live ? kWideOutOfRange : f_second ? gbase2[h]
-                      : ((gmask[h] >> f_tap) & 1) ? gbase[h] + (uint32_t)(tap_el * 2) : kWideOutOfRange;
-        if (!live) {
-            f_soffA = 0;
-#pragma unroll
-            for (int i = 0; i < MI; ++i) f_vA[i] = kWideOutOfRange;
-        }
+            f_vB[h] = f_second ? gbase2[h] : ((gmask[h] >> f_tap) & 1) ? gbase[h] + (uint32_t)(tap_el * 2) : kWideOutOfRange;
+    };
+    auto next_tap = [&]() __attribute__((always_inline)) {
+        ++f_tap;
+        if (++f_c == a.kw) { f_c = 0; ++f_r; }
+        load_tap(0);
     };
 #pragma unroll
     for (int i = 0; i < MI; ++i) f_vA[i] = wrow[i];
-    next_tap();
+    {
+        const int in_taps = taps * a.csteps;
+        f_tap = __builtin_amdgcn_readfirstlane(s_first < in_taps ? s_first / a.csteps : taps);
+        f_r = __builtin_amdgcn_readfirstlane(f_tap / a.kw);
+        f_c = f_tap - f_r * a.kw;
+        load_tap(s_first < in_taps ? s_first - f_tap * a.csteps : s_first - in_taps);
+        f_soffA = (uint32_t)s_first * (WK * 2);
+    }
     auto fetch = [&](auto SET) __attribute__((always_inline)) {
         constexpr int S = decltype(SET)::value;
 #pragma unroll
@@ -201,15 +225,17 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(const WideArgs a) {
                 f_second ? (void*)a.x2 : (void*)a.x, 0, f_second ? x2span : xspan, 0x00020000);
 #pragma unroll
             for (int i = 0; i < MI; ++i) areg[S][hs][i] = __builtin_amdgcn_raw_buffer_load_b128(wrsrc, f_vA[i], f_soffA, 0);
+            uint32_t soff = f_soffB;         // (channel by channel: one running scalar instead of eight kept ones)
 #pragma unroll
-            for (int h = 0; h < NI; ++h)
+            for (int k = 0; k < 8; ++k) {
 #pragma unroll
-                for (int k = 0; k < 8; ++k)
-                    breg[S][hs][h][k] = __builtin_amdgcn_raw_buffer_load_b16(xrsrc, f_vB[h], f_soffB[k], 0);
+                for (int h = 0; h < NI; ++h) breg[S][hs][h][k] = __builtin_amdgcn_raw_buffer_load_b16(xrsrc, f_vB[h], soff, 0);
+                soff += f_pb;
+            }
             f_soffA += WK * 2;
-#pragma unroll
-            for (int k = 0; k < 8; ++k) f_soffB[k] += f_inc;
-            if (--f_left == 0) next_tap();
+            f_soffB += f_inc;
+            if (--f_todo == 0) end_walk();
+            else if (--f_left == 0) next_tap();
         }
     };
     auto stash = [&](int buf, auto SET) __attribute__((always_inline)) {
@@ -286,6 +312,54 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(const WideArgs a) {
     wide_static_for<0, D - 1>([&](auto J) {
         if (s + decltype(J)::value < stages) body(J);
     });
+
+    // ---- K split over workgroups: the slices of a tile meet in memory
+    if (a.sk > 1) {
+        const size_t tile_id = (size_t)blockIdx.y * gridDim.x + blockIdx.x;
+        float* mine = a.part + (tile_id * a.sk + blockIdx.z) * (size_t)(TM * TN);
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    __hip_atomic_store(mine + ((mi * NI + ni) * 16 + i) * 256 + threadIdx.x, acc[mi][ni][i], __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+        // Device-scope stores and loads go to the level all dies share, so the slices' tiles need
+        // no cache write-back or invalidation (a release fence here writes back the whole L2 of
+        // the die: 50 us per launch measured); what orders them against the count is that every
+        // thread's stores are acknowledged before the workgroup's arrival is counted.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        int* flag = (int*)smem;           // (the stage buffers are no longer read: every wave is past the barrier)
+        if (threadIdx.x == 0) {
+            const int arrived = __hip_atomic_fetch_add(a.count + tile_id, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            *flag = arrived == a.sk - 1;
+            if (arrived == a.sk - 1) a.count[tile_id] = 0;      // every other slice has counted itself: ready for the next launch
+        }
+        __syncthreads();
+        const bool last = *flag != 0;
+        __syncthreads();                  // (smem is reused below)
+        if (!last) return;
+        // slice order, whoever arrived last: the sum does not depend on the order of arrival
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.0f;
+        for (int z = 0; z < a.sk; ++z) {
+            const float* src = a.part + (tile_id * a.sk + z) * (size_t)(TM * TN);
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i)
+                        acc[mi][ni][i] += __hip_atomic_load(src + ((mi * NI + ni) * 16 + i) * 256 + threadIdx.x, __ATOMIC_RELAXED,
+                                                            __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
 
     // ---- fused epilogue.  Lane l holds, per accumulator, pixel column l % 32 and the 16 rows
     //      8 * (i / 4) + 4 * (l / 32) + i % 4.
@@ -423,7 +497,7 @@ template <int MI, int NI>
 hipError_t launch_wide_tile(const WideArgs& a, hipStream_t s) {
     // (the smaller the tile, the fewer registers a set takes: deeper stages, more of them in flight)
     constexpr int HS = WIDE_HS(MI, NI), D = WIDE_D(MI, NI);
-    dim3 grid((unsigned)((a.total + 64 * NI - 1) / (64 * NI)), (unsigned)((a.cout + 64 * MI - 1) / (64 * MI)), 1);
+    dim3 grid((unsigned)((a.total + 64 * NI - 1) / (64 * NI)), (unsigned)((a.cout + 64 * MI - 1) / (64 * MI)), (unsigned)a.sk);
     CADNN_LAUNCH((dense_wide_kernel<MI, NI, HS, D>), grid, dim3(256), 0, s, a);
     return hipGetLastError();
 }
@@ -454,6 +528,7 @@ WideArgs wide_args(const void* w, const void* x, const TensorDesc& xd, void* y, 
     };
     a.group = group_of(yd, y);
     if (residual) a.group = std::min(a.group, group_of(rd, residual));
+    a.sk = 1;
     return a;
 }
 
@@ -467,6 +542,9 @@ WideArgs wide_args(const ConvLaunch& l) {
         a.csteps2 = l.x2d.c / WK;
         a.K += l.x2d.c;
     }
+    a.sk = l.sk > 1 ? l.sk : 1;
+    a.part = l.sk_part;
+    a.count = l.sk_count;
     return a;
 }
 
@@ -487,8 +565,9 @@ bool dense_wide_serves(bool is_f16, int cin, int taps, int64_t in_bytes, int64_t
 const std::vector<ConvVariant>& all_dense_wide_variants() {
     static const std::vector<ConvVariant> v = [] {
         std::vector<ConvVariant> out;
-        auto add = [&](const char* name, int tm, int tn, hipError_t (*launch)(const ConvLaunch&, hipStream_t)) {
+        auto add = [&](const char* name, int tm, int tn, hipError_t (*launch)(const ConvLaunch&, hipStream_t), int splitk = 1) {
             ConvVariant d{};
+            d.splitk = splitk;
             d.name = name;
             d.family = FAM_DENSE;
             d.is_f16 = true;
@@ -501,6 +580,12 @@ const std::vector<ConvVariant>& all_dense_wide_variants() {
         add("dense_mfma__Float16_128x64x32", 128, 64, &launch_wide_variant<128, 64>);
         add("dense_mfma__Float16_64x128x32", 64, 128, &launch_wide_variant<64, 128>);
         add("dense_mfma__Float16_64x64x32w", 64, 64, &launch_wide_variant<64, 64>);
+        // K split over 2 / 4 / 8 workgroups per tile, for layers whose tiles alone leave the chip idle
+        add("dense_mfma__Float16_64x64x32w_k2", 64, 64, &launch_wide_variant<64, 64>, 2);
+        add("dense_mfma__Float16_64x64x32w_k4", 64, 64, &launch_wide_variant<64, 64>, 4);
+        add("dense_mfma__Float16_64x64x32w_k8", 64, 64, &launch_wide_variant<64, 64>, 8);
+        add("dense_mfma__Float16_128x64x32_k2", 128, 64, &launch_wide_variant<128, 64>, 2);
+        add("dense_mfma__Float16_128x64x32_k4", 128, 64, &launch_wide_variant<128, 64>, 4);
         return out;
     }();
     return v;

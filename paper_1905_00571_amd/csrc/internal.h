@@ -75,6 +75,8 @@ struct DevBuf {
     void release();
     // Allocates (at least 16 bytes so that p is never NULL) and uploads `n` bytes from host.
     cadnn_status upload(const void* host, size_t n);
+    // Allocates `n` bytes of device memory, zero-filled if asked (never in a HostPlans scope).
+    cadnn_status alloc(size_t n, bool zero);
 };
 
 // ---- activation tensor layout --------------------------------------------------
@@ -233,6 +235,7 @@ struct ConvVariant {
     int nz_cap;           // FAM_STILE: most stream entries per (row group, chunk) the kernel buffers
     int flat;             // FAM_WTILE: 1 = pixel-wise layers (1x1 filters), pixels flattened over the batch;
                           //            0 = filters with taps, lanes in an (rw x 64/rw) grid over a 2-D tile
+    int splitk;           // FAM_DENSE, large tiles: workgroups that share one output tile, each a slice of K (0, 1: one)
     size_t lds_bytes;
     hipError_t (*launch)(const ConvLaunch&, hipStream_t);
     // several layers (at most kMaxCoLaunch) at once from a device table of launch records, of
@@ -285,6 +288,11 @@ struct ConvLaunch {
     uint32_t wt_m_sub, wt_m_pitch, wt_m_nphc;   // ceil(2^32 / d) for d = wt_sub, wt_pitch, wt_nphc: n / d = mulhi(n, m) for n < 2^16
     uint32_t wt_lds_bytes;
     uint32_t image_bytes;     // xd.image * sizeof(element)
+    // FAM_DENSE with K split over workgroups: the slices' fp32 partial tiles and one arrival
+    // counter per output tile (zero between launches: the last arriver resets it)
+    int sk;
+    float* sk_part;
+    int* sk_count;
     // launches of several layers (launch_multi) may carry window pools among them: 0 = a
     // convolution, 1 = a k x k maximum pool, 2 = a k x k mean pool (x, y, xd, yd, stride, pad
     // as for a layer; the output elements of image n are dealt round robin to the threads of
@@ -405,6 +413,7 @@ typedef std::tuple<const ConvVariant*, int, int, const void*, int> PlanKey;
 // de-interleaved, 2 = output or residual de-interleaved, 4 = a shortcut is fused in,
 // 8 = a global average pool is fused in, 16 = a depthwise layer is fused in, 32 = with stride 2)
 typedef std::array<int, 8> GeomKey;
+struct SkScratch { DevBuf part, count; bool in_use = false; };
 
 const std::vector<ConvVariant>& all_tile_variants();
 const std::vector<ConvVariant>& all_direct_variants();
@@ -450,6 +459,10 @@ struct cadnn_weights {
     mutable std::map<cadnn::PlanKey, std::shared_ptr<cadnn::ConvPlan>> plans;
     // variant pinned for a geometry by tuning or by the caller
     mutable std::map<cadnn::GeomKey, const cadnn::ConvVariant*> chosen;
+    // scratch of the split-K matrix-core variants, per (variant, layer geometry); never freed
+    // or moved before the handle is (launch records and captured graphs point into it); two
+    // launches of one layer that overlap in time would share it and race
+    mutable std::map<std::pair<const cadnn::ConvVariant*, cadnn::GeomKey>, std::unique_ptr<cadnn::SkScratch>> sk_scratch;
     // FAM_STILE variants whose per-(row group, chunk) stream was measured against the kernel's buffer
     // (its own lock: candidates are also listed by callers that hold `mu`)
     mutable std::mutex stile_mu;
@@ -482,6 +495,10 @@ struct ConvExtra {
 // Whether every (row group, channel chunk) stream of these weights fits the buffer of a
 // FAM_STILE variant (exact; cached on the handle).
 bool stile_streams_fit(const cadnn_weights* w, const ConvVariant* v);
+// Scratch of a split-K variant for one layer geometry: allocated (counters zeroed) on first use;
+// like a plan it is dropped after tuning unless an ordinary launch has used it or its variant is pinned.
+cadnn_status get_sk_scratch(const cadnn_weights* w, const ConvVariant* v, const GeomKey& key, size_t part_bytes,
+                            size_t count_bytes, float** part, int** count);
 cadnn_status get_conv_plan(const cadnn_weights* w, const ConvVariant* v, const TensorDesc& xd, int stride,
                            int pad, int wout, const ConvPlan** out, const ConvExtra* ex = nullptr,
                            std::shared_ptr<ConvPlan>* keep = nullptr);

@@ -65,6 +65,21 @@ cadnn_status DevBuf::upload(const void* host, size_t n) {
     return CADNN_OK;
 }
 
+cadnn_status DevBuf::alloc(size_t n, bool zero) {
+    if (g_no_device_alloc > 0) return fail(CADNN_EINVAL, "this call may not allocate device memory");
+    if (g_host_plans > 0) return fail(CADNN_EINVAL, "device scratch asked for while building host-only plans");
+    release();
+    const size_t sz = n < 16 ? 16 : n;
+    hipError_t e = hipMalloc(&p, sz);
+    if (e != hipSuccess) {
+        p = nullptr;
+        return fail(CADNN_ENOMEM, "hipMalloc(%zu) failed: %s", sz, hipGetErrorString(e));
+    }
+    bytes = sz;
+    if (zero) CADNN_HIP(hipMemset(p, 0, sz));
+    return CADNN_OK;
+}
+
 // IEEE binary32 -> binary16, round to nearest even (overflow -> inf, NaN kept quiet).
 uint16_t f32_to_f16_rne(float f) {
     uint32_t x;
@@ -894,6 +909,31 @@ void drop_unpinned_plans(const cadnn_weights* w) {
         for (const auto& c : w->chosen) pinned = pinned || c.second == std::get<0>(it->first);
         if (pinned) ++it; else it = w->plans.erase(it);
     }
+    for (auto it = w->sk_scratch.begin(); it != w->sk_scratch.end();) {
+        bool pinned = it->second->in_use;
+        auto c = w->chosen.find(it->first.second);
+        pinned = pinned || (c != w->chosen.end() && c->second == it->first.first);
+        if (pinned) ++it; else it = w->sk_scratch.erase(it);
+    }
+}
+
+cadnn_status get_sk_scratch(const cadnn_weights* w, const ConvVariant* v, const GeomKey& key, size_t part_bytes,
+                            size_t count_bytes, float** part, int** count) {
+    std::lock_guard<std::mutex> lock(w->mu);
+    const auto k = std::make_pair(v, key);
+    auto it = w->sk_scratch.find(k);
+    if (it == w->sk_scratch.end()) {
+        std::unique_ptr<SkScratch> sc(new (std::nothrow) SkScratch());
+        if (!sc) return fail(CADNN_ENOMEM, "out of host memory");
+        cadnn_status st = sc->part.alloc(part_bytes, false);
+        if (st == CADNN_OK) st = sc->count.alloc(count_bytes, true);
+        if (st != CADNN_OK) return st;
+        it = w->sk_scratch.emplace(k, std::move(sc)).first;
+    }
+    if (g_trial_plans == 0) it->second->in_use = true;
+    *part = (float*)it->second->part.p;
+    *count = (int*)it->second->count.p;
+    return CADNN_OK;
 }
 
 cadnn_status get_conv_plan(const cadnn_weights* w, const ConvVariant* v, const TensorDesc& xd, int stride,
