@@ -103,7 +103,7 @@ static bool variant_fits(const ConvVariant& v, const cadnn_weights* w, const Con
         const int64_t pixels = (int64_t)g.n * g.hout * g.wout;
         // in 2-byte storage a candidate for the measured selection at any density, once the batch
         // of pixels gives the matrix cores a few tiles
-        const bool by_tuning = v.is_f16 && pixels >= 256;
+        const bool by_tuning = v.is_f16 && pixels >= 96;
         if (!wide_dense) return any_density || dense_enough || by_tuning;
         int64_t in_bytes = g.xd.image * 2 * g.n;
         if (g.ex) {
