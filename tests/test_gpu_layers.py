@@ -611,6 +611,37 @@ def test_matrix_core_variants_in_a_bottleneck(cad, geom):
         net.free()
 
 
+def test_split_k_sums_in_slice_order(cad):
+    """The matrix-core variants that split K over several workgroups per output tile add the
+    slices' partial tiles in slice order, whoever arrives last: repeated launches give
+    bit-identical outputs, the arrival counters are back at zero after every launch (a stale
+    count would make a later launch finish a tile early, with slices missing), and the result
+    meets the bar of the unsplit kernel."""
+    cin, cout, k, stride, pad, h, w_, s, n = 256, 72, 3, 1, 1, 10, 9, 0.9, 5
+    x = wl.activation((n, cin, h, w_), "splitk", 0, relu=False).astype(np.float16)
+    w = wl.pruned_weights(cout, cin, k, k, s, "splitk", 1)
+    b = wl.bias_vector(cout, "splitk", 1, sigma=0.5)
+    r = wl.activation((n, cout, h, w_), "splitk", 2, relu=False, role="r").astype(np.float16)
+    ref = oracle.conv2d(x, w.astype(np.float16), b, r, stride, pad, True, np.float16)
+    cond = cond_conv(x, w.astype(np.float16), b, r, stride, pad)
+    hnd = cad.cadnn_pack_weights(w, cad.F16)
+    names = [nm for nm in cad.cadnn_conv2d_list_variants(hnd, n, h, w_, stride, pad) if "_k" in nm]
+    assert "dense_mfma__Float16_64x64x32w_k8" in names and "dense_mfma__Float16_128x64x32_k4" in names, names
+    xd, rd, bd = dev(x), dev(r), dev(b)
+    for name in names:
+        cad.cadnn_conv2d_set_variant(hnd, n, h, w_, stride, pad, name)
+        outs = []
+        for rep in range(6):
+            out = torch.full((n, cout, h, w_), float("nan"), device="cuda", dtype=torch.float16)
+            cad.cadnn_sparse_conv2d(hnd, xd, stride, pad, bd, rd, True, out=out)
+            torch.cuda.synchronize()
+            outs.append(out.cpu().numpy())
+        assert_layer_close(outs[0], ref, cond, TOL_F16, f"split K {name}", f16=True)
+        for rep in range(1, 6):
+            assert np.array_equal(outs[0].view(np.uint16), outs[rep].view(np.uint16)), f"{name}: launch {rep} differs from launch 0"
+    hnd.free()
+
+
 @pytest.mark.parametrize("geom", [(7, 7, 1, 1), (7, 7, 3, 3), (14, 14, 2, 1), (9, 5, 2, 3)])
 def test_fused_global_average_pool(cad, geom):
     """A global average pool that is the only reader of a small-image convolution is computed
