@@ -488,23 +488,21 @@ __global__ __launch_bounds__(256) void dense_wide_reorder_kernel(const _Float16*
     }
 }
 
-#ifndef WIDE_HS
-#define WIDE_HS(MI, NI) ((MI) * (NI) == 4 ? 1 : 2)
-#define WIDE_D(MI, NI) 2
-#endif
-
-template <int MI, int NI>
+// HS: 32-deep steps per stage.  Two halve the barriers of a long K; one keeps the LDS tile small
+// (more workgroups per CU) and wastes nothing on layers whose K is a step or two: both are
+// offered, except for the largest tile, whose registers only hold one.
+template <int MI, int NI, int HS>
 hipError_t launch_wide_tile(const WideArgs& a, hipStream_t s) {
-    // (the smaller the tile, the fewer registers a set takes: deeper stages, more of them in flight)
-    constexpr int HS = WIDE_HS(MI, NI), D = WIDE_D(MI, NI);
     dim3 grid((unsigned)((a.total + 64 * NI - 1) / (64 * NI)), (unsigned)((a.cout + 64 * MI - 1) / (64 * MI)), (unsigned)a.sk);
-    CADNN_LAUNCH((dense_wide_kernel<MI, NI, HS, D>), grid, dim3(256), 0, s, a);
+    CADNN_LAUNCH((dense_wide_kernel<MI, NI, HS, 2>), grid, dim3(256), 0, s, a);
     return hipGetLastError();
 }
 
-hipError_t launch_wide_args(const WideArgs& a, int tm, int tn, hipStream_t s) {
-    if (tm == 128) return tn == 128 ? launch_wide_tile<2, 2>(a, s) : launch_wide_tile<2, 1>(a, s);
-    return tn == 128 ? launch_wide_tile<1, 2>(a, s) : launch_wide_tile<1, 1>(a, s);
+hipError_t launch_wide_args(const WideArgs& a, int tm, int tn, int hs, hipStream_t s) {
+    if (tm == 128 && tn == 128) return launch_wide_tile<2, 2, 1>(a, s);
+    if (tm == 128) return hs == 2 ? launch_wide_tile<2, 1, 2>(a, s) : launch_wide_tile<2, 1, 1>(a, s);
+    if (tn == 128) return hs == 2 ? launch_wide_tile<1, 2, 2>(a, s) : launch_wide_tile<1, 2, 1>(a, s);
+    return hs == 2 ? launch_wide_tile<1, 1, 2>(a, s) : launch_wide_tile<1, 1, 1>(a, s);
 }
 
 WideArgs wide_args(const void* w, const void* x, const TensorDesc& xd, void* y, const TensorDesc& yd, const void* residual,
@@ -548,9 +546,9 @@ WideArgs wide_args(const ConvLaunch& l) {
     return a;
 }
 
-template <int TM, int TN>
+template <int TM, int TN, int HS = 2>
 hipError_t launch_wide_variant(const ConvLaunch& l, hipStream_t s) {
-    return launch_wide_args(wide_args(l), TM, TN, s);
+    return launch_wide_args(wide_args(l), TM, TN, HS, s);
 }
 
 }  // namespace
@@ -580,6 +578,9 @@ const std::vector<ConvVariant>& all_dense_wide_variants() {
         add("dense_mfma__Float16_128x64x32", 128, 64, &launch_wide_variant<128, 64>);
         add("dense_mfma__Float16_64x128x32", 64, 128, &launch_wide_variant<64, 128>);
         add("dense_mfma__Float16_64x64x32w", 64, 64, &launch_wide_variant<64, 64>);
+        add("dense_mfma__Float16_128x64x32_h1", 128, 64, &launch_wide_variant<128, 64, 1>);
+        add("dense_mfma__Float16_64x128x32_h1", 64, 128, &launch_wide_variant<64, 128, 1>);
+        add("dense_mfma__Float16_64x64x32w_h1", 64, 64, &launch_wide_variant<64, 64, 1>);
         // K split over 2 / 4 / 8 workgroups per tile, for layers whose tiles alone leave the chip idle
         add("dense_mfma__Float16_64x64x32w_k2", 64, 64, &launch_wide_variant<64, 64>, 2);
         add("dense_mfma__Float16_64x64x32w_k4", 64, 64, &launch_wide_variant<64, 64>, 4);
@@ -611,7 +612,7 @@ cadnn_status dense_wide_conv2d_raw(const void* w_dev, const void* x, const Tenso
     if (blocks_of(tm, tn) < 512 && cout <= 64) tm = 64;
     if (blocks_of(tm, tn) < 512) tn = 64;
     if (blocks_of(tm, tn) < 512) tm = 64;
-    e = launch_wide_args(a, tm, tn, s);
+    e = launch_wide_args(a, tm, tn, a.csteps * kh * kw >= 8 ? 2 : 1, s);
     const hipError_t e2 = hipFreeAsync(wr, s);
     CADNN_HIP(e);
     CADNN_HIP(e2);
