@@ -64,7 +64,8 @@ struct WideArgs {
     TensorDesc x2d;
     int stride2, csteps2;
     // pixels a thread of the epilogue writes with one store (8, 4 or 2: they lie side by side
-    // in the output and the residual, suitably aligned), or 0: one pixel per store
+    // in the output and the residual, suitably aligned), -1: pairs starting at odd columns (an
+    // output with a halo of one element), or 0: one pixel per store straight from the accumulators
     int group;
     // K split over `sk` workgroups per output tile (blockIdx.z): each writes its fp32 partial
     // tile to `part`, the last to arrive (counted in `count`, which it leaves at zero) adds them
@@ -449,9 +450,67 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(const WideArgs a) {
                 }
             }
         };
+        // Output with a halo of one element (no residual): a row starts at an odd element, so the
+        // aligned pairs are (odd column, next column); a pair at the end of a row, and the first
+        // pixel of the tile, are written singly.
+        auto run_halo = [&]() __attribute__((always_inline)) {
+            constexpr int per_row = TN / 2, rows_per_sweep = 256 / per_row, sweeps = 64 / rows_per_sweep;
+            const int cg = (int)threadIdx.x % per_row, r0 = (int)threadIdx.x / per_row;
+            const int Qa = n0 + 2 * cg + 1, Qb = Qa + 1;
+            uint32_t ya = kWideOutOfRange, yb = kWideOutOfRange, y0 = kWideOutOfRange, dummy;
+            bool together = false;
+            if (Qa < a.total) {
+                const int img = Qa / a.hwout, q = Qa - img * a.hwout;
+                const int oh = q / a.yd.w, ow = q - oh * a.yd.w;
+                ya = (uint32_t)(img * (int)a.yd.image + tensor_off(a.yd, oh, ow)) * 2u;
+                together = ow + 1 < a.yd.w && cg != per_row - 1;
+            }
+            if (cg != per_row - 1 && !together) place(Qb, yb, dummy);      // (the next tile writes its own first pixel)
+            if (threadIdx.x < 64) place(n0, y0, dummy);
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) {
+                __syncthreads();
+                if (mi == 0 && threadIdx.x < TM) bl[threadIdx.x] = my_bias;
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i)
+                        ct[(wm * 32 + (i >> 2) * 8 + fk * 4 + (i & 3)) * CPITCH + wn * 32 * NI + ni * 32 + fm] = acc[mi][ni][i];
+                __syncthreads();
+                auto finish = [&](float v, float b) __attribute__((always_inline)) {
+                    v += b;
+                    if (a.relu) v = v > 0.0f ? v : 0.0f;
+                    return (uint32_t)__builtin_bit_cast(unsigned short, (_Float16)v);
+                };
+#pragma unroll
+                for (int k = 0; k < sweeps; ++k) {
+                    const int r = r0 + k * rows_per_sweep;
+                    const int co = m0 + (r >> 5) * 32 * MI + mi * 32 + (r & 31);
+                    const bool live = co < a.cout;
+                    const uint32_t po = (uint32_t)(live ? co : 0) * (uint32_t)a.yd.plane * 2u;
+                    const float b = bl[mi * 64 + r];
+                    const uint32_t va = finish(ct[r * CPITCH + 2 * cg + 1], b);
+                    const uint32_t vb = cg != per_row - 1 ? finish(ct[r * CPITCH + 2 * cg + 2], b) : 0u;
+                    if (together) {
+                        __builtin_amdgcn_raw_buffer_store_b32(va | (vb << 16), yrsrc, live ? ya + po : kWideOutOfRange, 0u, 0);
+                    } else {
+                        __builtin_amdgcn_raw_buffer_store_b16((unsigned short)va, yrsrc, live && ya != kWideOutOfRange ? ya + po : kWideOutOfRange, 0u, 0);
+                        __builtin_amdgcn_raw_buffer_store_b16((unsigned short)vb, yrsrc, live && yb != kWideOutOfRange ? yb + po : kWideOutOfRange, 0u, 0);
+                    }
+                }
+                if (threadIdx.x < 64) {          // the tile's first pixel, one channel per thread
+                    const int r = (int)threadIdx.x;
+                    const int co = m0 + (r >> 5) * 32 * MI + mi * 32 + (r & 31);
+                    const bool live = co < a.cout && y0 != kWideOutOfRange;
+                    __builtin_amdgcn_raw_buffer_store_b16((unsigned short)finish(ct[r * CPITCH], bl[mi * 64 + r]), yrsrc,
+                                                          live ? y0 + (uint32_t)co * (uint32_t)a.yd.plane * 2u : kWideOutOfRange, 0u, 0);
+                }
+            }
+        };
         if (a.group == 8) run(std::integral_constant<int, 8>());
         else if (a.group == 4) run(std::integral_constant<int, 4>());
-        else run(std::integral_constant<int, 2>());
+        else if (a.group == 2) run(std::integral_constant<int, 2>());
+        else run_halo();
     } else {
 #pragma unroll
         for (int ni = 0; ni < NI; ++ni) {
@@ -526,6 +585,10 @@ WideArgs wide_args(const void* w, const void* x, const TensorDesc& xd, void* y, 
     };
     a.group = group_of(yd, y);
     if (residual) a.group = std::min(a.group, group_of(rd, residual));
+    // a halo of one element around an even-sized plane, no residual: aligned pairs start at odd columns
+    if (a.group == 0 && !residual && !yd.s2d && yd.pw == 1 && yd.w % 2 == 0 && yd.pitch % 2 == 0 && yd.plane % 2 == 0 && yd.image % 2 == 0 &&
+        (uintptr_t)y % 4 == 0)
+        a.group = -1;
     a.sk = 1;
     return a;
 }
