@@ -67,6 +67,10 @@ struct WideArgs {
     // in the output and the residual, suitably aligned), -1: pairs starting at odd columns (an
     // output with a halo of one element), or 0: one pixel per store straight from the accumulators
     int group;
+    // neighbouring pixels of a row one gather load takes (1, 2 or 4): the input is walked with unit
+    // stride, every tap of every pixel lies in memory (no padding, or a halo that holds it), groups
+    // do not straddle rows and there is no fused shortcut
+    int gather;
     // K split over `sk` workgroups per output tile (blockIdx.z): each writes its fp32 partial
     // tile to `part`, the last to arrive (counted in `count`, which it leaves at zero) adds them
     // up in slice order and finishes the tile
@@ -88,9 +92,15 @@ __device__ __forceinline__ void wide_static_for(F&& f) {
 // one or two workgroups on a CU the chain LDS write - barrier - LDS read - MFMA of a stage is
 // not hidden by anything, so it has to be paid as seldom as the LDS size allows.
 // D (even): register sets, that is how many stages ahead of the MFMAs the global loads run.
-template <int MI, int NI, int HS, int D>
+// G: neighbouring pixels per gather load.  The texture path takes a wave's load in 16 cycles
+// whether a lane asks for 2 bytes or 8, and with 2-byte loads that is what bounds the kernel.
+template <int MI, int NI, int HS, int D, int G>
 __global__ __launch_bounds__(256) void dense_wide_kernel(const WideArgs a) {
     constexpr int TM = 64 * MI, TN = 64 * NI;
+    // a gather item is G pixels x CH channels of a step, fetched with CH loads; thread t takes
+    // items t + 256 j, so that every wave's loads carry 64 lanes of wanted data
+    constexpr int GROUPS = TN / G, CH = GROUPS / 8 < 8 ? GROUPS / 8 : 8, NB = GROUPS / 8 / CH;
+    static_assert(CH >= 2 && GROUPS * (WK / CH) == 256 * NB, "256 threads cover a step's activations");
     constexpr int PITCH = WK * HS + 8;      // halves between rows in LDS: 80, 144 or 272 bytes, all conflict-free
     // (the two stage buffers of both operands; the epilogue reuses them for the output tile)
     constexpr int CPITCH = TN + 8;          // words between rows of the fp32 output tile
@@ -106,12 +116,15 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(const WideArgs a) {
 
     // ---- gather side: pixels n0 + lane (+ 64) -- byte offset of their own input position (tap
     //      offsets are added per step) and the taps that fall inside the image
-    uint32_t gbase[NI], gbase2[NI];
-    uint64_t gmask[NI];
+    uint32_t gbase[NB], gbase2[NB];
+    uint64_t gmask[NB];
+    int grow[NB], gch[NB];        // first LDS row (pixel of the tile) and first channel of the item
 #pragma unroll
-    for (int h = 0; h < NI; ++h) {
-        // (LDS row lane + 64 h feeds MFMA column lane % 32 of accumulator lane / 32 of wave h)
-        const int Q = n0 + 64 * h + lane;
+    for (int h = 0; h < NB; ++h) {
+        const int item = (int)threadIdx.x + 256 * h;
+        grow[h] = (item % GROUPS) * G;
+        gch[h] = item / GROUPS * CH;
+        const int Q = n0 + grow[h];
         gbase[h] = 0;
         gbase2[h] = kWideOutOfRange;
         gmask[h] = 0;
@@ -122,14 +135,18 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(const WideArgs a) {
             // a pixel-wise stride-1 layer takes each pixel's own place)
             const int at = !a.xd.s2d ? a.xd.origin + oh * a.stride * a.xd.pitch + ow * a.stride
                            : a.stride == 2 ? oh * a.xd.pitch + ow : tensor_off(a.xd, oh, ow);
-            gbase[h] = (uint32_t)(img * (int)a.xd.image + at) * 2u;
+            // (the item's first channel rides in the per-lane part: a wave may hold several)
+            gbase[h] = (uint32_t)(img * (int)a.xd.image + gch[h] * a.xd.plane + at) * 2u;
             if (a.x2)
-                gbase2[h] = (uint32_t)(img * (int)a.x2d.image + a.x2d.origin + oh * a.stride2 * a.x2d.pitch + ow * a.stride2) * 2u;
-            for (int r = 0; r < a.kh; ++r)
-                for (int c = 0; c < a.kw; ++c) {
-                    const int ih = oh * a.stride + r - a.pad, iw = ow * a.stride + c - a.pad;
-                    if (ih >= 0 && ih < a.xd.h && iw >= 0 && iw < a.xd.w) gmask[h] |= (uint64_t)1 << (r * a.kw + c);
-                }
+                gbase2[h] = (uint32_t)(img * (int)a.x2d.image + gch[h] * a.x2d.plane + a.x2d.origin + oh * a.stride2 * a.x2d.pitch +
+                                       ow * a.stride2) * 2u;
+            if constexpr (G > 1) gmask[h] = ~(uint64_t)0;       // (every tap of every pixel lies in memory)
+            else
+                for (int r = 0; r < a.kh; ++r)
+                    for (int c = 0; c < a.kw; ++c) {
+                        const int ih = oh * a.stride + r - a.pad, iw = ow * a.stride + c - a.pad;
+                        if (ih >= 0 && ih < a.xd.h && iw >= 0 && iw < a.xd.w) gmask[h] |= (uint64_t)1 << (r * a.kw + c);
+                    }
         }
     }
     // (readfirstlane: the compiler must keep the buffer descriptors in scalar registers)
@@ -160,7 +177,9 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(const WideArgs a) {
     // D register sets: the loads of stage s + D are issued while stage s is multiplied and stage
     // s + 1, fetched D - 1 stages earlier, is written to LDS.
     u32x4w areg[D][HS][MI];
-    unsigned short breg[D][HS][NI][8];      // (widened only when the set is used: see stash)
+    // (2-byte elements are widened only when the set is used: see stash)
+    typedef std::conditional_t<G == 1, unsigned short, std::conditional_t<G == 2, uint32_t, u32x2w>> gather_t;
+    gather_t breg[D][HS][NB][CH];
     // Steps are fetched in order and a wave is one serial instruction stream, so what a step
     // costs in scalar bookkeeping it costs in time: the state of the walk over K is carried
     // along -- per step about ten scalar additions and a counter -- and everything that depends on
@@ -179,13 +198,13 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(const WideArgs a) {
     int f_tap = 0, f_r = 0, f_c = 0, f_left = 0, f_todo = steps;          // (scalar)
     bool f_second = false;
     uint32_t f_soffA = 0, f_inc = 0, f_pb = 0, f_soffB = 0;
-    uint32_t f_vA[MI], f_vB[NI];
+    uint32_t f_vA[MI], f_vB[NB];
     // (past the slice only the per-lane parts of the addresses change, to out of range, which is
     // what the range check looks at; the scalar parts run on)
     auto end_walk = [&]() __attribute__((always_inline)) {
         f_left = 0x7fffffff;
 #pragma unroll
-        for (int h = 0; h < NI; ++h) f_vB[h] = kWideOutOfRange;
+        for (int h = 0; h < NB; ++h) f_vB[h] = kWideOutOfRange;
 #pragma unroll
         for (int i = 0; i < MI; ++i) f_vA[i] = kWideOutOfRange;
     };
@@ -198,9 +217,9 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(const WideArgs a) {
         f_pb = f_second ? plane2_bytes : plane_bytes;
         f_inc = WK * f_pb;
         f_left = (f_second ? a.csteps2 : a.csteps) - cb;
-        f_soffB = (uint32_t)(cb * WK + wv * 8) * f_pb;
+        f_soffB = (uint32_t)(cb * WK) * f_pb;
 #pragma unroll
-        for (int h = 0; h < NI; ++h)
+        for (int h = 0; h < NB; ++h)
             f_vB[h] = f_second ? gbase2[h] : ((gmask[h] >> f_tap) & 1) ? gbase[h] + (uint32_t)(tap_el * 2) : kWideOutOfRange;
     };
     auto next_tap = [&]() __attribute__((always_inline)) {
@@ -222,15 +241,24 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(const WideArgs a) {
         constexpr int S = decltype(SET)::value;
 #pragma unroll
         for (int hs = 0; hs < HS; ++hs) {
+            // (made scalar by hand: the compiler may fold this choice into per-lane control flow)
+            const uint64_t xp = f_second ? (uint64_t)a.x2 : (uint64_t)a.x;
+            // (the builtin returns a signed int: through uint32_t, or the low word's top bit smears over the high word)
+            const uint64_t xps = (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)xp) |
+                                 ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(xp >> 32)) << 32);
             const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
-                f_second ? (void*)a.x2 : (void*)a.x, 0, f_second ? x2span : xspan, 0x00020000);
+                (void*)xps, 0, __builtin_amdgcn_readfirstlane(f_second ? x2span : xspan), 0x00020000);
 #pragma unroll
             for (int i = 0; i < MI; ++i) areg[S][hs][i] = __builtin_amdgcn_raw_buffer_load_b128(wrsrc, f_vA[i], f_soffA, 0);
             uint32_t soff = f_soffB;         // (channel by channel: one running scalar instead of eight kept ones)
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
+            for (int k = 0; k < CH; ++k) {
 #pragma unroll
-                for (int h = 0; h < NI; ++h) breg[S][hs][h][k] = __builtin_amdgcn_raw_buffer_load_b16(xrsrc, f_vB[h], soff, 0);
+                for (int h = 0; h < NB; ++h) {
+                    if constexpr (G == 1) breg[S][hs][h][k] = __builtin_amdgcn_raw_buffer_load_b16(xrsrc, f_vB[h], soff, 0);
+                    else if constexpr (G == 2) breg[S][hs][h][k] = __builtin_amdgcn_raw_buffer_load_b32(xrsrc, f_vB[h], soff, 0);
+                    else breg[S][hs][h][k] = __builtin_amdgcn_raw_buffer_load_b64(xrsrc, f_vB[h], soff, 0);
+                }
                 soff += f_pb;
             }
             f_soffA += WK * 2;
@@ -250,9 +278,9 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(const WideArgs a) {
 #pragma unroll
             for (int i = 0; i < MI; ++i) asm volatile("" : "+v"(areg[S][hs][i]));
 #pragma unroll
-            for (int h = 0; h < NI; ++h)
+            for (int h = 0; h < NB; ++h)
 #pragma unroll
-                for (int k = 0; k < 8; ++k) asm volatile("" : "+v"(breg[S][hs][h][k]));
+                for (int k = 0; k < CH; ++k) asm volatile("" : "+v"(breg[S][hs][h][k]));
         }
 #pragma unroll
         for (int hs = 0; hs < HS; ++hs) {
@@ -260,12 +288,32 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(const WideArgs a) {
             for (int i = 0; i < MI; ++i)
                 *(u32x4w*)(&As[buf][(((int)threadIdx.x + 256 * i) >> 2) * PITCH + hs * WK + apart * 8]) = areg[S][hs][i];
 #pragma unroll
-            for (int h = 0; h < NI; ++h) {
-                u32x4w pk;
+            for (int h = 0; h < NB; ++h) {
+                _Float16* dst = &Bs[buf][grow[h] * PITCH + hs * WK + gch[h]];
+                if constexpr (G == 1) {
+                    u32x4w pk;
 #pragma unroll
-                for (int k = 0; k < 4; ++k)
-                    pk[k] = (uint32_t)breg[S][hs][h][2 * k] | ((uint32_t)breg[S][hs][h][2 * k + 1] << 16);
-                *(u32x4w*)(&Bs[buf][(lane + 64 * h) * PITCH + hs * WK + wv * 8]) = pk;
+                    for (int k = 0; k < 4; ++k)
+                        pk[k] = (uint32_t)breg[S][hs][h][2 * k] | ((uint32_t)breg[S][hs][h][2 * k + 1] << 16);
+                    *(u32x4w*)dst = pk;
+                } else {
+                    // a loaded word holds one channel of two neighbouring pixels: the low halves of
+                    // two channels make a word of the first pixel, the high halves one of the second
+#pragma unroll
+                    for (int j = 0; j < G; ++j) {
+                        uint32_t word[CH / 2];
+#pragma unroll
+                        for (int m = 0; m < CH / 2; ++m) {
+                            uint32_t lo, hi;
+                            if constexpr (G == 2) { lo = breg[S][hs][h][2 * m]; hi = breg[S][hs][h][2 * m + 1]; }
+                            else { lo = breg[S][hs][h][2 * m][j >> 1]; hi = breg[S][hs][h][2 * m + 1][j >> 1]; }
+                            word[m] = __builtin_amdgcn_perm(hi, lo, (j & 1) ? 0x07060302u : 0x05040100u);
+                        }
+                        if constexpr (CH == 2) *(uint32_t*)(dst + j * PITCH) = word[0];
+                        else if constexpr (CH == 4) *(u32x2w*)(dst + j * PITCH) = u32x2w{word[0], word[1]};
+                        else *(u32x4w*)(dst + j * PITCH) = u32x4w{word[0], word[1], word[2], word[3]};
+                    }
+                }
             }
         }
     };
@@ -282,27 +330,35 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(const WideArgs a) {
     // stage s: LDS buffer s % 2 holds it; register set (s + j) % D holds stage s + j, 0 < j < D
     auto body = [&](auto PAR) __attribute__((always_inline)) {
         constexpr int P = decltype(PAR)::value;
-        fetch(std::integral_constant<int, P>());
-        // (the scheduler keeps the three phases in this order: loads issued, products, then
-        // the wait for the oldest set and its way to LDS)
-        __builtin_amdgcn_sched_barrier(0);
+        // A wave is one in-order instruction stream and there are few waves per SIMD, so the
+        // order is chosen to keep a wait from standing right behind the request it waits for:
+        // the stage's fragments are requested from LDS first; the global loads of stage s + D
+        // are issued and the oldest set is waited for, packed and written to the LDS buffer
+        // nobody reads during this stage while the fragments arrive; the products follow
+        // without a wait in between and run on while the wave goes to the barrier.  (The
+        // scheduler is held to this order.)
+        h8 af[2 * HS][MI], bf[2 * HS][NI];
 #pragma unroll
         for (int ks = 0; ks < 2 * HS; ++ks) {
-            h8 af[MI], bf[NI];
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi)
-                af[mi] = *(const h8*)(&As[P & 1][(wm * 32 * MI + mi * 32 + fm) * PITCH + ks * 16 + fk * 8]);
+                af[ks][mi] = *(const h8*)(&As[P & 1][(wm * 32 * MI + mi * 32 + fm) * PITCH + ks * 16 + fk * 8]);
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni)
-                bf[ni] = *(const h8*)(&Bs[P & 1][(wn * 32 * NI + ni * 32 + fm) * PITCH + ks * 16 + fk * 8]);
+                bf[ks][ni] = *(const h8*)(&Bs[P & 1][(wn * 32 * NI + ni * 32 + fm) * PITCH + ks * 16 + fk * 8]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        fetch(std::integral_constant<int, P>());
+        __builtin_amdgcn_sched_barrier(0);
+        stash((P + 1) & 1, std::integral_constant<int, (P + 1) % D>());
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int ks = 0; ks < 2 * HS; ++ks)
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
                 for (int ni = 0; ni < NI; ++ni)
-                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[mi], bf[ni], acc[mi][ni], 0, 0, 0);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        stash((P + 1) & 1, std::integral_constant<int, (P + 1) % D>());
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[ks][mi], bf[ks][ni], acc[mi][ni], 0, 0, 0);
         __syncthreads();
     };
     wide_static_for<0, D>([&](auto J) { fetch(J); });
@@ -388,9 +444,9 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(const WideArgs a) {
         float* ct = (float*)smem;
         float* bl = (float*)(smem + TILE_BYTES);            // [pass][local row]
         auto run = [&](auto GG) __attribute__((always_inline)) {
-            constexpr int G = decltype(GG)::value, per_row = TN / G, rows_per_sweep = 256 / per_row, sweeps = 64 / rows_per_sweep;
+            constexpr int SG = decltype(GG)::value, per_row = TN / SG, rows_per_sweep = 256 / per_row, sweeps = 64 / rows_per_sweep;
             const int cg = (int)threadIdx.x % per_row, r0 = (int)threadIdx.x / per_row;
-            const int Q = n0 + cg * G;
+            const int Q = n0 + cg * SG;
             uint32_t yoff = kWideOutOfRange, roff = kWideOutOfRange;
             if (Q < a.total) {          // (the images' pixel counts are multiples of the group: all of it or none)
                 const int img = Q / a.hwout, q = Q - img * a.hwout;
@@ -414,7 +470,7 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(const WideArgs a) {
                     const bool live = co < a.cout && yoff != kWideOutOfRange;
                     const int cc = co < a.cout ? co : 0;
                     const float b = bl[mi * 64 + r];
-                    const float* src = ct + r * CPITCH + cg * G;
+                    const float* src = ct + r * CPITCH + cg * SG;
                     const uint32_t yo = live ? yoff + (uint32_t)cc * (uint32_t)a.yd.plane * 2u : kWideOutOfRange;
                     const uint32_t ro = live ? roff + (uint32_t)cc * (uint32_t)a.rd.plane * 2u : kWideOutOfRange;
                     auto finish = [&](float v, uint32_t rbits) __attribute__((always_inline)) {
@@ -423,7 +479,7 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(const WideArgs a) {
                         if (a.relu) v = v > 0.0f ? v : 0.0f;
                         return (uint32_t)__builtin_bit_cast(unsigned short, (_Float16)v);
                     };
-                    if constexpr (G == 8) {
+                    if constexpr (SG == 8) {
                         const f32x4w lo = *(const f32x4w*)src, hi = *(const f32x4w*)(src + 4);
                         u32x4w rr = {0u, 0u, 0u, 0u};
                         if (a.residual) rr = __builtin_amdgcn_raw_buffer_load_b128(rrsrc, ro, 0u, 0);
@@ -433,7 +489,7 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(const WideArgs a) {
                         o[2] = finish(hi[0], rr[2]) | (finish(hi[1], rr[2] >> 16) << 16);
                         o[3] = finish(hi[2], rr[3]) | (finish(hi[3], rr[3] >> 16) << 16);
                         __builtin_amdgcn_raw_buffer_store_b128(o, yrsrc, yo, 0u, 0);
-                    } else if constexpr (G == 4) {
+                    } else if constexpr (SG == 4) {
                         const f32x4w lo = *(const f32x4w*)src;
                         u32x2w rr = {0u, 0u};
                         if (a.residual) rr = __builtin_amdgcn_raw_buffer_load_b64(rrsrc, ro, 0u, 0);
@@ -550,10 +606,15 @@ __global__ __launch_bounds__(256) void dense_wide_reorder_kernel(const _Float16*
 // HS: 32-deep steps per stage.  Two halve the barriers of a long K; one keeps the LDS tile small
 // (more workgroups per CU) and wastes nothing on layers whose K is a step or two: both are
 // offered, except for the largest tile, whose registers only hold one.
+#ifndef CADNN_WIDE_DEPTH
+#define CADNN_WIDE_DEPTH 2
+#endif
 template <int MI, int NI, int HS>
 hipError_t launch_wide_tile(const WideArgs& a, hipStream_t s) {
     dim3 grid((unsigned)((a.total + 64 * NI - 1) / (64 * NI)), (unsigned)((a.cout + 64 * MI - 1) / (64 * MI)), (unsigned)a.sk);
-    CADNN_LAUNCH((dense_wide_kernel<MI, NI, HS, 2>), grid, dim3(256), 0, s, a);
+    if (a.gather == 4) CADNN_LAUNCH((dense_wide_kernel<MI, NI, HS, CADNN_WIDE_DEPTH, 4>), grid, dim3(256), 0, s, a);
+    else if (a.gather == 2) CADNN_LAUNCH((dense_wide_kernel<MI, NI, HS, CADNN_WIDE_DEPTH, 2>), grid, dim3(256), 0, s, a);
+    else CADNN_LAUNCH((dense_wide_kernel<MI, NI, HS, 2, 1>), grid, dim3(256), 0, s, a);
     return hipGetLastError();
 }
 
@@ -589,6 +650,10 @@ WideArgs wide_args(const void* w, const void* x, const TensorDesc& xd, void* y, 
     if (a.group == 0 && !residual && !yd.s2d && yd.pw == 1 && yd.w % 2 == 0 && yd.pitch % 2 == 0 && yd.plane % 2 == 0 && yd.image % 2 == 0 &&
         (uintptr_t)y % 4 == 0)
         a.group = -1;
+    a.gather = 1;
+    const bool taps_in_memory = pad == 0 || (xd.ph >= pad && xd.pw >= pad);
+    if (stride == 1 && !xd.s2d && taps_in_memory)
+        a.gather = yd.w % 4 == 0 ? 4 : yd.w % 2 == 0 ? 2 : 1;
     a.sk = 1;
     return a;
 }
@@ -602,6 +667,7 @@ WideArgs wide_args(const ConvLaunch& l) {
         a.stride2 = l.stride2;
         a.csteps2 = l.x2d.c / WK;
         a.K += l.x2d.c;
+        a.gather = 1;
     }
     a.sk = l.sk > 1 ? l.sk : 1;
     a.part = l.sk_part;
