@@ -18,7 +18,7 @@ INCLUDE = os.path.join(ROOT, "include")
 OBJDIR = os.path.join(ROOT, "_build")
 LIB = os.path.join(HERE, "libcadnn.so")
 
-SOURCES = ["pack.cpp", "api.cpp", "net.cpp", "conv_tile.hip", "conv_direct.hip", "conv_linear.hip", "conv_stile.hip", "conv_ptile.hip", "conv_wtile.hip", "conv_depthwise.hip", "misc_kernels.hip", "dense_conv.hip", "dense_wide.hip"]
+SOURCES = ["pack.cpp", "api.cpp", "net.cpp", "conv_tile.hip", "conv_direct.hip", "conv_linear.hip", "conv_quad.hip", "conv_stile.hip", "conv_ptile.hip", "conv_wtile.hip", "conv_depthwise.hip", "misc_kernels.hip", "dense_conv.hip", "dense_wide.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

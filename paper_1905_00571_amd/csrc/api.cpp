@@ -146,6 +146,8 @@ static bool variant_fits(const ConvVariant& v, const cadnn_weights* w, const Con
         // de-interleaved input is handed a plain view of the phase it starts in.
         const bool general = g.out_s2d || (g.xd.s2d && g.stride == 1);
         if (general != (v.s2d != 0)) return false;
+        // several rows per wave: the whole image in a row's share of the lanes, nothing fused
+        if (v.quad && (g.ex || g.hout * ((g.wout + v.p - 1) / v.p) > 64 / v.rpw)) return false;
         // a fused shortcut takes the dual-input instantiations; its input must be walkable
         // with one stride (plain layout, or de-interleaved and read with stride 2)
         const bool shortcut = g.ex && g.ex->w, pooled = g.ex && g.ex->pool_y, dwf = g.ex && g.ex->dw;
@@ -164,12 +166,12 @@ static bool variant_fits(const ConvVariant& v, const cadnn_weights* w, const Con
         // a lane's adjacent pixels must be adjacent in memory, on both sides; rows that split
         // evenly into groups take the plain instantiations, the others the ragged-row ones
         const int unit = g.xd.s2d ? 2 : 1;
-        if (v.adjacent && (g.stride != unit || (g.wout % v.p != 0) != (v.adjacent == 2))) return false;
+        if (v.adjacent && (g.stride != unit || (!v.quad && (g.wout % v.p != 0) != (v.adjacent == 2)))) return false;
         // The last group of a ragged row reads up to P-1 elements past its row.  Past the end
         // of the image that reads as zero dword by dword, which is fine for 4-byte storage; in
         // 2-byte storage the dword holding the image's last element would be dropped whole,
         // so there the input must end in a halo row instead.
-        if (v.adjacent == 2 && v.is_f16 && g.xd.ph < 1) return false;
+        if (v.adjacent == 2 && v.is_f16 && g.xd.ph < 1 && !(v.quad && g.wout % v.p == 0)) return false;
         // 1x1 filters read only the image proper; larger filters need the zero halo
         if (one) return g.pad == 0;
         return g.xd.ph >= g.pad && g.xd.pw >= g.pad;
@@ -200,6 +202,7 @@ static bool variant_fits(const ConvVariant& v, const cadnn_weights* w, const Con
 static std::vector<const ConvVariant*> candidates(const cadnn_weights* w, const ConvGeom& g) {
     std::vector<const ConvVariant*> out;
     for (const ConvVariant& v : all_linear_variants()) if (variant_fits(v, w, g)) out.push_back(&v);
+    for (const ConvVariant& v : all_quad_variants()) if (variant_fits(v, w, g)) out.push_back(&v);
     for (const ConvVariant& v : all_direct_variants()) if (variant_fits(v, w, g)) out.push_back(&v);
     for (const ConvVariant& v : all_tile_variants()) if (variant_fits(v, w, g)) out.push_back(&v);
     for (const ConvVariant& v : all_dense_variants()) if (variant_fits(v, w, g)) out.push_back(&v);
@@ -244,6 +247,8 @@ static double variant_cost(const cadnn_weights* w, const ConvGeom& g, const Conv
         const double K = (double)w->cin * w->kh * w->kw;
         cost = 2500.0 + std::ceil(blocks / 256.0) * std::ceil(K / 32.0) * 1100.0;
     } else if (v->family == FAM_STILE || v->family == FAM_PTILE || v->family == FAM_WTILE) {
+        return -1.0;
+    } else if (v->quad) {
         return -1.0;
     } else if (v->family != FAM_TILE) {
         const int P = v->p;

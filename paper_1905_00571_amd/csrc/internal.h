@@ -232,6 +232,7 @@ struct ConvVariant {
     int dual;             // FAM_LINEAR: accumulates a fused 1x1 shortcut on a second input
     int pool;             // FAM_LINEAR: global average pool fused into the epilogue
     int dw;               // FAM_LINEAR: a 3x3 depthwise layer fused into the epilogue
+    int quad;             // FAM_LINEAR: rpw packed rows per wave side by side, 64 / rpw lanes x p adjacent pixels each (small images)
     int nz_cap;           // FAM_STILE: most stream entries per (row group, chunk) the kernel buffers
     int flat;             // FAM_WTILE: 1 = pixel-wise layers (1x1 filters), pixels flattened over the batch;
                           //            0 = filters with taps, lanes in an (rw x 64/rw) grid over a 2-D tile
@@ -403,6 +404,8 @@ constexpr int kWtileMaxSteps = 10;
 inline size_t wtile_lds_budget(const ConvVariant& v) { return v.nw >= 16 ? (size_t)160 * 1024 : (size_t)80 * 1024; }
 constexpr int kPtileMaxSteps = 9;
 constexpr size_t kLdsBytesPerCU = 160 * 1024;
+// a plan entry's byte offset that no buffer this library accepts reaches: its load reads zero
+constexpr uint32_t kPlanOutOfRange = 0x7ffffff0u;
 constexpr int kFcTailEntries = 1024;   // 4 loads x 64 lanes x 4 entries
 
 // (variant, a, b, shortcut weights, shortcut input plane): FAM_LINEAR a = input plane,
@@ -418,6 +421,8 @@ struct SkScratch { DevBuf part, count; bool in_use = false; };
 const std::vector<ConvVariant>& all_tile_variants();
 const std::vector<ConvVariant>& all_direct_variants();
 const std::vector<ConvVariant>& all_linear_variants();
+// (the same plans and addresses, four rows per wave: conv_quad.hip)
+const std::vector<ConvVariant>& all_quad_variants();
 const std::vector<ConvVariant>& all_dense_variants();
 // fp16 storage, 128 x 128 tiles, tap-major weight matrix (marked by tw == 128)
 const std::vector<ConvVariant>& all_dense_wide_variants();

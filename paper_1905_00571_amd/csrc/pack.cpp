@@ -308,7 +308,9 @@ static cadnn_status build_linear_plan(const cadnn_weights* w, const ConvVariant*
     if (total > (int64_t)INT32_MAX / 2) return fail(CADNN_EUNSUPPORTED, "plan too large");
     std::vector<int32_t> hdr((size_t)rows_padded * ks * hw, 0);
     std::vector<int32_t> perm(rows_padded, -1);
-    std::vector<uint2> nz((size_t)total, make_uint2(0u, 0u));
+    // (four rows per wave are walked in lock step, the shorter ones into the unused end of their
+    // part: there an entry must not touch memory)
+    std::vector<uint2> nz((size_t)total, make_uint2(0u, v->quad ? kPlanOutOfRange : 0u));
     int64_t walked_entries = 0;
     for (int i = 0; i < rows_padded; ++i) {
         const int32_t b = i < w->cout ? w->row_ptr[i] : 0;

@@ -333,6 +333,10 @@ VARIANT_GEOMS = [
     # long K on few pixels: the variants that split K over several workgroups per output tile
     (160, 70, 3, 1, 1, 12, 11, 0.8, 2),
     (256, 40, 3, 1, 1, 9, 9, 0.9, 4),
+    # images of at most 16 groups of 4 adjacent pixels: four packed rows per wave (pixel-wise, and
+    # a 3x3 filter without padding, which needs no halo on a plain tensor)
+    (96, 50, 1, 1, 0, 7, 7, 0.8, 3),
+    (72, 41, 3, 1, 0, 9, 10, 0.85, 2),
 ]
 
 
@@ -387,6 +391,9 @@ def test_every_kernel_variant(cad, geom):
             assert "dense_mfma__Float16_128x128x32" in names, names
         if dtype == cad.F16 and cin * k * k // 32 >= 64 and cin % 32 == 0:
             assert "dense_mfma__Float16_64x64x32w_k8" in names, names
+        # (in 2-byte storage a row that does not split into groups of 4 needs a halo row behind the image)
+        if pad == 0 and stride == 1 and hout * ((wout + 3) // 4) <= 16 and (dtype == cad.F32 or wout % 4 == 0):
+            assert [nm for nm in names if nm.startswith("squad_") and "_r4" in nm] and [nm for nm in names if "_r2" in nm], names
         xd, rd, bd = dev(xs), dev(rs), dev(b)
         for name in names:
             cad.cadnn_conv2d_set_variant(hnd, n, h, w_, stride, pad, name)
@@ -499,7 +506,7 @@ def test_every_variant_on_deinterleaved_tensors(cad, geom):
         xd = dev(xs)
         for i in range(5):
             names = net.op_candidates(i)
-            assert names and (i == 4 or all(nm.startswith(("slinear", "swide")) for nm in names)), (i, names)
+            assert names and (i == 4 or all(nm.startswith(("slinear", "squad", "swide")) for nm in names)), (i, names)
             r = outs[3] if ops[i].res >= 0 else None
             cond = cond_conv(ins[i], ws[i].astype(npdt), bs[i], r, ops[i].stride, ops[i].pad)
             for name in names:
@@ -609,6 +616,52 @@ def test_matrix_core_variants_in_a_bottleneck(cad, geom):
                 assert_within_bound(got, outs[i], bounds[i], f"{geom} fuse={fuse} op {ops[i].name} {name}")
                 assert np.abs(got.astype(np.float64) - outs[i].astype(np.float64)).max() <= tol * np.abs(outs[i]).max()
         net.free()
+
+
+@pytest.mark.parametrize("dtype_name", ["f32", "f16"])
+@pytest.mark.parametrize("geom", [(7, 7, 2, 1), (14, 14, 1, 2), (8, 8, 3, 1), (5, 6, 2, 1), (16, 12, 2, 2), (10, 6, 2, 1)])
+def test_several_rows_per_wave_in_a_bottleneck(cad, geom, dtype_name):
+    """The small-image kernels (four packed rows per wave with 16 lanes of 4 adjacent pixels per
+    row, or two with 32 lanes of 2 pixels)
+    in the roles a net gives them: pixel-wise on a plain tensor, a 3x3 filter on a tensor with
+    a halo, a strided 3x3 on a de-interleaved tensor, widths that do and do not split into
+    groups of 4, a residual.  Each instantiation is pinned in turn and the layer's output
+    compared with the oracle."""
+    h, w_, n, stride = geom
+    ops = [wl.Op("conv", "t", 0, 1, 8, 40, 1, 1, 0, 0.5, True),
+           wl.Op("conv", "a", 1, 2, 40, 24, 1, 1, 0, 0.8, True),
+           wl.Op("conv", "b", 2, 3, 24, 50, 3, stride, 1, 0.85, True),
+           wl.Op("conv", "p", 1, 4, 40, 70, 1, stride, 0, 0.8, False),
+           wl.Op("conv", "c", 3, 5, 50, 70, 1, 1, 0, 0.8, True, 4),
+           wl.Op("conv", "post", 5, 6, 70, 6, 1, 1, 0, 0.2, False)]
+    shape = (n, 8, h, w_)
+    f16 = dtype_name == "f16"
+    npdt, tol = (np.float16, TOL_F16) if f16 else (np.float32, TOL_F32)
+    x, ws, bs = wl.net_tensors(ops, "quad-%d-%d-%d" % (h, w_, stride), shape, input_relu=True)
+    xs = x.astype(npdt)
+    ref, ins, outs = oracle.run_net(ops, xs, ws, bs, dtype=npdt)
+    bounds = chain_bounds(ops, ins, outs, ws, bs, f16)
+    xd = dev(xs)
+    net = cad.build_net(ops, ws, bs, shape, cad.F16 if f16 else cad.F32, use_graph=False, fuse=False)
+    seen = 0
+    for i in (1, 2, 4):
+        names = [nm for nm in net.op_candidates(i) if nm.startswith("squad_")]
+        small = outs[i].shape[2] * ((outs[i].shape[3] + 3) // 4) <= 16      # (10 x 6: only two rows per wave fit)
+        # (the layer in front of a strided 3x3 writes a de-interleaved tensor: not offered there)
+        # and in 2-byte storage ragged rows need an input with a halo, which only the 3x3 layer has)
+        if small and not (i == 1 and stride == 2) and (not f16 or i == 2 or outs[i].shape[3] % 4 == 0):
+            assert len(names) >= 5, (i, net.op_candidates(i))
+        for name in names:
+            net.set_op_variant(i, name)
+            assert net.op_variant(i) == name
+            net.run(xd)
+            torch.cuda.synchronize()
+            got = net.read_buffer(ops[i].dst, outs[i].shape)
+            assert_within_bound(got, outs[i], bounds[i], f"{geom} {dtype_name} op {ops[i].name} {name}")
+            assert np.abs(got.astype(np.float64) - outs[i].astype(np.float64)).max() <= tol * max(np.abs(outs[i]).max(), 1e-3)
+            seen += 1
+    assert seen >= 5
+    net.free()
 
 
 def test_split_k_sums_in_slice_order(cad):
