@@ -355,10 +355,17 @@ def main() -> int:
     if dom_name in MFMA_KERNELS:
         peak = MFMA_FP16_TFLOPS if dt == "f16" else FP32_VECTOR_TFLOPS     # (dense fp32 MFMA: 157.3 as well)
         achieved = dom["flops"] / dom["launches"] / avg_s / 1e12
-        roofline = {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
-                    "traffic": None,
-                    "note": "the dense contraction the kernel performs (every position of the weight matrix), "
-                            "not the nonzero count"}
+        gbs = dom["bytes"] / dom["launches"] / avg_s / 1e9
+        note = ("the dense contraction the kernel performs (every position of the weight matrix), not the nonzero "
+                "count; both roofs are given, 'bound' is the one that allows the launch less time")
+        if t_hbm > dom["flops"] / dom["launches"] / (peak * 1e12):
+            roofline = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
+                        "traffic": None}
+        else:
+            roofline = {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
+                        "traffic": None}
+        roofline.update({"note": note, "mfma_tflops": achieved, "frac_of_mfma_peak": achieved / peak,
+                         "hbm_gbs": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS})
     elif t_alu >= t_hbm:
         achieved = dom["flops"] / dom["launches"] / avg_s / 1e12
         roofline = {"bound": "alu", "achieved": achieved, "peak": FP32_VECTOR_TFLOPS, "unit": "TFLOP/s",

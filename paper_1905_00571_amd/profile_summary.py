@@ -86,6 +86,9 @@ RATIOS = [
     ("LDS bank-conflict / LDS active cycles", "SQ_LDS_BANK_CONFLICT", "SQ_ACTIVE_INST_LDS"),
     ("MFMA busy / busy-CU cycles", "SQ_VALU_MFMA_BUSY_CYCLES", "SQ_BUSY_CU_CYCLES"),
     ("L2 hit rate", "TCC_HIT_sum", None),
+    ("vector-cache line accesses per buffer-load wave instruction", "TCP_TOTAL_CACHE_ACCESSES_sum", "TA_BUFFER_LOAD_WAVEFRONTS_sum"),
+    ("address unit busy / vector-cache clocked cycles", "TA_TA_BUSY_sum", "TCP_GATE_EN1_sum"),
+    ("vector cache waiting on misses / clocked cycles", "TCP_PENDING_STALL_CYCLES_sum", "TCP_GATE_EN1_sum"),
 ]
 
 
