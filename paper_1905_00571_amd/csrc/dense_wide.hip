@@ -19,17 +19,19 @@
 // steps of 32 = 32 channels of one tap:
 //   * weights [128][32] arrive as 16-byte loads from the reordered matrix and lie in LDS with
 //     rows 80 bytes apart (the 16-byte fragment reads of 16 lanes hit 16 different bank groups);
-//   * activations [32][128]: lane l of wave w gathers pixels l and l + 64 of channels
-//     8w .. 8w+7 with 2-byte loads -- address = pixel's own offset + tap offset, in the vector
-//     part, + channel plane, in the scalar part; a tap that falls outside the image for a
-//     pixel gets an out-of-range offset and reads zero, so any padding works with or without
-//     a halo in memory.  The eight channels of a pixel are packed into one 16-byte LDS write,
-//     [pixel][k] with rows 80 bytes apart like the weights: the transposition NCHW needs on
-//     the way to the matrix cores happens in registers, and both MFMA operands are single
-//     16-byte LDS reads.
-// Global loads run D steps ahead in D register sets (2 for the largest tile, 8 for the
-// smallest): those of step s+D are issued before the MFMAs of step s, after which step s+1 is
-// written to the other LDS buffer: one barrier per step.  Epilogue: bias, residual, ReLU fused (Section 4).
+//   * activations [32][128]: gathered from NCHW with buffer loads of 1, 2 or 4 neighbouring
+//     pixels of one channel -- address = the pixel group's own offset + tap offset + the
+//     thread's first channel, in the vector part, + channel plane, in the scalar part.  With one
+//     pixel per load a tap that falls outside the image for a pixel gets an out-of-range offset
+//     and reads zero, so any padding works with or without a halo in memory; wider loads are
+//     used where every tap of every pixel lies in memory.  The channels a thread holds of a
+//     pixel are packed into one LDS write, [pixel][k] with rows 80 bytes apart like the
+//     weights: the transposition NCHW needs on the way to the matrix cores happens in
+//     registers, and both MFMA operands are single 16-byte LDS reads.
+// Global loads run two stages ahead in two register sets.  Within a stage a wave requests the
+// stage's fragments from LDS, issues the loads of stage s+2, waits for the set of stage s+1
+// and writes it to the other LDS buffer, then multiplies: one barrier per stage.  Epilogue:
+// bias, residual, ReLU fused (Section 4).
 #include <type_traits>
 
 #include "internal.h"
@@ -92,8 +94,8 @@ __device__ __forceinline__ void wide_static_for(F&& f) {
 // one or two workgroups on a CU the chain LDS write - barrier - LDS read - MFMA of a stage is
 // not hidden by anything, so it has to be paid as seldom as the LDS size allows.
 // D (even): register sets, that is how many stages ahead of the MFMAs the global loads run.
-// G: neighbouring pixels per gather load.  The texture path takes a wave's load in 16 cycles
-// whether a lane asks for 2 bytes or 8, and with 2-byte loads that is what bounds the kernel.
+// G: neighbouring pixels per gather load (a quarter of the load instructions with 4; measured:
+// a few percent of a layer's time, most where rows are short).
 template <int MI, int NI, int HS, int D, int G>
 __global__ __launch_bounds__(256) void dense_wide_kernel(const WideArgs a) {
     constexpr int TM = 64 * MI, TN = 64 * NI;
