@@ -66,9 +66,10 @@ struct WideArgs {
     TensorDesc x2d;
     int stride2, csteps2;
     // pixels a thread of the epilogue writes with one store (8, 4 or 2: they lie side by side
-    // in the output and the residual, suitably aligned), -1: pairs starting at odd columns (an
-    // output with a halo of one element), or 0: one pixel per store straight from the accumulators
-    int group;
+    // in the output and the residual, suitably aligned), or 0; then `rows`: pixels of one image
+    // row a thread finishes together (8, 4 or 2: the rows split into such groups, whatever the
+    // layout), or 0: one pixel per store straight from the accumulators
+    int group, rows;
     // neighbouring pixels of a row one gather load takes (1, 2 or 4): the input is walked with unit
     // stride, every tap of every pixel lies in memory (no padding, or a halo that holds it), groups
     // do not straddle rows and there is no fused shortcut
@@ -89,6 +90,12 @@ __device__ __forceinline__ void wide_static_for(F&& f) {
     }
 }
 
+// Waves per SIMD the register allocation is held to: the smallest tile with wide gathers fits
+// 72 registers without spilling, and seven workgroups on a CU instead of five take the 1 568
+// tiles of a 56 x 56 layer at batch 32 in one round.
+#ifndef CADNN_WIDE_WAVES
+#define CADNN_WIDE_WAVES(MI, NI, HS, G) ((MI) * (NI) == 1 && (HS) == 1 && (G) > 1 ? 7 : 1)
+#endif
 // MI x NI accumulators of 32 x 32 per wave: a workgroup's tile is 64 MI channels x 64 NI pixels.
 // HS: 32-deep steps of K per stage, i.e. per barrier (a stage's LDS tile is 32 HS deep); with
 // one or two workgroups on a CU the chain LDS write - barrier - LDS read - MFMA of a stage is
@@ -97,7 +104,7 @@ __device__ __forceinline__ void wide_static_for(F&& f) {
 // G: neighbouring pixels per gather load (a quarter of the load instructions with 4; measured:
 // a few percent of a layer's time, most where rows are short).
 template <int MI, int NI, int HS, int D, int G>
-__global__ __launch_bounds__(256) void dense_wide_kernel(const WideArgs a) {
+__global__ __launch_bounds__(256, CADNN_WIDE_WAVES(MI, NI, HS, G)) void dense_wide_kernel(const WideArgs a) {
     constexpr int TM = 64 * MI, TN = 64 * NI;
     // a gather item is G pixels x CH channels of a step, fetched with CH loads; thread t takes
     // items t + 256 j, so that every wave's loads carry 64 lanes of wanted data
@@ -437,7 +444,7 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(const WideArgs a) {
             roff = (uint32_t)(img * (int)a.rd.image + tensor_off(a.rd, oh, ow)) * 2u;
         }
     };
-    if (a.group) {
+    if (a.group || a.rows) {
         // Through LDS: the accumulators of 64 channels at a time are laid out [channel][pixel]
         // as fp32 and a thread takes `group` neighbouring pixels of one channel -- bias, residual,
         // ReLU, one rounding, ONE store of 4 to 16 bytes.  (A wave's own accumulator layout puts
@@ -508,23 +515,62 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(const WideArgs a) {
                 }
             }
         };
-        // Output with a halo of one element (no residual): a row starts at an odd element, so the
-        // aligned pairs are (odd column, next column); a pair at the end of a row, and the first
-        // pixel of the tile, are written singly.
-        auto run_halo = [&]() __attribute__((always_inline)) {
-            constexpr int per_row = TN / 2, rows_per_sweep = 256 / per_row, sweeps = 64 / rows_per_sweep;
+        // Any other layout whose rows split into groups of SG pixels (a halo, a de-interleaved
+        // tensor): the group lies in one row, so in memory it is one run of SG elements, or -- de-
+        // interleaved by column parity -- two runs of SG / 2 (pixels 0, 2, .. and 1, 3, ..).  A run
+        // is stored 4 or 8 bytes at a time at whatever 2-byte alignment it has (checked on the box:
+        // the buffer path takes such loads and stores).
+        auto run_rows = [&](auto GG) __attribute__((always_inline)) {
+            constexpr int SG = decltype(GG)::value, per_row = TN / SG, rows_per_sweep = 256 / per_row, sweeps = 64 / rows_per_sweep;
             const int cg = (int)threadIdx.x % per_row, r0 = (int)threadIdx.x / per_row;
-            const int Qa = n0 + 2 * cg + 1, Qb = Qa + 1;
-            uint32_t ya = kWideOutOfRange, yb = kWideOutOfRange, y0 = kWideOutOfRange, dummy;
-            bool together = false;
-            if (Qa < a.total) {
-                const int img = Qa / a.hwout, q = Qa - img * a.hwout;
+            const int Q = n0 + cg * SG;
+            uint32_t yo[2] = {kWideOutOfRange, kWideOutOfRange}, ro[2] = {kWideOutOfRange, kWideOutOfRange};
+            if (Q < a.total) {
+                const int img = Q / a.hwout, q = Q - img * a.hwout;
                 const int oh = q / a.yd.w, ow = q - oh * a.yd.w;
-                ya = (uint32_t)(img * (int)a.yd.image + tensor_off(a.yd, oh, ow)) * 2u;
-                together = ow + 1 < a.yd.w && cg != per_row - 1;
+#pragma unroll
+                for (int p = 0; p < 2; ++p) {
+                    yo[p] = (uint32_t)(img * (int)a.yd.image + tensor_off(a.yd, oh, ow + p)) * 2u;
+                    ro[p] = (uint32_t)(img * (int)a.rd.image + tensor_off(a.rd, oh, ow + p)) * 2u;
+                }
             }
-            if (cg != per_row - 1 && !together) place(Qb, yb, dummy);      // (the next tile writes its own first pixel)
-            if (threadIdx.x < 64) place(n0, y0, dummy);
+            // N halves to / from one run, in pieces of at most 8 bytes
+            auto load_run = [&](uint32_t off, auto NN, uint32_t (&h)[SG], int first, int step) __attribute__((always_inline)) {
+                constexpr int N = decltype(NN)::value;
+                uint32_t w[N / 2 > 0 ? N / 2 : 1];
+                if constexpr (N == 1) {
+                    h[first] = __builtin_amdgcn_raw_buffer_load_b16(rrsrc, off, 0u, 0);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < N / 2; i += 2) {
+                        if constexpr (N >= 4) {
+                            const u32x2w v = __builtin_amdgcn_raw_buffer_load_b64(rrsrc, off == kWideOutOfRange ? off : off + 4u * i, 0u, 0);
+                            w[i] = v[0]; w[i + 1] = v[1];
+                        } else {
+                            w[i] = __builtin_amdgcn_raw_buffer_load_b32(rrsrc, off, 0u, 0);
+                        }
+                    }
+#pragma unroll
+                    for (int i = 0; i < N; ++i) h[first + i * step] = (w[i / 2] >> (16 * (i & 1))) & 0xffffu;
+                }
+            };
+            auto store_run = [&](uint32_t off, auto NN, const uint32_t (&h)[SG], int first, int step) __attribute__((always_inline)) {
+                constexpr int N = decltype(NN)::value;
+                if constexpr (N == 1) {
+                    __builtin_amdgcn_raw_buffer_store_b16((unsigned short)h[first], yrsrc, off, 0u, 0);
+                } else {
+                    uint32_t w[N / 2];
+#pragma unroll
+                    for (int i = 0; i < N / 2; ++i) w[i] = h[first + 2 * i * step] | (h[first + (2 * i + 1) * step] << 16);
+#pragma unroll
+                    for (int i = 0; i < N / 2; i += 2) {
+                        if constexpr (N >= 4)
+                            __builtin_amdgcn_raw_buffer_store_b64(u32x2w{w[i], w[i + 1]}, yrsrc, off == kWideOutOfRange ? off : off + 4u * i, 0u, 0);
+                        else
+                            __builtin_amdgcn_raw_buffer_store_b32(w[i], yrsrc, off, 0u, 0);
+                    }
+                }
+            };
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi) {
                 __syncthreads();
@@ -535,40 +581,49 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(const WideArgs a) {
                     for (int i = 0; i < 16; ++i)
                         ct[(wm * 32 + (i >> 2) * 8 + fk * 4 + (i & 3)) * CPITCH + wn * 32 * NI + ni * 32 + fm] = acc[mi][ni][i];
                 __syncthreads();
-                auto finish = [&](float v, float b) __attribute__((always_inline)) {
-                    v += b;
-                    if (a.relu) v = v > 0.0f ? v : 0.0f;
-                    return (uint32_t)__builtin_bit_cast(unsigned short, (_Float16)v);
-                };
 #pragma unroll
                 for (int k = 0; k < sweeps; ++k) {
                     const int r = r0 + k * rows_per_sweep;
                     const int co = m0 + (r >> 5) * 32 * MI + mi * 32 + (r & 31);
-                    const bool live = co < a.cout;
-                    const uint32_t po = (uint32_t)(live ? co : 0) * (uint32_t)a.yd.plane * 2u;
+                    const bool live = co < a.cout && yo[0] != kWideOutOfRange;
+                    const uint32_t cc = (uint32_t)(co < a.cout ? co : 0);
                     const float b = bl[mi * 64 + r];
-                    const uint32_t va = finish(ct[r * CPITCH + 2 * cg + 1], b);
-                    const uint32_t vb = cg != per_row - 1 ? finish(ct[r * CPITCH + 2 * cg + 2], b) : 0u;
-                    if (together) {
-                        __builtin_amdgcn_raw_buffer_store_b32(va | (vb << 16), yrsrc, live ? ya + po : kWideOutOfRange, 0u, 0);
-                    } else {
-                        __builtin_amdgcn_raw_buffer_store_b16((unsigned short)va, yrsrc, live && ya != kWideOutOfRange ? ya + po : kWideOutOfRange, 0u, 0);
-                        __builtin_amdgcn_raw_buffer_store_b16((unsigned short)vb, yrsrc, live && yb != kWideOutOfRange ? yb + po : kWideOutOfRange, 0u, 0);
+                    const float* src = ct + r * CPITCH + cg * SG;
+                    uint32_t res[SG], out[SG];
+#pragma unroll
+                    for (int j = 0; j < SG; ++j) res[j] = 0u;
+                    if (a.residual) {
+                        const uint32_t po = cc * (uint32_t)a.rd.plane * 2u;
+                        if (a.rd.s2d) {
+                            load_run(live ? ro[0] + po : kWideOutOfRange, std::integral_constant<int, SG / 2>(), res, 0, 2);
+                            load_run(live ? ro[1] + po : kWideOutOfRange, std::integral_constant<int, SG / 2>(), res, 1, 2);
+                        } else {
+                            load_run(live ? ro[0] + po : kWideOutOfRange, std::integral_constant<int, SG>(), res, 0, 1);
+                        }
                     }
-                }
-                if (threadIdx.x < 64) {          // the tile's first pixel, one channel per thread
-                    const int r = (int)threadIdx.x;
-                    const int co = m0 + (r >> 5) * 32 * MI + mi * 32 + (r & 31);
-                    const bool live = co < a.cout && y0 != kWideOutOfRange;
-                    __builtin_amdgcn_raw_buffer_store_b16((unsigned short)finish(ct[r * CPITCH], bl[mi * 64 + r]), yrsrc,
-                                                          live ? y0 + (uint32_t)co * (uint32_t)a.yd.plane * 2u : kWideOutOfRange, 0u, 0);
+#pragma unroll
+                    for (int j = 0; j < SG; ++j) {
+                        float v = src[j] + b;
+                        if (a.residual) v += (float)__builtin_bit_cast(_Float16, (unsigned short)res[j]);
+                        if (a.relu) v = v > 0.0f ? v : 0.0f;
+                        out[j] = (uint32_t)__builtin_bit_cast(unsigned short, (_Float16)v);
+                    }
+                    const uint32_t po = cc * (uint32_t)a.yd.plane * 2u;
+                    if (a.yd.s2d) {
+                        store_run(live ? yo[0] + po : kWideOutOfRange, std::integral_constant<int, SG / 2>(), out, 0, 2);
+                        store_run(live ? yo[1] + po : kWideOutOfRange, std::integral_constant<int, SG / 2>(), out, 1, 2);
+                    } else {
+                        store_run(live ? yo[0] + po : kWideOutOfRange, std::integral_constant<int, SG>(), out, 0, 1);
+                    }
                 }
             }
         };
         if (a.group == 8) run(std::integral_constant<int, 8>());
         else if (a.group == 4) run(std::integral_constant<int, 4>());
         else if (a.group == 2) run(std::integral_constant<int, 2>());
-        else run_halo();
+        else if (a.rows == 8) run_rows(std::integral_constant<int, 8>());
+        else if (a.rows == 4) run_rows(std::integral_constant<int, 4>());
+        else run_rows(std::integral_constant<int, 2>());
     } else {
 #pragma unroll
         for (int ni = 0; ni < NI; ++ni) {
@@ -648,10 +703,9 @@ WideArgs wide_args(const void* w, const void* x, const TensorDesc& xd, void* y, 
     };
     a.group = group_of(yd, y);
     if (residual) a.group = std::min(a.group, group_of(rd, residual));
-    // a halo of one element around an even-sized plane, no residual: aligned pairs start at odd columns
-    if (a.group == 0 && !residual && !yd.s2d && yd.pw == 1 && yd.w % 2 == 0 && yd.pitch % 2 == 0 && yd.plane % 2 == 0 && yd.image % 2 == 0 &&
-        (uintptr_t)y % 4 == 0)
-        a.group = -1;
+    // any other layout (a halo, de-interleaved tensors): the widest groups the rows split into
+    a.rows = 0;
+    if (a.group == 0) a.rows = yd.w % 8 == 0 ? 8 : yd.w % 4 == 0 ? 4 : yd.w % 2 == 0 ? 2 : 0;
     a.gather = 1;
     const bool taps_in_memory = pad == 0 || (xd.ph >= pad && xd.pw >= pad);
     if (stride == 1 && !xd.s2d && taps_in_memory)
