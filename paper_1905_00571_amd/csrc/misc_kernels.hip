@@ -241,6 +241,77 @@ __global__ __launch_bounds__(256) void windowpool_kernel(const T* __restrict__ x
     windowpool_element<T>(x, y, xd, yd, img, i - (size_t)img * per_image, k, stride, pad, AVG);
 }
 
+// 3 x 3 / 2 maximum pool, four neighbouring outputs of a row per thread: their windows span 9
+// columns of 3 rows, fetched with three loads per row (4 + 4 + 1 elements, at whatever alignment
+// the row has) instead of 9 per output.  Positions outside the image are never looked at: they
+// enter the maximum as minus infinity (the loads themselves are range-checked buffer loads, so a
+// window hanging over the first row or column reads nothing it should not).
+typedef uint32_t u32x2m __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4m __attribute__((ext_vector_type(4)));
+template <typename T>
+__global__ __launch_bounds__(256) void maxpool3s2_kernel(const T* __restrict__ x, T* __restrict__ y, TensorDesc xd,
+                                                         TensorDesc yd, int n, int pad) {
+    const int groups = yd.w >> 2;
+    const size_t per_image = (size_t)yd.c * yd.h * groups;
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= per_image * n) return;
+    const int img = (int)(i / per_image);
+    const size_t r = i - (size_t)img * per_image;
+    const int ow0 = (int)(r % groups) * 4;
+    const int oh = (int)((r / groups) % yd.h);
+    const int c = (int)(r / ((size_t)groups * yd.h));
+    const uint32_t xbytes = (uint32_t)(xd.image * (int64_t)sizeof(T)), ybytes = (uint32_t)(yd.image * (int64_t)sizeof(T));
+    const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc((void*)(x + (size_t)img * xd.image), 0, xbytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t yr = __builtin_amdgcn_make_buffer_rsrc((void*)(y + (size_t)img * yd.image), 0, ybytes, 0x00020000);
+    const int iw0 = ow0 * 2 - pad;                    // first of the 9 columns
+    // (a row's loads start inside the row: a load that begins in front of the buffer would be
+    // dropped whole, valid columns included; the window's columns are the loaded ones shifted)
+    const int start = iw0 < 0 ? 0 : iw0, shift = start - iw0;
+    const float ninf = -__builtin_inff();
+    float m[4] = {ninf, ninf, ninf, ninf};
+#pragma unroll
+    for (int a = 0; a < 3; ++a) {
+        const int ih = oh * 2 + a - pad;
+        if (ih < 0 || ih >= xd.h) continue;
+        const uint32_t off = (uint32_t)((int64_t)c * xd.plane + xd.origin + (int64_t)ih * xd.pitch + start) * (uint32_t)sizeof(T);
+        float v[9];
+        if constexpr (sizeof(T) == 2) {
+            const u32x2m lo = __builtin_amdgcn_raw_buffer_load_b64(xr, off, 0u, 0);
+            const u32x2m hi = __builtin_amdgcn_raw_buffer_load_b64(xr, off + 8u, 0u, 0);
+            const uint32_t last = __builtin_amdgcn_raw_buffer_load_b16(xr, off + 16u, 0u, 0);
+            const uint32_t w[5] = {lo[0], lo[1], hi[0], hi[1], last};
+#pragma unroll
+            for (int j = 0; j < 9; ++j) v[j] = (float)__builtin_bit_cast(_Float16, (unsigned short)(w[j >> 1] >> (16 * (j & 1))));
+        } else {
+            const u32x4m lo = __builtin_amdgcn_raw_buffer_load_b128(xr, off, 0u, 0);
+            const u32x4m hi = __builtin_amdgcn_raw_buffer_load_b128(xr, off + 16u, 0u, 0);
+            const uint32_t last = __builtin_amdgcn_raw_buffer_load_b32(xr, off + 32u, 0u, 0);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { v[j] = __uint_as_float(lo[j]); v[4 + j] = __uint_as_float(hi[j]); }
+            v[8] = __uint_as_float(last);
+        }
+        if (shift) {        // (pad <= 1: by one column)
+#pragma unroll
+            for (int j = 8; j > 0; --j) v[j] = v[j - 1];
+        }
+#pragma unroll
+        for (int j = 0; j < 9; ++j)
+            if (iw0 + j < 0 || iw0 + j >= xd.w) v[j] = ninf;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) m[j] = fmaxf(m[j], fmaxf(fmaxf(v[2 * j], v[2 * j + 1]), v[2 * j + 2]));
+    }
+    const uint32_t yoff = (uint32_t)((int64_t)c * yd.plane + yd.origin + (int64_t)oh * yd.pitch + ow0) * (uint32_t)sizeof(T);
+    if constexpr (sizeof(T) == 2) {
+        uint32_t h[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) h[j] = (uint32_t)__builtin_bit_cast(unsigned short, (_Float16)m[j]);
+        __builtin_amdgcn_raw_buffer_store_b64(u32x2m{h[0] | (h[1] << 16), h[2] | (h[3] << 16)}, yr, yoff, 0u, 0);
+    } else {
+        __builtin_amdgcn_raw_buffer_store_b128(u32x4m{__float_as_uint(m[0]), __float_as_uint(m[1]), __float_as_uint(m[2]), __float_as_uint(m[3])},
+                                               yr, yoff, 0u, 0);
+    }
+}
+
 // One wave per (n, c) plane; lanes stride over the plane, shuffle reduction at the end.
 template <typename T>
 __global__ __launch_bounds__(256) void avgpool_kernel(const T* __restrict__ x, T* __restrict__ y,
@@ -298,6 +369,19 @@ static cadnn_status launch_windowpool(const void* x, const TensorDesc& xd, void*
                                       int k, int stride, int pad, cadnn_dtype dt, hipStream_t s) {
     const size_t total = (size_t)n * yd.c * yd.h * yd.w;
     if ((total + 255) / 256 > 0x7fffffffull) return fail(CADNN_EUNSUPPORTED, "pooling layer too large for one launch");
+    // the 3 x 3 / 2 maximum pool of the residual networks on plain tensors whose output rows split
+    // into groups of 4: four outputs per thread (an image behind a 32-bit byte offset)
+    const int64_t esz = dt == CADNN_F16 ? 2 : 4;
+    if (!AVG && k == 3 && stride == 2 && pad <= 1 && !xd.s2d && !yd.s2d && yd.w % 4 == 0 && xd.image * esz < 0x7ffffff0ll &&
+        yd.image * esz < 0x7ffffff0ll) {
+        const unsigned blocks4 = (unsigned)((total / 4 + 255) / 256);
+        if (dt == CADNN_F16)
+            CADNN_LAUNCH((maxpool3s2_kernel<_Float16>), dim3(blocks4), dim3(256), 0, s, (const _Float16*)x, (_Float16*)y, xd, yd, n, pad);
+        else
+            CADNN_LAUNCH((maxpool3s2_kernel<float>), dim3(blocks4), dim3(256), 0, s, (const float*)x, (float*)y, xd, yd, n, pad);
+        CADNN_HIP(hipGetLastError());
+        return CADNN_OK;
+    }
     const unsigned blocks = (unsigned)((total + 255) / 256);
     if (dt == CADNN_F16)
         CADNN_LAUNCH((windowpool_kernel<_Float16, AVG>), dim3(blocks), dim3(256), 0, s, (const _Float16*)x,

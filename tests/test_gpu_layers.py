@@ -266,6 +266,13 @@ def test_pools(cad):
     x16 = x.astype(np.float16)
     y = cad.cadnn_maxpool2d(dev(x16), 3, 2, 1)
     assert np.array_equal(y.cpu().numpy(), oracle.maxpool(x16, 3, 2, 1))
+    # output rows that split into groups of 4 take the kernel with four outputs per thread; the
+    # values are all negative, so a padding position read as zero would show
+    for shape, p in [((2, 5, 24, 31), 1), ((3, 4, 25, 33), 0), ((1, 3, 8, 8), 1)]:
+        xn = -np.abs(wl.activation(shape, "pool4", p, relu=False)) - 0.5
+        for xx in (xn, xn.astype(np.float16)):
+            y = cad.cadnn_maxpool2d(dev(xx), 3, 2, p)
+            assert np.array_equal(y.cpu().numpy(), oracle.maxpool(xx, 3, 2, p)), (shape, p, xx.dtype)
     for k, s, p in [(3, 1, 1), (3, 2, 0), (2, 2, 0), (5, 1, 2)]:
         y = cad.cadnn_avgpool2d(dev(x), k, s, p)
         # an fp32 sum of at most k*k terms against the mean of their magnitudes
