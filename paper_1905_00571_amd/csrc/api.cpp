@@ -114,6 +114,9 @@ static bool variant_fits(const ConvVariant& v, const cadnn_weights* w, const Con
         if (!dense_wide_serves(v.is_f16, w->cin, w->kh * w->kw, in_bytes,
                                (int64_t)w->cout * (g.hout + 64) * (g.wout + 64) * 2 * g.n, pixels))
             return false;
+        // few input channels: K is walked with a table of offsets by the 64-pixel tiles, on plain
+        // tensors, with nothing fused and K in one piece
+        if (w->cin % 32 != 0 && (v.p != 1 || g.ex || g.xd.s2d || v.splitk > 1)) return false;
         // a de-interleaved input is walked phase by phase (stride 2, taps starting inside the
         // halo) or pixel by pixel (stride 1, 1x1)
         if (g.xd.s2d && !(g.stride == 2 ? (g.xd.ph >= g.pad && g.xd.pw >= g.pad) : (g.stride == 1 && w->kh * w->kw == 1 && g.pad == 0)))

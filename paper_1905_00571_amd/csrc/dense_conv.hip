@@ -229,7 +229,7 @@ cadnn_status dense_conv2d_impl(const void* w_dev, const void* x, void* y, int n,
         yd.image * elem >= 0x7ffffff0ll)
         return fail(CADNN_EUNSUPPORTED, "cadnn_dense_conv2d: one image of a tensor is 2 GiB or more");
     // fp16 storage with whole 32-channel steps takes the 128 x 128-tile kernel
-    if (dense_wide_serves(dtype == CADNN_F16, cin, kh * kw, (int64_t)cin * h * wdt * elem * n, yd.image * elem * n,
+    if (cin % 32 == 0 && dense_wide_serves(dtype == CADNN_F16, cin, kh * kw, (int64_t)cin * h * wdt * elem * n, yd.image * elem * n,
                           (int64_t)n * hout * wout))
         return dense_wide_conv2d_raw(w_dev, x, make_desc(cin, h, wdt), y, yd, residual, yd, n, cout, kh, kw, stride, pad,
                                      bias, relu, s);

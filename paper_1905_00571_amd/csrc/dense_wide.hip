@@ -41,6 +41,7 @@ namespace cadnn {
 namespace {
 
 constexpr int WK = 32;
+constexpr int kWideTableK = 256;      // longest K walked with a table
 constexpr uint32_t kWideOutOfRange = 0x7ffffff0u;
 
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
@@ -59,6 +60,10 @@ struct WideArgs {
     TensorDesc xd, yd, rd;
     int n, cout, cin, kh, kw, stride, pad, relu;
     int hwout, total, K, csteps;   // total = n * hwout; csteps = cin / 32; K = row length of w
+    // few input channels (cin not a multiple of 32; a network's first layer): K runs over
+    // (ci, r, c) in the weights' own order, padded to whole steps, and the gather takes each k's
+    // offset and tap from a table the workgroup builds in LDS (64-pixel tiles, one pixel per load)
+    int table;
     // a fused 1x1 projection shortcut (x2 != NULL): csteps2 more steps of K read from x2, a
     // plain view walked with stride2 from pixel (0, 0); its bias is added as well
     const _Float16* x2;
@@ -115,6 +120,10 @@ __global__ __launch_bounds__(256, CADNN_WIDE_WAVES(MI, NI, HS, G)) void dense_wi
     constexpr int CPITCH = TN + 8;          // words between rows of the fp32 output tile
     constexpr int MAIN_BYTES = 2 * (TM + TN) * PITCH * 2, TILE_BYTES = 64 * CPITCH * 4, EPI_BYTES = TILE_BYTES + TM * 4;
     __shared__ __attribute__((aligned(16))) char smem[MAIN_BYTES > EPI_BYTES ? MAIN_BYTES : EPI_BYTES];
+    // (table mode: per k its byte offset from the pixel's own position and its tap; two stages
+    // past the end of K are fetched, from entries that stay zero)
+    constexpr bool TABLE = NI == 1 && G == 1;
+    __shared__ int2 ktab[TABLE ? kWideTableK + 2 * WK * HS * D : 1];
     _Float16 (*As)[TM * PITCH] = (_Float16 (*)[TM * PITCH])smem;
     _Float16 (*Bs)[TN * PITCH] = (_Float16 (*)[TN * PITCH])(smem + 2 * TM * PITCH * 2);
 
@@ -145,17 +154,25 @@ __global__ __launch_bounds__(256, CADNN_WIDE_WAVES(MI, NI, HS, G)) void dense_wi
             const int at = !a.xd.s2d ? a.xd.origin + oh * a.stride * a.xd.pitch + ow * a.stride
                            : a.stride == 2 ? oh * a.xd.pitch + ow : tensor_off(a.xd, oh, ow);
             // (the item's first channel rides in the per-lane part: a wave may hold several)
-            gbase[h] = (uint32_t)(img * (int)a.xd.image + gch[h] * a.xd.plane + at) * 2u;
+            gbase[h] = (uint32_t)(img * (int)a.xd.image + (a.table ? 0 : gch[h]) * a.xd.plane + at) * 2u;
             if (a.x2)
                 gbase2[h] = (uint32_t)(img * (int)a.x2d.image + gch[h] * a.x2d.plane + a.x2d.origin + oh * a.stride2 * a.x2d.pitch +
                                        ow * a.stride2) * 2u;
             if constexpr (G > 1) gmask[h] = ~(uint64_t)0;       // (every tap of every pixel lies in memory)
-            else
+            else {
+                // (the taps inside the image are a rectangle: rows times columns)
+                uint32_t rows_in = 0, cols_in = 0;
+                for (int r = 0; r < a.kh; ++r) {
+                    const int ih = oh * a.stride + r - a.pad;
+                    if (ih >= 0 && ih < a.xd.h) rows_in |= 1u << r;
+                }
+                for (int c = 0; c < a.kw; ++c) {
+                    const int iw = ow * a.stride + c - a.pad;
+                    if (iw >= 0 && iw < a.xd.w) cols_in |= 1u << c;
+                }
                 for (int r = 0; r < a.kh; ++r)
-                    for (int c = 0; c < a.kw; ++c) {
-                        const int ih = oh * a.stride + r - a.pad, iw = ow * a.stride + c - a.pad;
-                        if (ih >= 0 && ih < a.xd.h && iw >= 0 && iw < a.xd.w) gmask[h] |= (uint64_t)1 << (r * a.kw + c);
-                    }
+                    if ((rows_in >> r) & 1) gmask[h] |= (uint64_t)cols_in << (r * a.kw);
+            }
         }
     }
     // (readfirstlane: the compiler must keep the buffer descriptors in scalar registers)
@@ -196,7 +213,16 @@ __global__ __launch_bounds__(256, CADNN_WIDE_WAVES(MI, NI, HS, G)) void dense_wi
     // redone only when the tap changes, behind a scalar branch that issues no load.  Past the
     // last step zeros are fetched (out-of-range offsets on both sides) rather than nothing, so
     // that the number of loads in flight is known at compile time.
-    const int steps_all = taps * a.csteps + a.csteps2;
+    const int steps_all = a.table ? a.K / WK : taps * a.csteps + a.csteps2;
+    if constexpr (TABLE) {
+        if (a.table) {
+            for (int k = (int)threadIdx.x; k < kWideTableK + 2 * WK * HS * D; k += 256) {
+                const int ci = k / taps, t = k - ci * taps, r = t / a.kw, c = t - r * a.kw;
+                ktab[k] = k < a.cin * taps ? make_int2((ci * a.xd.plane + (r - a.pad) * a.xd.pitch + (c - a.pad)) * 2, t) : make_int2(0, 0);
+            }
+            __syncthreads();
+        }
+    }
     // this workgroup's slice of K: steps [s_first, s_first + steps)
     // (integer divisions run on the vector ALU: their results are made scalar again, or every
     // address derived from them would be a per-lane value to the compiler)
@@ -204,7 +230,7 @@ __global__ __launch_bounds__(256, CADNN_WIDE_WAVES(MI, NI, HS, G)) void dense_wi
     const int s_first = (int)blockIdx.z * per_slice;
     const int steps = min(per_slice, steps_all - s_first);
     const int stages = (steps + HS - 1) / HS;
-    int f_tap = 0, f_r = 0, f_c = 0, f_left = 0, f_todo = steps;          // (scalar)
+    int f_tap = 0, f_r = 0, f_c = 0, f_left = 0, f_todo = steps, f_step = s_first;          // (scalar)
     bool f_second = false;
     uint32_t f_soffA = 0, f_inc = 0, f_pb = 0, f_soffB = 0;
     uint32_t f_vA[MI], f_vB[NB];
@@ -238,7 +264,13 @@ __global__ __launch_bounds__(256, CADNN_WIDE_WAVES(MI, NI, HS, G)) void dense_wi
     };
 #pragma unroll
     for (int i = 0; i < MI; ++i) f_vA[i] = wrow[i];
-    {
+    if (a.table) {
+        // (no tap walk: a pixel's own position, every k's offset from the table)
+        f_left = 0x7fffffff;
+#pragma unroll
+        for (int h = 0; h < NB; ++h) f_vB[h] = (gmask[h] != 0) ? gbase[h] : kWideOutOfRange;
+        f_soffA = (uint32_t)s_first * (WK * 2);
+    } else {
         const int in_taps = taps * a.csteps;
         f_tap = __builtin_amdgcn_readfirstlane(s_first < in_taps ? s_first / a.csteps : taps);
         f_r = __builtin_amdgcn_readfirstlane(f_tap / a.kw);
@@ -259,6 +291,21 @@ __global__ __launch_bounds__(256, CADNN_WIDE_WAVES(MI, NI, HS, G)) void dense_wi
                 (void*)xps, 0, __builtin_amdgcn_readfirstlane(f_second ? x2span : xspan), 0x00020000);
 #pragma unroll
             for (int i = 0; i < MI; ++i) areg[S][hs][i] = __builtin_amdgcn_raw_buffer_load_b128(wrsrc, f_vA[i], f_soffA, 0);
+            if constexpr (TABLE) {
+                if (a.table) {
+                    // step f_step of K: this wave's eight k, each with its own offset and tap
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) {
+                        const int2 e = ktab[f_step * WK + wv * 8 + k];
+                        const uint32_t vo = (f_vB[0] != kWideOutOfRange && ((gmask[0] >> e.y) & 1)) ? f_vB[0] + (uint32_t)e.x : kWideOutOfRange;
+                        breg[S][hs][0][k] = __builtin_amdgcn_raw_buffer_load_b16(xrsrc, vo, 0u, 0);
+                    }
+                    f_soffA += WK * 2;
+                    ++f_step;
+                    if (--f_todo == 0) end_walk();
+                    continue;
+                }
+            }
             uint32_t soff = f_soffB;         // (channel by channel: one running scalar instead of eight kept ones)
 #pragma unroll
             for (int k = 0; k < CH; ++k) {
@@ -676,6 +723,8 @@ hipError_t launch_wide_tile(const WideArgs& a, hipStream_t s) {
 }
 
 hipError_t launch_wide_args(const WideArgs& a, int tm, int tn, int hs, hipStream_t s) {
+    // (K walked with a table: the 64-pixel tiles only, a K the table holds)
+    if (a.table && (tn != 64 || a.K > kWideTableK || a.x2 || a.xd.s2d || a.sk > 1)) return hipErrorInvalidValue;
     if (tm == 128 && tn == 128) return launch_wide_tile<2, 2, 1>(a, s);
     if (tm == 128) return hs == 2 ? launch_wide_tile<2, 1, 2>(a, s) : launch_wide_tile<2, 1, 1>(a, s);
     if (tn == 128) return hs == 2 ? launch_wide_tile<1, 2, 2>(a, s) : launch_wide_tile<1, 2, 1>(a, s);
@@ -691,7 +740,8 @@ WideArgs wide_args(const void* w, const void* x, const TensorDesc& xd, void* y, 
     a.n = n; a.cout = cout; a.cin = xd.c; a.kh = kh; a.kw = kw; a.stride = stride; a.pad = pad; a.relu = relu ? 1 : 0;
     a.hwout = yd.h * yd.w;
     a.total = n * a.hwout;
-    a.K = xd.c * kh * kw;
+    a.table = xd.c % WK != 0;
+    a.K = a.table ? (xd.c * kh * kw + WK - 1) / WK * WK : xd.c * kh * kw;
     a.csteps = xd.c / WK;
     // the widest store the layouts allow: an image's pixels contiguous (no halo, not
     // de-interleaved), groups that neither straddle images nor leave their alignment
@@ -708,7 +758,7 @@ WideArgs wide_args(const void* w, const void* x, const TensorDesc& xd, void* y, 
     if (a.group == 0) a.rows = yd.w % 8 == 0 ? 8 : yd.w % 4 == 0 ? 4 : yd.w % 2 == 0 ? 2 : 0;
     a.gather = 1;
     const bool taps_in_memory = pad == 0 || (xd.ph >= pad && xd.pw >= pad);
-    if (stride == 1 && !xd.s2d && taps_in_memory)
+    if (stride == 1 && !xd.s2d && taps_in_memory && !a.table)
         a.gather = yd.w % 4 == 0 ? 4 : yd.w % 2 == 0 ? 2 : 1;
     a.sk = 1;
     return a;
@@ -740,7 +790,7 @@ hipError_t launch_wide_variant(const ConvLaunch& l, hipStream_t s) {
 
 bool dense_wide_serves(bool is_f16, int cin, int taps, int64_t in_bytes, int64_t out_bytes, int64_t pixels) {
     // (the whole batch sits behind 32-bit byte offsets)
-    return is_f16 && cin % WK == 0 && taps <= 64 && in_bytes < 0x7ffffff0ll && out_bytes < 0x7ffffff0ll && pixels < 0x7fffff00ll;
+    return is_f16 && (cin % WK == 0 || cin * taps <= kWideTableK) && taps <= 64 && in_bytes < 0x7ffffff0ll && out_bytes < 0x7ffffff0ll && pixels < 0x7fffff00ll;
 }
 
 // tw == 128 marks the tap-major weight matrix with rows padded to 128 (build_dense_plan); the

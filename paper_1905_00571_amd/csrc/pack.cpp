@@ -784,7 +784,20 @@ static cadnn_status build_dense_plan(const cadnn_weights* w, const ConvVariant* 
     plan->walked = plan->nz_padded;
     plan->entry_bytes = (int)w->elem();
     cadnn_status st;
-    if (v->tw == 128) {
+    if (v->tw == 128 && w->cin % 32 != 0) {
+        // few input channels (a network's first layer): the canonical order k = (ci, r, c), rows
+        // padded with zeros to whole 32-deep steps; the kernel walks K with a table of offsets
+        if (ex) return fail(CADNN_EINVAL, "fused shortcut and kernel variant do not match");
+        const size_t Kp = (K1 + 31) / 32 * 32;
+        plan->rows_padded = (w->cout + 127) / 128 * 128;
+        plan->nz_padded = (int64_t)((size_t)plan->rows_padded * Kp);
+        plan->walked = plan->nz_padded;
+        std::vector<uint16_t> dense((size_t)plan->rows_padded * Kp, 0);
+        for (int i = 0; i < w->cout; ++i)
+            for (int32_t j = w->row_ptr[i]; j < w->row_ptr[i + 1]; ++j)
+                dense[(size_t)w->perm[i] * Kp + (size_t)w->col_idx[j]] = w->vals16[j];
+        st = plan->nz.upload(dense.data(), dense.size() * 2);
+    } else if (v->tw == 128) {
         const int taps = w->kh * w->kw;
         plan->rows_padded = (w->cout + 127) / 128 * 128;
         plan->nz_padded = (int64_t)((size_t)plan->rows_padded * K);

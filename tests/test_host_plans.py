@@ -39,8 +39,11 @@ def test_every_plan_builds_on_the_host_and_counts_its_bytes(layer, dtype_name):
         info = cad.cadnn_conv2d_plan_info(hnd, n, h, w_, stride, pad, nm)
         if nm.startswith("dense"):
             # (the tap-major matrix of the large-tile kernels pads its rows to whole 128-row tiles)
-            rows = cout if nm.endswith("_64x64x32") else (cout + 127) // 128 * 128
-            assert info["stream_bytes"] == rows * cin * k * k * (2 if dtype == cad.F16 else 4)
+            # (and, for few input channels, its K to whole 32-deep steps)
+            large = not nm.endswith("_64x64x32")
+            rows = (cout + 127) // 128 * 128 if large else cout
+            K = (cin * k * k + 31) // 32 * 32 if large and cin % 32 else cin * k * k
+            assert info["stream_bytes"] == rows * K * (2 if dtype == cad.F16 else 4)
             continue
         assert info["entries"] >= nnz and info["stream_bytes"] > 0 and info["chunks"] >= 1, (nm, info)
         per_entry = info["stream_bytes"] / info["entries"]
