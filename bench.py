@@ -79,7 +79,7 @@ def layer_costs(ops, weights, in_shape, elem):
     return rows
 
 
-KERNEL_OF_PREFIX = {"slinear": "sconv_linear_kernel", "stile": "sconv_stile_kernel", "sptile": "sconv_ptile_kernel",
+KERNEL_OF_PREFIX = {"slinear": "sconv_linear_kernel", "squad": "sconv_quad_kernel", "stile": "sconv_stile_kernel", "sptile": "sconv_ptile_kernel",
                     "swide": "sconv_wtile_kernel",
                     "sdirect": "sconv_direct_kernel", "sconv": "sconv_tile_kernel",
                     "dense": "dense_conv_kernel", "sfc": "sfc_kernel", "dwconv": "dwconv_kernel", "maxpool": "windowpool_kernel",
